@@ -1,0 +1,324 @@
+"""CPU oracle for the MotionDeltaCNN hot path.  TEST INFRASTRUCTURE ONLY.
+
+A plain, slow NumPy statement of what the path computes, written from the
+paper; it shares no code with the HIP library and must never be imported by
+the product path (only by tests, the smoke check and the CPU-baseline leg of
+the benchmark).
+
+What is followed, and where the paper defines it:
+
+* delta input, truncation to a per-pixel update mask, accumulated-values and
+  truncated-values buffers, delta propagation through linear layers by
+  linearity and through activations as f(acc + d) - f(acc)
+  -- Background: DeltaCNN;
+* spherical (2-D ring) buffers addressed with wrapped coordinates and a
+  per-layer pixel offset = tile offset x layer tile size -- Spherical Buffers;
+* newly unveiled pixels overwrite the pixels that left the ring, are reset and
+  receive the biases -- Dynamic Initialization; the bias is placed into the
+  truncated-values buffer of the reset pixels so the activation adds it
+  -- Supplementary, Implicit bias application;
+* every output that an in-view input can touch is computed; the outputs
+  outside the view ("dilated" pixels) are accumulated in a slightly enlarged
+  truncated-values buffer and attach when that region is unveiled
+  -- Padded Convolutions (a 64x64 input under a 3x3 kernel yields 66x66);
+* growing in one direction invalidates the stash of the opposite side, moving
+  back over it resets all buffers and the frame is inferred densely
+  -- Buffer management.
+
+Arithmetic: stored tensors (A, P, delta maps, weights, frames) are in the
+network's storage dtype; every elementwise operation is done in float32 in the
+written order with one rounding to the storage dtype per stored value; a
+convolution output is summed in float64, rounded once to float32 and added to
+the pending value in float32.
+
+Naming: A = accumulated values, P = pending = truncated values incl. the
+dilated border, N = newly unveiled this frame, U = touched by a producer this
+frame, M = update mask, L = compacted list of updated pixels.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+N_BIT, U_BIT, M_BIT = 1, 2, 4
+
+
+def conv_border(k, stride, pad, w_in, w_out):
+    """Dilated border (before, after) along one axis: the outputs outside
+    [0, w_out) that still read at least one input in [0, w_in).
+    Padded Convolutions: all outputs affected by the current input."""
+    if k == 0:
+        return 0, 0
+    before = (k - 1 - pad) // stride
+    after = (w_in - 1 + pad) // stride - (w_out - 1)
+    return max(before, 0), max(after, 0)
+
+
+class OracleSite:
+    def __init__(self, spec, H, W, tile, dtype, origin=(0, 0)):
+        self.spec = spec
+        self.H, self.W, self.C = H, W, spec.C
+        self.tile = tile
+        self.dtype = dtype
+        self.border = [0, 0, 0, 0]          # before_y, after_y, before_x, after_x
+        self.beta = np.zeros(spec.C, np.float32)
+        self.origin = origin                # physical rotation of the rings
+        self.gy = 0                         # global pixel coordinate of view pixel (0, 0)
+        self.gx = 0
+
+    def allocate(self):
+        by0, by1, bx0, bx1 = self.border
+        self.Hp, self.Wp = self.H + by0 + by1, self.W + bx0 + bx1
+        self.A = np.zeros((self.H, self.W, self.C), self.dtype)
+        self.P = np.zeros((self.Hp, self.Wp, self.C), self.dtype)
+        self.N = np.zeros((self.H, self.W), bool)
+        self.U = np.zeros((self.H, self.W), bool)
+        self.M = np.zeros((self.H, self.W), bool)
+        self.delta = np.zeros((self.H, self.W, self.C), self.dtype)
+        self.L = np.zeros(0, np.int32)
+        self.n_candidates = 0
+
+    # ring addressing: global pixel -> physical slot, wrapped (Spherical Buffers)
+    def _a_index(self):
+        r = (self.gy + np.arange(self.H) + self.origin[0]) % self.H
+        c = (self.gx + np.arange(self.W) + self.origin[1]) % self.W
+        return np.ix_(r, c)
+
+    def _p_index(self):
+        by0, _, bx0, _ = self.border
+        r = (self.gy - by0 + np.arange(self.Hp) + self.origin[0]) % self.Hp
+        c = (self.gx - bx0 + np.arange(self.Wp) + self.origin[1]) % self.Wp
+        return np.ix_(r, c)
+
+    def get_A(self):
+        return self.A[self._a_index()]
+
+    def set_A(self, v):
+        self.A[self._a_index()] = v
+
+    def get_P(self):
+        """Pending values over the padded window (view plus dilated border)."""
+        return self.P[self._p_index()]
+
+    def set_P(self, v):
+        self.P[self._p_index()] = v
+
+    def view_of_window(self, win):
+        by0, _, bx0, _ = self.border
+        return win[by0:by0 + self.H, bx0:bx0 + self.W]
+
+
+class OracleNet:
+    def __init__(self, net, origins=None):
+        self.net = net
+        self.dtype = net.np_dtype
+        self.sites = []
+        for i, s in enumerate(net.sites):
+            H, W = net.H // s.stride, net.W // s.stride
+            org = (0, 0) if origins is None else origins[i]
+            self.sites.append(OracleSite(s, H, W, net.total_stride // s.stride, self.dtype, org))
+        for e in net.edges:
+            src, dst = self.sites[e.src], self.sites[e.dst]
+            if e.k == 0:
+                assert (src.H, src.W, src.C) == (dst.H, dst.W, dst.C)
+            else:
+                oh = (src.H + 2 * e.pad - e.k) // e.stride + 1
+                ow = (src.W + 2 * e.pad - e.k) // e.stride + 1
+                if e.up:
+                    assert e.k == 1 and e.stride == 1 and e.pad == 0
+                assert (oh << e.up, ow << e.up) == (dst.H, dst.W), "edge shape mismatch"
+                by = conv_border(e.k, e.stride, e.pad, src.H, oh)
+                bx = conv_border(e.k, e.stride, e.pad, src.W, ow)
+                b = [by[0], by[1], bx[0], bx[1]]
+                dst.border = [max(p, q) for p, q in zip(dst.border, b)]
+                if e.b is not None:
+                    dst.beta = dst.beta + e.b.astype(np.float32)
+        for s in self.sites:
+            s.allocate()
+        self.fresh = True
+        self.R = dict(up=False, down=False, left=False, right=False)
+        self.n_resets = 0
+
+    # ------------------------------------------------------------------ shift
+    def shift_camera(self, dty, dtx):
+        """Buffer management: move every site's view by (dty, dtx) tiles; reset
+        the pixels that enter, or everything when growth is restricted."""
+        dty, dtx = int(dty), int(dtx)
+        R = self.R
+        full = self.fresh
+        full |= (dtx > 0 and R["right"]) or (dtx < 0 and R["left"])
+        full |= (dty > 0 and R["down"]) or (dty < 0 and R["up"])
+        for s in self.sites:
+            full |= abs(dtx) * s.tile >= s.W or abs(dty) * s.tile >= s.H
+        if full:
+            for s in self.sites:
+                s.gy += dty * s.tile
+                s.gx += dtx * s.tile
+                s.A[:] = 0
+                s.P[:] = s.beta.astype(s.dtype)
+                s.N[:] = True
+                s.U[:] = False
+            self.R = dict(up=False, down=False, left=False, right=False)
+            self.fresh = False
+            self.n_resets += 1
+            return True
+        if dtx > 0:
+            R["left"] = True
+        if dtx < 0:
+            R["right"] = True
+        if dty > 0:
+            R["up"] = True
+        if dty < 0:
+            R["down"] = True
+        for s in self.sites:
+            by0, _, bx0, _ = s.border
+            oy, ox = s.gy, s.gx
+            s.gy += dty * s.tile
+            s.gx += dtx * s.tile
+            # pixels of the new padded window that the old one did not hold
+            Y = (s.gy - by0 + np.arange(s.Hp))[:, None]
+            X = (s.gx - bx0 + np.arange(s.Wp))[None, :]
+            held = (Y >= oy - by0) & (Y < oy - by0 + s.Hp) & (X >= ox - bx0) & (X < ox - bx0 + s.Wp)
+            Pw = s.get_P()
+            Pw[~held] = s.beta.astype(s.dtype)
+            s.set_P(Pw)
+            # pixels of the new view that the old view did not hold
+            Y = (s.gy + np.arange(s.H))[:, None]
+            X = (s.gx + np.arange(s.W))[None, :]
+            seen = (Y >= oy) & (Y < oy + s.H) & (X >= ox) & (X < ox + s.W)
+            Av = s.get_A()
+            Av[~seen] = 0
+            s.set_A(Av)
+            s.N = ~seen
+            s.U[:] = False
+        return False
+
+    # ------------------------------------------------------- step 1 of a site
+    def _truncate(self, i, frame, forced):
+        s = self.sites[i]
+        f32 = np.float32
+        theta = f32(s.spec.theta)
+        A = s.get_A()
+        a = A.astype(f32)
+        if s.spec.kind == "input":
+            assert frame.shape == (s.H, s.W, s.C) and frame.dtype == s.dtype
+            cand = np.ones((s.H, s.W), bool)
+            out = frame.astype(f32) - a
+            newA = frame
+        else:
+            Pw = s.get_P()
+            t = s.view_of_window(Pw).astype(f32)
+            cand = s.U | s.N
+            if forced is not None:
+                cand = np.ones((s.H, s.W), bool)
+            acc = a + t
+            if s.spec.relu:
+                out = np.maximum(acc, f32(0)) - np.maximum(a, f32(0))
+            else:
+                out = acc - a
+            newA = acc.astype(s.dtype)
+        if forced is not None:
+            hit = forced.astype(bool)
+        else:
+            hit = np.abs(out).max(axis=2) > theta
+        M = cand & (s.N | hit)
+        A[M] = newA[M]
+        s.set_A(A)
+        s.delta[:] = 0
+        s.delta[M] = out.astype(s.dtype)[M]
+        if s.spec.kind != "input":
+            Pv = s.view_of_window(Pw)
+            Pv[M] = 0
+            s.set_P(Pw)
+        s.M = M
+        s.L = np.flatnonzero(M.ravel()).astype(np.int32)   # ascending view-linear index
+        s.n_candidates = int(cand.sum())
+        s.N = np.zeros_like(s.N)
+        s.U = np.zeros_like(s.U)
+
+    # ------------------------------------------------------------- one edge
+    def compute_list(self, e):
+        """Outputs (padded-window linear index of the destination, ascending)
+        whose footprint holds at least one updated in-view input pixel."""
+        src, dst = self.sites[e.src], self.sites[e.dst]
+        by0, _, bx0, _ = dst.border
+        cover = np.zeros((dst.Hp, dst.Wp), bool)
+        iy, ix = np.nonzero(src.M)
+        if e.k == 0:
+            cover[iy + by0, ix + bx0] = True
+        elif e.up:
+            f = 1 << e.up
+            for a in range(f):
+                for b in range(f):
+                    cover[iy * f + a + by0, ix * f + b + bx0] = True
+        else:
+            for jy in range(e.k):
+                for jx in range(e.k):
+                    ny, nx = iy + e.pad - jy, ix + e.pad - jx
+                    ok = (ny % e.stride == 0) & (nx % e.stride == 0)
+                    oy, ox = ny[ok] // e.stride, nx[ok] // e.stride
+                    cover[oy + by0, ox + bx0] = True
+        return np.flatnonzero(cover.ravel()).astype(np.int32)
+
+    def _edge(self, e):
+        src, dst = self.sites[e.src], self.sites[e.dst]
+        f32 = np.float32
+        by0, _, bx0, _ = dst.border
+        lst = self.compute_list(e)
+        wy, wx = lst // dst.Wp, lst % dst.Wp          # padded-window coordinates
+        oy, ox = wy - by0, wx - bx0                   # view coordinates of the destination
+        if e.k == 0:
+            y = src.delta[oy, ox].astype(f32)
+        else:
+            f = 1 << e.up
+            cy, cx = oy // f, ox // f                 # conv output coordinates
+            acc = np.zeros((len(lst), dst.C), np.float64)
+            w = e.w.astype(np.float64)
+            for jy in range(e.k):
+                for jx in range(e.k):
+                    iy = cy * e.stride - e.pad + jy
+                    ix = cx * e.stride - e.pad + jx
+                    ok = (iy >= 0) & (iy < src.H) & (ix >= 0) & (ix < src.W)
+                    ok[ok] = src.M[iy[ok], ix[ok]]
+                    rows = np.zeros((len(lst), src.C), np.float64)
+                    rows[ok] = src.delta[iy[ok], ix[ok]]
+                    acc += rows @ w[jy * e.k + jx].T
+            y = acc.astype(f32)
+        Pw = dst.get_P()
+        Pw[wy, wx] = (Pw[wy, wx].astype(f32) + y).astype(dst.dtype)
+        dst.set_P(Pw)
+        inview = (oy >= 0) & (oy < dst.H) & (ox >= 0) & (ox < dst.W)
+        dst.U[oy[inview], ox[inview]] = True
+        return lst
+
+    # ------------------------------------------------------------ public API
+    def layer_forward(self, i, frame=None, forced=None):
+        """Truncate site i (delta, threshold, mask, compaction) and push its
+        delta through all of its outgoing edges into the destinations' P."""
+        self._truncate(i, frame, forced)
+        lists = []
+        for e in self.net.out_edges(i):
+            lists.append(self._edge(e))
+        return lists
+
+    def readout(self, i):
+        s = self.sites[i]
+        out = s.view_of_window(s.get_P()).copy()
+        if s.spec.relu:
+            out = np.maximum(out, s.dtype(0))
+        return out
+
+    def frame(self, X, dty=0, dtx=0, forced=None, forced_all=None):
+        """One frame: shift, every non-terminal site in order, readout.
+        `forced` is an input-site mask; `forced_all` maps site index -> mask."""
+        did_reset = self.shift_camera(dty, dtx)
+        for i, s in enumerate(self.sites):
+            if s.spec.kind == "output":
+                continue
+            fm = None
+            if forced_all is not None:
+                fm = forced_all.get(i)
+            elif i == 0:
+                fm = forced
+            self.layer_forward(i, X if s.spec.kind == "input" else None, fm)
+        outs = [self.readout(i) for i in self.net.terminal_sites()]
+        return outs, did_reset
