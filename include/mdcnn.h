@@ -1,0 +1,205 @@
+/*
+ * mdcnn.h -- C ABI of the MotionDeltaCNN hot path for AMD MI355X (gfx950).
+ *
+ * Sparse CNN inference of frame differences for moving-camera video: the state
+ * of every layer lives in 2-D wrap-around ("spherical") ring buffers; per frame
+ * and per layer the library computes the delta against the accumulated values,
+ * truncates it into a per-pixel update mask, compacts the updated pixels, runs
+ * the padded convolution on those pixels only and accumulates the result into
+ * the next layer's ring buffer.
+ *
+ * Vocabulary.  A *site* is a tensor position that owns state: the network
+ * input, every pre-activation tensor, every network output.  Per site:
+ *   A  accumulated values (ring H x W)                       [Background: DeltaCNN]
+ *   P  pending = truncated-values buffer, enlarged by the dilated border
+ *      (ring (H+b0y+b1y) x (W+b0x+b1x))                      [Padded Convolutions]
+ *   N/U/M per-frame bitmaps: newly unveiled / touched by a producer / updated
+ *   L  compacted list of updated pixels (ascending view-linear index)
+ * An *edge* is a linear operator between two sites: a k x k convolution
+ * (optionally followed by nearest 2^n upsampling) or the identity (residual skip).
+ *
+ * Conventions.
+ *  - All tensors are NHWC ("channels innermost"), storage dtype f32 or f16;
+ *    arithmetic is always fp32 with one rounding per stored value.
+ *  - Every `*_dev` pointer is DEVICE memory owned by the CALLER.  The library
+ *    never allocates or frees device memory, never synchronises, and never reads
+ *    device data back to the host: all work is enqueued on `stream`
+ *    (a hipStream_t passed as void*; NULL = the default stream).
+ *  - Handles (mdcnn_buffer*, mdcnn_net*) are small HOST objects owned by the
+ *    library; destroy them with the matching call.
+ *  - Errors are return codes; on error nothing is enqueued.  mdcnn_last_error()
+ *    gives a thread-local description of the last failure.
+ *  - One camera shift per frame: after mdcnn_shift_camera every non-terminal
+ *    site must be passed through mdcnn_layer_forward (in topological order)
+ *    before the next shift.  mdcnn_frame does exactly that.
+ *  - Calls on the same buffers from several host threads or streams at once race.
+ */
+#ifndef MDCNN_H
+#define MDCNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MDCNN_OK = 0,
+    MDCNN_ERR_NULL = 1,    /* a required pointer is NULL                         */
+    MDCNN_ERR_SHAPE = 2,   /* shapes / channels / borders of the operands disagree */
+    MDCNN_ERR_DTYPE = 3,   /* unknown or mismatching storage dtype               */
+    MDCNN_ERR_ALIGN = 4,   /* device pointer not aligned as documented           */
+    MDCNN_ERR_SIZE = 5,    /* a byte count is too small / a size out of range    */
+    MDCNN_ERR_STATE = 6,   /* call order violated (e.g. forward before first shift) */
+    MDCNN_ERR_HIP = 7      /* a HIP launch failed; see mdcnn_last_error()        */
+} mdcnn_status;
+
+typedef enum { MDCNN_F32 = 0, MDCNN_F16 = 1 } mdcnn_dtype;
+typedef enum { MDCNN_SITE_INPUT = 0, MDCNN_SITE_PREACT = 1, MDCNN_SITE_OUTPUT = 2 } mdcnn_site_kind;
+
+/* Description of one site.  INPUT sites hold A only, OUTPUT sites hold P only. */
+typedef struct {
+    int H, W, C;              /* view extent in pixels of this site, channels           */
+    int dtype;                /* mdcnn_dtype                                            */
+    int kind;                 /* mdcnn_site_kind                                        */
+    int border[4];            /* dilated border of P: before_y, after_y, before_x,      */
+                              /* after_x (max over incoming edges, mdcnn_conv_border)   */
+    int tile;                 /* pixels of this site per camera tile (total stride /    */
+                              /* site stride)                    [Spherical Buffers]    */
+    int relu;                 /* 1: f = ReLU, 0: f = identity                           */
+    float theta;              /* truncation threshold on max-abs over channels, strict >*/
+    const float* bias_dev;    /* C floats: sum of the biases of all producers, or NULL  */
+    int origin_y, origin_x;   /* physical rotation of the rings (any value; results in  */
+                              /* view order do not depend on it)                        */
+} mdcnn_buffer_desc;
+
+typedef struct mdcnn_buffer mdcnn_buffer;
+typedef struct mdcnn_net mdcnn_net;
+
+/* One edge.  Weights: w_dev[tap][cout][cin], tap = ky*k + kx, storage dtype of
+ * the sites it joins, 16-byte aligned.  k == 0: identity edge (w_dev ignored,
+ * stride 1, pad 0, up 0, Cin == Cout).  up > 0 requires k == 1, stride 1, pad 0. */
+typedef struct {
+    int k, stride, pad;
+    int Cin, Cout;
+    int up;                   /* log2 of the nearest-neighbour upsampling factor        */
+    const void* w_dev;
+} mdcnn_conv_desc;
+
+/* Host-only helper.  Width of the dilated border along one axis for a
+ * convolution (k, stride, pad) from `in_extent` to `out_extent` pixels: how many
+ * outputs before 0 / after out_extent-1 still read an in-view input.
+ * 3x3 stride 1 pad 1 gives 1/1 (64 -> 66 outputs).        [Padded Convolutions] */
+mdcnn_status mdcnn_conv_border(int k, int stride, int pad, int in_extent, int out_extent,
+                               int* before, int* after);
+
+/* Host-only.  Bytes of device memory a site needs (rings + per-frame scratch:
+ * bitmaps, delta map, lists, counters).  Always a multiple of 256. */
+mdcnn_status mdcnn_buffer_bytes(const mdcnn_buffer_desc* desc, size_t* bytes);
+
+/* Wrap caller-owned device memory (256-byte aligned, >= mdcnn_buffer_bytes) as a
+ * site.  Enqueues nothing; the memory may hold anything: the first
+ * mdcnn_shift_camera performs a full reset.  The memory must stay valid until
+ * mdcnn_destroy_buffer and must not be touched by the caller in between, except
+ * through mdcnn_read_view / mdcnn_write_view.            [Spherical Buffers] */
+mdcnn_status mdcnn_create_buffer(const mdcnn_buffer_desc* desc, void* dev_mem, size_t bytes,
+                                 mdcnn_buffer** out);
+mdcnn_status mdcnn_destroy_buffer(mdcnn_buffer* buf);
+
+/* Move the camera by (dty, dtx) TILES for all `n` sites of one network at once
+ * (pixel offset per site = tile offset x desc.tile).  Applies the buffer-manager
+ * rule: a step against a direction in which the view has grown since the last
+ * reset, a step of a whole view or more, or the very first call resets every
+ * buffer (A = 0, P = bias, all pixels newly unveiled) and the frame is inferred
+ * densely; otherwise only the pixels entering the padded window are initialised
+ * (P = bias), pixels entering the view get A = 0 and are marked newly unveiled,
+ * and stashed border values of pixels that move from the border into the view
+ * are kept.  *did_full_reset (host, optional) is set to 0/1; it depends on the
+ * shift history only.   [Buffer management; Dynamic Initialization; Supplementary:
+ * Implicit bias application] */
+mdcnn_status mdcnn_shift_camera(mdcnn_buffer* const* bufs, int n, int dty, int dtx,
+                                void* stream, int* did_full_reset);
+
+/* One layer of delta inference on site `in`:
+ *   1. delta + truncation: INPUT site  d = frame - A;  PREACT site  d = f(A+P) - f(A)
+ *      on the pixels a producer touched or that are newly unveiled;
+ *      m = newly unveiled OR (forced mask given ? forced[p] : max_c |d_c| > theta);
+ *      where m: A <- frame (resp. A+P), P <- 0, delta map <- d.
+ *   2. compaction of m into the ascending list L (+ device-side count), and per
+ *      edge the compute list = destination pixels (padded-window linear index,
+ *      ascending) whose footprint holds an updated pixel.
+ *   3. per edge, in the given order: y = conv(delta) on the compute list only,
+ *      P_out <- P_out + y (border pixels included), U_out set.
+ * `frame_dev`: H*W*C storage-dtype values in view order, INPUT sites only (else NULL).
+ * `forced_mask_dev`: NULL, or H*W bytes (0/1) in view order replacing the
+ * threshold test (with a forced mask on a PREACT site every in-view pixel is a
+ * candidate).  `outs[i]` is the destination of `edges[i]`; OUTPUT sites take no
+ * forward call.                  [Background: DeltaCNN; Padded Convolutions] */
+mdcnn_status mdcnn_layer_forward(mdcnn_buffer* in, const void* frame_dev,
+                                 const uint8_t* forced_mask_dev,
+                                 const mdcnn_conv_desc* edges, mdcnn_buffer* const* outs,
+                                 int n_edges, void* stream);
+
+/* Network = sites in topological order + edges (edge i: sites[edge_src[i]] ->
+ * sites[edge_dst[i]], edge_src non-decreasing).  Topology only; holds no device
+ * memory.  Site 0 must be the only INPUT site. */
+mdcnn_status mdcnn_net_create(mdcnn_buffer* const* sites, int n_sites,
+                              const int* edge_src, const int* edge_dst,
+                              const mdcnn_conv_desc* edges, int n_edges, mdcnn_net** out);
+mdcnn_status mdcnn_net_destroy(mdcnn_net* net);
+
+/* One frame: mdcnn_shift_camera, mdcnn_layer_forward over all non-terminal sites
+ * in order, then the readout f(P) of every OUTPUT site in view order, written
+ * back to back (site order) into out_dev (storage dtype; out_bytes must match
+ * exactly).  `forced_mask_dev` applies to the input site only.   [Method, Fig. 3] */
+mdcnn_status mdcnn_frame(mdcnn_net* net, const void* frame_dev, const uint8_t* forced_mask_dev,
+                         int dty, int dtx, void* out_dev, size_t out_bytes, void* stream,
+                         int* did_full_reset);
+
+/* View-ordered access to a site's state (independent of the ring origin). */
+typedef enum {
+    MDCNN_VIEW_A = 0,        /* H*W*C storage dtype: accumulated values                     */
+    MDCNN_VIEW_P = 1,        /* Hp*Wp*C storage dtype: pending values over the padded window */
+    MDCNN_VIEW_DELTA = 2,    /* H*W*C storage dtype: delta map of the last forward (0 where not updated) */
+    MDCNN_VIEW_FLAGS = 3,    /* H*W bytes: bit0 newly unveiled, bit1 touched, bit2 updated  */
+    MDCNN_VIEW_LIST = 4,     /* 1 + H*W int32: count, then the ascending list L             */
+    MDCNN_VIEW_CLIST = 5,    /* 1 + Hp*Wp int32: count, then the compute list of the last   */
+                             /* non-upsampling edge that produced into this site            */
+    MDCNN_VIEW_STATS = 6,    /* 16 int32: [0] updated, [1] candidates, [2] compute-list      */
+                             /* count of the last edge into this site; [8..15] four 64-bit  */
+                             /* sums since creation: updated, candidates, multiply-         */
+                             /* accumulates issued into this site, compute-list entries     */
+    MDCNN_VIEW_OUT = 7       /* H*W*C storage dtype: f(P) over the view (readout)           */
+} mdcnn_view;
+mdcnn_status mdcnn_read_view(const mdcnn_buffer* buf, int what, void* dst_dev, size_t bytes,
+                             void* stream);
+/* Overwrite A, P or FLAGS from view-ordered data (restoring a saved state). */
+mdcnn_status mdcnn_write_view(mdcnn_buffer* buf, int what, const void* src_dev, size_t bytes,
+                              void* stream);
+
+/* Library options (process-wide, host-only). */
+typedef enum {
+    MDCNN_OPT_CONV_PATH = 0, /* 0 auto, 1 force the plain-FMA convolution kernel          */
+    MDCNN_OPT_PROFILE = 1    /* 1: bracket every kernel launch with a pair of HIP events  */
+} mdcnn_option;
+mdcnn_status mdcnn_set_option(int option, int value);
+
+/* Kernel classes reported by mdcnn_profile_read, in this order. */
+typedef enum {
+    MDCNN_K_SHIFT = 0, MDCNN_K_STEP1 = 1, MDCNN_K_LISTS = 2, MDCNN_K_CONV_MFMA = 3,
+    MDCNN_K_CONV_PLAIN = 4, MDCNN_K_IDENTITY = 5, MDCNN_K_READOUT = 6, MDCNN_K_COUNT = 7
+} mdcnn_kernel_class;
+/* Profiling mode only.  BLOCKS until the launches recorded since the last call
+ * have finished, then returns per class the summed device time in milliseconds
+ * and the number of launches (host arrays of n_classes == MDCNN_K_COUNT entries)
+ * and forgets them.  Not thread-safe. */
+mdcnn_status mdcnn_profile_read(int n_classes, double* ms, long long* launches);
+
+const char* mdcnn_last_error(void);
+const char* mdcnn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MDCNN_H */

@@ -1,0 +1,172 @@
+"""ctypes binding of libmdcnn.so: the same names as the C ABI (include/mdcnn.h).
+
+Argument marshalling only -- every step of the path runs in the HIP kernels.
+PyTorch provides device memory (tensors whose data_ptr() is handed over) and
+the stream.  Loading fails loudly when the library has not been built; there
+is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmdcnn.so")
+
+MDCNN_OK = 0
+MDCNN_F32, MDCNN_F16 = 0, 1
+MDCNN_SITE_INPUT, MDCNN_SITE_PREACT, MDCNN_SITE_OUTPUT = 0, 1, 2
+(MDCNN_VIEW_A, MDCNN_VIEW_P, MDCNN_VIEW_DELTA, MDCNN_VIEW_FLAGS, MDCNN_VIEW_LIST,
+ MDCNN_VIEW_CLIST, MDCNN_VIEW_STATS, MDCNN_VIEW_OUT) = range(8)
+MDCNN_OPT_CONV_PATH, MDCNN_OPT_PROFILE = 0, 1
+KERNEL_CLASSES = ["shift", "step1", "lists", "conv_mfma", "conv_plain", "identity", "readout"]
+FLAG_N, FLAG_U, FLAG_M = 1, 2, 4
+
+STATUS_NAMES = {0: "OK", 1: "ERR_NULL", 2: "ERR_SHAPE", 3: "ERR_DTYPE", 4: "ERR_ALIGN",
+                5: "ERR_SIZE", 6: "ERR_STATE", 7: "ERR_HIP"}
+
+EXPORTS = ["mdcnn_conv_border", "mdcnn_buffer_bytes", "mdcnn_create_buffer", "mdcnn_destroy_buffer",
+           "mdcnn_shift_camera", "mdcnn_layer_forward", "mdcnn_net_create", "mdcnn_net_destroy",
+           "mdcnn_frame", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read",
+           "mdcnn_last_error", "mdcnn_version"]
+
+
+class mdcnn_buffer_desc(C.Structure):
+    _fields_ = [("H", C.c_int), ("W", C.c_int), ("C", C.c_int), ("dtype", C.c_int), ("kind", C.c_int),
+                ("border", C.c_int * 4), ("tile", C.c_int), ("relu", C.c_int), ("theta", C.c_float),
+                ("bias_dev", C.c_void_p), ("origin_y", C.c_int), ("origin_x", C.c_int)]
+
+
+class mdcnn_conv_desc(C.Structure):
+    _fields_ = [("k", C.c_int), ("stride", C.c_int), ("pad", C.c_int), ("Cin", C.c_int), ("Cout", C.c_int),
+                ("up", C.c_int), ("w_dev", C.c_void_p)]
+
+
+class MdcnnError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__(f"mdcnn {STATUS_NAMES.get(status, status)}: {msg}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it was not built (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = C.CDLL(LIB_PATH)
+        vp, ip, sz = C.c_void_p, C.POINTER(C.c_int), C.c_size_t
+        L.mdcnn_conv_border.argtypes = [C.c_int] * 5 + [ip, ip]
+        L.mdcnn_buffer_bytes.argtypes = [C.POINTER(mdcnn_buffer_desc), C.POINTER(sz)]
+        L.mdcnn_create_buffer.argtypes = [C.POINTER(mdcnn_buffer_desc), vp, sz, C.POINTER(vp)]
+        L.mdcnn_destroy_buffer.argtypes = [vp]
+        L.mdcnn_shift_camera.argtypes = [C.POINTER(vp), C.c_int, C.c_int, C.c_int, vp, ip]
+        L.mdcnn_layer_forward.argtypes = [vp, vp, vp, C.POINTER(mdcnn_conv_desc), C.POINTER(vp), C.c_int, vp]
+        L.mdcnn_net_create.argtypes = [C.POINTER(vp), C.c_int, ip, ip, C.POINTER(mdcnn_conv_desc), C.c_int,
+                                       C.POINTER(vp)]
+        L.mdcnn_net_destroy.argtypes = [vp]
+        L.mdcnn_frame.argtypes = [vp, vp, vp, C.c_int, C.c_int, vp, sz, vp, ip]
+        L.mdcnn_read_view.argtypes = [vp, C.c_int, vp, sz, vp]
+        L.mdcnn_write_view.argtypes = [vp, C.c_int, vp, sz, vp]
+        L.mdcnn_set_option.argtypes = [C.c_int, C.c_int]
+        L.mdcnn_profile_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_longlong)]
+        L.mdcnn_last_error.restype = C.c_char_p
+        L.mdcnn_version.restype = C.c_char_p
+        for name in EXPORTS:
+            if name not in ("mdcnn_last_error", "mdcnn_version"):
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _check(status):
+    if status != MDCNN_OK:
+        raise MdcnnError(status, lib().mdcnn_last_error().decode())
+
+
+def mdcnn_last_error() -> str:
+    return lib().mdcnn_last_error().decode()
+
+
+def mdcnn_version() -> str:
+    return lib().mdcnn_version().decode()
+
+
+def mdcnn_set_option(option: int, value: int):
+    _check(lib().mdcnn_set_option(option, value))
+
+
+def mdcnn_profile_read():
+    """{class name: (milliseconds, launches)} since the last call (blocks)."""
+    n = len(KERNEL_CLASSES)
+    ms, cnt = (C.c_double * n)(), (C.c_longlong * n)()
+    _check(lib().mdcnn_profile_read(n, ms, cnt))
+    return {k: (ms[i], cnt[i]) for i, k in enumerate(KERNEL_CLASSES)}
+
+
+def mdcnn_conv_border(k, stride, pad, in_extent, out_extent):
+    b, a = C.c_int(), C.c_int()
+    _check(lib().mdcnn_conv_border(k, stride, pad, in_extent, out_extent, C.byref(b), C.byref(a)))
+    return b.value, a.value
+
+
+def mdcnn_buffer_bytes(desc: mdcnn_buffer_desc) -> int:
+    n = C.c_size_t()
+    _check(lib().mdcnn_buffer_bytes(C.byref(desc), C.byref(n)))
+    return n.value
+
+
+def mdcnn_create_buffer(desc: mdcnn_buffer_desc, dev_ptr: int, nbytes: int) -> int:
+    h = C.c_void_p()
+    _check(lib().mdcnn_create_buffer(C.byref(desc), dev_ptr, nbytes, C.byref(h)))
+    return h.value
+
+
+def mdcnn_destroy_buffer(buf: int):
+    _check(lib().mdcnn_destroy_buffer(buf))
+
+
+def _handles(bufs):
+    return (C.c_void_p * len(bufs))(*bufs)
+
+
+def mdcnn_shift_camera(bufs, dty: int, dtx: int, stream: int = 0) -> bool:
+    r = C.c_int()
+    _check(lib().mdcnn_shift_camera(_handles(bufs), len(bufs), int(dty), int(dtx), stream, C.byref(r)))
+    return bool(r.value)
+
+
+def mdcnn_layer_forward(buf: int, frame_ptr, forced_ptr, edges, outs, stream: int = 0):
+    n = len(edges)
+    arr = (mdcnn_conv_desc * max(n, 1))(*edges)
+    _check(lib().mdcnn_layer_forward(buf, frame_ptr, forced_ptr, arr, _handles(outs) if n else None, n, stream))
+
+
+def mdcnn_net_create(sites, edge_src, edge_dst, edges) -> int:
+    h = C.c_void_p()
+    n = len(edges)
+    _check(lib().mdcnn_net_create(_handles(sites), len(sites), (C.c_int * n)(*edge_src), (C.c_int * n)(*edge_dst),
+                                  (mdcnn_conv_desc * n)(*edges), n, C.byref(h)))
+    return h.value
+
+
+def mdcnn_net_destroy(net: int):
+    _check(lib().mdcnn_net_destroy(net))
+
+
+def mdcnn_frame(net: int, frame_ptr: int, forced_ptr, dty: int, dtx: int, out_ptr: int, out_bytes: int,
+                stream: int = 0) -> bool:
+    r = C.c_int()
+    _check(lib().mdcnn_frame(net, frame_ptr, forced_ptr, int(dty), int(dtx), out_ptr, out_bytes, stream, C.byref(r)))
+    return bool(r.value)
+
+
+def mdcnn_read_view(buf: int, what: int, dst_ptr: int, nbytes: int, stream: int = 0):
+    _check(lib().mdcnn_read_view(buf, what, dst_ptr, nbytes, stream))
+
+
+def mdcnn_write_view(buf: int, what: int, src_ptr: int, nbytes: int, stream: int = 0):
+    _check(lib().mdcnn_write_view(buf, what, src_ptr, nbytes, stream))

@@ -1,0 +1,529 @@
+// Host side of the C ABI: descriptors, the buffer manager (camera shifts, reset
+// rule, ring origins), argument validation and launch sequencing.  Allocates no
+// device memory and never synchronises.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "mdcnn_internal.h"
+
+using namespace mdcnn;
+
+namespace {
+
+thread_local char g_err[512] = "";
+int g_conv_path = 0;
+int g_profile = 0;
+
+// Profiling mode: every kernel launch is bracketed by a pair of events on its
+// own stream; mdcnn_profile_read waits for them and sums the times per class.
+struct TimedLaunch { int cls; hipEvent_t start, stop; };
+std::vector<TimedLaunch> g_timed;
+std::vector<hipEvent_t> g_event_pool;
+
+hipEvent_t take_event() {
+    if (!g_event_pool.empty()) { hipEvent_t e = g_event_pool.back(); g_event_pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+template <typename F>
+hipError_t timed(int cls, hipStream_t st, F&& launch) {
+    if (!g_profile) return launch();
+    TimedLaunch t{cls, take_event(), take_event()};
+    if (!t.start || !t.stop) return hipErrorOutOfMemory;
+    (void)hipEventRecord(t.start, st);
+    hipError_t err = launch();
+    (void)hipEventRecord(t.stop, st);
+    g_timed.push_back(t);
+    return err;
+}
+
+mdcnn_status fail(mdcnn_status st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+size_t esize(int dtype) { return dtype == MDCNN_F16 ? 2 : 4; }
+long long pmod(long long v, long long n) { long long r = v % n; return r < 0 ? r + n : r; }
+
+struct Layout {
+    size_t A, P, flags, delta, list, clist, counters, partials, cpartials, total;
+    int Hp, Wp, nblk1, nseg_c;
+};
+
+mdcnn_status check_desc(const mdcnn_buffer_desc* d) {
+    if (!d) return fail(MDCNN_ERR_NULL, "descriptor is NULL");
+    if (d->dtype != MDCNN_F32 && d->dtype != MDCNN_F16) return fail(MDCNN_ERR_DTYPE, "unknown dtype %d", d->dtype);
+    if (d->kind < MDCNN_SITE_INPUT || d->kind > MDCNN_SITE_OUTPUT) return fail(MDCNN_ERR_SHAPE, "unknown site kind %d", d->kind);
+    if (d->H < 1 || d->W < 1 || d->C < 1) return fail(MDCNN_ERR_SHAPE, "H, W, C must be positive");
+    if ((long long)d->H * d->W > (1 << 24) || d->C > 4096) return fail(MDCNN_ERR_SIZE, "site too large (H*W <= 2^24, C <= 4096)");
+    for (int i = 0; i < 4; ++i)
+        if (d->border[i] < 0 || d->border[i] > 64) return fail(MDCNN_ERR_SHAPE, "border[%d]=%d out of range [0,64]", i, d->border[i]);
+    if (d->tile < 1) return fail(MDCNN_ERR_SHAPE, "tile must be >= 1");
+    if (d->kind == MDCNN_SITE_INPUT && (d->border[0] | d->border[1] | d->border[2] | d->border[3]))
+        return fail(MDCNN_ERR_SHAPE, "an INPUT site has no border");
+    return MDCNN_OK;
+}
+
+void make_layout(const mdcnn_buffer_desc& d, Layout& L) {
+    const size_t e = esize(d.dtype);
+    const bool hasA = d.kind != MDCNN_SITE_OUTPUT, hasP = d.kind != MDCNN_SITE_INPUT;
+    L.Hp = d.H + d.border[0] + d.border[1];
+    L.Wp = d.W + d.border[2] + d.border[3];
+    SiteDev tmp{};
+    tmp.C = d.C; tmp.dtype = d.dtype;
+    const int ppb = step1_pixels_per_block(tmp);
+    L.nblk1 = (d.H * d.W + ppb - 1) / ppb;
+    L.nseg_c = (L.Hp * L.Wp + kSegPixels - 1) / kSegPixels;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
+    L.A = take(hasA ? (size_t)d.H * d.W * d.C * e : 0);
+    L.P = take(hasP ? (size_t)L.Hp * L.Wp * d.C * e : 0);
+    L.flags = take(hasA ? (size_t)d.H * d.W : 0);
+    L.delta = take(hasA ? (size_t)d.H * d.W * d.C * e : 0);
+    L.list = take(hasA ? (size_t)d.H * d.W * 4 : 0);
+    L.clist = take(hasP ? (size_t)L.Hp * L.Wp * 4 : 0);
+    L.counters = take(kNumCounters * 4);
+    L.partials = take(hasA ? (size_t)L.nblk1 * 2 * 4 : 0);
+    L.cpartials = take(hasP ? (size_t)L.nseg_c * 4 : 0);
+    L.total = off;
+}
+
+}  // namespace
+
+struct mdcnn_buffer {
+    mdcnn_buffer_desc d;
+    Layout L;
+    SiteDev dev;
+    long long gy, gx;          // global pixel coordinate of view pixel (0, 0)
+    bool fresh;                // no reset yet
+    bool r_up, r_down, r_left, r_right;   // directions in which growth is restricted
+};
+
+struct mdcnn_net {
+    std::vector<mdcnn_buffer*> sites;
+    std::vector<int> esrc, edst;
+    std::vector<mdcnn_conv_desc> edges;
+    size_t out_bytes;
+};
+
+namespace {
+
+void refresh_origins(mdcnn_buffer* b) {
+    const mdcnn_buffer_desc& d = b->d;
+    b->dev.a_oy = (int)pmod(b->gy + d.origin_y, d.H);
+    b->dev.a_ox = (int)pmod(b->gx + d.origin_x, d.W);
+    b->dev.p_oy = (int)pmod(b->gy - d.border[0] + d.origin_y, b->L.Hp);
+    b->dev.p_ox = (int)pmod(b->gx - d.border[2] + d.origin_x, b->L.Wp);
+}
+
+mdcnn_status border_1d(int k, int stride, int pad, int in_extent, int out_extent, int* before, int* after) {
+    if (k == 0) { *before = *after = 0; return MDCNN_OK; }
+    if (k < 1 || stride < 1 || pad < 0 || in_extent < 1 || out_extent < 1)
+        return fail(MDCNN_ERR_SHAPE, "bad convolution geometry k=%d stride=%d pad=%d", k, stride, pad);
+    int b0 = (k - 1 - pad) / stride;       // k-1-pad >= 0 here or the numerator is negative
+    if (k - 1 - pad < 0) b0 = 0;
+    int b1 = (in_extent - 1 + pad) / stride - (out_extent - 1);
+    *before = b0 < 0 ? 0 : b0;
+    *after = b1 < 0 ? 0 : b1;
+    return MDCNN_OK;
+}
+
+// Everything that must hold for the kernels of one edge to stay in bounds.
+mdcnn_status validate_edge(const mdcnn_buffer* in, const mdcnn_buffer* out, const mdcnn_conv_desc& c, int idx) {
+    if (!out) return fail(MDCNN_ERR_NULL, "edge %d: destination buffer is NULL", idx);
+    if (out == in) return fail(MDCNN_ERR_SHAPE, "edge %d: source and destination are the same site", idx);
+    if (out->d.kind == MDCNN_SITE_INPUT) return fail(MDCNN_ERR_SHAPE, "edge %d: destination is an INPUT site", idx);
+    if (out->d.dtype != in->d.dtype) return fail(MDCNN_ERR_DTYPE, "edge %d: dtype mismatch", idx);
+    if (c.Cin != in->d.C || c.Cout != out->d.C)
+        return fail(MDCNN_ERR_SHAPE, "edge %d: channels %d->%d do not match sites %d->%d", idx, c.Cin, c.Cout, in->d.C, out->d.C);
+    if (c.k == 0) {
+        if (c.stride != 1 || c.pad != 0 || c.up != 0 || c.Cin != c.Cout || in->d.H != out->d.H || in->d.W != out->d.W)
+            return fail(MDCNN_ERR_SHAPE, "edge %d: identity edge needs equal shapes, stride 1, pad 0, up 0", idx);
+        return MDCNN_OK;
+    }
+    if (c.k < 1 || c.k > 5 || c.stride < 1 || c.stride > 4 || c.pad < 0 || c.pad >= c.k || c.up < 0 || c.up > 5)
+        return fail(MDCNN_ERR_SHAPE, "edge %d: unsupported geometry k=%d stride=%d pad=%d up=%d", idx, c.k, c.stride, c.pad, c.up);
+    if (c.up && (c.k != 1 || c.stride != 1 || c.pad != 0))
+        return fail(MDCNN_ERR_SHAPE, "edge %d: upsampling needs a 1x1 stride-1 convolution", idx);
+    if (in->d.H + 2 * c.pad < c.k || in->d.W + 2 * c.pad < c.k)
+        return fail(MDCNN_ERR_SHAPE, "edge %d: kernel larger than the padded input", idx);
+    const int oh = (in->d.H + 2 * c.pad - c.k) / c.stride + 1, ow = (in->d.W + 2 * c.pad - c.k) / c.stride + 1;
+    if ((oh << c.up) != out->d.H || (ow << c.up) != out->d.W)
+        return fail(MDCNN_ERR_SHAPE, "edge %d: output %dx%d does not match destination %dx%d", idx, oh << c.up, ow << c.up, out->d.H, out->d.W);
+    int by0, by1, bx0, bx1;
+    mdcnn_status st = border_1d(c.k, c.stride, c.pad, in->d.H, oh, &by0, &by1);
+    if (st) return st;
+    st = border_1d(c.k, c.stride, c.pad, in->d.W, ow, &bx0, &bx1);
+    if (st) return st;
+    const int* b = out->d.border;
+    if (by0 > b[0] || by1 > b[1] || bx0 > b[2] || bx1 > b[3])
+        return fail(MDCNN_ERR_SHAPE, "edge %d: destination border {%d,%d,%d,%d} smaller than the convolution reaches {%d,%d,%d,%d}",
+                    idx, b[0], b[1], b[2], b[3], by0, by1, bx0, bx1);
+    if (!c.w_dev) return fail(MDCNN_ERR_NULL, "edge %d: weights are NULL", idx);
+    if ((uintptr_t)c.w_dev & 15) return fail(MDCNN_ERR_ALIGN, "edge %d: weights must be 16-byte aligned", idx);
+    return MDCNN_OK;
+}
+
+EdgeDev make_edge(const mdcnn_buffer* in, const mdcnn_buffer* out, const mdcnn_conv_desc& c) {
+    EdgeDev e{};
+    e.delta = in->dev.delta; e.sflags = in->dev.flags; e.slist = in->dev.list; e.scounters = in->dev.counters;
+    e.sH = in->d.H; e.sW = in->d.W; e.Cin = c.Cin;
+    e.P = out->dev.P; e.dflags = out->d.kind == MDCNN_SITE_OUTPUT ? nullptr : out->dev.flags;
+    e.clist = out->dev.clist; e.cpartials = out->dev.cpartials; e.dcounters = out->dev.counters;
+    e.dH = out->d.H; e.dW = out->d.W; e.Cout = c.Cout; e.Hp = out->L.Hp; e.Wp = out->L.Wp;
+    e.by0 = out->d.border[0]; e.bx0 = out->d.border[2]; e.p_oy = out->dev.p_oy; e.p_ox = out->dev.p_ox;
+    e.w = c.w_dev; e.k = c.k; e.stride = c.k ? c.stride : 1; e.pad = c.k ? c.pad : 0; e.up = c.k ? c.up : 0;
+    return e;
+}
+
+mdcnn_status validate_forward(const mdcnn_buffer* in, const void* frame, const mdcnn_conv_desc* edges,
+                              mdcnn_buffer* const* outs, int n_edges) {
+    if (!in) return fail(MDCNN_ERR_NULL, "input buffer is NULL");
+    if (in->d.kind == MDCNN_SITE_OUTPUT) return fail(MDCNN_ERR_STATE, "OUTPUT sites take no forward call");
+    if (in->fresh) return fail(MDCNN_ERR_STATE, "mdcnn_shift_camera must be called before the first forward");
+    if (in->d.kind == MDCNN_SITE_INPUT) {
+        if (!frame) return fail(MDCNN_ERR_NULL, "frame is NULL for an INPUT site");
+        if ((uintptr_t)frame & 15) return fail(MDCNN_ERR_ALIGN, "frame must be 16-byte aligned");
+    } else if (frame) {
+        return fail(MDCNN_ERR_SHAPE, "frame given for a site that is not INPUT");
+    }
+    if (n_edges < 0 || (n_edges > 0 && (!edges || !outs))) return fail(MDCNN_ERR_NULL, "edges/outs missing");
+    for (int i = 0; i < n_edges; ++i) {
+        mdcnn_status st = validate_edge(in, outs[i], edges[i], i);
+        if (st) return st;
+        if (outs[i]->fresh) return fail(MDCNN_ERR_STATE, "edge %d: destination was never reset (shift first)", i);
+    }
+    return MDCNN_OK;
+}
+
+mdcnn_status do_forward(mdcnn_buffer* in, const void* frame, const uint8_t* forced, const mdcnn_conv_desc* edges,
+                        mdcnn_buffer* const* outs, int n_edges, hipStream_t st) {
+    hipError_t err = timed(kClsStep1, st, [&] { return launch_step1(in->dev, frame, forced, st); });
+    if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "step-1 launch: %s", hipGetErrorString(err));
+    int i = 0;
+    bool first = true;
+    do {
+        // one batch: up to kMaxEdgesPerLaunch edges with pairwise distinct destinations
+        EdgeBatch eb{};
+        int j = i;
+        for (; j < n_edges && eb.n < kMaxEdgesPerLaunch; ++j) {
+            bool dup = false;
+            for (int q = i; q < j; ++q) dup |= outs[q] == outs[j];
+            if (dup) break;
+            eb.e[eb.n++] = make_edge(in, outs[j], edges[j]);
+        }
+        err = timed(kClsLists, st, [&] { return launch_lists(in->dev, eb, first, st); });
+        if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "list launch: %s", hipGetErrorString(err));
+        for (int q = 0; q < eb.n; ++q) {
+            int cls = kClsConvPlain;
+            if (g_profile) {          // the class is known only after dispatch: record around, file under it
+                TimedLaunch t{0, take_event(), take_event()};
+                if (!t.start || !t.stop) return fail(MDCNN_ERR_HIP, "cannot create profiling events");
+                (void)hipEventRecord(t.start, st);
+                err = launch_conv(eb.e[q], in->d.dtype, g_conv_path, st, &cls);
+                (void)hipEventRecord(t.stop, st);
+                t.cls = cls;
+                g_timed.push_back(t);
+            } else {
+                err = launch_conv(eb.e[q], in->d.dtype, g_conv_path, st, &cls);
+            }
+            if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "conv launch (edge %d): %s", i + q, hipGetErrorString(err));
+        }
+        first = false;
+        i = j;
+    } while (i < n_edges);
+    return MDCNN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* mdcnn_last_error(void) { return g_err; }
+const char* mdcnn_version(void) { return "mdcnn 0.1 (gfx950)"; }
+
+mdcnn_status mdcnn_set_option(int option, int value) {
+    if (option == MDCNN_OPT_CONV_PATH && (value == 0 || value == 1)) { g_conv_path = value; return MDCNN_OK; }
+    if (option == MDCNN_OPT_PROFILE && (value == 0 || value == 1)) { g_profile = value; return MDCNN_OK; }
+    return fail(MDCNN_ERR_SIZE, "unknown option %d / value %d", option, value);
+}
+
+mdcnn_status mdcnn_profile_read(int n_classes, double* ms, long long* launches) {
+    if (!ms || !launches) return fail(MDCNN_ERR_NULL, "ms/launches is NULL");
+    if (n_classes != kNumClasses) return fail(MDCNN_ERR_SIZE, "n_classes must be %d", (int)kNumClasses);
+    for (int i = 0; i < n_classes; ++i) { ms[i] = 0; launches[i] = 0; }
+    mdcnn_status rc = MDCNN_OK;
+    for (TimedLaunch& t : g_timed) {
+        float dt = 0.f;
+        hipError_t err = hipEventSynchronize(t.stop);
+        if (err == hipSuccess) err = hipEventElapsedTime(&dt, t.start, t.stop);
+        if (err != hipSuccess) rc = fail(MDCNN_ERR_HIP, "profiling event: %s", hipGetErrorString(err));
+        else { ms[t.cls] += dt; launches[t.cls] += 1; }
+        g_event_pool.push_back(t.start);
+        g_event_pool.push_back(t.stop);
+    }
+    g_timed.clear();
+    return rc;
+}
+
+mdcnn_status mdcnn_conv_border(int k, int stride, int pad, int in_extent, int out_extent, int* before, int* after) {
+    if (!before || !after) return fail(MDCNN_ERR_NULL, "before/after is NULL");
+    return border_1d(k, stride, pad, in_extent, out_extent, before, after);
+}
+
+mdcnn_status mdcnn_buffer_bytes(const mdcnn_buffer_desc* desc, size_t* bytes) {
+    mdcnn_status st = check_desc(desc);
+    if (st) return st;
+    if (!bytes) return fail(MDCNN_ERR_NULL, "bytes is NULL");
+    Layout L;
+    make_layout(*desc, L);
+    *bytes = L.total;
+    return MDCNN_OK;
+}
+
+mdcnn_status mdcnn_create_buffer(const mdcnn_buffer_desc* desc, void* dev_mem, size_t bytes, mdcnn_buffer** out) {
+    mdcnn_status st = check_desc(desc);
+    if (st) return st;
+    if (!dev_mem || !out) return fail(MDCNN_ERR_NULL, "dev_mem/out is NULL");
+    if ((uintptr_t)dev_mem & 255) return fail(MDCNN_ERR_ALIGN, "dev_mem must be 256-byte aligned");
+    mdcnn_buffer* b = new (std::nothrow) mdcnn_buffer();
+    if (!b) return fail(MDCNN_ERR_SIZE, "out of host memory");
+    b->d = *desc;
+    make_layout(*desc, b->L);
+    if (bytes < b->L.total) {
+        size_t need = b->L.total;
+        delete b;
+        return fail(MDCNN_ERR_SIZE, "dev_mem holds %zu bytes, %zu needed", bytes, need);
+    }
+    char* base = (char*)dev_mem;
+    const bool hasA = desc->kind != MDCNN_SITE_OUTPUT, hasP = desc->kind != MDCNN_SITE_INPUT;
+    SiteDev& s = b->dev;
+    s = SiteDev{};
+    s.A = hasA ? base + b->L.A : nullptr;
+    s.P = hasP ? base + b->L.P : nullptr;
+    s.flags = hasA ? (uint8_t*)(base + b->L.flags) : nullptr;
+    s.delta = hasA ? base + b->L.delta : nullptr;
+    s.list = hasA ? (int*)(base + b->L.list) : nullptr;
+    s.clist = hasP ? (int*)(base + b->L.clist) : nullptr;
+    s.counters = (int*)(base + b->L.counters);
+    s.partials = hasA ? (int*)(base + b->L.partials) : nullptr;
+    s.cpartials = hasP ? (int*)(base + b->L.cpartials) : nullptr;
+    s.bias = desc->bias_dev;
+    s.H = desc->H; s.W = desc->W; s.C = desc->C; s.Hp = b->L.Hp; s.Wp = b->L.Wp;
+    s.by0 = desc->border[0]; s.bx0 = desc->border[2];
+    s.theta = desc->theta; s.relu = desc->relu; s.kind = desc->kind; s.dtype = desc->dtype;
+    b->gy = b->gx = 0;
+    b->fresh = true;
+    b->r_up = b->r_down = b->r_left = b->r_right = false;
+    refresh_origins(b);
+    *out = b;
+    return MDCNN_OK;
+}
+
+mdcnn_status mdcnn_destroy_buffer(mdcnn_buffer* buf) {
+    delete buf;
+    return MDCNN_OK;
+}
+
+mdcnn_status mdcnn_shift_camera(mdcnn_buffer* const* bufs, int n, int dty, int dtx, void* stream, int* did_full_reset) {
+    if (!bufs || n < 1) return fail(MDCNN_ERR_NULL, "no buffers");
+    for (int i = 0; i < n; ++i) {
+        if (!bufs[i]) return fail(MDCNN_ERR_NULL, "buffer %d is NULL", i);
+        const mdcnn_buffer *a = bufs[0], *b = bufs[i];
+        if (a->fresh != b->fresh || a->r_up != b->r_up || a->r_down != b->r_down || a->r_left != b->r_left ||
+            a->r_right != b->r_right)
+            return fail(MDCNN_ERR_STATE, "buffer %d has a different shift history than buffer 0", i);
+    }
+    const mdcnn_buffer* f = bufs[0];
+    bool full = f->fresh;
+    full |= (dtx > 0 && f->r_right) || (dtx < 0 && f->r_left) || (dty > 0 && f->r_down) || (dty < 0 && f->r_up);
+    for (int i = 0; i < n; ++i) {
+        const mdcnn_buffer_desc& d = bufs[i]->d;
+        const long long sy = (long long)dty * d.tile, sx = (long long)dtx * d.tile;
+        full |= (sy >= d.H || -sy >= d.H || sx >= d.W || -sx >= d.W);
+    }
+    hipStream_t st = (hipStream_t)stream;
+    for (int i = 0; i < n; ++i) {
+        mdcnn_buffer* b = bufs[i];
+        const mdcnn_buffer_desc& d = b->d;
+        const long long sy = (long long)dty * d.tile, sx = (long long)dtx * d.tile;
+        b->gy += sy;
+        b->gx += sx;
+        refresh_origins(b);
+        KeepRect pr{b->L.Hp, b->L.Wp, 0, 0, 0, 0}, ar{d.H, d.W, 0, 0, 0, 0};
+        if (!full) {
+            // the old window, expressed in coordinates of the new one, is shifted by (-sy, -sx)
+            auto keep = [](int ext, long long s, int& lo, int& hi) {   // |s| < ext here
+                lo = -s > 0 ? (int)-s : 0;
+                hi = ext - s < ext ? (int)(ext - s) : ext;
+                if (hi < lo) hi = lo;
+            };
+            keep(b->L.Hp, sy, pr.y0, pr.y1);
+            keep(b->L.Wp, sx, pr.x0, pr.x1);
+            keep(d.H, sy, ar.y0, ar.y1);
+            keep(d.W, sx, ar.x0, ar.x1);
+        }
+        const int rc = full ? (b->fresh ? 2 : 1) : 0;
+        hipError_t err = timed(kClsShift, st, [&] { return launch_shift_fill(b->dev, pr, ar, rc, st); });
+        if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "shift launch (buffer %d): %s", i, hipGetErrorString(err));
+        if (full) {
+            b->r_up = b->r_down = b->r_left = b->r_right = false;
+            b->fresh = false;
+        } else {
+            // growing in one direction overwrites the stash of the opposite side
+            if (dtx > 0) b->r_left = true;
+            if (dtx < 0) b->r_right = true;
+            if (dty > 0) b->r_up = true;
+            if (dty < 0) b->r_down = true;
+        }
+    }
+    if (did_full_reset) *did_full_reset = full ? 1 : 0;
+    return MDCNN_OK;
+}
+
+mdcnn_status mdcnn_layer_forward(mdcnn_buffer* in, const void* frame_dev, const uint8_t* forced_mask_dev,
+                                 const mdcnn_conv_desc* edges, mdcnn_buffer* const* outs, int n_edges, void* stream) {
+    mdcnn_status st = validate_forward(in, frame_dev, edges, outs, n_edges);
+    if (st) return st;
+    return do_forward(in, frame_dev, forced_mask_dev, edges, outs, n_edges, (hipStream_t)stream);
+}
+
+mdcnn_status mdcnn_net_create(mdcnn_buffer* const* sites, int n_sites, const int* edge_src, const int* edge_dst,
+                              const mdcnn_conv_desc* edges, int n_edges, mdcnn_net** out) {
+    if (!sites || !out || n_sites < 2) return fail(MDCNN_ERR_NULL, "sites/out missing or fewer than 2 sites");
+    if (n_edges < 1 || !edge_src || !edge_dst || !edges) return fail(MDCNN_ERR_NULL, "edges missing");
+    for (int i = 0; i < n_sites; ++i) {
+        if (!sites[i]) return fail(MDCNN_ERR_NULL, "site %d is NULL", i);
+        if ((sites[i]->d.kind == MDCNN_SITE_INPUT) != (i == 0))
+            return fail(MDCNN_ERR_SHAPE, "site 0, and only site 0, must be the INPUT site");
+    }
+    for (int i = 0; i < n_edges; ++i) {
+        if (edge_src[i] < 0 || edge_dst[i] >= n_sites || edge_src[i] >= edge_dst[i])
+            return fail(MDCNN_ERR_SHAPE, "edge %d: needs 0 <= src < dst < n_sites", i);
+        if (i && edge_src[i] < edge_src[i - 1]) return fail(MDCNN_ERR_SHAPE, "edges must be grouped by ascending source site");
+        if (sites[edge_src[i]]->d.kind == MDCNN_SITE_OUTPUT) return fail(MDCNN_ERR_SHAPE, "edge %d leaves an OUTPUT site", i);
+        mdcnn_status st = validate_edge(sites[edge_src[i]], sites[edge_dst[i]], edges[i], i);
+        if (st) return st;
+    }
+    mdcnn_net* net = new (std::nothrow) mdcnn_net();
+    if (!net) return fail(MDCNN_ERR_SIZE, "out of host memory");
+    net->sites.assign(sites, sites + n_sites);
+    net->esrc.assign(edge_src, edge_src + n_edges);
+    net->edst.assign(edge_dst, edge_dst + n_edges);
+    net->edges.assign(edges, edges + n_edges);
+    net->out_bytes = 0;
+    for (int i = 0; i < n_sites; ++i)
+        if (sites[i]->d.kind == MDCNN_SITE_OUTPUT)
+            net->out_bytes += (size_t)sites[i]->d.H * sites[i]->d.W * sites[i]->d.C * esize(sites[i]->d.dtype);
+    *out = net;
+    return MDCNN_OK;
+}
+
+mdcnn_status mdcnn_net_destroy(mdcnn_net* net) {
+    delete net;
+    return MDCNN_OK;
+}
+
+mdcnn_status mdcnn_frame(mdcnn_net* net, const void* frame_dev, const uint8_t* forced_mask_dev, int dty, int dtx,
+                         void* out_dev, size_t out_bytes, void* stream, int* did_full_reset) {
+    if (!net) return fail(MDCNN_ERR_NULL, "net is NULL");
+    if (!frame_dev || !out_dev) return fail(MDCNN_ERR_NULL, "frame/out is NULL");
+    if (((uintptr_t)frame_dev | (uintptr_t)out_dev) & 15) return fail(MDCNN_ERR_ALIGN, "frame/out must be 16-byte aligned");
+    if (out_bytes != net->out_bytes) return fail(MDCNN_ERR_SIZE, "out_bytes is %zu, the outputs take %zu", out_bytes, net->out_bytes);
+    hipStream_t st = (hipStream_t)stream;
+    mdcnn_status rc = mdcnn_shift_camera(net->sites.data(), (int)net->sites.size(), dty, dtx, stream, did_full_reset);
+    if (rc) return rc;
+    const int n_edges = (int)net->edges.size();
+    int e0 = 0;
+    std::vector<mdcnn_buffer*> outs;
+    for (int i = 0; i < (int)net->sites.size(); ++i) {
+        mdcnn_buffer* s = net->sites[i];
+        if (s->d.kind == MDCNN_SITE_OUTPUT) continue;
+        int e1 = e0;
+        while (e1 < n_edges && net->esrc[e1] == i) ++e1;
+        outs.clear();
+        for (int e = e0; e < e1; ++e) outs.push_back(net->sites[net->edst[e]]);
+        rc = do_forward(s, i == 0 ? frame_dev : nullptr, i == 0 ? forced_mask_dev : nullptr,
+                        net->edges.data() + e0, outs.data(), e1 - e0, st);
+        if (rc) return rc;
+        e0 = e1;
+    }
+    char* o = (char*)out_dev;
+    for (mdcnn_buffer* s : net->sites) {
+        if (s->d.kind != MDCNN_SITE_OUTPUT) continue;
+        hipError_t err = timed(kClsReadout, st, [&] { return launch_read_view(s->dev, MDCNN_VIEW_OUT, o, st); });
+        if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "readout launch: %s", hipGetErrorString(err));
+        o += (size_t)s->d.H * s->d.W * s->d.C * esize(s->d.dtype);
+    }
+    return MDCNN_OK;
+}
+
+static mdcnn_status view_bytes(const mdcnn_buffer* b, int what, size_t* need) {
+    const mdcnn_buffer_desc& d = b->d;
+    const size_t e = esize(d.dtype);
+    const bool hasA = d.kind != MDCNN_SITE_OUTPUT, hasP = d.kind != MDCNN_SITE_INPUT;
+    switch (what) {
+        case MDCNN_VIEW_A:
+        case MDCNN_VIEW_DELTA:
+            if (!hasA) return fail(MDCNN_ERR_STATE, "OUTPUT sites hold no A / delta");
+            *need = (size_t)d.H * d.W * d.C * e; return MDCNN_OK;
+        case MDCNN_VIEW_P:
+            if (!hasP) return fail(MDCNN_ERR_STATE, "INPUT sites hold no P");
+            *need = (size_t)b->L.Hp * b->L.Wp * d.C * e; return MDCNN_OK;
+        case MDCNN_VIEW_OUT:
+            if (!hasP) return fail(MDCNN_ERR_STATE, "INPUT sites hold no P");
+            *need = (size_t)d.H * d.W * d.C * e; return MDCNN_OK;
+        case MDCNN_VIEW_FLAGS:
+            if (!hasA) return fail(MDCNN_ERR_STATE, "OUTPUT sites hold no flags");
+            *need = (size_t)d.H * d.W; return MDCNN_OK;
+        case MDCNN_VIEW_LIST:
+            if (!hasA) return fail(MDCNN_ERR_STATE, "OUTPUT sites hold no list");
+            *need = ((size_t)d.H * d.W + 1) * 4; return MDCNN_OK;
+        case MDCNN_VIEW_CLIST:
+            if (!hasP) return fail(MDCNN_ERR_STATE, "INPUT sites hold no compute list");
+            *need = ((size_t)b->L.Hp * b->L.Wp + 1) * 4; return MDCNN_OK;
+        case MDCNN_VIEW_STATS:
+            *need = 16 * 4; return MDCNN_OK;
+        default:
+            return fail(MDCNN_ERR_SIZE, "unknown view %d", what);
+    }
+}
+
+mdcnn_status mdcnn_read_view(const mdcnn_buffer* buf, int what, void* dst_dev, size_t bytes, void* stream) {
+    if (!buf || !dst_dev) return fail(MDCNN_ERR_NULL, "buf/dst is NULL");
+    if (buf->fresh) return fail(MDCNN_ERR_STATE, "buffer was never reset (shift first)");
+    size_t need = 0;
+    mdcnn_status st = view_bytes(buf, what, &need);
+    if (st) return st;
+    if (bytes != need) return fail(MDCNN_ERR_SIZE, "view %d takes %zu bytes, %zu given", what, need, bytes);
+    if ((uintptr_t)dst_dev & 15) return fail(MDCNN_ERR_ALIGN, "dst must be 16-byte aligned");
+    hipError_t err = launch_read_view(buf->dev, what, dst_dev, (hipStream_t)stream);
+    if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "read launch: %s", hipGetErrorString(err));
+    return MDCNN_OK;
+}
+
+mdcnn_status mdcnn_write_view(mdcnn_buffer* buf, int what, const void* src_dev, size_t bytes, void* stream) {
+    if (!buf || !src_dev) return fail(MDCNN_ERR_NULL, "buf/src is NULL");
+    if (buf->fresh) return fail(MDCNN_ERR_STATE, "buffer was never reset (shift first)");
+    if (what != MDCNN_VIEW_A && what != MDCNN_VIEW_P && what != MDCNN_VIEW_FLAGS)
+        return fail(MDCNN_ERR_SIZE, "only A, P and FLAGS can be written");
+    size_t need = 0;
+    mdcnn_status st = view_bytes(buf, what, &need);
+    if (st) return st;
+    if (bytes != need) return fail(MDCNN_ERR_SIZE, "view %d takes %zu bytes, %zu given", what, need, bytes);
+    hipError_t err = launch_write_view(buf->dev, what, src_dev, (hipStream_t)stream);
+    if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "write launch: %s", hipGetErrorString(err));
+    return MDCNN_OK;
+}
+
+}  // extern "C"

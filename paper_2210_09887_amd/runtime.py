@@ -1,0 +1,139 @@
+"""Marshalling helper: instantiate a network description on the GPU.
+
+Allocates device memory through PyTorch (site buffers, weights, biases),
+creates the library handles and forwards calls to the C ABI.  No step of the
+method is computed here.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+_KIND = {"input": B.MDCNN_SITE_INPUT, "preact": B.MDCNN_SITE_PREACT, "output": B.MDCNN_SITE_OUTPUT}
+
+
+class GpuNet:
+    """`spec` is any object with the fields of inputs.nets.NetSpec."""
+
+    def __init__(self, spec, origins=None, device="cuda:0"):
+        if not torch.cuda.is_available():
+            raise RuntimeError("mdcnn needs a GPU: there is no CPU path")
+        B.lib()
+        self.spec = spec
+        self.dev = torch.device(device)
+        self.tdtype = torch.float16 if spec.dtype == "f16" else torch.float32
+        self.ndtype = np.float16 if spec.dtype == "f16" else np.float32
+        self.esize = 2 if spec.dtype == "f16" else 4
+        dt = B.MDCNN_F16 if spec.dtype == "f16" else B.MDCNN_F32
+        n = len(spec.sites)
+        self.shape = [(spec.H // s.stride, spec.W // s.stride, s.C) for s in spec.sites]
+        border = [[0, 0, 0, 0] for _ in range(n)]
+        bias = [None] * n
+        self.weights, self.edges, self.esrc, self.edst = [], [], [], []
+        for e in spec.edges:
+            Hs, Ws, _ = self.shape[e.src]
+            cd = B.mdcnn_conv_desc(e.k, e.stride, e.pad, spec.sites[e.src].C, spec.sites[e.dst].C, e.up, None)
+            if e.k:
+                oh = (Hs + 2 * e.pad - e.k) // e.stride + 1
+                ow = (Ws + 2 * e.pad - e.k) // e.stride + 1
+                by = B.mdcnn_conv_border(e.k, e.stride, e.pad, Hs, oh)
+                bx = B.mdcnn_conv_border(e.k, e.stride, e.pad, Ws, ow)
+                border[e.dst] = [max(a, b) for a, b in zip(border[e.dst], [by[0], by[1], bx[0], bx[1]])]
+                w = torch.from_numpy(np.ascontiguousarray(e.w)).to(self.dev)
+                assert w.dtype == self.tdtype
+                self.weights.append(w)
+                cd.w_dev = w.data_ptr()
+                if e.b is not None:
+                    bias[e.dst] = e.b.astype(np.float32) if bias[e.dst] is None else bias[e.dst] + e.b.astype(np.float32)
+            self.edges.append(cd)
+            self.esrc.append(e.src)
+            self.edst.append(e.dst)
+        self.bias = [None if b is None else torch.from_numpy(b).to(self.dev) for b in bias]
+        self.mem, self.bufs, self.win = [], [], []
+        for i, s in enumerate(spec.sites):
+            H, W, Cc = self.shape[i]
+            d = B.mdcnn_buffer_desc()
+            d.H, d.W, d.C, d.dtype, d.kind = H, W, Cc, dt, _KIND[s.kind]
+            for j in range(4):
+                d.border[j] = border[i][j]
+            d.tile = spec.total_stride // s.stride
+            d.relu = int(s.relu)
+            d.theta = float(s.theta)
+            d.bias_dev = None if self.bias[i] is None else self.bias[i].data_ptr()
+            d.origin_y, d.origin_x = (0, 0) if origins is None else origins[i]
+            nbytes = B.mdcnn_buffer_bytes(d)
+            mem = torch.empty(nbytes, dtype=torch.uint8, device=self.dev)
+            self.mem.append(mem)
+            self.bufs.append(B.mdcnn_create_buffer(d, mem.data_ptr(), nbytes))
+            self.win.append((H + border[i][0] + border[i][1], W + border[i][2] + border[i][3]))
+        self.border = border
+        self.net = B.mdcnn_net_create(self.bufs, self.esrc, self.edst, self.edges)
+        self.terminals = [i for i, s in enumerate(spec.sites) if s.kind == "output"]
+        self.out_elems = sum(int(np.prod(self.shape[i])) for i in self.terminals)
+        self.out = torch.empty(self.out_elems, dtype=self.tdtype, device=self.dev)
+
+    def close(self):
+        if self.net:
+            B.mdcnn_net_destroy(self.net)
+            self.net = None
+        for b in self.bufs:
+            B.mdcnn_destroy_buffer(b)
+        self.bufs = []
+
+    @staticmethod
+    def _stream():
+        return torch.cuda.current_stream().cuda_stream
+
+    # -- the four calls of the boundary -------------------------------------------------
+    def shift_camera(self, dty, dtx) -> bool:
+        return B.mdcnn_shift_camera(self.bufs, dty, dtx, self._stream())
+
+    def layer_forward(self, i, frame=None, forced=None):
+        idx = [j for j, s in enumerate(self.esrc) if s == i]
+        B.mdcnn_layer_forward(self.bufs[i], None if frame is None else frame.data_ptr(),
+                              None if forced is None else forced.data_ptr(),
+                              [self.edges[j] for j in idx], [self.bufs[self.edst[j]] for j in idx], self._stream())
+
+    def frame(self, X, dty=0, dtx=0, forced=None, out=None):
+        """X: device tensor [H, W, C] storage dtype.  Returns (flat output tensor, did_reset)."""
+        out = self.out if out is None else out
+        r = B.mdcnn_frame(self.net, X.data_ptr(), None if forced is None else forced.data_ptr(), dty, dtx,
+                          out.data_ptr(), out.numel() * self.esize, self._stream())
+        return out, r
+
+    def split_outputs(self, out):
+        res, o = [], 0
+        for i in self.terminals:
+            n = int(np.prod(self.shape[i]))
+            res.append(out[o:o + n].reshape(self.shape[i]))
+            o += n
+        return res
+
+    # -- state access ---------------------------------------------------------------------
+    def read(self, i, what) -> np.ndarray:
+        H, W, Cc = self.shape[i]
+        Hp, Wp = self.win[i]
+        if what in (B.MDCNN_VIEW_A, B.MDCNN_VIEW_DELTA, B.MDCNN_VIEW_OUT):
+            t = torch.empty((H, W, Cc), dtype=self.tdtype, device=self.dev)
+        elif what == B.MDCNN_VIEW_P:
+            t = torch.empty((Hp, Wp, Cc), dtype=self.tdtype, device=self.dev)
+        elif what == B.MDCNN_VIEW_FLAGS:
+            t = torch.empty((H, W), dtype=torch.uint8, device=self.dev)
+        elif what == B.MDCNN_VIEW_LIST:
+            t = torch.empty(H * W + 1, dtype=torch.int32, device=self.dev)
+        elif what == B.MDCNN_VIEW_CLIST:
+            t = torch.empty(Hp * Wp + 1, dtype=torch.int32, device=self.dev)
+        else:
+            t = torch.empty(16, dtype=torch.int32, device=self.dev)
+        B.mdcnn_read_view(self.bufs[i], what, t.data_ptr(), t.numel() * t.element_size(), self._stream())
+        a = t.cpu().numpy()
+        if what in (B.MDCNN_VIEW_LIST, B.MDCNN_VIEW_CLIST):
+            return a[1:1 + a[0]].copy()
+        return a
+
+    def write(self, i, what, arr: np.ndarray):
+        t = torch.from_numpy(np.ascontiguousarray(arr)).to(self.dev)
+        B.mdcnn_write_view(self.bufs[i], what, t.data_ptr(), t.numel() * t.element_size(), self._stream())
+        torch.cuda.current_stream().synchronize()      # t must outlive the copy

@@ -1,0 +1,200 @@
+"""Lock-step drivers that run the HIP path (through the C ABI) beside the oracle.
+
+Three comparison protocols, because masks come from float compares and
+convolution sums differ in their last bits:
+  teacher_forced -- before every mdcnn_layer_forward the GPU site (and the P of
+                    its destinations) is loaded with the oracle's state bit for
+                    bit: masks, lists, compute lists and U flags must then be
+                    bit-exact, A / P / delta within the fp tolerance.
+  mask_forced    -- whole sequence on the GPU with the oracle's masks forced at
+                    every site: all floating-point outputs within tolerance.
+  free_running   -- mdcnn_frame end to end: reset decisions and the input-site
+                    list bit-exact, inner masks nearly equal, outputs close.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle.mdcnn_oracle import OracleNet
+from paper_2210_09887_amd import binding as B
+from paper_2210_09887_amd.runtime import GpuNet
+
+TOL = {"f32": 1e-4, "f16": 2e-2}
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def maxerr(a, b):
+    return float(np.abs(a.astype(np.float64) - b.astype(np.float64)).max()) if a.size else 0.0
+
+
+def oracle_flags(s):
+    return (s.N.astype(np.uint8) * B.FLAG_N) | (s.U.astype(np.uint8) * B.FLAG_U)
+
+
+def load_site(g: GpuNet, o: OracleNet, i: int):
+    s = o.sites[i]
+    if s.spec.kind != "output":
+        g.write(i, B.MDCNN_VIEW_A, s.get_A())
+        g.write(i, B.MDCNN_VIEW_FLAGS, oracle_flags(s))
+    if s.spec.kind != "input":
+        g.write(i, B.MDCNN_VIEW_P, s.get_P())
+
+
+def teacher_forced(net, frames, shifts, forced=None, origins=None, log=None):
+    """Returns the worst fp error seen; raises AssertionError on any integer mismatch."""
+    tol = TOL[net.dtype]
+    g, o = GpuNet(net, origins), OracleNet(net, origins)
+    worst = 0.0
+    try:
+        for t, X in enumerate(frames):
+            dy, dx = (int(v) for v in shifts[t])
+            r_g = g.shift_camera(dy, dx)
+            r_o = o.shift_camera(dy, dx)
+            assert r_g == r_o, f"frame {t}: reset decision differs"
+            if t == 0 or r_o:
+                # state after a (re)initialisation must already agree exactly
+                for i, s in enumerate(o.sites):
+                    if s.spec.kind != "input":
+                        assert np.array_equal(g.read(i, B.MDCNN_VIEW_P), s.get_P()), f"frame {t} site {i}: P after reset"
+                    if s.spec.kind != "output":
+                        assert np.array_equal(g.read(i, B.MDCNN_VIEW_A), s.get_A()), f"frame {t} site {i}: A after reset"
+            for i, s in enumerate(o.sites):
+                if s.spec.kind == "output":
+                    continue
+                if s.spec.kind != "output":
+                    # flags set by the GPU's own shift / producers must match the oracle's N, U
+                    fl = g.read(i, B.MDCNN_VIEW_FLAGS)
+                    assert np.array_equal(fl & (B.FLAG_N | B.FLAG_U), oracle_flags(s)), f"frame {t} site {i}: N/U flags"
+                edges = net.out_edges(i)
+                load_site(g, o, i)
+                for e in edges:
+                    load_site(g, o, e.dst)
+                fm = forced[t] if (forced is not None and i == 0) else None
+                Xd = dev(X) if i == 0 else None
+                fd = dev(fm) if fm is not None else None
+                g.layer_forward(i, Xd, fd)
+                lists = o.layer_forward(i, X if i == 0 else None, fm)
+                torch.cuda.synchronize()
+                where = f"frame {t} site {i} ({s.spec.name})"
+                fl = g.read(i, B.MDCNN_VIEW_FLAGS)
+                assert np.array_equal((fl & B.FLAG_M) != 0, s.M), where + ": update mask"
+                assert np.array_equal(g.read(i, B.MDCNN_VIEW_LIST), s.L), where + ": list L"
+                st = g.read(i, B.MDCNN_VIEW_STATS)
+                assert st[0] == len(s.L) and st[1] == s.n_candidates, where + ": counters"
+                errs = [maxerr(g.read(i, B.MDCNN_VIEW_A), s.get_A()), maxerr(g.read(i, B.MDCNN_VIEW_DELTA), s.delta)]
+                if s.spec.kind != "input":
+                    errs.append(maxerr(g.read(i, B.MDCNN_VIEW_P), s.get_P()))
+                seen = set()
+                for e, lst in zip(edges, lists):
+                    d = o.sites[e.dst]
+                    w2 = where + f" -> site {e.dst}"
+                    if not e.up and e.dst not in seen:
+                        pass
+                    errs.append(maxerr(g.read(e.dst, B.MDCNN_VIEW_P), d.get_P()))
+                    if d.spec.kind != "output":
+                        fl = g.read(e.dst, B.MDCNN_VIEW_FLAGS)
+                        assert np.array_equal(fl & (B.FLAG_N | B.FLAG_U), oracle_flags(d)), w2 + ": U flags"
+                    seen.add(e.dst)
+                # compute list: the last non-upsampling edge into each destination
+                last = {}
+                for e, lst in zip(edges, lists):
+                    if not e.up:
+                        last[e.dst] = lst
+                for dst, lst in last.items():
+                    assert np.array_equal(g.read(dst, B.MDCNN_VIEW_CLIST), lst), where + f": compute list into {dst}"
+                worst = max(worst, max(errs))
+                assert max(errs) < tol, where + f": fp error {max(errs):.3e} (A, delta, P, P_dst...) = {errs}"
+            for i in net.terminal_sites():
+                worst = max(worst, maxerr(g.read(i, B.MDCNN_VIEW_OUT), o.readout(i)))
+            if log:
+                log(f"  teacher-forced frame {t}: reset={r_o} worst={worst:.2e}")
+    finally:
+        g.close()
+    assert worst < tol
+    return worst
+
+
+def oracle_run(net, frames, shifts, forced=None, origins=None):
+    """Oracle alone; returns per-frame outputs, masks of every non-terminal site, resets."""
+    o = OracleNet(net, origins)
+    outs, masks, resets = [], [], []
+    for t, X in enumerate(frames):
+        dy, dx = (int(v) for v in shifts[t])
+        out, r = o.frame(X, dy, dx, None if forced is None else forced[t])
+        outs.append(out)
+        resets.append(r)
+        masks.append({i: s.M.copy() for i, s in enumerate(o.sites) if s.spec.kind != "output"})
+    return o, outs, masks, resets
+
+
+def mask_forced(net, frames, shifts, forced=None, log=None):
+    tol = TOL[net.dtype]
+    o, outs, masks, resets = oracle_run(net, frames, shifts, forced)
+    g = GpuNet(net)
+    worst = 0.0
+    try:
+        for t, X in enumerate(frames):
+            dy, dx = (int(v) for v in shifts[t])
+            assert g.shift_camera(dy, dx) == resets[t]
+            keep = []
+            for i, s in enumerate(net.sites):
+                if s.kind == "output":
+                    continue
+                fm = dev(masks[t][i].astype(np.uint8))
+                Xd = dev(X) if i == 0 else None
+                keep += [fm, Xd]
+                g.layer_forward(i, Xd, fm)
+            torch.cuda.synchronize()
+            for k, i in enumerate(net.terminal_sites()):
+                e = maxerr(g.read(i, B.MDCNN_VIEW_OUT), outs[t][k])
+                worst = max(worst, e)
+                assert e < tol, f"frame {t}: output error {e:.3e}"
+            for i, s in enumerate(net.sites):
+                if s.kind != "output":
+                    fl = g.read(i, B.MDCNN_VIEW_FLAGS)
+                    assert np.array_equal((fl & B.FLAG_M) != 0, masks[t][i]), f"frame {t} site {i}: forced mask not honoured"
+            if log:
+                log(f"  mask-forced frame {t}: reset={resets[t]} worst={worst:.2e}")
+        for i, s in enumerate(o.sites):
+            if s.spec.kind != "output":
+                worst = max(worst, maxerr(g.read(i, B.MDCNN_VIEW_A), s.get_A()))
+            if s.spec.kind != "input":
+                worst = max(worst, maxerr(g.read(i, B.MDCNN_VIEW_P), s.get_P()))
+    finally:
+        g.close()
+    assert worst < tol, f"final state error {worst:.3e}"
+    return worst
+
+
+def free_running(net, frames, shifts, forced=None, origins=None, log=None):
+    """mdcnn_frame end to end.  Returns dict(out_err, mask_mismatch, resets, outputs)."""
+    o, outs, masks, resets = oracle_run(net, frames, shifts, forced, origins)
+    g = GpuNet(net, origins)
+    out_err, mism, total = 0.0, 0, 0
+    got_all = []
+    try:
+        for t, X in enumerate(frames):
+            dy, dx = (int(v) for v in shifts[t])
+            fd = dev(forced[t]) if forced is not None else None
+            out, r = g.frame(dev(X), dy, dx, fd)
+            torch.cuda.synchronize()
+            assert r == resets[t], f"frame {t}: reset decision differs"
+            got = [x.cpu().numpy() for x in g.split_outputs(out)]
+            got_all.append(got)
+            for a, b in zip(got, outs[t]):
+                out_err = max(out_err, maxerr(a, b))
+            l0 = g.read(0, B.MDCNN_VIEW_LIST)
+            assert np.array_equal(l0, np.flatnonzero(masks[t][0].ravel())), f"frame {t}: input-site list differs"
+            for i in masks[t]:
+                m = (g.read(i, B.MDCNN_VIEW_FLAGS) & B.FLAG_M) != 0
+                mism += int((m != masks[t][i]).sum())
+                total += m.size
+            if log:
+                log(f"  free-running frame {t}: reset={r} out_err={out_err:.2e} mask mismatches={mism}/{total}")
+    finally:
+        g.close()
+    return dict(out_err=out_err, mask_mismatch=mism / max(total, 1), resets=resets, outputs=got_all, oracle_outputs=outs)

@@ -1,0 +1,162 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
+
+Integer outputs (update masks, lists L, compute lists, counters, reset
+decisions) must be bit-exact; floating-point state within max-abs 1e-4 (fp32)
+or 2e-2 (fp16 storage, fp32 accumulate).
+"""
+import numpy as np
+import pytest
+import torch
+
+from inputs import build_net, build_sequence
+
+pytestmark = pytest.mark.gpu
+
+
+def log(msg):
+    print(msg, flush=True)
+
+
+def set_theta(net, th):
+    for s in net.sites:
+        s.theta = th
+    return net
+
+
+CASES = {
+    # name: (config, net overrides, sequence overrides)
+    "c1_single_conv": (1, {}, {}),
+    "c2_cnn5_88x72": (2, dict(H=88, W=72), dict(n_frames=6, H=88, W=72)),
+    "c3_resnet_96": (3, dict(H=96, W=96, widths=(32, 64, 64, 128)), dict(n_frames=8, H=96, W=96)),
+    "c3_resnet_plain_80x112": (3, dict(H=80, W=112, widths=(8, 16, 24, 40)), dict(n_frames=6, H=80, W=112)),
+    "c4_hrnet_128x96": (4, dict(H=128, W=96, widths=(32, 64, 64, 128), blocks=1), dict(n_frames=10, H=128, W=96)),
+    "c5_bottleneck_40": (5, dict(H=40, W=40, C=128, Cm=32), dict(n_frames=12, H=40, W=40, C=128, density=0.2, shift_every=4, shift=8)),
+}
+
+
+def load_case(name):
+    cfg, kn, ks = CASES[name]
+    net = build_net(cfg, **kn)
+    seq = build_sequence(cfg, **ks)
+    return net, seq
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_teacher_forced(name):
+    import gpu_harness as H
+    net, seq = load_case(name)
+    log(f"[teacher-forced] {name}: {len(net.sites)} sites, {len(seq.frames)} frames")
+    worst = H.teacher_forced(net, seq.frames, seq.shifts, seq.forced, log=log)
+    log(f"[teacher-forced] {name}: worst fp error {worst:.3e}")
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_mask_forced(name):
+    import gpu_harness as H
+    net, seq = load_case(name)
+    log(f"[mask-forced] {name}")
+    worst = H.mask_forced(net, seq.frames, seq.shifts, seq.forced, log=log)
+    log(f"[mask-forced] {name}: worst fp error {worst:.3e}")
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_free_running(name):
+    import gpu_harness as H
+    net, seq = load_case(name)
+    log(f"[free-running] {name}")
+    r = H.free_running(net, seq.frames, seq.shifts, seq.forced, log=log)
+    th = max(s.theta for s in net.sites)
+    log(f"[free-running] {name}: out_err={r['out_err']:.3e} mask mismatch={r['mask_mismatch']:.2e} resets={sum(r['resets'])}")
+    assert r["mask_mismatch"] < 0.02
+    assert r["out_err"] < 10 * th + 4 * H.TOL[net.dtype]
+
+
+@pytest.mark.parametrize("name", ["c1_single_conv", "c3_resnet_96", "c4_hrnet_128x96"])
+def test_theta0_free_running_matches_oracle(name):
+    """Threshold 0: nothing is truncated, so the free-running GPU result must
+    agree with the oracle (and hence with the dense canvas result) within tolerance."""
+    import gpu_harness as H
+    net, seq = load_case(name)
+    set_theta(net, 0.0)
+    r = H.free_running(net, seq.frames, seq.shifts, seq.forced, log=log)
+    log(f"[theta 0] {name}: out_err={r['out_err']:.3e}")
+    assert r["out_err"] < 2 * H.TOL[net.dtype]
+
+
+def test_theta0_static_equals_library_dense_conv():
+    """Threshold 0, no camera motion: output == dense CNN of the current frame
+    computed with torch's CPU convolution (not the oracle)."""
+    import gpu_harness as H
+    import refs
+    net, seq = load_case("c2_cnn5_88x72")
+    set_theta(net, 0.0)
+    from paper_2210_09887_amd.runtime import GpuNet
+    g = GpuNet(net)
+    try:
+        for t, X in enumerate(seq.frames):
+            out, _ = g.frame(H.dev(X), 0, 0)
+            got = g.split_outputs(out)[0].cpu().numpy()
+            want = refs.dense_cnn(net, X)[0]
+            assert H.maxerr(got, want) < 1e-4
+    finally:
+        g.close()
+
+
+@pytest.mark.parametrize("name", ["c1_single_conv", "c3_resnet_96"])
+def test_origin_rotation_is_invisible(name):
+    """Any physical ring origin gives bit-identical view-ordered results."""
+    import gpu_harness as H
+    net, seq = load_case(name)
+    rng = np.random.default_rng(11)
+    origins = [(int(rng.integers(0, 1000)), int(rng.integers(-1000, 0))) for _ in net.sites]
+    a = H.free_running(net, seq.frames, seq.shifts, seq.forced)
+    b = H.free_running(net, seq.frames, seq.shifts, seq.forced, origins=origins)
+    for fa, fb in zip(a["outputs"], b["outputs"]):
+        for x, y in zip(fa, fb):
+            assert np.array_equal(x, y)
+
+
+def test_plain_conv_path_on_f16():
+    """The plain-FMA kernel and the MFMA kernel agree with the oracle on the same net."""
+    import gpu_harness as H
+    from paper_2210_09887_amd import binding as B
+    net, seq = load_case("c3_resnet_96")
+    B.mdcnn_set_option(B.MDCNN_OPT_CONV_PATH, 1)
+    try:
+        H.teacher_forced(net, seq.frames[:3], seq.shifts[:3], log=log)
+    finally:
+        B.mdcnn_set_option(B.MDCNN_OPT_CONV_PATH, 0)
+
+
+def test_degenerate_frames():
+    """Identical consecutive frames produce empty lists and leave the state untouched;
+    a shift of a whole view resets; calls in the wrong order are refused."""
+    import gpu_harness as H
+    from paper_2210_09887_amd import binding as B
+    from paper_2210_09887_amd.runtime import GpuNet
+    net, seq = load_case("c2_cnn5_88x72")
+    g = GpuNet(net)
+    try:
+        with pytest.raises(B.MdcnnError) as ei:
+            g.layer_forward(0, H.dev(seq.frames[0]))
+        assert ei.value.status == 6
+        X = H.dev(seq.frames[0])
+        out0, r0 = g.frame(X, 0, 0)
+        out0 = out0.clone()
+        assert r0
+        out1, r1 = g.frame(X, 0, 0)
+        torch.cuda.synchronize()
+        assert not r1
+        for i, s in enumerate(net.sites):
+            if s.kind != "output":
+                assert len(g.read(i, B.MDCNN_VIEW_LIST)) == 0
+                assert g.read(i, B.MDCNN_VIEW_STATS)[0] == 0
+        assert torch.equal(out0, out1)
+        _, r2 = g.frame(X, 0, net.W // net.total_stride)      # a whole view to the right
+        assert r2
+        _, r3 = g.frame(X, 0, 1)
+        _, r4 = g.frame(X, 0, -1)                              # back over a restricted side
+        assert (r3, r4) == (False, True)
+        torch.cuda.synchronize()
+    finally:
+        g.close()
