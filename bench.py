@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the MotionDeltaCNN hot path on one MI355X.
+
+One step = one frame of the whole per-frame path (camera shift + dynamic
+initialisation, delta/truncation/mask, compaction, padded sparse convolutions,
+residual adds, readout) through `mdcnn_frame` on the headline workload: the
+ResNet-18-style 512x512 fp16 network on the seeded 60-frame moving-camera
+sequence, all frames resident in HBM before the timed region starts.  The
+sequence is replayed cyclically (the jump back to its start is one more camera
+shift, which the buffer manager answers with a full reset).
+
+Prints ONE JSON line.  Besides the throughput it carries
+  roofline     -- the dominant kernel class, timed with HIP events recorded by
+                  the library around every launch of a second, instrumented pass
+                  over the same frames (algorithmic flops / bytes from device-side
+                  counters of that pass);
+  cpu_baseline -- the NumPy oracle timed on the host cores on the first frames
+                  of the same sequence.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_F16_TFLOPS = 2500.0
+PEAK_FP32_VALU_TFLOPS = 157.3
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=180)
+    ap.add_argument("--warmup", type=int, default=60)
+    ap.add_argument("--config", type=int, default=3, help="BASELINE config (3 = headline)")
+    ap.add_argument("--density", type=float, default=0.2, help="config 5 only")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle baseline; 0 disables it")
+    ap.add_argument("--dense", action="store_true", help="library dense mode: threshold 0 and all pixels forced")
+    return ap.parse_args()
+
+
+def site_bytes_per_pixel(g, i):
+    return g.shape[i][2] * g.esize
+
+
+def algorithmic_bytes(g, spec, before, after, frames):
+    """Algorithmic HBM bytes of the memory-bound passes over `frames` frames,
+    from the device-side counters (differences of the running sums)."""
+    d = {k: after["per_site"][k] - before["per_site"][k] for k in after["per_site"]}
+    step1 = 0
+    for i, s in enumerate(spec.sites):
+        if s.kind == "output":
+            continue
+        H, W, _ = g.shape[i]
+        cb = site_bytes_per_pixel(g, i)
+        # flags read+write per pixel; candidates read A and (X or P); updated write A, delta (and P)
+        writes = 2 if s.kind == "input" else 3
+        step1 += frames * H * W * 2 + int(d["candidates"][i]) * 2 * cb + int(d["updated"][i]) * writes * cb
+    return dict(step1=step1)
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from inputs import build_net, build_sequence
+    from paper_2210_09887_amd import binding as B
+    from paper_2210_09887_amd.runtime import GpuNet
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+
+    cfg = a.config
+    net = build_net(cfg)
+    seq = build_sequence(cfg, **({"density": a.density} if cfg == 5 else {}))
+    if a.dense:
+        for s in net.sites:
+            s.theta = 0.0
+    T = len(seq.frames)
+    shifts = seq.shifts.astype(np.int64).copy()
+    shifts[0] = -shifts[1:].sum(axis=0)            # closing the cycle: jump back to the start
+    frames = torch.from_numpy(seq.frames).cuda()
+    forced = None
+    if a.dense:
+        forced = torch.ones((T, net.H, net.W), dtype=torch.uint8, device="cuda")
+    elif seq.forced is not None:
+        forced = torch.from_numpy(seq.forced).cuda()
+    g = GpuNet(net)
+
+    state = {"t": 0, "resets": 0}
+
+    def step():
+        t = state["t"] % T
+        dy, dx = (0, 0) if state["t"] == 0 else (int(shifts[t][0]), int(shifts[t][1]))
+        _, r = g.frame(frames[t], dy, dx, None if forced is None else forced[t])
+        state["t"] += 1
+        state["resets"] += int(r)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    state["resets"] = 0
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    resets_timed = state["resets"]
+
+    # ---- instrumented pass: per-class kernel time (HIP events around every launch)
+    before = g.totals()
+    B.mdcnn_set_option(B.MDCNN_OPT_PROFILE, 1)
+    B.mdcnn_profile_read()
+    n_prof = min(a.steps, 2 * T)
+    t1 = time.perf_counter()
+    for _ in range(n_prof):
+        step()
+    prof = B.mdcnn_profile_read()
+    dt_prof = time.perf_counter() - t1
+    B.mdcnn_set_option(B.MDCNN_OPT_PROFILE, 0)
+    after = g.totals()
+
+    flops_mfma = 2.0 * (after["macs_mfma"] - before["macs_mfma"])
+    flops_plain = 2.0 * (after["macs_plain"] - before["macs_plain"])
+    ab = algorithmic_bytes(g, net, before, after, n_prof)
+    classes = {}
+    for k, (ms, cnt) in prof.items():
+        if cnt:
+            classes[k] = {"ms_total": round(ms, 3), "launches": int(cnt), "avg_us": round(1e3 * ms / cnt, 2)}
+    kernel_ms = sum(v[0] for v in prof.values())
+    dominant = max(prof, key=lambda k: prof[k][0])
+    rl_all = {}
+    if prof["conv_mfma"][1]:
+        ms, cnt = prof["conv_mfma"]
+        ach = flops_mfma / (ms * 1e-3) / 1e12
+        rl_all["conv_mfma"] = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
+                               "frac": round(ach / PEAK_MFMA_F16_TFLOPS, 4), "traffic": None,
+                               "flop_per_launch": round(flops_mfma / cnt), "avg_us": round(1e3 * ms / cnt, 2), "launches": int(cnt)}
+    if prof["conv_plain"][1]:
+        ms, cnt = prof["conv_plain"]
+        ach = flops_plain / (ms * 1e-3) / 1e12
+        rl_all["conv_plain"] = {"bound": "alu", "achieved": round(ach, 3), "peak": PEAK_FP32_VALU_TFLOPS, "unit": "TFLOP/s",
+                                "frac": round(ach / PEAK_FP32_VALU_TFLOPS, 5), "traffic": None,
+                                "flop_per_launch": round(flops_plain / cnt), "avg_us": round(1e3 * ms / cnt, 2), "launches": int(cnt)}
+    if prof["step1"][1]:
+        ms, cnt = prof["step1"]
+        ach = ab["step1"] / (ms * 1e-3) / 1e9
+        rl_all["step1"] = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                           "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None,
+                           "bytes_per_launch": round(ab["step1"] / cnt), "avg_us": round(1e3 * ms / cnt, 2), "launches": int(cnt)}
+    roofline = dict(rl_all.get(dominant, next(iter(rl_all.values()))))
+    roofline["kernel"] = dominant if dominant in rl_all else next(iter(rl_all))
+
+    # ---- CPU baseline: the oracle as it stands, on the first frames of the same sequence
+    cpu = None
+    if a.cpu_seconds > 0:
+        from oracle.mdcnn_oracle import OracleNet
+        o = OracleNet(net)
+        tc = time.perf_counter()
+        n_cpu = 0
+        while n_cpu < T and (n_cpu < 2 or time.perf_counter() - tc < a.cpu_seconds):
+            dy, dx = (0, 0) if n_cpu == 0 else (int(seq.shifts[n_cpu][0]), int(seq.shifts[n_cpu][1]))
+            fm = None
+            if a.dense:
+                fm = np.ones((net.H, net.W), np.uint8)
+            elif seq.forced is not None:
+                fm = seq.forced[n_cpu]
+            o.frame(seq.frames[n_cpu], dy, dx, fm)
+            n_cpu += 1
+        dtc = time.perf_counter() - tc
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count()
+        cpu = {"value": round(n_cpu / dtc, 4), "unit": "frames/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"first {n_cpu} frames of the same sequence ({o.n_resets} dense/reset frames), {dtc:.1f} s"}
+
+    upd = after["per_site"]["updated"] - before["per_site"]["updated"]
+    dens = [float(upd[i]) / (n_prof * g.shape[i][0] * g.shape[i][1]) for i, s in enumerate(net.sites) if s.kind != "output"]
+    out = {
+        "metric": "frames/s (ResNet-18-style 512x512, 1 GPU)" if cfg == 3 else f"frames/s (config {cfg}, 1 GPU)",
+        "value": round(a.steps / dt, 2), "unit": "frames/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(1e3 * dt / a.steps, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": net.dtype, "data": "synthetic",
+        "config": {"workload": f"config {cfg}: {net.name}, {T}-frame seeded moving-camera sequence replayed cyclically"
+                               + (", library dense mode" if a.dense else "")
+                               + (f", density {a.density}" if cfg == 5 else ""),
+                   "input": [net.H, net.W, net.sites[0].C], "sites": len(net.sites), "edges": len(net.edges),
+                   "resets_in_timed_steps": resets_timed, "mean_update_density": round(float(np.mean(dens)), 4),
+                   "input_update_density": round(dens[0], 4)},
+        "roofline": roofline,
+        "roofline_all": rl_all,
+        "kernel_classes": classes,
+        "kernel_ms_per_step": round(kernel_ms / n_prof, 4),
+        "instrumented_ms_per_step": round(1e3 * dt_prof / n_prof, 4),
+        "cpu_baseline": cpu,
+    }
+    g.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

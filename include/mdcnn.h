@@ -166,10 +166,11 @@ typedef enum {
     MDCNN_VIEW_LIST = 4,     /* 1 + H*W int32: count, then the ascending list L             */
     MDCNN_VIEW_CLIST = 5,    /* 1 + Hp*Wp int32: count, then the compute list of the last   */
                              /* non-upsampling edge that produced into this site            */
-    MDCNN_VIEW_STATS = 6,    /* 16 int32: [0] updated, [1] candidates, [2] compute-list      */
-                             /* count of the last edge into this site; [8..15] four 64-bit  */
+    MDCNN_VIEW_STATS = 6,    /* 18 int32: [0] updated, [1] candidates, [2] compute-list      */
+                             /* count of the last edge into this site; [8..17] five 64-bit  */
                              /* sums since creation: updated, candidates, multiply-         */
-                             /* accumulates issued into this site, compute-list entries     */
+                             /* accumulates of the MFMA kernel into this site, compute-list */
+                             /* entries, multiply-accumulates of the plain kernel           */
     MDCNN_VIEW_OUT = 7       /* H*W*C storage dtype: f(P) over the view (readout)           */
 } mdcnn_view;
 mdcnn_status mdcnn_read_view(const mdcnn_buffer* buf, int what, void* dst_dev, size_t bytes,

@@ -53,11 +53,11 @@ __device__ __forceinline__ unsigned tap_mask(const EdgeDev& e, int cy, int cx) {
 
 // Statistics: add (valid taps of this wave) x Cin x Cout to the destination's
 // multiply-accumulate counter.  Called by whole waves.
-__device__ __forceinline__ void count_macs(const EdgeDev& e, int taps) {
+__device__ __forceinline__ void count_macs(const EdgeDev& e, int taps, int slot) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) taps += __shfl_xor(taps, off);
     if ((threadIdx.x & 63) == 0 && taps)
-        atomicAdd(reinterpret_cast<unsigned long long*>(e.dcounters) + kAccMacs,
+        atomicAdd(reinterpret_cast<unsigned long long*>(e.dcounters) + slot,
                   (unsigned long long)taps * (unsigned long long)(e.Cin * e.Cout));
 }
 
@@ -102,7 +102,7 @@ __global__ __launch_bounds__(256) void k_conv_mfma_f16(EdgeDev e) {
             decode_entry(e, lst[ent], cy, cx, wy, wx);
             vmask = tap_mask(e, cy, cx);
         }
-        if (wn == 0 && blockIdx.y == 0) count_macs(e, kh == 0 ? __popc(vmask) : 0);
+        if (wn == 0 && blockIdx.y == 0) count_macs(e, kh == 0 ? __popc(vmask) : 0, kAccMacs);
         const int y0 = cy * e.stride - e.pad, x0 = cx * e.stride - e.pad;
         f32x16 acc;
 #pragma unroll
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(256) void k_conv_plain(EdgeDev e) {
             decode_entry(e, lst[ent], cy, cx, wy, wx);
             vmask = tap_mask(e, cy, cx);
         }
-        count_macs(e, cl == 0 ? __popc(vmask) : 0);
+        count_macs(e, cl == 0 ? __popc(vmask) : 0, kAccMacsPlain);
         if (!live) continue;
         const int y0 = cy * e.stride - e.pad, x0 = cx * e.stride - e.pad;
         for (int cg = 0; cg < e.Cout; cg += 64) {

@@ -552,7 +552,7 @@ __global__ __launch_bounds__(256) void k_read_ints(SiteDev s, int what, int* __r
     const int step = gridDim.x * 256;
     const int i0 = blockIdx.x * 256 + threadIdx.x;
     if (what == MDCNN_VIEW_STATS) {
-        if (i0 < 16) dst[i0] = s.counters[i0];
+        if (i0 < 18) dst[i0] = s.counters[i0];
         return;
     }
     const bool cl = what == MDCNN_VIEW_CLIST;

@@ -493,7 +493,7 @@ static mdcnn_status view_bytes(const mdcnn_buffer* b, int what, size_t* need) {
             if (!hasP) return fail(MDCNN_ERR_STATE, "INPUT sites hold no compute list");
             *need = ((size_t)b->L.Hp * b->L.Wp + 1) * 4; return MDCNN_OK;
         case MDCNN_VIEW_STATS:
-            *need = 16 * 4; return MDCNN_OK;
+            *need = 18 * 4; return MDCNN_OK;
         default:
             return fail(MDCNN_ERR_SIZE, "unknown view %d", what);
     }

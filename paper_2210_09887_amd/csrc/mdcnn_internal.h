@@ -21,8 +21,9 @@ constexpr int kNumPerFrame = 8;     // slots [0, 8) are per-frame values, zeroed
 // 64-bit accumulators since buffer creation (slot = index into (unsigned long long*)counters)
 constexpr int kAccUpdated = 4;      // sum of update counts
 constexpr int kAccCandidates = 5;   // sum of candidate counts
-constexpr int kAccMacs = 6;         // multiply-accumulates issued into this site (valid taps x Cin x Cout)
+constexpr int kAccMacs = 6;         // multiply-accumulates of the MFMA kernel into this site (valid taps x Cin x Cout)
 constexpr int kAccCompute = 7;      // sum of compute-list lengths of edges into this site
+constexpr int kAccMacsPlain = 8;    // multiply-accumulates of the plain-FMA kernel into this site
 constexpr int kNumCounters = 64;
 
 constexpr int kSegPixels = 1024;   // pixels per compaction segment

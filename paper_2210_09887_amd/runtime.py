@@ -126,12 +126,21 @@ class GpuNet:
         elif what == B.MDCNN_VIEW_CLIST:
             t = torch.empty(Hp * Wp + 1, dtype=torch.int32, device=self.dev)
         else:
-            t = torch.empty(16, dtype=torch.int32, device=self.dev)
+            t = torch.empty(18, dtype=torch.int32, device=self.dev)
         B.mdcnn_read_view(self.bufs[i], what, t.data_ptr(), t.numel() * t.element_size(), self._stream())
         a = t.cpu().numpy()
         if what in (B.MDCNN_VIEW_LIST, B.MDCNN_VIEW_CLIST):
             return a[1:1 + a[0]].copy()
         return a
+
+    def totals(self):
+        """Sums since creation over all sites: dict of updated / candidates / macs_mfma /
+        compute / macs_plain, plus per-site arrays of the same."""
+        keys = ["updated", "candidates", "macs_mfma", "compute", "macs_plain"]
+        per_site = np.stack([self.read(i, B.MDCNN_VIEW_STATS)[8:18].view(np.uint64) for i in range(len(self.bufs))])
+        out = {k: int(per_site[:, j].sum()) for j, k in enumerate(keys)}
+        out["per_site"] = {k: per_site[:, j].astype(np.int64) for j, k in enumerate(keys)}
+        return out
 
     def write(self, i, what, arr: np.ndarray):
         t = torch.from_numpy(np.ascontiguousarray(arr)).to(self.dev)
