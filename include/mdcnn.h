@@ -181,7 +181,7 @@ mdcnn_status mdcnn_write_view(mdcnn_buffer* buf, int what, const void* src_dev, 
 
 /* Library options (process-wide, host-only). */
 typedef enum {
-    MDCNN_OPT_CONV_PATH = 0, /* 0 auto, 1 force the plain-FMA convolution kernel          */
+    MDCNN_OPT_CONV_PATH = 0, /* 0 auto; fallbacks for testing: 1 plain FMA, 2 MFMA w/o LDS  */
     MDCNN_OPT_PROFILE = 1    /* 1: bracket every kernel launch with a pair of HIP events  */
 } mdcnn_option;
 mdcnn_status mdcnn_set_option(int option, int value);

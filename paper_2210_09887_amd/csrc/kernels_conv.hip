@@ -197,6 +197,251 @@ __global__ __launch_bounds__(256) void k_conv_plain(EdgeDev e) {
     }
 }
 
+
+// ---------------------------------------------------------------------------
+// Tiled MFMA gather-GEMM (the fast path for fp16 layers with Cin % 32 == 0).
+// Block tile = BM list entries (pixels) x BN couts, 4 waves arranged WM x WN,
+// each wave owning TM x TN 32x32 accumulators.  K runs over (active tap,
+// KC-channel chunk) steps; per step the weight slab [BN][KC] and the gathered
+// delta slab [BM][KC] (rows of taps that miss the update mask are zero) go
+// global -> registers -> LDS (rows padded by 16 bytes) while the previous step is
+// multiplied out of LDS.  Taps no entry of the tile uses are skipped.  The
+// accumulators are transposed through LDS so that P is updated with 16-byte
+// accesses that are contiguous along the channels.
+// ---------------------------------------------------------------------------
+template <int WM, int WN, int TM, int TN, int KC>
+struct TiledCfg {
+    static constexpr int BM = 32 * WM * TM, BN = 32 * WN * TN;
+    static constexpr int LDK = KC + 8;             // slab row, halves
+    static constexpr int LDC = BN + 4;             // transposed accumulator row, floats
+    static constexpr int CPR = KC / 8;             // 16-byte chunks per slab row
+    static constexpr int SLAB_BYTES = (BM + BN) * LDK * 2;
+    static constexpr int C_BYTES = BM * LDC * 4;
+    static constexpr int SMEM = SLAB_BYTES > C_BYTES ? SLAB_BYTES : C_BYTES;
+};
+
+template <int WM, int WN, int TM, int TN, int KC>
+__global__ __launch_bounds__(256) void k_conv_mfma_tiled(EdgeDev e) {
+    using Cfg = TiledCfg<WM, WN, TM, TN, KC>;
+    constexpr int BM = Cfg::BM, BN = Cfg::BN, LDK = Cfg::LDK, LDC = Cfg::LDC, CPR = Cfg::CPR;
+    constexpr int NB = (BM * CPR + 255) / 256, NA = (BN * CPR + 255) / 256;
+    static_assert(WM * WN == 4 && BM % 64 == 0, "4 waves, whole waves of entries");
+    extern __shared__ __align__(16) unsigned char smem[];
+    f16* sB = reinterpret_cast<f16*>(smem);              // [BM][LDK] gathered deltas
+    f16* sA = sB + BM * LDK;                             // [BN][LDK] weights
+    float* sC = reinterpret_cast<float*>(smem);          // [BM][LDC] after the K loop
+    __shared__ int s_base[BM], s_wy[BM], s_wx[BM];
+    __shared__ unsigned s_vm[BM];
+    __shared__ unsigned s_tilemask;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WM, wn = wave / WM;
+    const int r32 = lane & 31, kh = lane >> 5;
+    const int count = e.up ? e.scounters[kCntUpdated] : e.dcounters[kCntCompute];
+    const int* __restrict__ lst = e.up ? e.slist : e.clist;
+    const int n0 = blockIdx.y * BN;
+    const f16* __restrict__ delta = (const f16*)e.delta;
+    const f16* __restrict__ w = (const f16*)e.w;
+
+    for (int tile = blockIdx.x; tile * BM < count; tile += gridDim.x) {
+        __syncthreads();                                  // previous tile is done with LDS
+        if (tid == 0) s_tilemask = 0;
+        unsigned vmask = 0;
+        if (tid < BM) {
+            const int ent = tile * BM + tid;
+            int cy = 0, cx = 0, wy = 0, wx = 0;
+            if (ent < count) {
+                decode_entry(e, lst[ent], cy, cx, wy, wx);
+                vmask = tap_mask(e, cy, cx);
+                if (blockIdx.y == 0) mark_touched(e, wy, wx);
+            }
+            s_base[tid] = (cy * e.stride - e.pad) * e.sW + (cx * e.stride - e.pad);
+            s_wy[tid] = wy; s_wx[tid] = wx; s_vm[tid] = vmask;
+        }
+        if (tid < BM && blockIdx.y == 0) count_macs(e, __popc(vmask), kAccMacs);   // whole waves: BM % 64 == 0
+        __syncthreads();
+        if (vmask) atomicOr(&s_tilemask, vmask);
+        __syncthreads();
+        unsigned rem = s_tilemask;
+
+        f32x16 acc[TM][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+        f16x8 rb[NB], ra[NA];
+        auto load_slab = [&](int tap, int c0) {
+            const int jy = tap / e.k, jx = tap - jy * e.k;
+            const int toff = jy * e.sW + jx;
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                const int ch = tid + 256 * i;
+                const int row = ch / CPR, cc = ch - row * CPR;
+                f16x8 v;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) v[q] = (f16)0.f;
+                if (ch < BM * CPR && ((s_vm[row] >> tap) & 1u))
+                    v = *reinterpret_cast<const f16x8*>(delta + (size_t)(s_base[row] + toff) * e.Cin + c0 + cc * 8);
+                rb[i] = v;
+            }
+#pragma unroll
+            for (int i = 0; i < NA; ++i) {
+                const int ch = tid + 256 * i;
+                const int row = ch / CPR, cc = ch - row * CPR;
+                if (ch < BN * CPR)
+                    ra[i] = *reinterpret_cast<const f16x8*>(w + ((size_t)(tap * e.Cout + n0 + row)) * e.Cin + c0 + cc * 8);
+            }
+        };
+        auto store_slab = [&]() {
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                const int ch = tid + 256 * i;
+                const int row = ch / CPR, cc = ch - row * CPR;
+                if (ch < BM * CPR) *reinterpret_cast<f16x8*>(sB + row * LDK + cc * 8) = rb[i];
+            }
+#pragma unroll
+            for (int i = 0; i < NA; ++i) {
+                const int ch = tid + 256 * i;
+                const int row = ch / CPR, cc = ch - row * CPR;
+                if (ch < BN * CPR) *reinterpret_cast<f16x8*>(sA + row * LDK + cc * 8) = ra[i];
+            }
+        };
+
+        int tap = rem ? __ffs(rem) - 1 : -1, c0 = 0;
+        if (tap >= 0) { load_slab(tap, c0); store_slab(); }
+        __syncthreads();
+        while (tap >= 0) {
+            int ntap = tap, nc0 = c0 + KC;
+            if (nc0 >= e.Cin) { nc0 = 0; rem &= rem - 1; ntap = rem ? __ffs(rem) - 1 : -1; }
+            if (ntap >= 0) load_slab(ntap, nc0);            // in flight while this step is multiplied
+#pragma unroll
+            for (int kk = 0; kk < KC / 16; ++kk) {
+                f16x8 fb[TM], fa[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    fb[i] = *reinterpret_cast<const f16x8*>(sB + ((wm * TM + i) * 32 + r32) * LDK + kk * 16 + kh * 8);
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    fa[j] = *reinterpret_cast<const f16x8*>(sA + ((wn * TN + j) * 32 + r32) * LDK + kk * 16 + kh * 8);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[j], fb[i], acc[i][j], 0, 0, 0);
+            }
+            __syncthreads();
+            if (ntap >= 0) store_slab();
+            __syncthreads();
+            tap = ntap; c0 = nc0;
+        }
+
+        // accumulators -> LDS as [pixel][cout]
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                float* dst = sC + ((wm * TM + i) * 32 + r32) * LDC + (wn * TN + j) * 32 + 4 * kh;
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    *reinterpret_cast<float4*>(dst + 8 * g) =
+                        make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+            }
+        __syncthreads();
+        constexpr int TPR = BN / 8;                        // threads per pixel row, 8 couts each
+        const int c8 = (tid % TPR) * 8;
+        const int f = 1 << e.up;
+        for (int row = tid / TPR; row < BM; row += 256 / TPR) {
+            if (tile * BM + row >= count) break;
+            const float4 v0 = *reinterpret_cast<const float4*>(sC + row * LDC + c8);
+            const float4 v1 = *reinterpret_cast<const float4*>(sC + row * LDC + c8 + 4);
+            const float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+            for (int ua = 0; ua < f; ++ua)
+                for (int ub = 0; ub < f; ++ub) {
+                    f16* p = (f16*)e.P + pdst_offset(e, s_wy[row] + ua, s_wx[row] + ub) + n0 + c8;
+                    f16x8 o = *reinterpret_cast<f16x8*>(p);
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) o[q] = (f16)((float)o[q] + v[q]);
+                    *reinterpret_cast<f16x8*>(p) = o;
+                }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Plain FMA convolution with the weights of one tap staged in LDS as fp32
+// [cin][cout]; a thread owns one list entry and 8 consecutive couts.  Used for
+// fp32 networks and for layers the MFMA path does not take (e.g. a 3-channel
+// stem).  Needs Cout % 8 == 0, Cout <= 512, Cin * Cout * 4 <= 64 KiB.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void k_conv_ldsw(EdgeDev e, int groups, int ppb) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* sW = reinterpret_cast<float*>(smem);             // [Cin][Cout]
+    __shared__ unsigned s_tilemask;
+    const int tid = threadIdx.x;
+    const int cg = tid % groups, pl = tid / groups;         // cout group, local pixel
+    const bool worker = pl < ppb;
+    const int count = e.up ? e.scounters[kCntUpdated] : e.dcounters[kCntCompute];
+    const int* __restrict__ lst = e.up ? e.slist : e.clist;
+    const T* __restrict__ delta = (const T*)e.delta;
+    const T* __restrict__ w = (const T*)e.w;
+    const int taps = e.k * e.k;
+    for (int tile = blockIdx.x; tile * ppb < count; tile += gridDim.x) {
+        __syncthreads();
+        if (tid == 0) s_tilemask = 0;
+        const int ent = tile * ppb + pl;
+        const bool live = worker && ent < count;
+        int cy = 0, cx = 0, wy = 0, wx = 0;
+        unsigned vmask = 0;
+        if (live) {
+            decode_entry(e, lst[ent], cy, cx, wy, wx);
+            vmask = tap_mask(e, cy, cx);
+            if (cg == 0) mark_touched(e, wy, wx);
+        }
+        count_macs(e, cg == 0 ? __popc(vmask) : 0, kAccMacsPlain);
+        __syncthreads();
+        if (vmask && cg == 0) atomicOr(&s_tilemask, vmask);
+        __syncthreads();
+        const unsigned tilemask = s_tilemask;
+        const int base = (cy * e.stride - e.pad) * e.sW + (cx * e.stride - e.pad);
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int tap = 0; tap < taps; ++tap) {
+            if (!((tilemask >> tap) & 1u)) continue;         // block-uniform
+            __syncthreads();                                 // previous tap's weights no longer read
+            for (int i = tid; i < e.Cin * e.Cout; i += 256) {
+                const int co = i / e.Cin, ci = i - co * e.Cin;
+                sW[ci * e.Cout + co] = (float)w[(size_t)(tap * e.Cout) * e.Cin + i];
+            }
+            __syncthreads();
+            if ((vmask >> tap) & 1u) {
+                const int jy = tap / e.k, jx = tap - jy * e.k;
+                const T* drow = delta + (size_t)(base + jy * e.sW + jx) * e.Cin;
+                for (int ci = 0; ci < e.Cin; ++ci) {
+                    const float a = (float)drow[ci];
+                    const float4 w0 = *reinterpret_cast<const float4*>(sW + ci * e.Cout + cg * 8);
+                    const float4 w1 = *reinterpret_cast<const float4*>(sW + ci * e.Cout + cg * 8 + 4);
+                    acc[0] = fmaf(a, w0.x, acc[0]); acc[1] = fmaf(a, w0.y, acc[1]);
+                    acc[2] = fmaf(a, w0.z, acc[2]); acc[3] = fmaf(a, w0.w, acc[3]);
+                    acc[4] = fmaf(a, w1.x, acc[4]); acc[5] = fmaf(a, w1.y, acc[5]);
+                    acc[6] = fmaf(a, w1.z, acc[6]); acc[7] = fmaf(a, w1.w, acc[7]);
+                }
+            }
+        }
+        if (live) {
+            const int f = 1 << e.up;
+            for (int ua = 0; ua < f; ++ua)
+                for (int ub = 0; ub < f; ++ub) {
+                    T* pp = (T*)e.P + pdst_offset(e, wy + ua, wx + ub) + cg * 8;
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) pp[q] = (T)((float)pp[q] + acc[q]);
+                }
+        }
+    }
+}
+
 // Residual skip: P_dst[q] += delta[q] on the compute list (= updated pixels).
 template <typename T>
 __global__ __launch_bounds__(256) void k_identity(EdgeDev e) {
@@ -222,6 +467,38 @@ static unsigned cap_blocks(long long b, long long cap) {
     return (unsigned)b;
 }
 
+template <int WM, int WN, int TM, int TN, int KC>
+static hipError_t launch_tiled(const EdgeDev& e, long long max_entries, hipStream_t st) {
+    using Cfg = TiledCfg<WM, WN, TM, TN, KC>;
+    static bool attr_set = false;
+    auto kern = k_conv_mfma_tiled<WM, WN, TM, TN, KC>;
+    if (!attr_set) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::SMEM);
+        if (err != hipSuccess) return err;
+        attr_set = true;
+    }
+    unsigned g = cap_blocks((max_entries + Cfg::BM - 1) / Cfg::BM, 2048);
+    kern<<<dim3(g, e.Cout / Cfg::BN), dim3(256), Cfg::SMEM, st>>>(e);
+    return hipGetLastError();
+}
+
+template <int KC>
+static hipError_t launch_tiled_kc(const EdgeDev& e, long long max_entries, hipStream_t st) {
+    // the largest tile that still yields about one block per compute unit
+    auto blocks = [&](int bm, int bn) { return ((max_entries + bm - 1) / bm) * (e.Cout / bn); };
+    const long long want = 224;
+    if (e.Cout % 128 == 0) {
+        if (blocks(128, 128) >= want) return launch_tiled<2, 2, 2, 2, KC>(e, max_entries, st);
+        if (blocks(64, 128) >= want) return launch_tiled<2, 2, 1, 2, KC>(e, max_entries, st);
+    }
+    if (e.Cout % 64 == 0) {
+        if (blocks(256, 64) >= want) return launch_tiled<4, 1, 2, 2, KC>(e, max_entries, st);
+        if (blocks(128, 64) >= want) return launch_tiled<2, 2, 2, 1, KC>(e, max_entries, st);
+        return launch_tiled<2, 2, 1, 1, KC>(e, max_entries, st);
+    }
+    return launch_tiled<4, 1, 1, 1, KC>(e, max_entries, st);        // Cout % 32 == 0
+}
+
 hipError_t launch_conv(const EdgeDev& e, int dtype, int conv_path, hipStream_t st, int* cls) {
     const long long max_entries = e.up ? (long long)e.sH * e.sW : (long long)e.Hp * e.Wp;
     if (e.k == 0) {
@@ -231,7 +508,12 @@ hipError_t launch_conv(const EdgeDev& e, int dtype, int conv_path, hipStream_t s
         else k_identity<float><<<dim3(g), dim3(256), 0, st>>>(e);
         return hipGetLastError();
     }
+    // conv_path: 0 auto, 1 plain FMA (per-thread weights), 2 MFMA without LDS tiling
     const bool mfma_ok = dtype == MDCNN_F16 && conv_path != 1 && e.Cin % 16 == 0 && e.Cout % 32 == 0;
+    if (mfma_ok && conv_path == 0 && e.Cin % 32 == 0) {
+        *cls = kClsConvMfma;
+        return e.Cin % 64 == 0 ? launch_tiled_kc<64>(e, max_entries, st) : launch_tiled_kc<32>(e, max_entries, st);
+    }
     if (mfma_ok) {
         *cls = kClsConvMfma;
         if (e.Cout % 64 == 0) {
@@ -244,6 +526,15 @@ hipError_t launch_conv(const EdgeDev& e, int dtype, int conv_path, hipStream_t s
         return hipGetLastError();
     }
     *cls = kClsConvPlain;
+    const int groups = e.Cout / 8;
+    if (conv_path == 0 && e.Cout % 8 == 0 && groups <= 64 && (size_t)e.Cin * e.Cout * 4 <= 65536) {
+        const int ppb = 256 / groups;
+        const size_t smem = (size_t)e.Cin * e.Cout * 4;
+        unsigned g = cap_blocks((max_entries + ppb - 1) / ppb, 8192);
+        if (dtype == MDCNN_F16) k_conv_ldsw<f16><<<dim3(g), dim3(256), smem, st>>>(e, groups, ppb);
+        else k_conv_ldsw<float><<<dim3(g), dim3(256), smem, st>>>(e, groups, ppb);
+        return hipGetLastError();
+    }
     unsigned g = cap_blocks((max_entries + 15) / 16, 8192);
     if (dtype == MDCNN_F16) k_conv_plain<f16><<<dim3(g), dim3(256), 0, st>>>(e);
     else k_conv_plain<float><<<dim3(g), dim3(256), 0, st>>>(e);

@@ -253,7 +253,7 @@ const char* mdcnn_last_error(void) { return g_err; }
 const char* mdcnn_version(void) { return "mdcnn 0.1 (gfx950)"; }
 
 mdcnn_status mdcnn_set_option(int option, int value) {
-    if (option == MDCNN_OPT_CONV_PATH && (value == 0 || value == 1)) { g_conv_path = value; return MDCNN_OK; }
+    if (option == MDCNN_OPT_CONV_PATH && value >= 0 && value <= 2) { g_conv_path = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_PROFILE && (value == 0 || value == 1)) { g_profile = value; return MDCNN_OK; }
     return fail(MDCNN_ERR_SIZE, "unknown option %d / value %d", option, value);
 }

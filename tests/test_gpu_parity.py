@@ -116,12 +116,13 @@ def test_origin_rotation_is_invisible(name):
             assert np.array_equal(x, y)
 
 
-def test_plain_conv_path_on_f16():
-    """The plain-FMA kernel and the MFMA kernel agree with the oracle on the same net."""
+@pytest.mark.parametrize("path", [1, 2])
+def test_fallback_conv_paths_on_f16(path):
+    """The fallback kernels (plain FMA; MFMA without LDS tiling) agree with the oracle too."""
     import gpu_harness as H
     from paper_2210_09887_amd import binding as B
     net, seq = load_case("c3_resnet_96")
-    B.mdcnn_set_option(B.MDCNN_OPT_CONV_PATH, 1)
+    B.mdcnn_set_option(B.MDCNN_OPT_CONV_PATH, path)
     try:
         H.teacher_forced(net, seq.frames[:3], seq.shifts[:3], log=log)
     finally:
@@ -160,3 +161,32 @@ def test_degenerate_frames():
         torch.cuda.synchronize()
     finally:
         g.close()
+
+
+@pytest.mark.parametrize("cin,cout,H,W,k,stride", [
+    (64, 256, 128, 128, 3, 1),     # 128 x 128 tile
+    (64, 128, 160, 160, 3, 1),     # 64 x 128 tile
+    (64, 64, 240, 240, 3, 1),      # 256 x 64 tile
+    (128, 64, 184, 176, 3, 1),     # 128 x 64 tile
+    (32, 64, 96, 80, 3, 2),        # 64 x 64 tile, 32-channel K step, stride 2
+    (96, 32, 72, 72, 1, 1),        # 128 x 32 tile, 1x1
+    (16, 32, 40, 40, 3, 1),        # MFMA without LDS tiling (Cin % 32 != 0)
+    (3, 64, 64, 64, 3, 2),         # plain kernel with LDS weights (3-channel stem)
+])
+def test_conv_kernel_shapes(cin, cout, H, W, k, stride):
+    """Every convolution kernel variant / tile shape against the oracle: a dense
+    frame, a sparse frame and a frame after a camera shift."""
+    import gpu_harness as H_
+    from inputs.nets import tiny_net
+    net = tiny_net("f16", H, W, (cin, cout), k=k, stride=stride, theta=0.05, seed=cin + cout, total_stride=8)
+    rng = np.random.default_rng(cin * 1000 + cout)
+    x = rng.normal(0, 1, (H, W, cin)).astype(np.float32)
+    frames = [x.astype(np.float16)]
+    for _ in range(2):
+        x = x.copy()
+        y0, x0 = int(rng.integers(0, H - 24)), int(rng.integers(0, W - 24))
+        x[y0:y0 + 24, x0:x0 + 17] += rng.normal(0, 1, (24, 17, cin)).astype(np.float32)
+        x[rng.random((H, W)) < 0.02] += 0.5
+        frames.append(x.astype(np.float16))
+    worst = H_.teacher_forced(net, frames, [(0, 0), (0, 0), (1, -1)], log=log)
+    log(f"[conv shapes] {cin}->{cout} {H}x{W} k{k} s{stride}: worst {worst:.3e}")
