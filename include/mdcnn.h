@@ -162,7 +162,8 @@ typedef enum {
     MDCNN_VIEW_A = 0,        /* H*W*C storage dtype: accumulated values                     */
     MDCNN_VIEW_P = 1,        /* Hp*Wp*C storage dtype: pending values over the padded window */
     MDCNN_VIEW_DELTA = 2,    /* H*W*C storage dtype: delta map of the last forward (0 where not updated) */
-    MDCNN_VIEW_FLAGS = 3,    /* H*W bytes: bit0 newly unveiled, bit1 touched, bit2 updated  */
+    MDCNN_VIEW_FLAGS = 3,    /* H*W bytes: bit0 newly unveiled, bit1 touched, bit2 updated, */
+                             /* bit3 visited by the last forward                            */
     MDCNN_VIEW_LIST = 4,     /* 1 + H*W int32: count, then the ascending list L             */
     MDCNN_VIEW_CLIST = 5,    /* 1 + Hp*Wp int32: count, then the compute list of the last   */
                              /* non-upsampling edge that produced into this site            */

@@ -48,84 +48,89 @@ __device__ __forceinline__ size_t p_offset(const SiteDev& s, int wy, int wx) {
 }
 
 // ---------------------------------------------------------------------------
-// Dynamic initialisation.  Pixels of the new padded window outside the kept
-// rectangle get P = bias (the bias is added by the activation later on);
-// pixels of the new view outside the kept rectangle get A = 0 and flag N.
+// Dynamic initialisation, all sites of a network in one launch.  Pixels of the
+// new padded window outside the kept rectangle get P = bias (the activation
+// adds it later on); pixels of the new view outside the kept rectangle get
+// A = 0 and flag N.  Per-frame counters are cleared here.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void decode_new(const KeepRect& r, int idx, int& y, int& x) {
-    int top = r.y0 * r.Wn;
-    int bot = (r.Hn - r.y1) * r.Wn;
+__device__ __forceinline__ void decode_new(int Wn, int Hn, int y0, int y1, int x0, int x1, int idx, int& y, int& x) {
+    const int top = y0 * Wn;
+    const int bot = (Hn - y1) * Wn;
     if (idx < top) {
-        y = idx / r.Wn; x = idx - y * r.Wn;
+        y = idx / Wn; x = idx - y * Wn;
     } else if (idx < top + bot) {
-        int j = idx - top;
-        int q = j / r.Wn;
-        y = r.y1 + q; x = j - q * r.Wn;
+        const int j = idx - top;
+        const int q = j / Wn;
+        y = y1 + q; x = j - q * Wn;
     } else {
-        int j = idx - top - bot;
-        int mw = r.x0 + (r.Wn - r.x1);
-        int q = j / mw;
-        int c = j - q * mw;
-        y = r.y0 + q;
-        x = c < r.x0 ? c : r.x1 + (c - r.x0);
+        const int j = idx - top - bot;
+        const int mw = x0 + (Wn - x1);
+        const int q = j / mw;
+        const int c = j - q * mw;
+        y = y0 + q;
+        x = c < x0 ? c : x1 + (c - x0);
     }
 }
 
 template <typename T, int VEC>
-__global__ __launch_bounds__(256) void k_shift_fill(SiteDev s, KeepRect pr, KeepRect ar, int nP, int nA,
-                                                    int reset_counters) {
-    const int chunks = s.C / VEC;
-    const long long total = (long long)(nP + nA) * chunks;
-    long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-    // per-frame slots on every full reset, the accumulators only on the first one
-    if (reset_counters && idx < (reset_counters == 2 ? kNumCounters : kNumPerFrame)) s.counters[idx] = 0;
-    const long long step = (long long)gridDim.x * 256;
-    for (; idx < total; idx += step) {
-        int pix = (int)(idx / chunks);
-        int c0 = (int)(idx - (long long)pix * chunks) * VEC;
-        if (pix < nP) {
+__device__ __forceinline__ void fill_items(const FillJob& j, unsigned lb) {
+    const int chunks = j.C / VEC;
+    const long long total = (long long)(j.nP + j.nA) * chunks;
+    const long long begin = (long long)lb * kFillItemsPerBlock;
+    long long end = begin + kFillItemsPerBlock;
+    if (end > total) end = total;
+    for (long long idx = begin + threadIdx.x; idx < end; idx += 256) {
+        const int pix = (int)(idx / chunks);
+        const int c0 = (int)(idx - (long long)pix * chunks) * VEC;
+        if (pix < j.nP) {
             int wy, wx;
-            decode_new(pr, pix, wy, wx);
-            T* p = (T*)s.P + p_offset(s, wy, wx) + c0;
+            decode_new(j.Wp, j.Hp, j.py0, j.py1, j.px0, j.px1, pix, wy, wx);
+            const int py = wrap(j.p_oy + wy, j.Hp), px = wrap(j.p_ox + wx, j.Wp);
+            T* p = (T*)j.P + ((size_t)py * j.Wp + px) * j.C + c0;
+            if constexpr (VEC > 1) {
+                float v[VEC];
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) p[i] = (T)(s.bias ? s.bias[c0 + i] : 0.f);
+                for (int i = 0; i < VEC; ++i) v[i] = j.bias ? j.bias[c0 + i] : 0.f;
+                V16<T>::store(p, v);
+            } else {
+                p[0] = (T)(j.bias ? j.bias[c0] : 0.f);
+            }
         } else {
             int vy, vx;
-            decode_new(ar, pix - nP, vy, vx);
-            T* p = (T*)s.A + a_offset(s, vy, vx) + c0;
+            decode_new(j.W, j.H, j.ay0, j.ay1, j.ax0, j.ax1, pix - j.nP, vy, vx);
+            const int ay = wrap(j.a_oy + vy, j.H), ax = wrap(j.a_ox + vx, j.W);
+            T* p = (T*)j.A + ((size_t)ay * j.W + ax) * j.C + c0;
+            if constexpr (VEC > 1) {
+                float v[VEC];
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) p[i] = (T)0.f;
-            if (c0 == 0) s.flags[vy * s.W + vx] = (uint8_t)kFlagN;
+                for (int i = 0; i < VEC; ++i) v[i] = 0.f;
+                V16<T>::store(p, v);
+            } else {
+                p[0] = (T)0.f;
+            }
+            if (c0 == 0) j.flags[vy * j.W + vx] = (uint8_t)kFlagN;
         }
     }
 }
 
-// OUTPUT sites have no A ring; they still need nothing per view pixel.  INPUT
-// sites have no P ring.  The host passes nP / nA = 0 accordingly.
-
-template <typename T>
-static hipError_t shift_fill_t(const SiteDev& s, const KeepRect& pr, const KeepRect& ar, int reset_counters,
-                               hipStream_t st) {
-    int nP = s.P ? keep_count(pr) : 0;
-    int nA = s.A ? keep_count(ar) : 0;
-    if (nP + nA == 0 && !reset_counters) return hipSuccess;
-    constexpr int V = 16 / sizeof(T);
-    bool vec = (s.C % V) == 0;
-    long long total = (long long)(nP + nA) * (vec ? s.C / V : s.C);
-    long long blocks = (total + 255) / 256;
-    if (blocks < 1) blocks = 1;
-    if (blocks > 65536) blocks = 65536;
-    if (vec)
-        k_shift_fill<T, V><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(s, pr, ar, nP, nA, reset_counters);
-    else
-        k_shift_fill<T, 1><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(s, pr, ar, nP, nA, reset_counters);
-    return hipGetLastError();
+__global__ __launch_bounds__(256) void k_shift_fill(FillBatch fb) {
+    int ji = 0;
+    while (ji + 1 < fb.n && blockIdx.x >= fb.j[ji + 1].block_begin) ++ji;
+    const FillJob& j = fb.j[ji];
+    const unsigned lb = blockIdx.x - j.block_begin;
+    if (lb == 0 && j.reset_counters && (int)threadIdx.x < (j.reset_counters == 2 ? kNumCounters : kNumPerFrame))
+        j.counters[threadIdx.x] = 0;
+    if (j.dtype == MDCNN_F16) {
+        if (j.C % 8 == 0) fill_items<f16, 8>(j, lb); else fill_items<f16, 1>(j, lb);
+    } else {
+        if (j.C % 4 == 0) fill_items<float, 4>(j, lb); else fill_items<float, 1>(j, lb);
+    }
 }
 
-hipError_t launch_shift_fill(const SiteDev& s, const KeepRect& pr, const KeepRect& ar, int reset_counters,
-                             hipStream_t st) {
-    return s.dtype == MDCNN_F16 ? shift_fill_t<f16>(s, pr, ar, reset_counters, st)
-                                : shift_fill_t<float>(s, pr, ar, reset_counters, st);
+hipError_t launch_shift_fill(const FillBatch& fb, hipStream_t st) {
+    if (fb.n == 0 || fb.total_blocks == 0) return hipSuccess;
+    k_shift_fill<<<dim3(fb.total_blocks), dim3(256), 0, st>>>(fb);
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
@@ -197,16 +202,7 @@ __global__ __launch_bounds__(256) void k_step1(SiteDev s, const T* __restrict__ 
                 }
             }
         }
-        if (lp == 0) s.flags[pix] = (uint8_t)(m ? kFlagM : 0);
-    }
-    const unsigned long long bm = __ballot(m && lp == 0);
-    const unsigned long long bc = __ballot(cand && lp == 0);
-    __shared__ int sm[4], sc[4];
-    if ((tid & 63) == 0) { sm[tid >> 6] = __popcll(bm); sc[tid >> 6] = __popcll(bc); }
-    __syncthreads();
-    if (tid == 0) {
-        s.partials[blockIdx.x] = sm[0] + sm[1] + sm[2] + sm[3];
-        s.partials[gridDim.x + blockIdx.x] = sc[0] + sc[1] + sc[2] + sc[3];
+        if (lp == 0) s.flags[pix] = (uint8_t)((m ? kFlagM : 0) | (cand ? kFlagC : 0));
     }
 }
 
@@ -257,16 +253,7 @@ __global__ __launch_bounds__(256) void k_step1_scalar(SiteDev s, const T* __rest
                 }
             }
         }
-        s.flags[pix] = (uint8_t)(m ? kFlagM : 0);
-    }
-    const unsigned long long bm = __ballot(m);
-    const unsigned long long bc = __ballot(cand);
-    __shared__ int sm[4], sc[4];
-    if ((tid & 63) == 0) { sm[tid >> 6] = __popcll(bm); sc[tid >> 6] = __popcll(bc); }
-    __syncthreads();
-    if (tid == 0) {
-        s.partials[blockIdx.x] = sm[0] + sm[1] + sm[2] + sm[3];
-        s.partials[gridDim.x + blockIdx.x] = sc[0] + sc[1] + sc[2] + sc[3];
+        s.flags[pix] = (uint8_t)((m ? kFlagM : 0) | (cand ? kFlagC : 0));
     }
 }
 
@@ -281,13 +268,6 @@ static bool step1_shape(int C, int vec, int& G, int& CH) {
         if (g <= 64 && (g & (g - 1)) == 0) { G = g; CH = ch; return true; }
     }
     return false;
-}
-
-int step1_pixels_per_block(const SiteDev& s) {
-    int G, CH;
-    int vec = s.dtype == MDCNN_F16 ? 8 : 4;
-    if (!step1_shape(s.C, vec, G, CH)) return 256;
-    return 256 / G;
 }
 
 template <typename T, int G>
@@ -329,20 +309,12 @@ hipError_t launch_step1(const SiteDev& s, const void* frame, const uint8_t* forc
 
 // ---------------------------------------------------------------------------
 // Compaction.  A segment is kSegPixels consecutive linear indices handled by one
-// 256-thread block (4 per thread, ascending), so list order = index order.
-// Segment bases come from per-block counts written by an earlier kernel: no
-// waiting between blocks, no host round trip.
+// 256-thread block (4 per thread, ascending), compacted into the front of the
+// segment's slice of the list; the per-segment count goes to cnt[segment].  The
+// concatenation of the segments is the ascending list.  Blocks are independent:
+// no scan across blocks, no waiting, no host round trip; consumers walk
+// (segment, offset) pairs.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ int block_sum(int v, int* sh) {
-    const int tid = threadIdx.x;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-    __syncthreads();
-    if ((tid & 63) == 0) sh[tid >> 6] = v;
-    __syncthreads();
-    return sh[0] + sh[1] + sh[2] + sh[3];
-}
-
 // exclusive prefix of v over the 256 threads of the block; total in *tot
 __device__ __forceinline__ int block_excl_scan(int v, int* sh, int* tot) {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -352,7 +324,6 @@ __device__ __forceinline__ int block_excl_scan(int v, int* sh, int* tot) {
         int t = __shfl_up(inc, off);
         if (lane >= off) inc += t;
     }
-    __syncthreads();
     if (lane == 63) sh[w] = inc;
     __syncthreads();
     int base = 0;
@@ -361,6 +332,7 @@ __device__ __forceinline__ int block_excl_scan(int v, int* sh, int* tot) {
     return base + inc - v;
 }
 
+// does the footprint of window pixel widx of the destination hold an updated source pixel?
 __device__ __forceinline__ bool covered(const EdgeDev& e, int widx) {
     const int wy = widx / e.Wp, wx = widx - wy * e.Wp;
     const int oy = wy - e.by0, ox = wx - e.bx0;
@@ -369,125 +341,95 @@ __device__ __forceinline__ bool covered(const EdgeDev& e, int widx) {
         return e.sflags[oy * e.sW + ox] & kFlagM;
     }
     const int y0 = oy * e.stride - e.pad, x0 = ox * e.stride - e.pad;
+    int any = 0;
     for (int jy = 0; jy < e.k; ++jy) {
         const int iy = y0 + jy;
-        if (iy < 0 || iy >= e.sH) continue;
+        const bool yok = iy >= 0 && iy < e.sH;
         for (int jx = 0; jx < e.k; ++jx) {
             const int ix = x0 + jx;
-            if (ix < 0 || ix >= e.sW) continue;
-            if (e.sflags[iy * e.sW + ix] & kFlagM) return true;
+            const bool ok = yok && ix >= 0 && ix < e.sW;
+            any |= ok ? e.sflags[iy * e.sW + ix] : 0;      // independent loads, no early exit
         }
     }
-    return false;
+    return any & kFlagM;
 }
 
-// blockIdx.y == 0: compact the update mask of site s into its list L.
-// blockIdx.y >= 1: count, per segment, the compute-list entries of edge y-1.
-__global__ __launch_bounds__(256) void k_lists_a(SiteDev s, int ppb, int nblk1, EdgeBatch eb, int do_compact) {
+// blockIdx.y == 0: compact the update mask of site s into L.
+// blockIdx.y >= 1: compute list of edge y-1 (destination padded-window indices).
+__global__ __launch_bounds__(256) void k_lists(SiteDev s, EdgeBatch eb, int do_compact) {
     __shared__ int sh[4];
     const int tid = threadIdx.x;
     const int seg = blockIdx.x;
+    const int p0 = seg * kSegPixels + tid * 4;
     if (blockIdx.y == 0) {
-        if (!do_compact) return;
         const int HW = s.H * s.W;
-        const int nseg = (HW + kSegPixels - 1) / kSegPixels;
-        if (seg >= nseg) return;
-        const int nprev = seg * (kSegPixels / ppb);
-        int v = 0;
-        for (int i = tid; i < nprev; i += 256) v += s.partials[i];
-        const int base = block_sum(v, sh);
-        const int p0 = seg * kSegPixels + tid * 4;
-        int bits = 0;
+        if (!do_compact || seg * kSegPixels >= HW) return;
+        int bits = 0, ncand = 0;
+        if (p0 + 3 < HW) {
+            const unsigned f4 = *reinterpret_cast<const unsigned*>(s.flags + p0);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (p0 + j < HW && (s.flags[p0 + j] & kFlagM)) bits |= 1 << j;
+            for (int j = 0; j < 4; ++j) bits |= ((f4 >> (8 * j + 2)) & 1u) << j;      // kFlagM == 4
+            ncand = __popc(f4 & 0x08080808u);                                          // kFlagC == 8
+        } else {
+            for (int j = 0; j < 4; ++j)
+                if (p0 + j < HW) {
+                    const int f = s.flags[p0 + j];
+                    if (f & kFlagM) bits |= 1 << j;
+                    ncand += (f >> 3) & 1;
+                }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) ncand += __shfl_xor(ncand, o);
+        __shared__ int scand[4];
+        if ((tid & 63) == 0) scand[tid >> 6] = ncand;
         int tot;
-        int off = base + block_excl_scan(__popc(bits), sh, &tot);
+        int off = seg * kSegPixels + block_excl_scan(__popc(bits), sh, &tot);
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             if (bits & (1 << j)) s.list[off++] = p0 + j;
-        if (seg == nseg - 1) {
-            int c = 0;
-            for (int i = tid; i < nblk1; i += 256) c += s.partials[nblk1 + i];
-            c = block_sum(c, sh);
-            if (tid == 0) {
-                s.counters[kCntUpdated] = base + tot;
-                s.counters[kCntCandidates] = c;
-                unsigned long long* acc = reinterpret_cast<unsigned long long*>(s.counters);
-                acc[kAccUpdated] += (unsigned long long)(base + tot);
-                acc[kAccCandidates] += (unsigned long long)c;
-            }
+        if (tid == 0) {                                  // scand is complete: the scan has a barrier
+            s.lcnt[seg] = tot;
+            const int c = scand[0] + scand[1] + scand[2] + scand[3];
+            unsigned long long* acc = reinterpret_cast<unsigned long long*>(s.counters);
+            if (tot) { atomicAdd(&s.counters[kCntUpdated], tot); atomicAdd(acc + kAccUpdated, (unsigned long long)tot); }
+            if (c) { atomicAdd(&s.counters[kCntCandidates], c); atomicAdd(acc + kAccCandidates, (unsigned long long)c); }
         }
     } else {
         const int ei = blockIdx.y - 1;
         if (ei >= eb.n) return;
         const EdgeDev& e = eb.e[ei];
-        if (e.up) return;
         const int NW = e.Hp * e.Wp;
-        if (seg * kSegPixels >= NW) return;
-        const int p0 = seg * kSegPixels + tid * 4;
-        int c = 0;
+        if (e.up || seg * kSegPixels >= NW) return;
+        int bits = 0;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            if (p0 + j < NW && covered(e, p0 + j)) ++c;
-        c = block_sum(c, sh);
-        if (tid == 0) e.cpartials[seg] = c;
-    }
-}
-
-// blockIdx.y = edge: write the compute list (ascending padded-window index).
-__global__ __launch_bounds__(256) void k_lists_b(EdgeBatch eb) {
-    __shared__ int sh[4];
-    const int tid = threadIdx.x;
-    const int seg = blockIdx.x;
-    const EdgeDev& e = eb.e[blockIdx.y];
-    if (e.up) return;
-    const int NW = e.Hp * e.Wp;
-    const int nseg = (NW + kSegPixels - 1) / kSegPixels;
-    if (seg >= nseg) return;
-    int v = 0;
-    for (int i = tid; i < seg; i += 256) v += e.cpartials[i];
-    const int base = block_sum(v, sh);
-    const int p0 = seg * kSegPixels + tid * 4;
-    int bits = 0;
+            if (p0 + j < NW && covered(e, p0 + j)) bits |= 1 << j;
+        int tot;
+        int off = seg * kSegPixels + block_excl_scan(__popc(bits), sh, &tot);
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-        if (p0 + j < NW && covered(e, p0 + j)) bits |= 1 << j;
-    int tot;
-    int off = base + block_excl_scan(__popc(bits), sh, &tot);
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-        if (bits & (1 << j)) e.clist[off++] = p0 + j;
-    if (seg == nseg - 1 && tid == 0) {
-        e.dcounters[kCntCompute] = base + tot;
-        reinterpret_cast<unsigned long long*>(e.dcounters)[kAccCompute] += (unsigned long long)(base + tot);
+        for (int j = 0; j < 4; ++j)
+            if (bits & (1 << j)) e.clist[off++] = p0 + j;
+        if (tid == 0) {
+            e.ccnt[seg] = tot;
+            if (tot) atomicAdd(reinterpret_cast<unsigned long long*>(e.dcounters) + kAccCompute, (unsigned long long)tot);
+        }
     }
 }
 
 // One batch of edges of site s; the first batch of a site also compacts L.
 hipError_t launch_lists(const SiteDev& s, const EdgeBatch& eb, bool do_compact, hipStream_t st) {
     const int HW = s.H * s.W;
-    int nseg = do_compact ? (HW + kSegPixels - 1) / kSegPixels : 0;
-    int nseg_e = 0;
-    bool any = false;
+    int gx = do_compact ? (HW + kSegPixels - 1) / kSegPixels : 0;
+    int ny = 1;
     for (int i = 0; i < eb.n; ++i) {
         if (eb.e[i].up) continue;
-        any = true;
-        int n = (eb.e[i].Hp * eb.e[i].Wp + kSegPixels - 1) / kSegPixels;
-        if (n > nseg_e) nseg_e = n;
+        ny = 2 + i;
+        const int n = (eb.e[i].Hp * eb.e[i].Wp + kSegPixels - 1) / kSegPixels;
+        if (n > gx) gx = n;
     }
-    int gx = nseg > nseg_e ? nseg : nseg_e;
     if (gx == 0) return hipSuccess;
-    const int ppb = step1_pixels_per_block(s);
-    const int nblk1 = (HW + ppb - 1) / ppb;
-    k_lists_a<<<dim3(gx, 1 + (any ? eb.n : 0)), dim3(256), 0, st>>>(s, ppb, nblk1, eb, do_compact ? 1 : 0);
-    hipError_t err = hipGetLastError();
-    if (err != hipSuccess) return err;
-    if (any) {
-        k_lists_b<<<dim3(nseg_e, eb.n), dim3(256), 0, st>>>(eb);
-        err = hipGetLastError();
-    }
-    return err;
+    k_lists<<<dim3(gx, ny), dim3(256), 0, st>>>(s, eb, do_compact ? 1 : 0);
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
@@ -548,18 +490,31 @@ __global__ __launch_bounds__(256) void k_write_tensor(SiteDev s, int what, const
     }
 }
 
-__global__ __launch_bounds__(256) void k_read_ints(SiteDev s, int what, int* __restrict__ dst) {
-    const int step = gridDim.x * 256;
-    const int i0 = blockIdx.x * 256 + threadIdx.x;
-    if (what == MDCNN_VIEW_STATS) {
-        if (i0 < 18) dst[i0] = s.counters[i0];
-        return;
+// Single block: concatenates the segments of a list (ascending order), prefixed by its length.
+__global__ __launch_bounds__(256) void k_read_list(const int* __restrict__ list, const int* __restrict__ cnt, int n,
+                                                   int* __restrict__ dst) {
+    const int nseg = (n + kSegPixels - 1) / kSegPixels;
+    int running = 0;
+    for (int g = 0; g < nseg; ++g) {
+        const int c = cnt[g];
+        for (int i = threadIdx.x; i < c; i += 256) dst[1 + running + i] = list[g * kSegPixels + i];
+        running += c;
     }
-    const bool cl = what == MDCNN_VIEW_CLIST;
-    const int n = cl ? s.Hp * s.Wp : s.H * s.W;
-    const int cnt = s.counters[cl ? kCntCompute : kCntUpdated];
-    const int* src = cl ? s.clist : s.list;
-    for (int i = i0; i < n + 1; i += step) dst[i] = i == 0 ? cnt : (i - 1 < cnt ? src[i - 1] : -1);
+    for (int i = running + threadIdx.x; i < n; i += 256) dst[1 + i] = -1;
+    if (threadIdx.x == 0) dst[0] = running;
+}
+
+__global__ __launch_bounds__(256) void k_read_stats(SiteDev s, int* __restrict__ dst) {
+    const int i = threadIdx.x;
+    if (i < 18) dst[i] = s.counters[i];
+    if (i == 2) {
+        int c = 0;
+        if (s.ccnt) {
+            const int nseg = (s.Hp * s.Wp + kSegPixels - 1) / kSegPixels;
+            for (int g = 0; g < nseg; ++g) c += s.ccnt[g];
+        }
+        dst[2] = c;
+    }
 }
 
 __global__ __launch_bounds__(256) void k_copy_bytes(const uint8_t* __restrict__ src, uint8_t* __restrict__ dst, int n) {
@@ -594,13 +549,13 @@ hipError_t launch_read_view(const SiteDev& s, int what, void* dst, hipStream_t s
             k_copy_bytes<<<dim3(grid_for(s.H * s.W)), dim3(256), 0, st>>>(s.flags, (uint8_t*)dst, s.H * s.W);
             return hipGetLastError();
         case MDCNN_VIEW_LIST:
-            k_read_ints<<<dim3(grid_for(s.H * s.W + 1)), dim3(256), 0, st>>>(s, what, (int*)dst);
+            k_read_list<<<dim3(1), dim3(256), 0, st>>>(s.list, s.lcnt, s.H * s.W, (int*)dst);
             return hipGetLastError();
         case MDCNN_VIEW_CLIST:
-            k_read_ints<<<dim3(grid_for(s.Hp * s.Wp + 1)), dim3(256), 0, st>>>(s, what, (int*)dst);
+            k_read_list<<<dim3(1), dim3(256), 0, st>>>(s.clist, s.ccnt, s.Hp * s.Wp, (int*)dst);
             return hipGetLastError();
         default:
-            k_read_ints<<<dim3(1), dim3(256), 0, st>>>(s, MDCNN_VIEW_STATS, (int*)dst);
+            k_read_stats<<<dim3(1), dim3(256), 0, st>>>(s, (int*)dst);
             return hipGetLastError();
     }
 }

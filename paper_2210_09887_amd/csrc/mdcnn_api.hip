@@ -56,8 +56,8 @@ size_t esize(int dtype) { return dtype == MDCNN_F16 ? 2 : 4; }
 long long pmod(long long v, long long n) { long long r = v % n; return r < 0 ? r + n : r; }
 
 struct Layout {
-    size_t A, P, flags, delta, list, clist, counters, partials, cpartials, total;
-    int Hp, Wp, nblk1, nseg_c;
+    size_t A, P, flags, delta, list, lcnt, clist, ccnt, counters, total;
+    int Hp, Wp;
 };
 
 mdcnn_status check_desc(const mdcnn_buffer_desc* d) {
@@ -79,22 +79,19 @@ void make_layout(const mdcnn_buffer_desc& d, Layout& L) {
     const bool hasA = d.kind != MDCNN_SITE_OUTPUT, hasP = d.kind != MDCNN_SITE_INPUT;
     L.Hp = d.H + d.border[0] + d.border[1];
     L.Wp = d.W + d.border[2] + d.border[3];
-    SiteDev tmp{};
-    tmp.C = d.C; tmp.dtype = d.dtype;
-    const int ppb = step1_pixels_per_block(tmp);
-    L.nblk1 = (d.H * d.W + ppb - 1) / ppb;
-    L.nseg_c = (L.Hp * L.Wp + kSegPixels - 1) / kSegPixels;
+    const size_t nseg_l = ((size_t)d.H * d.W + kSegPixels - 1) / kSegPixels;
+    const size_t nseg_c = ((size_t)L.Hp * L.Wp + kSegPixels - 1) / kSegPixels;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
     L.A = take(hasA ? (size_t)d.H * d.W * d.C * e : 0);
     L.P = take(hasP ? (size_t)L.Hp * L.Wp * d.C * e : 0);
     L.flags = take(hasA ? (size_t)d.H * d.W : 0);
     L.delta = take(hasA ? (size_t)d.H * d.W * d.C * e : 0);
-    L.list = take(hasA ? (size_t)d.H * d.W * 4 : 0);
-    L.clist = take(hasP ? (size_t)L.Hp * L.Wp * 4 : 0);
+    L.list = take(hasA ? nseg_l * kSegPixels * 4 : 0);
+    L.lcnt = take(hasA ? nseg_l * 4 : 0);
+    L.clist = take(hasP ? nseg_c * kSegPixels * 4 : 0);
+    L.ccnt = take(hasP ? nseg_c * 4 : 0);
     L.counters = take(kNumCounters * 4);
-    L.partials = take(hasA ? (size_t)L.nblk1 * 2 * 4 : 0);
-    L.cpartials = take(hasP ? (size_t)L.nseg_c * 4 : 0);
     L.total = off;
 }
 
@@ -176,10 +173,10 @@ mdcnn_status validate_edge(const mdcnn_buffer* in, const mdcnn_buffer* out, cons
 
 EdgeDev make_edge(const mdcnn_buffer* in, const mdcnn_buffer* out, const mdcnn_conv_desc& c) {
     EdgeDev e{};
-    e.delta = in->dev.delta; e.sflags = in->dev.flags; e.slist = in->dev.list; e.scounters = in->dev.counters;
+    e.delta = in->dev.delta; e.sflags = in->dev.flags; e.slist = in->dev.list; e.slcnt = in->dev.lcnt;
     e.sH = in->d.H; e.sW = in->d.W; e.Cin = c.Cin;
     e.P = out->dev.P; e.dflags = out->d.kind == MDCNN_SITE_OUTPUT ? nullptr : out->dev.flags;
-    e.clist = out->dev.clist; e.cpartials = out->dev.cpartials; e.dcounters = out->dev.counters;
+    e.clist = out->dev.clist; e.ccnt = out->dev.ccnt; e.dcounters = out->dev.counters;
     e.dH = out->d.H; e.dW = out->d.W; e.Cout = c.Cout; e.Hp = out->L.Hp; e.Wp = out->L.Wp;
     e.by0 = out->d.border[0]; e.bx0 = out->d.border[2]; e.p_oy = out->dev.p_oy; e.p_ox = out->dev.p_ox;
     e.w = c.w_dev; e.k = c.k; e.stride = c.k ? c.stride : 1; e.pad = c.k ? c.pad : 0; e.up = c.k ? c.up : 0;
@@ -314,10 +311,10 @@ mdcnn_status mdcnn_create_buffer(const mdcnn_buffer_desc* desc, void* dev_mem, s
     s.flags = hasA ? (uint8_t*)(base + b->L.flags) : nullptr;
     s.delta = hasA ? base + b->L.delta : nullptr;
     s.list = hasA ? (int*)(base + b->L.list) : nullptr;
+    s.lcnt = hasA ? (int*)(base + b->L.lcnt) : nullptr;
     s.clist = hasP ? (int*)(base + b->L.clist) : nullptr;
+    s.ccnt = hasP ? (int*)(base + b->L.ccnt) : nullptr;
     s.counters = (int*)(base + b->L.counters);
-    s.partials = hasA ? (int*)(base + b->L.partials) : nullptr;
-    s.cpartials = hasP ? (int*)(base + b->L.cpartials) : nullptr;
     s.bias = desc->bias_dev;
     s.H = desc->H; s.W = desc->W; s.C = desc->C; s.Hp = b->L.Hp; s.Wp = b->L.Wp;
     s.by0 = desc->border[0]; s.bx0 = desc->border[2];
@@ -353,6 +350,13 @@ mdcnn_status mdcnn_shift_camera(mdcnn_buffer* const* bufs, int n, int dty, int d
         full |= (sy >= d.H || -sy >= d.H || sx >= d.W || -sx >= d.W);
     }
     hipStream_t st = (hipStream_t)stream;
+    FillBatch fb{};
+    auto flush = [&]() -> hipError_t {
+        hipError_t err = timed(kClsShift, st, [&] { return launch_shift_fill(fb, st); });
+        fb.n = 0;
+        fb.total_blocks = 0;
+        return err;
+    };
     for (int i = 0; i < n; ++i) {
         mdcnn_buffer* b = bufs[i];
         const mdcnn_buffer_desc& d = b->d;
@@ -360,7 +364,11 @@ mdcnn_status mdcnn_shift_camera(mdcnn_buffer* const* bufs, int n, int dty, int d
         b->gy += sy;
         b->gx += sx;
         refresh_origins(b);
-        KeepRect pr{b->L.Hp, b->L.Wp, 0, 0, 0, 0}, ar{d.H, d.W, 0, 0, 0, 0};
+        FillJob j{};
+        j.A = b->dev.A; j.P = b->dev.P; j.flags = b->dev.flags; j.bias = b->dev.bias; j.counters = b->dev.counters;
+        j.H = d.H; j.W = d.W; j.C = d.C; j.Hp = b->L.Hp; j.Wp = b->L.Wp;
+        j.a_oy = b->dev.a_oy; j.a_ox = b->dev.a_ox; j.p_oy = b->dev.p_oy; j.p_ox = b->dev.p_ox;
+        j.dtype = d.dtype;
         if (!full) {
             // the old window, expressed in coordinates of the new one, is shifted by (-sy, -sx)
             auto keep = [](int ext, long long s, int& lo, int& hi) {   // |s| < ext here
@@ -368,14 +376,28 @@ mdcnn_status mdcnn_shift_camera(mdcnn_buffer* const* bufs, int n, int dty, int d
                 hi = ext - s < ext ? (int)(ext - s) : ext;
                 if (hi < lo) hi = lo;
             };
-            keep(b->L.Hp, sy, pr.y0, pr.y1);
-            keep(b->L.Wp, sx, pr.x0, pr.x1);
-            keep(d.H, sy, ar.y0, ar.y1);
-            keep(d.W, sx, ar.x0, ar.x1);
+            keep(j.Hp, sy, j.py0, j.py1);
+            keep(j.Wp, sx, j.px0, j.px1);
+            keep(j.H, sy, j.ay0, j.ay1);
+            keep(j.W, sx, j.ax0, j.ax1);
         }
-        const int rc = full ? (b->fresh ? 2 : 1) : 0;
-        hipError_t err = timed(kClsShift, st, [&] { return launch_shift_fill(b->dev, pr, ar, rc, st); });
-        if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "shift launch (buffer %d): %s", i, hipGetErrorString(err));
+        auto outside = [](int Hn, int Wn, int y0, int y1, int x0, int x1) {
+            return (y0 + (Hn - y1)) * Wn + (y1 - y0) * (x0 + (Wn - x1));
+        };
+        j.nP = j.P ? outside(j.Hp, j.Wp, j.py0, j.py1, j.px0, j.px1) : 0;
+        j.nA = j.A ? outside(j.H, j.W, j.ay0, j.ay1, j.ax0, j.ax1) : 0;
+        j.reset_counters = b->fresh ? 2 : 1;             // per-frame counters start at zero every frame
+        const int vec = d.dtype == MDCNN_F16 ? 8 : 4;
+        const long long items = (long long)(j.nP + j.nA) * (d.C % vec == 0 ? d.C / vec : d.C);
+        long long blocks = (items + kFillItemsPerBlock - 1) / kFillItemsPerBlock;
+        if (blocks < 1) blocks = 1;
+        j.block_begin = fb.total_blocks;
+        fb.j[fb.n++] = j;
+        fb.total_blocks += (unsigned)blocks;
+        if (fb.n == kMaxFillJobs) {
+            hipError_t err = flush();
+            if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "shift launch: %s", hipGetErrorString(err));
+        }
         if (full) {
             b->r_up = b->r_down = b->r_left = b->r_right = false;
             b->fresh = false;
@@ -386,6 +408,10 @@ mdcnn_status mdcnn_shift_camera(mdcnn_buffer* const* bufs, int n, int dty, int d
             if (dty > 0) b->r_up = true;
             if (dty < 0) b->r_down = true;
         }
+    }
+    if (fb.n) {
+        hipError_t err = flush();
+        if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "shift launch: %s", hipGetErrorString(err));
     }
     if (did_full_reset) *did_full_reset = full ? 1 : 0;
     return MDCNN_OK;

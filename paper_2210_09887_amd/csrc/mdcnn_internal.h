@@ -12,21 +12,25 @@ namespace mdcnn {
 constexpr int kFlagN = 1;   // newly unveiled this frame
 constexpr int kFlagU = 2;   // touched by a producer this frame
 constexpr int kFlagM = 4;   // updated (emitted a delta) this frame
+constexpr int kFlagC = 8;   // was a candidate of step 1 this frame (statistics)
 
-// counters[] slots (int32, device)
-constexpr int kCntUpdated = 0;
-constexpr int kCntCandidates = 1;
-constexpr int kCntCompute = 2;
-constexpr int kNumPerFrame = 8;     // slots [0, 8) are per-frame values, zeroed by every full reset
-// 64-bit accumulators since buffer creation (slot = index into (unsigned long long*)counters)
+// counters[] of a site (int32 slots, device).  Slots [0, 8) are per-frame values
+// zeroed by every camera shift; 64-bit running sums follow (index into
+// (unsigned long long*)counters), zeroed when the buffer is first reset.
+constexpr int kCntUpdated = 0;      // pixels updated this frame
+constexpr int kCntCandidates = 1;   // pixels visited by step 1 this frame
+constexpr int kNumPerFrame = 8;
 constexpr int kAccUpdated = 4;      // sum of update counts
 constexpr int kAccCandidates = 5;   // sum of candidate counts
-constexpr int kAccMacs = 6;         // multiply-accumulates of the MFMA kernel into this site (valid taps x Cin x Cout)
+constexpr int kAccMacs = 6;         // multiply-accumulates of the MFMA kernels into this site (valid taps x Cin x Cout)
 constexpr int kAccCompute = 7;      // sum of compute-list lengths of edges into this site
-constexpr int kAccMacsPlain = 8;    // multiply-accumulates of the plain-FMA kernel into this site
+constexpr int kAccMacsPlain = 8;    // multiply-accumulates of the plain-FMA kernels into this site
 constexpr int kNumCounters = 64;
 
-constexpr int kSegPixels = 1024;   // pixels per compaction segment
+// Lists are compacted per segment of kSegPixels consecutive linear indices:
+// entries of segment g sit at list[g * kSegPixels ...], their number in cnt[g].
+// Concatenating the segments in order gives the ascending list.
+constexpr int kSegPixels = 1024;
 
 // Device-side view of one site, passed to kernels by value.
 struct SiteDev {
@@ -34,11 +38,11 @@ struct SiteDev {
     void* P;              // ring Hp x Wp x C
     uint8_t* flags;       // H*W, view order
     void* delta;          // H x W x C, view order
-    int* list;            // H*W
-    int* clist;           // Hp*Wp
+    int* list;            // H*W, segment-local compaction of the update mask
+    int* lcnt;            // entries per segment of list
+    int* clist;           // Hp*Wp, segment-local compute list of the last producer
+    int* ccnt;            // entries per segment of clist
     int* counters;        // kNumCounters
-    int* partials;        // per step-1 block update counts
-    int* cpartials;       // per segment compute-list counts
     const float* bias;    // C floats or nullptr
     int H, W, C, Hp, Wp;
     int by0, bx0;         // border before the view (rows, cols)
@@ -50,31 +54,45 @@ struct SiteDev {
     int dtype;
 };
 
-// A rectangle of "kept" pixels inside an extent; everything outside it is (re)initialised.
-struct KeepRect {
-    int Hn, Wn;           // extent
-    int y0, y1, x0, x1;   // kept rows [y0,y1) and cols [x0,x1); empty => all pixels new
+// Initialisation job of one site for one camera shift: everything outside the
+// kept rectangle of the padded window gets P = bias, everything outside the
+// kept rectangle of the view gets A = 0 and flag N.
+struct FillJob {
+    void* A;
+    void* P;
+    uint8_t* flags;
+    const float* bias;
+    int* counters;
+    int H, W, C, Hp, Wp;
+    int a_oy, a_ox, p_oy, p_ox;
+    int py0, py1, px0, px1;     // kept rows / cols of the padded window (empty: all new)
+    int ay0, ay1, ax0, ax1;     // kept rows / cols of the view
+    int nP, nA;                 // pixels to initialise in P / in A
+    int dtype;
+    int reset_counters;         // 1: per-frame slots, 2: all (first reset)
+    unsigned block_begin;       // first block of the launch that works on this job
 };
-
-inline int keep_count(const KeepRect& r) {
-    int rows_out = r.y0 + (r.Hn - r.y1);
-    int mid = (r.y1 - r.y0) * (r.x0 + (r.Wn - r.x1));
-    return rows_out * r.Wn + mid;
-}
+constexpr int kMaxFillJobs = 24;
+struct FillBatch {
+    FillJob j[kMaxFillJobs];
+    int n;
+    unsigned total_blocks;
+};
+constexpr int kFillItemsPerBlock = 2048;     // 16-byte chunks (or single elements) per block
 
 // One edge as seen by the list and convolution kernels.
 struct EdgeDev {
     // source
     const void* delta;
     const uint8_t* sflags;
-    const int* slist;         // L of the source
-    const int* scounters;
+    const int* slist;         // L of the source (segment-local)
+    const int* slcnt;
     int sH, sW, Cin;
     // destination
     void* P;
     uint8_t* dflags;          // nullptr for OUTPUT sites
     int* clist;
-    int* cpartials;
+    int* ccnt;
     int* dcounters;
     int dH, dW, Cout, Hp, Wp, by0, bx0, p_oy, p_ox;
     // operator
@@ -90,12 +108,9 @@ struct EdgeBatch {
     int n;
 };
 
-int step1_pixels_per_block(const SiteDev& s);
-
-// reset_counters: 0 none, 1 per-frame slots, 2 everything (first reset of a buffer)
-hipError_t launch_shift_fill(const SiteDev& s, const KeepRect& pr, const KeepRect& ar, int reset_counters,
-                             hipStream_t st);
+hipError_t launch_shift_fill(const FillBatch& fb, hipStream_t st);
 hipError_t launch_step1(const SiteDev& s, const void* frame, const uint8_t* forced, hipStream_t st);
+// compaction of the update mask of s (do_compact) and the compute lists of the edges in eb
 hipError_t launch_lists(const SiteDev& s, const EdgeBatch& eb, bool do_compact, hipStream_t st);
 // returns the kernel class that was launched in *cls
 hipError_t launch_conv(const EdgeDev& e, int dtype, int conv_path, hipStream_t st, int* cls);
