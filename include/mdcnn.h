@@ -183,7 +183,10 @@ mdcnn_status mdcnn_write_view(mdcnn_buffer* buf, int what, const void* src_dev, 
 /* Library options (process-wide, host-only). */
 typedef enum {
     MDCNN_OPT_CONV_PATH = 0, /* 0 auto; fallbacks for testing: 1 plain FMA, 2 MFMA w/o LDS  */
-    MDCNN_OPT_PROFILE = 1    /* 1: bracket every kernel launch with a pair of HIP events  */
+    MDCNN_OPT_PROFILE = 1,   /* 1: bracket every kernel launch with a pair of HIP events  */
+    MDCNN_OPT_CONV_TILE = 2, /* tuning: 0 auto, 1..10 force a tile shape of the MFMA kernel */
+    MDCNN_OPT_CONV_PIPE = 3, /* tuning: 0 auto, 1 / 2 prefetch depth of the MFMA kernel    */
+    MDCNN_OPT_CONV_XCD = 4   /* tuning: 1 (default) tie cout tiles to XCDs, 0 plain order  */
 } mdcnn_option;
 mdcnn_status mdcnn_set_option(int option, int value);
 

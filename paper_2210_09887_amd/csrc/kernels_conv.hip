@@ -4,14 +4,20 @@
 //   P_dst[q] <- P_dst[q] + y[q]        (border pixels included: they are stashed)
 // Output-stationary: one owner per output pixel, fixed summation order, so the
 // result does not depend on scheduling.  Weights are w[tap][cout][cin].
-// Lists are segment-local (kSegPixels indices per segment, count per segment):
-// a tile is (segment, offset inside the segment).
+// There is no separate list kernel: every block compacts the segment of the
+// compute list it works on itself, from the source's update mask (kSegPixels
+// indices per segment, one per thread, ballot + popcount ranks); a tile is
+// (segment, offset inside the segment).  The first tile of a segment also writes
+// the segment to the destination's compute list, the copy the ABI exposes, and
+// the first edge of a forward call compacts the source's update mask into L.
 //
 //   k_conv_mfma_tiled : LDS-tiled gather-GEMM on the CDNA4 matrix cores (fp16 in, fp32 acc)
 //   k_conv_mfma_f16   : MFMA without LDS staging (fallback for Cin % 32 != 0)
 //   k_conv_ldsw       : plain FMA with the weights resident in LDS (fp32 nets, stems)
 //   k_conv_plain      : plain FMA, any dtype / channel count
 //   k_identity        : residual skip, P_dst[q] += delta[q]
+#include <type_traits>
+
 #include "mdcnn_internal.h"
 
 namespace mdcnn {
@@ -26,20 +32,6 @@ __device__ __forceinline__ int wrapc(int v, int n) { return v >= n ? v - n : v; 
 __device__ __forceinline__ size_t pdst_offset(const EdgeDev& e, int wy, int wx) {
     int py = wrapc(e.p_oy + wy, e.Hp), px = wrapc(e.p_ox + wx, e.Wp);
     return ((size_t)py * e.Wp + px) * e.Cout;
-}
-
-// Which list an edge walks: upsampling edges walk the updated source pixels,
-// all others the compute list of the destination.
-struct ListRef {
-    const int* list;
-    const int* cnt;
-    int nseg;
-};
-__device__ __forceinline__ ListRef list_of(const EdgeDev& e) {
-    ListRef r;
-    if (e.up) { r.list = e.slist; r.cnt = e.slcnt; r.nseg = (e.sH * e.sW + kSegPixels - 1) / kSegPixels; }
-    else { r.list = e.clist; r.cnt = e.ccnt; r.nseg = (e.Hp * e.Wp + kSegPixels - 1) / kSegPixels; }
-    return r;
 }
 
 // Decode list entry -> conv-output coordinates (cy, cx) in the source-aligned
@@ -70,14 +62,24 @@ __device__ __forceinline__ unsigned tap_mask(const EdgeDev& e, int cy, int cx) {
     return m;
 }
 
-// Statistics: add (valid taps of this wave) x Cin x Cout to a multiply-accumulate
-// counter of the destination.  Called by whole waves.
-__device__ __forceinline__ void count_macs(const EdgeDev& e, int taps, int slot) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) taps += __shfl_xor(taps, off);
-    if ((threadIdx.x & 63) == 0 && taps)
-        atomicAdd(reinterpret_cast<unsigned long long*>(e.dcounters) + slot,
+// Number of list segments an edge walks: upsampling edges walk the source
+// pixels (view order), all others the destination's padded window.
+__device__ __forceinline__ int edge_segments(const EdgeDev& e) {
+    const int n = e.up ? e.sH * e.sW : e.Hp * e.Wp;
+    return (n + kSegPixels - 1) / kSegPixels;
+}
+
+// Statistics: add taps x Cin x Cout to one of the partial multiply-accumulate
+// sums of the destination (which: 0 MFMA kernels, 1 plain kernels).
+__device__ __forceinline__ void add_macs(const EdgeDev& e, long long taps, int which) {
+    if (taps)
+        atomicAdd(reinterpret_cast<unsigned long long*>(e.dcounters) + kAccMacsSpread + 8 * which + (blockIdx.x & 7),
                   (unsigned long long)taps * (unsigned long long)(e.Cin * e.Cout));
+}
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
 }
 
 __device__ __forceinline__ void mark_touched(const EdgeDev& e, int wy, int wx) {
@@ -88,6 +90,90 @@ __device__ __forceinline__ void mark_touched(const EdgeDev& e, int wy, int wx) {
             const int oy = wy + a - e.by0, ox = wx + b - e.bx0;
             if (oy >= 0 && oy < e.dH && ox >= 0 && ox < e.dW) e.dflags[oy * e.dW + ox] |= (uint8_t)kFlagU;
         }
+}
+
+// Per-tile prologue shared by all convolution kernels.  Thread t looks at index
+// seg * kSegPixels + t of the edge's index space, gathers the update flags of its
+// footprint (they become the tap mask), and the block ranks the non-empty ones
+// with ballot + popcount: the rank is the position in the segment's compute list.
+// Entries with rank in [first, first + bm) are decoded into the LDS rows
+// s_base / s_wy / s_wx / s_vm (s_vm = 0 beyond the live rows).  With `publish`
+// the segment is also written to the destination's compute list.  `touch` marks
+// the destination pixels as touched.  Returns the number of entries of the
+// segment; sh[4] = valid taps of the tile, sh[5] = OR of its tap masks.
+// Block-uniform; two barriers; the caller must have a barrier before the call.
+__device__ __forceinline__ int tile_prologue(const EdgeDev& e, int seg, int first, int bm, bool publish, bool touch,
+                                             int* s_base, int* s_wy, int* s_wx, unsigned* s_vm, int* sh) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = e.up ? e.sH * e.sW : e.Hp * e.Wp;
+    const int p = seg * kSegPixels + tid;
+    if (tid < bm) s_vm[tid] = 0;
+    if (tid == 0) { sh[4] = 0; sh[5] = 0; }
+    int cy = 0, cx = 0, wy = 0, wx = 0;
+    unsigned vm = 0;
+    if (p < n) {
+        decode_entry(e, p, cy, cx, wy, wx);
+        if (e.k == 0) vm = (cy >= 0 && cy < e.sH && cx >= 0 && cx < e.sW && (e.sflags[cy * e.sW + cx] & kFlagM)) ? 1u : 0u;
+        else vm = tap_mask(e, cy, cx);
+    }
+    const bool has = vm != 0;
+    const unsigned long long bal = __ballot(has);
+    const int rank = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) sh[wave] = __popcll(bal);
+    __syncthreads();
+    int off = rank;
+    for (int i = 0; i < wave; ++i) off += sh[i];
+    const int tot = sh[0] + sh[1] + sh[2] + sh[3];
+    const int r = off - first;
+    const bool mine = has && r >= 0 && r < bm;
+    if (mine) {
+        s_vm[r] = vm;
+        s_base[r] = (cy * e.stride - e.pad) * e.sW + (cx * e.stride - e.pad);
+        s_wy[r] = wy;
+        s_wx[r] = wx;
+        if (touch) mark_touched(e, wy, wx);
+    }
+    if (publish && has) e.clist[seg * kSegPixels + off] = p;
+    if (publish && tid == 0) {
+        e.ccnt[seg] = tot;
+        if (tot) atomicAdd(reinterpret_cast<unsigned long long*>(e.dcounters) + kAccCompute, (unsigned long long)tot);
+    }
+    unsigned orm = mine ? vm : 0u;
+    int taps = mine ? __popc(vm) : 0;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { orm |= __shfl_xor(orm, o); taps += __shfl_xor(taps, o); }
+    if (lane == 0 && orm) { atomicOr(reinterpret_cast<unsigned*>(&sh[5]), orm); atomicAdd(&sh[4], taps); }
+    __syncthreads();
+    return tot;
+}
+
+// The first edge of a forward call also compacts the update mask of the source
+// site into its list L (segment-local, ascending) and adds up the per-frame
+// statistics.  Called by all threads of every block before their own work.
+__device__ __forceinline__ void carry_source_compaction(const EdgeDev& e, int* sh) {
+    if (!e.pub_list || blockIdx.y != 0) return;
+    const int HW = e.sH * e.sW;
+    const int nseg = (HW + kSegPixels - 1) / kSegPixels;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int seg = blockIdx.x; seg < nseg; seg += gridDim.x) {
+        const int p = seg * kSegPixels + tid;
+        const int f = p < HW ? e.sflags[p] : 0;
+        const unsigned long long bm = __ballot(f & kFlagM), bc = __ballot(f & kFlagC);
+        __syncthreads();                                   // sh is free again
+        if (lane == 0) { sh[wave] = __popcll(bm); sh[4 + wave] = __popcll(bc); }
+        __syncthreads();
+        int off = __popcll(bm & ((1ull << lane) - 1ull));
+        for (int i = 0; i < wave; ++i) off += sh[i];
+        if (f & kFlagM) e.pub_list[seg * kSegPixels + off] = p;
+        if (tid == 0) {
+            const int tot = sh[0] + sh[1] + sh[2] + sh[3], c = sh[4] + sh[5] + sh[6] + sh[7];
+            e.pub_lcnt[seg] = tot;
+            unsigned long long* acc = reinterpret_cast<unsigned long long*>(e.scounters);
+            if (tot) { atomicAdd(&e.scounters[kCntUpdated], tot); atomicAdd(acc + kAccUpdated, (unsigned long long)tot); }
+            if (c) { atomicAdd(&e.scounters[kCntCandidates], c); atomicAdd(acc + kAccCandidates, (unsigned long long)c); }
+        }
+    }
+    __syncthreads();
 }
 
 // ---------------------------------------------------------------------------
@@ -105,72 +191,71 @@ __device__ __forceinline__ void mark_touched(const EdgeDev& e, int wy, int wx) {
 // starting at 8*(l/32); the result puts pixel l%32 on lane l with couts
 // 8*(r/4) + 4*(l/32) + r%4 in accumulator register r.
 // ---------------------------------------------------------------------------
-template <int WM, int WN, int TM, int TN, int KC>
+template <int WM, int WN, int TM, int TN, int KC, int PIPE>
 struct TiledCfg {
     static constexpr int BM = 32 * WM * TM, BN = 32 * WN * TN;
     static constexpr int LDK = KC + 8;             // slab row, halves
     static constexpr int LDC = BN + 4;             // transposed accumulator row, floats
     static constexpr int CPR = KC / 8;             // 16-byte chunks per slab row
-    static constexpr int SLAB_BYTES = (BM + BN) * LDK * 2;
+    static constexpr int STAGE_HALVES = (BM + BN) * LDK;
+    static constexpr int SLAB_BYTES = PIPE * STAGE_HALVES * 2;
     static constexpr int C_BYTES = BM * LDC * 4;
     static constexpr int SMEM = SLAB_BYTES > C_BYTES ? SLAB_BYTES : C_BYTES;
     static constexpr int TPS = kSegPixels / BM;    // tiles per list segment
 };
 
-template <int WM, int WN, int TM, int TN, int KC>
-__global__ __launch_bounds__(256) void k_conv_mfma_tiled(EdgeDev e) {
-    using Cfg = TiledCfg<WM, WN, TM, TN, KC>;
+// Work item u of a 1-D grid -> (pixel tile m, cout tile n).  Work groups are
+// dealt round-robin to the 8 XCDs, each with its own L2: tying u % 8 to the
+// cout tile makes all blocks of one XCD share the same weight slice.
+__device__ __forceinline__ void map_tile(int u, int NT, int xcd_map, int& m, int& n) {
+    if (xcd_map) {
+        const int q = 8 / NT, x = u & 7, r = u >> 3;
+        n = x % NT;
+        m = r * q + x / NT;
+    } else {
+        n = u % NT;
+        m = u / NT;
+    }
+}
+
+// PIPE = 1: one LDS buffer, loads one step ahead (two barriers per step).
+// PIPE = 2: two LDS buffers and two register stages, loads two steps ahead
+//           (one barrier per step).
+template <int WM, int WN, int TM, int TN, int KC, int PIPE>
+__global__ __launch_bounds__(256) void k_conv_mfma_tiled(EdgeDev e, int NT, int work_items, int xcd_map) {
+    using Cfg = TiledCfg<WM, WN, TM, TN, KC, PIPE>;
     constexpr int BM = Cfg::BM, BN = Cfg::BN, LDK = Cfg::LDK, LDC = Cfg::LDC, CPR = Cfg::CPR, TPS = Cfg::TPS;
     constexpr int NB = (BM * CPR + 255) / 256, NA = (BN * CPR + 255) / 256;
-    static_assert(WM * WN == 4 && BM % 64 == 0 && kSegPixels % BM == 0, "4 waves, whole waves of entries");
+    static_assert(WM * WN == 4 && kSegPixels % BM == 0, "4 waves; tiles do not straddle segments");
     extern __shared__ __align__(16) unsigned char smem[];
-    f16* sB = reinterpret_cast<f16*>(smem);              // [BM][LDK] gathered deltas
-    f16* sA = sB + BM * LDK;                             // [BN][LDK] weights
+    f16* slab = reinterpret_cast<f16*>(smem);            // PIPE x { [BM][LDK] deltas, [BN][LDK] weights }
     float* sC = reinterpret_cast<float*>(smem);          // [BM][LDC] after the K loop
     __shared__ int s_base[BM], s_wy[BM], s_wx[BM];
     __shared__ unsigned s_vm[BM];
-    __shared__ unsigned s_tilemask;
-    __shared__ int s_taps;
+    __shared__ int sh[8];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
     const int r32 = lane & 31, kh = lane >> 5;
-    const ListRef L = list_of(e);
-    const int n0 = blockIdx.y * BN;
+    const int MT = edge_segments(e) * TPS;
     const f16* __restrict__ delta = (const f16*)e.delta;
     const f16* __restrict__ w = (const f16*)e.w;
 
-    for (int tile = blockIdx.x; tile < L.nseg * TPS; tile += gridDim.x) {
-        const int seg = tile / TPS, first = (tile - seg * TPS) * BM;
-        const int live = L.cnt[seg] - first;               // entries of this tile (block-uniform)
-        if (live <= 0) continue;
-        const int* __restrict__ lst = L.list + seg * kSegPixels + first;
+    carry_source_compaction(e, sh);
+
+    for (int u = blockIdx.x; u < work_items; u += gridDim.x) {
+        int mt, nt;
+        map_tile(u, NT, xcd_map, mt, nt);
+        if (mt >= MT) continue;
+        const int seg = mt / TPS, first = (mt - seg * TPS) * BM;
+        const int n0 = nt * BN;
         __syncthreads();                                  // previous tile is done with LDS
-        if (tid == 0) { s_tilemask = 0; s_taps = 0; }
-        unsigned vmask = 0;
-        if (tid < BM) {
-            int cy = 0, cx = 0, wy = 0, wx = 0;
-            if (tid < live) {
-                decode_entry(e, lst[tid], cy, cx, wy, wx);
-                vmask = tap_mask(e, cy, cx);
-                if (blockIdx.y == 0) mark_touched(e, wy, wx);
-            }
-            s_base[tid] = (cy * e.stride - e.pad) * e.sW + (cx * e.stride - e.pad);
-            s_wy[tid] = wy; s_wx[tid] = wx; s_vm[tid] = vmask;
-        }
-        __syncthreads();
-        if (tid < BM) {                                    // whole waves: BM % 64 == 0
-            unsigned orm = vmask;
-            int taps = __popc(vmask);
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) { orm |= __shfl_xor(orm, off); taps += __shfl_xor(taps, off); }
-            if (lane == 0) { atomicOr(&s_tilemask, orm); atomicAdd(&s_taps, taps); }
-        }
-        __syncthreads();
-        unsigned rem = s_tilemask;
-        if (tid == 0 && blockIdx.y == 0)                   // statistics: one atomic per tile
-            atomicAdd(reinterpret_cast<unsigned long long*>(e.dcounters) + kAccMacs,
-                      (unsigned long long)s_taps * (unsigned long long)(e.Cin * e.Cout));
+        const int tot = tile_prologue(e, seg, first, BM, nt == 0 && first == 0 && !e.up, nt == 0,
+                                      s_base, s_wy, s_wx, s_vm, sh);
+        const int live = tot - first < BM ? tot - first : BM;     // entries of this tile (block-uniform)
+        if (live <= 0) continue;
+        const unsigned tilemask = (unsigned)sh[5];
+        if (tid == 0 && nt == 0) add_macs(e, sh[4], 0);    // statistics: one atomic per tile
 
         f32x16 acc[TM][TN];
 #pragma unroll
@@ -180,9 +265,14 @@ __global__ __launch_bounds__(256) void k_conv_mfma_tiled(EdgeDev e) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-        f16x8 rb[NB], ra[NA];
-        auto load_slab = [&](int tap, int c0) {
-            const int jy = tap / e.k, jx = tap - jy * e.k;
+        // the load iterator runs PIPE steps ahead of the multiplication
+        unsigned ld_rem = tilemask;
+        int ld_tap = ld_rem ? __ffs(ld_rem) - 1 : -1, ld_c0 = 0;
+        f16x8 rb[PIPE][NB], ra[PIPE][NA];
+        auto load_next = [&](auto stage) {
+            constexpr int S = decltype(stage)::value;
+            if (ld_tap < 0) return;
+            const int jy = ld_tap / e.k, jx = ld_tap - jy * e.k;
             const int toff = jy * e.sW + jx;
 #pragma unroll
             for (int i = 0; i < NB; ++i) {
@@ -191,40 +281,41 @@ __global__ __launch_bounds__(256) void k_conv_mfma_tiled(EdgeDev e) {
                 f16x8 v;
 #pragma unroll
                 for (int q = 0; q < 8; ++q) v[q] = (f16)0.f;
-                if (ch < BM * CPR && ((s_vm[row] >> tap) & 1u))
-                    v = *reinterpret_cast<const f16x8*>(delta + (size_t)(s_base[row] + toff) * e.Cin + c0 + cc * 8);
-                rb[i] = v;
+                if (ch < BM * CPR && ((s_vm[row] >> ld_tap) & 1u))
+                    v = *reinterpret_cast<const f16x8*>(delta + (size_t)(s_base[row] + toff) * e.Cin + ld_c0 + cc * 8);
+                rb[S][i] = v;
             }
 #pragma unroll
             for (int i = 0; i < NA; ++i) {
                 const int ch = tid + 256 * i;
                 const int row = ch / CPR, cc = ch - row * CPR;
                 if (ch < BN * CPR)
-                    ra[i] = *reinterpret_cast<const f16x8*>(w + ((size_t)(tap * e.Cout + n0 + row)) * e.Cin + c0 + cc * 8);
+                    ra[S][i] = *reinterpret_cast<const f16x8*>(w + ((size_t)(ld_tap * e.Cout + n0 + row)) * e.Cin + ld_c0 + cc * 8);
             }
+            ld_c0 += KC;
+            if (ld_c0 >= e.Cin) { ld_c0 = 0; ld_rem &= ld_rem - 1; ld_tap = ld_rem ? __ffs(ld_rem) - 1 : -1; }
         };
-        auto store_slab = [&]() {
+        auto store_stage = [&](auto stage) {
+            constexpr int S = decltype(stage)::value;
+            f16* sB = slab + S * Cfg::STAGE_HALVES;
+            f16* sA = sB + BM * LDK;
 #pragma unroll
             for (int i = 0; i < NB; ++i) {
                 const int ch = tid + 256 * i;
                 const int row = ch / CPR, cc = ch - row * CPR;
-                if (ch < BM * CPR) *reinterpret_cast<f16x8*>(sB + row * LDK + cc * 8) = rb[i];
+                if (ch < BM * CPR) *reinterpret_cast<f16x8*>(sB + row * LDK + cc * 8) = rb[S][i];
             }
 #pragma unroll
             for (int i = 0; i < NA; ++i) {
                 const int ch = tid + 256 * i;
                 const int row = ch / CPR, cc = ch - row * CPR;
-                if (ch < BN * CPR) *reinterpret_cast<f16x8*>(sA + row * LDK + cc * 8) = ra[i];
+                if (ch < BN * CPR) *reinterpret_cast<f16x8*>(sA + row * LDK + cc * 8) = ra[S][i];
             }
         };
-
-        int tap = rem ? __ffs(rem) - 1 : -1, c0 = 0;
-        if (tap >= 0) { load_slab(tap, c0); store_slab(); }
-        __syncthreads();
-        while (tap >= 0) {
-            int ntap = tap, nc0 = c0 + KC;
-            if (nc0 >= e.Cin) { nc0 = 0; rem &= rem - 1; ntap = rem ? __ffs(rem) - 1 : -1; }
-            if (ntap >= 0) load_slab(ntap, nc0);            // in flight while this step is multiplied
+        auto multiply = [&](auto stage) {
+            constexpr int S = decltype(stage)::value;
+            const f16* sB = slab + S * Cfg::STAGE_HALVES;
+            const f16* sA = sB + BM * LDK;
 #pragma unroll
             for (int kk = 0; kk < KC / 16; ++kk) {
                 f16x8 fb[TM], fa[TN];
@@ -240,10 +331,37 @@ __global__ __launch_bounds__(256) void k_conv_mfma_tiled(EdgeDev e) {
                     for (int j = 0; j < TN; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[j], fb[i], acc[i][j], 0, 0, 0);
             }
+        };
+        using S0 = std::integral_constant<int, 0>;
+        using S1 = std::integral_constant<int, PIPE - 1>;
+        int steps = __popc(tilemask) * (e.Cin / KC);
+        if constexpr (PIPE == 1) {
+            load_next(S0{});
+            store_stage(S0{});
             __syncthreads();
-            if (ntap >= 0) store_slab();
-            __syncthreads();
-            tap = ntap; c0 = nc0;
+            while (steps > 0) {
+                load_next(S0{});                             // in flight while this step is multiplied
+                multiply(S0{});
+                __syncthreads();
+                if (--steps > 0) store_stage(S0{});
+                __syncthreads();
+            }
+        } else {
+            load_next(S0{});
+            load_next(S1{});
+            while (steps > 0) {
+                store_stage(S0{});
+                load_next(S0{});                             // refill the registers just drained
+                __syncthreads();
+                multiply(S0{});
+                if (--steps == 0) break;
+                store_stage(S1{});
+                load_next(S1{});
+                __syncthreads();
+                multiply(S1{});
+                --steps;
+            }
+            __syncthreads();                                 // all multiplications done: LDS becomes the C tile
         }
 
         // accumulators -> LDS as [pixel][cout]
@@ -287,28 +405,29 @@ __global__ __launch_bounds__(256) void k_conv_mfma_f16(EdgeDev e) {
     constexpr int WM = 4 / WN;
     constexpr int TILE_M = 32 * WM;
     constexpr int TPS = kSegPixels / TILE_M;
+    __shared__ int s_base[TILE_M], s_wy[TILE_M], s_wx[TILE_M];
+    __shared__ unsigned s_vm[TILE_M];
+    __shared__ int sh[8];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave % WM, wn = wave / WM;
     const int col = lane & 31, kh = lane >> 5;
-    const ListRef L = list_of(e);
+    const int MT = edge_segments(e) * TPS;
     const int n0 = (blockIdx.y * WN + wn) * 32;
     const f16* __restrict__ delta = (const f16*)e.delta;
     const f16* __restrict__ w = (const f16*)e.w;
     const int taps = e.k * e.k;
-    for (int tile = blockIdx.x; tile < L.nseg * TPS; tile += gridDim.x) {
+    carry_source_compaction(e, sh);
+    for (int tile = blockIdx.x; tile < MT; tile += gridDim.x) {
         const int seg = tile / TPS, first = (tile - seg * TPS) * TILE_M;
-        const int cnt = L.cnt[seg];
-        if (first >= cnt) continue;
-        const int ent = first + wm * 32 + col;
-        const bool live = ent < cnt;
-        int cy = 0, cx = 0, wy = 0, wx = 0;
-        unsigned vmask = 0;
-        if (live) {
-            decode_entry(e, L.list[seg * kSegPixels + ent], cy, cx, wy, wx);
-            vmask = tap_mask(e, cy, cx);
-        }
-        if (wn == 0 && blockIdx.y == 0) count_macs(e, kh == 0 ? __popc(vmask) : 0, kAccMacs);
-        const int y0 = cy * e.stride - e.pad, x0 = cx * e.stride - e.pad;
+        __syncthreads();
+        const int tot = tile_prologue(e, seg, first, TILE_M, blockIdx.y == 0 && first == 0 && !e.up, blockIdx.y == 0,
+                                      s_base, s_wy, s_wx, s_vm, sh);
+        if (first >= tot) continue;
+        if (threadIdx.x == 0 && blockIdx.y == 0) add_macs(e, sh[4], 0);
+        const int row = wm * 32 + col;
+        const bool live = first + row < tot;
+        const unsigned vmask = s_vm[row];
+        const int base = s_base[row], wy = s_wy[row], wx = s_wx[row];
         f32x16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.f;
@@ -317,7 +436,7 @@ __global__ __launch_bounds__(256) void k_conv_mfma_f16(EdgeDev e) {
             if (__ballot(v) == 0ull) continue;                 // no pixel of this wave uses the tap
             const int jy = tap / e.k, jx = tap - jy * e.k;
             const f16* arow = w + ((size_t)(tap * e.Cout + n0 + col)) * e.Cin + kh * 8;
-            const f16* brow = delta + (v ? ((size_t)((y0 + jy) * e.sW + (x0 + jx))) * e.Cin + kh * 8 : 0);
+            const f16* brow = delta + (v ? ((size_t)(base + jy * e.sW + jx)) * e.Cin + kh * 8 : 0);
             for (int c0 = 0; c0 < e.Cin; c0 += 16) {
                 f16x8 a = *reinterpret_cast<const f16x8*>(arow + c0);
                 f16x8 b;
@@ -342,10 +461,28 @@ __global__ __launch_bounds__(256) void k_conv_mfma_f16(EdgeDev e) {
                         *reinterpret_cast<f16x4*>(p + 8 * g) = o;
                     }
                 }
-            if (kh == 0 && wn == 0 && blockIdx.y == 0) mark_touched(e, wy, wx);
         }
     }
 }
+
+template <typename T> struct Row8;
+template <> struct Row8<f16> {
+    __device__ static void add(f16* p, const float* v) {
+        f16x8 o = *reinterpret_cast<f16x8*>(p);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) o[q] = (f16)((float)o[q] + v[q]);
+        *reinterpret_cast<f16x8*>(p) = o;
+    }
+};
+template <> struct Row8<float> {
+    __device__ static void add(float* p, const float* v) {
+        float4 a = *reinterpret_cast<float4*>(p), b = *reinterpret_cast<float4*>(p + 4);
+        a.x += v[0]; a.y += v[1]; a.z += v[2]; a.w += v[3];
+        b.x += v[4]; b.y += v[5]; b.z += v[6]; b.w += v[7];
+        *reinterpret_cast<float4*>(p) = a;
+        *reinterpret_cast<float4*>(p + 4) = b;
+    }
+};
 
 // ---------------------------------------------------------------------------
 // Plain FMA convolution with ALL weights resident in LDS as fp32
@@ -358,36 +495,33 @@ template <typename T>
 __global__ __launch_bounds__(256) void k_conv_ldsw(EdgeDev e, int groups, int ppb) {
     extern __shared__ __align__(16) unsigned char smem[];
     float* sW = reinterpret_cast<float*>(smem);             // [tap][Cin][Cout]
+    __shared__ int s_base[256], s_wy[256], s_wx[256];
+    __shared__ unsigned s_vm[256];
+    __shared__ int sh[8];
     const int tid = threadIdx.x;
     const int cg = tid % groups, pl = tid / groups;         // cout group, local pixel
-    const ListRef L = list_of(e);
     const T* __restrict__ delta = (const T*)e.delta;
     const T* __restrict__ w = (const T*)e.w;
     const int taps = e.k * e.k;
     const int cc = e.Cin * e.Cout;
+    carry_source_compaction(e, sh);
     for (int i = tid; i < taps * cc; i += 256) {
         const int tap = i / cc, r = i - tap * cc;
         const int co = r / e.Cin, ci = r - co * e.Cin;
         sW[tap * cc + ci * e.Cout + co] = (float)w[i];
     }
-    __syncthreads();
+    long long block_taps = 0;                               // statistics (thread 0 only)
     const int tps = (kSegPixels + ppb - 1) / ppb;           // tiles per segment
-    for (int tile = blockIdx.x; tile < L.nseg * tps; tile += gridDim.x) {
+    const int MT = edge_segments(e) * tps;
+    for (int tile = blockIdx.x; tile < MT; tile += gridDim.x) {
         const int seg = tile / tps, first = (tile - seg * tps) * ppb;
-        const int cnt = L.cnt[seg];
-        if (first >= cnt) continue;
-        const int ent = first + pl;
-        const bool live = pl < ppb && ent < cnt;
-        int cy = 0, cx = 0, wy = 0, wx = 0;
-        unsigned vmask = 0;
-        if (live) {
-            decode_entry(e, L.list[seg * kSegPixels + ent], cy, cx, wy, wx);
-            vmask = tap_mask(e, cy, cx);
-            if (cg == 0) mark_touched(e, wy, wx);
-        }
-        count_macs(e, cg == 0 ? __popc(vmask) : 0, kAccMacsPlain);
-        if (!live) continue;
-        const int base = (cy * e.stride - e.pad) * e.sW + (cx * e.stride - e.pad);
+        __syncthreads();
+        const int tot = tile_prologue(e, seg, first, ppb, first == 0 && !e.up, true, s_base, s_wy, s_wx, s_vm, sh);
+        if (first >= tot) continue;
+        if (tid == 0) block_taps += sh[4];
+        if (pl >= ppb || first + pl >= tot) continue;
+        const unsigned vmask = s_vm[pl];
+        const int base = s_base[pl];
         float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         for (int tap = 0; tap < taps; ++tap) {
             if (!((vmask >> tap) & 1u)) continue;
@@ -406,12 +540,10 @@ __global__ __launch_bounds__(256) void k_conv_ldsw(EdgeDev e, int groups, int pp
         }
         const int f = 1 << e.up;
         for (int ua = 0; ua < f; ++ua)
-            for (int ub = 0; ub < f; ++ub) {
-                T* pp = (T*)e.P + pdst_offset(e, wy + ua, wx + ub) + cg * 8;
-#pragma unroll
-                for (int q = 0; q < 8; ++q) pp[q] = (T)((float)pp[q] + acc[q]);
-            }
+            for (int ub = 0; ub < f; ++ub)
+                Row8<T>::add((T*)e.P + pdst_offset(e, s_wy[pl] + ua, s_wx[pl] + ub) + cg * 8, acc);
     }
+    if (tid == 0) add_macs(e, block_taps, 1);               // statistics: one atomic per block
 }
 
 // ---------------------------------------------------------------------------
@@ -420,33 +552,31 @@ __global__ __launch_bounds__(256) void k_conv_ldsw(EdgeDev e, int groups, int pp
 // ---------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void k_conv_plain(EdgeDev e) {
+    __shared__ int s_base[16], s_wy[16], s_wx[16];
+    __shared__ unsigned s_vm[16];
+    __shared__ int sh[8];
     const int p = threadIdx.x >> 4, cl = threadIdx.x & 15;
-    const ListRef L = list_of(e);
     const T* __restrict__ delta = (const T*)e.delta;
     const T* __restrict__ w = (const T*)e.w;
     const int taps = e.k * e.k;
     constexpr int TPS = kSegPixels / 16;
-    for (int tile = blockIdx.x; tile < L.nseg * TPS; tile += gridDim.x) {
+    const int MT = edge_segments(e) * TPS;
+    carry_source_compaction(e, sh);
+    for (int tile = blockIdx.x; tile < MT; tile += gridDim.x) {
         const int seg = tile / TPS, first = (tile - seg * TPS) * 16;
-        const int cnt = L.cnt[seg];
-        if (first >= cnt) continue;
-        const int ent = first + p;
-        const bool live = ent < cnt;
-        int cy = 0, cx = 0, wy = 0, wx = 0;
-        unsigned vmask = 0;
-        if (live) {
-            decode_entry(e, L.list[seg * kSegPixels + ent], cy, cx, wy, wx);
-            vmask = tap_mask(e, cy, cx);
-        }
-        count_macs(e, cl == 0 ? __popc(vmask) : 0, kAccMacsPlain);
-        if (!live) continue;
-        const int y0 = cy * e.stride - e.pad, x0 = cx * e.stride - e.pad;
+        __syncthreads();
+        const int tot = tile_prologue(e, seg, first, 16, first == 0 && !e.up, true, s_base, s_wy, s_wx, s_vm, sh);
+        if (first >= tot) continue;
+        if (threadIdx.x == 0) add_macs(e, sh[4], 1);
+        if (first + p >= tot) continue;
+        const unsigned vmask = s_vm[p];
+        const int base = s_base[p], wy = s_wy[p], wx = s_wx[p];
         for (int cg = 0; cg < e.Cout; cg += 64) {
             float acc[4] = {0.f, 0.f, 0.f, 0.f};
             for (int tap = 0; tap < taps; ++tap) {
                 if (!((vmask >> tap) & 1u)) continue;
                 const int jy = tap / e.k, jx = tap - jy * e.k;
-                const T* drow = delta + ((size_t)((y0 + jy) * e.sW + (x0 + jx))) * e.Cin;
+                const T* drow = delta + ((size_t)(base + jy * e.sW + jx)) * e.Cin;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int co = cg + cl + 16 * j;
@@ -468,36 +598,47 @@ __global__ __launch_bounds__(256) void k_conv_plain(EdgeDev e) {
                     }
                 }
         }
-        if (cl == 0) mark_touched(e, wy, wx);
     }
 }
 
-// Residual skip: P_dst[q] += delta[q] for every updated pixel q of the source
-// (a scan over the view: one thread per pixel and VEC channels).
+// Residual skip: P_dst[q] += delta[q] for every updated pixel q of the source.
+// One block per (list segment, group of 8 channel chunks).
 template <typename T, int VEC>
 __global__ __launch_bounds__(256) void k_identity(EdgeDev e) {
+    __shared__ int s_base[kSegPixels], s_wy[kSegPixels], s_wx[kSegPixels];
+    __shared__ unsigned s_vm[kSegPixels];
+    __shared__ int sh[8];
+    const int nseg = edge_segments(e);
     const int chunks = e.Cin / VEC;
-    const long long total = (long long)e.sH * e.sW * chunks;
-    const long long step = (long long)gridDim.x * 256;
-    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += step) {
-        const int pix = (int)(i / chunks);
-        if (!(e.sflags[pix] & kFlagM)) continue;
-        const int c0 = (int)(i - (long long)pix * chunks) * VEC;
-        const int oy = pix / e.sW, ox = pix - oy * e.sW;
-        T* pp = (T*)e.P + pdst_offset(e, oy + e.by0, ox + e.bx0) + c0;
-        const T* d = (const T*)e.delta + (size_t)pix * e.Cin + c0;
-        if constexpr (VEC == 8) {
-            f16x8 o = *reinterpret_cast<f16x8*>(pp);
-            const f16x8 v = *reinterpret_cast<const f16x8*>(d);
+    const int ch0 = blockIdx.y * 8, nch = chunks - ch0 < 8 ? chunks - ch0 : 8;
+    carry_source_compaction(e, sh);
+    for (int seg = blockIdx.x; seg < nseg; seg += gridDim.x) {
+        __syncthreads();
+        const int tot = tile_prologue(e, seg, 0, kSegPixels, blockIdx.y == 0, blockIdx.y == 0, s_base, s_wy, s_wx, s_vm, sh);
+        for (int i = threadIdx.x; i < tot * nch; i += 256) {
+            const int ent = i / nch;
+            const int c0 = (ch0 + i - ent * nch) * VEC;
+            // stride 1, pad 0: s_base is the source pixel itself
+            T* pp = (T*)e.P + pdst_offset(e, s_wy[ent], s_wx[ent]) + c0;
+            const T* d = (const T*)e.delta + (size_t)s_base[ent] * e.Cin + c0;
+            if constexpr (VEC == 8) {
+                f16x8 o = *reinterpret_cast<f16x8*>(pp);
+                const f16x8 v = *reinterpret_cast<const f16x8*>(d);
 #pragma unroll
-            for (int q = 0; q < 8; ++q) o[q] = (f16)((float)o[q] + (float)v[q]);
-            *reinterpret_cast<f16x8*>(pp) = o;
-        } else {
+                for (int q = 0; q < 8; ++q) o[q] = (f16)((float)o[q] + (float)v[q]);
+                *reinterpret_cast<f16x8*>(pp) = o;
+            } else {
 #pragma unroll
-            for (int q = 0; q < VEC; ++q) pp[q] = (T)((float)pp[q] + (float)d[q]);
+                for (int q = 0; q < VEC; ++q) pp[q] = (T)((float)pp[q] + (float)d[q]);
+            }
         }
-        if (c0 == 0) mark_touched(e, oy + e.by0, ox + e.bx0);
     }
+}
+
+// Compaction of the update mask alone (a forward call without outgoing edges).
+__global__ __launch_bounds__(256) void k_compact_source(EdgeDev e) {
+    __shared__ int sh[8];
+    carry_source_compaction(e, sh);
 }
 
 static unsigned cap_blocks(long long b, long long cap) {
@@ -506,37 +647,64 @@ static unsigned cap_blocks(long long b, long long cap) {
     return (unsigned)b;
 }
 
-template <int WM, int WN, int TM, int TN, int KC>
+// Tuning knobs (mdcnn_set_option): forced tile shape, pipeline depth, XCD mapping.
+int g_tile = 0, g_pipe = 0, g_xcd = 1;
+
+template <int WM, int WN, int TM, int TN, int KC, int PIPE>
 static hipError_t launch_tiled(const EdgeDev& e, long long max_entries, hipStream_t st) {
-    using Cfg = TiledCfg<WM, WN, TM, TN, KC>;
+    using Cfg = TiledCfg<WM, WN, TM, TN, KC, PIPE>;
     static bool attr_set = false;
-    auto kern = k_conv_mfma_tiled<WM, WN, TM, TN, KC>;
+    auto kern = k_conv_mfma_tiled<WM, WN, TM, TN, KC, PIPE>;
     if (!attr_set) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::SMEM);
         if (err != hipSuccess) return err;
         attr_set = true;
     }
     const long long nseg = (max_entries + kSegPixels - 1) / kSegPixels;
-    unsigned g = cap_blocks(nseg * Cfg::TPS, 2048);
-    kern<<<dim3(g, e.Cout / Cfg::BN), dim3(256), Cfg::SMEM, st>>>(e);
+    const long long MT = nseg * Cfg::TPS;
+    const int NT = e.Cout / Cfg::BN;
+    const int xcd = g_xcd && NT <= 8 && (8 % NT) == 0;
+    const long long items = xcd ? 8 * ((MT + 8 / NT - 1) / (8 / NT)) : MT * NT;
+    unsigned g = cap_blocks(items, 4096);
+    g = (g + 7u) & ~7u;                                    // whole rounds over the 8 XCDs
+    kern<<<dim3(g), dim3(256), Cfg::SMEM, st>>>(e, NT, (int)items, xcd);
     return hipGetLastError();
+}
+
+template <int WM, int WN, int TM, int TN, int KC>
+static hipError_t launch_tiled_p(const EdgeDev& e, long long max_entries, hipStream_t st) {
+    // deep prefetch pays when the K loop is long
+    const int steps = e.k * e.k * (e.Cin / KC);
+    const bool deep = g_pipe ? g_pipe == 2 : steps >= 16;
+    return deep ? launch_tiled<WM, WN, TM, TN, KC, 2>(e, max_entries, st)
+                : launch_tiled<WM, WN, TM, TN, KC, 1>(e, max_entries, st);
 }
 
 template <int KC>
 static hipError_t launch_tiled_kc(const EdgeDev& e, long long max_entries, hipStream_t st) {
-    // the largest tile that still yields about one block per compute unit
     auto blocks = [&](int bm, int bn) { return ((max_entries + bm - 1) / bm) * (e.Cout / bn); };
-    const long long want = 224;
-    if (e.Cout % 128 == 0) {
-        if (blocks(128, 128) >= want) return launch_tiled<2, 2, 2, 2, KC>(e, max_entries, st);
-        if (blocks(64, 128) >= want) return launch_tiled<2, 2, 1, 2, KC>(e, max_entries, st);
+    int tile = g_tile;
+    if (tile == 0) {
+        // the largest tile that still yields about one block per compute unit
+        const long long want = 224;
+        if (e.Cout % 128 == 0 && blocks(128, 128) >= want) tile = 4;
+        else if (e.Cout % 128 == 0 && blocks(64, 128) >= want) tile = 5;
+        else if (e.Cout % 64 == 0) tile = blocks(256, 64) >= want ? 1 : blocks(128, 64) >= want ? 2 : 3;
+        else tile = 6;
     }
-    if (e.Cout % 64 == 0) {
-        if (blocks(256, 64) >= want) return launch_tiled<4, 1, 2, 2, KC>(e, max_entries, st);
-        if (blocks(128, 64) >= want) return launch_tiled<2, 2, 2, 1, KC>(e, max_entries, st);
-        return launch_tiled<2, 2, 1, 1, KC>(e, max_entries, st);
+    switch (tile) {
+        case 1: if (e.Cout % 64 == 0) return launch_tiled_p<4, 1, 2, 2, KC>(e, max_entries, st); break;    // 256 x 64
+        case 2: if (e.Cout % 64 == 0) return launch_tiled_p<2, 2, 2, 1, KC>(e, max_entries, st); break;    // 128 x 64
+        case 3: if (e.Cout % 64 == 0) return launch_tiled_p<2, 2, 1, 1, KC>(e, max_entries, st); break;    //  64 x 64
+        case 4: if (e.Cout % 128 == 0) return launch_tiled_p<2, 2, 2, 2, KC>(e, max_entries, st); break;   // 128 x 128
+        case 5: if (e.Cout % 128 == 0) return launch_tiled_p<2, 2, 1, 2, KC>(e, max_entries, st); break;   //  64 x 128
+        case 7: if (e.Cout % 128 == 0) return launch_tiled_p<4, 1, 1, 4, KC>(e, max_entries, st); break;   // 128 x 128, wave 32 x 128
+        case 8: if (e.Cout % 256 == 0) return launch_tiled_p<2, 2, 2, 4, KC>(e, max_entries, st); break;   // 128 x 256, wave 64 x 128
+        case 9: if (e.Cout % 256 == 0) return launch_tiled_p<1, 4, 2, 2, KC>(e, max_entries, st); break;   //  64 x 256, wave 64 x 64
+        case 10: if (e.Cout % 256 == 0) return launch_tiled_p<2, 2, 1, 4, KC>(e, max_entries, st); break;  //  64 x 256, wave 32 x 128
+        default: break;
     }
-    return launch_tiled<4, 1, 1, 1, KC>(e, max_entries, st);        // Cout % 32 == 0
+    return launch_tiled_p<4, 1, 1, 1, KC>(e, max_entries, st);                                             // 128 x 32
 }
 
 template <typename T>
@@ -553,7 +721,7 @@ static hipError_t launch_ldsw(const EdgeDev& e, long long max_entries, hipStream
     const long long nseg = (max_entries + kSegPixels - 1) / kSegPixels;
     const long long tps = (kSegPixels + ppb - 1) / ppb;
     // weights are staged once per block: keep the blocks few and persistent
-    unsigned g = cap_blocks(nseg * tps, smem > 32768 ? 256 : 1024);
+    unsigned g = cap_blocks(nseg * tps, smem > 32768 ? 256 : 768);
     kern<<<dim3(g), dim3(256), smem, st>>>(e, groups, ppb);
     return hipGetLastError();
 }
@@ -561,15 +729,20 @@ static hipError_t launch_ldsw(const EdgeDev& e, long long max_entries, hipStream
 hipError_t launch_conv(const EdgeDev& e, int dtype, int conv_path, hipStream_t st, int* cls) {
     const long long max_entries = e.up ? (long long)e.sH * e.sW : (long long)e.Hp * e.Wp;
     const long long nseg = (max_entries + kSegPixels - 1) / kSegPixels;
+    if (e.k < 0) {                                         // no operator: source compaction only
+        *cls = kClsLists;
+        k_compact_source<<<dim3(cap_blocks(((long long)e.sH * e.sW + kSegPixels - 1) / kSegPixels, 4096)), dim3(256), 0, st>>>(e);
+        return hipGetLastError();
+    }
     if (e.k == 0) {
         *cls = kClsIdentity;
-        const long long px = (long long)e.sH * e.sW;
+        const unsigned g = cap_blocks(nseg, 4096);
         if (dtype == MDCNN_F16) {
-            if (e.Cin % 8 == 0) k_identity<f16, 8><<<dim3(cap_blocks((px * (e.Cin / 8) + 255) / 256, 8192)), dim3(256), 0, st>>>(e);
-            else k_identity<f16, 1><<<dim3(cap_blocks((px * e.Cin + 255) / 256, 8192)), dim3(256), 0, st>>>(e);
+            if (e.Cin % 8 == 0) k_identity<f16, 8><<<dim3(g, (e.Cin / 8 + 7) / 8), dim3(256), 0, st>>>(e);
+            else k_identity<f16, 1><<<dim3(g, (e.Cin + 7) / 8), dim3(256), 0, st>>>(e);
         } else {
-            if (e.Cin % 4 == 0) k_identity<float, 4><<<dim3(cap_blocks((px * (e.Cin / 4) + 255) / 256, 8192)), dim3(256), 0, st>>>(e);
-            else k_identity<float, 1><<<dim3(cap_blocks((px * e.Cin + 255) / 256, 8192)), dim3(256), 0, st>>>(e);
+            if (e.Cin % 4 == 0) k_identity<float, 4><<<dim3(g, (e.Cin / 4 + 7) / 8), dim3(256), 0, st>>>(e);
+            else k_identity<float, 1><<<dim3(g, (e.Cin + 7) / 8), dim3(256), 0, st>>>(e);
         }
         return hipGetLastError();
     }

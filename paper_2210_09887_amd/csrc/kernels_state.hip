@@ -1,6 +1,6 @@
 // Memory-bound kernels of the hot path: dynamic initialisation of unveiled
-// pixels, delta + truncation + mask (input and inner sites), stream compaction
-// of the mask, compute lists of the padded convolution, view-ordered readout.
+// pixels, delta + truncation + mask (input and inner sites), view-ordered
+// readout.  (Compaction lives with its consumer, the convolution kernels.)
 // gfx950 only: 64-wide wavefronts, ballot/popcount compaction, 16-byte accesses.
 #include "mdcnn_internal.h"
 
@@ -76,6 +76,8 @@ template <typename T, int VEC>
 __device__ __forceinline__ void fill_items(const FillJob& j, unsigned lb) {
     const int chunks = j.C / VEC;
     const long long total = (long long)(j.nP + j.nA) * chunks;
+    // a full reset (empty kept rectangles) needs no ring arithmetic
+    const bool full = j.py0 == j.py1 && j.px0 == j.px1 && j.ay0 == j.ay1 && j.ax0 == j.ax1 && j.py0 == 0 && j.ay0 == 0;
     const long long begin = (long long)lb * kFillItemsPerBlock;
     long long end = begin + kFillItemsPerBlock;
     if (end > total) end = total;
@@ -83,10 +85,14 @@ __device__ __forceinline__ void fill_items(const FillJob& j, unsigned lb) {
         const int pix = (int)(idx / chunks);
         const int c0 = (int)(idx - (long long)pix * chunks) * VEC;
         if (pix < j.nP) {
-            int wy, wx;
-            decode_new(j.Wp, j.Hp, j.py0, j.py1, j.px0, j.px1, pix, wy, wx);
-            const int py = wrap(j.p_oy + wy, j.Hp), px = wrap(j.p_ox + wx, j.Wp);
-            T* p = (T*)j.P + ((size_t)py * j.Wp + px) * j.C + c0;
+            size_t poff = (size_t)pix;                     // everything is new: any order covers the ring
+            if (!full) {
+                int wy, wx;
+                decode_new(j.Wp, j.Hp, j.py0, j.py1, j.px0, j.px1, pix, wy, wx);
+                const int py = wrap(j.p_oy + wy, j.Hp), px = wrap(j.p_ox + wx, j.Wp);
+                poff = (size_t)py * j.Wp + px;
+            }
+            T* p = (T*)j.P + poff * j.C + c0;
             if constexpr (VEC > 1) {
                 float v[VEC];
 #pragma unroll
@@ -96,10 +102,17 @@ __device__ __forceinline__ void fill_items(const FillJob& j, unsigned lb) {
                 p[0] = (T)(j.bias ? j.bias[c0] : 0.f);
             }
         } else {
-            int vy, vx;
-            decode_new(j.W, j.H, j.ay0, j.ay1, j.ax0, j.ax1, pix - j.nP, vy, vx);
-            const int ay = wrap(j.a_oy + vy, j.H), ax = wrap(j.a_ox + vx, j.W);
-            T* p = (T*)j.A + ((size_t)ay * j.W + ax) * j.C + c0;
+            const int ap = pix - j.nP;
+            size_t aoff = (size_t)ap;
+            int vlin = ap;                                 // view-linear index for the flag
+            if (!full) {
+                int vy, vx;
+                decode_new(j.W, j.H, j.ay0, j.ay1, j.ax0, j.ax1, ap, vy, vx);
+                const int ay = wrap(j.a_oy + vy, j.H), ax = wrap(j.a_ox + vx, j.W);
+                aoff = (size_t)ay * j.W + ax;
+                vlin = vy * j.W + vx;
+            }
+            T* p = (T*)j.A + aoff * j.C + c0;
             if constexpr (VEC > 1) {
                 float v[VEC];
 #pragma unroll
@@ -108,7 +121,7 @@ __device__ __forceinline__ void fill_items(const FillJob& j, unsigned lb) {
             } else {
                 p[0] = (T)0.f;
             }
-            if (c0 == 0) j.flags[vy * j.W + vx] = (uint8_t)kFlagN;
+            if (c0 == 0) j.flags[vlin] = (uint8_t)kFlagN;
         }
     }
 }
@@ -308,131 +321,6 @@ hipError_t launch_step1(const SiteDev& s, const void* frame, const uint8_t* forc
 }
 
 // ---------------------------------------------------------------------------
-// Compaction.  A segment is kSegPixels consecutive linear indices handled by one
-// 256-thread block (4 per thread, ascending), compacted into the front of the
-// segment's slice of the list; the per-segment count goes to cnt[segment].  The
-// concatenation of the segments is the ascending list.  Blocks are independent:
-// no scan across blocks, no waiting, no host round trip; consumers walk
-// (segment, offset) pairs.
-// ---------------------------------------------------------------------------
-// exclusive prefix of v over the 256 threads of the block; total in *tot
-__device__ __forceinline__ int block_excl_scan(int v, int* sh, int* tot) {
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    int inc = v;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        int t = __shfl_up(inc, off);
-        if (lane >= off) inc += t;
-    }
-    if (lane == 63) sh[w] = inc;
-    __syncthreads();
-    int base = 0;
-    for (int i = 0; i < w; ++i) base += sh[i];
-    *tot = sh[0] + sh[1] + sh[2] + sh[3];
-    return base + inc - v;
-}
-
-// does the footprint of window pixel widx of the destination hold an updated source pixel?
-__device__ __forceinline__ bool covered(const EdgeDev& e, int widx) {
-    const int wy = widx / e.Wp, wx = widx - wy * e.Wp;
-    const int oy = wy - e.by0, ox = wx - e.bx0;
-    if (e.k == 0) {
-        if (oy < 0 || oy >= e.sH || ox < 0 || ox >= e.sW) return false;
-        return e.sflags[oy * e.sW + ox] & kFlagM;
-    }
-    const int y0 = oy * e.stride - e.pad, x0 = ox * e.stride - e.pad;
-    int any = 0;
-    for (int jy = 0; jy < e.k; ++jy) {
-        const int iy = y0 + jy;
-        const bool yok = iy >= 0 && iy < e.sH;
-        for (int jx = 0; jx < e.k; ++jx) {
-            const int ix = x0 + jx;
-            const bool ok = yok && ix >= 0 && ix < e.sW;
-            any |= ok ? e.sflags[iy * e.sW + ix] : 0;      // independent loads, no early exit
-        }
-    }
-    return any & kFlagM;
-}
-
-// blockIdx.y == 0: compact the update mask of site s into L.
-// blockIdx.y >= 1: compute list of edge y-1 (destination padded-window indices).
-__global__ __launch_bounds__(256) void k_lists(SiteDev s, EdgeBatch eb, int do_compact) {
-    __shared__ int sh[4];
-    const int tid = threadIdx.x;
-    const int seg = blockIdx.x;
-    const int p0 = seg * kSegPixels + tid * 4;
-    if (blockIdx.y == 0) {
-        const int HW = s.H * s.W;
-        if (!do_compact || seg * kSegPixels >= HW) return;
-        int bits = 0, ncand = 0;
-        if (p0 + 3 < HW) {
-            const unsigned f4 = *reinterpret_cast<const unsigned*>(s.flags + p0);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) bits |= ((f4 >> (8 * j + 2)) & 1u) << j;      // kFlagM == 4
-            ncand = __popc(f4 & 0x08080808u);                                          // kFlagC == 8
-        } else {
-            for (int j = 0; j < 4; ++j)
-                if (p0 + j < HW) {
-                    const int f = s.flags[p0 + j];
-                    if (f & kFlagM) bits |= 1 << j;
-                    ncand += (f >> 3) & 1;
-                }
-        }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) ncand += __shfl_xor(ncand, o);
-        __shared__ int scand[4];
-        if ((tid & 63) == 0) scand[tid >> 6] = ncand;
-        int tot;
-        int off = seg * kSegPixels + block_excl_scan(__popc(bits), sh, &tot);
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (bits & (1 << j)) s.list[off++] = p0 + j;
-        if (tid == 0) {                                  // scand is complete: the scan has a barrier
-            s.lcnt[seg] = tot;
-            const int c = scand[0] + scand[1] + scand[2] + scand[3];
-            unsigned long long* acc = reinterpret_cast<unsigned long long*>(s.counters);
-            if (tot) { atomicAdd(&s.counters[kCntUpdated], tot); atomicAdd(acc + kAccUpdated, (unsigned long long)tot); }
-            if (c) { atomicAdd(&s.counters[kCntCandidates], c); atomicAdd(acc + kAccCandidates, (unsigned long long)c); }
-        }
-    } else {
-        const int ei = blockIdx.y - 1;
-        if (ei >= eb.n) return;
-        const EdgeDev& e = eb.e[ei];
-        const int NW = e.Hp * e.Wp;
-        if (e.up || seg * kSegPixels >= NW) return;
-        int bits = 0;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (p0 + j < NW && covered(e, p0 + j)) bits |= 1 << j;
-        int tot;
-        int off = seg * kSegPixels + block_excl_scan(__popc(bits), sh, &tot);
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (bits & (1 << j)) e.clist[off++] = p0 + j;
-        if (tid == 0) {
-            e.ccnt[seg] = tot;
-            if (tot) atomicAdd(reinterpret_cast<unsigned long long*>(e.dcounters) + kAccCompute, (unsigned long long)tot);
-        }
-    }
-}
-
-// One batch of edges of site s; the first batch of a site also compacts L.
-hipError_t launch_lists(const SiteDev& s, const EdgeBatch& eb, bool do_compact, hipStream_t st) {
-    const int HW = s.H * s.W;
-    int gx = do_compact ? (HW + kSegPixels - 1) / kSegPixels : 0;
-    int ny = 1;
-    for (int i = 0; i < eb.n; ++i) {
-        if (eb.e[i].up) continue;
-        ny = 2 + i;
-        const int n = (eb.e[i].Hp * eb.e[i].Wp + kSegPixels - 1) / kSegPixels;
-        if (n > gx) gx = n;
-    }
-    if (gx == 0) return hipSuccess;
-    k_lists<<<dim3(gx, ny), dim3(256), 0, st>>>(s, eb, do_compact ? 1 : 0);
-    return hipGetLastError();
-}
-
-// ---------------------------------------------------------------------------
 // View-ordered access (readout of OUTPUT sites is on the per-frame path).
 // ---------------------------------------------------------------------------
 template <typename T, int VEC>
@@ -505,16 +393,21 @@ __global__ __launch_bounds__(256) void k_read_list(const int* __restrict__ list,
 }
 
 __global__ __launch_bounds__(256) void k_read_stats(SiteDev s, int* __restrict__ dst) {
-    const int i = threadIdx.x;
-    if (i < 18) dst[i] = s.counters[i];
-    if (i == 2) {
-        int c = 0;
-        if (s.ccnt) {
-            const int nseg = (s.Hp * s.Wp + kSegPixels - 1) / kSegPixels;
-            for (int g = 0; g < nseg; ++g) c += s.ccnt[g];
-        }
-        dst[2] = c;
+    if (threadIdx.x != 0) return;
+    for (int i = 0; i < 18; ++i) dst[i] = s.counters[i];
+    int c = 0;
+    if (s.ccnt) {
+        const int nseg = (s.Hp * s.Wp + kSegPixels - 1) / kSegPixels;
+        for (int g = 0; g < nseg; ++g) c += s.ccnt[g];
     }
+    dst[2] = c;
+    // the multiply-accumulate sums are kept as 8 partials each
+    const unsigned long long* acc = reinterpret_cast<const unsigned long long*>(s.counters);
+    unsigned long long m = 0, p = 0;
+    for (int j = 0; j < 8; ++j) { m += acc[kAccMacsSpread + j]; p += acc[kAccMacsSpread + 8 + j]; }
+    unsigned long long* d64 = reinterpret_cast<unsigned long long*>(dst);
+    d64[kAccMacs] = m;
+    d64[kAccMacsPlain] = p;
 }
 
 __global__ __launch_bounds__(256) void k_copy_bytes(const uint8_t* __restrict__ src, uint8_t* __restrict__ dst, int n) {

@@ -173,7 +173,7 @@ mdcnn_status validate_edge(const mdcnn_buffer* in, const mdcnn_buffer* out, cons
 
 EdgeDev make_edge(const mdcnn_buffer* in, const mdcnn_buffer* out, const mdcnn_conv_desc& c) {
     EdgeDev e{};
-    e.delta = in->dev.delta; e.sflags = in->dev.flags; e.slist = in->dev.list; e.slcnt = in->dev.lcnt;
+    e.delta = in->dev.delta; e.sflags = in->dev.flags; e.pub_list = nullptr; e.pub_lcnt = nullptr; e.scounters = in->dev.counters;
     e.sH = in->d.H; e.sW = in->d.W; e.Cin = c.Cin;
     e.P = out->dev.P; e.dflags = out->d.kind == MDCNN_SITE_OUTPUT ? nullptr : out->dev.flags;
     e.clist = out->dev.clist; e.ccnt = out->dev.ccnt; e.dcounters = out->dev.counters;
@@ -207,38 +207,37 @@ mdcnn_status do_forward(mdcnn_buffer* in, const void* frame, const uint8_t* forc
                         mdcnn_buffer* const* outs, int n_edges, hipStream_t st) {
     hipError_t err = timed(kClsStep1, st, [&] { return launch_step1(in->dev, frame, forced, st); });
     if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "step-1 launch: %s", hipGetErrorString(err));
-    int i = 0;
-    bool first = true;
-    do {
-        // one batch: up to kMaxEdgesPerLaunch edges with pairwise distinct destinations
-        EdgeBatch eb{};
-        int j = i;
-        for (; j < n_edges && eb.n < kMaxEdgesPerLaunch; ++j) {
-            bool dup = false;
-            for (int q = i; q < j; ++q) dup |= outs[q] == outs[j];
-            if (dup) break;
-            eb.e[eb.n++] = make_edge(in, outs[j], edges[j]);
+    auto launch_edge = [&](EdgeDev& e, int idx) -> mdcnn_status {
+        int cls = kClsConvPlain;
+        TimedLaunch t{0, nullptr, nullptr};
+        if (g_profile) {              // the class is known only after dispatch: record around, file under it
+            t.start = take_event();
+            t.stop = take_event();
+            if (!t.start || !t.stop) return fail(MDCNN_ERR_HIP, "cannot create profiling events");
+            (void)hipEventRecord(t.start, st);
         }
-        err = timed(kClsLists, st, [&] { return launch_lists(in->dev, eb, first, st); });
-        if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "list launch: %s", hipGetErrorString(err));
-        for (int q = 0; q < eb.n; ++q) {
-            int cls = kClsConvPlain;
-            if (g_profile) {          // the class is known only after dispatch: record around, file under it
-                TimedLaunch t{0, take_event(), take_event()};
-                if (!t.start || !t.stop) return fail(MDCNN_ERR_HIP, "cannot create profiling events");
-                (void)hipEventRecord(t.start, st);
-                err = launch_conv(eb.e[q], in->d.dtype, g_conv_path, st, &cls);
-                (void)hipEventRecord(t.stop, st);
-                t.cls = cls;
-                g_timed.push_back(t);
-            } else {
-                err = launch_conv(eb.e[q], in->d.dtype, g_conv_path, st, &cls);
-            }
-            if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "conv launch (edge %d): %s", i + q, hipGetErrorString(err));
+        err = launch_conv(e, in->d.dtype, g_conv_path, st, &cls);
+        if (g_profile) {
+            (void)hipEventRecord(t.stop, st);
+            t.cls = cls;
+            g_timed.push_back(t);
         }
-        first = false;
-        i = j;
-    } while (i < n_edges);
+        if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "conv launch (edge %d): %s", idx, hipGetErrorString(err));
+        return MDCNN_OK;
+    };
+    if (n_edges == 0) {
+        EdgeDev e{};
+        e.sflags = in->dev.flags; e.sH = in->d.H; e.sW = in->d.W;
+        e.pub_list = in->dev.list; e.pub_lcnt = in->dev.lcnt; e.scounters = in->dev.counters;
+        e.k = -1;
+        return launch_edge(e, -1);
+    }
+    for (int i = 0; i < n_edges; ++i) {
+        EdgeDev e = make_edge(in, outs[i], edges[i]);
+        if (i == 0) { e.pub_list = in->dev.list; e.pub_lcnt = in->dev.lcnt; }
+        mdcnn_status rc = launch_edge(e, i);
+        if (rc) return rc;
+    }
     return MDCNN_OK;
 }
 
@@ -252,6 +251,9 @@ const char* mdcnn_version(void) { return "mdcnn 0.1 (gfx950)"; }
 mdcnn_status mdcnn_set_option(int option, int value) {
     if (option == MDCNN_OPT_CONV_PATH && value >= 0 && value <= 2) { g_conv_path = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_PROFILE && (value == 0 || value == 1)) { g_profile = value; return MDCNN_OK; }
+    if (option == MDCNN_OPT_CONV_TILE && value >= 0 && value <= 10) { g_tile = value; return MDCNN_OK; }
+    if (option == MDCNN_OPT_CONV_PIPE && value >= 0 && value <= 2) { g_pipe = value; return MDCNN_OK; }
+    if (option == MDCNN_OPT_CONV_XCD && (value == 0 || value == 1)) { g_xcd = value; return MDCNN_OK; }
     return fail(MDCNN_ERR_SIZE, "unknown option %d / value %d", option, value);
 }
 

@@ -25,12 +25,15 @@ constexpr int kAccCandidates = 5;   // sum of candidate counts
 constexpr int kAccMacs = 6;         // multiply-accumulates of the MFMA kernels into this site (valid taps x Cin x Cout)
 constexpr int kAccCompute = 7;      // sum of compute-list lengths of edges into this site
 constexpr int kAccMacsPlain = 8;    // multiply-accumulates of the plain-FMA kernels into this site
+// The two multiply-accumulate sums are kept as 8 partial sums each (slot + 8 * {1, 2} + block % 8)
+// so that the statistics atomics of a launch do not all hit one address.
+constexpr int kAccMacsSpread = 16;  // [16, 24): MFMA partials, [24, 32): plain partials
 constexpr int kNumCounters = 64;
 
 // Lists are compacted per segment of kSegPixels consecutive linear indices:
 // entries of segment g sit at list[g * kSegPixels ...], their number in cnt[g].
 // Concatenating the segments in order gives the ascending list.
-constexpr int kSegPixels = 1024;
+constexpr int kSegPixels = 256;      // = threads per block: one index per thread
 
 // Device-side view of one site, passed to kernels by value.
 struct SiteDev {
@@ -85,8 +88,9 @@ struct EdgeDev {
     // source
     const void* delta;
     const uint8_t* sflags;
-    const int* slist;         // L of the source (segment-local)
-    const int* slcnt;
+    int* pub_list;            // non-null on the one edge of a forward call that also compacts
+    int* pub_lcnt;            //   the source's update mask into its list L (segment-local)
+    int* scounters;
     int sH, sW, Cin;
     // destination
     void* P;
@@ -102,18 +106,12 @@ struct EdgeDev {
 
 enum KernelClass { kClsShift = 0, kClsStep1, kClsLists, kClsConvMfma, kClsConvPlain, kClsIdentity, kClsReadout, kNumClasses };
 
-constexpr int kMaxEdgesPerLaunch = 8;
-struct EdgeBatch {
-    EdgeDev e[kMaxEdgesPerLaunch];
-    int n;
-};
-
 hipError_t launch_shift_fill(const FillBatch& fb, hipStream_t st);
 hipError_t launch_step1(const SiteDev& s, const void* frame, const uint8_t* forced, hipStream_t st);
-// compaction of the update mask of s (do_compact) and the compute lists of the edges in eb
-hipError_t launch_lists(const SiteDev& s, const EdgeBatch& eb, bool do_compact, hipStream_t st);
+// e.k < 0: no operator, only the compaction of the source's update mask.
 // returns the kernel class that was launched in *cls
 hipError_t launch_conv(const EdgeDev& e, int dtype, int conv_path, hipStream_t st, int* cls);
+extern int g_tile, g_pipe, g_xcd;   // convolution tuning knobs
 hipError_t launch_read_view(const SiteDev& s, int what, void* dst, hipStream_t st);
 hipError_t launch_write_view(const SiteDev& s, int what, const void* src, hipStream_t st);
 
