@@ -186,7 +186,8 @@ typedef enum {
     MDCNN_OPT_PROFILE = 1,   /* 1: bracket every kernel launch with a pair of HIP events  */
     MDCNN_OPT_CONV_TILE = 2, /* tuning: 0 auto, 1..10 force a tile shape of the MFMA kernel */
     MDCNN_OPT_CONV_PIPE = 3, /* tuning: 0 auto, 1 / 2 prefetch depth of the MFMA kernel    */
-    MDCNN_OPT_CONV_XCD = 4   /* tuning: 1 (default) tie cout tiles to XCDs, 0 plain order  */
+    MDCNN_OPT_CONV_XCD = 4,  /* tuning: 1 (default) tie cout tiles to XCDs, 0 plain order  */
+    MDCNN_OPT_CONV_KC = 5    /* tuning: 0 auto, 64 cap the K step at 64 channels           */
 } mdcnn_option;
 mdcnn_status mdcnn_set_option(int option, int value);
 

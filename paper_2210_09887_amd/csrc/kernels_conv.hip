@@ -265,33 +265,51 @@ __global__ __launch_bounds__(256) void k_conv_mfma_tiled(EdgeDev e, int NT, int 
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+        // Per-thread chunk descriptors of this tile: which slab rows this thread
+        // moves, their source offsets (elements) and tap masks.  Per step only a
+        // block-uniform offset is added, and rows whose tap misses the update mask
+        // are zeroed with selects (no divergent branches in the K loop).
+        long long offB[NB], offA[NA];
+        unsigned vmB[NB];
+        int ldsB[NB], ldsA[NA];
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int ch = tid + 256 * i;
+            const int row = (ch / CPR) % BM, cc = ch % CPR;          // % BM: keep partial last rounds in range
+            offB[i] = (long long)s_base[row] * e.Cin + cc * 8;
+            vmB[i] = (BM * CPR) % 256 == 0 || ch < BM * CPR ? s_vm[row] : 0u;
+            ldsB[i] = row * LDK + cc * 8;
+        }
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            const int ch = tid + 256 * i;
+            const int row = (ch / CPR) % BN, cc = ch % CPR;
+            offA[i] = (long long)(n0 + row) * e.Cin + cc * 8;
+            ldsA[i] = row * LDK + cc * 8;
+        }
+        const long long tap_stride_w = (long long)e.Cout * e.Cin;
+
         // the load iterator runs PIPE steps ahead of the multiplication
         unsigned ld_rem = tilemask;
         int ld_tap = ld_rem ? __ffs(ld_rem) - 1 : -1, ld_c0 = 0;
         f16x8 rb[PIPE][NB], ra[PIPE][NA];
-        auto load_next = [&](auto stage) {
+        bool okB[PIPE][NB];                                  // zeroing happens when the stage is stored,
+        auto load_next = [&](auto stage) {                   // so that nothing waits on a load just issued
             constexpr int S = decltype(stage)::value;
             if (ld_tap < 0) return;
             const int jy = ld_tap / e.k, jx = ld_tap - jy * e.k;
-            const int toff = jy * e.sW + jx;
+            const long long stepB = (long long)(jy * e.sW + jx) * e.Cin + ld_c0;     // block-uniform
+            const long long stepA = ld_tap * tap_stride_w + ld_c0;
 #pragma unroll
             for (int i = 0; i < NB; ++i) {
-                const int ch = tid + 256 * i;
-                const int row = ch / CPR, cc = ch - row * CPR;
-                f16x8 v;
-#pragma unroll
-                for (int q = 0; q < 8; ++q) v[q] = (f16)0.f;
-                if (ch < BM * CPR && ((s_vm[row] >> ld_tap) & 1u))
-                    v = *reinterpret_cast<const f16x8*>(delta + (size_t)(s_base[row] + toff) * e.Cin + ld_c0 + cc * 8);
-                rb[S][i] = v;
+                const bool valid = (vmB[i] >> ld_tap) & 1u;
+                const f16* src = valid ? delta + offB[i] + stepB : delta;           // always a readable address
+                rb[S][i] = *reinterpret_cast<const f16x8*>(src);
+                okB[S][i] = valid;
             }
 #pragma unroll
-            for (int i = 0; i < NA; ++i) {
-                const int ch = tid + 256 * i;
-                const int row = ch / CPR, cc = ch - row * CPR;
-                if (ch < BN * CPR)
-                    ra[S][i] = *reinterpret_cast<const f16x8*>(w + ((size_t)(ld_tap * e.Cout + n0 + row)) * e.Cin + ld_c0 + cc * 8);
-            }
+            for (int i = 0; i < NA; ++i)
+                ra[S][i] = *reinterpret_cast<const f16x8*>(w + offA[i] + stepA);
             ld_c0 += KC;
             if (ld_c0 >= e.Cin) { ld_c0 = 0; ld_rem &= ld_rem - 1; ld_tap = ld_rem ? __ffs(ld_rem) - 1 : -1; }
         };
@@ -301,36 +319,35 @@ __global__ __launch_bounds__(256) void k_conv_mfma_tiled(EdgeDev e, int NT, int 
             f16* sA = sB + BM * LDK;
 #pragma unroll
             for (int i = 0; i < NB; ++i) {
-                const int ch = tid + 256 * i;
-                const int row = ch / CPR, cc = ch - row * CPR;
-                if (ch < BM * CPR) *reinterpret_cast<f16x8*>(sB + row * LDK + cc * 8) = rb[S][i];
+                f16x8 v = rb[S][i];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) v[q] = okB[S][i] ? v[q] : (f16)0.f;
+                if ((BM * CPR) % 256 == 0 || tid + 256 * i < BM * CPR) *reinterpret_cast<f16x8*>(sB + ldsB[i]) = v;
             }
 #pragma unroll
-            for (int i = 0; i < NA; ++i) {
-                const int ch = tid + 256 * i;
-                const int row = ch / CPR, cc = ch - row * CPR;
-                if (ch < BN * CPR) *reinterpret_cast<f16x8*>(sA + row * LDK + cc * 8) = ra[S][i];
-            }
+            for (int i = 0; i < NA; ++i)
+                if ((BN * CPR) % 256 == 0 || tid + 256 * i < BN * CPR) *reinterpret_cast<f16x8*>(sA + ldsA[i]) = ra[S][i];
         };
         auto multiply = [&](auto stage) {
             constexpr int S = decltype(stage)::value;
-            const f16* sB = slab + S * Cfg::STAGE_HALVES;
-            const f16* sA = sB + BM * LDK;
+            constexpr int KK = KC / 16;
+            const f16* sB = slab + S * Cfg::STAGE_HALVES + (wm * TM * 32 + r32) * LDK + kh * 8;
+            const f16* sA = slab + S * Cfg::STAGE_HALVES + BM * LDK + (wn * TN * 32 + r32) * LDK + kh * 8;
+            f16x8 fb[KK][TM], fa[KK][TN];                    // all fragments of the step, then the MFMAs
 #pragma unroll
-            for (int kk = 0; kk < KC / 16; ++kk) {
-                f16x8 fb[TM], fa[TN];
+            for (int kk = 0; kk < KK; ++kk) {
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
-                    fb[i] = *reinterpret_cast<const f16x8*>(sB + ((wm * TM + i) * 32 + r32) * LDK + kk * 16 + kh * 8);
+                for (int i = 0; i < TM; ++i) fb[kk][i] = *reinterpret_cast<const f16x8*>(sB + i * 32 * LDK + kk * 16);
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    fa[j] = *reinterpret_cast<const f16x8*>(sA + ((wn * TN + j) * 32 + r32) * LDK + kk * 16 + kh * 8);
+                for (int j = 0; j < TN; ++j) fa[kk][j] = *reinterpret_cast<const f16x8*>(sA + j * 32 * LDK + kk * 16);
+            }
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk)
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[j], fb[i], acc[i][j], 0, 0, 0);
-            }
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[kk][j], fb[kk][i], acc[i][j], 0, 0, 0);
         };
         using S0 = std::integral_constant<int, 0>;
         using S1 = std::integral_constant<int, PIPE - 1>;
@@ -648,7 +665,7 @@ static unsigned cap_blocks(long long b, long long cap) {
 }
 
 // Tuning knobs (mdcnn_set_option): forced tile shape, pipeline depth, XCD mapping.
-int g_tile = 0, g_pipe = 0, g_xcd = 1;
+int g_tile = 0, g_pipe = 0, g_xcd = 1, g_kc = 0;
 
 template <int WM, int WN, int TM, int TN, int KC, int PIPE>
 static hipError_t launch_tiled(const EdgeDev& e, long long max_entries, hipStream_t st) {
@@ -673,9 +690,9 @@ static hipError_t launch_tiled(const EdgeDev& e, long long max_entries, hipStrea
 
 template <int WM, int WN, int TM, int TN, int KC>
 static hipError_t launch_tiled_p(const EdgeDev& e, long long max_entries, hipStream_t st) {
-    // deep prefetch pays when the K loop is long
-    const int steps = e.k * e.k * (e.Cin / KC);
-    const bool deep = g_pipe ? g_pipe == 2 : steps >= 16;
+    // measured on MI355X: with L2 latencies of ~200 cycles one step of prefetch is
+    // enough; the second register stage only costs occupancy
+    const bool deep = g_pipe == 2;
     return deep ? launch_tiled<WM, WN, TM, TN, KC, 2>(e, max_entries, st)
                 : launch_tiled<WM, WN, TM, TN, KC, 1>(e, max_entries, st);
 }
@@ -750,6 +767,7 @@ hipError_t launch_conv(const EdgeDev& e, int dtype, int conv_path, hipStream_t s
     const bool mfma_ok = dtype == MDCNN_F16 && conv_path != 1 && e.Cin % 16 == 0 && e.Cout % 32 == 0;
     if (mfma_ok && conv_path == 0 && e.Cin % 32 == 0) {
         *cls = kClsConvMfma;
+        if (e.Cin % 128 == 0 && g_kc != 64) return launch_tiled_kc<128>(e, max_entries, st);
         return e.Cin % 64 == 0 ? launch_tiled_kc<64>(e, max_entries, st) : launch_tiled_kc<32>(e, max_entries, st);
     }
     if (mfma_ok) {

@@ -111,7 +111,7 @@ hipError_t launch_step1(const SiteDev& s, const void* frame, const uint8_t* forc
 // e.k < 0: no operator, only the compaction of the source's update mask.
 // returns the kernel class that was launched in *cls
 hipError_t launch_conv(const EdgeDev& e, int dtype, int conv_path, hipStream_t st, int* cls);
-extern int g_tile, g_pipe, g_xcd;   // convolution tuning knobs
+extern int g_tile, g_pipe, g_xcd, g_kc;   // convolution tuning knobs
 hipError_t launch_read_view(const SiteDev& s, int what, void* dst, hipStream_t st);
 hipError_t launch_write_view(const SiteDev& s, int what, const void* src, hipStream_t st);
 
