@@ -134,9 +134,9 @@ __device__ __forceinline__ int tile_prologue(const EdgeDev& e, int seg, int firs
         if (touch) mark_touched(e, wy, wx);
     }
     if (publish && has) e.clist[seg * kSegPixels + off] = p;
-    if (publish && tid == 0) {
+    if (publish && tid == 0) {                             // single writer per segment: no atomics
         e.ccnt[seg] = tot;
-        if (tot) atomicAdd(reinterpret_cast<unsigned long long*>(e.dcounters) + kAccCompute, (unsigned long long)tot);
+        e.cacc[seg] += (unsigned long long)tot;
     }
     unsigned orm = mine ? vm : 0u;
     int taps = mine ? __popc(vm) : 0;
@@ -165,12 +165,12 @@ __device__ __forceinline__ void carry_source_compaction(const EdgeDev& e, int* s
         int off = __popcll(bm & ((1ull << lane) - 1ull));
         for (int i = 0; i < wave; ++i) off += sh[i];
         if (f & kFlagM) e.pub_list[seg * kSegPixels + off] = p;
-        if (tid == 0) {
+        if (tid == 0) {                                    // single writer per segment: no atomics
             const int tot = sh[0] + sh[1] + sh[2] + sh[3], c = sh[4] + sh[5] + sh[6] + sh[7];
-            e.pub_lcnt[seg] = tot;
-            unsigned long long* acc = reinterpret_cast<unsigned long long*>(e.scounters);
-            if (tot) { atomicAdd(&e.scounters[kCntUpdated], tot); atomicAdd(acc + kAccUpdated, (unsigned long long)tot); }
-            if (c) { atomicAdd(&e.scounters[kCntCandidates], c); atomicAdd(acc + kAccCandidates, (unsigned long long)c); }
+            e.pub_lcnt[2 * seg] = tot;
+            e.pub_lcnt[2 * seg + 1] = c;
+            e.pub_lacc[2 * seg] += (unsigned long long)tot;
+            e.pub_lacc[2 * seg + 1] += (unsigned long long)c;
         }
     }
     __syncthreads();
@@ -564,6 +564,81 @@ __global__ __launch_bounds__(256) void k_conv_ldsw(EdgeDev e, int groups, int pp
 }
 
 // ---------------------------------------------------------------------------
+// Stem-type layers (few input channels, e.g. RGB): compile-time footprint
+// KK x KK x CIN.  A thread owns one list entry and CPT couts; all of its
+// KK*KK*CIN inputs are fetched up front (independent loads), the weights are
+// broadcast from LDS ([tap][cin][cout], fp32).
+// ---------------------------------------------------------------------------
+template <typename T, int KK, int CIN, int CPT>
+__global__ __launch_bounds__(256) void k_conv_small(EdgeDev e, int groups, int ppb) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* sW = reinterpret_cast<float*>(smem);             // [tap][CIN][Cout]
+    __shared__ int s_base[256], s_wy[256], s_wx[256];
+    __shared__ unsigned s_vm[256];
+    __shared__ int sh[8];
+    constexpr int TAPS = KK * KK;
+    const int tid = threadIdx.x;
+    const int cg = tid % groups, pl = tid / groups;
+    const T* __restrict__ delta = (const T*)e.delta;
+    const T* __restrict__ w = (const T*)e.w;
+    const int cc = CIN * e.Cout;
+    carry_source_compaction(e, sh);
+    for (int i = tid; i < TAPS * cc; i += 256) {
+        const int tap = i / cc, r = i - tap * cc;
+        const int co = r / CIN, ci = r - co * CIN;
+        sW[tap * cc + ci * e.Cout + co] = (float)w[i];
+    }
+    long long block_taps = 0;
+    const int tps = (kSegPixels + ppb - 1) / ppb;
+    const int MT = edge_segments(e) * tps;
+    for (int tile = blockIdx.x; tile < MT; tile += gridDim.x) {
+        const int seg = tile / tps, first = (tile - seg * tps) * ppb;
+        __syncthreads();
+        const int tot = tile_prologue(e, seg, first, ppb, first == 0 && !e.up, true, s_base, s_wy, s_wx, s_vm, sh);
+        if (first >= tot) continue;
+        if (tid == 0) block_taps += sh[4];
+        if (pl >= ppb || first + pl >= tot) continue;
+        const unsigned vmask = s_vm[pl];
+        const int base = s_base[pl];
+        float in[TAPS * CIN];
+#pragma unroll
+        for (int tap = 0; tap < TAPS; ++tap) {
+            const bool v = (vmask >> tap) & 1u;
+            const T* src = delta + (v ? (size_t)(base + (tap / KK) * e.sW + (tap % KK)) * CIN : (size_t)0);
+#pragma unroll
+            for (int ci = 0; ci < CIN; ++ci) in[tap * CIN + ci] = (float)src[ci];
+        }
+#pragma unroll
+        for (int tap = 0; tap < TAPS; ++tap)
+            if (!((vmask >> tap) & 1u))
+#pragma unroll
+                for (int ci = 0; ci < CIN; ++ci) in[tap * CIN + ci] = 0.f;
+        float acc[CPT];
+#pragma unroll
+        for (int q = 0; q < CPT; ++q) acc[q] = 0.f;
+#pragma unroll
+        for (int t = 0; t < TAPS * CIN; ++t) {
+            const float a = in[t];
+            const float* wt = sW + t * e.Cout + cg * CPT;
+#pragma unroll
+            for (int q = 0; q < CPT; q += 4) {
+                const float4 w4 = *reinterpret_cast<const float4*>(wt + q);
+                acc[q] = fmaf(a, w4.x, acc[q]); acc[q + 1] = fmaf(a, w4.y, acc[q + 1]);
+                acc[q + 2] = fmaf(a, w4.z, acc[q + 2]); acc[q + 3] = fmaf(a, w4.w, acc[q + 3]);
+            }
+        }
+        const int f = 1 << e.up;
+        for (int ua = 0; ua < f; ++ua)
+            for (int ub = 0; ub < f; ++ub) {
+                T* pp = (T*)e.P + pdst_offset(e, s_wy[pl] + ua, s_wx[pl] + ub) + cg * CPT;
+#pragma unroll
+                for (int q = 0; q < CPT; q += 8) Row8<T>::add(pp + q, acc + q);
+            }
+    }
+    if (tid == 0) add_macs(e, block_taps, 1);
+}
+
+// ---------------------------------------------------------------------------
 // Plain FMA convolution for any dtype / channel count.
 // Block = 16 list entries x 16 cout lanes; each thread keeps 4 couts at a time.
 // ---------------------------------------------------------------------------
@@ -779,6 +854,15 @@ hipError_t launch_conv(const EdgeDev& e, int dtype, int conv_path, hipStream_t s
         return hipGetLastError();
     }
     *cls = kClsConvPlain;
+    if (conv_path == 0 && e.k == 3 && e.Cin == 3 && e.Cout % 32 == 0 && e.Cout <= 256) {
+        const int groups = e.Cout / 32, ppb = 256 / groups;
+        const size_t smem = (size_t)27 * e.Cout * 4;
+        const long long tps = (kSegPixels + ppb - 1) / ppb;
+        const unsigned g = cap_blocks(nseg * tps, 2048);
+        if (dtype == MDCNN_F16) k_conv_small<f16, 3, 3, 32><<<dim3(g), dim3(256), smem, st>>>(e, groups, ppb);
+        else k_conv_small<float, 3, 3, 32><<<dim3(g), dim3(256), smem, st>>>(e, groups, ppb);
+        return hipGetLastError();
+    }
     const int groups = e.Cout / 8;
     if (conv_path == 0 && e.Cout % 8 == 0 && groups <= 64 && (size_t)e.k * e.k * e.Cin * e.Cout * 4 <= 150 * 1024)
         return dtype == MDCNN_F16 ? launch_ldsw<f16>(e, max_entries, st) : launch_ldsw<float>(e, max_entries, st);

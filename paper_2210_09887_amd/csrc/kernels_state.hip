@@ -133,6 +133,10 @@ __global__ __launch_bounds__(256) void k_shift_fill(FillBatch fb) {
     const unsigned lb = blockIdx.x - j.block_begin;
     if (lb == 0 && j.reset_counters && (int)threadIdx.x < (j.reset_counters == 2 ? kNumCounters : kNumPerFrame))
         j.counters[threadIdx.x] = 0;
+    if (lb == 0 && j.reset_counters == 2) {                // first reset: clear the per-segment running sums
+        for (int i = threadIdx.x; i < j.n_lacc; i += 256) j.lacc[i] = 0ull;
+        for (int i = threadIdx.x; i < j.n_cacc; i += 256) j.cacc[i] = 0ull;
+    }
     if (j.dtype == MDCNN_F16) {
         if (j.C % 8 == 0) fill_items<f16, 8>(j, lb); else fill_items<f16, 1>(j, lb);
     } else {
@@ -379,12 +383,13 @@ __global__ __launch_bounds__(256) void k_write_tensor(SiteDev s, int what, const
 }
 
 // Single block: concatenates the segments of a list (ascending order), prefixed by its length.
-__global__ __launch_bounds__(256) void k_read_list(const int* __restrict__ list, const int* __restrict__ cnt, int n,
-                                                   int* __restrict__ dst) {
+// cnt[g * stride] = entries of segment g.
+__global__ __launch_bounds__(256) void k_read_list(const int* __restrict__ list, const int* __restrict__ cnt, int stride,
+                                                   int n, int* __restrict__ dst) {
     const int nseg = (n + kSegPixels - 1) / kSegPixels;
     int running = 0;
     for (int g = 0; g < nseg; ++g) {
-        const int c = cnt[g];
+        const int c = cnt[g * stride];
         for (int i = threadIdx.x; i < c; i += 256) dst[1 + running + i] = list[g * kSegPixels + i];
         running += c;
     }
@@ -392,21 +397,36 @@ __global__ __launch_bounds__(256) void k_read_list(const int* __restrict__ list,
     if (threadIdx.x == 0) dst[0] = running;
 }
 
+// Single block: per-frame counts and running sums of a site, added up over its segments.
 __global__ __launch_bounds__(256) void k_read_stats(SiteDev s, int* __restrict__ dst) {
-    if (threadIdx.x != 0) return;
-    for (int i = 0; i < 18; ++i) dst[i] = s.counters[i];
-    int c = 0;
-    if (s.ccnt) {
-        const int nseg = (s.Hp * s.Wp + kSegPixels - 1) / kSegPixels;
-        for (int g = 0; g < nseg; ++g) c += s.ccnt[g];
+    __shared__ unsigned long long red[256];
+    const int tid = threadIdx.x;
+    const int nl = s.lcnt ? (s.H * s.W + kSegPixels - 1) / kSegPixels : 0;
+    const int nc = s.ccnt ? (s.Hp * s.Wp + kSegPixels - 1) / kSegPixels : 0;
+    unsigned long long v[7] = {0, 0, 0, 0, 0, 0, 0};   // upd, cand, clist (frame); upd, cand, clist (sums)
+    for (int g = tid; g < nl; g += 256) { v[0] += s.lcnt[2 * g]; v[1] += s.lcnt[2 * g + 1]; v[3] += s.lacc[2 * g]; v[4] += s.lacc[2 * g + 1]; }
+    for (int g = tid; g < nc; g += 256) { v[2] += s.ccnt[g]; v[5] += s.cacc[g]; }
+    unsigned long long tot[6];
+    for (int k = 0; k < 6; ++k) {
+        __syncthreads();
+        red[tid] = v[k];
+        __syncthreads();
+        for (int o = 128; o > 0; o >>= 1) { if (tid < o) red[tid] += red[tid + o]; __syncthreads(); }
+        tot[k] = red[0];
     }
-    dst[2] = c;
-    // the multiply-accumulate sums are kept as 8 partials each
+    if (tid != 0) return;
+    for (int i = 0; i < 18; ++i) dst[i] = 0;
+    dst[kCntUpdated] = (int)tot[0];
+    dst[kCntCandidates] = (int)tot[1];
+    dst[2] = (int)tot[2];
     const unsigned long long* acc = reinterpret_cast<const unsigned long long*>(s.counters);
-    unsigned long long m = 0, p = 0;
+    unsigned long long m = 0, p = 0;                        // multiply-accumulate sums: 8 partials each
     for (int j = 0; j < 8; ++j) { m += acc[kAccMacsSpread + j]; p += acc[kAccMacsSpread + 8 + j]; }
     unsigned long long* d64 = reinterpret_cast<unsigned long long*>(dst);
+    d64[kAccUpdated] = tot[3];
+    d64[kAccCandidates] = tot[4];
     d64[kAccMacs] = m;
+    d64[kAccCompute] = tot[5];
     d64[kAccMacsPlain] = p;
 }
 
@@ -442,10 +462,10 @@ hipError_t launch_read_view(const SiteDev& s, int what, void* dst, hipStream_t s
             k_copy_bytes<<<dim3(grid_for(s.H * s.W)), dim3(256), 0, st>>>(s.flags, (uint8_t*)dst, s.H * s.W);
             return hipGetLastError();
         case MDCNN_VIEW_LIST:
-            k_read_list<<<dim3(1), dim3(256), 0, st>>>(s.list, s.lcnt, s.H * s.W, (int*)dst);
+            k_read_list<<<dim3(1), dim3(256), 0, st>>>(s.list, s.lcnt, 2, s.H * s.W, (int*)dst);
             return hipGetLastError();
         case MDCNN_VIEW_CLIST:
-            k_read_list<<<dim3(1), dim3(256), 0, st>>>(s.clist, s.ccnt, s.Hp * s.Wp, (int*)dst);
+            k_read_list<<<dim3(1), dim3(256), 0, st>>>(s.clist, s.ccnt, 1, s.Hp * s.Wp, (int*)dst);
             return hipGetLastError();
         default:
             k_read_stats<<<dim3(1), dim3(256), 0, st>>>(s, (int*)dst);

@@ -56,7 +56,8 @@ size_t esize(int dtype) { return dtype == MDCNN_F16 ? 2 : 4; }
 long long pmod(long long v, long long n) { long long r = v % n; return r < 0 ? r + n : r; }
 
 struct Layout {
-    size_t A, P, flags, delta, list, lcnt, clist, ccnt, counters, total;
+    size_t A, P, flags, delta, list, lcnt, lacc, clist, ccnt, cacc, counters, total;
+    int nseg_l, nseg_c;
     int Hp, Wp;
 };
 
@@ -88,9 +89,13 @@ void make_layout(const mdcnn_buffer_desc& d, Layout& L) {
     L.flags = take(hasA ? (size_t)d.H * d.W : 0);
     L.delta = take(hasA ? (size_t)d.H * d.W * d.C * e : 0);
     L.list = take(hasA ? nseg_l * kSegPixels * 4 : 0);
-    L.lcnt = take(hasA ? nseg_l * 4 : 0);
+    L.lcnt = take(hasA ? nseg_l * 2 * 4 : 0);
+    L.lacc = take(hasA ? nseg_l * 2 * 8 : 0);
+    L.nseg_l = hasA ? (int)nseg_l : 0;
+    L.nseg_c = hasP ? (int)nseg_c : 0;
     L.clist = take(hasP ? nseg_c * kSegPixels * 4 : 0);
     L.ccnt = take(hasP ? nseg_c * 4 : 0);
+    L.cacc = take(hasP ? nseg_c * 8 : 0);
     L.counters = take(kNumCounters * 4);
     L.total = off;
 }
@@ -176,7 +181,7 @@ EdgeDev make_edge(const mdcnn_buffer* in, const mdcnn_buffer* out, const mdcnn_c
     e.delta = in->dev.delta; e.sflags = in->dev.flags; e.pub_list = nullptr; e.pub_lcnt = nullptr; e.scounters = in->dev.counters;
     e.sH = in->d.H; e.sW = in->d.W; e.Cin = c.Cin;
     e.P = out->dev.P; e.dflags = out->d.kind == MDCNN_SITE_OUTPUT ? nullptr : out->dev.flags;
-    e.clist = out->dev.clist; e.ccnt = out->dev.ccnt; e.dcounters = out->dev.counters;
+    e.clist = out->dev.clist; e.ccnt = out->dev.ccnt; e.cacc = out->dev.cacc; e.dcounters = out->dev.counters;
     e.dH = out->d.H; e.dW = out->d.W; e.Cout = c.Cout; e.Hp = out->L.Hp; e.Wp = out->L.Wp;
     e.by0 = out->d.border[0]; e.bx0 = out->d.border[2]; e.p_oy = out->dev.p_oy; e.p_ox = out->dev.p_ox;
     e.w = c.w_dev; e.k = c.k; e.stride = c.k ? c.stride : 1; e.pad = c.k ? c.pad : 0; e.up = c.k ? c.up : 0;
@@ -228,13 +233,13 @@ mdcnn_status do_forward(mdcnn_buffer* in, const void* frame, const uint8_t* forc
     if (n_edges == 0) {
         EdgeDev e{};
         e.sflags = in->dev.flags; e.sH = in->d.H; e.sW = in->d.W;
-        e.pub_list = in->dev.list; e.pub_lcnt = in->dev.lcnt; e.scounters = in->dev.counters;
+        e.pub_list = in->dev.list; e.pub_lcnt = in->dev.lcnt; e.pub_lacc = in->dev.lacc; e.scounters = in->dev.counters;
         e.k = -1;
         return launch_edge(e, -1);
     }
     for (int i = 0; i < n_edges; ++i) {
         EdgeDev e = make_edge(in, outs[i], edges[i]);
-        if (i == 0) { e.pub_list = in->dev.list; e.pub_lcnt = in->dev.lcnt; }
+        if (i == 0) { e.pub_list = in->dev.list; e.pub_lcnt = in->dev.lcnt; e.pub_lacc = in->dev.lacc; }
         mdcnn_status rc = launch_edge(e, i);
         if (rc) return rc;
     }
@@ -315,6 +320,8 @@ mdcnn_status mdcnn_create_buffer(const mdcnn_buffer_desc* desc, void* dev_mem, s
     s.delta = hasA ? base + b->L.delta : nullptr;
     s.list = hasA ? (int*)(base + b->L.list) : nullptr;
     s.lcnt = hasA ? (int*)(base + b->L.lcnt) : nullptr;
+    s.lacc = hasA ? (unsigned long long*)(base + b->L.lacc) : nullptr;
+    s.cacc = hasP ? (unsigned long long*)(base + b->L.cacc) : nullptr;
     s.clist = hasP ? (int*)(base + b->L.clist) : nullptr;
     s.ccnt = hasP ? (int*)(base + b->L.ccnt) : nullptr;
     s.counters = (int*)(base + b->L.counters);
@@ -369,6 +376,7 @@ mdcnn_status mdcnn_shift_camera(mdcnn_buffer* const* bufs, int n, int dty, int d
         refresh_origins(b);
         FillJob j{};
         j.A = b->dev.A; j.P = b->dev.P; j.flags = b->dev.flags; j.bias = b->dev.bias; j.counters = b->dev.counters;
+        j.lacc = b->dev.lacc; j.cacc = b->dev.cacc; j.n_lacc = 2 * b->L.nseg_l; j.n_cacc = b->L.nseg_c;
         j.H = d.H; j.W = d.W; j.C = d.C; j.Hp = b->L.Hp; j.Wp = b->L.Wp;
         j.a_oy = b->dev.a_oy; j.a_ox = b->dev.a_ox; j.p_oy = b->dev.p_oy; j.p_ox = b->dev.p_ox;
         j.dtype = d.dtype;

@@ -42,9 +42,11 @@ struct SiteDev {
     uint8_t* flags;       // H*W, view order
     void* delta;          // H x W x C, view order
     int* list;            // H*W, segment-local compaction of the update mask
-    int* lcnt;            // entries per segment of list
+    int* lcnt;            // per segment of list: [2g] entries, [2g+1] candidates of step 1 (this frame)
+    unsigned long long* lacc;   // per segment: running sums of the two since the first reset
     int* clist;           // Hp*Wp, segment-local compute list of the last producer
     int* ccnt;            // entries per segment of clist
+    unsigned long long* cacc;   // per segment: running sum of compute-list entries
     int* counters;        // kNumCounters
     const float* bias;    // C floats or nullptr
     int H, W, C, Hp, Wp;
@@ -66,6 +68,9 @@ struct FillJob {
     uint8_t* flags;
     const float* bias;
     int* counters;
+    unsigned long long* lacc;   // per-segment running sums, cleared on the first reset
+    unsigned long long* cacc;
+    int n_lacc, n_cacc;
     int H, W, C, Hp, Wp;
     int a_oy, a_ox, p_oy, p_ox;
     int py0, py1, px0, px1;     // kept rows / cols of the padded window (empty: all new)
@@ -75,7 +80,7 @@ struct FillJob {
     int reset_counters;         // 1: per-frame slots, 2: all (first reset)
     unsigned block_begin;       // first block of the launch that works on this job
 };
-constexpr int kMaxFillJobs = 24;
+constexpr int kMaxFillJobs = 22;
 struct FillBatch {
     FillJob j[kMaxFillJobs];
     int n;
@@ -90,6 +95,7 @@ struct EdgeDev {
     const uint8_t* sflags;
     int* pub_list;            // non-null on the one edge of a forward call that also compacts
     int* pub_lcnt;            //   the source's update mask into its list L (segment-local)
+    unsigned long long* pub_lacc;
     int* scounters;
     int sH, sW, Cin;
     // destination
@@ -97,6 +103,7 @@ struct EdgeDev {
     uint8_t* dflags;          // nullptr for OUTPUT sites
     int* clist;
     int* ccnt;
+    unsigned long long* cacc;
     int* dcounters;
     int dH, dW, Cout, Hp, Wp, by0, bx0, p_oy, p_ox;
     // operator
