@@ -182,7 +182,9 @@ def _hrnet(rng, H=384, W=288, widths=(32, 64, 128, 256), blocks=4) -> NetSpec:
     3x3 stride-2 convs (ReLU between chain links), lower -> higher through a 1x1
     conv followed by nearest upsampling.  A new branch is opened from the fused
     lowest-resolution branch with a 3x3 stride-2 conv.  The network output is
-    the fused highest-resolution branch of the last stage.  Total stride 32."""
+    the fused highest-resolution branch of the last stage.  Total stride 32.
+    Folded batch-norm scales (0.25 on the second conv of every block, 0.35 on
+    the fusion convs) keep the activations within a few units in fp16."""
     net = NetSpec(CONFIG_NAMES[4], "f16", H, W, 32)
     b = _Builder(net, rng, bias_amp=0.1)
     th = 0.015
@@ -198,7 +200,7 @@ def _hrnet(rng, H=384, W=288, widths=(32, 64, 128, 256), blocks=4) -> NetSpec:
         nb = len(br)
         for j in range(nb):
             for k in range(blocks):
-                br[j] = b.basic_block(br[j], widths[j], 1, th, f"st{stage}.b{j}.blk{k}")
+                br[j] = b.basic_block(br[j], widths[j], 1, th, f"st{stage}.b{j}.blk{k}", branch_gain=0.25)
         last_stage = stage == 4
         outs = [0] if last_stage else list(range(nb))
         fused = []
@@ -210,7 +212,7 @@ def _hrnet(rng, H=384, W=288, widths=(32, 64, 128, 256), blocks=4) -> NetSpec:
                 if j == i:
                     b.identity(br[j], fused[oi])
                 elif j > i:
-                    b.conv(br[j], fused[oi], 1, 1, pad=0, up=j - i, gain=0.5)
+                    b.conv(br[j], fused[oi], 1, 1, pad=0, up=j - i, gain=0.35)
                 else:
                     cur = br[j]
                     for step in range(i - j - 1):
@@ -218,7 +220,7 @@ def _hrnet(rng, H=384, W=288, widths=(32, 64, 128, 256), blocks=4) -> NetSpec:
                                      net.sites[cur].stride * 2, theta=th)
                         b.conv(cur, nxt, 3, 2)
                         cur = nxt
-                    b.conv(cur, fused[oi], 3, 2, gain=0.5)
+                    b.conv(cur, fused[oi], 3, 2, gain=0.35)
         if last_stage:
             br = fused
         else:

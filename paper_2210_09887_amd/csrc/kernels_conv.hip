@@ -794,6 +794,10 @@ static hipError_t launch_tiled_kc(const EdgeDev& e, long long max_entries, hipSt
         case 8: if (e.Cout % 256 == 0) return launch_tiled_p<2, 2, 2, 4, KC>(e, max_entries, st); break;   // 128 x 256, wave 64 x 128
         case 9: if (e.Cout % 256 == 0) return launch_tiled_p<1, 4, 2, 2, KC>(e, max_entries, st); break;   //  64 x 256, wave 64 x 64
         case 10: if (e.Cout % 256 == 0) return launch_tiled_p<2, 2, 1, 4, KC>(e, max_entries, st); break;  //  64 x 256, wave 32 x 128
+        case 11: if (e.Cout % 128 == 0) return launch_tiled_p<1, 4, 1, 1, KC>(e, max_entries, st); break;  //  32 x 128
+        case 12: if (e.Cout % 256 == 0) return launch_tiled_p<1, 4, 1, 2, KC>(e, max_entries, st); break;  //  32 x 256
+        case 13: if (e.Cout % 128 == 0) return launch_tiled_p<1, 4, 2, 1, KC>(e, max_entries, st); break;  //  64 x 128, wave 64 x 32
+        case 14: if (e.Cout % 64 == 0) return launch_tiled_p<1, 4, 2, 1, 32>(e, max_entries, st); break;   //  same, 32-channel steps
         default: break;
     }
     return launch_tiled_p<4, 1, 1, 1, KC>(e, max_entries, st);                                             // 128 x 32

@@ -256,7 +256,7 @@ const char* mdcnn_version(void) { return "mdcnn 0.1 (gfx950)"; }
 mdcnn_status mdcnn_set_option(int option, int value) {
     if (option == MDCNN_OPT_CONV_PATH && value >= 0 && value <= 2) { g_conv_path = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_PROFILE && (value == 0 || value == 1)) { g_profile = value; return MDCNN_OK; }
-    if (option == MDCNN_OPT_CONV_TILE && value >= 0 && value <= 10) { g_tile = value; return MDCNN_OK; }
+    if (option == MDCNN_OPT_CONV_TILE && value >= 0 && value <= 14) { g_tile = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_CONV_PIPE && value >= 0 && value <= 2) { g_pipe = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_CONV_XCD && (value == 0 || value == 1)) { g_xcd = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_CONV_KC && (value == 0 || value == 64)) { g_kc = value; return MDCNN_OK; }
