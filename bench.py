@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--density", type=float, default=0.2, help="config 5 only")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle baseline; 0 disables it")
     ap.add_argument("--dense", action="store_true", help="library dense mode: threshold 0 and all pixels forced")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (a kernel of known traffic, to scale rocprofv3 byte counters)")
     return ap.parse_args()
 
 
@@ -63,7 +65,30 @@ def algorithmic_bytes(g, spec, before, after, frames):
         # flags read+write per pixel; candidates read A and (X or P); updated write A, delta (and P)
         writes = 2 if s.kind == "input" else 3
         step1 += frames * H * W * 2 + int(d["candidates"][i]) * 2 * cb + int(d["updated"][i]) * writes * cb
-    return dict(step1=step1)
+    # convolutions: every updated source row once, read-modify-write of the pending
+    # row of every compute-list entry, the weights once per launch
+    conv = 0
+    skip_entries = [0] * len(spec.sites)
+    for e in spec.edges:
+        if e.k == 0:
+            skip_entries[e.dst] += int(d["updated"][e.src])
+    for e in spec.edges:
+        if e.k == 0:
+            continue
+        conv += int(d["updated"][e.src]) * site_bytes_per_pixel(g, e.src) + frames * e.w.size * g.esize
+    for i, s in enumerate(spec.sites):
+        if s.kind != "input":
+            conv += max(int(d["compute"][i]) - skip_entries[i], 0) * 2 * site_bytes_per_pixel(g, i)
+    return dict(step1=step1, conv=conv)
+
+
+def measured_traffic(cfg, cls):
+    """HBM bytes per launch from the committed rocprofv3 byte-counter summary, if any."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
+            return json.load(f)[f"config{cfg}"][cls]["hbm_bytes_per_launch"]
+    except Exception:
+        return None
 
 
 def main():
@@ -145,19 +170,22 @@ def main():
         ms, cnt = prof["conv_mfma"]
         ach = flops_mfma / (ms * 1e-3) / 1e12
         rl_all["conv_mfma"] = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
-                               "frac": round(ach / PEAK_MFMA_F16_TFLOPS, 4), "traffic": None,
-                               "flop_per_launch": round(flops_mfma / cnt), "avg_us": round(1e3 * ms / cnt, 2), "launches": int(cnt)}
+                               "frac": round(ach / PEAK_MFMA_F16_TFLOPS, 4), "traffic": measured_traffic(cfg, "conv_mfma"),
+                               "flop_per_launch": round(flops_mfma / cnt), "avg_us": round(1e3 * ms / cnt, 2), "launches": int(cnt),
+                               "algorithmic_bytes_per_launch": round(ab["conv"] / (cnt + prof["conv_plain"][1])),
+                               "hbm_bound_us": round(ab["conv"] / (cnt + prof["conv_plain"][1]) / PEAK_HBM_GBS / 1e3, 2),
+                               "mfma_bound_us": round(flops_mfma / cnt / PEAK_MFMA_F16_TFLOPS / 1e6, 2)}
     if prof["conv_plain"][1]:
         ms, cnt = prof["conv_plain"]
         ach = flops_plain / (ms * 1e-3) / 1e12
         rl_all["conv_plain"] = {"bound": "alu", "achieved": round(ach, 3), "peak": PEAK_FP32_VALU_TFLOPS, "unit": "TFLOP/s",
-                                "frac": round(ach / PEAK_FP32_VALU_TFLOPS, 5), "traffic": None,
+                                "frac": round(ach / PEAK_FP32_VALU_TFLOPS, 5), "traffic": measured_traffic(cfg, "conv_plain"),
                                 "flop_per_launch": round(flops_plain / cnt), "avg_us": round(1e3 * ms / cnt, 2), "launches": int(cnt)}
     if prof["step1"][1]:
         ms, cnt = prof["step1"]
         ach = ab["step1"] / (ms * 1e-3) / 1e9
         rl_all["step1"] = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                           "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None,
+                           "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": measured_traffic(cfg, "step1"),
                            "bytes_per_launch": round(ab["step1"] / cnt), "avg_us": round(1e3 * ms / cnt, 2), "launches": int(cnt)}
     roofline = dict(rl_all.get(dominant, next(iter(rl_all.values()))))
     roofline["kernel"] = dominant if dominant in rl_all else next(iter(rl_all))
@@ -207,6 +235,12 @@ def main():
         "instrumented_ms_per_step": round(1e3 * dt_prof / n_prof, 4),
         "cpu_baseline": cpu,
     }
+    if a.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        out["copy_calibration_bytes"] = 1 << 30
     g.close()
     print(json.dumps(out))
 
