@@ -79,13 +79,26 @@ typedef struct mdcnn_net mdcnn_net;
 
 /* One edge.  Weights: w_dev[tap][cout][cin], tap = ky*k + kx, storage dtype of
  * the sites it joins, 16-byte aligned.  k == 0: identity edge (w_dev ignored,
- * stride 1, pad 0, up 0, Cin == Cout).  up > 0 requires k == 1, stride 1, pad 0. */
+ * stride 1, pad 0, up 0, Cin == Cout).  up > 0 requires k == 1, stride 1, pad 0.
+ * w_packed_dev: NULL, or the copy of w_dev that mdcnn_pack_weights wrote (fp16,
+ * Cin % 16 == 0); with it 3x3 stride-1 edges run on the faster matrix-core
+ * kernel.  Both copies must stay valid and equal while the edge is in use. */
 typedef struct {
     int k, stride, pad;
     int Cin, Cout;
     int up;                   /* log2 of the nearest-neighbour upsampling factor        */
     const void* w_dev;
+    const void* w_packed_dev;
 } mdcnn_conv_desc;
+
+/* Model preparation, once per edge: writes the weights of `edge` (w_dev, fp16,
+ * Cin % 16 == 0, Cout % 32 == 0) to dst_dev in the order
+ * [tap][cin/16][cout][16], in which the 32 couts x 16 cin operand of one
+ * matrix-core instruction is 1 KiB of consecutive memory.  dst_dev: caller-owned
+ * device memory, 16-byte aligned, dst_bytes == k*k*Cin*Cout*2 exactly.
+ * Asynchronous on `stream`.  Errors: MDCNN_ERR_SHAPE for other shapes or dtypes. */
+mdcnn_status mdcnn_pack_weights(const mdcnn_conv_desc* edge, int dtype, void* dst_dev, size_t dst_bytes,
+                                void* stream);
 
 /* Host-only helper.  Width of the dilated border along one axis for a
  * convolution (k, stride, pad) from `in_extent` to `out_extent` pixels: how many
@@ -182,12 +195,16 @@ mdcnn_status mdcnn_write_view(mdcnn_buffer* buf, int what, const void* src_dev, 
 
 /* Library options (process-wide, host-only). */
 typedef enum {
-    MDCNN_OPT_CONV_PATH = 0, /* 0 auto; fallbacks for testing: 1 plain FMA, 2 MFMA w/o LDS  */
+    MDCNN_OPT_CONV_PATH = 0, /* 0 auto; fallbacks for testing: 1 plain FMA, 2 MFMA w/o LDS, */
+                             /* 3 auto but never the packed-weights kernel                */
     MDCNN_OPT_PROFILE = 1,   /* 1: bracket every kernel launch with a pair of HIP events  */
     MDCNN_OPT_CONV_TILE = 2, /* tuning: 0 auto, 1..10 force a tile shape of the MFMA kernel */
     MDCNN_OPT_CONV_PIPE = 3, /* tuning: 0 auto, 1 / 2 prefetch depth of the MFMA kernel    */
     MDCNN_OPT_CONV_XCD = 4,  /* tuning: 1 (default) tie cout tiles to XCDs, 0 plain order  */
-    MDCNN_OPT_CONV_KC = 5    /* tuning: 0 auto, 64 cap the K step at 64 channels           */
+    MDCNN_OPT_CONV_KC = 5,   /* tuning: 0 auto, 64 cap the K step at 64 channels           */
+    MDCNN_OPT_CONV_HALO = 6, /* tuning: 1 (default) packed-weights kernel where it applies,  */
+                             /* 0 never, 2 with 32-cout tiles                              */
+    MDCNN_OPT_CONV_HALO_SUB = 7 /* tuning: 0 auto, 1 / 2 / 4 tiles per list segment of that kernel */
 } mdcnn_option;
 mdcnn_status mdcnn_set_option(int option, int value);
 

@@ -18,7 +18,8 @@ MDCNN_F32, MDCNN_F16 = 0, 1
 MDCNN_SITE_INPUT, MDCNN_SITE_PREACT, MDCNN_SITE_OUTPUT = 0, 1, 2
 (MDCNN_VIEW_A, MDCNN_VIEW_P, MDCNN_VIEW_DELTA, MDCNN_VIEW_FLAGS, MDCNN_VIEW_LIST,
  MDCNN_VIEW_CLIST, MDCNN_VIEW_STATS, MDCNN_VIEW_OUT) = range(8)
-MDCNN_OPT_CONV_PATH, MDCNN_OPT_PROFILE, MDCNN_OPT_CONV_TILE, MDCNN_OPT_CONV_PIPE, MDCNN_OPT_CONV_XCD, MDCNN_OPT_CONV_KC = range(6)
+MDCNN_OPT_CONV_PATH, MDCNN_OPT_PROFILE, MDCNN_OPT_CONV_TILE, MDCNN_OPT_CONV_PIPE, MDCNN_OPT_CONV_XCD, MDCNN_OPT_CONV_KC, \
+    MDCNN_OPT_CONV_HALO, MDCNN_OPT_CONV_HALO_SUB = range(8)
 KERNEL_CLASSES = ["shift", "step1", "lists", "conv_mfma", "conv_plain", "identity", "readout"]
 FLAG_N, FLAG_U, FLAG_M = 1, 2, 4
 
@@ -28,7 +29,7 @@ STATUS_NAMES = {0: "OK", 1: "ERR_NULL", 2: "ERR_SHAPE", 3: "ERR_DTYPE", 4: "ERR_
 EXPORTS = ["mdcnn_conv_border", "mdcnn_buffer_bytes", "mdcnn_create_buffer", "mdcnn_destroy_buffer",
            "mdcnn_shift_camera", "mdcnn_layer_forward", "mdcnn_net_create", "mdcnn_net_destroy",
            "mdcnn_frame", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read",
-           "mdcnn_last_error", "mdcnn_version"]
+           "mdcnn_pack_weights", "mdcnn_last_error", "mdcnn_version"]
 
 
 class mdcnn_buffer_desc(C.Structure):
@@ -39,7 +40,7 @@ class mdcnn_buffer_desc(C.Structure):
 
 class mdcnn_conv_desc(C.Structure):
     _fields_ = [("k", C.c_int), ("stride", C.c_int), ("pad", C.c_int), ("Cin", C.c_int), ("Cout", C.c_int),
-                ("up", C.c_int), ("w_dev", C.c_void_p)]
+                ("up", C.c_int), ("w_dev", C.c_void_p), ("w_packed_dev", C.c_void_p)]
 
 
 class MdcnnError(RuntimeError):
@@ -72,6 +73,7 @@ def lib():
         L.mdcnn_read_view.argtypes = [vp, C.c_int, vp, sz, vp]
         L.mdcnn_write_view.argtypes = [vp, C.c_int, vp, sz, vp]
         L.mdcnn_set_option.argtypes = [C.c_int, C.c_int]
+        L.mdcnn_pack_weights.argtypes = [C.POINTER(mdcnn_conv_desc), C.c_int, vp, sz, vp]
         L.mdcnn_profile_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_longlong)]
         L.mdcnn_last_error.restype = C.c_char_p
         L.mdcnn_version.restype = C.c_char_p
@@ -151,6 +153,10 @@ def mdcnn_net_create(sites, edge_src, edge_dst, edges) -> int:
     _check(lib().mdcnn_net_create(_handles(sites), len(sites), (C.c_int * n)(*edge_src), (C.c_int * n)(*edge_dst),
                                   (mdcnn_conv_desc * n)(*edges), n, C.byref(h)))
     return h.value
+
+
+def mdcnn_pack_weights(edge, dtype: int, dst_ptr: int, dst_bytes: int, stream: int = 0):
+    _check(lib().mdcnn_pack_weights(C.byref(edge), int(dtype), dst_ptr, dst_bytes, stream))
 
 
 def mdcnn_net_destroy(net: int):

@@ -412,6 +412,328 @@ __global__ __launch_bounds__(256) void k_conv_mfma_tiled(EdgeDev e, int NT, int 
     }
 }
 
+// Variant of tile_prologue for tiles that are index sub-ranges of a segment: the
+// tile takes the entries among indices [sub_lo, sub_lo + sub_n) of segment `seg`
+// (sub_lo a multiple of 64).  Returns their number; rows s_* are filled for them.
+__device__ __forceinline__ int tile_prologue_sub(const EdgeDev& e, int seg, int sub_lo, int sub_n, bool publish, bool touch,
+                                                 int* s_wy, int* s_wx, int* sh) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = e.Hp * e.Wp;
+    const int p = seg * kSegPixels + tid;
+    if (tid == 0) sh[4] = 0;
+    int cy = 0, cx = 0, wy = 0, wx = 0;
+    unsigned vm = 0;
+    if (p < n) {
+        decode_entry(e, p, cy, cx, wy, wx);
+        vm = tap_mask(e, cy, cx);
+    }
+    const bool has = vm != 0;
+    const unsigned long long bal = __ballot(has);
+    const int rank = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) sh[wave] = __popcll(bal);
+    __syncthreads();
+    int off = rank, base = 0, cnt = 0;
+    for (int i = 0; i < 4; ++i) {
+        if (i < wave) off += sh[i];
+        if (i * 64 < sub_lo) base += sh[i];
+        else if (i * 64 < sub_lo + sub_n) cnt += sh[i];
+    }
+    const bool mine = has && tid >= sub_lo && tid < sub_lo + sub_n;
+    if (mine) {
+        s_wy[off - base] = wy;
+        s_wx[off - base] = wx;
+        if (touch) mark_touched(e, wy, wx);
+    }
+    if (publish && has) e.clist[seg * kSegPixels + off] = p;
+    if (publish && tid == 0) {                             // single writer per segment: no atomics
+        const int tot = sh[0] + sh[1] + sh[2] + sh[3];
+        e.ccnt[seg] = tot;
+        e.cacc[seg] += (unsigned long long)tot;
+    }
+    int taps = mine ? __popc(vm) : 0;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) taps += __shfl_xor(taps, o);
+    if (lane == 0 && taps) atomicAdd(&sh[4], taps);
+    __syncthreads();
+    return cnt;
+}
+
+// ---------------------------------------------------------------------------
+// Halo-staged MFMA convolution: KS x KS, stride 1, fp16, weights in the packed
+// order [tap][cin/16][cout][16] (k_pack_weights).
+// A tile is one NSUB-th of a list segment -- the entries among SUB = kSegPixels
+// / NSUB consecutive indices of the padded window -- x BN couts.  Every input
+// pixel those entries read lies in a small rectangle of the source (the rows
+// the index range spans plus KS-1, full width if it spans more than one row).
+// Per KC-channel chunk that rectangle is staged ONCE in LDS -- zero rows for
+// pixels out of view or not updated, which is all the masking the taps need --
+// and all KS*KS taps multiply out of it: the deltas are fetched once instead
+// of once per tap.  The weights never touch LDS: the four waves are WMV
+// (row-tile groups) x WK (K split); a wave multiplies its row tiles x TN 32x32
+// accumulators over every WK-th 16-channel block of every tap and loads
+// exactly the fragments it needs, 1 KiB contiguous each, several steps ahead.
+// The body of a chunk is straight-line code (static taps, static register
+// rings), so the loads of the next steps and of the next chunk stay in flight
+// behind the matrix instructions; two tiles per compute unit cover each
+// other's barriers.  The K-split partial sums are added in a fixed order
+// through LDS, so the result does not depend on timing; P is then updated with
+// 16-byte accesses.
+// ---------------------------------------------------------------------------
+template <int NSUB, int WMV, int WK, int TM, int TN, int KC, int NLD_, int KS>
+struct HaloCfg {
+    static constexpr int SUB = kSegPixels / NSUB;    // indices (and at most entries) per tile
+    static_assert(WMV * WK == 4 && WMV * TM * 32 == SUB && SUB % 64 == 0, "4 waves cover one tile");
+    static constexpr int BN = 32 * TN;
+    static constexpr int KB = KC / 16;               // 16-channel blocks per chunk
+    static_assert(KB % WK == 0, "every K wave takes the same number of blocks per tap");
+    static constexpr int MB = KB / WK;               // blocks per tap and wave
+    static constexpr int NS = KS * KS * MB;          // steps per chunk and wave
+    static constexpr int RING = 3;                   // weight-fragment sets in flight; divides NS, so the
+                                                     // ring carries over from chunk to chunk
+    static_assert(NS % RING == 0, "static ring slots");
+    static constexpr int CPR = KC / 8;               // 16-byte pieces per staged pixel
+    static constexpr int NLD = NLD_;                 // pieces per thread and chunk
+    static constexpr int CAP = NLD * 256 / CPR;      // staged pixels
+    static constexpr int LDK = KC + 8;               // staged row, halves (16 bytes of padding)
+    static constexpr int LDC = BN + 4;               // accumulator row, floats
+    static constexpr int HALO_BYTES = CAP * LDK * 2;
+    static constexpr int C_BYTES = SUB * LDC * 4;
+    static constexpr int MAIN_BYTES = HALO_BYTES > C_BYTES ? HALO_BYTES : C_BYTES;
+    static constexpr int SMEM = MAIN_BYTES + CAP * 4;   // + source pixel index of every staged position
+    static constexpr int LPS = (NLD + NS / 2 - 1) / (NS / 2);   // staging loads per step (first steps of a chunk)
+    static constexpr int NLS = (NLD + LPS - 1) / LPS;
+    static_assert(NLS <= NS, "staging loads fit the steps of a chunk");
+    static constexpr int MINB = NSUB >= 2 ? 2 : 1;   // tiles per compute unit the registers are budgeted for
+};
+
+template <int NSUB, int WMV, int WK, int TM, int TN, int KC, int NLD_, int KS>
+__global__ __launch_bounds__(256, (NSUB >= 2 ? 2 : 1))
+void k_conv_halo(EdgeDev e, int NT, int work_items) {
+    using Cfg = HaloCfg<NSUB, WMV, WK, TM, TN, KC, NLD_, KS>;
+    constexpr int SUB = Cfg::SUB, BN = Cfg::BN, KB = Cfg::KB, MB = Cfg::MB, NS = Cfg::NS, CPR = Cfg::CPR, NLD = Cfg::NLD,
+                  LDK = Cfg::LDK, LDC = Cfg::LDC;
+    extern __shared__ __align__(16) unsigned char smem[];
+    f16* halo = reinterpret_cast<f16*>(smem);            // [CAP][LDK] during the K loop
+    float* sC = reinterpret_cast<float*>(smem);          // [SUB][LDC] after it
+    int* s_pix = reinterpret_cast<int*>(smem + Cfg::MAIN_BYTES);
+    __shared__ int s_wy[SUB], s_wx[SUB];
+    __shared__ int sh[8];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform: scalar branches below
+    const int wm = wave % WMV, wk = wave / WMV;
+    const int r32 = lane & 31, kh = lane >> 5;
+    const int ntiles = edge_segments(e) * NSUB;
+    const int nchunks = e.Cin / KC;
+    const int nwin = e.Hp * e.Wp;
+    const f16* __restrict__ delta = (const f16*)e.delta;
+    const long long tap_stride = (long long)(e.Cin / 16) * e.Cout * 16;   // packed weights: halves per tap
+    const long long blk_stride = (long long)e.Cout * 16;                  //                 per 16-channel block
+
+    carry_source_compaction(e, sh);
+
+    for (int u = blockIdx.x; u < work_items; u += gridDim.x) {
+        const int nt = u % NT, mt = u / NT;              // u % 8 picks the XCD: few cout tiles per XCD
+        if (mt >= ntiles) continue;
+        const int seg = mt / NSUB, sub_lo = (mt % NSUB) * SUB;
+        const int n0 = nt * BN;
+        __syncthreads();                                  // previous tile is done with LDS
+        const int tot = tile_prologue_sub(e, seg, sub_lo, SUB, nt == 0 && sub_lo == 0, nt == 0, s_wy, s_wx, sh);
+        if (tot <= 0) continue;
+        if (tid == 0 && nt == 0) add_macs(e, sh[4], 0);
+
+        // the source rectangle this index range reads (block-uniform)
+        const int a = seg * kSegPixels + sub_lo;
+        const int last = (a + SUB < nwin ? a + SUB : nwin) - 1;
+        const int wyA = a / e.Wp, wyB = last / e.Wp;
+        const int cxA = wyA == wyB ? a - wyA * e.Wp - e.bx0 : -e.bx0;
+        const int cxB = wyA == wyB ? last - wyA * e.Wp - e.bx0 : e.Wp - 1 - e.bx0;
+        const int iy0 = wyA - e.by0 - e.pad, ix0 = cxA - e.pad;
+        const int RW = cxB - cxA + KS, npos = (wyB - wyA + KS) * RW;       // npos <= CAP: checked by the host
+        for (int pos = tid; pos < npos; pos += 256) {
+            const int ry = pos / RW, rx = pos - ry * RW;
+            const int iy = iy0 + ry, ix = ix0 + rx;
+            const bool ok = iy >= 0 && iy < e.sH && ix >= 0 && ix < e.sW && (e.sflags[iy * e.sW + ix] & kFlagM);
+            s_pix[pos] = ok ? iy * e.sW + ix : -1;
+        }
+        __syncthreads();
+        const int nrt = (tot + 31) >> 5;                  // live 32-entry row tiles of the tile
+        const int mylive = nrt > wm ? (nrt - wm + WMV - 1) / WMV : 0;      // of this wave: row tiles wm, wm + WMV, ...
+
+        // staging: piece q = tid + 256 j is 16 bytes of staged pixel q / CPR.  Dead
+        // pieces (outside the rectangle, out of view, not updated) are loaded from
+        // pixel 0 and never stored; their rows are zeroed once per tile.
+        f16x8 hreg[NLD];
+        unsigned hval = 0;
+        unsigned hsrc[NLD];                               // element offsets (the host checks they fit 32 bits)
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            const int q = tid + 256 * j, pos = q / CPR;
+            const bool inr = pos < npos;
+            const int pix = inr ? s_pix[pos] : -1;
+            hval |= (pix >= 0 ? 1u : 0u) << j;
+            hsrc[j] = (unsigned)(pix >= 0 ? pix : 0) * (unsigned)e.Cin + (q % CPR) * 8;
+            if (inr && pix < 0) {
+                f16x8 z;
+#pragma unroll
+                for (int t = 0; t < 8; ++t) z[t] = (f16)0.f;
+                *reinterpret_cast<f16x8*>(halo + pos * LDK + (q % CPR) * 8) = z;
+            }
+        }
+        auto halo_store = [&]() {
+#pragma unroll
+            for (int j = 0; j < NLD; ++j)
+                if ((hval >> j) & 1u) {
+                    const int q = tid + 256 * j;
+                    *reinterpret_cast<f16x8*>(halo + (q / CPR) * LDK + (q % CPR) * 8) = hreg[j];
+                }
+        };
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) hreg[j] = *reinterpret_cast<const f16x8*>(delta + hsrc[j]);
+        halo_store();
+
+        f32x16 acc[TM][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        int rowoff[TM];                                   // this lane's staged row per row tile (halves)
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int r = (i * WMV + wm) * 32 + r32;
+            rowoff[i] = kh * 8 + wk * 16 + (r < tot ? ((s_wy[r] - e.by0 - e.pad - iy0) * RW + (s_wx[r] - e.bx0 - e.pad - ix0)) * LDK : 0);
+        }
+        const f16* wlane = (const f16*)e.wp + ((long long)wk * e.Cout + n0 + r32) * 16 + kh * 8;
+        __syncthreads();
+
+        // The K loop for L live row tiles of this wave.  Step i of a chunk: tap i / MB,
+        // 16-channel block wk + WK * (i % MB) of the chunk.
+        auto kloop = [&](auto lc) {
+            constexpr int L = decltype(lc)::value;
+            constexpr int D = Cfg::RING;
+            f16x8 fa[D][TN], fb[3][L > 0 ? L : 1];
+            auto load_a = [&](int slot, int c, int i) {              // i may run into the next chunk
+                const int cc = i < NS ? c : (c + 1 < nchunks ? c + 1 : c), ii = i < NS ? i : i - NS;
+                const f16* src = wlane + (ii / MB) * tap_stride + (cc * KB + WK * (ii % MB)) * blk_stride;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) fa[slot][j] = *reinterpret_cast<const f16x8*>(src + j * 32 * 16);
+            };
+            auto load_b = [&](int slot, int i) {
+                const int tap = i / MB;
+                const f16* hb = halo + ((tap / KS) * RW + tap % KS) * LDK + WK * (i % MB) * 16;
+#pragma unroll
+                for (int t = 0; t < L; ++t) fb[slot][t] = *reinterpret_cast<const f16x8*>(hb + rowoff[t]);
+            };
+#pragma unroll
+            for (int i = 0; i < D - 1; ++i) load_a(i, 0, i);
+            for (int c = 0; c < nchunks; ++c) {
+                const int cn = c + 1 < nchunks ? c + 1 : c;          // the last chunk re-reads itself: no branch
+                const unsigned hc = (unsigned)cn * KC;
+                load_b(0, 0);
+                load_b(1, 1);
+#pragma unroll
+                for (int i = 0; i < NS; ++i) {
+                    if (i < Cfg::NLS) {                   // staging loads of the next chunk, a few per step
+#pragma unroll
+                        for (int j = i * Cfg::LPS; j < (i + 1) * Cfg::LPS && j < NLD; ++j)
+                            hreg[j] = *reinterpret_cast<const f16x8*>(delta + hsrc[j] + hc);
+                    }
+                    load_a((i + D - 1) % D, c, i + D - 1);
+                    if (i + 2 < NS) load_b((i + 2) % 3, i + 2);
+                    __builtin_amdgcn_sched_barrier(0);       // keep the loads of later steps ahead of these MFMAs
+#pragma unroll
+                    for (int t = 0; t < L; ++t)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            acc[t][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i % D][j], fb[i % 3][t], acc[t][j], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                __syncthreads();                          // everyone is done reading the staged chunk
+                if (c + 1 < nchunks) {
+                    halo_store();
+                    __syncthreads();
+                }
+            }
+        };
+        switch (mylive) {
+            case 0: kloop(std::integral_constant<int, 0>{}); break;
+            case 1: kloop(std::integral_constant<int, 1>{}); break;
+            case 2: kloop(std::integral_constant<int, TM >= 2 ? 2 : TM>{}); break;
+            case 3: kloop(std::integral_constant<int, TM >= 3 ? 3 : TM>{}); break;
+            default: kloop(std::integral_constant<int, TM>{}); break;
+        }
+
+        // K-split partial sums -> LDS [entry][cout], added in the order of the K waves
+#pragma unroll
+        for (int kq = 0; kq < WK; ++kq) {
+            if (wk == kq) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    if (i < mylive) {
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) {
+                            float* dst = sC + ((i * WMV + wm) * 32 + r32) * LDC + j * 32 + 4 * kh;
+#pragma unroll
+                            for (int g = 0; g < 4; ++g) {
+                                float4 v = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+                                if (kq > 0) {
+                                    const float4 o = *reinterpret_cast<const float4*>(dst + 8 * g);
+                                    v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+                                }
+                                *reinterpret_cast<float4*>(dst + 8 * g) = v;
+                            }
+                        }
+                    }
+            }
+            __syncthreads();
+        }
+        // P <- P + sum: all reads of P go out first (their latency is paid once), then the stores
+        constexpr int TPR = BN / 8;                        // threads per entry, 8 couts each
+        constexpr int RPP = 256 / TPR, NPASS = (SUB + RPP - 1) / RPP;
+        const int c8 = (tid % TPR) * 8;
+        f16x8 pold[NPASS];
+        f16* pp[NPASS];
+#pragma unroll
+        for (int t = 0; t < NPASS; ++t) {
+            const int row = tid / TPR + t * RPP;
+            const int rr = row < tot ? row : 0;             // dead rows read entry 0 and store nothing
+            pp[t] = (f16*)e.P + pdst_offset(e, s_wy[rr], s_wx[rr]) + n0 + c8;
+            pold[t] = *reinterpret_cast<const f16x8*>(pp[t]);
+        }
+#pragma unroll
+        for (int t = 0; t < NPASS; ++t) {
+            const int row = tid / TPR + t * RPP;
+            if (row < tot) {
+                const float4 v0 = *reinterpret_cast<const float4*>(sC + row * LDC + c8);
+                const float4 v1 = *reinterpret_cast<const float4*>(sC + row * LDC + c8 + 4);
+                const float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+                f16x8 o = pold[t];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) o[q] = (f16)((float)o[q] + v[q]);
+                *reinterpret_cast<f16x8*>(pp[t]) = o;
+            }
+        }
+    }
+}
+
+// Weights [tap][cout][cin] -> [tap][cin/16][cout][16]: the 32 couts x 16 cin
+// operand of one MFMA becomes 1 KiB of consecutive memory.  One thread per 8 halves.
+__global__ __launch_bounds__(256) void k_pack_weights(const f16* __restrict__ src, f16* __restrict__ dst, int taps, int Cout, int Cin) {
+    const long long n8 = (long long)taps * Cout * Cin / 8;
+    const int KBT = Cin / 16;
+    for (long long i = blockIdx.x * 256ll + threadIdx.x; i < n8; i += gridDim.x * 256ll) {
+        const int h = (int)(i & 1);
+        long long r = i >> 1;
+        const int co = (int)(r % Cout); r /= Cout;
+        const int kb = (int)(r % KBT);
+        const int tap = (int)(r / KBT);
+        *reinterpret_cast<f16x8*>(dst + i * 8) =
+            *reinterpret_cast<const f16x8*>(src + ((long long)tap * Cout + co) * Cin + kb * 16 + h * 8);
+    }
+}
+
 // ---------------------------------------------------------------------------
 // MFMA without LDS staging: every wave loads its own fragments from global
 // memory.  Block = 4 waves arranged (4/WN) x WN over (pixels x couts); every
@@ -803,6 +1125,74 @@ static hipError_t launch_tiled_kc(const EdgeDev& e, long long max_entries, hipSt
     return launch_tiled_p<4, 1, 1, 1, KC>(e, max_entries, st);                                             // 128 x 32
 }
 
+int g_halo = 1;          // 0: never use the halo-staged kernel, 2: force 32-cout tiles
+int g_halo_sub = 0;      // 0: auto, 1 / 2 / 4: tiles per list segment of the halo-staged kernel
+
+template <int NSUB, int WMV, int WK, int TM, int TN, int KC, int NLD>
+static hipError_t launch_halo_t(const EdgeDev& e, long long nseg, hipStream_t st) {
+    using Cfg = HaloCfg<NSUB, WMV, WK, TM, TN, KC, NLD, 3>;
+    static bool attr_set = false;
+    auto kern = k_conv_halo<NSUB, WMV, WK, TM, TN, KC, NLD, 3>;
+    if (!attr_set) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::SMEM);
+        if (err != hipSuccess) return err;
+        attr_set = true;
+    }
+    const int NT = e.Cout / Cfg::BN;
+    const long long items = nseg * NSUB * NT;
+    kern<<<dim3(cap_blocks(items, 16384)), dim3(256), Cfg::SMEM, st>>>(e, NT, (int)items);
+    return hipGetLastError();
+}
+
+// Staged pixels the rectangle of `sub` consecutive window indices can need.
+static long long halo_worst(const EdgeDev& e, int sub) {
+    const long long span = (sub - 2) / e.Wp + 2;                            // window rows the range can straddle
+    const long long width = span > 1 || sub > e.Wp ? e.Wp : sub;
+    return (span + e.k - 1) * (width - 1 + e.k);
+}
+
+// Halo-staged kernel if the rectangle a tile can read fits the staging buffer
+// (the fewer channels per chunk, the more pixels fit).  *done = false: not applicable.
+// Tiles are whole segments, halves or quarters: the smallest split that gives
+// every compute unit about two tiles.
+template <int TN>
+static hipError_t launch_halo_n(const EdgeDev& e, long long nseg, hipStream_t st, bool* done) {
+    const long long per_split = nseg * (e.Cout / (32 * TN));
+    int nsub = g_halo_sub ? g_halo_sub : (per_split >= 384 ? 1 : per_split * 2 >= 384 ? 2 : 4);
+    *done = true;
+    for (; nsub <= 4; nsub *= 2) {
+        const long long worst = halo_worst(e, kSegPixels / nsub);
+        const bool c64 = e.Cin % 64 == 0, c32 = e.Cin % 32 == 0;
+        if (nsub == 1) {
+            if (c64 && worst <= HaloCfg<1, 2, 2, 4, TN, 64, 16, 3>::CAP) return launch_halo_t<1, 2, 2, 4, TN, 64, 16>(e, nseg, st);
+            if (c32 && worst <= HaloCfg<1, 2, 2, 4, TN, 32, 12, 3>::CAP) return launch_halo_t<1, 2, 2, 4, TN, 32, 12>(e, nseg, st);
+            if (worst <= HaloCfg<1, 4, 1, 2, TN, 16, 12, 3>::CAP) return launch_halo_t<1, 4, 1, 2, TN, 16, 12>(e, nseg, st);
+        } else if (nsub == 2) {
+            if (c64 && worst <= HaloCfg<2, 2, 2, 2, TN, 64, 11, 3>::CAP) return launch_halo_t<2, 2, 2, 2, TN, 64, 11>(e, nseg, st);
+            if (c32 && worst <= HaloCfg<2, 2, 2, 2, TN, 32, 9, 3>::CAP) return launch_halo_t<2, 2, 2, 2, TN, 32, 9>(e, nseg, st);
+            if (worst <= HaloCfg<2, 4, 1, 1, TN, 16, 9, 3>::CAP) return launch_halo_t<2, 4, 1, 1, TN, 16, 9>(e, nseg, st);
+        } else {
+            if (c64 && worst <= HaloCfg<4, 1, 4, 2, TN, 64, 9, 3>::CAP) return launch_halo_t<4, 1, 4, 2, TN, 64, 9>(e, nseg, st);
+            if (c32 && worst <= HaloCfg<4, 2, 2, 1, TN, 32, 6, 3>::CAP) return launch_halo_t<4, 2, 2, 1, TN, 32, 6>(e, nseg, st);
+        }
+    }
+    *done = false;
+    return hipSuccess;
+}
+
+static hipError_t launch_halo(const EdgeDev& e, long long nseg, hipStream_t st, bool* done) {
+    *done = false;
+    if (!g_halo || !e.wp || e.k != 3 || e.stride != 1 || e.up != 0 || e.Cin % 16 || e.Cout % 32) return hipSuccess;
+    if ((long long)e.sH * e.sW * e.Cin >= (1ll << 31)) return hipSuccess;      // 32-bit staging offsets
+    return e.Cout % 64 == 0 && g_halo != 2 ? launch_halo_n<2>(e, nseg, st, done) : launch_halo_n<1>(e, nseg, st, done);
+}
+
+hipError_t launch_pack_weights(const void* src, void* dst, int taps, int Cout, int Cin, hipStream_t st) {
+    const long long n8 = (long long)taps * Cout * Cin / 8;
+    k_pack_weights<<<dim3(cap_blocks((n8 + 255) / 256, 2048)), dim3(256), 0, st>>>((const f16*)src, (f16*)dst, taps, Cout, Cin);
+    return hipGetLastError();
+}
+
 template <typename T>
 static hipError_t launch_ldsw(const EdgeDev& e, long long max_entries, hipStream_t st) {
     static size_t attr_bytes = 0;
@@ -842,9 +1232,14 @@ hipError_t launch_conv(const EdgeDev& e, int dtype, int conv_path, hipStream_t s
         }
         return hipGetLastError();
     }
-    // conv_path: 0 auto, 1 plain FMA (per-thread weights), 2 MFMA without LDS tiling
+    // conv_path: 0 auto, 1 plain FMA (per-thread weights), 2 MFMA without LDS tiling, 3 auto without halo staging
     const bool mfma_ok = dtype == MDCNN_F16 && conv_path != 1 && e.Cin % 16 == 0 && e.Cout % 32 == 0;
-    if (mfma_ok && conv_path == 0 && e.Cin % 32 == 0) {
+    if (mfma_ok && conv_path == 0) {
+        bool done = false;
+        const hipError_t err = launch_halo(e, nseg, st, &done);
+        if (done) { *cls = kClsConvMfma; return err; }
+    }
+    if (mfma_ok && (conv_path == 0 || conv_path == 3) && e.Cin % 32 == 0) {
         *cls = kClsConvMfma;
         if (e.Cin % 128 == 0 && g_kc != 64) return launch_tiled_kc<128>(e, max_entries, st);
         return e.Cin % 64 == 0 ? launch_tiled_kc<64>(e, max_entries, st) : launch_tiled_kc<32>(e, max_entries, st);
@@ -858,7 +1253,7 @@ hipError_t launch_conv(const EdgeDev& e, int dtype, int conv_path, hipStream_t s
         return hipGetLastError();
     }
     *cls = kClsConvPlain;
-    if (conv_path == 0 && e.k == 3 && e.Cin == 3 && e.Cout % 32 == 0 && e.Cout <= 256) {
+    if ((conv_path == 0 || conv_path == 3) && e.k == 3 && e.Cin == 3 && e.Cout % 32 == 0 && e.Cout <= 256) {
         const int groups = e.Cout / 32, ppb = 256 / groups;
         const size_t smem = (size_t)27 * e.Cout * 4;
         const long long tps = (kSegPixels + ppb - 1) / ppb;
@@ -868,7 +1263,7 @@ hipError_t launch_conv(const EdgeDev& e, int dtype, int conv_path, hipStream_t s
         return hipGetLastError();
     }
     const int groups = e.Cout / 8;
-    if (conv_path == 0 && e.Cout % 8 == 0 && groups <= 64 && (size_t)e.k * e.k * e.Cin * e.Cout * 4 <= 150 * 1024)
+    if ((conv_path == 0 || conv_path == 3) && e.Cout % 8 == 0 && groups <= 64 && (size_t)e.k * e.k * e.Cin * e.Cout * 4 <= 150 * 1024)
         return dtype == MDCNN_F16 ? launch_ldsw<f16>(e, max_entries, st) : launch_ldsw<float>(e, max_entries, st);
     unsigned g = cap_blocks(nseg * (kSegPixels / 16), 8192);
     if (dtype == MDCNN_F16) k_conv_plain<f16><<<dim3(g), dim3(256), 0, st>>>(e);

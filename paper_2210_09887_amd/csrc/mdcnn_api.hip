@@ -173,6 +173,11 @@ mdcnn_status validate_edge(const mdcnn_buffer* in, const mdcnn_buffer* out, cons
                     idx, b[0], b[1], b[2], b[3], by0, by1, bx0, bx1);
     if (!c.w_dev) return fail(MDCNN_ERR_NULL, "edge %d: weights are NULL", idx);
     if ((uintptr_t)c.w_dev & 15) return fail(MDCNN_ERR_ALIGN, "edge %d: weights must be 16-byte aligned", idx);
+    if (c.w_packed_dev) {
+        if ((uintptr_t)c.w_packed_dev & 15) return fail(MDCNN_ERR_ALIGN, "edge %d: packed weights must be 16-byte aligned", idx);
+        if (in->d.dtype != MDCNN_F16 || c.Cin % 16 || c.Cout % 32)
+            return fail(MDCNN_ERR_SHAPE, "edge %d: packed weights need fp16, Cin %% 16 == 0, Cout %% 32 == 0", idx);
+    }
     return MDCNN_OK;
 }
 
@@ -184,7 +189,7 @@ EdgeDev make_edge(const mdcnn_buffer* in, const mdcnn_buffer* out, const mdcnn_c
     e.clist = out->dev.clist; e.ccnt = out->dev.ccnt; e.cacc = out->dev.cacc; e.dcounters = out->dev.counters;
     e.dH = out->d.H; e.dW = out->d.W; e.Cout = c.Cout; e.Hp = out->L.Hp; e.Wp = out->L.Wp;
     e.by0 = out->d.border[0]; e.bx0 = out->d.border[2]; e.p_oy = out->dev.p_oy; e.p_ox = out->dev.p_ox;
-    e.w = c.w_dev; e.k = c.k; e.stride = c.k ? c.stride : 1; e.pad = c.k ? c.pad : 0; e.up = c.k ? c.up : 0;
+    e.w = c.w_dev; e.wp = c.k ? c.w_packed_dev : nullptr; e.k = c.k; e.stride = c.k ? c.stride : 1; e.pad = c.k ? c.pad : 0; e.up = c.k ? c.up : 0;
     return e;
 }
 
@@ -254,7 +259,9 @@ const char* mdcnn_last_error(void) { return g_err; }
 const char* mdcnn_version(void) { return "mdcnn 0.1 (gfx950)"; }
 
 mdcnn_status mdcnn_set_option(int option, int value) {
-    if (option == MDCNN_OPT_CONV_PATH && value >= 0 && value <= 2) { g_conv_path = value; return MDCNN_OK; }
+    if (option == MDCNN_OPT_CONV_PATH && value >= 0 && value <= 3) { g_conv_path = value; return MDCNN_OK; }
+    if (option == MDCNN_OPT_CONV_HALO && value >= 0 && value <= 2) { g_halo = value; return MDCNN_OK; }
+    if (option == MDCNN_OPT_CONV_HALO_SUB && (value == 0 || value == 1 || value == 2 || value == 4)) { g_halo_sub = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_PROFILE && (value == 0 || value == 1)) { g_profile = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_CONV_TILE && value >= 0 && value <= 14) { g_tile = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_CONV_PIPE && value >= 0 && value <= 2) { g_pipe = value; return MDCNN_OK; }
@@ -279,6 +286,18 @@ mdcnn_status mdcnn_profile_read(int n_classes, double* ms, long long* launches) 
     }
     g_timed.clear();
     return rc;
+}
+
+mdcnn_status mdcnn_pack_weights(const mdcnn_conv_desc* edge, int dtype, void* dst_dev, size_t dst_bytes, void* stream) {
+    if (!edge || !edge->w_dev || !dst_dev) return fail(MDCNN_ERR_NULL, "pack_weights: NULL argument");
+    if (dtype != MDCNN_F16 || edge->k < 1 || edge->k > 5 || edge->Cin < 16 || edge->Cin % 16 || edge->Cout < 32 || edge->Cout % 32)
+        return fail(MDCNN_ERR_SHAPE, "pack_weights: needs fp16, 1 <= k <= 5, Cin %% 16 == 0, Cout %% 32 == 0");
+    if (((uintptr_t)edge->w_dev | (uintptr_t)dst_dev) & 15) return fail(MDCNN_ERR_ALIGN, "pack_weights: pointers must be 16-byte aligned");
+    const size_t want = (size_t)edge->k * edge->k * edge->Cin * edge->Cout * 2;
+    if (dst_bytes != want) return fail(MDCNN_ERR_SIZE, "pack_weights: dst_bytes %zu, expected %zu", dst_bytes, want);
+    const hipError_t err = launch_pack_weights(edge->w_dev, dst_dev, edge->k * edge->k, edge->Cout, edge->Cin, (hipStream_t)stream);
+    if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "pack_weights launch: %s", hipGetErrorString(err));
+    return MDCNN_OK;
 }
 
 mdcnn_status mdcnn_conv_border(int k, int stride, int pad, int in_extent, int out_extent, int* before, int* after) {

@@ -107,7 +107,8 @@ struct EdgeDev {
     int* dcounters;
     int dH, dW, Cout, Hp, Wp, by0, bx0, p_oy, p_ox;
     // operator
-    const void* w;
+    const void* w;            // [tap][cout][cin]
+    const void* wp;           // the same weights packed [tap][cin/16][cout][16], or nullptr
     int k, stride, pad, up;
 };
 
@@ -118,7 +119,8 @@ hipError_t launch_step1(const SiteDev& s, const void* frame, const uint8_t* forc
 // e.k < 0: no operator, only the compaction of the source's update mask.
 // returns the kernel class that was launched in *cls
 hipError_t launch_conv(const EdgeDev& e, int dtype, int conv_path, hipStream_t st, int* cls);
-extern int g_tile, g_pipe, g_xcd, g_kc;   // convolution tuning knobs
+extern int g_tile, g_pipe, g_xcd, g_kc, g_halo, g_halo_sub;   // convolution tuning knobs
+hipError_t launch_pack_weights(const void* src, void* dst, int taps, int Cout, int Cin, hipStream_t st);
 hipError_t launch_read_view(const SiteDev& s, int what, void* dst, hipStream_t st);
 hipError_t launch_write_view(const SiteDev& s, int what, const void* src, hipStream_t st);
 

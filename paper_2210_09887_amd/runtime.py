@@ -34,7 +34,7 @@ class GpuNet:
         self.weights, self.edges, self.esrc, self.edst = [], [], [], []
         for e in spec.edges:
             Hs, Ws, _ = self.shape[e.src]
-            cd = B.mdcnn_conv_desc(e.k, e.stride, e.pad, spec.sites[e.src].C, spec.sites[e.dst].C, e.up, None)
+            cd = B.mdcnn_conv_desc(e.k, e.stride, e.pad, spec.sites[e.src].C, spec.sites[e.dst].C, e.up, None, None)
             if e.k:
                 oh = (Hs + 2 * e.pad - e.k) // e.stride + 1
                 ow = (Ws + 2 * e.pad - e.k) // e.stride + 1
@@ -45,6 +45,11 @@ class GpuNet:
                 assert w.dtype == self.tdtype
                 self.weights.append(w)
                 cd.w_dev = w.data_ptr()
+                if dt == B.MDCNN_F16 and e.k == 3 and e.stride == 1 and not e.up and cd.Cin % 16 == 0 and cd.Cout % 32 == 0:
+                    wp = torch.empty_like(w)             # second copy in matrix-core operand order
+                    B.mdcnn_pack_weights(cd, dt, wp.data_ptr(), wp.numel() * 2)
+                    self.weights.append(wp)
+                    cd.w_packed_dev = wp.data_ptr()
                 if e.b is not None:
                     bias[e.dst] = e.b.astype(np.float32) if bias[e.dst] is None else bias[e.dst] + e.b.astype(np.float32)
             self.edges.append(cd)
