@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--density", type=float, default=0.2, help="config 5 only")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle baseline; 0 disables it")
     ap.add_argument("--dense", action="store_true", help="library dense mode: threshold 0 and all pixels forced")
+    ap.add_argument("--opt", action="append", default=[], metavar="ID=VALUE",
+                    help="library tuning option (mdcnn_set_option), e.g. --opt 6=0 switches the halo-staged kernel off")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a kernel of known traffic, to scale rocprofv3 byte counters)")
     return ap.parse_args()
@@ -121,6 +123,9 @@ def main():
         forced = torch.ones((T, net.H, net.W), dtype=torch.uint8, device="cuda")
     elif seq.forced is not None:
         forced = torch.from_numpy(seq.forced).cuda()
+    for kv in a.opt:
+        k, v = kv.split("=")
+        B.mdcnn_set_option(int(k), int(v))
     g = GpuNet(net)
 
     state = {"t": 0, "resets": 0}

@@ -157,10 +157,10 @@ __device__ __forceinline__ void carry_source_compaction(const EdgeDev& e, int* s
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     for (int seg = blockIdx.x; seg < nseg; seg += gridDim.x) {
         const int p = seg * kSegPixels + tid;
-        const int f = p < HW ? e.sflags[p] : 0;
+        const int f = p < HW && tid < kSegPixels ? e.sflags[p] : 0;       // waves beyond the fourth only keep the barriers
         const unsigned long long bm = __ballot(f & kFlagM), bc = __ballot(f & kFlagC);
         __syncthreads();                                   // sh is free again
-        if (lane == 0) { sh[wave] = __popcll(bm); sh[4 + wave] = __popcll(bc); }
+        if (lane == 0 && wave < 4) { sh[wave] = __popcll(bm); sh[4 + wave] = __popcll(bc); }
         __syncthreads();
         int off = __popcll(bm & ((1ull << lane) - 1ull));
         for (int i = 0; i < wave; ++i) off += sh[i];
@@ -423,14 +423,14 @@ __device__ __forceinline__ int tile_prologue_sub(const EdgeDev& e, int seg, int 
     if (tid == 0) sh[4] = 0;
     int cy = 0, cx = 0, wy = 0, wx = 0;
     unsigned vm = 0;
-    if (p < n) {
+    if (p < n && tid < kSegPixels) {                       // waves beyond the fourth only keep the barriers
         decode_entry(e, p, cy, cx, wy, wx);
         vm = tap_mask(e, cy, cx);
     }
     const bool has = vm != 0;
     const unsigned long long bal = __ballot(has);
     const int rank = __popcll(bal & ((1ull << lane) - 1ull));
-    if (lane == 0) sh[wave] = __popcll(bal);
+    if (lane == 0 && wave < 4) sh[wave] = __popcll(bal);
     __syncthreads();
     int off = rank, base = 0, cnt = 0;
     for (int i = 0; i < 4; ++i) {
@@ -479,7 +479,7 @@ __device__ __forceinline__ int tile_prologue_sub(const EdgeDev& e, int seg, int 
 // through LDS, so the result does not depend on timing; P is then updated with
 // 16-byte accesses.
 // ---------------------------------------------------------------------------
-template <int NSUB, int WMV, int WK, int TM, int TN, int KC, int NLD_, int KS>
+template <int NSUB, int WMV, int WK, int TM, int TN, int KC, int NLD_, int KS, int RING_ = 3, int MINB_ = (NSUB >= 2 ? 2 : 1)>
 struct HaloCfg {
     static constexpr int SUB = kSegPixels / NSUB;    // indices (and at most entries) per tile
     static_assert(WMV * WK == 4 && WMV * TM * 32 == SUB && SUB % 64 == 0, "4 waves cover one tile");
@@ -488,7 +488,7 @@ struct HaloCfg {
     static_assert(KB % WK == 0, "every K wave takes the same number of blocks per tap");
     static constexpr int MB = KB / WK;               // blocks per tap and wave
     static constexpr int NS = KS * KS * MB;          // steps per chunk and wave
-    static constexpr int RING = 3;                   // weight-fragment sets in flight; divides NS, so the
+    static constexpr int RING = RING_;               // weight-fragment sets in flight; divides NS, so the
                                                      // ring carries over from chunk to chunk
     static_assert(NS % RING == 0, "static ring slots");
     static constexpr int CPR = KC / 8;               // 16-byte pieces per staged pixel
@@ -503,13 +503,13 @@ struct HaloCfg {
     static constexpr int LPS = (NLD + NS / 2 - 1) / (NS / 2);   // staging loads per step (first steps of a chunk)
     static constexpr int NLS = (NLD + LPS - 1) / LPS;
     static_assert(NLS <= NS, "staging loads fit the steps of a chunk");
-    static constexpr int MINB = NSUB >= 2 ? 2 : 1;   // tiles per compute unit the registers are budgeted for
+    static constexpr int MINB = MINB_;               // tiles per compute unit the registers are budgeted for
 };
 
-template <int NSUB, int WMV, int WK, int TM, int TN, int KC, int NLD_, int KS>
-__global__ __launch_bounds__(256, (NSUB >= 2 ? 2 : 1))
+template <int NSUB, int WMV, int WK, int TM, int TN, int KC, int NLD_, int KS, int RING_ = 3, int MINB_ = (NSUB >= 2 ? 2 : 1)>
+__global__ __launch_bounds__(256, MINB_)
 void k_conv_halo(EdgeDev e, int NT, int work_items) {
-    using Cfg = HaloCfg<NSUB, WMV, WK, TM, TN, KC, NLD_, KS>;
+    using Cfg = HaloCfg<NSUB, WMV, WK, TM, TN, KC, NLD_, KS, RING_, MINB_>;
     constexpr int SUB = Cfg::SUB, BN = Cfg::BN, KB = Cfg::KB, MB = Cfg::MB, NS = Cfg::NS, CPR = Cfg::CPR, NLD = Cfg::NLD,
                   LDK = Cfg::LDK, LDC = Cfg::LDC;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -613,7 +613,8 @@ void k_conv_halo(EdgeDev e, int NT, int work_items) {
         auto kloop = [&](auto lc) {
             constexpr int L = decltype(lc)::value;
             constexpr int D = Cfg::RING;
-            f16x8 fa[D][TN], fb[3][L > 0 ? L : 1];
+            constexpr int FBR = TM > 4 ? 2 : 3;                      // sets of staged-row fragments in flight
+            f16x8 fa[D][TN], fb[FBR][L > 0 ? L : 1];
             auto load_a = [&](int slot, int c, int i) {              // i may run into the next chunk
                 const int cc = i < NS ? c : (c + 1 < nchunks ? c + 1 : c), ii = i < NS ? i : i - NS;
                 const f16* src = wlane + (ii / MB) * tap_stride + (cc * KB + WK * (ii % MB)) * blk_stride;
@@ -631,8 +632,8 @@ void k_conv_halo(EdgeDev e, int NT, int work_items) {
             for (int c = 0; c < nchunks; ++c) {
                 const int cn = c + 1 < nchunks ? c + 1 : c;          // the last chunk re-reads itself: no branch
                 const unsigned hc = (unsigned)cn * KC;
-                load_b(0, 0);
-                load_b(1, 1);
+#pragma unroll
+                for (int i = 0; i < FBR - 1; ++i) load_b(i, i);
 #pragma unroll
                 for (int i = 0; i < NS; ++i) {
                     if (i < Cfg::NLS) {                   // staging loads of the next chunk, a few per step
@@ -641,13 +642,13 @@ void k_conv_halo(EdgeDev e, int NT, int work_items) {
                             hreg[j] = *reinterpret_cast<const f16x8*>(delta + hsrc[j] + hc);
                     }
                     load_a((i + D - 1) % D, c, i + D - 1);
-                    if (i + 2 < NS) load_b((i + 2) % 3, i + 2);
+                    if (i + FBR - 1 < NS) load_b((i + FBR - 1) % FBR, i + FBR - 1);
                     __builtin_amdgcn_sched_barrier(0);       // keep the loads of later steps ahead of these MFMAs
 #pragma unroll
                     for (int t = 0; t < L; ++t)
 #pragma unroll
                         for (int j = 0; j < TN; ++j)
-                            acc[t][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i % D][j], fb[i % 3][t], acc[t][j], 0, 0, 0);
+                            acc[t][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i % D][j], fb[i % FBR][t], acc[t][j], 0, 0, 0);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 __syncthreads();                          // everyone is done reading the staged chunk
@@ -661,33 +662,49 @@ void k_conv_halo(EdgeDev e, int NT, int work_items) {
             case 0: kloop(std::integral_constant<int, 0>{}); break;
             case 1: kloop(std::integral_constant<int, 1>{}); break;
             case 2: kloop(std::integral_constant<int, TM >= 2 ? 2 : TM>{}); break;
-            case 3: kloop(std::integral_constant<int, TM >= 3 ? 3 : TM>{}); break;
+            case 3: kloop(std::integral_constant<int, (TM > 4 ? 4 : TM >= 3 ? 3 : TM)>{}); break;    // rounded up: dead tiles are not stored
+            case 4: kloop(std::integral_constant<int, (TM >= 4 ? 4 : TM)>{}); break;
             default: kloop(std::integral_constant<int, TM>{}); break;
         }
 
-        // K-split partial sums -> LDS [entry][cout], added in the order of the K waves
+        // K-split partial sums -> LDS [entry][cout].  Every element is added up in a fixed
+        // order of the K waves: with four K waves over all rows, wave w takes quarter
+        // (w + p) % 4 of the rows in phase p (all waves busy in every phase); otherwise
+        // the K waves take turns.
+        auto put = [&](int i, bool add) {
 #pragma unroll
-        for (int kq = 0; kq < WK; ++kq) {
-            if (wk == kq) {
+            for (int j = 0; j < TN; ++j) {
+                float* dst = sC + ((i * WMV + wm) * 32 + r32) * LDC + j * 32 + 4 * kh;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    float4 v = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+                    if (add) {
+                        const float4 o = *reinterpret_cast<const float4*>(dst + 8 * g);
+                        v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+                    }
+                    *reinterpret_cast<float4*>(dst + 8 * g) = v;
+                }
+            }
+        };
+        if constexpr (WK == 4 && WMV == 1 && TM % 4 == 0) {
+#pragma unroll
+            for (int ph = 0; ph < 4; ++ph) {
+                const int q = (wk + ph) & 3;
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
-                    if (i < mylive) {
-#pragma unroll
-                        for (int j = 0; j < TN; ++j) {
-                            float* dst = sC + ((i * WMV + wm) * 32 + r32) * LDC + j * 32 + 4 * kh;
-#pragma unroll
-                            for (int g = 0; g < 4; ++g) {
-                                float4 v = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-                                if (kq > 0) {
-                                    const float4 o = *reinterpret_cast<const float4*>(dst + 8 * g);
-                                    v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
-                                }
-                                *reinterpret_cast<float4*>(dst + 8 * g) = v;
-                            }
-                        }
-                    }
+                    if (i / (TM / 4) == q && i < mylive) put(i, ph > 0);
+                __syncthreads();
             }
-            __syncthreads();
+        } else {
+#pragma unroll
+            for (int kq = 0; kq < WK; ++kq) {
+                if (wk == kq) {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+                        if (i < mylive) put(i, kq > 0);
+                }
+                __syncthreads();
+            }
         }
         // P <- P + sum: all reads of P go out first (their latency is paid once), then the stores
         constexpr int TPR = BN / 8;                        // threads per entry, 8 couts each
@@ -1128,11 +1145,11 @@ static hipError_t launch_tiled_kc(const EdgeDev& e, long long max_entries, hipSt
 int g_halo = 1;          // 0: never use the halo-staged kernel, 2: force 32-cout tiles
 int g_halo_sub = 0;      // 0: auto, 1 / 2 / 4: tiles per list segment of the halo-staged kernel
 
-template <int NSUB, int WMV, int WK, int TM, int TN, int KC, int NLD>
+template <int NSUB, int WMV, int WK, int TM, int TN, int KC, int NLD, int RING = 3, int MINB = (NSUB >= 2 ? 2 : 1)>
 static hipError_t launch_halo_t(const EdgeDev& e, long long nseg, hipStream_t st) {
-    using Cfg = HaloCfg<NSUB, WMV, WK, TM, TN, KC, NLD, 3>;
+    using Cfg = HaloCfg<NSUB, WMV, WK, TM, TN, KC, NLD, 3, RING, MINB>;
     static bool attr_set = false;
-    auto kern = k_conv_halo<NSUB, WMV, WK, TM, TN, KC, NLD, 3>;
+    auto kern = k_conv_halo<NSUB, WMV, WK, TM, TN, KC, NLD, 3, RING, MINB>;
     if (!attr_set) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::SMEM);
         if (err != hipSuccess) return err;
@@ -1152,13 +1169,16 @@ static long long halo_worst(const EdgeDev& e, int sub) {
 }
 
 // Halo-staged kernel if the rectangle a tile can read fits the staging buffer
-// (the fewer channels per chunk, the more pixels fit).  *done = false: not applicable.
-// Tiles are whole segments, halves or quarters: the smallest split that gives
-// every compute unit about two tiles.
+// (the fewer channels per chunk, the more pixels fit; below 32 channels per chunk
+// -- rows wider than about 250 pixels -- the tiled kernel is faster).
+// *done = false: not applicable.
+// Tiles are whole segments, halves or quarters: the smallest split that keeps at
+// least half of the compute units busy (measured: finer splits re-read the weights
+// more often than the extra parallelism pays back).
 template <int TN>
 static hipError_t launch_halo_n(const EdgeDev& e, long long nseg, hipStream_t st, bool* done) {
     const long long per_split = nseg * (e.Cout / (32 * TN));
-    int nsub = g_halo_sub ? g_halo_sub : (per_split >= 384 ? 1 : per_split * 2 >= 384 ? 2 : 4);
+    int nsub = g_halo_sub ? g_halo_sub : (per_split >= 256 ? 1 : per_split * 2 >= 128 ? 2 : 4);
     *done = true;
     for (; nsub <= 4; nsub *= 2) {
         const long long worst = halo_worst(e, kSegPixels / nsub);
@@ -1166,11 +1186,9 @@ static hipError_t launch_halo_n(const EdgeDev& e, long long nseg, hipStream_t st
         if (nsub == 1) {
             if (c64 && worst <= HaloCfg<1, 2, 2, 4, TN, 64, 16, 3>::CAP) return launch_halo_t<1, 2, 2, 4, TN, 64, 16>(e, nseg, st);
             if (c32 && worst <= HaloCfg<1, 2, 2, 4, TN, 32, 12, 3>::CAP) return launch_halo_t<1, 2, 2, 4, TN, 32, 12>(e, nseg, st);
-            if (worst <= HaloCfg<1, 4, 1, 2, TN, 16, 12, 3>::CAP) return launch_halo_t<1, 4, 1, 2, TN, 16, 12>(e, nseg, st);
         } else if (nsub == 2) {
             if (c64 && worst <= HaloCfg<2, 2, 2, 2, TN, 64, 11, 3>::CAP) return launch_halo_t<2, 2, 2, 2, TN, 64, 11>(e, nseg, st);
             if (c32 && worst <= HaloCfg<2, 2, 2, 2, TN, 32, 9, 3>::CAP) return launch_halo_t<2, 2, 2, 2, TN, 32, 9>(e, nseg, st);
-            if (worst <= HaloCfg<2, 4, 1, 1, TN, 16, 9, 3>::CAP) return launch_halo_t<2, 4, 1, 1, TN, 16, 9>(e, nseg, st);
         } else {
             if (c64 && worst <= HaloCfg<4, 1, 4, 2, TN, 64, 9, 3>::CAP) return launch_halo_t<4, 1, 4, 2, TN, 64, 9>(e, nseg, st);
             if (c32 && worst <= HaloCfg<4, 2, 2, 1, TN, 32, 6, 3>::CAP) return launch_halo_t<4, 2, 2, 1, TN, 32, 6>(e, nseg, st);
