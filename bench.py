@@ -54,11 +54,19 @@ def site_bytes_per_pixel(g, i):
     return g.shape[i][2] * g.esize
 
 
-def algorithmic_bytes(g, spec, before, after, frames):
+def algorithmic_bytes(g, spec, before, after, frames, fused_skips=True):
     """Algorithmic HBM bytes of the memory-bound passes over `frames` frames,
-    from the device-side counters (differences of the running sums)."""
+    from the device-side counters (differences of the running sums).  With fused
+    residual skips the delta kernel of the source also reads and writes the
+    pending row of the skip's destination for every updated pixel."""
     d = {k: after["per_site"][k] - before["per_site"][k] for k in after["per_site"]}
     step1 = 0
+    if fused_skips:
+        seen = set()
+        for e in spec.edges:
+            if e.k == 0 and e.src not in seen:        # one fused skip per source site
+                seen.add(e.src)
+                step1 += int(d["updated"][e.src]) * 2 * site_bytes_per_pixel(g, e.src)
     for i, s in enumerate(spec.sites):
         if s.kind == "output":
             continue
@@ -72,7 +80,7 @@ def algorithmic_bytes(g, spec, before, after, frames):
     conv = 0
     skip_entries = [0] * len(spec.sites)
     for e in spec.edges:
-        if e.k == 0:
+        if e.k == 0 and not fused_skips:              # fused skips add nothing to the compute statistics
             skip_entries[e.dst] += int(d["updated"][e.src])
     for e in spec.edges:
         if e.k == 0:
@@ -163,7 +171,7 @@ def main():
 
     flops_mfma = 2.0 * (after["macs_mfma"] - before["macs_mfma"])
     flops_plain = 2.0 * (after["macs_plain"] - before["macs_plain"])
-    ab = algorithmic_bytes(g, net, before, after, n_prof)
+    ab = algorithmic_bytes(g, net, before, after, n_prof, fused_skips="8=0" not in a.opt)
     classes = {}
     for k, (ms, cnt) in prof.items():
         if cnt:

@@ -165,7 +165,9 @@ mdcnn_status mdcnn_net_destroy(mdcnn_net* net);
 /* One frame: mdcnn_shift_camera, mdcnn_layer_forward over all non-terminal sites
  * in order, then the readout f(P) of every OUTPUT site in view order, written
  * back to back (site order) into out_dev (storage dtype; out_bytes must match
- * exactly).  `forced_mask_dev` applies to the input site only.   [Method, Fig. 3] */
+ * exactly).  `forced_mask_dev` applies to the input site only.  Results are
+ * identical, bit for bit, to the same sequence of mdcnn_shift_camera /
+ * mdcnn_layer_forward / mdcnn_read_view calls.                [Method, Fig. 3] */
 mdcnn_status mdcnn_frame(mdcnn_net* net, const void* frame_dev, const uint8_t* forced_mask_dev,
                          int dty, int dtx, void* out_dev, size_t out_bytes, void* stream,
                          int* did_full_reset);
@@ -204,7 +206,11 @@ typedef enum {
     MDCNN_OPT_CONV_KC = 5,   /* tuning: 0 auto, 64 cap the K step at 64 channels           */
     MDCNN_OPT_CONV_HALO = 6, /* tuning: 1 (default) packed-weights kernel where it applies,  */
                              /* 0 never, 2 with 32-cout tiles                              */
-    MDCNN_OPT_CONV_HALO_SUB = 7 /* tuning: 0 auto, 1 / 2 / 4 tiles per list segment of that kernel */
+    MDCNN_OPT_CONV_HALO_SUB = 7, /* tuning: 0 auto, 1 / 2 / 4 tiles per list segment of that kernel */
+    MDCNN_OPT_FUSE_SKIP = 8  /* 1 (default): mdcnn_frame lets the delta kernel of a site add its   */
+                             /* residual skip (identity edge) instead of a launch of its own; */
+                             /* such an edge then adds nothing to the compute-list statistics  */
+                             /* of its destination.  0: one launch per edge                  */
 } mdcnn_option;
 mdcnn_status mdcnn_set_option(int option, int value);
 

@@ -46,6 +46,10 @@ __device__ __forceinline__ size_t p_offset(const SiteDev& s, int wy, int wx) {
     int py = wrap(s.p_oy + wy, s.Hp), px = wrap(s.p_ox + wx, s.Wp);
     return ((size_t)py * s.Wp + px) * s.C;
 }
+__device__ __forceinline__ size_t skip_offset(const SkipDev& k, int vy, int vx, int C) {
+    int py = wrap(k.p_oy + vy + k.by0, k.Hp), px = wrap(k.p_ox + vx + k.bx0, k.Wp);
+    return ((size_t)py * k.Wp + px) * C;
+}
 
 // ---------------------------------------------------------------------------
 // Dynamic initialisation, all sites of a network in one launch.  Pixels of the
@@ -161,7 +165,7 @@ hipError_t launch_shift_fill(const FillBatch& fb, hipStream_t st) {
 // ---------------------------------------------------------------------------
 template <typename T, int G, int CH>
 __global__ __launch_bounds__(256) void k_step1(SiteDev s, const T* __restrict__ X,
-                                               const uint8_t* __restrict__ forced) {
+                                               const uint8_t* __restrict__ forced, SkipDev skip) {
     constexpr int VEC = V16<T>::N;
     constexpr int PPB = 256 / G;
     const int tid = threadIdx.x;
@@ -217,6 +221,19 @@ __global__ __launch_bounds__(256) void k_step1(SiteDev s, const T* __restrict__ 
                     V16<T>::store(Dp + c0, out[j]);
                     if (!is_input) V16<T>::store(Pp + c0, z);
                 }
+                if (skip.P) {                              // fused residual skip: P_dst += delta (as stored)
+                    T* Sp = (T*)skip.P + skip_offset(skip, vy, vx, s.C);
+#pragma unroll
+                    for (int j = 0; j < CH; ++j) {
+                        const int c0 = (lp + j * G) * VEC;
+                        float t[VEC];
+                        V16<T>::load(Sp + c0, t);
+#pragma unroll
+                        for (int i = 0; i < VEC; ++i) t[i] += (float)(T)out[j][i];
+                        V16<T>::store(Sp + c0, t);
+                    }
+                    if (lp == 0 && skip.dflags) skip.dflags[pix] |= (uint8_t)kFlagU;
+                }
             }
         }
         if (lp == 0) s.flags[pix] = (uint8_t)((m ? kFlagM : 0) | (cand ? kFlagC : 0));
@@ -226,7 +243,7 @@ __global__ __launch_bounds__(256) void k_step1(SiteDev s, const T* __restrict__ 
 // Any channel count: one lane per pixel, scalar accesses.
 template <typename T>
 __global__ __launch_bounds__(256) void k_step1_scalar(SiteDev s, const T* __restrict__ X,
-                                                      const uint8_t* __restrict__ forced) {
+                                                      const uint8_t* __restrict__ forced, SkipDev skip) {
     const int tid = threadIdx.x;
     const int pix = blockIdx.x * 256 + tid;
     const int HW = s.H * s.W;
@@ -255,17 +272,21 @@ __global__ __launch_bounds__(256) void k_step1_scalar(SiteDev s, const T* __rest
             m = (fl & kFlagN) || hit;
             if (m) {
                 T* Dp = (T*)s.delta + (size_t)pix * s.C;
+                T* Sp = skip.P ? (T*)skip.P + skip_offset(skip, vy, vx, s.C) : nullptr;
+                if (Sp && skip.dflags) skip.dflags[pix] |= (uint8_t)kFlagU;
                 for (int c = 0; c < s.C; ++c) {
                     float a = (float)Ap[c];
                     if (is_input) {
                         float x = (float)Xp[c];
                         Ap[c] = (T)x;
                         Dp[c] = (T)(x - a);
+                        if (Sp) Sp[c] = (T)((float)Sp[c] + (float)Dp[c]);
                     } else {
                         float n = a + (float)Pp[c];
                         Ap[c] = (T)n;
                         Dp[c] = (T)(s.relu ? fmaxf(n, 0.f) - fmaxf(a, 0.f) : n - a);
                         Pp[c] = (T)0.f;
+                        if (Sp) Sp[c] = (T)((float)Sp[c] + (float)Dp[c]);
                     }
                 }
             }
@@ -288,40 +309,40 @@ static bool step1_shape(int C, int vec, int& G, int& CH) {
 }
 
 template <typename T, int G>
-static void step1_g(const SiteDev& s, const T* X, const uint8_t* forced, int CH, dim3 grid, hipStream_t st) {
+static void step1_g(const SiteDev& s, const T* X, const uint8_t* forced, const SkipDev& skip, int CH, dim3 grid, hipStream_t st) {
     switch (CH) {
-        case 1: k_step1<T, G, 1><<<grid, dim3(256), 0, st>>>(s, X, forced); break;
-        case 2: k_step1<T, G, 2><<<grid, dim3(256), 0, st>>>(s, X, forced); break;
-        case 3: k_step1<T, G, 3><<<grid, dim3(256), 0, st>>>(s, X, forced); break;
-        default: k_step1<T, G, 4><<<grid, dim3(256), 0, st>>>(s, X, forced); break;
+        case 1: k_step1<T, G, 1><<<grid, dim3(256), 0, st>>>(s, X, forced, skip); break;
+        case 2: k_step1<T, G, 2><<<grid, dim3(256), 0, st>>>(s, X, forced, skip); break;
+        case 3: k_step1<T, G, 3><<<grid, dim3(256), 0, st>>>(s, X, forced, skip); break;
+        default: k_step1<T, G, 4><<<grid, dim3(256), 0, st>>>(s, X, forced, skip); break;
     }
 }
 
 template <typename T>
-static hipError_t step1_t(const SiteDev& s, const void* frame, const uint8_t* forced, hipStream_t st) {
+static hipError_t step1_t(const SiteDev& s, const void* frame, const uint8_t* forced, const SkipDev& skip, hipStream_t st) {
     int G = 0, CH = 0;
     const T* X = (const T*)frame;
     const int HW = s.H * s.W;
     if (!step1_shape(s.C, V16<T>::N, G, CH)) {
-        k_step1_scalar<T><<<dim3((HW + 255) / 256), dim3(256), 0, st>>>(s, X, forced);
+        k_step1_scalar<T><<<dim3((HW + 255) / 256), dim3(256), 0, st>>>(s, X, forced, skip);
         return hipGetLastError();
     }
     const int ppb = 256 / G;
     dim3 grid((HW + ppb - 1) / ppb);
     switch (G) {
-        case 1: step1_g<T, 1>(s, X, forced, CH, grid, st); break;
-        case 2: step1_g<T, 2>(s, X, forced, CH, grid, st); break;
-        case 4: step1_g<T, 4>(s, X, forced, CH, grid, st); break;
-        case 8: step1_g<T, 8>(s, X, forced, CH, grid, st); break;
-        case 16: step1_g<T, 16>(s, X, forced, CH, grid, st); break;
-        case 32: step1_g<T, 32>(s, X, forced, CH, grid, st); break;
-        default: step1_g<T, 64>(s, X, forced, CH, grid, st); break;
+        case 1: step1_g<T, 1>(s, X, forced, skip, CH, grid, st); break;
+        case 2: step1_g<T, 2>(s, X, forced, skip, CH, grid, st); break;
+        case 4: step1_g<T, 4>(s, X, forced, skip, CH, grid, st); break;
+        case 8: step1_g<T, 8>(s, X, forced, skip, CH, grid, st); break;
+        case 16: step1_g<T, 16>(s, X, forced, skip, CH, grid, st); break;
+        case 32: step1_g<T, 32>(s, X, forced, skip, CH, grid, st); break;
+        default: step1_g<T, 64>(s, X, forced, skip, CH, grid, st); break;
     }
     return hipGetLastError();
 }
 
-hipError_t launch_step1(const SiteDev& s, const void* frame, const uint8_t* forced, hipStream_t st) {
-    return s.dtype == MDCNN_F16 ? step1_t<f16>(s, frame, forced, st) : step1_t<float>(s, frame, forced, st);
+hipError_t launch_step1(const SiteDev& s, const void* frame, const uint8_t* forced, const SkipDev& skip, hipStream_t st) {
+    return s.dtype == MDCNN_F16 ? step1_t<f16>(s, frame, forced, skip, st) : step1_t<float>(s, frame, forced, skip, st);
 }
 
 // ---------------------------------------------------------------------------

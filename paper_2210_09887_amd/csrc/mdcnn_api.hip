@@ -16,6 +16,7 @@ namespace {
 
 thread_local char g_err[512] = "";
 int g_conv_path = 0;
+int g_fuse_skip = 1;      // mdcnn_frame: residual skips are added by the step-1 kernel of their source
 int g_profile = 0;
 
 // Profiling mode: every kernel launch is bracketed by a pair of events on its
@@ -213,9 +214,19 @@ mdcnn_status validate_forward(const mdcnn_buffer* in, const void* frame, const m
     return MDCNN_OK;
 }
 
+// fuse_skip: index of an identity edge whose add is done by the step-1 kernel (its
+// destination is touched there and the edge gets no launch of its own), or -1.
 mdcnn_status do_forward(mdcnn_buffer* in, const void* frame, const uint8_t* forced, const mdcnn_conv_desc* edges,
-                        mdcnn_buffer* const* outs, int n_edges, hipStream_t st) {
-    hipError_t err = timed(kClsStep1, st, [&] { return launch_step1(in->dev, frame, forced, st); });
+                        mdcnn_buffer* const* outs, int n_edges, hipStream_t st, int fuse_skip = -1) {
+    SkipDev skip{};
+    if (fuse_skip >= 0) {
+        const mdcnn_buffer* d = outs[fuse_skip];
+        skip.P = d->dev.P;
+        skip.dflags = d->d.kind == MDCNN_SITE_OUTPUT ? nullptr : d->dev.flags;
+        skip.Hp = d->L.Hp; skip.Wp = d->L.Wp; skip.by0 = d->d.border[0]; skip.bx0 = d->d.border[2];
+        skip.p_oy = d->dev.p_oy; skip.p_ox = d->dev.p_ox;
+    }
+    hipError_t err = timed(kClsStep1, st, [&] { return launch_step1(in->dev, frame, forced, skip, st); });
     if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "step-1 launch: %s", hipGetErrorString(err));
     auto launch_edge = [&](EdgeDev& e, int idx) -> mdcnn_status {
         int cls = kClsConvPlain;
@@ -235,16 +246,18 @@ mdcnn_status do_forward(mdcnn_buffer* in, const void* frame, const uint8_t* forc
         if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "conv launch (edge %d): %s", idx, hipGetErrorString(err));
         return MDCNN_OK;
     };
-    if (n_edges == 0) {
+    if (n_edges == 0 || (n_edges == 1 && fuse_skip == 0)) {
         EdgeDev e{};
         e.sflags = in->dev.flags; e.sH = in->d.H; e.sW = in->d.W;
         e.pub_list = in->dev.list; e.pub_lcnt = in->dev.lcnt; e.pub_lacc = in->dev.lacc; e.scounters = in->dev.counters;
         e.k = -1;
         return launch_edge(e, -1);
     }
+    bool first = true;
     for (int i = 0; i < n_edges; ++i) {
+        if (i == fuse_skip) continue;
         EdgeDev e = make_edge(in, outs[i], edges[i]);
-        if (i == 0) { e.pub_list = in->dev.list; e.pub_lcnt = in->dev.lcnt; e.pub_lacc = in->dev.lacc; }
+        if (first) { e.pub_list = in->dev.list; e.pub_lcnt = in->dev.lcnt; e.pub_lacc = in->dev.lacc; first = false; }
         mdcnn_status rc = launch_edge(e, i);
         if (rc) return rc;
     }
@@ -261,6 +274,7 @@ const char* mdcnn_version(void) { return "mdcnn 0.1 (gfx950)"; }
 mdcnn_status mdcnn_set_option(int option, int value) {
     if (option == MDCNN_OPT_CONV_PATH && value >= 0 && value <= 3) { g_conv_path = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_CONV_HALO && value >= 0 && value <= 2) { g_halo = value; return MDCNN_OK; }
+    if (option == MDCNN_OPT_FUSE_SKIP && (value == 0 || value == 1)) { g_fuse_skip = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_CONV_HALO_SUB && (value == 0 || value == 1 || value == 2 || value == 4)) { g_halo_sub = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_PROFILE && (value == 0 || value == 1)) { g_profile = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_CONV_TILE && value >= 0 && value <= 14) { g_tile = value; return MDCNN_OK; }
@@ -509,8 +523,18 @@ mdcnn_status mdcnn_frame(mdcnn_net* net, const void* frame_dev, const uint8_t* f
         while (e1 < n_edges && net->esrc[e1] == i) ++e1;
         outs.clear();
         for (int e = e0; e < e1; ++e) outs.push_back(net->sites[net->edst[e]]);
+        // a residual skip is added by the step-1 kernel of its source; its place in the
+        // order of the producers of its destination stays the same as long as no other
+        // edge of this call goes to the same destination before it
+        int fuse = -1;
+        for (int e = e0; e < e1 && g_fuse_skip && fuse < 0; ++e) {
+            if (net->edges[e].k != 0) continue;
+            bool earlier = false;
+            for (int q = e0; q < e; ++q) earlier |= net->edst[q] == net->edst[e];
+            if (!earlier) fuse = e - e0;
+        }
         rc = do_forward(s, i == 0 ? frame_dev : nullptr, i == 0 ? forced_mask_dev : nullptr,
-                        net->edges.data() + e0, outs.data(), e1 - e0, st);
+                        net->edges.data() + e0, outs.data(), e1 - e0, st, fuse);
         if (rc) return rc;
         e0 = e1;
     }

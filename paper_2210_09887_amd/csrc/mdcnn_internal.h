@@ -59,6 +59,15 @@ struct SiteDev {
     int dtype;
 };
 
+// Destination of a residual skip fused into step 1 of its source site: the delta
+// a pixel emits is also added to the pending ring of the destination (same view
+// shape, same channels) and the pixel is marked touched there.  P == nullptr: none.
+struct SkipDev {
+    void* P;
+    uint8_t* dflags;          // nullptr for OUTPUT sites
+    int Hp, Wp, by0, bx0, p_oy, p_ox;
+};
+
 // Initialisation job of one site for one camera shift: everything outside the
 // kept rectangle of the padded window gets P = bias, everything outside the
 // kept rectangle of the view gets A = 0 and flag N.
@@ -115,7 +124,7 @@ struct EdgeDev {
 enum KernelClass { kClsShift = 0, kClsStep1, kClsLists, kClsConvMfma, kClsConvPlain, kClsIdentity, kClsReadout, kNumClasses };
 
 hipError_t launch_shift_fill(const FillBatch& fb, hipStream_t st);
-hipError_t launch_step1(const SiteDev& s, const void* frame, const uint8_t* forced, hipStream_t st);
+hipError_t launch_step1(const SiteDev& s, const void* frame, const uint8_t* forced, const SkipDev& skip, hipStream_t st);
 // e.k < 0: no operator, only the compaction of the source's update mask.
 // returns the kernel class that was launched in *cls
 hipError_t launch_conv(const EdgeDev& e, int dtype, int conv_path, hipStream_t st, int* cls);

@@ -116,9 +116,10 @@ def test_origin_rotation_is_invisible(name):
             assert np.array_equal(x, y)
 
 
-@pytest.mark.parametrize("path", [1, 2])
+@pytest.mark.parametrize("path", [1, 2, 3])
 def test_fallback_conv_paths_on_f16(path):
-    """The fallback kernels (plain FMA; MFMA without LDS tiling) agree with the oracle too."""
+    """The fallback kernels (plain FMA; MFMA without LDS tiling; the tiled MFMA kernel
+    where the halo-staged one would run) agree with the oracle too."""
     import gpu_harness as H
     from paper_2210_09887_amd import binding as B
     net, seq = load_case("c3_resnet_96")
@@ -127,6 +128,25 @@ def test_fallback_conv_paths_on_f16(path):
         H.teacher_forced(net, seq.frames[:3], seq.shifts[:3], log=log)
     finally:
         B.mdcnn_set_option(B.MDCNN_OPT_CONV_PATH, 0)
+
+
+@pytest.mark.parametrize("name", ["c3_resnet_96", "c3_resnet_plain_80x112", "c4_hrnet_128x96", "c5_bottleneck_40"])
+def test_fused_skip_equals_separate_launch(name):
+    """mdcnn_frame adds residual skips inside the delta kernel of their source; the
+    outputs must equal, bit for bit, those of one launch per edge."""
+    import gpu_harness as H
+    from paper_2210_09887_amd import binding as B
+    net, seq = load_case(name)
+    a = H.free_running(net, seq.frames, seq.shifts, seq.forced)
+    B.mdcnn_set_option(B.MDCNN_OPT_FUSE_SKIP, 0)
+    try:
+        b = H.free_running(net, seq.frames, seq.shifts, seq.forced)
+    finally:
+        B.mdcnn_set_option(B.MDCNN_OPT_FUSE_SKIP, 1)
+    for fa, fb in zip(a["outputs"], b["outputs"]):
+        for x, y in zip(fa, fb):
+            assert np.array_equal(x, y)
+    assert a["resets"] == b["resets"]
 
 
 def test_degenerate_frames():
