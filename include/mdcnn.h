@@ -172,6 +172,21 @@ mdcnn_status mdcnn_frame(mdcnn_net* net, const void* frame_dev, const uint8_t* f
                          int dty, int dtx, void* out_dev, size_t out_bytes, void* stream,
                          int* did_full_reset);
 
+/* The same for n_streams independent video streams in the same launches (the
+ * paper fills the GPU with a batch of streams [Evaluation: batch size]).  Stream b
+ * is nets[b]: all nets must have the same topology and the same site and edge
+ * shapes, each its own buffers (weights may be shared); they keep their own
+ * camera paths, masks and reset decisions.  All arrays are host arrays of
+ * n_streams entries (1 <= n_streams <= 16); frames_dev[b] / outs_dev[b] as in
+ * mdcnn_frame, out_bytes per stream; forced_masks_dev may be NULL or hold NULL
+ * entries; did_full_reset: n_streams ints or NULL.  The results of every stream
+ * are identical, bit for bit, to those of mdcnn_frame on it alone.
+ * Errors: MDCNN_ERR_SHAPE if the nets differ, MDCNN_ERR_STATE if two streams
+ * share a net or buffers, MDCNN_ERR_SIZE for n_streams out of range. */
+mdcnn_status mdcnn_frame_batch(mdcnn_net* const* nets, int n_streams, const void* const* frames_dev,
+                               const uint8_t* const* forced_masks_dev, const int* dty, const int* dtx,
+                               void* const* outs_dev, size_t out_bytes, void* stream, int* did_full_reset);
+
 /* View-ordered access to a site's state (independent of the ring origin). */
 typedef enum {
     MDCNN_VIEW_A = 0,        /* H*W*C storage dtype: accumulated values                     */

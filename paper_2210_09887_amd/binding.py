@@ -28,7 +28,7 @@ STATUS_NAMES = {0: "OK", 1: "ERR_NULL", 2: "ERR_SHAPE", 3: "ERR_DTYPE", 4: "ERR_
 
 EXPORTS = ["mdcnn_conv_border", "mdcnn_buffer_bytes", "mdcnn_create_buffer", "mdcnn_destroy_buffer",
            "mdcnn_shift_camera", "mdcnn_layer_forward", "mdcnn_net_create", "mdcnn_net_destroy",
-           "mdcnn_frame", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read",
+           "mdcnn_frame", "mdcnn_frame_batch", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read",
            "mdcnn_pack_weights", "mdcnn_last_error", "mdcnn_version"]
 
 
@@ -70,6 +70,7 @@ def lib():
                                        C.POINTER(vp)]
         L.mdcnn_net_destroy.argtypes = [vp]
         L.mdcnn_frame.argtypes = [vp, vp, vp, C.c_int, C.c_int, vp, sz, vp, ip]
+        L.mdcnn_frame_batch.argtypes = [C.POINTER(vp), C.c_int, C.POINTER(vp), C.POINTER(vp), ip, ip, C.POINTER(vp), sz, vp, ip]
         L.mdcnn_read_view.argtypes = [vp, C.c_int, vp, sz, vp]
         L.mdcnn_write_view.argtypes = [vp, C.c_int, vp, sz, vp]
         L.mdcnn_set_option.argtypes = [C.c_int, C.c_int]
@@ -168,6 +169,17 @@ def mdcnn_frame(net: int, frame_ptr: int, forced_ptr, dty: int, dtx: int, out_pt
     r = C.c_int()
     _check(lib().mdcnn_frame(net, frame_ptr, forced_ptr, int(dty), int(dtx), out_ptr, out_bytes, stream, C.byref(r)))
     return bool(r.value)
+
+
+def mdcnn_frame_batch(nets, frame_ptrs, forced_ptrs, dty, dtx, out_ptrs, out_bytes: int, stream: int = 0):
+    """One frame for len(nets) streams; returns the list of reset decisions."""
+    n = len(nets)
+    r = (C.c_int * n)()
+    forced = None if forced_ptrs is None else (C.c_void_p * n)(*forced_ptrs)
+    _check(lib().mdcnn_frame_batch(_handles(nets), n, (C.c_void_p * n)(*frame_ptrs), forced,
+                                   (C.c_int * n)(*[int(v) for v in dty]), (C.c_int * n)(*[int(v) for v in dtx]),
+                                   (C.c_void_p * n)(*out_ptrs), out_bytes, stream, r))
+    return [bool(v) for v in r]
 
 
 def mdcnn_read_view(buf: int, what: int, dst_ptr: int, nbytes: int, stream: int = 0):

@@ -222,7 +222,8 @@ __device__ __forceinline__ void map_tile(int u, int NT, int xcd_map, int& m, int
 // PIPE = 2: two LDS buffers and two register stages, loads two steps ahead
 //           (one barrier per step).
 template <int WM, int WN, int TM, int TN, int KC, int PIPE>
-__global__ __launch_bounds__(256) void k_conv_mfma_tiled(EdgeDev e, int NT, int work_items, int xcd_map) {
+__global__ __launch_bounds__(256) void k_conv_mfma_tiled(EdgeBatch eb, int NT, int work_items, int xcd_map) {
+    const EdgeDev& e = eb.d[blockIdx.z];                  // blockIdx.z: stream of the batch
     using Cfg = TiledCfg<WM, WN, TM, TN, KC, PIPE>;
     constexpr int BM = Cfg::BM, BN = Cfg::BN, LDK = Cfg::LDK, LDC = Cfg::LDC, CPR = Cfg::CPR, TPS = Cfg::TPS;
     constexpr int NB = (BM * CPR + 255) / 256, NA = (BN * CPR + 255) / 256;
@@ -508,7 +509,8 @@ struct HaloCfg {
 
 template <int NSUB, int WMV, int WK, int TM, int TN, int KC, int NLD_, int KS, int RING_ = 3, int MINB_ = (NSUB >= 2 ? 2 : 1)>
 __global__ __launch_bounds__(256, MINB_)
-void k_conv_halo(EdgeDev e, int NT, int work_items) {
+void k_conv_halo(EdgeBatch eb, int NT, int work_items) {
+    const EdgeDev& e = eb.d[blockIdx.z];                  // blockIdx.z: stream of the batch
     using Cfg = HaloCfg<NSUB, WMV, WK, TM, TN, KC, NLD_, KS, RING_, MINB_>;
     constexpr int SUB = Cfg::SUB, BN = Cfg::BN, KB = Cfg::KB, MB = Cfg::MB, NS = Cfg::NS, CPR = Cfg::CPR, NLD = Cfg::NLD,
                   LDK = Cfg::LDK, LDC = Cfg::LDC;
@@ -757,7 +759,8 @@ __global__ __launch_bounds__(256) void k_pack_weights(const f16* __restrict__ sr
 // lane updates its own pixel of P.  Fallback for Cin % 32 != 0.
 // ---------------------------------------------------------------------------
 template <int WN>
-__global__ __launch_bounds__(256) void k_conv_mfma_f16(EdgeDev e) {
+__global__ __launch_bounds__(256) void k_conv_mfma_f16(EdgeBatch eb) {
+    const EdgeDev& e = eb.d[blockIdx.z];                  // blockIdx.z: stream of the batch
     constexpr int WM = 4 / WN;
     constexpr int TILE_M = 32 * WM;
     constexpr int TPS = kSegPixels / TILE_M;
@@ -848,7 +851,8 @@ template <> struct Row8<float> {
 // of LDS.  Tiles of ppb entries never straddle a list segment.
 // ---------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void k_conv_ldsw(EdgeDev e, int groups, int ppb) {
+__global__ __launch_bounds__(256) void k_conv_ldsw(EdgeBatch eb, int groups, int ppb) {
+    const EdgeDev& e = eb.d[blockIdx.z];                  // blockIdx.z: stream of the batch
     extern __shared__ __align__(16) unsigned char smem[];
     float* sW = reinterpret_cast<float*>(smem);             // [tap][Cin][Cout]
     __shared__ int s_base[256], s_wy[256], s_wx[256];
@@ -909,7 +913,8 @@ __global__ __launch_bounds__(256) void k_conv_ldsw(EdgeDev e, int groups, int pp
 // broadcast from LDS ([tap][cin][cout], fp32).
 // ---------------------------------------------------------------------------
 template <typename T, int KK, int CIN, int CPT>
-__global__ __launch_bounds__(256) void k_conv_small(EdgeDev e, int groups, int ppb) {
+__global__ __launch_bounds__(256) void k_conv_small(EdgeBatch eb, int groups, int ppb) {
+    const EdgeDev& e = eb.d[blockIdx.z];                  // blockIdx.z: stream of the batch
     extern __shared__ __align__(16) unsigned char smem[];
     float* sW = reinterpret_cast<float*>(smem);             // [tap][CIN][Cout]
     __shared__ int s_base[256], s_wy[256], s_wx[256];
@@ -982,7 +987,8 @@ __global__ __launch_bounds__(256) void k_conv_small(EdgeDev e, int groups, int p
 // Block = 16 list entries x 16 cout lanes; each thread keeps 4 couts at a time.
 // ---------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void k_conv_plain(EdgeDev e) {
+__global__ __launch_bounds__(256) void k_conv_plain(EdgeBatch eb) {
+    const EdgeDev& e = eb.d[blockIdx.z];                  // blockIdx.z: stream of the batch
     __shared__ int s_base[16], s_wy[16], s_wx[16];
     __shared__ unsigned s_vm[16];
     __shared__ int sh[8];
@@ -1035,7 +1041,8 @@ __global__ __launch_bounds__(256) void k_conv_plain(EdgeDev e) {
 // Residual skip: P_dst[q] += delta[q] for every updated pixel q of the source.
 // One block per (list segment, group of 8 channel chunks).
 template <typename T, int VEC>
-__global__ __launch_bounds__(256) void k_identity(EdgeDev e) {
+__global__ __launch_bounds__(256) void k_identity(EdgeBatch eb) {
+    const EdgeDev& e = eb.d[blockIdx.z];                  // blockIdx.z: stream of the batch
     __shared__ int s_base[kSegPixels], s_wy[kSegPixels], s_wx[kSegPixels];
     __shared__ unsigned s_vm[kSegPixels];
     __shared__ int sh[8];
@@ -1067,7 +1074,8 @@ __global__ __launch_bounds__(256) void k_identity(EdgeDev e) {
 }
 
 // Compaction of the update mask alone (a forward call without outgoing edges).
-__global__ __launch_bounds__(256) void k_compact_source(EdgeDev e) {
+__global__ __launch_bounds__(256) void k_compact_source(EdgeBatch eb) {
+    const EdgeDev& e = eb.d[blockIdx.z];                  // blockIdx.z: stream of the batch
     __shared__ int sh[8];
     carry_source_compaction(e, sh);
 }
@@ -1082,7 +1090,8 @@ static unsigned cap_blocks(long long b, long long cap) {
 int g_tile = 0, g_pipe = 0, g_xcd = 1, g_kc = 0;
 
 template <int WM, int WN, int TM, int TN, int KC, int PIPE>
-static hipError_t launch_tiled(const EdgeDev& e, long long max_entries, hipStream_t st) {
+static hipError_t launch_tiled(const EdgeBatch& eb, int nb, long long max_entries, hipStream_t st) {
+    const EdgeDev& e = eb.d[0];
     using Cfg = TiledCfg<WM, WN, TM, TN, KC, PIPE>;
     static bool attr_set = false;
     auto kern = k_conv_mfma_tiled<WM, WN, TM, TN, KC, PIPE>;
@@ -1098,21 +1107,23 @@ static hipError_t launch_tiled(const EdgeDev& e, long long max_entries, hipStrea
     const long long items = xcd ? 8 * ((MT + 8 / NT - 1) / (8 / NT)) : MT * NT;
     unsigned g = cap_blocks(items, 4096);
     g = (g + 7u) & ~7u;                                    // whole rounds over the 8 XCDs
-    kern<<<dim3(g), dim3(256), Cfg::SMEM, st>>>(e, NT, (int)items, xcd);
+    kern<<<dim3(g, 1, nb), dim3(256), Cfg::SMEM, st>>>(eb, NT, (int)items, xcd);
     return hipGetLastError();
 }
 
 template <int WM, int WN, int TM, int TN, int KC>
-static hipError_t launch_tiled_p(const EdgeDev& e, long long max_entries, hipStream_t st) {
+static hipError_t launch_tiled_p(const EdgeBatch& eb, int nb, long long max_entries, hipStream_t st) {
+    const EdgeDev& e = eb.d[0];
     // measured on MI355X: with L2 latencies of ~200 cycles one step of prefetch is
     // enough; the second register stage only costs occupancy
     const bool deep = g_pipe == 2;
-    return deep ? launch_tiled<WM, WN, TM, TN, KC, 2>(e, max_entries, st)
-                : launch_tiled<WM, WN, TM, TN, KC, 1>(e, max_entries, st);
+    return deep ? launch_tiled<WM, WN, TM, TN, KC, 2>(eb, nb, max_entries, st)
+                : launch_tiled<WM, WN, TM, TN, KC, 1>(eb, nb, max_entries, st);
 }
 
 template <int KC>
-static hipError_t launch_tiled_kc(const EdgeDev& e, long long max_entries, hipStream_t st) {
+static hipError_t launch_tiled_kc(const EdgeBatch& eb, int nb, long long max_entries, hipStream_t st) {
+    const EdgeDev& e = eb.d[0];
     auto blocks = [&](int bm, int bn) { return ((max_entries + bm - 1) / bm) * (e.Cout / bn); };
     int tile = g_tile;
     if (tile == 0) {
@@ -1124,29 +1135,30 @@ static hipError_t launch_tiled_kc(const EdgeDev& e, long long max_entries, hipSt
         else tile = 6;
     }
     switch (tile) {
-        case 1: if (e.Cout % 64 == 0) return launch_tiled_p<4, 1, 2, 2, KC>(e, max_entries, st); break;    // 256 x 64
-        case 2: if (e.Cout % 64 == 0) return launch_tiled_p<2, 2, 2, 1, KC>(e, max_entries, st); break;    // 128 x 64
-        case 3: if (e.Cout % 64 == 0) return launch_tiled_p<2, 2, 1, 1, KC>(e, max_entries, st); break;    //  64 x 64
-        case 4: if (e.Cout % 128 == 0) return launch_tiled_p<2, 2, 2, 2, KC>(e, max_entries, st); break;   // 128 x 128
-        case 5: if (e.Cout % 128 == 0) return launch_tiled_p<2, 2, 1, 2, KC>(e, max_entries, st); break;   //  64 x 128
-        case 7: if (e.Cout % 128 == 0) return launch_tiled_p<4, 1, 1, 4, KC>(e, max_entries, st); break;   // 128 x 128, wave 32 x 128
-        case 8: if (e.Cout % 256 == 0) return launch_tiled_p<2, 2, 2, 4, KC>(e, max_entries, st); break;   // 128 x 256, wave 64 x 128
-        case 9: if (e.Cout % 256 == 0) return launch_tiled_p<1, 4, 2, 2, KC>(e, max_entries, st); break;   //  64 x 256, wave 64 x 64
-        case 10: if (e.Cout % 256 == 0) return launch_tiled_p<2, 2, 1, 4, KC>(e, max_entries, st); break;  //  64 x 256, wave 32 x 128
-        case 11: if (e.Cout % 128 == 0) return launch_tiled_p<1, 4, 1, 1, KC>(e, max_entries, st); break;  //  32 x 128
-        case 12: if (e.Cout % 256 == 0) return launch_tiled_p<1, 4, 1, 2, KC>(e, max_entries, st); break;  //  32 x 256
-        case 13: if (e.Cout % 128 == 0) return launch_tiled_p<1, 4, 2, 1, KC>(e, max_entries, st); break;  //  64 x 128, wave 64 x 32
-        case 14: if (e.Cout % 64 == 0) return launch_tiled_p<1, 4, 2, 1, 32>(e, max_entries, st); break;   //  same, 32-channel steps
+        case 1: if (e.Cout % 64 == 0) return launch_tiled_p<4, 1, 2, 2, KC>(eb, nb, max_entries, st); break;    // 256 x 64
+        case 2: if (e.Cout % 64 == 0) return launch_tiled_p<2, 2, 2, 1, KC>(eb, nb, max_entries, st); break;    // 128 x 64
+        case 3: if (e.Cout % 64 == 0) return launch_tiled_p<2, 2, 1, 1, KC>(eb, nb, max_entries, st); break;    //  64 x 64
+        case 4: if (e.Cout % 128 == 0) return launch_tiled_p<2, 2, 2, 2, KC>(eb, nb, max_entries, st); break;   // 128 x 128
+        case 5: if (e.Cout % 128 == 0) return launch_tiled_p<2, 2, 1, 2, KC>(eb, nb, max_entries, st); break;   //  64 x 128
+        case 7: if (e.Cout % 128 == 0) return launch_tiled_p<4, 1, 1, 4, KC>(eb, nb, max_entries, st); break;   // 128 x 128, wave 32 x 128
+        case 8: if (e.Cout % 256 == 0) return launch_tiled_p<2, 2, 2, 4, KC>(eb, nb, max_entries, st); break;   // 128 x 256, wave 64 x 128
+        case 9: if (e.Cout % 256 == 0) return launch_tiled_p<1, 4, 2, 2, KC>(eb, nb, max_entries, st); break;   //  64 x 256, wave 64 x 64
+        case 10: if (e.Cout % 256 == 0) return launch_tiled_p<2, 2, 1, 4, KC>(eb, nb, max_entries, st); break;  //  64 x 256, wave 32 x 128
+        case 11: if (e.Cout % 128 == 0) return launch_tiled_p<1, 4, 1, 1, KC>(eb, nb, max_entries, st); break;  //  32 x 128
+        case 12: if (e.Cout % 256 == 0) return launch_tiled_p<1, 4, 1, 2, KC>(eb, nb, max_entries, st); break;  //  32 x 256
+        case 13: if (e.Cout % 128 == 0) return launch_tiled_p<1, 4, 2, 1, KC>(eb, nb, max_entries, st); break;  //  64 x 128, wave 64 x 32
+        case 14: if (e.Cout % 64 == 0) return launch_tiled_p<1, 4, 2, 1, 32>(eb, nb, max_entries, st); break;   //  same, 32-channel steps
         default: break;
     }
-    return launch_tiled_p<4, 1, 1, 1, KC>(e, max_entries, st);                                             // 128 x 32
+    return launch_tiled_p<4, 1, 1, 1, KC>(eb, nb, max_entries, st);                                             // 128 x 32
 }
 
 int g_halo = 1;          // 0: never use the halo-staged kernel, 2: force 32-cout tiles
 int g_halo_sub = 0;      // 0: auto, 1 / 2 / 4: tiles per list segment of the halo-staged kernel
 
 template <int NSUB, int WMV, int WK, int TM, int TN, int KC, int NLD, int RING = 3, int MINB = (NSUB >= 2 ? 2 : 1)>
-static hipError_t launch_halo_t(const EdgeDev& e, long long nseg, hipStream_t st) {
+static hipError_t launch_halo_t(const EdgeBatch& eb, int nb, long long nseg, hipStream_t st) {
+    const EdgeDev& e = eb.d[0];
     using Cfg = HaloCfg<NSUB, WMV, WK, TM, TN, KC, NLD, 3, RING, MINB>;
     static bool attr_set = false;
     auto kern = k_conv_halo<NSUB, WMV, WK, TM, TN, KC, NLD, 3, RING, MINB>;
@@ -1157,7 +1169,7 @@ static hipError_t launch_halo_t(const EdgeDev& e, long long nseg, hipStream_t st
     }
     const int NT = e.Cout / Cfg::BN;
     const long long items = nseg * NSUB * NT;
-    kern<<<dim3(cap_blocks(items, 16384)), dim3(256), Cfg::SMEM, st>>>(e, NT, (int)items);
+    kern<<<dim3(cap_blocks(items, 16384), 1, nb), dim3(256), Cfg::SMEM, st>>>(eb, NT, (int)items);
     return hipGetLastError();
 }
 
@@ -1176,7 +1188,8 @@ static long long halo_worst(const EdgeDev& e, int sub) {
 // least half of the compute units busy (measured: finer splits re-read the weights
 // more often than the extra parallelism pays back).
 template <int TN>
-static hipError_t launch_halo_n(const EdgeDev& e, long long nseg, hipStream_t st, bool* done) {
+static hipError_t launch_halo_n(const EdgeBatch& eb, int nb, long long nseg, hipStream_t st, bool* done) {
+    const EdgeDev& e = eb.d[0];
     const long long per_split = nseg * (e.Cout / (32 * TN));
     int nsub = g_halo_sub ? g_halo_sub : (per_split >= 256 ? 1 : per_split * 2 >= 128 ? 2 : 4);
     *done = true;
@@ -1184,25 +1197,26 @@ static hipError_t launch_halo_n(const EdgeDev& e, long long nseg, hipStream_t st
         const long long worst = halo_worst(e, kSegPixels / nsub);
         const bool c64 = e.Cin % 64 == 0, c32 = e.Cin % 32 == 0;
         if (nsub == 1) {
-            if (c64 && worst <= HaloCfg<1, 2, 2, 4, TN, 64, 16, 3>::CAP) return launch_halo_t<1, 2, 2, 4, TN, 64, 16>(e, nseg, st);
-            if (c32 && worst <= HaloCfg<1, 2, 2, 4, TN, 32, 12, 3>::CAP) return launch_halo_t<1, 2, 2, 4, TN, 32, 12>(e, nseg, st);
+            if (c64 && worst <= HaloCfg<1, 2, 2, 4, TN, 64, 16, 3>::CAP) return launch_halo_t<1, 2, 2, 4, TN, 64, 16>(eb, nb, nseg, st);
+            if (c32 && worst <= HaloCfg<1, 2, 2, 4, TN, 32, 12, 3>::CAP) return launch_halo_t<1, 2, 2, 4, TN, 32, 12>(eb, nb, nseg, st);
         } else if (nsub == 2) {
-            if (c64 && worst <= HaloCfg<2, 2, 2, 2, TN, 64, 11, 3>::CAP) return launch_halo_t<2, 2, 2, 2, TN, 64, 11>(e, nseg, st);
-            if (c32 && worst <= HaloCfg<2, 2, 2, 2, TN, 32, 9, 3>::CAP) return launch_halo_t<2, 2, 2, 2, TN, 32, 9>(e, nseg, st);
+            if (c64 && worst <= HaloCfg<2, 2, 2, 2, TN, 64, 11, 3>::CAP) return launch_halo_t<2, 2, 2, 2, TN, 64, 11>(eb, nb, nseg, st);
+            if (c32 && worst <= HaloCfg<2, 2, 2, 2, TN, 32, 9, 3>::CAP) return launch_halo_t<2, 2, 2, 2, TN, 32, 9>(eb, nb, nseg, st);
         } else {
-            if (c64 && worst <= HaloCfg<4, 1, 4, 2, TN, 64, 9, 3>::CAP) return launch_halo_t<4, 1, 4, 2, TN, 64, 9>(e, nseg, st);
-            if (c32 && worst <= HaloCfg<4, 2, 2, 1, TN, 32, 6, 3>::CAP) return launch_halo_t<4, 2, 2, 1, TN, 32, 6>(e, nseg, st);
+            if (c64 && worst <= HaloCfg<4, 1, 4, 2, TN, 64, 9, 3>::CAP) return launch_halo_t<4, 1, 4, 2, TN, 64, 9>(eb, nb, nseg, st);
+            if (c32 && worst <= HaloCfg<4, 2, 2, 1, TN, 32, 6, 3>::CAP) return launch_halo_t<4, 2, 2, 1, TN, 32, 6>(eb, nb, nseg, st);
         }
     }
     *done = false;
     return hipSuccess;
 }
 
-static hipError_t launch_halo(const EdgeDev& e, long long nseg, hipStream_t st, bool* done) {
+static hipError_t launch_halo(const EdgeBatch& eb, int nb, long long nseg, hipStream_t st, bool* done) {
+    const EdgeDev& e = eb.d[0];
     *done = false;
     if (!g_halo || !e.wp || e.k != 3 || e.stride != 1 || e.up != 0 || e.Cin % 16 || e.Cout % 32) return hipSuccess;
     if ((long long)e.sH * e.sW * e.Cin >= (1ll << 31)) return hipSuccess;      // 32-bit staging offsets
-    return e.Cout % 64 == 0 && g_halo != 2 ? launch_halo_n<2>(e, nseg, st, done) : launch_halo_n<1>(e, nseg, st, done);
+    return e.Cout % 64 == 0 && g_halo != 2 ? launch_halo_n<2>(eb, nb, nseg, st, done) : launch_halo_n<1>(eb, nb, nseg, st, done);
 }
 
 hipError_t launch_pack_weights(const void* src, void* dst, int taps, int Cout, int Cin, hipStream_t st) {
@@ -1212,7 +1226,8 @@ hipError_t launch_pack_weights(const void* src, void* dst, int taps, int Cout, i
 }
 
 template <typename T>
-static hipError_t launch_ldsw(const EdgeDev& e, long long max_entries, hipStream_t st) {
+static hipError_t launch_ldsw(const EdgeBatch& eb, int nb, long long max_entries, hipStream_t st) {
+    const EdgeDev& e = eb.d[0];
     static size_t attr_bytes = 0;
     const int groups = e.Cout / 8, ppb = 256 / groups;
     const size_t smem = (size_t)e.k * e.k * e.Cin * e.Cout * 4;
@@ -1226,27 +1241,28 @@ static hipError_t launch_ldsw(const EdgeDev& e, long long max_entries, hipStream
     const long long tps = (kSegPixels + ppb - 1) / ppb;
     // weights are staged once per block: keep the blocks few and persistent
     unsigned g = cap_blocks(nseg * tps, smem > 32768 ? 256 : 768);
-    kern<<<dim3(g), dim3(256), smem, st>>>(e, groups, ppb);
+    kern<<<dim3(g, 1, nb), dim3(256), smem, st>>>(eb, groups, ppb);
     return hipGetLastError();
 }
 
-hipError_t launch_conv(const EdgeDev& e, int dtype, int conv_path, hipStream_t st, int* cls) {
+hipError_t launch_conv(const EdgeBatch& eb, int nb, int dtype, int conv_path, hipStream_t st, int* cls) {
+    const EdgeDev& e = eb.d[0];                            // geometry and weights layout are the same for all streams
     const long long max_entries = e.up ? (long long)e.sH * e.sW : (long long)e.Hp * e.Wp;
     const long long nseg = (max_entries + kSegPixels - 1) / kSegPixels;
     if (e.k < 0) {                                         // no operator: source compaction only
         *cls = kClsLists;
-        k_compact_source<<<dim3(cap_blocks(((long long)e.sH * e.sW + kSegPixels - 1) / kSegPixels, 4096)), dim3(256), 0, st>>>(e);
+        k_compact_source<<<dim3(cap_blocks(((long long)e.sH * e.sW + kSegPixels - 1) / kSegPixels, 4096), 1, nb), dim3(256), 0, st>>>(eb);
         return hipGetLastError();
     }
     if (e.k == 0) {
         *cls = kClsIdentity;
         const unsigned g = cap_blocks(nseg, 4096);
         if (dtype == MDCNN_F16) {
-            if (e.Cin % 8 == 0) k_identity<f16, 8><<<dim3(g, (e.Cin / 8 + 7) / 8), dim3(256), 0, st>>>(e);
-            else k_identity<f16, 1><<<dim3(g, (e.Cin + 7) / 8), dim3(256), 0, st>>>(e);
+            if (e.Cin % 8 == 0) k_identity<f16, 8><<<dim3(g, (e.Cin / 8 + 7) / 8, nb), dim3(256), 0, st>>>(eb);
+            else k_identity<f16, 1><<<dim3(g, (e.Cin + 7) / 8, nb), dim3(256), 0, st>>>(eb);
         } else {
-            if (e.Cin % 4 == 0) k_identity<float, 4><<<dim3(g, (e.Cin / 4 + 7) / 8), dim3(256), 0, st>>>(e);
-            else k_identity<float, 1><<<dim3(g, (e.Cin + 7) / 8), dim3(256), 0, st>>>(e);
+            if (e.Cin % 4 == 0) k_identity<float, 4><<<dim3(g, (e.Cin / 4 + 7) / 8, nb), dim3(256), 0, st>>>(eb);
+            else k_identity<float, 1><<<dim3(g, (e.Cin + 7) / 8, nb), dim3(256), 0, st>>>(eb);
         }
         return hipGetLastError();
     }
@@ -1254,20 +1270,20 @@ hipError_t launch_conv(const EdgeDev& e, int dtype, int conv_path, hipStream_t s
     const bool mfma_ok = dtype == MDCNN_F16 && conv_path != 1 && e.Cin % 16 == 0 && e.Cout % 32 == 0;
     if (mfma_ok && conv_path == 0) {
         bool done = false;
-        const hipError_t err = launch_halo(e, nseg, st, &done);
+        const hipError_t err = launch_halo(eb, nb, nseg, st, &done);
         if (done) { *cls = kClsConvMfma; return err; }
     }
     if (mfma_ok && (conv_path == 0 || conv_path == 3) && e.Cin % 32 == 0) {
         *cls = kClsConvMfma;
-        if (e.Cin % 128 == 0 && g_kc != 64) return launch_tiled_kc<128>(e, max_entries, st);
-        return e.Cin % 64 == 0 ? launch_tiled_kc<64>(e, max_entries, st) : launch_tiled_kc<32>(e, max_entries, st);
+        if (e.Cin % 128 == 0 && g_kc != 64) return launch_tiled_kc<128>(eb, nb, max_entries, st);
+        return e.Cin % 64 == 0 ? launch_tiled_kc<64>(eb, nb, max_entries, st) : launch_tiled_kc<32>(eb, nb, max_entries, st);
     }
     if (mfma_ok) {
         *cls = kClsConvMfma;
         if (e.Cout % 64 == 0)
-            k_conv_mfma_f16<2><<<dim3(cap_blocks(nseg * (kSegPixels / 64), 4096), e.Cout / 64), dim3(256), 0, st>>>(e);
+            k_conv_mfma_f16<2><<<dim3(cap_blocks(nseg * (kSegPixels / 64), 4096), e.Cout / 64, nb), dim3(256), 0, st>>>(eb);
         else
-            k_conv_mfma_f16<1><<<dim3(cap_blocks(nseg * (kSegPixels / 128), 4096), e.Cout / 32), dim3(256), 0, st>>>(e);
+            k_conv_mfma_f16<1><<<dim3(cap_blocks(nseg * (kSegPixels / 128), 4096), e.Cout / 32, nb), dim3(256), 0, st>>>(eb);
         return hipGetLastError();
     }
     *cls = kClsConvPlain;
@@ -1276,16 +1292,16 @@ hipError_t launch_conv(const EdgeDev& e, int dtype, int conv_path, hipStream_t s
         const size_t smem = (size_t)27 * e.Cout * 4;
         const long long tps = (kSegPixels + ppb - 1) / ppb;
         const unsigned g = cap_blocks(nseg * tps, 2048);
-        if (dtype == MDCNN_F16) k_conv_small<f16, 3, 3, 32><<<dim3(g), dim3(256), smem, st>>>(e, groups, ppb);
-        else k_conv_small<float, 3, 3, 32><<<dim3(g), dim3(256), smem, st>>>(e, groups, ppb);
+        if (dtype == MDCNN_F16) k_conv_small<f16, 3, 3, 32><<<dim3(g, 1, nb), dim3(256), smem, st>>>(eb, groups, ppb);
+        else k_conv_small<float, 3, 3, 32><<<dim3(g, 1, nb), dim3(256), smem, st>>>(eb, groups, ppb);
         return hipGetLastError();
     }
     const int groups = e.Cout / 8;
     if ((conv_path == 0 || conv_path == 3) && e.Cout % 8 == 0 && groups <= 64 && (size_t)e.k * e.k * e.Cin * e.Cout * 4 <= 150 * 1024)
-        return dtype == MDCNN_F16 ? launch_ldsw<f16>(e, max_entries, st) : launch_ldsw<float>(e, max_entries, st);
+        return dtype == MDCNN_F16 ? launch_ldsw<f16>(eb, nb, max_entries, st) : launch_ldsw<float>(eb, nb, max_entries, st);
     unsigned g = cap_blocks(nseg * (kSegPixels / 16), 8192);
-    if (dtype == MDCNN_F16) k_conv_plain<f16><<<dim3(g), dim3(256), 0, st>>>(e);
-    else k_conv_plain<float><<<dim3(g), dim3(256), 0, st>>>(e);
+    if (dtype == MDCNN_F16) k_conv_plain<f16><<<dim3(g, 1, nb), dim3(256), 0, st>>>(eb);
+    else k_conv_plain<float><<<dim3(g, 1, nb), dim3(256), 0, st>>>(eb);
     return hipGetLastError();
 }
 

@@ -138,8 +138,8 @@ __global__ __launch_bounds__(256) void k_shift_fill(FillBatch fb) {
     if (lb == 0 && j.reset_counters && (int)threadIdx.x < (j.reset_counters == 2 ? kNumCounters : kNumPerFrame))
         j.counters[threadIdx.x] = 0;
     if (lb == 0 && j.reset_counters == 2) {                // first reset: clear the per-segment running sums
-        for (int i = threadIdx.x; i < j.n_lacc; i += 256) j.lacc[i] = 0ull;
-        for (int i = threadIdx.x; i < j.n_cacc; i += 256) j.cacc[i] = 0ull;
+        for (int i = threadIdx.x; i < j.n_lacc; i += 256) { j.lacc[i] = 0ull; j.lcnt[i] = 0; }
+        for (int i = threadIdx.x; i < j.n_cacc; i += 256) { j.cacc[i] = 0ull; j.ccnt[i] = 0; }
     }
     if (j.dtype == MDCNN_F16) {
         if (j.C % 8 == 0) fill_items<f16, 8>(j, lb); else fill_items<f16, 1>(j, lb);
@@ -164,8 +164,11 @@ hipError_t launch_shift_fill(const FillBatch& fb, hipStream_t st) {
 // The block writes its update / candidate counts for the compaction pass.
 // ---------------------------------------------------------------------------
 template <typename T, int G, int CH>
-__global__ __launch_bounds__(256) void k_step1(SiteDev s, const T* __restrict__ X,
-                                               const uint8_t* __restrict__ forced, SkipDev skip) {
+__global__ __launch_bounds__(256) void k_step1(Step1Batch bt) {
+    const SiteDev& s = bt.s[blockIdx.z];
+    const SkipDev& skip = bt.skip[blockIdx.z];
+    const T* __restrict__ X = (const T*)bt.X[blockIdx.z];
+    const uint8_t* __restrict__ forced = bt.forced[blockIdx.z];
     constexpr int VEC = V16<T>::N;
     constexpr int PPB = 256 / G;
     const int tid = threadIdx.x;
@@ -242,8 +245,11 @@ __global__ __launch_bounds__(256) void k_step1(SiteDev s, const T* __restrict__ 
 
 // Any channel count: one lane per pixel, scalar accesses.
 template <typename T>
-__global__ __launch_bounds__(256) void k_step1_scalar(SiteDev s, const T* __restrict__ X,
-                                                      const uint8_t* __restrict__ forced, SkipDev skip) {
+__global__ __launch_bounds__(256) void k_step1_scalar(Step1Batch bt) {
+    const SiteDev& s = bt.s[blockIdx.z];
+    const SkipDev& skip = bt.skip[blockIdx.z];
+    const T* __restrict__ X = (const T*)bt.X[blockIdx.z];
+    const uint8_t* __restrict__ forced = bt.forced[blockIdx.z];
     const int tid = threadIdx.x;
     const int pix = blockIdx.x * 256 + tid;
     const int HW = s.H * s.W;
@@ -309,40 +315,40 @@ static bool step1_shape(int C, int vec, int& G, int& CH) {
 }
 
 template <typename T, int G>
-static void step1_g(const SiteDev& s, const T* X, const uint8_t* forced, const SkipDev& skip, int CH, dim3 grid, hipStream_t st) {
+static void step1_g(const Step1Batch& bt, int CH, dim3 grid, hipStream_t st) {
     switch (CH) {
-        case 1: k_step1<T, G, 1><<<grid, dim3(256), 0, st>>>(s, X, forced, skip); break;
-        case 2: k_step1<T, G, 2><<<grid, dim3(256), 0, st>>>(s, X, forced, skip); break;
-        case 3: k_step1<T, G, 3><<<grid, dim3(256), 0, st>>>(s, X, forced, skip); break;
-        default: k_step1<T, G, 4><<<grid, dim3(256), 0, st>>>(s, X, forced, skip); break;
+        case 1: k_step1<T, G, 1><<<grid, dim3(256), 0, st>>>(bt); break;
+        case 2: k_step1<T, G, 2><<<grid, dim3(256), 0, st>>>(bt); break;
+        case 3: k_step1<T, G, 3><<<grid, dim3(256), 0, st>>>(bt); break;
+        default: k_step1<T, G, 4><<<grid, dim3(256), 0, st>>>(bt); break;
     }
 }
 
 template <typename T>
-static hipError_t step1_t(const SiteDev& s, const void* frame, const uint8_t* forced, const SkipDev& skip, hipStream_t st) {
+static hipError_t step1_t(const Step1Batch& bt, int n, hipStream_t st) {
     int G = 0, CH = 0;
-    const T* X = (const T*)frame;
+    const SiteDev& s = bt.s[0];
     const int HW = s.H * s.W;
     if (!step1_shape(s.C, V16<T>::N, G, CH)) {
-        k_step1_scalar<T><<<dim3((HW + 255) / 256), dim3(256), 0, st>>>(s, X, forced, skip);
+        k_step1_scalar<T><<<dim3((HW + 255) / 256, 1, n), dim3(256), 0, st>>>(bt);
         return hipGetLastError();
     }
     const int ppb = 256 / G;
-    dim3 grid((HW + ppb - 1) / ppb);
+    dim3 grid((HW + ppb - 1) / ppb, 1, n);
     switch (G) {
-        case 1: step1_g<T, 1>(s, X, forced, skip, CH, grid, st); break;
-        case 2: step1_g<T, 2>(s, X, forced, skip, CH, grid, st); break;
-        case 4: step1_g<T, 4>(s, X, forced, skip, CH, grid, st); break;
-        case 8: step1_g<T, 8>(s, X, forced, skip, CH, grid, st); break;
-        case 16: step1_g<T, 16>(s, X, forced, skip, CH, grid, st); break;
-        case 32: step1_g<T, 32>(s, X, forced, skip, CH, grid, st); break;
-        default: step1_g<T, 64>(s, X, forced, skip, CH, grid, st); break;
+        case 1: step1_g<T, 1>(bt, CH, grid, st); break;
+        case 2: step1_g<T, 2>(bt, CH, grid, st); break;
+        case 4: step1_g<T, 4>(bt, CH, grid, st); break;
+        case 8: step1_g<T, 8>(bt, CH, grid, st); break;
+        case 16: step1_g<T, 16>(bt, CH, grid, st); break;
+        case 32: step1_g<T, 32>(bt, CH, grid, st); break;
+        default: step1_g<T, 64>(bt, CH, grid, st); break;
     }
     return hipGetLastError();
 }
 
-hipError_t launch_step1(const SiteDev& s, const void* frame, const uint8_t* forced, const SkipDev& skip, hipStream_t st) {
-    return s.dtype == MDCNN_F16 ? step1_t<f16>(s, frame, forced, skip, st) : step1_t<float>(s, frame, forced, skip, st);
+hipError_t launch_step1(const Step1Batch& bt, int n, hipStream_t st) {
+    return bt.s[0].dtype == MDCNN_F16 ? step1_t<f16>(bt, n, st) : step1_t<float>(bt, n, st);
 }
 
 // ---------------------------------------------------------------------------

@@ -214,21 +214,33 @@ mdcnn_status validate_forward(const mdcnn_buffer* in, const void* frame, const m
     return MDCNN_OK;
 }
 
+// One forward call for `n` streams of the same network at once (n <= kMaxBatch;
+// the caller has checked that all streams have the same shapes): stream b goes
+// from ins[b] along edges[b][0 .. n_edges) to outs[b][0 .. n_edges).
 // fuse_skip: index of an identity edge whose add is done by the step-1 kernel (its
 // destination is touched there and the edge gets no launch of its own), or -1.
-mdcnn_status do_forward(mdcnn_buffer* in, const void* frame, const uint8_t* forced, const mdcnn_conv_desc* edges,
-                        mdcnn_buffer* const* outs, int n_edges, hipStream_t st, int fuse_skip = -1) {
-    SkipDev skip{};
-    if (fuse_skip >= 0) {
-        const mdcnn_buffer* d = outs[fuse_skip];
-        skip.P = d->dev.P;
-        skip.dflags = d->d.kind == MDCNN_SITE_OUTPUT ? nullptr : d->dev.flags;
-        skip.Hp = d->L.Hp; skip.Wp = d->L.Wp; skip.by0 = d->d.border[0]; skip.bx0 = d->d.border[2];
-        skip.p_oy = d->dev.p_oy; skip.p_ox = d->dev.p_ox;
+mdcnn_status do_forward(int n, mdcnn_buffer* const* ins, const void* const* frames, const uint8_t* const* forced,
+                        const mdcnn_conv_desc* const* edges, mdcnn_buffer* const* const* outs, int n_edges,
+                        hipStream_t st, int fuse_skip = -1) {
+    static Step1Batch sb;                                  // 3.4 KiB each: kept off the stack
+    static EdgeBatch eb;
+    for (int b = 0; b < n; ++b) {
+        sb.s[b] = ins[b]->dev;
+        sb.X[b] = frames ? frames[b] : nullptr;
+        sb.forced[b] = forced ? forced[b] : nullptr;
+        sb.skip[b] = SkipDev{};
+        if (fuse_skip >= 0) {
+            const mdcnn_buffer* d = outs[b][fuse_skip];
+            SkipDev& k = sb.skip[b];
+            k.P = d->dev.P;
+            k.dflags = d->d.kind == MDCNN_SITE_OUTPUT ? nullptr : d->dev.flags;
+            k.Hp = d->L.Hp; k.Wp = d->L.Wp; k.by0 = d->d.border[0]; k.bx0 = d->d.border[2];
+            k.p_oy = d->dev.p_oy; k.p_ox = d->dev.p_ox;
+        }
     }
-    hipError_t err = timed(kClsStep1, st, [&] { return launch_step1(in->dev, frame, forced, skip, st); });
+    hipError_t err = timed(kClsStep1, st, [&] { return launch_step1(sb, n, st); });
     if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "step-1 launch: %s", hipGetErrorString(err));
-    auto launch_edge = [&](EdgeDev& e, int idx) -> mdcnn_status {
+    auto launch_edge = [&](int idx) -> mdcnn_status {
         int cls = kClsConvPlain;
         TimedLaunch t{0, nullptr, nullptr};
         if (g_profile) {              // the class is known only after dispatch: record around, file under it
@@ -237,7 +249,7 @@ mdcnn_status do_forward(mdcnn_buffer* in, const void* frame, const uint8_t* forc
             if (!t.start || !t.stop) return fail(MDCNN_ERR_HIP, "cannot create profiling events");
             (void)hipEventRecord(t.start, st);
         }
-        err = launch_conv(e, in->d.dtype, g_conv_path, st, &cls);
+        err = launch_conv(eb, n, ins[0]->d.dtype, g_conv_path, st, &cls);
         if (g_profile) {
             (void)hipEventRecord(t.stop, st);
             t.cls = cls;
@@ -246,20 +258,103 @@ mdcnn_status do_forward(mdcnn_buffer* in, const void* frame, const uint8_t* forc
         if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "conv launch (edge %d): %s", idx, hipGetErrorString(err));
         return MDCNN_OK;
     };
+    auto with_source_list = [&](EdgeDev& e, const mdcnn_buffer* in) {
+        e.pub_list = in->dev.list; e.pub_lcnt = in->dev.lcnt; e.pub_lacc = in->dev.lacc;
+    };
     if (n_edges == 0 || (n_edges == 1 && fuse_skip == 0)) {
-        EdgeDev e{};
-        e.sflags = in->dev.flags; e.sH = in->d.H; e.sW = in->d.W;
-        e.pub_list = in->dev.list; e.pub_lcnt = in->dev.lcnt; e.pub_lacc = in->dev.lacc; e.scounters = in->dev.counters;
-        e.k = -1;
-        return launch_edge(e, -1);
+        for (int b = 0; b < n; ++b) {
+            EdgeDev e{};
+            e.sflags = ins[b]->dev.flags; e.sH = ins[b]->d.H; e.sW = ins[b]->d.W;
+            e.scounters = ins[b]->dev.counters;
+            with_source_list(e, ins[b]);
+            e.k = -1;
+            eb.d[b] = e;
+        }
+        return launch_edge(-1);
     }
     bool first = true;
     for (int i = 0; i < n_edges; ++i) {
         if (i == fuse_skip) continue;
-        EdgeDev e = make_edge(in, outs[i], edges[i]);
-        if (first) { e.pub_list = in->dev.list; e.pub_lcnt = in->dev.lcnt; e.pub_lacc = in->dev.lacc; first = false; }
-        mdcnn_status rc = launch_edge(e, i);
+        for (int b = 0; b < n; ++b) {
+            eb.d[b] = make_edge(ins[b], outs[b][i], edges[b][i]);
+            if (first) with_source_list(eb.d[b], ins[b]);
+        }
+        first = false;
+        mdcnn_status rc = launch_edge(i);
         if (rc) return rc;
+    }
+    return MDCNN_OK;
+}
+
+// Two networks can share launches if they have the same topology and the same
+// site and edge shapes (weights and buffers may differ).
+bool same_shape(const mdcnn_net* a, const mdcnn_net* b) {
+    if (a->sites.size() != b->sites.size() || a->esrc != b->esrc || a->edst != b->edst) return false;
+    for (size_t i = 0; i < a->sites.size(); ++i) {
+        const mdcnn_buffer_desc &x = a->sites[i]->d, &y = b->sites[i]->d;
+        if (x.H != y.H || x.W != y.W || x.C != y.C || x.dtype != y.dtype || x.kind != y.kind || x.relu != y.relu ||
+            x.border[0] != y.border[0] || x.border[1] != y.border[1] || x.border[2] != y.border[2] || x.border[3] != y.border[3])
+            return false;
+    }
+    for (size_t i = 0; i < a->edges.size(); ++i) {
+        const mdcnn_conv_desc &x = a->edges[i], &y = b->edges[i];
+        if (x.k != y.k || x.stride != y.stride || x.pad != y.pad || x.Cin != y.Cin || x.Cout != y.Cout || x.up != y.up ||
+            (x.w_packed_dev == nullptr) != (y.w_packed_dev == nullptr))
+            return false;
+    }
+    return true;
+}
+
+// Shift, forward over all non-terminal sites, readout: for n streams at once.
+mdcnn_status frame_batch(mdcnn_net* const* nets, int n, const void* const* frames, const uint8_t* const* forced,
+                         const int* dty, const int* dtx, void* const* outs_dev, void* stream, int* did_full_reset) {
+    hipStream_t st = (hipStream_t)stream;
+    for (int b = 0; b < n; ++b) {
+        mdcnn_status rc = mdcnn_shift_camera(nets[b]->sites.data(), (int)nets[b]->sites.size(), dty[b], dtx[b], stream,
+                                             did_full_reset ? did_full_reset + b : nullptr);
+        if (rc) return rc;
+    }
+    const mdcnn_net* net = nets[0];
+    const int n_edges = (int)net->edges.size();
+    int e0 = 0;
+    std::vector<mdcnn_buffer*> outs_flat;
+    mdcnn_buffer* ins[kMaxBatch];
+    const mdcnn_conv_desc* edges[kMaxBatch];
+    mdcnn_buffer* const* outs[kMaxBatch];
+    for (int i = 0; i < (int)net->sites.size(); ++i) {
+        if (net->sites[i]->d.kind == MDCNN_SITE_OUTPUT) continue;
+        int e1 = e0;
+        while (e1 < n_edges && net->esrc[e1] == i) ++e1;
+        const int ne = e1 - e0;
+        outs_flat.resize((size_t)n * (ne > 0 ? ne : 1));
+        for (int b = 0; b < n; ++b) {
+            ins[b] = nets[b]->sites[i];
+            edges[b] = nets[b]->edges.data() + e0;
+            for (int e = e0; e < e1; ++e) outs_flat[(size_t)b * ne + (e - e0)] = nets[b]->sites[net->edst[e]];
+            outs[b] = outs_flat.data() + (size_t)b * ne;
+        }
+        // a residual skip is added by the step-1 kernel of its source; its place in the
+        // order of the producers of its destination stays the same as long as no other
+        // edge of this call goes to the same destination before it
+        int fuse = -1;
+        for (int e = e0; e < e1 && g_fuse_skip && fuse < 0; ++e) {
+            if (net->edges[e].k != 0) continue;
+            bool earlier = false;
+            for (int q = e0; q < e; ++q) earlier |= net->edst[q] == net->edst[e];
+            if (!earlier) fuse = e - e0;
+        }
+        mdcnn_status rc = do_forward(n, ins, i == 0 ? frames : nullptr, i == 0 ? forced : nullptr, edges, outs, ne, st, fuse);
+        if (rc) return rc;
+        e0 = e1;
+    }
+    for (int b = 0; b < n; ++b) {
+        char* o = (char*)outs_dev[b];
+        for (mdcnn_buffer* s : nets[b]->sites) {
+            if (s->d.kind != MDCNN_SITE_OUTPUT) continue;
+            hipError_t err = timed(kClsReadout, st, [&] { return launch_read_view(s->dev, MDCNN_VIEW_OUT, o, st); });
+            if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "readout launch: %s", hipGetErrorString(err));
+            o += (size_t)s->d.H * s->d.W * s->d.C * esize(s->d.dtype);
+        }
     }
     return MDCNN_OK;
 }
@@ -409,7 +504,8 @@ mdcnn_status mdcnn_shift_camera(mdcnn_buffer* const* bufs, int n, int dty, int d
         refresh_origins(b);
         FillJob j{};
         j.A = b->dev.A; j.P = b->dev.P; j.flags = b->dev.flags; j.bias = b->dev.bias; j.counters = b->dev.counters;
-        j.lacc = b->dev.lacc; j.cacc = b->dev.cacc; j.n_lacc = 2 * b->L.nseg_l; j.n_cacc = b->L.nseg_c;
+        j.lacc = b->dev.lacc; j.cacc = b->dev.cacc; j.lcnt = b->dev.lcnt; j.ccnt = b->dev.ccnt;
+        j.n_lacc = 2 * b->L.nseg_l; j.n_cacc = b->L.nseg_c;
         j.H = d.H; j.W = d.W; j.C = d.C; j.Hp = b->L.Hp; j.Wp = b->L.Wp;
         j.a_oy = b->dev.a_oy; j.a_ox = b->dev.a_ox; j.p_oy = b->dev.p_oy; j.p_ox = b->dev.p_ox;
         j.dtype = d.dtype;
@@ -465,7 +561,7 @@ mdcnn_status mdcnn_layer_forward(mdcnn_buffer* in, const void* frame_dev, const 
                                  const mdcnn_conv_desc* edges, mdcnn_buffer* const* outs, int n_edges, void* stream) {
     mdcnn_status st = validate_forward(in, frame_dev, edges, outs, n_edges);
     if (st) return st;
-    return do_forward(in, frame_dev, forced_mask_dev, edges, outs, n_edges, (hipStream_t)stream);
+    return do_forward(1, &in, &frame_dev, &forced_mask_dev, &edges, &outs, n_edges, (hipStream_t)stream);
 }
 
 mdcnn_status mdcnn_net_create(mdcnn_buffer* const* sites, int n_sites, const int* edge_src, const int* edge_dst,
@@ -510,42 +606,25 @@ mdcnn_status mdcnn_frame(mdcnn_net* net, const void* frame_dev, const uint8_t* f
     if (!frame_dev || !out_dev) return fail(MDCNN_ERR_NULL, "frame/out is NULL");
     if (((uintptr_t)frame_dev | (uintptr_t)out_dev) & 15) return fail(MDCNN_ERR_ALIGN, "frame/out must be 16-byte aligned");
     if (out_bytes != net->out_bytes) return fail(MDCNN_ERR_SIZE, "out_bytes is %zu, the outputs take %zu", out_bytes, net->out_bytes);
-    hipStream_t st = (hipStream_t)stream;
-    mdcnn_status rc = mdcnn_shift_camera(net->sites.data(), (int)net->sites.size(), dty, dtx, stream, did_full_reset);
-    if (rc) return rc;
-    const int n_edges = (int)net->edges.size();
-    int e0 = 0;
-    std::vector<mdcnn_buffer*> outs;
-    for (int i = 0; i < (int)net->sites.size(); ++i) {
-        mdcnn_buffer* s = net->sites[i];
-        if (s->d.kind == MDCNN_SITE_OUTPUT) continue;
-        int e1 = e0;
-        while (e1 < n_edges && net->esrc[e1] == i) ++e1;
-        outs.clear();
-        for (int e = e0; e < e1; ++e) outs.push_back(net->sites[net->edst[e]]);
-        // a residual skip is added by the step-1 kernel of its source; its place in the
-        // order of the producers of its destination stays the same as long as no other
-        // edge of this call goes to the same destination before it
-        int fuse = -1;
-        for (int e = e0; e < e1 && g_fuse_skip && fuse < 0; ++e) {
-            if (net->edges[e].k != 0) continue;
-            bool earlier = false;
-            for (int q = e0; q < e; ++q) earlier |= net->edst[q] == net->edst[e];
-            if (!earlier) fuse = e - e0;
-        }
-        rc = do_forward(s, i == 0 ? frame_dev : nullptr, i == 0 ? forced_mask_dev : nullptr,
-                        net->edges.data() + e0, outs.data(), e1 - e0, st, fuse);
-        if (rc) return rc;
-        e0 = e1;
+    return frame_batch(&net, 1, &frame_dev, &forced_mask_dev, &dty, &dtx, &out_dev, stream, did_full_reset);
+}
+
+mdcnn_status mdcnn_frame_batch(mdcnn_net* const* nets, int n_streams, const void* const* frames_dev,
+                               const uint8_t* const* forced_masks_dev, const int* dty, const int* dtx,
+                               void* const* outs_dev, size_t out_bytes, void* stream, int* did_full_reset) {
+    if (!nets || !frames_dev || !dty || !dtx || !outs_dev) return fail(MDCNN_ERR_NULL, "frame_batch: NULL argument");
+    if (n_streams < 1 || n_streams > kMaxBatch) return fail(MDCNN_ERR_SIZE, "frame_batch: 1 <= n_streams <= %d", kMaxBatch);
+    const uint8_t* no_forced[kMaxBatch] = {};
+    for (int b = 0; b < n_streams; ++b) {
+        if (!nets[b] || !frames_dev[b] || !outs_dev[b]) return fail(MDCNN_ERR_NULL, "frame_batch: stream %d: net/frame/out is NULL", b);
+        if (((uintptr_t)frames_dev[b] | (uintptr_t)outs_dev[b]) & 15) return fail(MDCNN_ERR_ALIGN, "frame_batch: stream %d: frame/out must be 16-byte aligned", b);
+        if (out_bytes != nets[b]->out_bytes) return fail(MDCNN_ERR_SIZE, "frame_batch: out_bytes is %zu, the outputs take %zu", out_bytes, nets[b]->out_bytes);
+        if (b && !same_shape(nets[0], nets[b])) return fail(MDCNN_ERR_SHAPE, "frame_batch: stream %d differs from stream 0 in topology or shapes", b);
+        for (int c = 0; c < b; ++c)
+            if (nets[c] == nets[b] || nets[c]->sites[0] == nets[b]->sites[0])
+                return fail(MDCNN_ERR_STATE, "frame_batch: streams %d and %d share a network or buffers", c, b);
     }
-    char* o = (char*)out_dev;
-    for (mdcnn_buffer* s : net->sites) {
-        if (s->d.kind != MDCNN_SITE_OUTPUT) continue;
-        hipError_t err = timed(kClsReadout, st, [&] { return launch_read_view(s->dev, MDCNN_VIEW_OUT, o, st); });
-        if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "readout launch: %s", hipGetErrorString(err));
-        o += (size_t)s->d.H * s->d.W * s->d.C * esize(s->d.dtype);
-    }
-    return MDCNN_OK;
+    return frame_batch(nets, n_streams, frames_dev, forced_masks_dev ? forced_masks_dev : no_forced, dty, dtx, outs_dev, stream, did_full_reset);
 }
 
 static mdcnn_status view_bytes(const mdcnn_buffer* b, int what, size_t* need) {

@@ -79,6 +79,8 @@ struct FillJob {
     int* counters;
     unsigned long long* lacc;   // per-segment running sums, cleared on the first reset
     unsigned long long* cacc;
+    int* lcnt;                  // per-segment counts of the frame (n_lacc / n_cacc entries), cleared with them:
+    int* ccnt;                  // a site no edge publishes a compute list for must still read as empty
     int n_lacc, n_cacc;
     int H, W, C, Hp, Wp;
     int a_oy, a_ox, p_oy, p_ox;
@@ -121,13 +123,28 @@ struct EdgeDev {
     int k, stride, pad, up;
 };
 
+// Several independent streams (same network, own buffers and camera paths) share
+// one launch: blockIdx.z picks the stream.  The descriptors travel as kernel
+// arguments (4 KiB at most), hence the limit.
+constexpr int kMaxBatch = 16;
+struct EdgeBatch { EdgeDev d[kMaxBatch]; };
+struct Step1Batch {
+    SiteDev s[kMaxBatch];
+    SkipDev skip[kMaxBatch];
+    const void* X[kMaxBatch];
+    const uint8_t* forced[kMaxBatch];
+};
+static_assert(sizeof(FillBatch) <= 4000, "kernel arguments stay below 4 KiB");
+static_assert(sizeof(EdgeBatch) <= 3800 && sizeof(Step1Batch) <= 3800, "kernel arguments stay below 4 KiB");
+
 enum KernelClass { kClsShift = 0, kClsStep1, kClsLists, kClsConvMfma, kClsConvPlain, kClsIdentity, kClsReadout, kNumClasses };
 
 hipError_t launch_shift_fill(const FillBatch& fb, hipStream_t st);
-hipError_t launch_step1(const SiteDev& s, const void* frame, const uint8_t* forced, const SkipDev& skip, hipStream_t st);
+// n streams; geometry and dtype are those of stream 0 (the host checks that all agree)
+hipError_t launch_step1(const Step1Batch& b, int n, hipStream_t st);
 // e.k < 0: no operator, only the compaction of the source's update mask.
 // returns the kernel class that was launched in *cls
-hipError_t launch_conv(const EdgeDev& e, int dtype, int conv_path, hipStream_t st, int* cls);
+hipError_t launch_conv(const EdgeBatch& eb, int n, int dtype, int conv_path, hipStream_t st, int* cls);
 extern int g_tile, g_pipe, g_xcd, g_kc, g_halo, g_halo_sub;   // convolution tuning knobs
 hipError_t launch_pack_weights(const void* src, void* dst, int taps, int Cout, int Cin, hipStream_t st);
 hipError_t launch_read_view(const SiteDev& s, int what, void* dst, hipStream_t st);

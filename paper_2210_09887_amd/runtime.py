@@ -17,7 +17,9 @@ _KIND = {"input": B.MDCNN_SITE_INPUT, "preact": B.MDCNN_SITE_PREACT, "output": B
 class GpuNet:
     """`spec` is any object with the fields of inputs.nets.NetSpec."""
 
-    def __init__(self, spec, origins=None, device="cuda:0"):
+    def __init__(self, spec, origins=None, device="cuda:0", share_weights=None):
+        """share_weights: another GpuNet of the same spec whose weight tensors are reused
+        (streams of one batch share the model)."""
         if not torch.cuda.is_available():
             raise RuntimeError("mdcnn needs a GPU: there is no CPU path")
         B.lib()
@@ -41,15 +43,19 @@ class GpuNet:
                 by = B.mdcnn_conv_border(e.k, e.stride, e.pad, Hs, oh)
                 bx = B.mdcnn_conv_border(e.k, e.stride, e.pad, Ws, ow)
                 border[e.dst] = [max(a, b) for a, b in zip(border[e.dst], [by[0], by[1], bx[0], bx[1]])]
-                w = torch.from_numpy(np.ascontiguousarray(e.w)).to(self.dev)
-                assert w.dtype == self.tdtype
-                self.weights.append(w)
-                cd.w_dev = w.data_ptr()
-                if dt == B.MDCNN_F16 and e.k == 3 and e.stride == 1 and not e.up and cd.Cin % 16 == 0 and cd.Cout % 32 == 0:
-                    wp = torch.empty_like(w)             # second copy in matrix-core operand order
-                    B.mdcnn_pack_weights(cd, dt, wp.data_ptr(), wp.numel() * 2)
-                    self.weights.append(wp)
-                    cd.w_packed_dev = wp.data_ptr()
+                if share_weights is not None:
+                    src = share_weights.edges[len(self.edges)]
+                    cd.w_dev, cd.w_packed_dev = src.w_dev, src.w_packed_dev
+                else:
+                    w = torch.from_numpy(np.ascontiguousarray(e.w)).to(self.dev)
+                    assert w.dtype == self.tdtype
+                    self.weights.append(w)
+                    cd.w_dev = w.data_ptr()
+                    if dt == B.MDCNN_F16 and e.k == 3 and e.stride == 1 and not e.up and cd.Cin % 16 == 0 and cd.Cout % 32 == 0:
+                        wp = torch.empty_like(w)             # second copy in matrix-core operand order
+                        B.mdcnn_pack_weights(cd, dt, wp.data_ptr(), wp.numel() * 2)
+                        self.weights.append(wp)
+                        cd.w_packed_dev = wp.data_ptr()
                 if e.b is not None:
                     bias[e.dst] = e.b.astype(np.float32) if bias[e.dst] is None else bias[e.dst] + e.b.astype(np.float32)
             self.edges.append(cd)
@@ -86,6 +92,9 @@ class GpuNet:
         for b in self.bufs:
             B.mdcnn_destroy_buffer(b)
         self.bufs = []
+
+    def keep_alive(self, other):
+        self._shared = other                 # the owner of shared weights must outlive this net
 
     @staticmethod
     def _stream():
@@ -151,3 +160,29 @@ class GpuNet:
         t = torch.from_numpy(np.ascontiguousarray(arr)).to(self.dev)
         B.mdcnn_write_view(self.bufs[i], what, t.data_ptr(), t.numel() * t.element_size(), self._stream())
         torch.cuda.current_stream().synchronize()      # t must outlive the copy
+
+
+class GpuBatch:
+    """n independent streams of one network behind mdcnn_frame_batch: own buffers and
+    camera paths, shared weights.  Marshalling only."""
+
+    def __init__(self, spec, n_streams, device="cuda:0"):
+        first = GpuNet(spec, device=device)
+        self.streams = [first]
+        for _ in range(n_streams - 1):
+            g = GpuNet(spec, device=device, share_weights=first)
+            g.keep_alive(first)
+            self.streams.append(g)
+
+    def frame(self, frames, dty, dtx, forced=None):
+        """frames: one device tensor [H, W, C] per stream.  Returns (list of flat outputs, list of reset flags)."""
+        g0 = self.streams[0]
+        outs = [g.out for g in self.streams]
+        r = B.mdcnn_frame_batch([g.net for g in self.streams], [x.data_ptr() for x in frames],
+                                None if forced is None else [None if f is None else f.data_ptr() for f in forced],
+                                dty, dtx, [o.data_ptr() for o in outs], g0.out.numel() * g0.esize, g0._stream())
+        return outs, r
+
+    def close(self):
+        for g in reversed(self.streams):
+            g.close()

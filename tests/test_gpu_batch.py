@@ -1,0 +1,81 @@
+"""Batch of independent streams (mdcnn_frame_batch): every stream must give, bit for
+bit, what mdcnn_frame gives on it alone -- outputs, reset decisions and counters --
+although all streams share their launches."""
+import numpy as np
+import pytest
+import torch
+
+from test_gpu_parity import load_case
+
+pytestmark = pytest.mark.gpu
+
+
+def stream_inputs(seq, b):
+    """Stream b plays the sequence from frame b on (its own camera path and resets)."""
+    forced = None if seq.forced is None else seq.forced[b:]
+    return seq.frames[b:], seq.shifts[b:], forced
+
+
+@pytest.mark.parametrize("name,n_streams", [("c1_single_conv", 2), ("c3_resnet_96", 3), ("c4_hrnet_128x96", 4),
+                                            ("c5_bottleneck_40", 3), ("c3_resnet_plain_80x112", 2)])
+def test_batch_equals_single_streams(name, n_streams):
+    import gpu_harness as H
+    from paper_2210_09887_amd import binding as B
+    from paper_2210_09887_amd.runtime import GpuBatch, GpuNet
+    net, seq = load_case(name)
+    T = len(seq.frames) - n_streams + 1
+    # reference: every stream alone
+    want, want_resets, want_stats = [], [], []
+    for b in range(n_streams):
+        fr, sh, fo = stream_inputs(seq, b)
+        g = GpuNet(net)
+        outs, resets = [], []
+        try:
+            for t in range(T):
+                o, r = g.frame(H.dev(fr[t]), int(sh[t][0]), int(sh[t][1]), None if fo is None else H.dev(fo[t]))
+                outs.append(o.cpu().numpy().copy())
+                resets.append(r)
+            want_stats.append([g.read(i, B.MDCNN_VIEW_STATS).copy() for i in range(len(net.sites))])
+        finally:
+            g.close()
+        want.append(outs)
+        want_resets.append(resets)
+    gb = GpuBatch(net, n_streams)
+    try:
+        for t in range(T):
+            ins = [stream_inputs(seq, b) for b in range(n_streams)]
+            frames = [H.dev(fr[t]) for fr, _, _ in ins]
+            forced = None if seq.forced is None else [H.dev(fo[t]) for _, _, fo in ins]
+            outs, resets = gb.frame(frames, [int(sh[t][0]) for _, sh, _ in ins], [int(sh[t][1]) for _, sh, _ in ins], forced)
+            torch.cuda.synchronize()
+            for b in range(n_streams):
+                assert resets[b] == want_resets[b][t], f"frame {t} stream {b}: reset decision"
+                assert np.array_equal(outs[b].cpu().numpy(), want[b][t]), f"frame {t} stream {b}: output differs"
+        for b, g in enumerate(gb.streams):
+            for i in range(len(net.sites)):
+                assert np.array_equal(g.read(i, B.MDCNN_VIEW_STATS), want_stats[b][i]), f"stream {b} site {i}: counters"
+    finally:
+        gb.close()
+
+
+def test_batch_argument_checks():
+    from paper_2210_09887_amd import binding as B
+    from paper_2210_09887_amd.runtime import GpuBatch, GpuNet
+    net, seq = load_case("c1_single_conv")
+    gb = GpuBatch(net, 2)
+    other_net, _ = load_case("c5_bottleneck_40")
+    other = GpuNet(other_net)
+    try:
+        X = torch.zeros((net.H, net.W, net.sites[0].C), dtype=gb.streams[0].tdtype, device="cuda")
+        nets = [g.net for g in gb.streams]
+        outs = [g.out.data_ptr() for g in gb.streams]
+        nbytes = gb.streams[0].out.numel() * gb.streams[0].esize
+        with pytest.raises(B.MdcnnError):              # the same stream twice
+            B.mdcnn_frame_batch([nets[0], nets[0]], [X.data_ptr()] * 2, None, [0, 0], [0, 0], outs, nbytes)
+        with pytest.raises(B.MdcnnError):              # different networks
+            B.mdcnn_frame_batch([nets[0], other.net], [X.data_ptr()] * 2, None, [0, 0], [0, 0], outs, nbytes)
+        with pytest.raises(B.MdcnnError):              # too many streams
+            B.mdcnn_frame_batch(nets * 9, [X.data_ptr()] * 18, None, [0] * 18, [0] * 18, outs * 9, nbytes)
+    finally:
+        other.close()
+        gb.close()
