@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--density", type=float, default=0.2, help="config 5 only")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle baseline; 0 disables it")
     ap.add_argument("--dense", action="store_true", help="library dense mode: threshold 0 and all pixels forced")
+    ap.add_argument("--streams", type=int, default=8,
+                    help="after the headline run, the same workload as a batch of this many independent streams "
+                         "(mdcnn_frame_batch; reported under \"batched\"); 0 disables it")
     ap.add_argument("--opt", action="append", default=[], metavar="ID=VALUE",
                     help="library tuning option (mdcnn_set_option), e.g. --opt 6=0 switches the halo-staged kernel off")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -99,6 +102,95 @@ def measured_traffic(cfg, cls):
             return json.load(f)[f"config{cfg}"][cls]["hbm_bytes_per_launch"]
     except Exception:
         return None
+
+
+def rooflines(prof, flops_mfma, flops_plain, ab, cfg, with_traffic=True):
+    """Per-class kernel times (from the library's HIP events) and the roofline entries."""
+    tr = (lambda c: measured_traffic(cfg, c)) if with_traffic else (lambda c: None)
+    classes = {}
+    for k, (ms, cnt) in prof.items():
+        if cnt:
+            classes[k] = {"ms_total": round(ms, 3), "launches": int(cnt), "avg_us": round(1e3 * ms / cnt, 2)}
+    kernel_ms = sum(v[0] for v in prof.values())
+    dominant = max(prof, key=lambda k: prof[k][0])
+    rl_all = {}
+    if prof["conv_mfma"][1]:
+        ms, cnt = prof["conv_mfma"]
+        ach = flops_mfma / (ms * 1e-3) / 1e12
+        rl_all["conv_mfma"] = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
+                               "frac": round(ach / PEAK_MFMA_F16_TFLOPS, 4), "traffic": tr("conv_mfma"),
+                               "flop_per_launch": round(flops_mfma / cnt), "avg_us": round(1e3 * ms / cnt, 2), "launches": int(cnt),
+                               "algorithmic_bytes_per_launch": round(ab["conv"] / (cnt + prof["conv_plain"][1])),
+                               "hbm_bound_us": round(ab["conv"] / (cnt + prof["conv_plain"][1]) / PEAK_HBM_GBS / 1e3, 2),
+                               "mfma_bound_us": round(flops_mfma / cnt / PEAK_MFMA_F16_TFLOPS / 1e6, 2)}
+    if prof["conv_plain"][1]:
+        ms, cnt = prof["conv_plain"]
+        ach = flops_plain / (ms * 1e-3) / 1e12
+        rl_all["conv_plain"] = {"bound": "alu", "achieved": round(ach, 3), "peak": PEAK_FP32_VALU_TFLOPS, "unit": "TFLOP/s",
+                                "frac": round(ach / PEAK_FP32_VALU_TFLOPS, 5), "traffic": tr("conv_plain"),
+                                "flop_per_launch": round(flops_plain / cnt), "avg_us": round(1e3 * ms / cnt, 2), "launches": int(cnt)}
+    if prof["step1"][1]:
+        ms, cnt = prof["step1"]
+        ach = ab["step1"] / (ms * 1e-3) / 1e9
+        rl_all["step1"] = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                           "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": tr("step1"),
+                           "bytes_per_launch": round(ab["step1"] / cnt), "avg_us": round(1e3 * ms / cnt, 2), "launches": int(cnt)}
+    roofline = dict(rl_all.get(dominant, next(iter(rl_all.values()))))
+    roofline["kernel"] = dominant if dominant in rl_all else next(iter(rl_all))
+    return classes, kernel_ms, rl_all, roofline
+
+
+def sum_totals(ts):
+    """Adds up GpuNet.totals() of several streams."""
+    out = {k: sum(t[k] for t in ts) for k in ts[0] if k != "per_site"}
+    out["per_site"] = {k: sum(t["per_site"][k] for t in ts) for k in ts[0]["per_site"]}
+    return out
+
+
+def run_batched(a, cfg, net, T, frames, shifts, forced, fused):
+    """The same workload as a.streams independent streams in shared launches: stream b
+    plays the sequence cyclically from frame b * T / streams on."""
+    import torch
+    from paper_2210_09887_amd import binding as B
+    from paper_2210_09887_amd.runtime import GpuBatch
+    n = a.streams
+    gb = GpuBatch(net, n)
+    phase = [(b * T) // n for b in range(n)]
+    state = {"t": 0}
+
+    def step():
+        ts = [(state["t"] + p) % T for p in phase]
+        first = state["t"] == 0
+        gb.frame([frames[t] for t in ts], [0 if first else int(shifts[t][0]) for t in ts],
+                 [0 if first else int(shifts[t][1]) for t in ts],
+                 None if forced is None else [forced[t] for t in ts])
+        state["t"] += 1
+
+    steps = max(10, a.steps // n * 2)
+    for _ in range(max(4, a.warmup // n)):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    before = sum_totals([g.totals() for g in gb.streams])
+    B.mdcnn_set_option(B.MDCNN_OPT_PROFILE, 1)
+    B.mdcnn_profile_read()
+    n_prof = min(steps, T)
+    for _ in range(n_prof):
+        step()
+    prof = B.mdcnn_profile_read()
+    B.mdcnn_set_option(B.MDCNN_OPT_PROFILE, 0)
+    after = sum_totals([g.totals() for g in gb.streams])
+    ab = algorithmic_bytes(gb.streams[0], net, before, after, n_prof * n, fused_skips=fused)
+    classes, kernel_ms, rl_all, _ = rooflines(prof, 2.0 * (after["macs_mfma"] - before["macs_mfma"]),
+                                              2.0 * (after["macs_plain"] - before["macs_plain"]), ab, cfg, with_traffic=False)
+    gb.close()
+    return {"streams": n, "value": round(n * steps / dt, 2), "unit": "frames/s", "batch_steps": steps,
+            "ms_per_batch_step": round(1e3 * dt / steps, 4), "roofline_all": rl_all, "kernel_classes": classes,
+            "kernel_ms_per_batch_step": round(kernel_ms / n_prof, 4)}
 
 
 def main():
@@ -172,36 +264,7 @@ def main():
     flops_mfma = 2.0 * (after["macs_mfma"] - before["macs_mfma"])
     flops_plain = 2.0 * (after["macs_plain"] - before["macs_plain"])
     ab = algorithmic_bytes(g, net, before, after, n_prof, fused_skips="8=0" not in a.opt)
-    classes = {}
-    for k, (ms, cnt) in prof.items():
-        if cnt:
-            classes[k] = {"ms_total": round(ms, 3), "launches": int(cnt), "avg_us": round(1e3 * ms / cnt, 2)}
-    kernel_ms = sum(v[0] for v in prof.values())
-    dominant = max(prof, key=lambda k: prof[k][0])
-    rl_all = {}
-    if prof["conv_mfma"][1]:
-        ms, cnt = prof["conv_mfma"]
-        ach = flops_mfma / (ms * 1e-3) / 1e12
-        rl_all["conv_mfma"] = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
-                               "frac": round(ach / PEAK_MFMA_F16_TFLOPS, 4), "traffic": measured_traffic(cfg, "conv_mfma"),
-                               "flop_per_launch": round(flops_mfma / cnt), "avg_us": round(1e3 * ms / cnt, 2), "launches": int(cnt),
-                               "algorithmic_bytes_per_launch": round(ab["conv"] / (cnt + prof["conv_plain"][1])),
-                               "hbm_bound_us": round(ab["conv"] / (cnt + prof["conv_plain"][1]) / PEAK_HBM_GBS / 1e3, 2),
-                               "mfma_bound_us": round(flops_mfma / cnt / PEAK_MFMA_F16_TFLOPS / 1e6, 2)}
-    if prof["conv_plain"][1]:
-        ms, cnt = prof["conv_plain"]
-        ach = flops_plain / (ms * 1e-3) / 1e12
-        rl_all["conv_plain"] = {"bound": "alu", "achieved": round(ach, 3), "peak": PEAK_FP32_VALU_TFLOPS, "unit": "TFLOP/s",
-                                "frac": round(ach / PEAK_FP32_VALU_TFLOPS, 5), "traffic": measured_traffic(cfg, "conv_plain"),
-                                "flop_per_launch": round(flops_plain / cnt), "avg_us": round(1e3 * ms / cnt, 2), "launches": int(cnt)}
-    if prof["step1"][1]:
-        ms, cnt = prof["step1"]
-        ach = ab["step1"] / (ms * 1e-3) / 1e9
-        rl_all["step1"] = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                           "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": measured_traffic(cfg, "step1"),
-                           "bytes_per_launch": round(ab["step1"] / cnt), "avg_us": round(1e3 * ms / cnt, 2), "launches": int(cnt)}
-    roofline = dict(rl_all.get(dominant, next(iter(rl_all.values()))))
-    roofline["kernel"] = dominant if dominant in rl_all else next(iter(rl_all))
+    classes, kernel_ms, rl_all, roofline = rooflines(prof, flops_mfma, flops_plain, ab, cfg)
 
     # ---- CPU baseline: the oracle as it stands, on the first frames of the same sequence
     cpu = None
@@ -248,13 +311,15 @@ def main():
         "instrumented_ms_per_step": round(1e3 * dt_prof / n_prof, 4),
         "cpu_baseline": cpu,
     }
+    g.close()
+    if a.streams > 1 and not a.copy_calibration:
+        out["batched"] = run_batched(a, cfg, net, T, frames, shifts, forced, "8=0" not in a.opt)
     if a.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
         out["copy_calibration_bytes"] = 1 << 30
-    g.close()
     print(json.dumps(out))
 
 
