@@ -645,12 +645,19 @@ void k_conv_halo(EdgeBatch eb, int NT, int work_items) {
                     }
                     load_a((i + D - 1) % D, c, i + D - 1);
                     if (i + FBR - 1 < NS) load_b((i + FBR - 1) % FBR, i + FBR - 1);
-                    __builtin_amdgcn_sched_barrier(0);       // keep the loads of later steps ahead of these MFMAs
 #pragma unroll
                     for (int t = 0; t < L; ++t)
 #pragma unroll
                         for (int j = 0; j < TN; ++j)
                             acc[t][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i % D][j], fb[i % FBR][t], acc[t][j], 0, 0, 0);
+                    // the loads just issued (for later steps) stay ahead of these MFMAs and are
+                    // spread between them: one LDS read, one global load, a quarter of the MFMAs
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                       // one LDS read
+                        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                       // one global load
+                        __builtin_amdgcn_sched_group_barrier(0x008, (L * TN + 3) / 4, 0);        // a quarter of the MFMAs
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 __syncthreads();                          // everyone is done reading the staged chunk

@@ -85,6 +85,31 @@ __device__ __forceinline__ void fill_items(const FillJob& j, unsigned lb) {
     const long long begin = (long long)lb * kFillItemsPerBlock;
     long long end = begin + kFillItemsPerBlock;
     if (end > total) end = total;
+    if constexpr (VEC > 1) {
+        // Full reset with a power-of-two number of 16-byte chunks per pixel (<= 256): the
+        // rings are filled front to back, a thread keeps its channel chunk over the whole
+        // loop (block starts and the stride of 256 are multiples of `chunks`), so the loop
+        // body is one store: no divisions, no bias loads.
+        if (full && (chunks & (chunks - 1)) == 0 && chunks <= 256 && total < (1ll << 31)) {
+            const unsigned nPc = (unsigned)j.nP * chunks, e32 = (unsigned)end;
+            const int c0 = (int)(threadIdx.x & (chunks - 1)) * VEC;
+            int sh = 0;
+            while ((1 << sh) < chunks) ++sh;
+            float bv[VEC], zv[VEC];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) { bv[i] = j.bias ? j.bias[c0 + i] : 0.f; zv[i] = 0.f; }
+            for (unsigned idx = (unsigned)begin + threadIdx.x; idx < e32; idx += 256) {
+                if (idx < nPc) {
+                    V16<T>::store((T*)j.P + (size_t)idx * VEC, bv);
+                } else {
+                    const unsigned ia = idx - nPc;
+                    V16<T>::store((T*)j.A + (size_t)ia * VEC, zv);
+                    if (c0 == 0) j.flags[ia >> sh] = (uint8_t)kFlagN;
+                }
+            }
+            return;
+        }
+    }
     for (long long idx = begin + threadIdx.x; idx < end; idx += 256) {
         const int pix = (int)(idx / chunks);
         const int c0 = (int)(idx - (long long)pix * chunks) * VEC;
