@@ -1104,7 +1104,7 @@ static hipError_t launch_tiled(const EdgeBatch& eb, int nb, long long max_entrie
     auto kern = k_conv_mfma_tiled<WM, WN, TM, TN, KC, PIPE>;
     if (!attr_set) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::SMEM);
-        if (err != hipSuccess) return err;
+        if (err != hipSuccess) { (void)hipGetLastError(); return err; }    // do not leave it for the next call to report
         attr_set = true;
     }
     const long long nseg = (max_entries + kSegPixels - 1) / kSegPixels;
@@ -1123,7 +1123,7 @@ static hipError_t launch_tiled_p(const EdgeBatch& eb, int nb, long long max_entr
     const EdgeDev& e = eb.d[0];
     // measured on MI355X: with L2 latencies of ~200 cycles one step of prefetch is
     // enough; the second register stage only costs occupancy
-    const bool deep = g_pipe == 2;
+    const bool deep = g_pipe == 2 && TiledCfg<WM, WN, TM, TN, KC, 2>::SMEM <= 150 * 1024;   // two stages must fit the LDS
     return deep ? launch_tiled<WM, WN, TM, TN, KC, 2>(eb, nb, max_entries, st)
                 : launch_tiled<WM, WN, TM, TN, KC, 1>(eb, nb, max_entries, st);
 }
@@ -1171,7 +1171,7 @@ static hipError_t launch_halo_t(const EdgeBatch& eb, int nb, long long nseg, hip
     auto kern = k_conv_halo<NSUB, WMV, WK, TM, TN, KC, NLD, 3, RING, MINB>;
     if (!attr_set) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::SMEM);
-        if (err != hipSuccess) return err;
+        if (err != hipSuccess) { (void)hipGetLastError(); return err; }    // do not leave it for the next call to report
         attr_set = true;
     }
     const int NT = e.Cout / Cfg::BN;
