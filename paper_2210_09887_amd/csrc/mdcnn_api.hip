@@ -222,8 +222,8 @@ mdcnn_status validate_forward(const mdcnn_buffer* in, const void* frame, const m
 mdcnn_status do_forward(int n, mdcnn_buffer* const* ins, const void* const* frames, const uint8_t* const* forced,
                         const mdcnn_conv_desc* const* edges, mdcnn_buffer* const* const* outs, int n_edges,
                         hipStream_t st, int fuse_skip = -1) {
-    static Step1Batch sb;                                  // 3.4 KiB each: kept off the stack
-    static EdgeBatch eb;
+    static thread_local Step1Batch sb;                     // 3.4 KiB each: kept off the stack
+    static thread_local EdgeBatch eb;
     for (int b = 0; b < n; ++b) {
         sb.s[b] = ins[b]->dev;
         sb.X[b] = frames ? frames[b] : nullptr;

@@ -130,3 +130,23 @@ def test_multi_gpu_bench_is_refused():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr)
+
+
+def test_pack_weights_and_batch_argument_checks_need_no_gpu():
+    """Both entry points validate before they touch the device."""
+    from paper_2210_09887_amd import binding as B
+    cd = B.mdcnn_conv_desc(3, 1, 1, 64, 64, 0, 4096, None)
+    ok_bytes = 9 * 64 * 64 * 2
+    for desc, dtype, dst, nbytes in [
+        (B.mdcnn_conv_desc(3, 1, 1, 24, 64, 0, 4096, None), B.MDCNN_F16, 8192, 9 * 24 * 64 * 2),   # Cin % 16
+        (B.mdcnn_conv_desc(3, 1, 1, 64, 48, 0, 4096, None), B.MDCNN_F16, 8192, 9 * 64 * 48 * 2),   # Cout % 32
+        (cd, B.MDCNN_F32, 8192, ok_bytes),                                                          # dtype
+        (cd, B.MDCNN_F16, 8200, ok_bytes),                                                          # alignment
+        (cd, B.MDCNN_F16, 8192, ok_bytes - 2),                                                      # size
+        (cd, B.MDCNN_F16, None, ok_bytes),                                                          # NULL
+    ]:
+        with pytest.raises(B.MdcnnError):
+            B.mdcnn_pack_weights(desc, dtype, dst, nbytes)
+    for n in (0, 17):
+        with pytest.raises(B.MdcnnError):
+            B.mdcnn_frame_batch([4096] * n, [4096] * n, None, [0] * n, [0] * n, [4096] * n, 16)
