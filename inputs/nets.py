@@ -2,8 +2,8 @@
 
 A network is a DAG of *sites* (tensor positions that own state: the network
 input, every pre-activation tensor and every network output) joined by
-*edges* (linear operators: a k x k convolution, optionally followed by a
-nearest-neighbour 2^n upsampling, or the identity for a residual skip).
+*edges* (a k x k convolution, optionally followed by a nearest-neighbour 2^n
+upsampling, the identity for a residual skip, or a k x k max pooling).
 Sites are listed in topological order; edges are listed grouped by source
 site and, for one destination, in the order their contributions are applied.
 
@@ -52,6 +52,7 @@ class EdgeSpec:
     up: int              # log2 of the nearest-neighbour upsampling after the conv
     w: Optional[np.ndarray]   # [k*k, Cout, Cin] storage dtype, None for identity
     b: Optional[np.ndarray]   # [Cout] float32, None = no bias
+    pool: bool = False        # True: k x k max pooling of the source's activations (no weights)
 
 
 @dataclass
@@ -101,6 +102,10 @@ class _Builder:
         if bias and self.bias_amp > 0:
             b = self.rng.uniform(-self.bias_amp, self.bias_amp, cout).astype(np.float32)
         self.net.edges.append(EdgeSpec(src, dst, k, stride, pad, up, w, b))
+
+    def maxpool(self, src, dst, k, stride, pad=None):
+        assert self.net.sites[src].C == self.net.sites[dst].C
+        self.net.edges.append(EdgeSpec(src, dst, k, stride, k // 2 if pad is None else pad, 0, None, None, True))
 
     def identity(self, src, dst):
         assert self.net.sites[src].C == self.net.sites[dst].C
@@ -154,17 +159,22 @@ def _cnn5(rng, H=256, W=256) -> NetSpec:
     return net
 
 
-def _resnet18(rng, H=512, W=512, widths=(64, 128, 256, 512)) -> NetSpec:
+def _resnet18(rng, H=512, W=512, widths=(64, 128, 256, 512), pool_stem=False) -> NetSpec:
     """3x3 stem with stride 2, then four stages of two basic blocks each, stage
     strides 1/2/2/1 (total stride 8), 1x1 projection wherever the shape changes.
     The second conv of every block carries a folded batch-norm scale of 0.5 so
-    that activations stay O(1) in fp16 storage."""
-    net = NetSpec(CONFIG_NAMES[3], "f16", H, W, 8)
+    that activations stay O(1) in fp16 storage.  pool_stem: the usual ResNet stem,
+    a 3x3 stride-2 max pooling after the stem convolution (total stride 16)."""
+    net = NetSpec(CONFIG_NAMES[3] + ("_poolstem" if pool_stem else ""), "f16", H, W, 16 if pool_stem else 8)
     b = _Builder(net, rng, bias_amp=0.1)
     th_in, th = 0.02, 0.01
     x = b.site("in", 3, 1, "input", False, th_in)
     s = b.site("stem", widths[0], 2, theta=th)
     b.conv(x, s, 3, 2)
+    if pool_stem:
+        p = b.site("pool", widths[0], 4, "preact", False, th)
+        b.maxpool(s, p, 3, 2)
+        s = p
     strides = (1, 2, 2, 1)
     for si, (C, st) in enumerate(zip(widths, strides)):
         for bi in range(2):
@@ -301,4 +311,33 @@ def tiny_net(dtype="f32", H=6, W=6, C=(1, 2, 1), k=3, stride=1, relu=True, theta
                      False if last else relu, 0.0 if last else theta)
         b.conv(prev, cur, k, stride)
         prev = cur
+    return net
+
+
+def pool_net(dtype="f32", H=16, W=16, C=(2, 4, 3), k=3, stride=2, pad=1, theta=0.0, seed=0, bias_amp=0.1,
+             relu=True) -> NetSpec:
+    """input -> 3x3 conv -> activation site -> k x k max pooling -> site -> 3x3 conv -> output."""
+    rng = np.random.default_rng(seed)
+    net = NetSpec("pool", dtype, H, W, stride)
+    b = _Builder(net, rng, bias_amp)
+    x = b.site("in", C[0], 1, "input", False, theta)
+    a = b.site("act", C[1], 1, "preact", relu, theta)
+    p = b.site("pool", C[1], stride, "preact", False, theta)
+    y = b.site("out", C[2], stride, "output", False, 0.0)
+    b.conv(x, a, 3, 1)
+    b.maxpool(a, p, k, stride, pad)
+    b.conv(p, y, 3, 1)
+    return net
+
+
+def pool_front_net(dtype="f32", H=16, W=16, C=(3, 2), k=3, stride=2, pad=1, theta=0.0, seed=0) -> NetSpec:
+    """input -> k x k max pooling -> site -> 1x1 conv -> output (pooling straight on the frames)."""
+    rng = np.random.default_rng(seed)
+    net = NetSpec("pool_front", dtype, H, W, stride)
+    b = _Builder(net, rng, 0.1)
+    x = b.site("in", C[0], 1, "input", False, theta)
+    p = b.site("pool", C[0], stride, "preact", False, theta)
+    y = b.site("out", C[1], stride, "output", False, 0.0)
+    b.maxpool(x, p, k, stride, pad)
+    b.conv(p, y, 1, 1, pad=0)
     return net

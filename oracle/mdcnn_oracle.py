@@ -23,7 +23,10 @@ What is followed, and where the paper defines it:
   -- Padded Convolutions (a 64x64 input under a 3x3 kernel yields 66x66);
 * growing in one direction invalidates the stash of the opposite side, moving
   back over it resets all buffers and the frame is inferred densely
-  -- Buffer management.
+  -- Buffer management;
+* max pooling keeps the previous output of every pixel in a buffer of its own:
+  the delta of a pixel is taken against that previous output, or against zero
+  if the pixel was reset in the current frame -- Supplementary, Maximum Pooling.
 
 Arithmetic: stored tensors (A, P, delta maps, weights, frames) are in the
 network's storage dtype; every elementwise operation is done in float32 in the
@@ -64,6 +67,7 @@ class OracleSite:
         self.origin = origin                # physical rotation of the rings
         self.gy = 0                         # global pixel coordinate of view pixel (0, 0)
         self.gx = 0
+        self.pooled = False                 # destination of a max-pooling edge
 
     def allocate(self):
         by0, by1, bx0, bx1 = self.border
@@ -76,6 +80,7 @@ class OracleSite:
         self.delta = np.zeros((self.H, self.W, self.C), self.dtype)
         self.L = np.zeros(0, np.int32)
         self.n_candidates = 0
+        self.Y = np.zeros((self.H, self.W, self.C), self.dtype) if self.pooled else None   # previous pooling output (ring like A)
 
     # ring addressing: global pixel -> physical slot, wrapped (Spherical Buffers)
     def _a_index(self):
@@ -94,6 +99,12 @@ class OracleSite:
 
     def set_A(self, v):
         self.A[self._a_index()] = v
+
+    def get_Y(self):
+        return self.Y[self._a_index()]
+
+    def set_Y(self, v):
+        self.Y[self._a_index()] = v
 
     def get_P(self):
         """Pending values over the padded window (view plus dilated border)."""
@@ -120,6 +131,11 @@ class OracleNet:
             src, dst = self.sites[e.src], self.sites[e.dst]
             if e.k == 0:
                 assert (src.H, src.W, src.C) == (dst.H, dst.W, dst.C)
+            elif getattr(e, "pool", False):
+                oh = (src.H + 2 * e.pad - e.k) // e.stride + 1
+                ow = (src.W + 2 * e.pad - e.k) // e.stride + 1
+                assert (oh, ow, src.C) == (dst.H, dst.W, dst.C) and e.up == 0 and dst.spec.kind == "preact"
+                dst.pooled = True               # pooling outputs exist inside the view only: no border
             else:
                 oh = (src.H + 2 * e.pad - e.k) // e.stride + 1
                 ow = (src.W + 2 * e.pad - e.k) // e.stride + 1
@@ -256,6 +272,9 @@ class OracleNet:
                     ny, nx = iy + e.pad - jy, ix + e.pad - jx
                     ok = (ny % e.stride == 0) & (nx % e.stride == 0)
                     oy, ox = ny[ok] // e.stride, nx[ok] // e.stride
+                    if getattr(e, "pool", False):   # pooling outputs exist inside the view only
+                        inv = (oy >= 0) & (oy < dst.H) & (ox >= 0) & (ox < dst.W)
+                        oy, ox = oy[inv], ox[inv]
                     cover[oy + by0, ox + bx0] = True
         return np.flatnonzero(cover.ravel()).astype(np.int32)
 
@@ -266,7 +285,26 @@ class OracleNet:
         lst = self.compute_list(e)
         wy, wx = lst // dst.Wp, lst % dst.Wp          # padded-window coordinates
         oy, ox = wy - by0, wx - bx0                   # view coordinates of the destination
-        if e.k == 0:
+        if getattr(e, "pool", False):
+            # Maximum Pooling: the output is recomputed from the source's activations
+            # (in-view pixels of the window only); its delta is taken against the pixel's
+            # previous output, or against zero if the pixel was reset this frame.
+            act = src.get_A().astype(f32)
+            if src.spec.relu:
+                act = np.maximum(act, f32(0))
+            out = np.full((len(lst), dst.C), -np.inf, f32)
+            for jy in range(e.k):
+                for jx in range(e.k):
+                    iy = oy * e.stride - e.pad + jy
+                    ix = ox * e.stride - e.pad + jx
+                    ok = (iy >= 0) & (iy < src.H) & (ix >= 0) & (ix < src.W)
+                    out[ok] = np.maximum(out[ok], act[iy[ok], ix[ok]])
+            Yv = dst.get_Y()
+            prev = np.where(dst.N[oy, ox][:, None], f32(0), Yv[oy, ox].astype(f32))
+            y = out - prev
+            Yv[oy, ox] = out.astype(dst.dtype)
+            dst.set_Y(Yv)
+        elif e.k == 0:
             y = src.delta[oy, ox].astype(f32)
         else:
             f = 1 << e.up

@@ -30,6 +30,12 @@ def _conv64(x_hwc, e):
     return y
 
 
+def maxpool64(x_hwc, k, stride, pad):
+    """Library max pooling (torch, padding counts as -inf), x [H, W, C] float64."""
+    x = torch.from_numpy(np.ascontiguousarray(x_hwc.astype(np.float64))).permute(2, 0, 1)[None]
+    return F.max_pool2d(x, k, stride, pad)[0].permute(1, 2, 0).numpy()
+
+
 def site_bias(net, i):
     b = np.zeros(net.sites[i].C, np.float64)
     for e in net.edges:
@@ -46,7 +52,10 @@ def dense_cnn(net, X, return_all=False):
         acc = np.zeros(net.site_hw(i) + (net.sites[i].C,), np.float64) + site_bias(net, i)
         for e in net.edges:
             if e.dst == i:
-                acc = acc + (val[e.src] if e.k == 0 else _conv64(val[e.src], e))
+                if getattr(e, "pool", False):
+                    acc = acc + maxpool64(val[e.src], e.k, e.stride, e.pad)
+                else:
+                    acc = acc + (val[e.src] if e.k == 0 else _conv64(val[e.src], e))
         val[i] = np.maximum(acc, 0) if net.sites[i].relu else acc
     if return_all:
         return val

@@ -194,6 +194,97 @@ def test_brute_force_tiny(k, stride):
         assert np.abs(outs[0] - y).max() < 1e-5
 
 
+# ---- max pooling (Supplementary, Maximum Pooling)
+def pool_cases():
+    from inputs.nets import pool_net
+    return {"k3s2": pool_net("f32", 16, 16, (2, 4, 3), 3, 2, 1, seed=1), "k2s2": pool_net("f32", 16, 16, (2, 4, 3), 2, 2, 0, seed=2),
+            "k3s1": pool_net("f32", 12, 12, (2, 3, 2), 3, 1, 1, seed=3), "f16": pool_net("f16", 16, 16, (2, 8, 3), 3, 2, 1, seed=4),
+            "resnet_poolstem": build_net(3, H=64, W=64, widths=(8, 8, 16, 16), pool_stem=True)}
+
+
+@pytest.mark.parametrize("name", ["k3s2", "k2s2", "k3s1", "f16", "resnet_poolstem"])
+def test_pool_theta0_static_equals_dense(name):
+    """Threshold 0, static camera: delta inference through a max pooling equals dense
+    inference with a library pooling routine, frame after frame."""
+    net = set_theta(pool_cases()[name], 0.0)
+    o = OracleNet(net)
+    for X in rand_frames(net, 4, 7):
+        outs, _ = o.frame(X, 0, 0)
+        ref = refs.dense_cnn(net, X)
+        for a, b in zip(outs, ref):
+            assert np.abs(a.astype(np.float64) - b).max() < TOL[net.dtype]
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_pool_on_moving_frames_equals_library_pooling(seed):
+    """Pooling straight on the frames, threshold 0, moving camera, every pixel changing every
+    frame: what the pooled site has accumulated is exactly the library max pooling of the
+    current frame -- newly unveiled pixels included (their delta is taken against zero, not
+    against the previous output of the pixel that left their ring slot)."""  # noqa
+    from inputs.nets import pool_front_net
+    net = pool_front_net("f32", 16, 24, (3, 2), 3, 2, 1, seed=seed)
+    rng = np.random.default_rng(seed)
+    origins = [(int(rng.integers(0, 30)), int(rng.integers(0, 30))) for _ in net.sites]
+    o = OracleNet(net, origins)
+    frames = rand_frames(net, 7, seed + 20, walk=1.0)
+    for X, (dy, dx) in zip(frames, monotone_shifts(7, seed)):
+        o.frame(X, dy, dx)
+        p = o.sites[1]
+        want = refs.maxpool64(X, 3, 2, 1)
+        assert np.abs(p.get_A().astype(np.float64) - want).max() < 1e-5      # sums of fp32 deltas: a few ulp
+        assert np.array_equal(p.get_Y().astype(np.float64), want)             # the stored previous output is exact
+
+
+def test_pool_conservation_under_truncation():
+    """Threshold > 0, static camera: accumulated + pending of the pooled site always equals the
+    library pooling of the source's accumulated activations (nothing is lost, only deferred)."""
+    from inputs.nets import pool_net
+    net = pool_net("f32", 16, 16, (2, 4, 3), 3, 2, 1, theta=0.3, seed=5)
+    o = OracleNet(net)
+    sparse = False
+    for X in rand_frames(net, 6, 9, walk=0.1):
+        o.frame(X, 0, 0)
+        a, p = o.sites[1], o.sites[2]
+        want = refs.maxpool64(np.maximum(a.get_A(), 0), 3, 2, 1)
+        got = p.get_A().astype(np.float64) + p.view_of_window(p.get_P())
+        assert np.abs(got - want).max() < 1e-5
+        sparse |= 0 < p.M.mean() < 1
+    assert sparse
+
+
+def test_pool_brute_force_tiny():
+    from inputs.nets import pool_front_net
+    net = pool_front_net("f32", 6, 8, (2, 2), 3, 2, 1, seed=3)
+    o = OracleNet(net)
+    rng = np.random.default_rng(1)
+    for t in range(3):
+        X = rng.normal(0, 1, (6, 8, 2)).astype(np.float32)
+        o.frame(X, 0, 0)
+        got = o.sites[1].get_A()
+        for oy in range(3):
+            for ox in range(4):
+                for c in range(2):
+                    m = max(float(X[iy, ix, c]) for iy in range(2 * oy - 1, 2 * oy + 2) for ix in range(2 * ox - 1, 2 * ox + 2)
+                            if 0 <= iy < 6 and 0 <= ix < 8)
+                    assert abs(float(got[oy, ox, c]) - m) < 1e-5
+
+
+def test_pins_catch_a_pool_delta_against_the_stale_output(monkeypatch):
+    """Planted mistake: the previous output is used also for pixels reset this frame."""
+    from inputs.nets import pool_front_net
+    net = pool_front_net("f32", 16, 24, (3, 2), 3, 2, 1, seed=0)
+    o = OracleNet(net)
+    frames = rand_frames(net, 5, 20, walk=1.0)
+    bad = False
+    for X, (dy, dx) in zip(frames, [(0, 0), (1, 1), (1, 0), (0, 1), (1, 1)]):
+        o.shift_camera(dy, dx)
+        o.sites[1].N[:] = False                      # the mistake: nobody is "newly unveiled" for the pooling
+        for i in (0, 1):
+            o.layer_forward(i, X if i == 0 else None)
+        bad |= np.abs(o.sites[1].get_A().astype(np.float64) - refs.maxpool64(X, 3, 2, 1)).max() > 1e-3
+    assert bad
+
+
 def test_impulse_footprint_and_padded_extent():
     g = golden()
     # a 64x64 input under a 3x3 kernel produces 66x66 outputs
