@@ -72,6 +72,9 @@ typedef struct {
     const float* bias_dev;    /* C floats: sum of the biases of all producers, or NULL  */
     int origin_y, origin_x;   /* physical rotation of the rings (any value; results in  */
                               /* view order do not depend on it)                        */
+    int pool_prev;            /* 1: destination of a max-pooling edge: the site also    */
+                              /* keeps the previous pooling output of every view pixel  */
+                              /* (ring H x W x C, PREACT sites only)                    */
 } mdcnn_buffer_desc;
 
 typedef struct mdcnn_buffer mdcnn_buffer;
@@ -89,6 +92,13 @@ typedef struct {
     int up;                   /* log2 of the nearest-neighbour upsampling factor        */
     const void* w_dev;
     const void* w_packed_dev;
+    int op;                   /* 0: convolution / identity as above.  1: k x k max pooling of */
+                              /* the source's activations f(A) (in-view pixels of the window  */
+                              /* only; weights ignored; Cin == Cout, up == 0, k >= 1): the    */
+                              /* delta of an output pixel is taken against its previous       */
+                              /* output, or against zero if the pixel is newly unveiled; the   */
+                              /* destination must be a PREACT site with pool_prev = 1 and gets */
+                              /* no border from this edge.  [Supplementary: Maximum Pooling]  */
 } mdcnn_conv_desc;
 
 /* Model preparation, once per edge: writes the weights of `edge` (w_dev, fp16,
@@ -202,11 +212,12 @@ typedef enum {
                              /* sums since creation: updated, candidates, multiply-         */
                              /* accumulates of the MFMA kernel into this site, compute-list */
                              /* entries, multiply-accumulates of the plain kernel           */
-    MDCNN_VIEW_OUT = 7       /* H*W*C storage dtype: f(P) over the view (readout)           */
+    MDCNN_VIEW_OUT = 7,      /* H*W*C storage dtype: f(P) over the view (readout)           */
+    MDCNN_VIEW_POOL_PREV = 8 /* H*W*C storage dtype: previous pooling output (pool_prev sites) */
 } mdcnn_view;
 mdcnn_status mdcnn_read_view(const mdcnn_buffer* buf, int what, void* dst_dev, size_t bytes,
                              void* stream);
-/* Overwrite A, P or FLAGS from view-ordered data (restoring a saved state). */
+/* Overwrite A, P, FLAGS or POOL_PREV from view-ordered data (restoring a saved state). */
 mdcnn_status mdcnn_write_view(mdcnn_buffer* buf, int what, const void* src_dev, size_t bytes,
                               void* stream);
 
@@ -232,7 +243,7 @@ mdcnn_status mdcnn_set_option(int option, int value);
 /* Kernel classes reported by mdcnn_profile_read, in this order. */
 typedef enum {
     MDCNN_K_SHIFT = 0, MDCNN_K_STEP1 = 1, MDCNN_K_LISTS = 2, MDCNN_K_CONV_MFMA = 3,
-    MDCNN_K_CONV_PLAIN = 4, MDCNN_K_IDENTITY = 5, MDCNN_K_READOUT = 6, MDCNN_K_COUNT = 7
+    MDCNN_K_CONV_PLAIN = 4, MDCNN_K_IDENTITY = 5, MDCNN_K_READOUT = 6, MDCNN_K_POOL = 7, MDCNN_K_COUNT = 8
 } mdcnn_kernel_class;
 /* Profiling mode only.  BLOCKS until the launches recorded since the last call
  * have finished, then returns per class the summed device time in milliseconds

@@ -17,10 +17,10 @@ MDCNN_OK = 0
 MDCNN_F32, MDCNN_F16 = 0, 1
 MDCNN_SITE_INPUT, MDCNN_SITE_PREACT, MDCNN_SITE_OUTPUT = 0, 1, 2
 (MDCNN_VIEW_A, MDCNN_VIEW_P, MDCNN_VIEW_DELTA, MDCNN_VIEW_FLAGS, MDCNN_VIEW_LIST,
- MDCNN_VIEW_CLIST, MDCNN_VIEW_STATS, MDCNN_VIEW_OUT) = range(8)
+ MDCNN_VIEW_CLIST, MDCNN_VIEW_STATS, MDCNN_VIEW_OUT, MDCNN_VIEW_POOL_PREV) = range(9)
 MDCNN_OPT_CONV_PATH, MDCNN_OPT_PROFILE, MDCNN_OPT_CONV_TILE, MDCNN_OPT_CONV_PIPE, MDCNN_OPT_CONV_XCD, MDCNN_OPT_CONV_KC, \
     MDCNN_OPT_CONV_HALO, MDCNN_OPT_CONV_HALO_SUB, MDCNN_OPT_FUSE_SKIP = range(9)
-KERNEL_CLASSES = ["shift", "step1", "lists", "conv_mfma", "conv_plain", "identity", "readout"]
+KERNEL_CLASSES = ["shift", "step1", "lists", "conv_mfma", "conv_plain", "identity", "readout", "pool"]
 FLAG_N, FLAG_U, FLAG_M = 1, 2, 4
 
 STATUS_NAMES = {0: "OK", 1: "ERR_NULL", 2: "ERR_SHAPE", 3: "ERR_DTYPE", 4: "ERR_ALIGN",
@@ -35,12 +35,12 @@ EXPORTS = ["mdcnn_conv_border", "mdcnn_buffer_bytes", "mdcnn_create_buffer", "md
 class mdcnn_buffer_desc(C.Structure):
     _fields_ = [("H", C.c_int), ("W", C.c_int), ("C", C.c_int), ("dtype", C.c_int), ("kind", C.c_int),
                 ("border", C.c_int * 4), ("tile", C.c_int), ("relu", C.c_int), ("theta", C.c_float),
-                ("bias_dev", C.c_void_p), ("origin_y", C.c_int), ("origin_x", C.c_int)]
+                ("bias_dev", C.c_void_p), ("origin_y", C.c_int), ("origin_x", C.c_int), ("pool_prev", C.c_int)]
 
 
 class mdcnn_conv_desc(C.Structure):
     _fields_ = [("k", C.c_int), ("stride", C.c_int), ("pad", C.c_int), ("Cin", C.c_int), ("Cout", C.c_int),
-                ("up", C.c_int), ("w_dev", C.c_void_p), ("w_packed_dev", C.c_void_p)]
+                ("up", C.c_int), ("w_dev", C.c_void_p), ("w_packed_dev", C.c_void_p), ("op", C.c_int)]
 
 
 class MdcnnError(RuntimeError):

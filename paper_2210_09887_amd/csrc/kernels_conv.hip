@@ -114,6 +114,7 @@ __device__ __forceinline__ int tile_prologue(const EdgeDev& e, int seg, int firs
     if (p < n) {
         decode_entry(e, p, cy, cx, wy, wx);
         if (e.k == 0) vm = (cy >= 0 && cy < e.sH && cx >= 0 && cx < e.sW && (e.sflags[cy * e.sW + cx] & kFlagM)) ? 1u : 0u;
+        else if (e.op == 1 && (cy < 0 || cy >= e.dH || cx < 0 || cx >= e.dW)) vm = 0;     // pooling outputs exist inside the view only
         else vm = tap_mask(e, cy, cx);
     }
     const bool has = vm != 0;
@@ -1080,6 +1081,60 @@ __global__ __launch_bounds__(256) void k_identity(EdgeBatch eb) {
     }
 }
 
+// Max pooling in delta form: for every destination view pixel whose window holds an
+// updated source pixel, y = max of the source's activations f(A) over the in-view
+// pixels of the window; P_dst += y - (newly unveiled ? 0 : previous output); the
+// previous output is replaced by y.  One block per (list segment, group of 8
+// channel chunks), as for the residual skip.
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void k_pool(EdgeBatch eb) {
+    const EdgeDev& e = eb.d[blockIdx.z];                  // blockIdx.z: stream of the batch
+    __shared__ int s_base[kSegPixels], s_wy[kSegPixels], s_wx[kSegPixels];
+    __shared__ unsigned s_vm[kSegPixels];
+    __shared__ int sh[8];
+    const int nseg = edge_segments(e);
+    const int chunks = e.Cin / VEC;
+    const int ch0 = blockIdx.y * 8, nch = chunks - ch0 < 8 ? chunks - ch0 : 8;
+    carry_source_compaction(e, sh);
+    for (int seg = blockIdx.x; seg < nseg; seg += gridDim.x) {
+        __syncthreads();
+        // the destination's flags still hold this frame's N (set by the shift); marking the
+        // pixels touched only ORs U in, so the channel groups may read N at any time
+        const int tot = tile_prologue(e, seg, 0, kSegPixels, blockIdx.y == 0, blockIdx.y == 0, s_base, s_wy, s_wx, s_vm, sh);
+        for (int i = threadIdx.x; i < tot * nch; i += 256) {
+            const int ent = i / nch;
+            const int c0 = (ch0 + i - ent * nch) * VEC;
+            const int oy = s_wy[ent] - e.by0, ox = s_wx[ent] - e.bx0;          // view pixel of the destination
+            float y[VEC];
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) y[q] = -INFINITY;
+            for (int jy = 0; jy < e.k; ++jy)
+                for (int jx = 0; jx < e.k; ++jx) {
+                    const int iy = oy * e.stride - e.pad + jy, ix = ox * e.stride - e.pad + jx;
+                    if (iy < 0 || iy >= e.sH || ix < 0 || ix >= e.sW) continue;
+                    const int ay = wrapc(e.s_aoy + iy, e.sH), ax = wrapc(e.s_aox + ix, e.sW);
+                    const T* a = (const T*)e.sA + ((size_t)ay * e.sW + ax) * e.Cin + c0;
+#pragma unroll
+                    for (int q = 0; q < VEC; ++q) {
+                        float v = (float)a[q];
+                        if (e.s_relu) v = fmaxf(v, 0.f);
+                        y[q] = fmaxf(y[q], v);
+                    }
+                }
+            const bool fresh = e.dflags[oy * e.dW + ox] & kFlagN;
+            const int yy = wrapc(e.d_aoy + oy, e.dH), yx = wrapc(e.d_aox + ox, e.dW);
+            T* prev = (T*)e.dY + ((size_t)yy * e.dW + yx) * e.Cout + c0;
+            T* pp = (T*)e.P + pdst_offset(e, s_wy[ent], s_wx[ent]) + c0;
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) {
+                const float d = y[q] - (fresh ? 0.f : (float)prev[q]);
+                pp[q] = (T)((float)pp[q] + d);
+                prev[q] = (T)y[q];
+            }
+        }
+    }
+}
+
 // Compaction of the update mask alone (a forward call without outgoing edges).
 __global__ __launch_bounds__(256) void k_compact_source(EdgeBatch eb) {
     const EdgeDev& e = eb.d[blockIdx.z];                  // blockIdx.z: stream of the batch
@@ -1259,6 +1314,18 @@ hipError_t launch_conv(const EdgeBatch& eb, int nb, int dtype, int conv_path, hi
     if (e.k < 0) {                                         // no operator: source compaction only
         *cls = kClsLists;
         k_compact_source<<<dim3(cap_blocks(((long long)e.sH * e.sW + kSegPixels - 1) / kSegPixels, 4096), 1, nb), dim3(256), 0, st>>>(eb);
+        return hipGetLastError();
+    }
+    if (e.op == 1) {
+        *cls = kClsPool;
+        const unsigned g = cap_blocks(nseg, 4096);
+        if (dtype == MDCNN_F16) {
+            if (e.Cin % 8 == 0) k_pool<f16, 8><<<dim3(g, (e.Cin / 8 + 7) / 8, nb), dim3(256), 0, st>>>(eb);
+            else k_pool<f16, 1><<<dim3(g, (e.Cin + 7) / 8, nb), dim3(256), 0, st>>>(eb);
+        } else {
+            if (e.Cin % 4 == 0) k_pool<float, 4><<<dim3(g, (e.Cin / 4 + 7) / 8, nb), dim3(256), 0, st>>>(eb);
+            else k_pool<float, 1><<<dim3(g, (e.Cin + 7) / 8, nb), dim3(256), 0, st>>>(eb);
+        }
         return hipGetLastError();
     }
     if (e.k == 0) {

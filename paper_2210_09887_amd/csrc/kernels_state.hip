@@ -395,6 +395,7 @@ __global__ __launch_bounds__(256) void k_read_tensor(SiteDev s, int what, T* __r
         if (what == MDCNN_VIEW_A) src = (const T*)s.A + a_offset(s, y, x);
         else if (what == MDCNN_VIEW_P) src = (const T*)s.P + p_offset(s, y, x);
         else if (what == MDCNN_VIEW_OUT) src = (const T*)s.P + p_offset(s, y + s.by0, x + s.bx0);
+        else if (what == MDCNN_VIEW_POOL_PREV) src = (const T*)s.Y + a_offset(s, y, x);
         else { src = (const T*)s.delta + (size_t)pix * s.C; zero = !(s.flags[pix] & kFlagM); }
         T* d = dst + (size_t)pix * s.C + c0;
         if constexpr (VEC > 1) {
@@ -427,7 +428,8 @@ __global__ __launch_bounds__(256) void k_write_tensor(SiteDev s, int what, const
         const int pix = (int)(idx / chunks);
         const int c0 = (int)(idx - (long long)pix * chunks) * VEC;
         const int y = pix / Wn, x = pix - y * Wn;
-        T* d = what == MDCNN_VIEW_A ? (T*)s.A + a_offset(s, y, x) : (T*)s.P + p_offset(s, y, x);
+        T* d = what == MDCNN_VIEW_A ? (T*)s.A + a_offset(s, y, x)
+             : what == MDCNN_VIEW_POOL_PREV ? (T*)s.Y + a_offset(s, y, x) : (T*)s.P + p_offset(s, y, x);
         const T* sp = src + (size_t)pix * s.C + c0;
 #pragma unroll
         for (int i = 0; i < VEC; ++i) d[c0 + i] = sp[i];
@@ -508,7 +510,7 @@ static hipError_t read_tensor_t(const SiteDev& s, int what, void* dst, hipStream
 
 hipError_t launch_read_view(const SiteDev& s, int what, void* dst, hipStream_t st) {
     switch (what) {
-        case MDCNN_VIEW_A: case MDCNN_VIEW_P: case MDCNN_VIEW_DELTA: case MDCNN_VIEW_OUT:
+        case MDCNN_VIEW_A: case MDCNN_VIEW_P: case MDCNN_VIEW_DELTA: case MDCNN_VIEW_OUT: case MDCNN_VIEW_POOL_PREV:
             return s.dtype == MDCNN_F16 ? read_tensor_t<f16>(s, what, dst, st) : read_tensor_t<float>(s, what, dst, st);
         case MDCNN_VIEW_FLAGS:
             k_copy_bytes<<<dim3(grid_for(s.H * s.W)), dim3(256), 0, st>>>(s.flags, (uint8_t*)dst, s.H * s.W);

@@ -57,7 +57,7 @@ size_t esize(int dtype) { return dtype == MDCNN_F16 ? 2 : 4; }
 long long pmod(long long v, long long n) { long long r = v % n; return r < 0 ? r + n : r; }
 
 struct Layout {
-    size_t A, P, flags, delta, list, lcnt, lacc, clist, ccnt, cacc, counters, total;
+    size_t A, P, flags, delta, list, lcnt, lacc, clist, ccnt, cacc, counters, Y, total;
     int nseg_l, nseg_c;
     int Hp, Wp;
 };
@@ -73,6 +73,8 @@ mdcnn_status check_desc(const mdcnn_buffer_desc* d) {
     if (d->tile < 1) return fail(MDCNN_ERR_SHAPE, "tile must be >= 1");
     if (d->kind == MDCNN_SITE_INPUT && (d->border[0] | d->border[1] | d->border[2] | d->border[3]))
         return fail(MDCNN_ERR_SHAPE, "an INPUT site has no border");
+    if (d->pool_prev != 0 && (d->pool_prev != 1 || d->kind != MDCNN_SITE_PREACT))
+        return fail(MDCNN_ERR_SHAPE, "pool_prev is 0 or 1 and needs a PREACT site");
     return MDCNN_OK;
 }
 
@@ -98,6 +100,7 @@ void make_layout(const mdcnn_buffer_desc& d, Layout& L) {
     L.ccnt = take(hasP ? nseg_c * 4 : 0);
     L.cacc = take(hasP ? nseg_c * 8 : 0);
     L.counters = take(kNumCounters * 4);
+    L.Y = take(d.pool_prev ? (size_t)d.H * d.W * d.C * e : 0);
     L.total = off;
 }
 
@@ -150,10 +153,11 @@ mdcnn_status validate_edge(const mdcnn_buffer* in, const mdcnn_buffer* out, cons
     if (c.Cin != in->d.C || c.Cout != out->d.C)
         return fail(MDCNN_ERR_SHAPE, "edge %d: channels %d->%d do not match sites %d->%d", idx, c.Cin, c.Cout, in->d.C, out->d.C);
     if (c.k == 0) {
-        if (c.stride != 1 || c.pad != 0 || c.up != 0 || c.Cin != c.Cout || in->d.H != out->d.H || in->d.W != out->d.W)
+        if (c.op != 0 || c.stride != 1 || c.pad != 0 || c.up != 0 || c.Cin != c.Cout || in->d.H != out->d.H || in->d.W != out->d.W)
             return fail(MDCNN_ERR_SHAPE, "edge %d: identity edge needs equal shapes, stride 1, pad 0, up 0", idx);
         return MDCNN_OK;
     }
+    if (c.op != 0 && c.op != 1) return fail(MDCNN_ERR_SHAPE, "edge %d: unknown op %d", idx, c.op);
     if (c.k < 1 || c.k > 5 || c.stride < 1 || c.stride > 4 || c.pad < 0 || c.pad >= c.k || c.up < 0 || c.up > 5)
         return fail(MDCNN_ERR_SHAPE, "edge %d: unsupported geometry k=%d stride=%d pad=%d up=%d", idx, c.k, c.stride, c.pad, c.up);
     if (c.up && (c.k != 1 || c.stride != 1 || c.pad != 0))
@@ -163,6 +167,12 @@ mdcnn_status validate_edge(const mdcnn_buffer* in, const mdcnn_buffer* out, cons
     const int oh = (in->d.H + 2 * c.pad - c.k) / c.stride + 1, ow = (in->d.W + 2 * c.pad - c.k) / c.stride + 1;
     if ((oh << c.up) != out->d.H || (ow << c.up) != out->d.W)
         return fail(MDCNN_ERR_SHAPE, "edge %d: output %dx%d does not match destination %dx%d", idx, oh << c.up, ow << c.up, out->d.H, out->d.W);
+    if (c.op == 1) {                                       // max pooling: no weights, no border
+        if (c.up || c.Cin != c.Cout) return fail(MDCNN_ERR_SHAPE, "edge %d: max pooling needs up == 0 and Cin == Cout", idx);
+        if (out->d.kind != MDCNN_SITE_PREACT || !out->d.pool_prev)
+            return fail(MDCNN_ERR_SHAPE, "edge %d: the destination of a max pooling must be a PREACT site with pool_prev = 1", idx);
+        return MDCNN_OK;
+    }
     int by0, by1, bx0, bx1;
     mdcnn_status st = border_1d(c.k, c.stride, c.pad, in->d.H, oh, &by0, &by1);
     if (st) return st;
@@ -190,7 +200,10 @@ EdgeDev make_edge(const mdcnn_buffer* in, const mdcnn_buffer* out, const mdcnn_c
     e.clist = out->dev.clist; e.ccnt = out->dev.ccnt; e.cacc = out->dev.cacc; e.dcounters = out->dev.counters;
     e.dH = out->d.H; e.dW = out->d.W; e.Cout = c.Cout; e.Hp = out->L.Hp; e.Wp = out->L.Wp;
     e.by0 = out->d.border[0]; e.bx0 = out->d.border[2]; e.p_oy = out->dev.p_oy; e.p_ox = out->dev.p_ox;
-    e.w = c.w_dev; e.wp = c.k ? c.w_packed_dev : nullptr; e.k = c.k; e.stride = c.k ? c.stride : 1; e.pad = c.k ? c.pad : 0; e.up = c.k ? c.up : 0;
+    e.op = c.k ? c.op : 0;
+    e.sA = in->dev.A; e.s_aoy = in->dev.a_oy; e.s_aox = in->dev.a_ox; e.s_relu = in->d.relu;
+    e.dY = out->dev.Y; e.d_aoy = out->dev.a_oy; e.d_aox = out->dev.a_ox;
+    e.w = c.w_dev; e.wp = c.k && !c.op ? c.w_packed_dev : nullptr; e.k = c.k; e.stride = c.k ? c.stride : 1; e.pad = c.k ? c.pad : 0; e.up = c.k ? c.up : 0;
     return e;
 }
 
@@ -298,7 +311,7 @@ bool same_shape(const mdcnn_net* a, const mdcnn_net* b) {
     }
     for (size_t i = 0; i < a->edges.size(); ++i) {
         const mdcnn_conv_desc &x = a->edges[i], &y = b->edges[i];
-        if (x.k != y.k || x.stride != y.stride || x.pad != y.pad || x.Cin != y.Cin || x.Cout != y.Cout || x.up != y.up ||
+        if (x.k != y.k || x.stride != y.stride || x.pad != y.pad || x.Cin != y.Cin || x.Cout != y.Cout || x.up != y.up || x.op != y.op ||
             (x.w_packed_dev == nullptr) != (y.w_packed_dev == nullptr))
             return false;
     }
@@ -446,6 +459,7 @@ mdcnn_status mdcnn_create_buffer(const mdcnn_buffer_desc* desc, void* dev_mem, s
     s.P = hasP ? base + b->L.P : nullptr;
     s.flags = hasA ? (uint8_t*)(base + b->L.flags) : nullptr;
     s.delta = hasA ? base + b->L.delta : nullptr;
+    s.Y = desc->pool_prev ? base + b->L.Y : nullptr;
     s.list = hasA ? (int*)(base + b->L.list) : nullptr;
     s.lcnt = hasA ? (int*)(base + b->L.lcnt) : nullptr;
     s.lacc = hasA ? (unsigned long long*)(base + b->L.lacc) : nullptr;
@@ -653,6 +667,9 @@ static mdcnn_status view_bytes(const mdcnn_buffer* b, int what, size_t* need) {
             *need = ((size_t)b->L.Hp * b->L.Wp + 1) * 4; return MDCNN_OK;
         case MDCNN_VIEW_STATS:
             *need = 18 * 4; return MDCNN_OK;
+        case MDCNN_VIEW_POOL_PREV:
+            if (!d.pool_prev) return fail(MDCNN_ERR_STATE, "the site keeps no previous pooling output");
+            *need = (size_t)d.H * d.W * d.C * e; return MDCNN_OK;
         default:
             return fail(MDCNN_ERR_SIZE, "unknown view %d", what);
     }
@@ -674,8 +691,8 @@ mdcnn_status mdcnn_read_view(const mdcnn_buffer* buf, int what, void* dst_dev, s
 mdcnn_status mdcnn_write_view(mdcnn_buffer* buf, int what, const void* src_dev, size_t bytes, void* stream) {
     if (!buf || !src_dev) return fail(MDCNN_ERR_NULL, "buf/src is NULL");
     if (buf->fresh) return fail(MDCNN_ERR_STATE, "buffer was never reset (shift first)");
-    if (what != MDCNN_VIEW_A && what != MDCNN_VIEW_P && what != MDCNN_VIEW_FLAGS)
-        return fail(MDCNN_ERR_SIZE, "only A, P and FLAGS can be written");
+    if (what != MDCNN_VIEW_A && what != MDCNN_VIEW_P && what != MDCNN_VIEW_FLAGS && what != MDCNN_VIEW_POOL_PREV)
+        return fail(MDCNN_ERR_SIZE, "only A, P, FLAGS and POOL_PREV can be written");
     size_t need = 0;
     mdcnn_status st = view_bytes(buf, what, &need);
     if (st) return st;

@@ -49,6 +49,7 @@ struct SiteDev {
     unsigned long long* cacc;   // per segment: running sum of compute-list entries
     int* counters;        // kNumCounters
     const float* bias;    // C floats or nullptr
+    void* Y;              // ring H x W x C: previous max-pooling output (pool_prev sites), else nullptr
     int H, W, C, Hp, Wp;
     int by0, bx0;         // border before the view (rows, cols)
     int a_oy, a_ox;       // physical ring position of view pixel (0,0) in A
@@ -121,6 +122,10 @@ struct EdgeDev {
     const void* w;            // [tap][cout][cin]
     const void* wp;           // the same weights packed [tap][cin/16][cout][16], or nullptr
     int k, stride, pad, up;
+    // max pooling (op == 1): the source's accumulated ring and the destination's previous outputs
+    const void* sA;
+    void* dY;
+    int s_aoy, s_aox, s_relu, d_aoy, d_aox, op;
 };
 
 // Several independent streams (same network, own buffers and camera paths) share
@@ -137,7 +142,7 @@ struct Step1Batch {
 static_assert(sizeof(FillBatch) <= 4000, "kernel arguments stay below 4 KiB");
 static_assert(sizeof(EdgeBatch) <= 3800 && sizeof(Step1Batch) <= 3800, "kernel arguments stay below 4 KiB");
 
-enum KernelClass { kClsShift = 0, kClsStep1, kClsLists, kClsConvMfma, kClsConvPlain, kClsIdentity, kClsReadout, kNumClasses };
+enum KernelClass { kClsShift = 0, kClsStep1, kClsLists, kClsConvMfma, kClsConvPlain, kClsIdentity, kClsReadout, kClsPool, kNumClasses };
 
 hipError_t launch_shift_fill(const FillBatch& fb, hipStream_t st);
 // n streams; geometry and dtype are those of stream 0 (the host checks that all agree)

@@ -34,10 +34,14 @@ class GpuNet:
         border = [[0, 0, 0, 0] for _ in range(n)]
         bias = [None] * n
         self.weights, self.edges, self.esrc, self.edst = [], [], [], []
+        pooled = set()
         for e in spec.edges:
             Hs, Ws, _ = self.shape[e.src]
-            cd = B.mdcnn_conv_desc(e.k, e.stride, e.pad, spec.sites[e.src].C, spec.sites[e.dst].C, e.up, None, None)
-            if e.k:
+            cd = B.mdcnn_conv_desc(e.k, e.stride, e.pad, spec.sites[e.src].C, spec.sites[e.dst].C, e.up, None, None,
+                                   1 if getattr(e, "pool", False) else 0)
+            if getattr(e, "pool", False):
+                pooled.add(e.dst)                    # max pooling: no weights, no border
+            elif e.k:
                 oh = (Hs + 2 * e.pad - e.k) // e.stride + 1
                 ow = (Ws + 2 * e.pad - e.k) // e.stride + 1
                 by = B.mdcnn_conv_border(e.k, e.stride, e.pad, Hs, oh)
@@ -74,6 +78,7 @@ class GpuNet:
             d.theta = float(s.theta)
             d.bias_dev = None if self.bias[i] is None else self.bias[i].data_ptr()
             d.origin_y, d.origin_x = (0, 0) if origins is None else origins[i]
+            d.pool_prev = int(i in pooled)
             nbytes = B.mdcnn_buffer_bytes(d)
             mem = torch.empty(nbytes, dtype=torch.uint8, device=self.dev)
             self.mem.append(mem)
@@ -129,7 +134,7 @@ class GpuNet:
     def read(self, i, what) -> np.ndarray:
         H, W, Cc = self.shape[i]
         Hp, Wp = self.win[i]
-        if what in (B.MDCNN_VIEW_A, B.MDCNN_VIEW_DELTA, B.MDCNN_VIEW_OUT):
+        if what in (B.MDCNN_VIEW_A, B.MDCNN_VIEW_DELTA, B.MDCNN_VIEW_OUT, B.MDCNN_VIEW_POOL_PREV):
             t = torch.empty((H, W, Cc), dtype=self.tdtype, device=self.dev)
         elif what == B.MDCNN_VIEW_P:
             t = torch.empty((Hp, Wp, Cc), dtype=self.tdtype, device=self.dev)

@@ -42,6 +42,8 @@ def load_site(g: GpuNet, o: OracleNet, i: int):
         g.write(i, B.MDCNN_VIEW_FLAGS, oracle_flags(s))
     if s.spec.kind != "input":
         g.write(i, B.MDCNN_VIEW_P, s.get_P())
+    if s.pooled:
+        g.write(i, B.MDCNN_VIEW_POOL_PREV, s.get_Y())
 
 
 def teacher_forced(net, frames, shifts, forced=None, origins=None, log=None):
@@ -95,6 +97,8 @@ def teacher_forced(net, frames, shifts, forced=None, origins=None, log=None):
                     if not e.up and e.dst not in seen:
                         pass
                     errs.append(maxerr(g.read(e.dst, B.MDCNN_VIEW_P), d.get_P()))
+                    if getattr(e, "pool", False):   # a maximum of stored values: exact
+                        assert np.array_equal(g.read(e.dst, B.MDCNN_VIEW_POOL_PREV), d.get_Y()), w2 + ": previous pooling output"
                     if d.spec.kind != "output":
                         fl = g.read(e.dst, B.MDCNN_VIEW_FLAGS)
                         assert np.array_equal(fl & (B.FLAG_N | B.FLAG_U), oracle_flags(d)), w2 + ": U flags"

@@ -58,6 +58,31 @@ def test_batch_equals_single_streams(name, n_streams):
         gb.close()
 
 
+def test_batch_with_max_pooling():
+    """The pooling kernel in a batch: streams with different camera paths equal their single runs."""
+    import gpu_harness as H
+    from test_gpu_parity import pool_cases, pool_sequence
+    from paper_2210_09887_amd.runtime import GpuBatch, GpuNet
+    net, tile = pool_cases()["resnet_poolstem_128"]
+    seqs = [pool_sequence(net, tile, n=6, seed=b) for b in range(3)]
+    want = []
+    for fr, sh in seqs:
+        g = GpuNet(net)
+        try:
+            want.append([g.frame(H.dev(fr[t]), int(sh[t][0]), int(sh[t][1]))[0].cpu().numpy().copy() for t in range(len(fr))])
+        finally:
+            g.close()
+    gb = GpuBatch(net, 3)
+    try:
+        for t in range(6):
+            outs, _ = gb.frame([H.dev(fr[t]) for fr, _ in seqs], [int(sh[t][0]) for _, sh in seqs], [int(sh[t][1]) for _, sh in seqs])
+            torch.cuda.synchronize()
+            for b in range(3):
+                assert np.array_equal(outs[b].cpu().numpy(), want[b][t]), f"frame {t} stream {b}"
+    finally:
+        gb.close()
+
+
 def test_batch_argument_checks():
     from paper_2210_09887_amd import binding as B
     from paper_2210_09887_amd.runtime import GpuBatch, GpuNet

@@ -149,6 +149,54 @@ def test_fused_skip_equals_separate_launch(name):
     assert a["resets"] == b["resets"]
 
 
+def pool_cases():
+    from inputs.nets import pool_front_net, pool_net
+    return {
+        "pool_f32_k3s2": (pool_net("f32", 40, 56, (3, 8, 5), 3, 2, 1, theta=0.05, seed=1), 2),
+        "pool_f16_k3s2": (pool_net("f16", 48, 64, (3, 16, 8), 3, 2, 1, theta=0.05, seed=2), 2),
+        "pool_f16_k2s2_odd_channels": (pool_net("f16", 32, 48, (3, 12, 6), 2, 2, 0, theta=0.05, seed=3), 2),
+        "pool_f32_k3s1": (pool_net("f32", 24, 40, (2, 6, 4), 3, 1, 1, theta=0.05, seed=4), 1),
+        "pool_front": (pool_front_net("f16", 32, 48, (8, 8), 3, 2, 1, theta=0.05, seed=5), 2),
+        "resnet_poolstem_128": (build_net(3, H=128, W=128, widths=(32, 64, 64, 128), pool_stem=True), 16),
+    }
+
+
+def pool_sequence(net, tile, n=7, seed=0):
+    """Frames of a seeded blob panorama under a camera that moves by whole tiles and reverses once."""
+    rng = np.random.default_rng(seed)
+    C = net.sites[0].C
+    pano = rng.normal(0, 1, (net.H + 8 * tile, net.W + 8 * tile, C)).astype(np.float32)
+    from scipy.ndimage import gaussian_filter
+    pano = gaussian_filter(pano, (3, 3, 0)) * 4
+    pos = [(2 * tile, 2 * tile)]
+    steps = [(1, 0), (1, 1), (0, 1), (0, 0), (-1, 0), (1, 1)]
+    for k in range(n - 1):
+        dy, dx = steps[k % len(steps)]
+        pos.append((pos[-1][0] + dy * tile, pos[-1][1] + dx * tile))
+    frames, shifts = [], []
+    for k, (y, x) in enumerate(pos):
+        f = pano[y:y + net.H, x:x + net.W] + rng.normal(0, 0.01, (net.H, net.W, C)).astype(np.float32)
+        frames.append(f.astype(net.np_dtype))
+        shifts.append((0, 0) if k == 0 else ((y - pos[k - 1][0]) // tile, (x - pos[k - 1][1]) // tile))
+    return np.stack(frames), np.array(shifts, np.int32)
+
+
+@pytest.mark.parametrize("name", ["pool_f32_k3s2", "pool_f16_k3s2", "pool_f16_k2s2_odd_channels", "pool_f32_k3s1",
+                                  "pool_front", "resnet_poolstem_128"])
+def test_max_pooling(name):
+    """Max pooling in delta form (previous-output buffer, zero reference for newly
+    unveiled pixels): all three protocols against the oracle, moving camera with a reset."""
+    import gpu_harness as H
+    net, tile = pool_cases()[name]
+    frames, shifts = pool_sequence(net, tile)
+    H.teacher_forced(net, frames, shifts, log=log)
+    H.mask_forced(net, frames, shifts)
+    r = H.free_running(net, frames, shifts)
+    log(f"{name}: free-running out_err {r['out_err']:.2e} mask mismatch {r['mask_mismatch']:.2e} resets {r['resets']}")
+    assert sum(r["resets"]) >= 2
+    assert r["mask_mismatch"] < 0.02 and r["out_err"] < 10 * 0.05 + 4 * H.TOL[net.dtype]
+
+
 def test_degenerate_frames():
     """Identical consecutive frames produce empty lists and leave the state untouched;
     a shift of a whole view resets; calls in the wrong order are refused."""
