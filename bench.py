@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--density", type=float, default=0.2, help="config 5 only")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle baseline; 0 disables it")
     ap.add_argument("--dense", action="store_true", help="library dense mode: threshold 0 and all pixels forced")
+    ap.add_argument("--pool-stem", action="store_true",
+                    help="config 3 with the usual ResNet stem: 3x3 stride-2 max pooling after the stem convolution (total stride 16)")
     ap.add_argument("--streams", type=int, default=8,
                     help="after the headline run, the same workload as a batch of this many independent streams "
                          "(mdcnn_frame_batch; reported under \"batched\"); 0 disables it")
@@ -85,14 +87,22 @@ def algorithmic_bytes(g, spec, before, after, frames, fused_skips=True):
     for e in spec.edges:
         if e.k == 0 and not fused_skips:              # fused skips add nothing to the compute statistics
             skip_entries[e.dst] += int(d["updated"][e.src])
+    pool = 0
+    pooled = set()
     for e in spec.edges:
-        if e.k == 0:
+        if getattr(e, "pool", False):
+            # per computed output: stride^2 source rows (each source pixel once), previous output
+            # read + written, pending row read + written
+            pooled.add(e.dst)
+            pool += int(d["compute"][e.dst]) * (e.stride * e.stride + 4) * site_bytes_per_pixel(g, e.dst)
+    for e in spec.edges:
+        if e.k == 0 or getattr(e, "pool", False):
             continue
         conv += int(d["updated"][e.src]) * site_bytes_per_pixel(g, e.src) + frames * e.w.size * g.esize
     for i, s in enumerate(spec.sites):
-        if s.kind != "input":
+        if s.kind != "input" and i not in pooled:
             conv += max(int(d["compute"][i]) - skip_entries[i], 0) * 2 * site_bytes_per_pixel(g, i)
-    return dict(step1=step1, conv=conv)
+    return dict(step1=step1, conv=conv, pool=pool)
 
 
 def measured_traffic(cfg, cls):
@@ -135,6 +145,12 @@ def rooflines(prof, flops_mfma, flops_plain, ab, cfg, with_traffic=True):
         rl_all["step1"] = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                            "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": tr("step1"),
                            "bytes_per_launch": round(ab["step1"] / cnt), "avg_us": round(1e3 * ms / cnt, 2), "launches": int(cnt)}
+    if prof.get("pool", (0, 0))[1]:
+        ms, cnt = prof["pool"]
+        ach = ab["pool"] / (ms * 1e-3) / 1e9
+        rl_all["pool"] = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                          "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None,
+                          "bytes_per_launch": round(ab["pool"] / cnt), "avg_us": round(1e3 * ms / cnt, 2), "launches": int(cnt)}
     roofline = dict(rl_all.get(dominant, next(iter(rl_all.values()))))
     roofline["kernel"] = dominant if dominant in rl_all else next(iter(rl_all))
     return classes, kernel_ms, rl_all, roofline
@@ -209,8 +225,8 @@ def main():
         sys.exit(3)
 
     cfg = a.config
-    net = build_net(cfg)
-    seq = build_sequence(cfg, **({"density": a.density} if cfg == 5 else {}))
+    net = build_net(cfg, **({"pool_stem": True} if a.pool_stem and cfg == 3 else {}))
+    seq = build_sequence(cfg, **({"density": a.density} if cfg == 5 else {"tile": 16} if a.pool_stem and cfg == 3 else {}))
     if a.dense:
         for s in net.sites:
             s.theta = 0.0
@@ -299,6 +315,7 @@ def main():
         "ms_per_step": round(1e3 * dt / a.steps, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": net.dtype, "data": "synthetic",
         "config": {"workload": f"config {cfg}: {net.name}, {T}-frame seeded moving-camera sequence replayed cyclically"
+                               + (", max-pooling stem" if a.pool_stem and cfg == 3 else "")
                                + (", library dense mode" if a.dense else "")
                                + (f", density {a.density}" if cfg == 5 else ""),
                    "input": [net.H, net.W, net.sites[0].C], "sites": len(net.sites), "edges": len(net.edges),

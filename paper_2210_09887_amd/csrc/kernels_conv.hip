@@ -1084,8 +1084,42 @@ __global__ __launch_bounds__(256) void k_identity(EdgeBatch eb) {
 // Max pooling in delta form: for every destination view pixel whose window holds an
 // updated source pixel, y = max of the source's activations f(A) over the in-view
 // pixels of the window; P_dst += y - (newly unveiled ? 0 : previous output); the
-// previous output is replaced by y.  One block per (list segment, group of 8
-// channel chunks), as for the residual skip.
+// previous output is replaced by y.
+template <typename T, int VEC> struct PoolVec {
+    static __device__ __forceinline__ void load(const T* p, float* v) {
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) v[q] = (float)p[q];
+    }
+    static __device__ __forceinline__ void store(T* p, const float* v) {
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) p[q] = (T)v[q];
+    }
+};
+template <> struct PoolVec<f16, 8> {
+    static __device__ __forceinline__ void load(const f16* p, float* v) {
+        const f16x8 t = *reinterpret_cast<const f16x8*>(p);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v[q] = (float)t[q];
+    }
+    static __device__ __forceinline__ void store(f16* p, const float* v) {
+        f16x8 t;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) t[q] = (f16)v[q];
+        *reinterpret_cast<f16x8*>(p) = t;
+    }
+};
+template <> struct PoolVec<float, 4> {
+    static __device__ __forceinline__ void load(const float* p, float* v) {
+        const float4 t = *reinterpret_cast<const float4*>(p);
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    }
+    static __device__ __forceinline__ void store(float* p, const float* v) {
+        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+
+// One block per (list segment, channel chunk): thread t owns entry t of the segment and
+// VEC channels; the k*k source rows of its window are independent 16-byte loads.
 template <typename T, int VEC>
 __global__ __launch_bounds__(256) void k_pool(EdgeBatch eb) {
     const EdgeDev& e = eb.d[blockIdx.z];                  // blockIdx.z: stream of the batch
@@ -1093,45 +1127,40 @@ __global__ __launch_bounds__(256) void k_pool(EdgeBatch eb) {
     __shared__ unsigned s_vm[kSegPixels];
     __shared__ int sh[8];
     const int nseg = edge_segments(e);
-    const int chunks = e.Cin / VEC;
-    const int ch0 = blockIdx.y * 8, nch = chunks - ch0 < 8 ? chunks - ch0 : 8;
+    const int c0 = blockIdx.y * VEC;
     carry_source_compaction(e, sh);
     for (int seg = blockIdx.x; seg < nseg; seg += gridDim.x) {
         __syncthreads();
         // the destination's flags still hold this frame's N (set by the shift); marking the
-        // pixels touched only ORs U in, so the channel groups may read N at any time
+        // pixels touched only ORs U in, so the channel chunks may read N at any time
         const int tot = tile_prologue(e, seg, 0, kSegPixels, blockIdx.y == 0, blockIdx.y == 0, s_base, s_wy, s_wx, s_vm, sh);
-        for (int i = threadIdx.x; i < tot * nch; i += 256) {
-            const int ent = i / nch;
-            const int c0 = (ch0 + i - ent * nch) * VEC;
-            const int oy = s_wy[ent] - e.by0, ox = s_wx[ent] - e.bx0;          // view pixel of the destination
-            float y[VEC];
+        const int ent = threadIdx.x;
+        if (ent >= tot) continue;
+        const int oy = s_wy[ent] - e.by0, ox = s_wx[ent] - e.bx0;              // view pixel of the destination
+        float y[VEC];
 #pragma unroll
-            for (int q = 0; q < VEC; ++q) y[q] = -INFINITY;
-            for (int jy = 0; jy < e.k; ++jy)
-                for (int jx = 0; jx < e.k; ++jx) {
-                    const int iy = oy * e.stride - e.pad + jy, ix = ox * e.stride - e.pad + jx;
-                    if (iy < 0 || iy >= e.sH || ix < 0 || ix >= e.sW) continue;
-                    const int ay = wrapc(e.s_aoy + iy, e.sH), ax = wrapc(e.s_aox + ix, e.sW);
-                    const T* a = (const T*)e.sA + ((size_t)ay * e.sW + ax) * e.Cin + c0;
+        for (int q = 0; q < VEC; ++q) y[q] = -INFINITY;
+        for (int jy = 0; jy < e.k; ++jy)
+            for (int jx = 0; jx < e.k; ++jx) {
+                const int iy = oy * e.stride - e.pad + jy, ix = ox * e.stride - e.pad + jx;
+                if (iy < 0 || iy >= e.sH || ix < 0 || ix >= e.sW) continue;
+                const int ay = wrapc(e.s_aoy + iy, e.sH), ax = wrapc(e.s_aox + ix, e.sW);
+                float v[VEC];
+                PoolVec<T, VEC>::load((const T*)e.sA + ((size_t)ay * e.sW + ax) * e.Cin + c0, v);
 #pragma unroll
-                    for (int q = 0; q < VEC; ++q) {
-                        float v = (float)a[q];
-                        if (e.s_relu) v = fmaxf(v, 0.f);
-                        y[q] = fmaxf(y[q], v);
-                    }
-                }
-            const bool fresh = e.dflags[oy * e.dW + ox] & kFlagN;
-            const int yy = wrapc(e.d_aoy + oy, e.dH), yx = wrapc(e.d_aox + ox, e.dW);
-            T* prev = (T*)e.dY + ((size_t)yy * e.dW + yx) * e.Cout + c0;
-            T* pp = (T*)e.P + pdst_offset(e, s_wy[ent], s_wx[ent]) + c0;
-#pragma unroll
-            for (int q = 0; q < VEC; ++q) {
-                const float d = y[q] - (fresh ? 0.f : (float)prev[q]);
-                pp[q] = (T)((float)pp[q] + d);
-                prev[q] = (T)y[q];
+                for (int q = 0; q < VEC; ++q) y[q] = fmaxf(y[q], e.s_relu ? fmaxf(v[q], 0.f) : v[q]);
             }
-        }
+        const bool fresh = e.dflags[oy * e.dW + ox] & kFlagN;
+        const int yy = wrapc(e.d_aoy + oy, e.dH), yx = wrapc(e.d_aox + ox, e.dW);
+        T* prev = (T*)e.dY + ((size_t)yy * e.dW + yx) * e.Cout + c0;
+        T* pp = (T*)e.P + pdst_offset(e, s_wy[ent], s_wx[ent]) + c0;
+        float pv[VEC], pd[VEC];
+        PoolVec<T, VEC>::load(prev, pv);
+        PoolVec<T, VEC>::load(pp, pd);
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) pd[q] = (float)(T)(pd[q] + (y[q] - (fresh ? 0.f : pv[q])));
+        PoolVec<T, VEC>::store(pp, pd);
+        PoolVec<T, VEC>::store(prev, y);
     }
 }
 
@@ -1320,11 +1349,11 @@ hipError_t launch_conv(const EdgeBatch& eb, int nb, int dtype, int conv_path, hi
         *cls = kClsPool;
         const unsigned g = cap_blocks(nseg, 4096);
         if (dtype == MDCNN_F16) {
-            if (e.Cin % 8 == 0) k_pool<f16, 8><<<dim3(g, (e.Cin / 8 + 7) / 8, nb), dim3(256), 0, st>>>(eb);
-            else k_pool<f16, 1><<<dim3(g, (e.Cin + 7) / 8, nb), dim3(256), 0, st>>>(eb);
+            if (e.Cin % 8 == 0) k_pool<f16, 8><<<dim3(g, e.Cin / 8, nb), dim3(256), 0, st>>>(eb);
+            else k_pool<f16, 1><<<dim3(g, e.Cin, nb), dim3(256), 0, st>>>(eb);
         } else {
-            if (e.Cin % 4 == 0) k_pool<float, 4><<<dim3(g, (e.Cin / 4 + 7) / 8, nb), dim3(256), 0, st>>>(eb);
-            else k_pool<float, 1><<<dim3(g, (e.Cin + 7) / 8, nb), dim3(256), 0, st>>>(eb);
+            if (e.Cin % 4 == 0) k_pool<float, 4><<<dim3(g, e.Cin / 4, nb), dim3(256), 0, st>>>(eb);
+            else k_pool<float, 1><<<dim3(g, e.Cin, nb), dim3(256), 0, st>>>(eb);
         }
         return hipGetLastError();
     }
