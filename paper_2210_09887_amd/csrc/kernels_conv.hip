@@ -11,11 +11,16 @@
 // the segment to the destination's compute list, the copy the ABI exposes, and
 // the first edge of a forward call compacts the source's update mask into L.
 //
+//   k_conv_halo       : 3x3 stride-1 fp16 layers: source rectangle of a tile staged once per
+//                       channel chunk in LDS, packed weights straight into MFMA fragments
 //   k_conv_mfma_tiled : LDS-tiled gather-GEMM on the CDNA4 matrix cores (fp16 in, fp32 acc)
 //   k_conv_mfma_f16   : MFMA without LDS staging (fallback for Cin % 32 != 0)
-//   k_conv_ldsw       : plain FMA with the weights resident in LDS (fp32 nets, stems)
+//   k_conv_small      : 3-channel 3x3 stems, plain FMA
+//   k_conv_ldsw       : plain FMA with the weights resident in LDS (fp32 nets)
 //   k_conv_plain      : plain FMA, any dtype / channel count
-//   k_identity        : residual skip, P_dst[q] += delta[q]
+//   k_identity        : residual skip, P_dst[q] += delta[q] (when it is not fused into step 1)
+//   k_pool            : max pooling in delta form against a previous-output ring
+//   k_pack_weights    : [tap][cout][cin] -> [tap][cin/16][cout][16]
 #include <type_traits>
 
 #include "mdcnn_internal.h"
