@@ -144,3 +144,41 @@ def test_large_site_limits():
         assert np.array_equal(g.read(1, B.MDCNN_VIEW_CLIST), np.flatnonzero(m.ravel()))
     finally:
         g.close()
+
+
+def test_config3_full_512_batch_of_streams():
+    """Two streams of the headline workload in shared launches equal their single runs, bit for bit."""
+    import gpu_harness as H
+    from paper_2210_09887_amd.runtime import GpuBatch, GpuNet
+    net = build_net(3)
+    seq = build_sequence(3, n_frames=5)
+    starts = (0, 1)
+    want = []
+    for s0 in starts:
+        g = GpuNet(net)
+        try:
+            want.append([g.frame(H.dev(seq.frames[t]), int(seq.shifts[t][0]), int(seq.shifts[t][1]))[0].cpu().numpy().copy()
+                         for t in range(s0, s0 + 4)])
+        finally:
+            g.close()
+    gb = GpuBatch(net, 2)
+    try:
+        for k in range(4):
+            ts = [s0 + k for s0 in starts]
+            outs, _ = gb.frame([H.dev(seq.frames[t]) for t in ts], [int(seq.shifts[t][0]) for t in ts], [int(seq.shifts[t][1]) for t in ts])
+            torch.cuda.synchronize()
+            for b in range(2):
+                assert np.array_equal(outs[b].cpu().numpy(), want[b][k]), f"step {k} stream {b}"
+    finally:
+        gb.close()
+
+
+def test_config3_full_512_pooling_stem():
+    """The headline network with the usual max-pooling stem, full size, against the oracle."""
+    import gpu_harness as H
+    net = build_net(3, pool_stem=True)
+    seq = build_sequence(3, n_frames=4, tile=16)
+    r = H.free_running(net, seq.frames, seq.shifts, log=log)
+    log(f"config 3 pooling stem free-running: out_err {r['out_err']:.2e} mask mismatch {r['mask_mismatch']:.2e} resets {r['resets']}")
+    assert r["mask_mismatch"] < 0.02
+    assert r["out_err"] < 0.1 + 4 * H.TOL["f16"]
