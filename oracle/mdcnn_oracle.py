@@ -26,7 +26,12 @@ What is followed, and where the paper defines it:
   -- Buffer management;
 * max pooling keeps the previous output of every pixel in a buffer of its own:
   the delta of a pixel is taken against that previous output, or against zero
-  if the pixel was reset in the current frame -- Supplementary, Maximum Pooling.
+  if the pixel was reset in the current frame -- Supplementary, Maximum Pooling;
+* a frame may cover only a tile-aligned part of the buffers (a crop, e.g. the
+  bounding box of a region of interest); the tile offsets given with the frame
+  place it in the buffers, every layer works on the crop scaled to its own
+  tile size, and the rest of the buffers keeps what it holds -- Spherical
+  Buffers (cropped inputs), Evaluation: Human Pose Estimation.
 
 Arithmetic: stored tensors (A, P, delta maps, weights, frames) are in the
 network's storage dtype; every elementwise operation is done in float32 in the
@@ -81,6 +86,10 @@ class OracleSite:
         self.L = np.zeros(0, np.int32)
         self.n_candidates = 0
         self.Y = np.zeros((self.H, self.W, self.C), self.dtype) if self.pooled else None   # previous pooling output (ring like A)
+        # cropped frames: what a pixel of the ring still owes (rings like A)
+        self.unseen = np.zeros((self.H, self.W), bool)   # allocated, not yet inside any frame
+        self.dirty = np.zeros((self.H, self.W), bool)    # touched by a producer while outside the frame
+        self.crop = (0, self.H, 0, self.W)               # rows y0:y1, columns x0:x1 of the view the frame covers
 
     # ring addressing: global pixel -> physical slot, wrapped (Spherical Buffers)
     def _a_index(self):
@@ -106,6 +115,18 @@ class OracleSite:
     def set_Y(self, v):
         self.Y[self._a_index()] = v
 
+    def get_ring(self, name):
+        return getattr(self, name)[self._a_index()]
+
+    def set_ring(self, name, v):
+        getattr(self, name)[self._a_index()] = v
+
+    def in_crop(self):
+        y0, y1, x0, x1 = self.crop
+        m = np.zeros((self.H, self.W), bool)
+        m[y0:y1, x0:x1] = True
+        return m
+
     def get_P(self):
         """Pending values over the padded window (view plus dilated border)."""
         return self.P[self._p_index()]
@@ -119,8 +140,10 @@ class OracleSite:
 
 
 class OracleNet:
-    def __init__(self, net, origins=None):
+    def __init__(self, net, origins=None, crops=False):
+        """crops=True: frames may cover a part of the buffers only (set_crop)."""
         self.net = net
+        self.crops = bool(crops)
         self.dtype = net.np_dtype
         self.sites = []
         for i, s in enumerate(net.sites):
@@ -173,6 +196,10 @@ class OracleNet:
                 s.P[:] = s.beta.astype(s.dtype)
                 s.N[:] = True
                 s.U[:] = False
+                s.unseen[:] = True
+                s.dirty[:] = False
+                if self.crops and s.pooled:
+                    s.Y[:] = 0
             self.R = dict(up=False, down=False, left=False, right=False)
             self.fresh = False
             self.n_resets += 1
@@ -206,7 +233,26 @@ class OracleNet:
             s.set_A(Av)
             s.N = ~seen
             s.U[:] = False
+            for name, fresh in (("unseen", True), ("dirty", False)):
+                v = s.get_ring(name)
+                v[~seen] = fresh
+                s.set_ring(name, v)
+            if self.crops and s.pooled:
+                Yv = s.get_Y()
+                Yv[~seen] = 0
+                s.set_Y(Yv)
         return False
+
+    def set_crop(self, ty0, tx0, th, tw):
+        """The next frames cover tiles [ty0, ty0+th) x [tx0, tx0+tw) of the
+        buffers' view (tile offsets relative to the view after the shift); every
+        site works on that rectangle scaled by its own tile size
+        (Spherical Buffers: tile offset x layer tile size)."""
+        assert self.crops
+        for s in self.sites:
+            assert 0 <= ty0 and 0 < th and (ty0 + th) * s.tile <= s.H
+            assert 0 <= tx0 and 0 < tw and (tx0 + tw) * s.tile <= s.W
+            s.crop = (ty0 * s.tile, (ty0 + th) * s.tile, tx0 * s.tile, (tx0 + tw) * s.tile)
 
     # ------------------------------------------------------- step 1 of a site
     def _truncate(self, i, frame, forced):
@@ -215,9 +261,34 @@ class OracleNet:
         theta = f32(s.spec.theta)
         A = s.get_A()
         a = A.astype(f32)
+        inside = np.ones((s.H, s.W), bool)
+        if self.crops:
+            # Only the pixels the frame covers are worked on.  Of those, the ones no frame
+            # has covered since they were allocated are the newly unveiled ones, and the ones
+            # a producer touched while they lay outside earlier frames count as touched.
+            y0, y1, x0, x1 = s.crop
+            inside = s.in_crop()
+            unseen, dirty = s.get_ring("unseen"), s.get_ring("dirty")
+            s.N = inside & unseen
+            dirty |= s.U & ~inside                     # remembered until a frame covers the pixel
+            s.U = inside & (s.U | dirty)
+            unseen[inside] = False
+            dirty[inside] = False
+            s.set_ring("unseen", unseen)
+            s.set_ring("dirty", dirty)
+            if frame is not None:                      # the frame and the forced mask have the crop's shape
+                assert frame.shape == (y1 - y0, x1 - x0, s.C)
+                full = np.zeros((s.H, s.W, s.C), s.dtype)
+                full[y0:y1, x0:x1] = frame
+                frame = full
+            if forced is not None:
+                assert forced.shape == (y1 - y0, x1 - x0)
+                full = np.zeros((s.H, s.W), bool)
+                full[y0:y1, x0:x1] = forced.astype(bool)
+                forced = full
         if s.spec.kind == "input":
             assert frame.shape == (s.H, s.W, s.C) and frame.dtype == s.dtype
-            cand = np.ones((s.H, s.W), bool)
+            cand = inside.copy()
             out = frame.astype(f32) - a
             newA = frame
         else:
@@ -225,7 +296,7 @@ class OracleNet:
             t = s.view_of_window(Pw).astype(f32)
             cand = s.U | s.N
             if forced is not None:
-                cand = np.ones((s.H, s.W), bool)
+                cand = inside.copy()
             acc = a + t
             if s.spec.relu:
                 out = np.maximum(acc, f32(0)) - np.maximum(a, f32(0))
@@ -300,7 +371,12 @@ class OracleNet:
                     ok = (iy >= 0) & (iy < src.H) & (ix >= 0) & (ix < src.W)
                     out[ok] = np.maximum(out[ok], act[iy[ok], ix[ok]])
             Yv = dst.get_Y()
-            prev = np.where(dst.N[oy, ox][:, None], f32(0), Yv[oy, ox].astype(f32))
+            if self.crops:
+                # a reset pixel may be pooled in a later frame than the one that reset it:
+                # the reset itself zeroes the previous output (shift_camera)
+                prev = Yv[oy, ox].astype(f32)
+            else:
+                prev = np.where(dst.N[oy, ox][:, None], f32(0), Yv[oy, ox].astype(f32))
             y = out - prev
             Yv[oy, ox] = out.astype(dst.dtype)
             dst.set_Y(Yv)
@@ -343,12 +419,18 @@ class OracleNet:
         out = s.view_of_window(s.get_P()).copy()
         if s.spec.relu:
             out = np.maximum(out, s.dtype(0))
+        if self.crops:
+            y0, y1, x0, x1 = s.crop
+            out = out[y0:y1, x0:x1].copy()
         return out
 
-    def frame(self, X, dty=0, dtx=0, forced=None, forced_all=None):
+    def frame(self, X, dty=0, dtx=0, forced=None, forced_all=None, crop=None):
         """One frame: shift, every non-terminal site in order, readout.
-        `forced` is an input-site mask; `forced_all` maps site index -> mask."""
+        `forced` is an input-site mask; `forced_all` maps site index -> mask;
+        `crop` = (ty0, tx0, th, tw): the tiles of the view that X covers."""
         did_reset = self.shift_camera(dty, dtx)
+        if crop is not None:
+            self.set_crop(*crop)
         for i, s in enumerate(self.sites):
             if s.spec.kind == "output":
                 continue

@@ -93,12 +93,25 @@ class CanvasReference:
         x0 = (self.ox + self.tx * self.net.total_stride) // s.stride
         return slice(y0, y0 + H), slice(x0, x0 + W)
 
-    def frame(self, X, dty, dtx, reset):
+    def _crop(self, i, crop):
+        """The part of site i's view that a frame covering tiles `crop` =
+        (ty0, tx0, th, tw) of the view works on."""
+        vy, vx = self._view(i)
+        if crop is None:
+            return vy, vx
+        t = self.net.total_stride // self.net.sites[i].stride
+        ty0, tx0, th, tw = crop
+        return (slice(vy.start + ty0 * t, vy.start + (ty0 + th) * t),
+                slice(vx.start + tx0 * t, vx.start + (tx0 + tw) * t))
+
+    def frame(self, X, dty, dtx, reset, crop=None):
         self.ty += int(dty)
         self.tx += int(dtx)
         assert abs(self.ty) <= self.ext and abs(self.tx) <= self.ext
         if reset:
             self.clear()
+        if crop is not None:
+            return self._frame_crop(X, crop)
         net = self.net
         self.canvas[0][self._view(0)] = X.astype(np.float64)
         for i in range(1, len(net.sites)):
@@ -111,6 +124,23 @@ class CanvasReference:
             v = self._view(i)
             self.canvas[i][v] = val[v]
         return [self.canvas[i][self._view(i)].copy() for i in net.terminal_sites()]
+
+    def _frame_crop(self, X, crop):
+        """Cropped frame: the same recomputation, but a site's canvas takes the new
+        values inside the crop only (scaled to the site); everything else, inside or
+        outside the view, keeps what it had."""
+        net = self.net
+        self.canvas[0][self._crop(0, crop)] = X.astype(np.float64)
+        for i in range(1, len(net.sites)):
+            acc = np.zeros_like(self.canvas[i]) + site_bias(net, i)
+            for e in net.edges:
+                if e.dst == i:
+                    src = self.canvas[e.src]
+                    acc = acc + (src if e.k == 0 else _conv64(src, e))
+            val = np.maximum(acc, 0) if net.sites[i].relu else acc
+            v = self._crop(i, crop)
+            self.canvas[i][v] = val[v]
+        return [self.canvas[i][self._crop(i, crop)].copy() for i in net.terminal_sites()]
 
     def dense_valid_mask(self, i, radius_px):
         """[H, W] bool for site i: pixels further than radius_px (site pixels)
