@@ -75,6 +75,9 @@ typedef struct {
     int pool_prev;            /* 1: destination of a max-pooling edge: the site also    */
                               /* keeps the previous pooling output of every view pixel  */
                               /* (ring H x W x C, PREACT sites only)                    */
+    int crops;                /* 1: frames may cover a part of the view only            */
+                              /* (mdcnn_set_crop); the site then keeps one more byte    */
+                              /* per view pixel.  All sites of a network must agree.    */
 } mdcnn_buffer_desc;
 
 typedef struct mdcnn_buffer mdcnn_buffer;
@@ -144,6 +147,21 @@ mdcnn_status mdcnn_destroy_buffer(mdcnn_buffer* buf);
 mdcnn_status mdcnn_shift_camera(mdcnn_buffer* const* bufs, int n, int dty, int dtx,
                                 void* stream, int* did_full_reset);
 
+/* Cropped frames, host-only: from now on a frame covers tiles [ty0, ty0 + th) x
+ * [tx0, tx0 + tw) of the view (tile offsets relative to the view as it lies after
+ * the last mdcnn_shift_camera; they stay in force across later shifts until
+ * changed; a new buffer starts with the whole view).  Site by site the crop is
+ * that rectangle times desc.tile pixels.  Only pixels inside the crop are worked
+ * on by mdcnn_layer_forward: of those, the ones no frame has covered since they
+ * were allocated count as newly unveiled, and the ones a producer touched while
+ * they lay outside earlier crops count as touched; a pixel a producer touches
+ * outside the crop keeps the pending value and is remembered.  With the crop equal
+ * to the view the results are those of a network without crops, bit for bit.
+ * Errors: MDCNN_ERR_STATE if a buffer was created with crops == 0,
+ * MDCNN_ERR_SHAPE if the rectangle is empty or leaves the view of a site.
+ *                  [Spherical Buffers: cropped inputs, tile offset indices] */
+mdcnn_status mdcnn_set_crop(mdcnn_buffer* const* bufs, int n, int ty0, int tx0, int th, int tw);
+
 /* One layer of delta inference on site `in`:
  *   1. delta + truncation: INPUT site  d = frame - A;  PREACT site  d = f(A+P) - f(A)
  *      on the pixels a producer touched or that are newly unveiled;
@@ -158,7 +176,9 @@ mdcnn_status mdcnn_shift_camera(mdcnn_buffer* const* bufs, int n, int dty, int d
  * `forced_mask_dev`: NULL, or H*W bytes (0/1) in view order replacing the
  * threshold test (with a forced mask on a PREACT site every in-view pixel is a
  * candidate).  `outs[i]` is the destination of `edges[i]`; OUTPUT sites take no
- * forward call.                  [Background: DeltaCNN; Padded Convolutions] */
+ * forward call.  On a site with a crop (mdcnn_set_crop) `frame_dev` and
+ * `forced_mask_dev` have the crop's extent and order, and step 1 leaves the
+ * pixels outside the crop alone.   [Background: DeltaCNN; Padded Convolutions] */
 mdcnn_status mdcnn_layer_forward(mdcnn_buffer* in, const void* frame_dev,
                                  const uint8_t* forced_mask_dev,
                                  const mdcnn_conv_desc* edges, mdcnn_buffer* const* outs,
@@ -182,6 +202,15 @@ mdcnn_status mdcnn_frame(mdcnn_net* net, const void* frame_dev, const uint8_t* f
                          int dty, int dtx, void* out_dev, size_t out_bytes, void* stream,
                          int* did_full_reset);
 
+/* One cropped frame: mdcnn_shift_camera by (dty, dtx), mdcnn_set_crop(ty0, tx0, th,
+ * tw), the forward calls, then the readout f(P) of every OUTPUT site over its crop,
+ * in crop order (MDCNN_VIEW_CROP_OUT), back to back.  frame_dev / forced_mask_dev
+ * cover the crop of the input site; out_bytes must equal the summed crop sizes.
+ * All sites need crops == 1.  The crop stays in force afterwards. */
+mdcnn_status mdcnn_frame_crop(mdcnn_net* net, const void* frame_dev, const uint8_t* forced_mask_dev,
+                              int dty, int dtx, int ty0, int tx0, int th, int tw,
+                              void* out_dev, size_t out_bytes, void* stream, int* did_full_reset);
+
 /* The same for n_streams independent video streams in the same launches (the
  * paper fills the GPU with a batch of streams [Evaluation: batch size]).  Stream b
  * is nets[b]: all nets must have the same topology and the same site and edge
@@ -192,7 +221,8 @@ mdcnn_status mdcnn_frame(mdcnn_net* net, const void* frame_dev, const uint8_t* f
  * entries; did_full_reset: n_streams ints or NULL.  The results of every stream
  * are identical, bit for bit, to those of mdcnn_frame on it alone.
  * Errors: MDCNN_ERR_SHAPE if the nets differ, MDCNN_ERR_STATE if two streams
- * share a net or buffers, MDCNN_ERR_SIZE for n_streams out of range. */
+ * share a net or buffers or a stream has a crop smaller than its view,
+ * MDCNN_ERR_SIZE for n_streams out of range. */
 mdcnn_status mdcnn_frame_batch(mdcnn_net* const* nets, int n_streams, const void* const* frames_dev,
                                const uint8_t* const* forced_masks_dev, const int* dty, const int* dtx,
                                void* const* outs_dev, size_t out_bytes, void* stream, int* did_full_reset);
@@ -213,11 +243,14 @@ typedef enum {
                              /* accumulates of the MFMA kernel into this site, compute-list */
                              /* entries, multiply-accumulates of the plain kernel           */
     MDCNN_VIEW_OUT = 7,      /* H*W*C storage dtype: f(P) over the view (readout)           */
-    MDCNN_VIEW_POOL_PREV = 8 /* H*W*C storage dtype: previous pooling output (pool_prev sites) */
+    MDCNN_VIEW_POOL_PREV = 8,/* H*W*C storage dtype: previous pooling output (pool_prev sites) */
+    MDCNN_VIEW_CROP_OUT = 9, /* h*w*C storage dtype: f(P) over the crop, crop order (read only) */
+    MDCNN_VIEW_PENDING = 10  /* H*W bytes, sites with crops: bit0 no frame has covered the pixel */
+                             /* since it was allocated, bit1 touched while outside the crops   */
 } mdcnn_view;
 mdcnn_status mdcnn_read_view(const mdcnn_buffer* buf, int what, void* dst_dev, size_t bytes,
                              void* stream);
-/* Overwrite A, P, FLAGS or POOL_PREV from view-ordered data (restoring a saved state). */
+/* Overwrite A, P, FLAGS, POOL_PREV or PENDING from view-ordered data (restoring a saved state). */
 mdcnn_status mdcnn_write_view(mdcnn_buffer* buf, int what, const void* src_dev, size_t bytes,
                               void* stream);
 

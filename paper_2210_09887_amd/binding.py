@@ -17,25 +17,27 @@ MDCNN_OK = 0
 MDCNN_F32, MDCNN_F16 = 0, 1
 MDCNN_SITE_INPUT, MDCNN_SITE_PREACT, MDCNN_SITE_OUTPUT = 0, 1, 2
 (MDCNN_VIEW_A, MDCNN_VIEW_P, MDCNN_VIEW_DELTA, MDCNN_VIEW_FLAGS, MDCNN_VIEW_LIST,
- MDCNN_VIEW_CLIST, MDCNN_VIEW_STATS, MDCNN_VIEW_OUT, MDCNN_VIEW_POOL_PREV) = range(9)
+ MDCNN_VIEW_CLIST, MDCNN_VIEW_STATS, MDCNN_VIEW_OUT, MDCNN_VIEW_POOL_PREV, MDCNN_VIEW_CROP_OUT,
+ MDCNN_VIEW_PENDING) = range(11)
 MDCNN_OPT_CONV_PATH, MDCNN_OPT_PROFILE, MDCNN_OPT_CONV_TILE, MDCNN_OPT_CONV_PIPE, MDCNN_OPT_CONV_XCD, MDCNN_OPT_CONV_KC, \
     MDCNN_OPT_CONV_HALO, MDCNN_OPT_CONV_HALO_SUB, MDCNN_OPT_FUSE_SKIP = range(9)
 KERNEL_CLASSES = ["shift", "step1", "lists", "conv_mfma", "conv_plain", "identity", "readout", "pool"]
 FLAG_N, FLAG_U, FLAG_M = 1, 2, 4
+STATE_UNSEEN, STATE_DIRTY = 1, 2
 
 STATUS_NAMES = {0: "OK", 1: "ERR_NULL", 2: "ERR_SHAPE", 3: "ERR_DTYPE", 4: "ERR_ALIGN",
                 5: "ERR_SIZE", 6: "ERR_STATE", 7: "ERR_HIP"}
 
 EXPORTS = ["mdcnn_conv_border", "mdcnn_buffer_bytes", "mdcnn_create_buffer", "mdcnn_destroy_buffer",
-           "mdcnn_shift_camera", "mdcnn_layer_forward", "mdcnn_net_create", "mdcnn_net_destroy",
-           "mdcnn_frame", "mdcnn_frame_batch", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read",
+           "mdcnn_shift_camera", "mdcnn_set_crop", "mdcnn_layer_forward", "mdcnn_net_create", "mdcnn_net_destroy",
+           "mdcnn_frame", "mdcnn_frame_crop", "mdcnn_frame_batch", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read",
            "mdcnn_pack_weights", "mdcnn_last_error", "mdcnn_version"]
 
 
 class mdcnn_buffer_desc(C.Structure):
     _fields_ = [("H", C.c_int), ("W", C.c_int), ("C", C.c_int), ("dtype", C.c_int), ("kind", C.c_int),
                 ("border", C.c_int * 4), ("tile", C.c_int), ("relu", C.c_int), ("theta", C.c_float),
-                ("bias_dev", C.c_void_p), ("origin_y", C.c_int), ("origin_x", C.c_int), ("pool_prev", C.c_int)]
+                ("bias_dev", C.c_void_p), ("origin_y", C.c_int), ("origin_x", C.c_int), ("pool_prev", C.c_int), ("crops", C.c_int)]
 
 
 class mdcnn_conv_desc(C.Structure):
@@ -65,6 +67,8 @@ def lib():
         L.mdcnn_create_buffer.argtypes = [C.POINTER(mdcnn_buffer_desc), vp, sz, C.POINTER(vp)]
         L.mdcnn_destroy_buffer.argtypes = [vp]
         L.mdcnn_shift_camera.argtypes = [C.POINTER(vp), C.c_int, C.c_int, C.c_int, vp, ip]
+        L.mdcnn_set_crop.argtypes = [C.POINTER(vp), C.c_int] + [C.c_int] * 4
+        L.mdcnn_frame_crop.argtypes = [vp, vp, vp] + [C.c_int] * 6 + [vp, sz, vp, ip]
         L.mdcnn_layer_forward.argtypes = [vp, vp, vp, C.POINTER(mdcnn_conv_desc), C.POINTER(vp), C.c_int, vp]
         L.mdcnn_net_create.argtypes = [C.POINTER(vp), C.c_int, ip, ip, C.POINTER(mdcnn_conv_desc), C.c_int,
                                        C.POINTER(vp)]
@@ -142,6 +146,10 @@ def mdcnn_shift_camera(bufs, dty: int, dtx: int, stream: int = 0) -> bool:
     return bool(r.value)
 
 
+def mdcnn_set_crop(bufs, ty0: int, tx0: int, th: int, tw: int):
+    _check(lib().mdcnn_set_crop(_handles(bufs), len(bufs), int(ty0), int(tx0), int(th), int(tw)))
+
+
 def mdcnn_layer_forward(buf: int, frame_ptr, forced_ptr, edges, outs, stream: int = 0):
     n = len(edges)
     arr = (mdcnn_conv_desc * max(n, 1))(*edges)
@@ -168,6 +176,16 @@ def mdcnn_frame(net: int, frame_ptr: int, forced_ptr, dty: int, dtx: int, out_pt
                 stream: int = 0) -> bool:
     r = C.c_int()
     _check(lib().mdcnn_frame(net, frame_ptr, forced_ptr, int(dty), int(dtx), out_ptr, out_bytes, stream, C.byref(r)))
+    return bool(r.value)
+
+
+def mdcnn_frame_crop(net: int, frame_ptr: int, forced_ptr, dty: int, dtx: int, crop, out_ptr: int, out_bytes: int,
+                     stream: int = 0) -> bool:
+    """crop = (ty0, tx0, th, tw) in tiles of the view."""
+    r = C.c_int()
+    ty0, tx0, th, tw = (int(v) for v in crop)
+    _check(lib().mdcnn_frame_crop(net, frame_ptr, forced_ptr, int(dty), int(dtx), ty0, tx0, th, tw, out_ptr, out_bytes,
+                                  stream, C.byref(r)))
     return bool(r.value)
 
 

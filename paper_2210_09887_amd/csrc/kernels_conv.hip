@@ -119,7 +119,7 @@ __device__ __forceinline__ int tile_prologue(const EdgeDev& e, int seg, int firs
     if (p < n) {
         decode_entry(e, p, cy, cx, wy, wx);
         if (e.k == 0) vm = (cy >= 0 && cy < e.sH && cx >= 0 && cx < e.sW && (e.sflags[cy * e.sW + cx] & kFlagM)) ? 1u : 0u;
-        else if (e.op == 1 && (cy < 0 || cy >= e.dH || cx < 0 || cx >= e.dW)) vm = 0;     // pooling outputs exist inside the view only
+        else if (e.op && (cy < 0 || cy >= e.dH || cx < 0 || cx >= e.dW)) vm = 0;     // pooling outputs exist inside the view only
         else vm = tap_mask(e, cy, cx);
     }
     const bool has = vm != 0;
@@ -1155,7 +1155,9 @@ __global__ __launch_bounds__(256) void k_pool(EdgeBatch eb) {
 #pragma unroll
                 for (int q = 0; q < VEC; ++q) y[q] = fmaxf(y[q], e.s_relu ? fmaxf(v[q], 0.f) : v[q]);
             }
-        const bool fresh = e.dflags[oy * e.dW + ox] & kFlagN;
+        // op == 2: the reset of a pixel zeroed its previous output as well (sites with crops, where a
+        // reset pixel may be pooled in a later frame than the reset)
+        const bool fresh = e.op == 1 && (e.dflags[oy * e.dW + ox] & kFlagN);
         const int yy = wrapc(e.d_aoy + oy, e.dH), yx = wrapc(e.d_aox + ox, e.dW);
         T* prev = (T*)e.dY + ((size_t)yy * e.dW + yx) * e.Cout + c0;
         T* pp = (T*)e.P + pdst_offset(e, s_wy[ent], s_wx[ent]) + c0;
@@ -1350,7 +1352,7 @@ hipError_t launch_conv(const EdgeBatch& eb, int nb, int dtype, int conv_path, hi
         k_compact_source<<<dim3(cap_blocks(((long long)e.sH * e.sW + kSegPixels - 1) / kSegPixels, 4096), 1, nb), dim3(256), 0, st>>>(eb);
         return hipGetLastError();
     }
-    if (e.op == 1) {
+    if (e.op) {
         *cls = kClsPool;
         const unsigned g = cap_blocks(nseg, 4096);
         if (dtype == MDCNN_F16) {

@@ -55,7 +55,8 @@ __device__ __forceinline__ size_t skip_offset(const SkipDev& k, int vy, int vx, 
 // Dynamic initialisation, all sites of a network in one launch.  Pixels of the
 // new padded window outside the kept rectangle get P = bias (the activation
 // adds it later on); pixels of the new view outside the kept rectangle get
-// A = 0 and flag N.  Per-frame counters are cleared here.
+// A = 0 and flag N (sites with crops: state "unseen" in their ring S and a zero
+// previous pooling output).  Per-frame counters are cleared here.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void decode_new(int Wn, int Hn, int y0, int y1, int x0, int x1, int idx, int& y, int& x) {
     const int top = y0 * Wn;
@@ -85,6 +86,8 @@ __device__ __forceinline__ void fill_items(const FillJob& j, unsigned lb) {
     const long long begin = (long long)lb * kFillItemsPerBlock;
     long long end = begin + kFillItemsPerBlock;
     if (end > total) end = total;
+    uint8_t* const Sr = j.s_off ? (uint8_t*)j.A + (size_t)j.s_off * 256 : nullptr;   // rings like A
+    T* const Yr = j.y_off ? (T*)((char*)j.A + (size_t)j.y_off * 256) : nullptr;
     if constexpr (VEC > 1) {
         // Full reset with a power-of-two number of 16-byte chunks per pixel (<= 256): the
         // rings are filled front to back, a thread keeps its channel chunk over the whole
@@ -104,7 +107,11 @@ __device__ __forceinline__ void fill_items(const FillJob& j, unsigned lb) {
                 } else {
                     const unsigned ia = idx - nPc;
                     V16<T>::store((T*)j.A + (size_t)ia * VEC, zv);
-                    if (c0 == 0) j.flags[ia >> sh] = (uint8_t)kFlagN;
+                    if (Yr) V16<T>::store(Yr + (size_t)ia * VEC, zv);
+                    if (c0 == 0) {
+                        j.flags[ia >> sh] = (uint8_t)kFlagN;
+                        if (Sr) Sr[ia >> sh] = (uint8_t)kStateUnseen;
+                    }
                 }
             }
             return;
@@ -147,10 +154,15 @@ __device__ __forceinline__ void fill_items(const FillJob& j, unsigned lb) {
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) v[i] = 0.f;
                 V16<T>::store(p, v);
+                if (Yr) V16<T>::store(Yr + aoff * j.C + c0, v);
             } else {
                 p[0] = (T)0.f;
+                if (Yr) Yr[aoff * j.C + c0] = (T)0.f;
             }
-            if (c0 == 0) j.flags[vlin] = (uint8_t)kFlagN;
+            if (c0 == 0) {
+                j.flags[vlin] = (uint8_t)kFlagN;
+                if (Sr) Sr[aoff] = (uint8_t)kStateUnseen;
+            }
         }
     }
 }
@@ -188,6 +200,30 @@ hipError_t launch_shift_fill(const FillBatch& fb, hipStream_t st) {
 // G lanes share one pixel, each lane owns CH 16-byte chunks of its channels.
 // The block writes its update / candidate counts for the compaction pass.
 // ---------------------------------------------------------------------------
+// Sites with crops.  A pixel inside the crop takes its flags from the state ring: newly
+// unveiled if no frame has covered it since it was allocated, touched if a producer touched
+// it this frame or while it lay outside earlier crops; its state is cleared.  A pixel outside
+// the crop is left alone, and a touch of this frame is remembered in the ring.  All lanes of
+// a pixel read the state, `writer` (one of them, same wavefront) updates it afterwards.
+// Returns whether the pixel is inside; fl becomes the flags to act on, xpix the pixel's
+// index in crop order.
+__device__ __forceinline__ bool crop_state(const SiteDev& s, int pix, bool writer, int& fl, int& xpix) {
+    const int vy = pix / s.W, vx = pix - vy * s.W;
+    uint8_t* sp = s.S() + a_offset(s, vy, vx) / s.C;
+    const int y0 = s.cy0(), x0 = s.cx0(), x1 = s.cx1();
+    const bool inside = vy >= y0 && vy < s.cy1() && vx >= x0 && vx < x1;
+    if (inside) {
+        const int st = *sp;
+        if (st && writer) *sp = 0;
+        fl = (fl & kFlagU) | (st & kStateUnseen ? kFlagN : 0) | (st & kStateDirty ? kFlagU : 0);
+        xpix = (vy - y0) * (x1 - x0) + (vx - x0);
+    } else {
+        if ((fl & kFlagU) && writer) *sp |= (uint8_t)kStateDirty;
+        fl = 0;
+    }
+    return inside;
+}
+
 template <typename T, int G, int CH>
 __global__ __launch_bounds__(256) void k_step1(Step1Batch bt) {
     const SiteDev& s = bt.s[blockIdx.z];
@@ -202,14 +238,17 @@ __global__ __launch_bounds__(256) void k_step1(Step1Batch bt) {
     const int HW = s.H * s.W;
     bool m = false, cand = false;
     if (pix < HW) {
-        const int fl = s.flags[pix];
+        int fl = s.flags[pix];
         const bool is_input = s.kind == MDCNN_SITE_INPUT;
-        cand = is_input || forced != nullptr || (fl & (kFlagN | kFlagU));
+        int xpix = pix;                                    // index into the frame and the forced mask
+        bool inside = true;
+        if (s.s_off) inside = crop_state(s, pix, lp == 0, fl, xpix);
+        cand = inside && (is_input || forced != nullptr || (fl & (kFlagN | kFlagU)));
         if (cand) {
             const int vy = pix / s.W, vx = pix - vy * s.W;
             T* Ap = (T*)s.A + a_offset(s, vy, vx);
             T* Pp = is_input ? nullptr : (T*)s.P + p_offset(s, vy + s.by0, vx + s.bx0);
-            const T* Xp = is_input ? X + (size_t)pix * s.C : nullptr;
+            const T* Xp = is_input ? X + (size_t)xpix * s.C : nullptr;
             float na[CH][VEC], out[CH][VEC];
             float mx = 0.f;
 #pragma unroll
@@ -235,7 +274,7 @@ __global__ __launch_bounds__(256) void k_step1(Step1Batch bt) {
             }
 #pragma unroll
             for (int off = G / 2; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-            const bool hit = forced ? forced[pix] != 0 : mx > s.theta;
+            const bool hit = forced ? forced[xpix] != 0 : mx > s.theta;
             m = (fl & kFlagN) || hit;
             if (m) {
                 T* Dp = (T*)s.delta + (size_t)pix * s.C;
@@ -280,14 +319,17 @@ __global__ __launch_bounds__(256) void k_step1_scalar(Step1Batch bt) {
     const int HW = s.H * s.W;
     bool m = false, cand = false;
     if (pix < HW) {
-        const int fl = s.flags[pix];
+        int fl = s.flags[pix];
         const bool is_input = s.kind == MDCNN_SITE_INPUT;
-        cand = is_input || forced != nullptr || (fl & (kFlagN | kFlagU));
+        int xpix = pix;
+        bool inside = true;
+        if (s.s_off) inside = crop_state(s, pix, true, fl, xpix);
+        cand = inside && (is_input || forced != nullptr || (fl & (kFlagN | kFlagU)));
         if (cand) {
             const int vy = pix / s.W, vx = pix - vy * s.W;
             T* Ap = (T*)s.A + a_offset(s, vy, vx);
             T* Pp = is_input ? nullptr : (T*)s.P + p_offset(s, vy + s.by0, vx + s.bx0);
-            const T* Xp = is_input ? X + (size_t)pix * s.C : nullptr;
+            const T* Xp = is_input ? X + (size_t)xpix * s.C : nullptr;
             float mx = 0.f;
             for (int c = 0; c < s.C; ++c) {
                 float a = (float)Ap[c], o;
@@ -299,7 +341,7 @@ __global__ __launch_bounds__(256) void k_step1_scalar(Step1Batch bt) {
                 }
                 mx = fmaxf(mx, fabsf(o));
             }
-            const bool hit = forced ? forced[pix] != 0 : mx > s.theta;
+            const bool hit = forced ? forced[xpix] != 0 : mx > s.theta;
             m = (fl & kFlagN) || hit;
             if (m) {
                 T* Dp = (T*)s.delta + (size_t)pix * s.C;
@@ -383,13 +425,17 @@ template <typename T, int VEC>
 __global__ __launch_bounds__(256) void k_read_tensor(SiteDev s, int what, T* __restrict__ dst) {
     const int chunks = s.C / VEC;
     const bool win = what == MDCNN_VIEW_P;
-    const int Wn = win ? s.Wp : s.W;
-    const long long total = (long long)(win ? s.Hp * s.Wp : s.H * s.W) * chunks;
+    const bool crop = what == MDCNN_VIEW_CROP_OUT;         // f(P) over the crop, in crop order
+    if (crop) what = MDCNN_VIEW_OUT;
+    const int Wn = win ? s.Wp : crop ? s.cx1() - s.cx0() : s.W;
+    const int Hn = win ? s.Hp : crop ? s.cy1() - s.cy0() : s.H;
+    const long long total = (long long)Hn * Wn * chunks;
     const long long step = (long long)gridDim.x * 256;
     for (long long idx = (long long)blockIdx.x * 256 + threadIdx.x; idx < total; idx += step) {
         const int pix = (int)(idx / chunks);
         const int c0 = (int)(idx - (long long)pix * chunks) * VEC;
-        const int y = pix / Wn, x = pix - y * Wn;
+        int y = pix / Wn, x = pix - y * Wn;
+        if (crop) { y += s.cy0(); x += s.cx0(); }
         const T* src;
         bool zero = false;
         if (what == MDCNN_VIEW_A) src = (const T*)s.A + a_offset(s, y, x);
@@ -484,6 +530,16 @@ __global__ __launch_bounds__(256) void k_read_stats(SiteDev s, int* __restrict__
     d64[kAccMacsPlain] = p;
 }
 
+// The state ring of a site with crops, view order <-> ring order.
+__global__ __launch_bounds__(256) void k_copy_state(SiteDev s, uint8_t* __restrict__ view, int to_ring) {
+    const int n = s.H * s.W, step = gridDim.x * 256;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += step) {
+        const int y = i / s.W, x = i - y * s.W;
+        uint8_t* r = s.S() + a_offset(s, y, x) / s.C;
+        if (to_ring) *r = view[i]; else view[i] = *r;
+    }
+}
+
 __global__ __launch_bounds__(256) void k_copy_bytes(const uint8_t* __restrict__ src, uint8_t* __restrict__ dst, int n) {
     const int step = gridDim.x * 256;
     for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += step) dst[i] = src[i];
@@ -500,7 +556,9 @@ template <typename T>
 static hipError_t read_tensor_t(const SiteDev& s, int what, void* dst, hipStream_t st) {
     constexpr int V = V16<T>::N;
     const bool vec = (s.C % V) == 0;
-    const long long pix = what == MDCNN_VIEW_P ? (long long)s.Hp * s.Wp : (long long)s.H * s.W;
+    const long long pix = what == MDCNN_VIEW_P ? (long long)s.Hp * s.Wp
+                        : what == MDCNN_VIEW_CROP_OUT ? (long long)(s.cy1() - s.cy0()) * (s.cx1() - s.cx0())
+                                                      : (long long)s.H * s.W;
     if (vec)
         k_read_tensor<T, V><<<dim3(grid_for(pix * (s.C / V))), dim3(256), 0, st>>>(s, what, (T*)dst);
     else
@@ -511,9 +569,13 @@ static hipError_t read_tensor_t(const SiteDev& s, int what, void* dst, hipStream
 hipError_t launch_read_view(const SiteDev& s, int what, void* dst, hipStream_t st) {
     switch (what) {
         case MDCNN_VIEW_A: case MDCNN_VIEW_P: case MDCNN_VIEW_DELTA: case MDCNN_VIEW_OUT: case MDCNN_VIEW_POOL_PREV:
+        case MDCNN_VIEW_CROP_OUT:
             return s.dtype == MDCNN_F16 ? read_tensor_t<f16>(s, what, dst, st) : read_tensor_t<float>(s, what, dst, st);
         case MDCNN_VIEW_FLAGS:
             k_copy_bytes<<<dim3(grid_for(s.H * s.W)), dim3(256), 0, st>>>(s.flags, (uint8_t*)dst, s.H * s.W);
+            return hipGetLastError();
+        case MDCNN_VIEW_PENDING:
+            k_copy_state<<<dim3(grid_for(s.H * s.W)), dim3(256), 0, st>>>(s, (uint8_t*)dst, 0);
             return hipGetLastError();
         case MDCNN_VIEW_LIST:
             k_read_list<<<dim3(1), dim3(256), 0, st>>>(s.list, s.lcnt, 2, s.H * s.W, (int*)dst);
@@ -530,6 +592,10 @@ hipError_t launch_read_view(const SiteDev& s, int what, void* dst, hipStream_t s
 hipError_t launch_write_view(const SiteDev& s, int what, const void* src, hipStream_t st) {
     if (what == MDCNN_VIEW_FLAGS) {
         k_copy_bytes<<<dim3(grid_for(s.H * s.W)), dim3(256), 0, st>>>((const uint8_t*)src, s.flags, s.H * s.W);
+        return hipGetLastError();
+    }
+    if (what == MDCNN_VIEW_PENDING) {
+        k_copy_state<<<dim3(grid_for(s.H * s.W)), dim3(256), 0, st>>>(s, (uint8_t*)src, 1);   // read only in this mode
         return hipGetLastError();
     }
     const long long pix = what == MDCNN_VIEW_P ? (long long)s.Hp * s.Wp : (long long)s.H * s.W;

@@ -57,7 +57,7 @@ size_t esize(int dtype) { return dtype == MDCNN_F16 ? 2 : 4; }
 long long pmod(long long v, long long n) { long long r = v % n; return r < 0 ? r + n : r; }
 
 struct Layout {
-    size_t A, P, flags, delta, list, lcnt, lacc, clist, ccnt, cacc, counters, Y, total;
+    size_t A, P, flags, delta, list, lcnt, lacc, clist, ccnt, cacc, counters, Y, S, total;
     int nseg_l, nseg_c;
     int Hp, Wp;
 };
@@ -75,6 +75,8 @@ mdcnn_status check_desc(const mdcnn_buffer_desc* d) {
         return fail(MDCNN_ERR_SHAPE, "an INPUT site has no border");
     if (d->pool_prev != 0 && (d->pool_prev != 1 || d->kind != MDCNN_SITE_PREACT))
         return fail(MDCNN_ERR_SHAPE, "pool_prev is 0 or 1 and needs a PREACT site");
+    if (d->crops != 0 && d->crops != 1) return fail(MDCNN_ERR_SHAPE, "crops is 0 or 1");
+    if (d->crops && (d->H > 65535 || d->W > 65535)) return fail(MDCNN_ERR_SIZE, "a site with crops has H, W < 65536");
     return MDCNN_OK;
 }
 
@@ -101,6 +103,7 @@ void make_layout(const mdcnn_buffer_desc& d, Layout& L) {
     L.cacc = take(hasP ? nseg_c * 8 : 0);
     L.counters = take(kNumCounters * 4);
     L.Y = take(d.pool_prev ? (size_t)d.H * d.W * d.C * e : 0);
+    L.S = take(d.crops && hasA ? (size_t)d.H * d.W : 0);
     L.total = off;
 }
 
@@ -201,6 +204,7 @@ EdgeDev make_edge(const mdcnn_buffer* in, const mdcnn_buffer* out, const mdcnn_c
     e.dH = out->d.H; e.dW = out->d.W; e.Cout = c.Cout; e.Hp = out->L.Hp; e.Wp = out->L.Wp;
     e.by0 = out->d.border[0]; e.bx0 = out->d.border[2]; e.p_oy = out->dev.p_oy; e.p_ox = out->dev.p_ox;
     e.op = c.k ? c.op : 0;
+    if (e.op == 1 && out->d.crops) e.op = 2;               // the reset zeroes the previous pooling output
     e.sA = in->dev.A; e.s_aoy = in->dev.a_oy; e.s_aox = in->dev.a_ox; e.s_relu = in->d.relu;
     e.dY = out->dev.Y; e.d_aoy = out->dev.a_oy; e.d_aox = out->dev.a_ox;
     e.w = c.w_dev; e.wp = c.k && !c.op ? c.w_packed_dev : nullptr; e.k = c.k; e.stride = c.k ? c.stride : 1; e.pad = c.k ? c.pad : 0; e.up = c.k ? c.up : 0;
@@ -305,7 +309,7 @@ bool same_shape(const mdcnn_net* a, const mdcnn_net* b) {
     if (a->sites.size() != b->sites.size() || a->esrc != b->esrc || a->edst != b->edst) return false;
     for (size_t i = 0; i < a->sites.size(); ++i) {
         const mdcnn_buffer_desc &x = a->sites[i]->d, &y = b->sites[i]->d;
-        if (x.H != y.H || x.W != y.W || x.C != y.C || x.dtype != y.dtype || x.kind != y.kind || x.relu != y.relu ||
+        if (x.H != y.H || x.W != y.W || x.C != y.C || x.dtype != y.dtype || x.kind != y.kind || x.relu != y.relu || x.crops != y.crops ||
             x.border[0] != y.border[0] || x.border[1] != y.border[1] || x.border[2] != y.border[2] || x.border[3] != y.border[3])
             return false;
     }
@@ -317,6 +321,12 @@ bool same_shape(const mdcnn_net* a, const mdcnn_net* b) {
     }
     return true;
 }
+
+size_t crop_pixels(const mdcnn_buffer* b) {                // sites without crops: the view
+    if (!b->d.crops) return (size_t)b->d.H * b->d.W;
+    return (size_t)(b->dev.cy1() - b->dev.cy0()) * (size_t)(b->dev.cx1() - b->dev.cx0());
+}
+bool whole_view(const mdcnn_buffer* b) { return crop_pixels(b) == (size_t)b->d.H * b->d.W; }
 
 // Shift, forward over all non-terminal sites, readout: for n streams at once.
 mdcnn_status frame_batch(mdcnn_net* const* nets, int n, const void* const* frames, const uint8_t* const* forced,
@@ -364,9 +374,9 @@ mdcnn_status frame_batch(mdcnn_net* const* nets, int n, const void* const* frame
         char* o = (char*)outs_dev[b];
         for (mdcnn_buffer* s : nets[b]->sites) {
             if (s->d.kind != MDCNN_SITE_OUTPUT) continue;
-            hipError_t err = timed(kClsReadout, st, [&] { return launch_read_view(s->dev, MDCNN_VIEW_OUT, o, st); });
+            hipError_t err = timed(kClsReadout, st, [&] { return launch_read_view(s->dev, s->d.crops ? MDCNN_VIEW_CROP_OUT : MDCNN_VIEW_OUT, o, st); });
             if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "readout launch: %s", hipGetErrorString(err));
-            o += (size_t)s->d.H * s->d.W * s->d.C * esize(s->d.dtype);
+            o += crop_pixels(s) * s->d.C * esize(s->d.dtype);
         }
     }
     return MDCNN_OK;
@@ -471,6 +481,9 @@ mdcnn_status mdcnn_create_buffer(const mdcnn_buffer_desc* desc, void* dev_mem, s
     s.H = desc->H; s.W = desc->W; s.C = desc->C; s.Hp = b->L.Hp; s.Wp = b->L.Wp;
     s.by0 = desc->border[0]; s.bx0 = desc->border[2];
     s.theta = desc->theta; s.relu = desc->relu; s.kind = desc->kind; s.dtype = desc->dtype;
+    s.s_off = desc->crops && hasA ? (unsigned)((b->L.S - b->L.A) / 256) : 0u;
+    s.cy = (unsigned)desc->H << 16;                        // the whole view
+    s.cx = (unsigned)desc->W << 16;
     b->gy = b->gx = 0;
     b->fresh = true;
     b->r_up = b->r_down = b->r_left = b->r_right = false;
@@ -520,6 +533,8 @@ mdcnn_status mdcnn_shift_camera(mdcnn_buffer* const* bufs, int n, int dty, int d
         j.A = b->dev.A; j.P = b->dev.P; j.flags = b->dev.flags; j.bias = b->dev.bias; j.counters = b->dev.counters;
         j.lacc = b->dev.lacc; j.cacc = b->dev.cacc; j.lcnt = b->dev.lcnt; j.ccnt = b->dev.ccnt;
         j.n_lacc = 2 * b->L.nseg_l; j.n_cacc = b->L.nseg_c;
+        j.s_off = b->dev.s_off;
+        j.y_off = d.crops && d.pool_prev ? (unsigned)((b->L.Y - b->L.A) / 256) : 0u;
         j.H = d.H; j.W = d.W; j.C = d.C; j.Hp = b->L.Hp; j.Wp = b->L.Wp;
         j.a_oy = b->dev.a_oy; j.a_ox = b->dev.a_ox; j.p_oy = b->dev.p_oy; j.p_ox = b->dev.p_ox;
         j.dtype = d.dtype;
@@ -571,6 +586,24 @@ mdcnn_status mdcnn_shift_camera(mdcnn_buffer* const* bufs, int n, int dty, int d
     return MDCNN_OK;
 }
 
+mdcnn_status mdcnn_set_crop(mdcnn_buffer* const* bufs, int n, int ty0, int tx0, int th, int tw) {
+    if (!bufs || n < 1) return fail(MDCNN_ERR_NULL, "no buffers");
+    for (int i = 0; i < n; ++i) {
+        if (!bufs[i]) return fail(MDCNN_ERR_NULL, "buffer %d is NULL", i);
+        const mdcnn_buffer_desc& d = bufs[i]->d;
+        if (!d.crops) return fail(MDCNN_ERR_STATE, "buffer %d was created without crops", i);
+        if (ty0 < 0 || tx0 < 0 || th < 1 || tw < 1 || ((long long)ty0 + th) * d.tile > d.H || ((long long)tx0 + tw) * d.tile > d.W)
+            return fail(MDCNN_ERR_SHAPE, "buffer %d: crop of %dx%d tiles at (%d, %d) leaves the view of %dx%d pixels (tile %d)",
+                        i, th, tw, ty0, tx0, d.H, d.W, d.tile);
+    }
+    for (int i = 0; i < n; ++i) {
+        const int t = bufs[i]->d.tile;
+        bufs[i]->dev.cy = (unsigned)(ty0 * t) | (unsigned)((ty0 + th) * t) << 16;
+        bufs[i]->dev.cx = (unsigned)(tx0 * t) | (unsigned)((tx0 + tw) * t) << 16;
+    }
+    return MDCNN_OK;
+}
+
 mdcnn_status mdcnn_layer_forward(mdcnn_buffer* in, const void* frame_dev, const uint8_t* forced_mask_dev,
                                  const mdcnn_conv_desc* edges, mdcnn_buffer* const* outs, int n_edges, void* stream) {
     mdcnn_status st = validate_forward(in, frame_dev, edges, outs, n_edges);
@@ -586,6 +619,8 @@ mdcnn_status mdcnn_net_create(mdcnn_buffer* const* sites, int n_sites, const int
         if (!sites[i]) return fail(MDCNN_ERR_NULL, "site %d is NULL", i);
         if ((sites[i]->d.kind == MDCNN_SITE_INPUT) != (i == 0))
             return fail(MDCNN_ERR_SHAPE, "site 0, and only site 0, must be the INPUT site");
+        if (sites[i]->d.crops != sites[0]->d.crops)
+            return fail(MDCNN_ERR_SHAPE, "site %d: crops differs from site 0", i);
     }
     for (int i = 0; i < n_edges; ++i) {
         if (edge_src[i] < 0 || edge_dst[i] >= n_sites || edge_src[i] >= edge_dst[i])
@@ -620,6 +655,28 @@ mdcnn_status mdcnn_frame(mdcnn_net* net, const void* frame_dev, const uint8_t* f
     if (!frame_dev || !out_dev) return fail(MDCNN_ERR_NULL, "frame/out is NULL");
     if (((uintptr_t)frame_dev | (uintptr_t)out_dev) & 15) return fail(MDCNN_ERR_ALIGN, "frame/out must be 16-byte aligned");
     if (out_bytes != net->out_bytes) return fail(MDCNN_ERR_SIZE, "out_bytes is %zu, the outputs take %zu", out_bytes, net->out_bytes);
+    if (!whole_view(net->sites[0])) return fail(MDCNN_ERR_STATE, "the network has a crop smaller than its view: use mdcnn_frame_crop");
+    return frame_batch(&net, 1, &frame_dev, &forced_mask_dev, &dty, &dtx, &out_dev, stream, did_full_reset);
+}
+
+mdcnn_status mdcnn_frame_crop(mdcnn_net* net, const void* frame_dev, const uint8_t* forced_mask_dev, int dty, int dtx,
+                              int ty0, int tx0, int th, int tw, void* out_dev, size_t out_bytes, void* stream,
+                              int* did_full_reset) {
+    if (!net) return fail(MDCNN_ERR_NULL, "net is NULL");
+    if (!frame_dev || !out_dev) return fail(MDCNN_ERR_NULL, "frame/out is NULL");
+    if (((uintptr_t)frame_dev | (uintptr_t)out_dev) & 15) return fail(MDCNN_ERR_ALIGN, "frame/out must be 16-byte aligned");
+    // all checks first: a refused call changes nothing
+    size_t need = 0;
+    for (const mdcnn_buffer* b : net->sites) {
+        const mdcnn_buffer_desc& d = b->d;
+        if (!d.crops) return fail(MDCNN_ERR_STATE, "the network was created without crops");
+        if (ty0 < 0 || tx0 < 0 || th < 1 || tw < 1 || ((long long)ty0 + th) * d.tile > d.H || ((long long)tx0 + tw) * d.tile > d.W)
+            return fail(MDCNN_ERR_SHAPE, "crop of %dx%d tiles at (%d, %d) leaves a view of %dx%d pixels (tile %d)", th, tw, ty0, tx0, d.H, d.W, d.tile);
+        if (d.kind == MDCNN_SITE_OUTPUT) need += (size_t)th * d.tile * tw * d.tile * d.C * esize(d.dtype);
+    }
+    if (out_bytes != need) return fail(MDCNN_ERR_SIZE, "out_bytes is %zu, the cropped outputs take %zu", out_bytes, need);
+    mdcnn_status rc = mdcnn_set_crop(net->sites.data(), (int)net->sites.size(), ty0, tx0, th, tw);
+    if (rc) return rc;
     return frame_batch(&net, 1, &frame_dev, &forced_mask_dev, &dty, &dtx, &out_dev, stream, did_full_reset);
 }
 
@@ -633,6 +690,7 @@ mdcnn_status mdcnn_frame_batch(mdcnn_net* const* nets, int n_streams, const void
         if (!nets[b] || !frames_dev[b] || !outs_dev[b]) return fail(MDCNN_ERR_NULL, "frame_batch: stream %d: net/frame/out is NULL", b);
         if (((uintptr_t)frames_dev[b] | (uintptr_t)outs_dev[b]) & 15) return fail(MDCNN_ERR_ALIGN, "frame_batch: stream %d: frame/out must be 16-byte aligned", b);
         if (out_bytes != nets[b]->out_bytes) return fail(MDCNN_ERR_SIZE, "frame_batch: out_bytes is %zu, the outputs take %zu", out_bytes, nets[b]->out_bytes);
+        if (!whole_view(nets[b]->sites[0])) return fail(MDCNN_ERR_STATE, "frame_batch: stream %d has a crop smaller than its view", b);
         if (b && !same_shape(nets[0], nets[b])) return fail(MDCNN_ERR_SHAPE, "frame_batch: stream %d differs from stream 0 in topology or shapes", b);
         for (int c = 0; c < b; ++c)
             if (nets[c] == nets[b] || nets[c]->sites[0] == nets[b]->sites[0])
@@ -670,6 +728,12 @@ static mdcnn_status view_bytes(const mdcnn_buffer* b, int what, size_t* need) {
         case MDCNN_VIEW_POOL_PREV:
             if (!d.pool_prev) return fail(MDCNN_ERR_STATE, "the site keeps no previous pooling output");
             *need = (size_t)d.H * d.W * d.C * e; return MDCNN_OK;
+        case MDCNN_VIEW_CROP_OUT:
+            if (!hasP || !d.crops) return fail(MDCNN_ERR_STATE, "CROP_OUT needs a site with P and crops");
+            *need = crop_pixels(b) * d.C * e; return MDCNN_OK;
+        case MDCNN_VIEW_PENDING:
+            if (!d.crops || !hasA) return fail(MDCNN_ERR_STATE, "the site keeps no crop state");
+            *need = (size_t)d.H * d.W; return MDCNN_OK;
         default:
             return fail(MDCNN_ERR_SIZE, "unknown view %d", what);
     }
@@ -691,8 +755,8 @@ mdcnn_status mdcnn_read_view(const mdcnn_buffer* buf, int what, void* dst_dev, s
 mdcnn_status mdcnn_write_view(mdcnn_buffer* buf, int what, const void* src_dev, size_t bytes, void* stream) {
     if (!buf || !src_dev) return fail(MDCNN_ERR_NULL, "buf/src is NULL");
     if (buf->fresh) return fail(MDCNN_ERR_STATE, "buffer was never reset (shift first)");
-    if (what != MDCNN_VIEW_A && what != MDCNN_VIEW_P && what != MDCNN_VIEW_FLAGS && what != MDCNN_VIEW_POOL_PREV)
-        return fail(MDCNN_ERR_SIZE, "only A, P, FLAGS and POOL_PREV can be written");
+    if (what != MDCNN_VIEW_A && what != MDCNN_VIEW_P && what != MDCNN_VIEW_FLAGS && what != MDCNN_VIEW_POOL_PREV && what != MDCNN_VIEW_PENDING)
+        return fail(MDCNN_ERR_SIZE, "only A, P, FLAGS, POOL_PREV and PENDING can be written");
     size_t need = 0;
     mdcnn_status st = view_bytes(buf, what, &need);
     if (st) return st;

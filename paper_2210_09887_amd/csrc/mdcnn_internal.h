@@ -13,6 +13,9 @@ constexpr int kFlagN = 1;   // newly unveiled this frame
 constexpr int kFlagU = 2;   // touched by a producer this frame
 constexpr int kFlagM = 4;   // updated (emitted a delta) this frame
 constexpr int kFlagC = 8;   // was a candidate of step 1 this frame (statistics)
+// ring-ordered state of sites with crops, kept across frames
+constexpr int kStateUnseen = 1;   // allocated, no frame has covered the pixel yet
+constexpr int kStateDirty = 2;    // touched by a producer while outside the crop
 
 // counters[] of a site (int32 slots, device).  Slots [0, 8) are per-frame values
 // zeroed by every camera shift; 64-bit running sums follow (index into
@@ -58,6 +61,15 @@ struct SiteDev {
     int relu;
     int kind;
     int dtype;
+    // Sites with crops (H, W < 65536).  s_off: their state ring S (H x W bytes, kStateUnseen | kStateDirty per
+    // pixel, ring order of A) as an offset from A in units of 256 bytes, 0: no crops.  cy, cx: the rows / columns
+    // of the view the frame covers, first in the low and end in the high 16 bits (whole view by default).
+    unsigned s_off, cy, cx;
+    __host__ __device__ uint8_t* S() const { return s_off ? (uint8_t*)A + (size_t)s_off * 256 : nullptr; }
+    __host__ __device__ int cy0() const { return (int)(cy & 0xffffu); }
+    __host__ __device__ int cy1() const { return (int)(cy >> 16); }
+    __host__ __device__ int cx0() const { return (int)(cx & 0xffffu); }
+    __host__ __device__ int cx1() const { return (int)(cx >> 16); }
 };
 
 // Destination of a residual skip fused into step 1 of its source site: the delta
@@ -82,6 +94,8 @@ struct FillJob {
     unsigned long long* cacc;
     int* lcnt;                  // per-segment counts of the frame (n_lacc / n_cacc entries), cleared with them:
     int* ccnt;                  // a site no edge publishes a compute list for must still read as empty
+    unsigned s_off, y_off;      // S and Y of the site as offsets from A in units of 256 bytes (0: none): pixels that
+                                // enter the view get S = unseen and Y = 0
     int n_lacc, n_cacc;
     int H, W, C, Hp, Wp;
     int a_oy, a_ox, p_oy, p_ox;
@@ -122,7 +136,8 @@ struct EdgeDev {
     const void* w;            // [tap][cout][cin]
     const void* wp;           // the same weights packed [tap][cin/16][cout][16], or nullptr
     int k, stride, pad, up;
-    // max pooling (op == 1): the source's accumulated ring and the destination's previous outputs
+    // max pooling (op == 1; op == 2: the previous output of a reset pixel was zeroed with it): the source's
+    // accumulated ring and the destination's previous outputs
     const void* sA;
     void* dY;
     int s_aoy, s_aox, s_relu, d_aoy, d_aox, op;

@@ -17,9 +17,10 @@ _KIND = {"input": B.MDCNN_SITE_INPUT, "preact": B.MDCNN_SITE_PREACT, "output": B
 class GpuNet:
     """`spec` is any object with the fields of inputs.nets.NetSpec."""
 
-    def __init__(self, spec, origins=None, device="cuda:0", share_weights=None):
+    def __init__(self, spec, origins=None, device="cuda:0", share_weights=None, crops=False):
         """share_weights: another GpuNet of the same spec whose weight tensors are reused
-        (streams of one batch share the model)."""
+        (streams of one batch share the model).  crops: frames may cover a part of the
+        view only (set_crop / frame_crop)."""
         if not torch.cuda.is_available():
             raise RuntimeError("mdcnn needs a GPU: there is no CPU path")
         B.lib()
@@ -79,6 +80,7 @@ class GpuNet:
             d.bias_dev = None if self.bias[i] is None else self.bias[i].data_ptr()
             d.origin_y, d.origin_x = (0, 0) if origins is None else origins[i]
             d.pool_prev = int(i in pooled)
+            d.crops = int(bool(crops))
             nbytes = B.mdcnn_buffer_bytes(d)
             mem = torch.empty(nbytes, dtype=torch.uint8, device=self.dev)
             self.mem.append(mem)
@@ -89,6 +91,8 @@ class GpuNet:
         self.terminals = [i for i, s in enumerate(spec.sites) if s.kind == "output"]
         self.out_elems = sum(int(np.prod(self.shape[i])) for i in self.terminals)
         self.out = torch.empty(self.out_elems, dtype=self.tdtype, device=self.dev)
+        self.tile = [spec.total_stride // s.stride for s in spec.sites]
+        self.crop = None                     # (ty0, tx0, th, tw) once set
 
     def close(self):
         if self.net:
@@ -108,6 +112,33 @@ class GpuNet:
     # -- the four calls of the boundary -------------------------------------------------
     def shift_camera(self, dty, dtx) -> bool:
         return B.mdcnn_shift_camera(self.bufs, dty, dtx, self._stream())
+
+    def set_crop(self, ty0, tx0, th, tw):
+        B.mdcnn_set_crop(self.bufs, ty0, tx0, th, tw)
+        self.crop = (int(ty0), int(tx0), int(th), int(tw))
+
+    def crop_shape(self, i):
+        """Extent of the crop at site i."""
+        if self.crop is None:
+            return self.shape[i]
+        return (self.crop[2] * self.tile[i], self.crop[3] * self.tile[i], self.shape[i][2])
+
+    def frame_crop(self, X, dty, dtx, crop, forced=None):
+        """X: device tensor covering the crop at the input site.  Returns (list of output tensors in crop
+        order, did_reset)."""
+        th, tw = int(crop[2]), int(crop[3])
+        n = sum(th * self.tile[i] * tw * self.tile[i] * self.shape[i][2] for i in self.terminals)
+        out = self.out[:n]
+        r = B.mdcnn_frame_crop(self.net, X.data_ptr(), None if forced is None else forced.data_ptr(), dty, dtx, crop,
+                               out.data_ptr(), n * self.esize, self._stream())
+        self.crop = tuple(int(v) for v in crop)
+        res, o = [], 0
+        for i in self.terminals:
+            shp = self.crop_shape(i)
+            m = int(np.prod(shp))
+            res.append(out[o:o + m].reshape(shp))
+            o += m
+        return res, r
 
     def layer_forward(self, i, frame=None, forced=None):
         idx = [j for j, s in enumerate(self.esrc) if s == i]
@@ -138,7 +169,9 @@ class GpuNet:
             t = torch.empty((H, W, Cc), dtype=self.tdtype, device=self.dev)
         elif what == B.MDCNN_VIEW_P:
             t = torch.empty((Hp, Wp, Cc), dtype=self.tdtype, device=self.dev)
-        elif what == B.MDCNN_VIEW_FLAGS:
+        elif what == B.MDCNN_VIEW_CROP_OUT:
+            t = torch.empty(self.crop_shape(i), dtype=self.tdtype, device=self.dev)
+        elif what in (B.MDCNN_VIEW_FLAGS, B.MDCNN_VIEW_PENDING):
             t = torch.empty((H, W), dtype=torch.uint8, device=self.dev)
         elif what == B.MDCNN_VIEW_LIST:
             t = torch.empty(H * W + 1, dtype=torch.int32, device=self.dev)

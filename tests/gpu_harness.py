@@ -35,8 +35,21 @@ def oracle_flags(s):
     return (s.N.astype(np.uint8) * B.FLAG_N) | (s.U.astype(np.uint8) * B.FLAG_U)
 
 
+def oracle_pending(s):
+    return (s.get_ring("unseen").astype(np.uint8) * B.STATE_UNSEEN) | (s.get_ring("dirty").astype(np.uint8) * B.STATE_DIRTY)
+
+
+def cut(net, a, crop):
+    """The part of an input-site array [H, W, ...] that a frame covering `crop` = (ty0, tx0, th, tw) tiles holds."""
+    T = net.total_stride
+    ty0, tx0, th, tw = crop
+    return np.ascontiguousarray(a[ty0 * T:(ty0 + th) * T, tx0 * T:(tx0 + tw) * T])
+
+
 def load_site(g: GpuNet, o: OracleNet, i: int):
     s = o.sites[i]
+    if o.crops and s.spec.kind != "output":
+        g.write(i, B.MDCNN_VIEW_PENDING, oracle_pending(s))
     if s.spec.kind != "output":
         g.write(i, B.MDCNN_VIEW_A, s.get_A())
         g.write(i, B.MDCNN_VIEW_FLAGS, oracle_flags(s))
@@ -46,10 +59,12 @@ def load_site(g: GpuNet, o: OracleNet, i: int):
         g.write(i, B.MDCNN_VIEW_POOL_PREV, s.get_Y())
 
 
-def teacher_forced(net, frames, shifts, forced=None, origins=None, log=None):
-    """Returns the worst fp error seen; raises AssertionError on any integer mismatch."""
+def teacher_forced(net, frames, shifts, forced=None, origins=None, log=None, crops=None):
+    """Returns the worst fp error seen; raises AssertionError on any integer mismatch.
+    crops: per frame the tiles (ty0, tx0, th, tw) of the view that the frame covers; frames
+    and forced masks are given over the whole view and cut here."""
     tol = TOL[net.dtype]
-    g, o = GpuNet(net, origins), OracleNet(net, origins)
+    g, o = GpuNet(net, origins, crops=crops is not None), OracleNet(net, origins, crops=crops is not None)
     worst = 0.0
     try:
         for t, X in enumerate(frames):
@@ -57,6 +72,15 @@ def teacher_forced(net, frames, shifts, forced=None, origins=None, log=None):
             r_g = g.shift_camera(dy, dx)
             r_o = o.shift_camera(dy, dx)
             assert r_g == r_o, f"frame {t}: reset decision differs"
+            if crops is not None:
+                g.set_crop(*crops[t])
+                o.set_crop(*crops[t])
+                X = cut(net, X, crops[t])
+                for i, s in enumerate(o.sites):
+                    if s.spec.kind != "output":
+                        assert np.array_equal(g.read(i, B.MDCNN_VIEW_PENDING), oracle_pending(s)), f"frame {t} site {i}: crop state after the shift"
+                    if s.pooled:
+                        assert np.array_equal(g.read(i, B.MDCNN_VIEW_POOL_PREV), s.get_Y()), f"frame {t} site {i}: previous pooling output after the shift"
             if t == 0 or r_o:
                 # state after a (re)initialisation must already agree exactly
                 for i, s in enumerate(o.sites):
@@ -76,6 +100,8 @@ def teacher_forced(net, frames, shifts, forced=None, origins=None, log=None):
                 for e in edges:
                     load_site(g, o, e.dst)
                 fm = forced[t] if (forced is not None and i == 0) else None
+                if fm is not None and crops is not None:
+                    fm = cut(net, fm, crops[t])
                 Xd = dev(X) if i == 0 else None
                 fd = dev(fm) if fm is not None else None
                 g.layer_forward(i, Xd, fd)
@@ -84,6 +110,8 @@ def teacher_forced(net, frames, shifts, forced=None, origins=None, log=None):
                 where = f"frame {t} site {i} ({s.spec.name})"
                 fl = g.read(i, B.MDCNN_VIEW_FLAGS)
                 assert np.array_equal((fl & B.FLAG_M) != 0, s.M), where + ": update mask"
+                if crops is not None:
+                    assert np.array_equal(g.read(i, B.MDCNN_VIEW_PENDING), oracle_pending(s)), where + ": crop state"
                 assert np.array_equal(g.read(i, B.MDCNN_VIEW_LIST), s.L), where + ": list L"
                 st = g.read(i, B.MDCNN_VIEW_STATS)
                 assert st[0] == len(s.L) and st[1] == s.n_candidates, where + ": counters"
@@ -113,7 +141,7 @@ def teacher_forced(net, frames, shifts, forced=None, origins=None, log=None):
                 worst = max(worst, max(errs))
                 assert max(errs) < tol, where + f": fp error {max(errs):.3e} (A, delta, P, P_dst...) = {errs}"
             for i in net.terminal_sites():
-                worst = max(worst, maxerr(g.read(i, B.MDCNN_VIEW_OUT), o.readout(i)))
+                worst = max(worst, maxerr(g.read(i, B.MDCNN_VIEW_CROP_OUT if crops is not None else B.MDCNN_VIEW_OUT), o.readout(i)))
             if log:
                 log(f"  teacher-forced frame {t}: reset={r_o} worst={worst:.2e}")
     finally:

@@ -150,3 +150,28 @@ def test_pack_weights_and_batch_argument_checks_need_no_gpu():
     for n in (0, 17):
         with pytest.raises(B.MdcnnError):
             B.mdcnn_frame_batch([4096] * n, [4096] * n, None, [0] * n, [0] * n, [4096] * n, 16)
+
+
+def test_crop_argument_checks_need_no_gpu():
+    d = desc(H=16, W=16, tile=4)
+    n0 = B.mdcnn_buffer_bytes(d)
+    d.crops = 1
+    n1 = B.mdcnn_buffer_bytes(d)
+    assert n1 == n0 + 256                      # one more byte per view pixel
+    h = B.mdcnn_create_buffer(d, FAKE, n1)
+    B.mdcnn_set_crop([h], 1, 2, 3, 2)          # host state only
+    for bad in [(0, 0, 5, 1), (3, 0, 2, 1), (0, 0, 0, 1), (0, -1, 1, 1)]:
+        with pytest.raises(B.MdcnnError) as ei:
+            B.mdcnn_set_crop([h], *bad)
+        assert ei.value.status == 2
+    B.mdcnn_destroy_buffer(h)
+    d.crops = 0
+    h = B.mdcnn_create_buffer(d, FAKE, n0)
+    with pytest.raises(B.MdcnnError) as ei:
+        B.mdcnn_set_crop([h], 0, 0, 1, 1)
+    assert ei.value.status == 6
+    B.mdcnn_destroy_buffer(h)
+    d.crops = 2
+    with pytest.raises(B.MdcnnError) as ei:
+        B.mdcnn_buffer_bytes(d)
+    assert ei.value.status == 2
