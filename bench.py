@@ -45,6 +45,9 @@ def parse():
     ap.add_argument("--dense", action="store_true", help="library dense mode: threshold 0 and all pixels forced")
     ap.add_argument("--pool-stem", action="store_true",
                     help="config 3 with the usual ResNet stem: 3x3 stride-2 max pooling after the stem convolution (total stride 16)")
+    ap.add_argument("--crops", action="store_true",
+                    help="every frame covers a bounding box of about 2/3 x 2/3 of the view that wanders over it "
+                         "(mdcnn_frame_crop; one stream only)")
     ap.add_argument("--streams", type=int, default=8,
                     help="after the headline run, the same workload as a batch of this many independent streams "
                          "(mdcnn_frame_batch; reported under \"batched\"); 0 disables it")
@@ -242,14 +245,37 @@ def main():
     for kv in a.opt:
         k, v = kv.split("=")
         B.mdcnn_set_option(int(k), int(v))
-    g = GpuNet(net)
+    g = GpuNet(net, crops=a.crops)
+
+    crops = None
+    if a.crops:
+        # a box of about 2/3 x 2/3 of the view, moving by one tile every fourth frame (seeded walk)
+        rng = np.random.default_rng(2210)
+        Ts = net.total_stride
+        Ht, Wt = net.H // Ts, net.W // Ts
+        th, tw = max(1, round(2 * Ht / 3)), max(1, round(2 * Wt / 3))
+        y, x = (Ht - th) // 2, (Wt - tw) // 2
+        crops = []
+        for t in range(T):
+            if t % 4 == 0 and t:
+                y = int(np.clip(y + rng.integers(-1, 2), 0, Ht - th))
+                x = int(np.clip(x + rng.integers(-1, 2), 0, Wt - tw))
+            crops.append((y, x, th, tw))
+        crops[0] = (0, 0, Ht, Wt)                  # the cycle starts from a frame that covers the whole view
+        cut = lambda v, c: v[c[0] * Ts:(c[0] + c[2]) * Ts, c[1] * Ts:(c[1] + c[3]) * Ts].contiguous()
+        frames_c = [cut(frames[t], crops[t]) for t in range(T)]
+        forced_c = None if forced is None else [cut(forced[t], crops[t]) for t in range(T)]
+        a.streams = 0
 
     state = {"t": 0, "resets": 0}
 
     def step():
         t = state["t"] % T
         dy, dx = (0, 0) if state["t"] == 0 else (int(shifts[t][0]), int(shifts[t][1]))
-        _, r = g.frame(frames[t], dy, dx, None if forced is None else forced[t])
+        if crops is not None:
+            _, r = g.frame_crop(frames_c[t], dy, dx, crops[t], None if forced is None else forced_c[t])
+        else:
+            _, r = g.frame(frames[t], dy, dx, None if forced is None else forced[t])
         state["t"] += 1
         state["resets"] += int(r)
 
@@ -286,7 +312,8 @@ def main():
     cpu = None
     if a.cpu_seconds > 0:
         from oracle.mdcnn_oracle import OracleNet
-        o = OracleNet(net)
+        o = OracleNet(net, crops=a.crops)
+        ncut = lambda v, c: np.ascontiguousarray(v[c[0] * Ts:(c[0] + c[2]) * Ts, c[1] * Ts:(c[1] + c[3]) * Ts])
         tc = time.perf_counter()
         n_cpu = 0
         while n_cpu < T and (n_cpu < 2 or time.perf_counter() - tc < a.cpu_seconds):
@@ -296,7 +323,11 @@ def main():
                 fm = np.ones((net.H, net.W), np.uint8)
             elif seq.forced is not None:
                 fm = seq.forced[n_cpu]
-            o.frame(seq.frames[n_cpu], dy, dx, fm)
+            if crops is not None:
+                c = crops[n_cpu]
+                o.frame(ncut(seq.frames[n_cpu], c), dy, dx, None if fm is None else ncut(fm, c), crop=c)
+            else:
+                o.frame(seq.frames[n_cpu], dy, dx, fm)
             n_cpu += 1
         dtc = time.perf_counter() - tc
         try:
@@ -316,6 +347,7 @@ def main():
         "dtype": net.dtype, "data": "synthetic",
         "config": {"workload": f"config {cfg}: {net.name}, {T}-frame seeded moving-camera sequence replayed cyclically"
                                + (", max-pooling stem" if a.pool_stem and cfg == 3 else "")
+                               + (f", frames cropped to a wandering box of {crops[1][2]}x{crops[1][3]} of {net.H // net.total_stride}x{net.W // net.total_stride} tiles" if crops is not None else "")
                                + (", library dense mode" if a.dense else "")
                                + (f", density {a.density}" if cfg == 5 else ""),
                    "input": [net.H, net.W, net.sites[0].C], "sites": len(net.sites), "edges": len(net.edges),

@@ -150,13 +150,17 @@ def teacher_forced(net, frames, shifts, forced=None, origins=None, log=None, cro
     return worst
 
 
-def oracle_run(net, frames, shifts, forced=None, origins=None):
+def oracle_run(net, frames, shifts, forced=None, origins=None, crops=None):
     """Oracle alone; returns per-frame outputs, masks of every non-terminal site, resets."""
-    o = OracleNet(net, origins)
+    o = OracleNet(net, origins, crops=crops is not None)
     outs, masks, resets = [], [], []
     for t, X in enumerate(frames):
         dy, dx = (int(v) for v in shifts[t])
-        out, r = o.frame(X, dy, dx, None if forced is None else forced[t])
+        if crops is not None:
+            fm = None if forced is None else cut(net, forced[t], crops[t])
+            out, r = o.frame(cut(net, X, crops[t]), dy, dx, fm, crop=crops[t])
+        else:
+            out, r = o.frame(X, dy, dx, None if forced is None else forced[t])
         outs.append(out)
         resets.append(r)
         masks.append({i: s.M.copy() for i, s in enumerate(o.sites) if s.spec.kind != "output"})
@@ -202,20 +206,25 @@ def mask_forced(net, frames, shifts, forced=None, log=None):
     return worst
 
 
-def free_running(net, frames, shifts, forced=None, origins=None, log=None):
-    """mdcnn_frame end to end.  Returns dict(out_err, mask_mismatch, resets, outputs)."""
-    o, outs, masks, resets = oracle_run(net, frames, shifts, forced, origins)
-    g = GpuNet(net, origins)
+def free_running(net, frames, shifts, forced=None, origins=None, log=None, crops=None):
+    """mdcnn_frame (with crops: mdcnn_frame_crop) end to end.  Returns dict(out_err, mask_mismatch, resets, outputs)."""
+    o, outs, masks, resets = oracle_run(net, frames, shifts, forced, origins, crops)
+    g = GpuNet(net, origins, crops=crops is not None)
     out_err, mism, total = 0.0, 0, 0
     got_all = []
     try:
         for t, X in enumerate(frames):
             dy, dx = (int(v) for v in shifts[t])
-            fd = dev(forced[t]) if forced is not None else None
-            out, r = g.frame(dev(X), dy, dx, fd)
+            if crops is not None:
+                fd = dev(cut(net, forced[t], crops[t])) if forced is not None else None
+                parts, r = g.frame_crop(dev(cut(net, X, crops[t])), dy, dx, crops[t], fd)
+            else:
+                fd = dev(forced[t]) if forced is not None else None
+                out, r = g.frame(dev(X), dy, dx, fd)
+                parts = g.split_outputs(out)
             torch.cuda.synchronize()
             assert r == resets[t], f"frame {t}: reset decision differs"
-            got = [x.cpu().numpy() for x in g.split_outputs(out)]
+            got = [x.cpu().numpy() for x in parts]
             got_all.append(got)
             for a, b in zip(got, outs[t]):
                 out_err = max(out_err, maxerr(a, b))

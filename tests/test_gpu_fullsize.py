@@ -182,3 +182,33 @@ def test_config3_full_512_pooling_stem():
     log(f"config 3 pooling stem free-running: out_err {r['out_err']:.2e} mask mismatch {r['mask_mismatch']:.2e} resets {r['resets']}")
     assert r["mask_mismatch"] < 0.02
     assert r["out_err"] < 0.1 + 4 * H.TOL["f16"]
+
+
+def wandering_box(net, n, seed=2210):
+    """The crops bench.py --crops uses: a box of about 2/3 x 2/3 of the view that moves by one tile
+    every fourth frame; the first frame covers the whole view."""
+    rng = np.random.default_rng(seed)
+    Ht, Wt = net.H // net.total_stride, net.W // net.total_stride
+    th, tw = max(1, round(2 * Ht / 3)), max(1, round(2 * Wt / 3))
+    y, x = (Ht - th) // 2, (Wt - tw) // 2
+    out = []
+    for t in range(n):
+        if t % 4 == 0 and t:
+            y = int(np.clip(y + rng.integers(-1, 2), 0, Ht - th))
+            x = int(np.clip(x + rng.integers(-1, 2), 0, Wt - tw))
+        out.append((y, x, th, tw))
+    out[0] = (0, 0, Ht, Wt)
+    return out
+
+
+@pytest.mark.parametrize("cfg,n", [(3, 5), (4, 9)])
+def test_full_size_cropped_frames(cfg, n):
+    """mdcnn_frame_crop at full size on the workload of bench.py --crops, against the oracle."""
+    import gpu_harness as H
+    net = build_net(cfg)
+    seq = build_sequence(cfg, n_frames=n)
+    crops = wandering_box(net, n)
+    r = H.free_running(net, seq.frames, seq.shifts, log=log, crops=crops)
+    log(f"config {cfg} cropped free-running: out_err {r['out_err']:.2e} mask mismatch {r['mask_mismatch']:.2e} resets {r['resets']}")
+    assert r["mask_mismatch"] < 0.02
+    assert r["out_err"] < 0.15 + 4 * H.TOL["f16"]
