@@ -31,7 +31,11 @@ What is followed, and where the paper defines it:
   bounding box of a region of interest); the tile offsets given with the frame
   place it in the buffers, every layer works on the crop scaled to its own
   tile size, and the rest of the buffers keeps what it holds -- Spherical
-  Buffers (cropped inputs), Evaluation: Human Pose Estimation.
+  Buffers (cropped inputs), Evaluation: Human Pose Estimation;
+* the update mask of the input may be post-processed before it is used: the
+  delta is weighted by a region-of-interest map, isolated updates are
+  suppressed on a downscaled delta, and the mask is dilated by a few pixels
+  -- Optimizations; Supplementary (ROI-focused sensing, first-layer dilation).
 
 Arithmetic: stored tensors (A, P, delta maps, weights, frames) are in the
 network's storage dtype; every elementwise operation is done in float32 in the
@@ -442,3 +446,55 @@ class OracleNet:
             self.layer_forward(i, X if s.spec.kind == "input" else None, fm)
         outs = [self.readout(i) for i in self.net.terminal_sites()]
         return outs, did_reset
+
+    # ------------------------------------------------- mask post-processing
+    def input_mask(self, X, roi=None, theta=None, base=0.4, gain=0.6, pool=1, suppress=False, dilate=0):
+        """Update mask of the input site for frame X with the optional
+        post-processing steps, to be used as the forced mask of that frame
+        (newly unveiled pixels are updated in any case).  X, roi and the
+        result cover the current crop (the whole view without crops).
+          1. magnitude e = max over channels of |X - A|   (Background: DeltaCNN)
+          2. ROI-focused sensing: e is scaled by base + gain * roi, roi in
+             [0, 1] from the previous result (Supplementary: 0.4 + 0.6 m)
+          3. downscaling: e is averaged over pool x pool cells and the cells
+             are compared with the threshold, strict >        (Optimizations)
+          4. a cell that exceeds the threshold alone among the 3 x 3 cells
+             around it is dropped: the 3 x 3 average pooling of the binary
+             map stays at 1/9 there                            (Optimizations)
+          5. every remaining cell covers its pixels, and the mask is dilated
+             by `dilate` pixels in all directions (d = 10 spreads one pixel
+             over 21 x 21)                       (Supplementary, first layer)
+        All floating-point steps in float32, the cell sum row by row."""
+        s = self.sites[0]
+        f32 = np.float32
+        theta = f32(s.spec.theta if theta is None else theta)
+        y0, y1, x0, x1 = s.crop if self.crops else (0, s.H, 0, s.W)
+        Hc, Wc = y1 - y0, x1 - x0
+        assert X.shape == (Hc, Wc, s.C) and Hc % pool == 0 and Wc % pool == 0
+        A = s.get_A()[y0:y1, x0:x1].astype(f32)
+        e = np.abs(X.astype(f32) - A).max(axis=2)
+        if roi is not None:
+            assert roi.shape == (Hc, Wc)
+            e = e * (f32(base) + f32(gain) * roi.astype(f32))
+        acc = np.zeros((Hc // pool, Wc // pool), f32)
+        for dy in range(pool):
+            for dx in range(pool):
+                acc = acc + e[dy::pool, dx::pool]
+        hit = acc / f32(pool * pool) > theta
+        if suppress:
+            cnt = np.zeros(hit.shape, np.int32)
+            padded = np.pad(hit, 1).astype(np.int32)
+            for dy in range(3):
+                for dx in range(3):
+                    cnt += padded[dy:dy + hit.shape[0], dx:dx + hit.shape[1]]
+            hit = hit & (cnt >= 2)
+        m = np.repeat(np.repeat(hit, pool, axis=0), pool, axis=1)
+        if dilate:
+            d = int(dilate)
+            padded = np.pad(m, d)
+            out = np.zeros_like(m)
+            for dy in range(2 * d + 1):
+                for dx in range(2 * d + 1):
+                    out |= padded[dy:dy + Hc, dx:dx + Wc]
+            m = out
+        return m.astype(np.uint8)
