@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--crops", action="store_true",
                     help="every frame covers a bounding box of about 2/3 x 2/3 of the view that wanders over it "
                          "(mdcnn_frame_crop; one stream only)")
+    ap.add_argument("--front-end", action="store_true",
+                    help="the input update mask of every frame comes from mdcnn_input_mask (isolated updates suppressed, "
+                         "dilation by 2 pixels) and is forced; one stream only")
     ap.add_argument("--streams", type=int, default=8,
                     help="after the headline run, the same workload as a batch of this many independent streams "
                          "(mdcnn_frame_batch; reported under \"batched\"); 0 disables it")
@@ -267,12 +270,26 @@ def main():
         forced_c = None if forced is None else [cut(forced[t], crops[t]) for t in range(T)]
         a.streams = 0
 
+    FE = dict(suppress=True, dilate=2)
+    if a.front_end:
+        assert crops is None and forced is None, "--front-end excludes --crops, --dense and config 5"
+        a.streams = 0
+
     state = {"t": 0, "resets": 0}
 
     def step():
         t = state["t"] % T
         dy, dx = (0, 0) if state["t"] == 0 else (int(shifts[t][0]), int(shifts[t][1]))
-        if crops is not None:
+        if a.front_end:
+            # the mask needs the shifted buffers: shift, mask, then the forward calls of mdcnn_frame one by one
+            r = g.shift_camera(dy, dx)
+            fm = g.input_mask(frames[t], **FE)
+            for i, sp in enumerate(net.sites):
+                if sp.kind != "output":
+                    g.layer_forward(i, frames[t] if i == 0 else None, fm if i == 0 else None)
+            for i in g.terminals:
+                B.mdcnn_read_view(g.bufs[i], B.MDCNN_VIEW_OUT, g.out.data_ptr(), g.out.numel() * g.esize, g._stream())
+        elif crops is not None:
             _, r = g.frame_crop(frames_c[t], dy, dx, crops[t], None if forced is None else forced_c[t])
         else:
             _, r = g.frame(frames[t], dy, dx, None if forced is None else forced[t])
@@ -323,7 +340,14 @@ def main():
                 fm = np.ones((net.H, net.W), np.uint8)
             elif seq.forced is not None:
                 fm = seq.forced[n_cpu]
-            if crops is not None:
+            if a.front_end:
+                o.shift_camera(dy, dx)
+                fmo = o.input_mask(seq.frames[n_cpu], **FE)
+                for i, sp in enumerate(net.sites):
+                    if sp.kind != "output":
+                        o.layer_forward(i, seq.frames[n_cpu] if i == 0 else None, fmo if i == 0 else None)
+                [o.readout(i) for i in net.terminal_sites()]
+            elif crops is not None:
                 c = crops[n_cpu]
                 o.frame(ncut(seq.frames[n_cpu], c), dy, dx, None if fm is None else ncut(fm, c), crop=c)
             else:
@@ -360,6 +384,22 @@ def main():
         "instrumented_ms_per_step": round(1e3 * dt_prof / n_prof, 4),
         "cpu_baseline": cpu,
     }
+    if a.front_end:
+        # the mask kernel alone, HIP events on the stream it is launched on (torch's current stream)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 200
+        g.input_mask(frames[0], **FE)
+        ev0.record()
+        for k in range(reps):
+            g.input_mask(frames[k % T], **FE)
+        ev1.record()
+        torch.cuda.synchronize()
+        us = 1e3 * ev0.elapsed_time(ev1) / reps
+        by = net.H * net.W * (2 * net.sites[0].C * g.esize + 1)       # frame + accumulated input read once, mask written
+        out["front_end"] = {"kernel": "k_input_mask", "params": FE, "avg_us": round(us, 2), "algorithmic_bytes_per_launch": by,
+                            "roofline": {"bound": "hbm", "achieved": round(by / us / 1e3, 2), "peak": 8000.0, "unit": "GB/s",
+                                         "frac": round(by / us / 1e3 / 8000.0, 5), "traffic": None}}
+        out["config"]["workload"] += ", input masks from mdcnn_input_mask (suppress, dilate 2), one call per layer"
     g.close()
     if a.streams > 1 and not a.copy_calibration:
         out["batched"] = run_batched(a, cfg, net, T, frames, shifts, forced, "8=0" not in a.opt)

@@ -227,6 +227,38 @@ mdcnn_status mdcnn_frame_batch(mdcnn_net* const* nets, int n_streams, const void
                                const uint8_t* const* forced_masks_dev, const int* dty, const int* dtx,
                                void* const* outs_dev, size_t out_bytes, void* stream, int* did_full_reset);
 
+/* Optional post-processing of the input update mask.  Writes, for the frame
+ * `frame_dev` (not yet passed to a forward call), the mask that the threshold
+ * test of the INPUT site `in` would give after these steps, as bytes 0/1 to be
+ * handed to mdcnn_layer_forward / mdcnn_frame as the forced mask of that frame
+ * (newly unveiled pixels are updated regardless):
+ *   1. e(p) = max over channels of |frame - A|                [Background: DeltaCNN]
+ *   2. with roi_dev (floats in [0, 1], e.g. the dilated previous result):
+ *      e(p) *= sens_base + sens_gain * roi(p)   [Supplementary: ROI-focused sensing, 0.4 + 0.6 m]
+ *   3. e is averaged over pool x pool cells (row by row, fp32) and the cells are
+ *      compared with theta, strict >                                 [Optimizations]
+ *   4. suppress = 1: a cell above the threshold with no other such cell among the
+ *      3 x 3 cells around it is dropped                              [Optimizations]
+ *   5. the cells cover their pixels and the mask is dilated by `dilate` pixels in
+ *      every direction (10 spreads one pixel over 21 x 21), clipped to the frame
+ *                                                    [Supplementary: first-layer dilation]
+ * frame_dev, roi_dev (may be NULL) and mask_dev cover the site's crop (the view
+ * without crops), row-major; mask_bytes must equal its pixel count.  All steps in
+ * fp32.  Asynchronous on `stream`; reads A, changes no state.
+ * Errors: MDCNN_ERR_SHAPE unless `in` is an INPUT site, pool is 1, 2, 4 or 8 and
+ * divides both extents, 0 <= dilate <= 32, suppress is 0 or 1; MDCNN_ERR_STATE
+ * before the first shift; MDCNN_ERR_SIZE for a wrong mask_bytes. */
+typedef struct {
+    float theta;
+    float sens_base, sens_gain;
+    int pool;
+    int suppress;
+    int dilate;
+} mdcnn_mask_params;
+mdcnn_status mdcnn_input_mask(const mdcnn_buffer* in, const void* frame_dev, const float* roi_dev,
+                              const mdcnn_mask_params* prm, uint8_t* mask_dev, size_t mask_bytes,
+                              void* stream);
+
 /* View-ordered access to a site's state (independent of the ring origin). */
 typedef enum {
     MDCNN_VIEW_A = 0,        /* H*W*C storage dtype: accumulated values                     */

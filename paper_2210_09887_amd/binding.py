@@ -30,7 +30,7 @@ STATUS_NAMES = {0: "OK", 1: "ERR_NULL", 2: "ERR_SHAPE", 3: "ERR_DTYPE", 4: "ERR_
 
 EXPORTS = ["mdcnn_conv_border", "mdcnn_buffer_bytes", "mdcnn_create_buffer", "mdcnn_destroy_buffer",
            "mdcnn_shift_camera", "mdcnn_set_crop", "mdcnn_layer_forward", "mdcnn_net_create", "mdcnn_net_destroy",
-           "mdcnn_frame", "mdcnn_frame_crop", "mdcnn_frame_batch", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read",
+           "mdcnn_frame", "mdcnn_frame_crop", "mdcnn_frame_batch", "mdcnn_input_mask", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read",
            "mdcnn_pack_weights", "mdcnn_last_error", "mdcnn_version"]
 
 
@@ -43,6 +43,11 @@ class mdcnn_buffer_desc(C.Structure):
 class mdcnn_conv_desc(C.Structure):
     _fields_ = [("k", C.c_int), ("stride", C.c_int), ("pad", C.c_int), ("Cin", C.c_int), ("Cout", C.c_int),
                 ("up", C.c_int), ("w_dev", C.c_void_p), ("w_packed_dev", C.c_void_p), ("op", C.c_int)]
+
+
+class mdcnn_mask_params(C.Structure):
+    _fields_ = [("theta", C.c_float), ("sens_base", C.c_float), ("sens_gain", C.c_float), ("pool", C.c_int),
+                ("suppress", C.c_int), ("dilate", C.c_int)]
 
 
 class MdcnnError(RuntimeError):
@@ -75,6 +80,7 @@ def lib():
         L.mdcnn_net_destroy.argtypes = [vp]
         L.mdcnn_frame.argtypes = [vp, vp, vp, C.c_int, C.c_int, vp, sz, vp, ip]
         L.mdcnn_frame_batch.argtypes = [C.POINTER(vp), C.c_int, C.POINTER(vp), C.POINTER(vp), ip, ip, C.POINTER(vp), sz, vp, ip]
+        L.mdcnn_input_mask.argtypes = [vp, vp, vp, C.POINTER(mdcnn_mask_params), vp, sz, vp]
         L.mdcnn_read_view.argtypes = [vp, C.c_int, vp, sz, vp]
         L.mdcnn_write_view.argtypes = [vp, C.c_int, vp, sz, vp]
         L.mdcnn_set_option.argtypes = [C.c_int, C.c_int]
@@ -198,6 +204,10 @@ def mdcnn_frame_batch(nets, frame_ptrs, forced_ptrs, dty, dtx, out_ptrs, out_byt
                                    (C.c_int * n)(*[int(v) for v in dty]), (C.c_int * n)(*[int(v) for v in dtx]),
                                    (C.c_void_p * n)(*out_ptrs), out_bytes, stream, r))
     return [bool(v) for v in r]
+
+
+def mdcnn_input_mask(buf: int, frame_ptr: int, roi_ptr, prm: mdcnn_mask_params, mask_ptr: int, mask_bytes: int, stream: int = 0):
+    _check(lib().mdcnn_input_mask(buf, frame_ptr, roi_ptr, C.byref(prm), mask_ptr, mask_bytes, stream))
 
 
 def mdcnn_read_view(buf: int, what: int, dst_ptr: int, nbytes: int, stream: int = 0):

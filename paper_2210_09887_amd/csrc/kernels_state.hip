@@ -419,6 +419,91 @@ hipError_t launch_step1(const Step1Batch& bt, int n, hipStream_t st) {
 }
 
 // ---------------------------------------------------------------------------
+// Post-processing of the input update mask.  A block owns 32 x 32 output pixels
+// and keeps everything in LDS: the cells above the threshold of the region its
+// dilation can reach (one more ring of cells for the suppression), the cells
+// that survive the suppression, then a separable OR (along rows, then columns).
+// Cells outside the frame count as not updated.  fp32 in a fixed order: the
+// decisions are those of a sequential evaluation.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int floor_div(int a, int q) { return a >= 0 ? a / q : -((-a + q - 1) / q); }
+
+constexpr int kMaskTile = 32;
+constexpr int kMaskCells = kMaskTile + 2 * kMaskMaxDilate;            // cells a tile can need per axis (pool = 1)
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_input_mask(MaskJob j) {
+    __shared__ uint8_t s_hit[(kMaskCells + 2) * (kMaskCells + 2)];
+    __shared__ uint8_t s_keep[kMaskCells * kMaskCells];
+    __shared__ uint8_t s_row[kMaskCells * kMaskTile];
+    const SiteDev& s = j.s;
+    const int tid = threadIdx.x, q = j.q, d = j.d;
+    const int ty0 = blockIdx.y * kMaskTile, tx0 = blockIdx.x * kMaskTile;
+    const int gh = j.Hc / q, gw = j.Wc / q;                           // cell grid of the frame
+    // cells whose pixels the dilated tile can reach
+    const int ky0 = floor_div(ty0 - d, q), ky1 = floor_div(ty0 + kMaskTile - 1 + d, q);
+    const int kx0 = floor_div(tx0 - d, q), kx1 = floor_div(tx0 + kMaskTile - 1 + d, q);
+    const int kh = ky1 - ky0 + 1, kw = kx1 - kx0 + 1;
+    const int hy0 = ky0 - 1, hx0 = kx0 - 1, hh = kh + 2, hw = kw + 2;  // one more ring for the 3 x 3 count
+    const T* X = (const T*)j.X;
+    for (int i = tid; i < hh * hw; i += 256) {
+        const int cy = hy0 + i / hw, cx = hx0 + i % hw;
+        bool hit = false;
+        if (cy >= 0 && cy < gh && cx >= 0 && cx < gw) {
+            float acc = 0.f;
+            for (int py = cy * q; py < cy * q + q; ++py)
+                for (int px = cx * q; px < cx * q + q; ++px) {
+                    const T* xp = X + ((size_t)py * j.Wc + px) * s.C;
+                    const T* ap = (const T*)s.A + a_offset(s, j.y0 + py, j.x0 + px);
+                    float e = 0.f;
+                    for (int c = 0; c < s.C; ++c) e = fmaxf(e, fabsf((float)xp[c] - (float)ap[c]));
+                    if (j.roi) e = e * (j.base + j.gain * j.roi[(size_t)py * j.Wc + px]);
+                    acc = acc + e;
+                }
+            hit = acc / (float)(q * q) > j.theta;
+        }
+        s_hit[i] = hit;
+    }
+    __syncthreads();
+    for (int i = tid; i < kh * kw; i += 256) {
+        const int r = i / kw, c = i % kw;                              // cell (ky0 + r, kx0 + c) = s_hit[(r + 1) * hw + c + 1]
+        bool keep = s_hit[(r + 1) * hw + c + 1];
+        if (keep && j.suppress) {
+            int cnt = 0;
+            for (int a = 0; a < 3; ++a)
+                for (int b = 0; b < 3; ++b) cnt += s_hit[(r + a) * hw + c + b];
+            keep = cnt >= 2;
+        }
+        s_keep[i] = keep;
+    }
+    __syncthreads();
+    for (int i = tid; i < kh * kMaskTile; i += 256) {
+        const int r = i / kMaskTile, x = tx0 + i % kMaskTile;
+        const int c0 = floor_div(x - d, q) - kx0, c1 = floor_div(x + d, q) - kx0;
+        bool any = false;
+        for (int c = c0; c <= c1; ++c) any |= s_keep[r * kw + c] != 0;
+        s_row[i] = any;
+    }
+    __syncthreads();
+    for (int i = tid; i < kMaskTile * kMaskTile; i += 256) {
+        const int yl = i / kMaskTile, xl = i % kMaskTile;
+        const int y = ty0 + yl, x = tx0 + xl;
+        if (y >= j.Hc || x >= j.Wc) continue;
+        const int r0 = floor_div(y - d, q) - ky0, r1 = floor_div(y + d, q) - ky0;
+        bool any = false;
+        for (int r = r0; r <= r1; ++r) any |= s_row[r * kMaskTile + xl] != 0;
+        j.mask[(size_t)y * j.Wc + x] = any;
+    }
+}
+
+hipError_t launch_input_mask(const MaskJob& j, hipStream_t st) {
+    const dim3 grid((j.Wc + kMaskTile - 1) / kMaskTile, (j.Hc + kMaskTile - 1) / kMaskTile);
+    if (j.s.dtype == MDCNN_F16) k_input_mask<f16><<<grid, dim3(256), 0, st>>>(j);
+    else k_input_mask<float><<<grid, dim3(256), 0, st>>>(j);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // View-ordered access (readout of OUTPUT sites is on the per-frame path).
 // ---------------------------------------------------------------------------
 template <typename T, int VEC>

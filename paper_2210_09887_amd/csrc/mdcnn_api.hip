@@ -699,6 +699,32 @@ mdcnn_status mdcnn_frame_batch(mdcnn_net* const* nets, int n_streams, const void
     return frame_batch(nets, n_streams, frames_dev, forced_masks_dev ? forced_masks_dev : no_forced, dty, dtx, outs_dev, stream, did_full_reset);
 }
 
+mdcnn_status mdcnn_input_mask(const mdcnn_buffer* in, const void* frame_dev, const float* roi_dev,
+                              const mdcnn_mask_params* prm, uint8_t* mask_dev, size_t mask_bytes, void* stream) {
+    if (!in || !frame_dev || !prm || !mask_dev) return fail(MDCNN_ERR_NULL, "input_mask: NULL argument");
+    if (in->d.kind != MDCNN_SITE_INPUT) return fail(MDCNN_ERR_SHAPE, "input_mask: needs an INPUT site");
+    if (in->fresh) return fail(MDCNN_ERR_STATE, "input_mask: mdcnn_shift_camera must be called first");
+    MaskJob j{};
+    j.s = in->dev;
+    j.y0 = in->d.crops ? in->dev.cy0() : 0;
+    j.x0 = in->d.crops ? in->dev.cx0() : 0;
+    j.Hc = in->d.crops ? in->dev.cy1() - j.y0 : in->d.H;
+    j.Wc = in->d.crops ? in->dev.cx1() - j.x0 : in->d.W;
+    const int q = prm->pool;
+    if ((q != 1 && q != 2 && q != 4 && q != 8) || j.Hc % q || j.Wc % q)
+        return fail(MDCNN_ERR_SHAPE, "input_mask: pool must be 1, 2, 4 or 8 and divide the frame of %dx%d pixels", j.Hc, j.Wc);
+    if (prm->dilate < 0 || prm->dilate > kMaskMaxDilate || (prm->suppress != 0 && prm->suppress != 1))
+        return fail(MDCNN_ERR_SHAPE, "input_mask: 0 <= dilate <= %d, suppress is 0 or 1", kMaskMaxDilate);
+    if (mask_bytes != (size_t)j.Hc * j.Wc) return fail(MDCNN_ERR_SIZE, "input_mask: mask_bytes is %zu, the frame has %zu pixels", mask_bytes, (size_t)j.Hc * j.Wc);
+    if ((uintptr_t)frame_dev & (esize(in->d.dtype) - 1) || (uintptr_t)roi_dev & 3) return fail(MDCNN_ERR_ALIGN, "input_mask: misaligned frame or roi");
+    j.X = frame_dev; j.roi = roi_dev; j.mask = mask_dev;
+    j.theta = prm->theta; j.base = prm->sens_base; j.gain = prm->sens_gain;
+    j.q = q; j.suppress = prm->suppress; j.d = prm->dilate;
+    const hipError_t err = launch_input_mask(j, (hipStream_t)stream);
+    if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "input_mask launch: %s", hipGetErrorString(err));
+    return MDCNN_OK;
+}
+
 static mdcnn_status view_bytes(const mdcnn_buffer* b, int what, size_t* need) {
     const mdcnn_buffer_desc& d = b->d;
     const size_t e = esize(d.dtype);

@@ -167,6 +167,18 @@ hipError_t launch_step1(const Step1Batch& b, int n, hipStream_t st);
 hipError_t launch_conv(const EdgeBatch& eb, int n, int dtype, int conv_path, hipStream_t st, int* cls);
 extern int g_tile, g_pipe, g_xcd, g_kc, g_halo, g_halo_sub;   // convolution tuning knobs
 hipError_t launch_pack_weights(const void* src, void* dst, int taps, int Cout, int Cin, hipStream_t st);
+// Post-processed update mask of an INPUT site over the rectangle (y0, x0, Hc, Wc) of its view.
+struct MaskJob {
+    SiteDev s;
+    const void* X;            // Hc x Wc x C, storage dtype
+    const float* roi;         // Hc x Wc or nullptr
+    uint8_t* mask;            // Hc x Wc
+    int y0, x0, Hc, Wc;
+    float theta, base, gain;
+    int q, suppress, d;
+};
+constexpr int kMaskMaxDilate = 32;
+hipError_t launch_input_mask(const MaskJob& j, hipStream_t st);
 hipError_t launch_read_view(const SiteDev& s, int what, void* dst, hipStream_t st);
 hipError_t launch_write_view(const SiteDev& s, int what, const void* src, hipStream_t st);
 

@@ -140,6 +140,16 @@ class GpuNet:
             o += m
         return res, r
 
+    def input_mask(self, X, roi=None, theta=None, base=0.4, gain=0.6, pool=1, suppress=False, dilate=0):
+        """Post-processed update mask of the input site for frame X (device tensor over the crop): a uint8
+        device tensor to pass as the forced mask of that frame."""
+        prm = B.mdcnn_mask_params(float(self.spec.sites[0].theta if theta is None else theta), float(base), float(gain),
+                                  int(pool), int(bool(suppress)), int(dilate))
+        mask = torch.empty(X.shape[:2], dtype=torch.uint8, device=self.dev)
+        B.mdcnn_input_mask(self.bufs[0], X.data_ptr(), None if roi is None else roi.data_ptr(), prm, mask.data_ptr(),
+                           mask.numel(), self._stream())
+        return mask
+
     def layer_forward(self, i, frame=None, forced=None):
         idx = [j for j, s in enumerate(self.esrc) if s == i]
         B.mdcnn_layer_forward(self.bufs[i], None if frame is None else frame.data_ptr(),

@@ -175,3 +175,22 @@ def test_crop_argument_checks_need_no_gpu():
     with pytest.raises(B.MdcnnError) as ei:
         B.mdcnn_buffer_bytes(d)
     assert ei.value.status == 2
+
+
+def test_input_mask_argument_checks_need_no_gpu():
+    prm = B.mdcnn_mask_params(0.1, 0.4, 0.6, 1, 0, 0)
+    d = desc(H=16, W=16, Cc=3, kind=B.MDCNN_SITE_INPUT, border=(0, 0, 0, 0))
+    h = B.mdcnn_create_buffer(d, FAKE, B.mdcnn_buffer_bytes(d))
+    with pytest.raises(B.MdcnnError) as ei:                 # never shifted
+        B.mdcnn_input_mask(h, FAKE, None, prm, FAKE, 256)
+    assert ei.value.status == 6
+    with pytest.raises(B.MdcnnError) as ei:
+        B.mdcnn_input_mask(h, None, None, prm, FAKE, 256)
+    assert ei.value.status == 1
+    B.mdcnn_destroy_buffer(h)
+    p = desc()
+    h = B.mdcnn_create_buffer(p, FAKE, B.mdcnn_buffer_bytes(p))
+    with pytest.raises(B.MdcnnError) as ei:                 # not an INPUT site
+        B.mdcnn_input_mask(h, FAKE, None, prm, FAKE, 64)
+    assert ei.value.status == 2
+    B.mdcnn_destroy_buffer(h)
