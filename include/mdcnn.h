@@ -298,10 +298,21 @@ typedef enum {
     MDCNN_OPT_CONV_HALO = 6, /* tuning: 1 (default) packed-weights kernel where it applies,  */
                              /* 0 never, 2 with 32-cout tiles                              */
     MDCNN_OPT_CONV_HALO_SUB = 7, /* tuning: 0 auto, 1 / 2 / 4 tiles per list segment of that kernel */
-    MDCNN_OPT_FUSE_SKIP = 8  /* 1 (default): mdcnn_frame lets the delta kernel of a site add its   */
+    MDCNN_OPT_FUSE_SKIP = 8, /* 1 (default): mdcnn_frame lets the delta kernel of a site add its   */
                              /* residual skip (identity edge) instead of a launch of its own; */
                              /* such an edge then adds nothing to the compute-list statistics  */
                              /* of its destination.  0: one launch per edge                  */
+    MDCNN_OPT_STREAMS = 9    /* 2..4: mdcnn_frame, mdcnn_frame_crop and mdcnn_frame_batch put       */
+                             /* independent branches of the network on up to this many streams:     */
+                             /* the caller's plus the library's own (per host thread, default     */
+                             /* priority, created on first use).  The caller's stream forks into  */
+                             /* them after the camera shift and waits for them before the readout, */
+                             /* so the call stays in stream order; launches that write one site    */
+                             /* keep their order, so the results do not change by a bit.  1: all   */
+                             /* launches on the caller's stream.  0 (default): four streams if the */
+                             /* network has parallel branches that shorten a frame by a fifth or   */
+                             /* more (counted in launches, a wait for another stream as one), else */
+                             /* the caller's stream only                                           */
 } mdcnn_option;
 mdcnn_status mdcnn_set_option(int option, int value);
 

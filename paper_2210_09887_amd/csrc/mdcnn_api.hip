@@ -18,6 +18,7 @@ thread_local char g_err[512] = "";
 int g_conv_path = 0;
 int g_fuse_skip = 1;      // mdcnn_frame: residual skips are added by the step-1 kernel of their source
 int g_profile = 0;
+int g_streams = 0;        // mdcnn_frame: independent branches of the network go to up to this many streams; 0: decide per network
 
 // Profiling mode: every kernel launch is bracketed by a pair of events on its
 // own stream; mdcnn_profile_read waits for them and sums the times per class.
@@ -118,11 +119,25 @@ struct mdcnn_buffer {
     bool r_up, r_down, r_left, r_right;   // directions in which growth is restricted
 };
 
+// Launch plan of one frame: node = one kernel launch in program order (per non-terminal site its
+// step-1 launch, then one launch per edge that gets one, or the compaction-only launch).
+struct PlanNode {
+    int stream;                // index into the streams of the call (0: the caller's)
+    bool record;               // a node on another stream waits for this one
+    std::vector<int> wait;     // nodes on other streams that must have finished
+};
+struct Plan {
+    int key = -1;              // g_streams * 2 + g_fuse_skip the plan was made for
+    int streams = 1;           // streams that carry at least one node
+    std::vector<PlanNode> nodes;
+};
+
 struct mdcnn_net {
     std::vector<mdcnn_buffer*> sites;
     std::vector<int> esrc, edst;
     std::vector<mdcnn_conv_desc> edges;
     size_t out_bytes;
+    Plan plan;
 };
 
 namespace {
@@ -236,9 +251,36 @@ mdcnn_status validate_forward(const mdcnn_buffer* in, const void* frame, const m
 // from ins[b] along edges[b][0 .. n_edges) to outs[b][0 .. n_edges).
 // fuse_skip: index of an identity edge whose add is done by the step-1 kernel (its
 // destination is touched there and the edge gets no launch of its own), or -1.
+// Streams and events of one multi-stream frame.  Every wait is on an event that was recorded
+// earlier in the same call, so no stream can wait for something that never happens.
+constexpr int kMaxStreams = 4;
+struct Sched {
+    const Plan* plan = nullptr;
+    hipStream_t s[kMaxStreams] = {};
+    std::vector<hipEvent_t> ev;                            // per node, set where plan->nodes[i].record
+    int next = 0;                                          // node of the next launch
+    hipError_t err = hipSuccess;
+    hipStream_t begin() {                                  // waits of the next node; returns its stream
+        const PlanNode& nd = plan->nodes[next];
+        for (int w : nd.wait) {
+            const hipError_t e = hipStreamWaitEvent(s[nd.stream], ev[w], 0);
+            if (e != hipSuccess && err == hipSuccess) err = e;
+        }
+        return s[nd.stream];
+    }
+    void end() {
+        const PlanNode& nd = plan->nodes[next];
+        if (nd.record) {
+            const hipError_t e = hipEventRecord(ev[next], s[nd.stream]);
+            if (e != hipSuccess && err == hipSuccess) err = e;
+        }
+        ++next;
+    }
+};
+
 mdcnn_status do_forward(int n, mdcnn_buffer* const* ins, const void* const* frames, const uint8_t* const* forced,
                         const mdcnn_conv_desc* const* edges, mdcnn_buffer* const* const* outs, int n_edges,
-                        hipStream_t st, int fuse_skip = -1) {
+                        hipStream_t st, int fuse_skip = -1, Sched* sc = nullptr) {
     static thread_local Step1Batch sb;                     // 3.4 KiB each: kept off the stack
     static thread_local EdgeBatch eb;
     for (int b = 0; b < n; ++b) {
@@ -255,9 +297,13 @@ mdcnn_status do_forward(int n, mdcnn_buffer* const* ins, const void* const* fram
             k.p_oy = d->dev.p_oy; k.p_ox = d->dev.p_ox;
         }
     }
+    if (sc) st = sc->begin();
     hipError_t err = timed(kClsStep1, st, [&] { return launch_step1(sb, n, st); });
+    if (sc) sc->end();
     if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "step-1 launch: %s", hipGetErrorString(err));
     auto launch_edge = [&](int idx) -> mdcnn_status {
+        if (sc) st = sc->begin();
+        struct AtExit { Sched* sc; ~AtExit() { if (sc) sc->end(); } } at_exit{sc};
         int cls = kClsConvPlain;
         TimedLaunch t{0, nullptr, nullptr};
         if (g_profile) {              // the class is known only after dispatch: record around, file under it
@@ -322,6 +368,123 @@ bool same_shape(const mdcnn_net* a, const mdcnn_net* b) {
     return true;
 }
 
+// Which edge of the forward call of site i (edges [e0, e1)) is added by the step-1 kernel: a
+// residual skip keeps its place in the order of the producers of its destination as long as
+// no other edge of the call goes to the same destination before it.  -1: none.
+int fused_skip(const mdcnn_net* net, int e0, int e1) {
+    if (!g_fuse_skip) return -1;
+    for (int e = e0; e < e1; ++e) {
+        if (net->edges[e].k != 0) continue;
+        bool earlier = false;
+        for (int q = e0; q < e; ++q) earlier |= net->edst[q] == net->edst[e];
+        if (!earlier) return e - e0;
+    }
+    return -1;
+}
+
+// Plan of a frame on up to `ns` streams.  A launch reads its source site and reads and writes
+// its destination site (step 1: its own site and the destination of a fused skip), so it has
+// to follow the last writer of each; writers of one site keep their program order (the sum in
+// P is taken in that order, whatever the streams do).  Every site gets a home stream on which
+// everything that writes it runs: that of the source for the first launched edge of a forward
+// call - a chain of layers stays on one stream - and the next stream in turn for the others,
+// which are the starts of parallel branches.
+void make_plan(const mdcnn_net* net, int ns, Plan& plan) {
+    const int n_sites = (int)net->sites.size(), n_edges = (int)net->edges.size();
+    std::vector<int> home(n_sites, -1), lastw(n_sites, -1);
+    plan.nodes.clear();
+    home[0] = 0;
+    int rr = 0, e0 = 0;
+    auto add = [&](int stream, std::initializer_list<int> deps) {
+        PlanNode nd{stream, false, {}};
+        for (int d : deps) {
+            if (d < 0 || plan.nodes[d].stream == stream) continue;      // same stream: already in order
+            bool have = false;
+            for (int w : nd.wait) have |= w == d;
+            if (!have) { nd.wait.push_back(d); plan.nodes[d].record = true; }
+        }
+        plan.nodes.push_back(nd);
+        return (int)plan.nodes.size() - 1;
+    };
+    for (int i = 0; i < n_sites; ++i) {
+        if (net->sites[i]->d.kind == MDCNN_SITE_OUTPUT) continue;
+        int e1 = e0;
+        while (e1 < n_edges && net->esrc[e1] == i) ++e1;
+        if (home[i] < 0) home[i] = 0;
+        const int fuse = fused_skip(net, e0, e1);
+        const int skip_dst = fuse >= 0 ? net->edst[e0 + fuse] : -1;
+        const int s1 = add(home[i], {lastw[i], skip_dst >= 0 ? lastw[skip_dst] : -1});
+        lastw[i] = s1;
+        if (skip_dst >= 0) {
+            lastw[skip_dst] = s1;
+            if (home[skip_dst] < 0) home[skip_dst] = home[i];
+        }
+        bool first = true;
+        for (int e = e0; e < e1; ++e) {
+            if (e - e0 == fuse) continue;
+            const int d = net->edst[e];
+            if (home[d] < 0) {
+                if (first) home[d] = home[i];
+                else {
+                    rr = (rr + 1) % ns;
+                    if (rr == home[i] && ns > 1) rr = (rr + 1) % ns;
+                    home[d] = rr;
+                }
+            }
+            lastw[d] = add(home[d], {s1, lastw[d]});
+            first = false;
+        }
+        if (first) add(home[i], {s1});                     // no launched edge: the compaction-only launch
+        e0 = e1;
+    }
+    plan.streams = 1;
+    for (const PlanNode& nd : plan.nodes) plan.streams = nd.stream + 1 > plan.streams ? nd.stream + 1 : plan.streams;
+}
+
+// Length of a plan in launches, if every launch took one unit of time and a wait for another
+// stream one more (measured: such a wait costs about as much as a small launch).  These
+// launches are bound by their latency, not by the size of the GPU, so this is the time a frame
+// takes; a plan on one stream is as long as it has nodes.
+double plan_length(const Plan& plan) {
+    std::vector<double> done(plan.nodes.size(), 0.0);
+    double avail[kMaxStreams] = {}, total = 0.0;
+    for (size_t i = 0; i < plan.nodes.size(); ++i) {
+        const PlanNode& nd = plan.nodes[i];
+        double t = avail[nd.stream];
+        for (int w : nd.wait) t = done[w] + 1.0 > t ? done[w] + 1.0 : t;
+        done[i] = avail[nd.stream] = t + 1.0;
+        total = done[i] > total ? done[i] : total;
+    }
+    return total;
+}
+
+// The library's own streams (per host thread, default priority, made on first use) and events.
+struct Aux {
+    hipStream_t s[kMaxStreams - 1] = {};
+    int n = 0, device = -1;
+    std::vector<hipEvent_t> events;
+};
+thread_local Aux g_aux;
+
+hipError_t aux_prepare(int streams, size_t events) {
+    int dev = 0;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    if (g_aux.device != dev) { g_aux = Aux{}; g_aux.device = dev; }       // streams of another device are left alone
+    while (g_aux.n < streams - 1) {
+        err = hipStreamCreateWithFlags(&g_aux.s[g_aux.n], hipStreamNonBlocking);
+        if (err != hipSuccess) return err;
+        ++g_aux.n;
+    }
+    while (g_aux.events.size() < events) {
+        hipEvent_t e = nullptr;
+        err = hipEventCreateWithFlags(&e, hipEventDisableTiming);
+        if (err != hipSuccess) return err;
+        g_aux.events.push_back(e);
+    }
+    return hipSuccess;
+}
+
 size_t crop_pixels(const mdcnn_buffer* b) {                // sites without crops: the view
     if (!b->d.crops) return (size_t)b->d.H * b->d.W;
     return (size_t)(b->dev.cy1() - b->dev.cy0()) * (size_t)(b->dev.cx1() - b->dev.cx0());
@@ -337,8 +500,49 @@ mdcnn_status frame_batch(mdcnn_net* const* nets, int n, const void* const* frame
                                              did_full_reset ? did_full_reset + b : nullptr);
         if (rc) return rc;
     }
-    const mdcnn_net* net = nets[0];
+    mdcnn_net* net = nets[0];
     const int n_edges = (int)net->edges.size();
+    // independent branches of the network on streams of their own; the caller's stream forks into
+    // them after the shift and joins them before the readout, so to the caller the call is in
+    // stream order as before
+    Sched sched, *sc = nullptr;
+    if (g_streams != 1) {
+        const int key = g_streams * 2 + g_fuse_skip;
+        if (net->plan.key != key) {
+            make_plan(net, g_streams ? g_streams : kMaxStreams, net->plan);
+            // left to itself the library uses the streams only where the network has branches
+            // that are worth it: the plan must be a fifth shorter than the launches in a row
+            if (!g_streams && plan_length(net->plan) > 0.8 * (double)net->plan.nodes.size()) make_plan(net, 1, net->plan);
+            net->plan.key = key;
+        }
+        if (net->plan.streams > 1) {
+            const size_t n_nodes = net->plan.nodes.size();
+            hipError_t err = aux_prepare(net->plan.streams, n_nodes + kMaxStreams);
+            if (err == hipSuccess) err = hipEventRecord(g_aux.events[n_nodes], st);          // fork
+            for (int k = 1; k < net->plan.streams && err == hipSuccess; ++k) err = hipStreamWaitEvent(g_aux.s[k - 1], g_aux.events[n_nodes], 0);
+            if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "stream set-up: %s", hipGetErrorString(err));
+            sched.plan = &net->plan;
+            sched.s[0] = st;
+            for (int k = 1; k < net->plan.streams; ++k) sched.s[k] = g_aux.s[k - 1];
+            sched.ev.assign(g_aux.events.begin(), g_aux.events.begin() + n_nodes);
+            sc = &sched;
+        }
+    }
+    // whatever happens below, the caller's stream waits for the other streams before the call returns
+    struct Join {
+        Sched* sc; hipStream_t st; size_t base;
+        hipError_t run() {
+            hipError_t err = hipSuccess;
+            for (int k = 1; sc && k < sc->plan->streams; ++k) {
+                hipError_t e = hipEventRecord(g_aux.events[base + k], sc->s[k]);
+                if (e == hipSuccess) e = hipStreamWaitEvent(st, g_aux.events[base + k], 0);
+                if (e != hipSuccess && err == hipSuccess) err = e;
+            }
+            sc = nullptr;
+            return err;
+        }
+        ~Join() { (void)run(); }
+    } join{sc, st, net->plan.nodes.size()};
     int e0 = 0;
     std::vector<mdcnn_buffer*> outs_flat;
     mdcnn_buffer* ins[kMaxBatch];
@@ -359,16 +563,15 @@ mdcnn_status frame_batch(mdcnn_net* const* nets, int n, const void* const* frame
         // a residual skip is added by the step-1 kernel of its source; its place in the
         // order of the producers of its destination stays the same as long as no other
         // edge of this call goes to the same destination before it
-        int fuse = -1;
-        for (int e = e0; e < e1 && g_fuse_skip && fuse < 0; ++e) {
-            if (net->edges[e].k != 0) continue;
-            bool earlier = false;
-            for (int q = e0; q < e; ++q) earlier |= net->edst[q] == net->edst[e];
-            if (!earlier) fuse = e - e0;
-        }
-        mdcnn_status rc = do_forward(n, ins, i == 0 ? frames : nullptr, i == 0 ? forced : nullptr, edges, outs, ne, st, fuse);
+        const int fuse = fused_skip(net, e0, e1);
+        mdcnn_status rc = do_forward(n, ins, i == 0 ? frames : nullptr, i == 0 ? forced : nullptr, edges, outs, ne, st, fuse, sc);
         if (rc) return rc;
         e0 = e1;
+    }
+    if (sc) {
+        hipError_t err = join.run();
+        if (err == hipSuccess) err = sched.err;
+        if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "stream synchronisation: %s", hipGetErrorString(err));
     }
     for (int b = 0; b < n; ++b) {
         char* o = (char*)outs_dev[b];
@@ -392,6 +595,7 @@ const char* mdcnn_version(void) { return "mdcnn 0.1 (gfx950)"; }
 mdcnn_status mdcnn_set_option(int option, int value) {
     if (option == MDCNN_OPT_CONV_PATH && value >= 0 && value <= 3) { g_conv_path = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_CONV_HALO && value >= 0 && value <= 2) { g_halo = value; return MDCNN_OK; }
+    if (option == MDCNN_OPT_STREAMS && value >= 0 && value <= kMaxStreams) { g_streams = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_FUSE_SKIP && (value == 0 || value == 1)) { g_fuse_skip = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_CONV_HALO_SUB && (value == 0 || value == 1 || value == 2 || value == 4)) { g_halo_sub = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_PROFILE && (value == 0 || value == 1)) { g_profile = value; return MDCNN_OK; }
