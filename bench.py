@@ -39,7 +39,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=180)
     ap.add_argument("--warmup", type=int, default=60)
-    ap.add_argument("--config", type=int, default=3, help="BASELINE config (3 = headline)")
+    ap.add_argument("--config", type=int, default=3, help="benchmark workload 1..5 (3 = headline)")
     ap.add_argument("--density", type=float, default=0.2, help="config 5 only")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle baseline; 0 disables it")
     ap.add_argument("--dense", action="store_true", help="library dense mode: threshold 0 and all pixels forced")

@@ -282,7 +282,7 @@ def _toposort(net: NetSpec):
 
 
 def build_net(config: int, **overrides) -> NetSpec:
-    """Network of BASELINE config `config` (1..5); `overrides` shrink the input
+    """Network of benchmark workload `config` (1..5); `overrides` shrink the input
     size or the widths for quick parity cases (same topology, same seed)."""
     rng = np.random.default_rng(np.random.PCG64(BASE_SEED + 100 + config))
     fn = {1: _single_conv, 2: _cnn5, 3: _resnet18, 4: _hrnet, 5: _bottleneck}[config]

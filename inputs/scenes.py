@@ -204,6 +204,6 @@ def _seq5(density=0.2, n_frames=50, H=128, W=128, C=256, shift_every=10, shift=1
 
 
 def build_sequence(config: int, **kw) -> Sequence:
-    """Frame sequence of BASELINE config `config` (1..5).  Keyword overrides
+    """Frame sequence of benchmark workload `config` (1..5).  Keyword overrides
     (n_frames, H, W, density, ...) give reduced parity cases from the same recipe."""
     return {1: _seq1, 2: _seq2, 3: _seq3, 4: _seq4, 5: _seq5}[config](**kw)

@@ -1,4 +1,4 @@
-"""GPU parity at the full sizes of the five BASELINE workloads, in the launch
+"""GPU parity at the full sizes of the five benchmark workloads, in the launch
 configuration bench.py times (mdcnn_frame end to end), checked against the
 oracle on the first frames of each sequence and against properties that hold
 at any size (reset frames equal a dense CNN computed with a library routine)."""
