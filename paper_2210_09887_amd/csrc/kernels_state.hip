@@ -446,23 +446,50 @@ __global__ __launch_bounds__(256) void k_input_mask(MaskJob j) {
     const int kh = ky1 - ky0 + 1, kw = kx1 - kx0 + 1;
     const int hy0 = ky0 - 1, hx0 = kx0 - 1, hh = kh + 2, hw = kw + 2;  // one more ring for the 3 x 3 count
     const T* X = (const T*)j.X;
-    for (int i = tid; i < hh * hw; i += 256) {
-        const int cy = hy0 + i / hw, cx = hx0 + i % hw;
-        bool hit = false;
-        if (cy >= 0 && cy < gh && cx >= 0 && cx < gw) {
-            float acc = 0.f;
-            for (int py = cy * q; py < cy * q + q; ++py)
-                for (int px = cx * q; px < cx * q + q; ++px) {
-                    const T* xp = X + ((size_t)py * j.Wc + px) * s.C;
-                    const T* ap = (const T*)s.A + a_offset(s, j.y0 + py, j.x0 + px);
-                    float e = 0.f;
-                    for (int c = 0; c < s.C; ++c) e = fmaxf(e, fabsf((float)xp[c] - (float)ap[c]));
-                    if (j.roi) e = e * (j.base + j.gain * j.roi[(size_t)py * j.Wc + px]);
-                    acc = acc + e;
-                }
-            hit = acc / (float)(q * q) > j.theta;
+    auto magnitude = [&](int py, int px) {                             // of one pixel of the frame
+        const T* xp = X + ((size_t)py * j.Wc + px) * s.C;
+        const T* ap = (const T*)s.A + a_offset(s, j.y0 + py, j.x0 + px);
+        float e = 0.f;
+        if (s.C <= 4) {                                                // images: all loads go out before the first use
+            float xv[4], av[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) { xv[c] = (float)xp[c < s.C ? c : 0]; av[c] = (float)ap[c < s.C ? c : 0]; }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) e = fmaxf(e, fabsf(xv[c] - av[c]));    // a repeated channel does not change the maximum
+        } else {
+            for (int c = 0; c < s.C; ++c) e = fmaxf(e, fabsf((float)xp[c] - (float)ap[c]));
         }
-        s_hit[i] = hit;
+        if (j.roi) e = e * (j.base + j.gain * j.roi[(size_t)py * j.Wc + px]);
+        return e;
+    };
+    if (q == 1) {
+        // a pixel per cell: four cells of a thread at a time, so that their loads overlap
+        for (int i0 = tid; i0 < hh * hw; i0 += 4 * 256) {
+            float e[4];
+            bool in[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = i0 + u * 256;
+                const int cy = hy0 + i / hw, cx = hx0 + i % hw;
+                in[u] = i < hh * hw && cy >= 0 && cy < gh && cx >= 0 && cx < gw;
+                e[u] = magnitude(in[u] ? cy : 0, in[u] ? cx : 0);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (i0 + u * 256 < hh * hw) s_hit[i0 + u * 256] = in[u] && e[u] > j.theta;
+        }
+    } else {
+        for (int i = tid; i < hh * hw; i += 256) {
+            const int cy = hy0 + i / hw, cx = hx0 + i % hw;
+            bool hit = false;
+            if (cy >= 0 && cy < gh && cx >= 0 && cx < gw) {
+                float acc = 0.f;
+                for (int py = cy * q; py < cy * q + q; ++py)
+                    for (int px = cx * q; px < cx * q + q; ++px) acc = acc + magnitude(py, px);
+                hit = acc / (float)(q * q) > j.theta;
+            }
+            s_hit[i] = hit;
+        }
     }
     __syncthreads();
     for (int i = tid; i < kh * kw; i += 256) {
