@@ -211,6 +211,21 @@ mdcnn_status mdcnn_frame_crop(mdcnn_net* net, const void* frame_dev, const uint8
                               int dty, int dtx, int ty0, int tx0, int th, int tw,
                               void* out_dev, size_t out_bytes, void* stream, int* did_full_reset);
 
+/* Host-only.  The launch plan that mdcnn_frame follows for `net` when it may use
+ * `streams` streams (1..4, or 0 for the library's own choice, see
+ * MDCNN_OPT_STREAMS): one entry per kernel launch between the camera shift and the
+ * readout, in launch order - per non-terminal site its delta launch, then one
+ * launch per outgoing edge that gets one (a residual skip added by the delta kernel
+ * gets none; a site without such edges gets one compaction launch).
+ * stream_of[i]: stream of launch i (0 = the caller's); waits_of[2i], waits_of[2i+1]:
+ * launches on other streams that launch i waits for, or -1 (launches on one stream
+ * run in order anyway).  Both arrays are caller-owned with room for `cap` launches
+ * (2 * cap ints for waits_of) and may be NULL; *n_launches and *n_streams (optional)
+ * get the number of launches and of streams used.
+ * Errors: MDCNN_ERR_SIZE if cap is too small or streams out of range. */
+mdcnn_status mdcnn_frame_plan(mdcnn_net* net, int streams, int* stream_of, int* waits_of, int cap,
+                              int* n_launches, int* n_streams);
+
 /* The same for n_streams independent video streams in the same launches (the
  * paper fills the GPU with a batch of streams [Evaluation: batch size]).  Stream b
  * is nets[b]: all nets must have the same topology and the same site and edge

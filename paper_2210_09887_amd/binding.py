@@ -30,7 +30,7 @@ STATUS_NAMES = {0: "OK", 1: "ERR_NULL", 2: "ERR_SHAPE", 3: "ERR_DTYPE", 4: "ERR_
 
 EXPORTS = ["mdcnn_conv_border", "mdcnn_buffer_bytes", "mdcnn_create_buffer", "mdcnn_destroy_buffer",
            "mdcnn_shift_camera", "mdcnn_set_crop", "mdcnn_layer_forward", "mdcnn_net_create", "mdcnn_net_destroy",
-           "mdcnn_frame", "mdcnn_frame_crop", "mdcnn_frame_batch", "mdcnn_input_mask", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read",
+           "mdcnn_frame", "mdcnn_frame_crop", "mdcnn_frame_batch", "mdcnn_frame_plan", "mdcnn_input_mask", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read",
            "mdcnn_pack_weights", "mdcnn_last_error", "mdcnn_version"]
 
 
@@ -80,6 +80,7 @@ def lib():
         L.mdcnn_net_destroy.argtypes = [vp]
         L.mdcnn_frame.argtypes = [vp, vp, vp, C.c_int, C.c_int, vp, sz, vp, ip]
         L.mdcnn_frame_batch.argtypes = [C.POINTER(vp), C.c_int, C.POINTER(vp), C.POINTER(vp), ip, ip, C.POINTER(vp), sz, vp, ip]
+        L.mdcnn_frame_plan.argtypes = [vp, C.c_int, ip, ip, C.c_int, ip, ip]
         L.mdcnn_input_mask.argtypes = [vp, vp, vp, C.POINTER(mdcnn_mask_params), vp, sz, vp]
         L.mdcnn_read_view.argtypes = [vp, C.c_int, vp, sz, vp]
         L.mdcnn_write_view.argtypes = [vp, C.c_int, vp, sz, vp]
@@ -204,6 +205,16 @@ def mdcnn_frame_batch(nets, frame_ptrs, forced_ptrs, dty, dtx, out_ptrs, out_byt
                                    (C.c_int * n)(*[int(v) for v in dty]), (C.c_int * n)(*[int(v) for v in dtx]),
                                    (C.c_void_p * n)(*out_ptrs), out_bytes, stream, r))
     return [bool(v) for v in r]
+
+
+def mdcnn_frame_plan(net: int, streams: int = 0):
+    """(stream of every launch, [launches it waits for], streams used) of a frame of `net`."""
+    n, ns = C.c_int(), C.c_int()
+    _check(lib().mdcnn_frame_plan(net, int(streams), None, None, 0, C.byref(n), C.byref(ns)))
+    so, wo = (C.c_int * n.value)(), (C.c_int * (2 * n.value))()
+    _check(lib().mdcnn_frame_plan(net, int(streams), so, wo, n.value, None, None))
+    waits = [[w for w in (wo[2 * i], wo[2 * i + 1]) if w >= 0] for i in range(n.value)]
+    return list(so), waits, ns.value
 
 
 def mdcnn_input_mask(buf: int, frame_ptr: int, roi_ptr, prm: mdcnn_mask_params, mask_ptr: int, mask_bytes: int, stream: int = 0):

@@ -458,6 +458,13 @@ double plan_length(const Plan& plan) {
     return total;
 }
 
+// streams = 0: left to itself the library uses four streams, and only where the network has
+// branches that are worth it: the plan must be a fifth shorter than the launches in a row.
+void choose_plan(const mdcnn_net* net, int streams, Plan& plan) {
+    make_plan(net, streams ? streams : kMaxStreams, plan);
+    if (!streams && plan_length(plan) > 0.8 * (double)plan.nodes.size()) make_plan(net, 1, plan);
+}
+
 // The library's own streams (per host thread, default priority, made on first use) and events.
 struct Aux {
     hipStream_t s[kMaxStreams - 1] = {};
@@ -509,10 +516,7 @@ mdcnn_status frame_batch(mdcnn_net* const* nets, int n, const void* const* frame
     if (g_streams != 1) {
         const int key = g_streams * 2 + g_fuse_skip;
         if (net->plan.key != key) {
-            make_plan(net, g_streams ? g_streams : kMaxStreams, net->plan);
-            // left to itself the library uses the streams only where the network has branches
-            // that are worth it: the plan must be a fifth shorter than the launches in a row
-            if (!g_streams && plan_length(net->plan) > 0.8 * (double)net->plan.nodes.size()) make_plan(net, 1, net->plan);
+            choose_plan(net, g_streams, net->plan);
             net->plan.key = key;
         }
         if (net->plan.streams > 1) {
@@ -882,6 +886,27 @@ mdcnn_status mdcnn_frame_crop(mdcnn_net* net, const void* frame_dev, const uint8
     mdcnn_status rc = mdcnn_set_crop(net->sites.data(), (int)net->sites.size(), ty0, tx0, th, tw);
     if (rc) return rc;
     return frame_batch(&net, 1, &frame_dev, &forced_mask_dev, &dty, &dtx, &out_dev, stream, did_full_reset);
+}
+
+mdcnn_status mdcnn_frame_plan(mdcnn_net* net, int streams, int* stream_of, int* waits_of, int cap, int* n_launches,
+                              int* n_streams) {
+    if (!net) return fail(MDCNN_ERR_NULL, "net is NULL");
+    if (streams < 0 || streams > kMaxStreams) return fail(MDCNN_ERR_SIZE, "frame_plan: 0 <= streams <= %d", kMaxStreams);
+    Plan plan;
+    choose_plan(net, streams, plan);
+    const int n = (int)plan.nodes.size();
+    if ((stream_of || waits_of) && cap < n) return fail(MDCNN_ERR_SIZE, "frame_plan: %d launches, room for %d", n, cap);
+    for (int i = 0; i < n; ++i) {
+        const PlanNode& nd = plan.nodes[i];
+        if (stream_of) stream_of[i] = nd.stream;
+        if (waits_of) {
+            waits_of[2 * i] = nd.wait.size() > 0 ? nd.wait[0] : -1;
+            waits_of[2 * i + 1] = nd.wait.size() > 1 ? nd.wait[1] : -1;
+        }
+    }
+    if (n_launches) *n_launches = n;
+    if (n_streams) *n_streams = plan.streams;
+    return MDCNN_OK;
 }
 
 mdcnn_status mdcnn_frame_batch(mdcnn_net* const* nets, int n_streams, const void* const* frames_dev,

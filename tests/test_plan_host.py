@@ -1,0 +1,128 @@
+"""Host-side check of the launch plan of a frame (mdcnn_frame_plan): whatever
+streams the launches are put on, two launches that touch the same site, at
+least one of them writing it, must be ordered - by running on one stream or
+through the waits.  The launches and what they touch are derived here from the
+network description alone; no GPU is needed (buffers wrap a fake address)."""
+import pytest
+
+from inputs import build_net
+from inputs.nets import pool_net
+from paper_2210_09887_amd import binding as B
+
+FAKE = 0x7F0000000000
+
+
+def host_net(spec):
+    """The library handles of `spec` without device memory (nothing is launched)."""
+    dt = B.MDCNN_F16 if spec.dtype == "f16" else B.MDCNN_F32
+    shape = [(spec.H // s.stride, spec.W // s.stride, s.C) for s in spec.sites]
+    border = [[0, 0, 0, 0] for _ in spec.sites]
+    pooled, edges = set(), []
+    for e in spec.edges:
+        Hs, Ws, _ = shape[e.src]
+        pool = getattr(e, "pool", False)
+        cd = B.mdcnn_conv_desc(e.k, e.stride, e.pad, spec.sites[e.src].C, spec.sites[e.dst].C, e.up, FAKE if e.k and not pool else None, None, int(pool))
+        if pool:
+            pooled.add(e.dst)
+        elif e.k:
+            oh, ow = (Hs + 2 * e.pad - e.k) // e.stride + 1, (Ws + 2 * e.pad - e.k) // e.stride + 1
+            by, bx = B.mdcnn_conv_border(e.k, e.stride, e.pad, Hs, oh), B.mdcnn_conv_border(e.k, e.stride, e.pad, Ws, ow)
+            border[e.dst] = [max(a, b) for a, b in zip(border[e.dst], [by[0], by[1], bx[0], bx[1]])]
+        edges.append(cd)
+    kinds = {"input": B.MDCNN_SITE_INPUT, "preact": B.MDCNN_SITE_PREACT, "output": B.MDCNN_SITE_OUTPUT}
+    bufs = []
+    for i, s in enumerate(spec.sites):
+        d = B.mdcnn_buffer_desc()
+        d.H, d.W, d.C, d.dtype, d.kind = shape[i][0], shape[i][1], shape[i][2], dt, kinds[s.kind]
+        for j in range(4):
+            d.border[j] = border[i][j]
+        d.tile = spec.total_stride // s.stride
+        d.pool_prev = int(i in pooled)
+        bufs.append(B.mdcnn_create_buffer(d, FAKE, B.mdcnn_buffer_bytes(d)))
+    net = B.mdcnn_net_create(bufs, [e.src for e in spec.edges], [e.dst for e in spec.edges], edges)
+    return net, bufs
+
+
+def launches_of(spec):
+    """[(sites read, sites written)] per launch in program order, as the frame call issues them:
+    the delta launch of a site (which also adds a residual skip that is the first edge of the call
+    into its destination), then one launch per remaining edge, or one compaction launch."""
+    out = []
+    for i, s in enumerate(spec.sites):
+        if s.kind == "output":
+            continue
+        mine = [e for e in spec.edges if e.src == i]
+        fused = None
+        for n, e in enumerate(mine):
+            if e.k == 0 and all(q.dst != e.dst for q in mine[:n]):
+                fused = n
+                break
+        out.append((set(), {i} | ({mine[fused].dst} if fused is not None else set())))
+        rest = [e for n, e in enumerate(mine) if n != fused]
+        for e in rest:
+            out.append(({i}, {e.dst}))
+        if not rest:
+            out.append(({i}, {i}))                          # compaction of the site's own list
+    return out
+
+
+def ordered_before(streams, waits):
+    """reach[b] = set of launches that are certain to have finished when b starts."""
+    reach, last_on = [], {}
+    for b, (s, w) in enumerate(zip(streams, waits)):
+        r = set()
+        for a in ([last_on[s]] if s in last_on else []) + list(w):
+            r |= reach[a] | {a}
+        reach.append(r)
+        last_on[s] = b
+    return reach
+
+
+NETS = {
+    "resnet": lambda: build_net(3, H=64, W=64, widths=(32, 64, 64, 128)),
+    "resnet_poolstem": lambda: build_net(3, H=64, W=64, widths=(32, 64, 64, 128), pool_stem=True),
+    "hrnet": lambda: build_net(4, H=128, W=96, widths=(32, 64, 64, 128), blocks=2),
+    "hrnet_full": lambda: build_net(4),
+    "bottleneck": lambda: build_net(5, H=16, W=16, C=64, Cm=32),
+    "cnn5": lambda: build_net(2, H=64, W=64),
+    "pool": lambda: pool_net("f16", 16, 16, (8, 16, 8), 3, 2, 1),
+}
+
+
+@pytest.mark.parametrize("name", list(NETS))
+@pytest.mark.parametrize("streams", [0, 1, 2, 3, 4])
+def test_conflicting_launches_are_ordered(name, streams):
+    spec = NETS[name]()
+    net, bufs = host_net(spec)
+    try:
+        so, waits, used = B.mdcnn_frame_plan(net, streams)
+        want = launches_of(spec)
+        assert len(so) == len(want)
+        assert used == max(so) + 1 and used <= (streams or 4)
+        assert all(a < b for b, w in enumerate(waits) for a in w)          # only launches issued earlier are waited for
+        assert all(so[a] != so[b] for b, w in enumerate(waits) for a in w)
+        reach = ordered_before(so, waits)
+        for b, (rb, wb) in enumerate(want):
+            for a in range(b):
+                ra, wa = want[a]
+                if (wa & (rb | wb)) or (ra & wb):
+                    assert a in reach[b], f"launches {a} and {b} touch {(wa & (rb | wb)) | (ra & wb)} unordered"
+        if streams == 1:
+            assert used == 1
+    finally:
+        B.mdcnn_net_destroy(net)
+        for b in bufs:
+            B.mdcnn_destroy_buffer(b)
+
+
+def test_streams_are_used_where_the_network_has_branches():
+    used = {}
+    for name in ("resnet", "hrnet_full", "cnn5"):
+        net, bufs = host_net(NETS[name]())
+        used[name] = (B.mdcnn_frame_plan(net, 0)[2], B.mdcnn_frame_plan(net, 4)[2])
+        B.mdcnn_net_destroy(net)
+        for b in bufs:
+            B.mdcnn_destroy_buffer(b)
+    assert used["cnn5"] == (1, 1)                  # a chain
+    assert used["resnet"][0] == 1 and used["resnet"][1] > 1      # three projection branches do not pay for the waits
+    assert used["hrnet_full"] == (4, 4)            # four branches
