@@ -54,9 +54,6 @@ def parse():
     ap.add_argument("--streams", type=int, default=8,
                     help="after the headline run, the same workload as a batch of this many independent streams "
                          "(mdcnn_frame_batch; reported under \"batched\"); 0 disables it")
-    ap.add_argument("--graph", action="store_true",
-                    help="mdcnn_frame replays a recorded HIP graph of the frame (on a created stream: the legacy default "
-                         "stream cannot be recorded); the instrumented pass still uses ordinary launches")
     ap.add_argument("--opt", action="append", default=[], metavar="ID=VALUE",
                     help="library tuning option (mdcnn_set_option), e.g. --opt 6=0 switches the halo-staged kernel off")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -233,9 +230,6 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
 
-    if a.graph:
-        torch.cuda.set_stream(torch.cuda.Stream())
-        B.mdcnn_set_option(B.MDCNN_OPT_GRAPH, 1)
     cfg = a.config
     net = build_net(cfg, **({"pool_stem": True} if a.pool_stem and cfg == 3 else {}))
     seq = build_sequence(cfg, **({"density": a.density} if cfg == 5 else {"tile": 16} if a.pool_stem and cfg == 3 else {}))
@@ -378,7 +372,6 @@ def main():
         "config": {"workload": f"config {cfg}: {net.name}, {T}-frame seeded moving-camera sequence replayed cyclically"
                                + (", max-pooling stem" if a.pool_stem and cfg == 3 else "")
                                + (f", frames cropped to a wandering box of {crops[1][2]}x{crops[1][3]} of {net.H // net.total_stride}x{net.W // net.total_stride} tiles" if crops is not None else "")
-                               + (", frames replayed as a recorded HIP graph" if a.graph else "")
                                + (", library dense mode" if a.dense else "")
                                + (f", density {a.density}" if cfg == 5 else ""),
                    "input": [net.H, net.W, net.sites[0].C], "sites": len(net.sites), "edges": len(net.edges),

@@ -317,7 +317,7 @@ typedef enum {
                              /* residual skip (identity edge) instead of a launch of its own; */
                              /* such an edge then adds nothing to the compute-list statistics  */
                              /* of its destination.  0: one launch per edge                  */
-    MDCNN_OPT_STREAMS = 9,   /* 2..4: mdcnn_frame, mdcnn_frame_crop and mdcnn_frame_batch put       */
+    MDCNN_OPT_STREAMS = 9    /* 2..4: mdcnn_frame, mdcnn_frame_crop and mdcnn_frame_batch put       */
                              /* independent branches of the network on up to this many streams:     */
                              /* the caller's plus the library's own (per host thread, default     */
                              /* priority, created on first use).  The caller's stream forks into  */
@@ -328,14 +328,6 @@ typedef enum {
                              /* network has parallel branches that shorten a frame by a fifth or   */
                              /* more (counted in launches, a wait for another stream as one), else */
                              /* the caller's stream only                                           */
-    MDCNN_OPT_GRAPH = 10     /* 1: mdcnn_frame records the launches of a frame as a HIP graph the   */
-                             /* second time it runs on a network and replays it afterwards; only    */
-                             /* the arguments of the initialisation launches are set per frame (the */
-                             /* other launches read ring origins, frame, mask and output pointers   */
-                             /* from the sites' memory).  Results do not change by a bit.  Not used */
-                             /* for crops, batches, in profiling mode, while the caller's stream is */
-                             /* being captured, or if recording is refused (the legacy default     */
-                             /* stream cannot be captured).  0 (default): ordinary launches         */
 } mdcnn_option;
 mdcnn_status mdcnn_set_option(int option, int value);
 

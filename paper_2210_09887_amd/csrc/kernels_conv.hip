@@ -34,10 +34,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 __device__ __forceinline__ int wrapc(int v, int n) { return v >= n ? v - n : v; }
 
-// Ring origins: from the arguments, or (use_vars, block-uniform) from the sites' memory.
 __device__ __forceinline__ size_t pdst_offset(const EdgeDev& e, int wy, int wx) {
-    const int oy = e.use_vars ? vars_of(e.dcounters)->p_oy : e.p_oy, ox = e.use_vars ? vars_of(e.dcounters)->p_ox : e.p_ox;
-    int py = wrapc(oy + wy, e.Hp), px = wrapc(ox + wx, e.Wp);
+    int py = wrapc(e.p_oy + wy, e.Hp), px = wrapc(e.p_ox + wx, e.Wp);
     return ((size_t)py * e.Wp + px) * e.Cout;
 }
 
@@ -1151,8 +1149,7 @@ __global__ __launch_bounds__(256) void k_pool(EdgeBatch eb) {
             for (int jx = 0; jx < e.k; ++jx) {
                 const int iy = oy * e.stride - e.pad + jy, ix = ox * e.stride - e.pad + jx;
                 if (iy < 0 || iy >= e.sH || ix < 0 || ix >= e.sW) continue;
-                const int ay = wrapc((e.use_vars ? vars_of(e.scounters)->a_oy : e.s_aoy) + iy, e.sH),
-                          ax = wrapc((e.use_vars ? vars_of(e.scounters)->a_ox : e.s_aox) + ix, e.sW);
+                const int ay = wrapc(e.s_aoy + iy, e.sH), ax = wrapc(e.s_aox + ix, e.sW);
                 float v[VEC];
                 PoolVec<T, VEC>::load((const T*)e.sA + ((size_t)ay * e.sW + ax) * e.Cin + c0, v);
 #pragma unroll
@@ -1161,8 +1158,7 @@ __global__ __launch_bounds__(256) void k_pool(EdgeBatch eb) {
         // op == 2: the reset of a pixel zeroed its previous output as well (sites with crops, where a
         // reset pixel may be pooled in a later frame than the reset)
         const bool fresh = e.op == 1 && (e.dflags[oy * e.dW + ox] & kFlagN);
-        const int yy = wrapc((e.use_vars ? vars_of(e.dcounters)->a_oy : e.d_aoy) + oy, e.dH),
-                  yx = wrapc((e.use_vars ? vars_of(e.dcounters)->a_ox : e.d_aox) + ox, e.dW);
+        const int yy = wrapc(e.d_aoy + oy, e.dH), yx = wrapc(e.d_aox + ox, e.dW);
         T* prev = (T*)e.dY + ((size_t)yy * e.dW + yx) * e.Cout + c0;
         T* pp = (T*)e.P + pdst_offset(e, s_wy[ent], s_wx[ent]) + c0;
         float pv[VEC], pd[VEC];

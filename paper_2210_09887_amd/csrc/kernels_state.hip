@@ -37,21 +37,17 @@ template <> struct V16<f16> {
     }
 };
 
-// Ring origins: from the arguments, or (use_vars, block-uniform) from the site's memory.
 __device__ __forceinline__ size_t a_offset(const SiteDev& s, int vy, int vx) {
-    const int oy = s.use_vars ? vars_of(s.counters)->a_oy : s.a_oy, ox = s.use_vars ? vars_of(s.counters)->a_ox : s.a_ox;
-    int ay = wrap(oy + vy, s.H), ax = wrap(ox + vx, s.W);
+    int ay = wrap(s.a_oy + vy, s.H), ax = wrap(s.a_ox + vx, s.W);
     return ((size_t)ay * s.W + ax) * s.C;
 }
 // wy, wx: padded-window coordinates
 __device__ __forceinline__ size_t p_offset(const SiteDev& s, int wy, int wx) {
-    const int oy = s.use_vars ? vars_of(s.counters)->p_oy : s.p_oy, ox = s.use_vars ? vars_of(s.counters)->p_ox : s.p_ox;
-    int py = wrap(oy + wy, s.Hp), px = wrap(ox + wx, s.Wp);
+    int py = wrap(s.p_oy + wy, s.Hp), px = wrap(s.p_ox + wx, s.Wp);
     return ((size_t)py * s.Wp + px) * s.C;
 }
 __device__ __forceinline__ size_t skip_offset(const SkipDev& k, int vy, int vx, int C) {
-    const int oy = k.vars ? k.vars->p_oy : k.p_oy, ox = k.vars ? k.vars->p_ox : k.p_ox;
-    int py = wrap(oy + vy + k.by0, k.Hp), px = wrap(ox + vx + k.bx0, k.Wp);
+    int py = wrap(k.p_oy + vy + k.by0, k.Hp), px = wrap(k.p_ox + vx + k.bx0, k.Wp);
     return ((size_t)py * k.Wp + px) * C;
 }
 
@@ -178,11 +174,6 @@ __global__ __launch_bounds__(256) void k_shift_fill(FillBatch fb) {
     const unsigned lb = blockIdx.x - j.block_begin;
     if (lb == 0 && j.reset_counters && (int)threadIdx.x < (j.reset_counters == 2 ? kNumCounters : kNumPerFrame))
         j.counters[threadIdx.x] = 0;
-    if (lb == 0 && threadIdx.x == 0) {                     // the site's state of this frame, for launches that read it from here
-        SiteVars* v = const_cast<SiteVars*>(vars_of(j.counters));
-        v->a_oy = j.a_oy; v->a_ox = j.a_ox; v->p_oy = j.p_oy; v->p_ox = j.p_ox;
-        v->io = j.io; v->forced = j.forced;
-    }
     if (lb == 0 && j.reset_counters == 2) {                // first reset: clear the per-segment running sums
         for (int i = threadIdx.x; i < j.n_lacc; i += 256) { j.lacc[i] = 0ull; j.lcnt[i] = 0; }
         for (int i = threadIdx.x; i < j.n_cacc; i += 256) { j.cacc[i] = 0ull; j.ccnt[i] = 0; }
@@ -194,14 +185,11 @@ __global__ __launch_bounds__(256) void k_shift_fill(FillBatch fb) {
     }
 }
 
-// grid = 0: as many blocks as the jobs need.  A recorded launch is given the largest grid its
-// jobs can ever need; blocks beyond the work of the last job find nothing to do.
-hipError_t launch_shift_fill(const FillBatch& fb, unsigned grid, hipStream_t st) {
+hipError_t launch_shift_fill(const FillBatch& fb, hipStream_t st) {
     if (fb.n == 0 || fb.total_blocks == 0) return hipSuccess;
-    k_shift_fill<<<dim3(grid > fb.total_blocks ? grid : fb.total_blocks), dim3(256), 0, st>>>(fb);
+    k_shift_fill<<<dim3(fb.total_blocks), dim3(256), 0, st>>>(fb);
     return hipGetLastError();
 }
-const void* shift_fill_function() { return reinterpret_cast<const void*>(&k_shift_fill); }
 
 // ---------------------------------------------------------------------------
 // Step 1 of a site: delta, truncation, update mask.
@@ -240,8 +228,8 @@ template <typename T, int G, int CH>
 __global__ __launch_bounds__(256) void k_step1(Step1Batch bt) {
     const SiteDev& s = bt.s[blockIdx.z];
     const SkipDev& skip = bt.skip[blockIdx.z];
-    const T* __restrict__ X = (const T*)(s.use_vars ? vars_of(s.counters)->io : bt.X[blockIdx.z]);
-    const uint8_t* __restrict__ forced = s.use_vars ? vars_of(s.counters)->forced : bt.forced[blockIdx.z];
+    const T* __restrict__ X = (const T*)bt.X[blockIdx.z];
+    const uint8_t* __restrict__ forced = bt.forced[blockIdx.z];
     constexpr int VEC = V16<T>::N;
     constexpr int PPB = 256 / G;
     const int tid = threadIdx.x;
@@ -324,8 +312,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void k_step1_scalar(Step1Batch bt) {
     const SiteDev& s = bt.s[blockIdx.z];
     const SkipDev& skip = bt.skip[blockIdx.z];
-    const T* __restrict__ X = (const T*)(s.use_vars ? vars_of(s.counters)->io : bt.X[blockIdx.z]);
-    const uint8_t* __restrict__ forced = s.use_vars ? vars_of(s.counters)->forced : bt.forced[blockIdx.z];
+    const T* __restrict__ X = (const T*)bt.X[blockIdx.z];
+    const uint8_t* __restrict__ forced = bt.forced[blockIdx.z];
     const int tid = threadIdx.x;
     const int pix = blockIdx.x * 256 + tid;
     const int HW = s.H * s.W;
@@ -547,7 +535,6 @@ hipError_t launch_input_mask(const MaskJob& j, hipStream_t st) {
 // ---------------------------------------------------------------------------
 template <typename T, int VEC>
 __global__ __launch_bounds__(256) void k_read_tensor(SiteDev s, int what, T* __restrict__ dst) {
-    if (s.use_vars) dst = (T*)const_cast<void*>(vars_of(s.counters)->io);      // the readout of a recorded frame
     const int chunks = s.C / VEC;
     const bool win = what == MDCNN_VIEW_P;
     const bool crop = what == MDCNN_VIEW_CROP_OUT;         // f(P) over the crop, in crop order

@@ -18,8 +18,6 @@ thread_local char g_err[512] = "";
 int g_conv_path = 0;
 int g_fuse_skip = 1;      // mdcnn_frame: residual skips are added by the step-1 kernel of their source
 int g_profile = 0;
-int g_graph = 0;          // mdcnn_frame: 1 replays a recorded HIP graph of the frame where it can
-int g_epoch = 0;          // bumped by every option change: recorded graphs are made anew
 int g_streams = 0;        // mdcnn_frame: independent branches of the network go to up to this many streams; 0: decide per network
 
 // Profiling mode: every kernel launch is bracketed by a pair of events on its
@@ -104,7 +102,7 @@ void make_layout(const mdcnn_buffer_desc& d, Layout& L) {
     L.clist = take(hasP ? nseg_c * kSegPixels * 4 : 0);
     L.ccnt = take(hasP ? nseg_c * 4 : 0);
     L.cacc = take(hasP ? nseg_c * 8 : 0);
-    L.counters = take(kNumCounters * 4 + sizeof(SiteVars));   // the per-frame state sits right behind the counters
+    L.counters = take(kNumCounters * 4);
     L.Y = take(d.pool_prev ? (size_t)d.H * d.W * d.C * e : 0);
     L.S = take(d.crops && hasA ? (size_t)d.H * d.W : 0);
     L.total = off;
@@ -140,15 +138,6 @@ struct mdcnn_net {
     std::vector<mdcnn_conv_desc> edges;
     size_t out_bytes;
     Plan plan;
-    // recorded frame (MDCNN_OPT_GRAPH): the launches of one frame with arguments that stay valid,
-    // except those of the initialisation launches, which are set anew for every frame
-    hipGraphExec_t gexec = nullptr;
-    std::vector<hipGraphNode_t> gfill;         // the initialisation launches, in launch order
-    std::vector<unsigned> gfill_grid;
-    int gkey = -1;
-    int frames_seen = 0;                       // the first frame is never recorded: it sets up kernel attributes
-    bool graph_failed = false;                 // recording was refused once (e.g. on the legacy default stream)
-    std::vector<hipGraph_t> ggraph_keep;       // the graphs the node handles above belong to
 };
 
 namespace {
@@ -291,12 +280,11 @@ struct Sched {
 
 mdcnn_status do_forward(int n, mdcnn_buffer* const* ins, const void* const* frames, const uint8_t* const* forced,
                         const mdcnn_conv_desc* const* edges, mdcnn_buffer* const* const* outs, int n_edges,
-                        hipStream_t st, int fuse_skip = -1, Sched* sc = nullptr, bool use_vars = false) {
+                        hipStream_t st, int fuse_skip = -1, Sched* sc = nullptr) {
     static thread_local Step1Batch sb;                     // 3.4 KiB each: kept off the stack
     static thread_local EdgeBatch eb;
     for (int b = 0; b < n; ++b) {
         sb.s[b] = ins[b]->dev;
-        sb.s[b].use_vars = use_vars;
         sb.X[b] = frames ? frames[b] : nullptr;
         sb.forced[b] = forced ? forced[b] : nullptr;
         sb.skip[b] = SkipDev{};
@@ -307,7 +295,6 @@ mdcnn_status do_forward(int n, mdcnn_buffer* const* ins, const void* const* fram
             k.dflags = d->d.kind == MDCNN_SITE_OUTPUT ? nullptr : d->dev.flags;
             k.Hp = d->L.Hp; k.Wp = d->L.Wp; k.by0 = d->d.border[0]; k.bx0 = d->d.border[2];
             k.p_oy = d->dev.p_oy; k.p_ox = d->dev.p_ox;
-            k.vars = use_vars ? vars_of(d->dev.counters) : nullptr;
         }
     }
     if (sc) st = sc->begin();
@@ -353,7 +340,6 @@ mdcnn_status do_forward(int n, mdcnn_buffer* const* ins, const void* const* fram
         if (i == fuse_skip) continue;
         for (int b = 0; b < n; ++b) {
             eb.d[b] = make_edge(ins[b], outs[b][i], edges[b][i]);
-            eb.d[b].use_vars = use_vars;
             if (first) with_source_list(eb.d[b], ins[b]);
         }
         first = false;
@@ -506,125 +492,33 @@ hipError_t aux_prepare(int streams, size_t events) {
     return hipSuccess;
 }
 
-// What a frame hands to the sites for launches that read their per-frame state from device
-// memory: the frame and its forced mask (INPUT site), the readout destinations (OUTPUT sites,
-// back to back in site order).  nullptr: not known at the time of the shift.
-struct FrameIO { const void* frame; const uint8_t* forced; char* out; };
-
-// The buffer manager's part of a camera shift: decides on a full reset, moves the host-side
-// state of every buffer and returns the initialisation jobs, grouped into launches.
-mdcnn_status shift_jobs(mdcnn_buffer* const* bufs, int n, int dty, int dtx, const FrameIO* io, std::vector<FillBatch>& fbs,
-                        int* did_full_reset) {
-    if (!bufs || n < 1) return fail(MDCNN_ERR_NULL, "no buffers");
-    for (int i = 0; i < n; ++i) {
-        if (!bufs[i]) return fail(MDCNN_ERR_NULL, "buffer %d is NULL", i);
-        const mdcnn_buffer *a = bufs[0], *b = bufs[i];
-        if (a->fresh != b->fresh || a->r_up != b->r_up || a->r_down != b->r_down || a->r_left != b->r_left ||
-            a->r_right != b->r_right)
-            return fail(MDCNN_ERR_STATE, "buffer %d has a different shift history than buffer 0", i);
-    }
-    const mdcnn_buffer* f = bufs[0];
-    bool full = f->fresh;
-    full |= (dtx > 0 && f->r_right) || (dtx < 0 && f->r_left) || (dty > 0 && f->r_down) || (dty < 0 && f->r_up);
-    for (int i = 0; i < n; ++i) {
-        const mdcnn_buffer_desc& d = bufs[i]->d;
-        const long long sy = (long long)dty * d.tile, sx = (long long)dtx * d.tile;
-        full |= (sy >= d.H || -sy >= d.H || sx >= d.W || -sx >= d.W);
-    }
-    FillBatch fb{};
-    auto flush = [&]() {
-        fbs.push_back(fb);
-        fb.n = 0;
-        fb.total_blocks = 0;
-    };
-    char* out = io ? io->out : nullptr;
-    for (int i = 0; i < n; ++i) {
-        mdcnn_buffer* b = bufs[i];
-        const mdcnn_buffer_desc& d = b->d;
-        const long long sy = (long long)dty * d.tile, sx = (long long)dtx * d.tile;
-        b->gy += sy;
-        b->gx += sx;
-        refresh_origins(b);
-        FillJob j{};
-        j.A = b->dev.A; j.P = b->dev.P; j.flags = b->dev.flags; j.bias = b->dev.bias; j.counters = b->dev.counters;
-        j.lacc = b->dev.lacc; j.cacc = b->dev.cacc; j.lcnt = b->dev.lcnt; j.ccnt = b->dev.ccnt;
-        j.n_lacc = 2 * b->L.nseg_l; j.n_cacc = b->L.nseg_c;
-        j.s_off = b->dev.s_off;
-        j.y_off = d.crops && d.pool_prev ? (unsigned)((b->L.Y - b->L.A) / 256) : 0u;
-        j.H = d.H; j.W = d.W; j.C = d.C; j.Hp = b->L.Hp; j.Wp = b->L.Wp;
-        j.a_oy = b->dev.a_oy; j.a_ox = b->dev.a_ox; j.p_oy = b->dev.p_oy; j.p_ox = b->dev.p_ox;
-        j.dtype = d.dtype;
-        if (io && d.kind == MDCNN_SITE_INPUT) { j.io = io->frame; j.forced = io->forced; }
-        if (io && d.kind == MDCNN_SITE_OUTPUT) { j.io = out; out += (size_t)d.H * d.W * d.C * esize(d.dtype); }
-        if (!full) {
-            // the old window, expressed in coordinates of the new one, is shifted by (-sy, -sx)
-            auto keep = [](int ext, long long s, int& lo, int& hi) {   // |s| < ext here
-                lo = -s > 0 ? (int)-s : 0;
-                hi = ext - s < ext ? (int)(ext - s) : ext;
-                if (hi < lo) hi = lo;
-            };
-            keep(j.Hp, sy, j.py0, j.py1);
-            keep(j.Wp, sx, j.px0, j.px1);
-            keep(j.H, sy, j.ay0, j.ay1);
-            keep(j.W, sx, j.ax0, j.ax1);
-        }
-        auto outside = [](int Hn, int Wn, int y0, int y1, int x0, int x1) {
-            return (y0 + (Hn - y1)) * Wn + (y1 - y0) * (x0 + (Wn - x1));
-        };
-        j.nP = j.P ? outside(j.Hp, j.Wp, j.py0, j.py1, j.px0, j.px1) : 0;
-        j.nA = j.A ? outside(j.H, j.W, j.ay0, j.ay1, j.ax0, j.ax1) : 0;
-        j.reset_counters = b->fresh ? 2 : 1;             // per-frame counters start at zero every frame
-        const int vec = d.dtype == MDCNN_F16 ? 8 : 4;
-        const long long items = (long long)(j.nP + j.nA) * (d.C % vec == 0 ? d.C / vec : d.C);
-        long long blocks = (items + kFillItemsPerBlock - 1) / kFillItemsPerBlock;
-        if (blocks < 1) blocks = 1;
-        j.block_begin = fb.total_blocks;
-        fb.j[fb.n++] = j;
-        fb.total_blocks += (unsigned)blocks;
-        if (fb.n == kMaxFillJobs) flush();
-        if (full) {
-            b->r_up = b->r_down = b->r_left = b->r_right = false;
-            b->fresh = false;
-        } else {
-            // growing in one direction overwrites the stash of the opposite side
-            if (dtx > 0) b->r_left = true;
-            if (dtx < 0) b->r_right = true;
-            if (dty > 0) b->r_up = true;
-            if (dty < 0) b->r_down = true;
-        }
-    }
-    if (fb.n) flush();
-    if (did_full_reset) *did_full_reset = full ? 1 : 0;
-    return MDCNN_OK;
-}
-
 size_t crop_pixels(const mdcnn_buffer* b) {                // sites without crops: the view
     if (!b->d.crops) return (size_t)b->d.H * b->d.W;
     return (size_t)(b->dev.cy1() - b->dev.cy0()) * (size_t)(b->dev.cx1() - b->dev.cx0());
 }
 bool whole_view(const mdcnn_buffer* b) { return crop_pixels(b) == (size_t)b->d.H * b->d.W; }
 
-// The launches of one frame after the camera shift: forward over all non-terminal sites on the
-// streams of the plan, then the readouts.  use_vars: the launches take origins, frame, mask and
-// readout pointers from the sites' memory (written by this frame's initialisation launches).
-void ensure_plan(mdcnn_net* net) {
-    const int key = g_streams * 2 + g_fuse_skip;
-    if (net->plan.key != key) {
-        choose_plan(net, g_streams, net->plan);
-        net->plan.key = key;
+// Shift, forward over all non-terminal sites, readout: for n streams at once.
+mdcnn_status frame_batch(mdcnn_net* const* nets, int n, const void* const* frames, const uint8_t* const* forced,
+                         const int* dty, const int* dtx, void* const* outs_dev, void* stream, int* did_full_reset) {
+    hipStream_t st = (hipStream_t)stream;
+    for (int b = 0; b < n; ++b) {
+        mdcnn_status rc = mdcnn_shift_camera(nets[b]->sites.data(), (int)nets[b]->sites.size(), dty[b], dtx[b], stream,
+                                             did_full_reset ? did_full_reset + b : nullptr);
+        if (rc) return rc;
     }
-}
-
-mdcnn_status frame_launches(mdcnn_net* const* nets, int n, const void* const* frames, const uint8_t* const* forced,
-                            void* const* outs_dev, hipStream_t st, bool use_vars, bool one_stream = false) {
     mdcnn_net* net = nets[0];
     const int n_edges = (int)net->edges.size();
     // independent branches of the network on streams of their own; the caller's stream forks into
     // them after the shift and joins them before the readout, so to the caller the call is in
     // stream order as before
     Sched sched, *sc = nullptr;
-    if (g_streams != 1 && !one_stream) {
-        ensure_plan(net);
+    if (g_streams != 1) {
+        const int key = g_streams * 2 + g_fuse_skip;
+        if (net->plan.key != key) {
+            choose_plan(net, g_streams, net->plan);
+            net->plan.key = key;
+        }
         if (net->plan.streams > 1) {
             const size_t n_nodes = net->plan.nodes.size();
             hipError_t err = aux_prepare(net->plan.streams, n_nodes + kMaxStreams);
@@ -670,8 +564,11 @@ mdcnn_status frame_launches(mdcnn_net* const* nets, int n, const void* const* fr
             for (int e = e0; e < e1; ++e) outs_flat[(size_t)b * ne + (e - e0)] = nets[b]->sites[net->edst[e]];
             outs[b] = outs_flat.data() + (size_t)b * ne;
         }
+        // a residual skip is added by the step-1 kernel of its source; its place in the
+        // order of the producers of its destination stays the same as long as no other
+        // edge of this call goes to the same destination before it
         const int fuse = fused_skip(net, e0, e1);
-        mdcnn_status rc = do_forward(n, ins, i == 0 ? frames : nullptr, i == 0 ? forced : nullptr, edges, outs, ne, st, fuse, sc, use_vars);
+        mdcnn_status rc = do_forward(n, ins, i == 0 ? frames : nullptr, i == 0 ? forced : nullptr, edges, outs, ne, st, fuse, sc);
         if (rc) return rc;
         e0 = e1;
     }
@@ -684,191 +581,12 @@ mdcnn_status frame_launches(mdcnn_net* const* nets, int n, const void* const* fr
         char* o = (char*)outs_dev[b];
         for (mdcnn_buffer* s : nets[b]->sites) {
             if (s->d.kind != MDCNN_SITE_OUTPUT) continue;
-            SiteDev dev = s->dev;
-            dev.use_vars = use_vars;
-            hipError_t err = timed(kClsReadout, st, [&] { return launch_read_view(dev, s->d.crops ? MDCNN_VIEW_CROP_OUT : MDCNN_VIEW_OUT, o, st); });
+            hipError_t err = timed(kClsReadout, st, [&] { return launch_read_view(s->dev, s->d.crops ? MDCNN_VIEW_CROP_OUT : MDCNN_VIEW_OUT, o, st); });
             if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "readout launch: %s", hipGetErrorString(err));
             o += crop_pixels(s) * s->d.C * esize(s->d.dtype);
         }
     }
     return MDCNN_OK;
-}
-
-void drop_graph(mdcnn_net* net) {
-    if (net->gexec) (void)hipGraphExecDestroy(net->gexec);
-    net->gexec = nullptr;
-    net->gfill.clear();
-    net->gfill_grid.clear();
-    net->gkey = -1;
-}
-
-// Blocks the initialisation jobs of `fb` can need at most (a full reset of every site in it).
-unsigned max_fill_blocks(const FillBatch& fb) {
-    unsigned total = 0;
-    for (int i = 0; i < fb.n; ++i) {
-        const FillJob& j = fb.j[i];
-        const int vec = j.dtype == MDCNN_F16 ? 8 : 4;
-        const long long pix = (j.P ? (long long)j.Hp * j.Wp : 0) + (j.A ? (long long)j.H * j.W : 0);
-        const long long items = pix * (j.C % vec == 0 ? j.C / vec : j.C);
-        const long long blocks = (items + kFillItemsPerBlock - 1) / kFillItemsPerBlock;
-        total += (unsigned)(blocks < 1 ? 1 : blocks);
-    }
-    return total;
-}
-
-// One frame of one stream as a recorded graph.  The first such frame of a network records it
-// (the launches are captured from the caller's stream, the library's other streams included);
-// later frames set the arguments of the initialisation launches - they carry everything that
-// changes from frame to frame - and replay.  Returns false if the frame has to be launched the
-// ordinary way (recording refused); *rc is the status if it returns true.
-bool frame_graph(mdcnn_net* net, const std::vector<FillBatch>& fbs, const void* frame, const uint8_t* forced, void* out_dev,
-                 hipStream_t st, mdcnn_status* rc) {
-    *rc = MDCNN_OK;
-    const int key = g_epoch;
-    if (net->gexec && (net->gkey != key || net->gfill.size() != fbs.size())) drop_graph(net);
-    if (!net->gexec) {
-        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-        if (hipStreamIsCapturing(st, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) { (void)hipGetLastError(); return false; }
-        if (hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal) != hipSuccess) {
-            (void)hipGetLastError();
-            net->graph_failed = true;                       // e.g. the legacy default stream cannot be captured
-            return false;
-        }
-        // recorded on the caller's stream alone, in program order: a chain of kernel nodes
-        std::vector<unsigned> grids;
-        hipError_t err = hipSuccess;
-        for (const FillBatch& fb : fbs) {
-            grids.push_back(max_fill_blocks(fb));
-            if (err == hipSuccess) err = launch_shift_fill(fb, grids.back(), st);
-        }
-        mdcnn_status lrc = MDCNN_OK;
-        if (err == hipSuccess) lrc = frame_launches(&net, 1, &frame, &forced, &out_dev, st, true, true);
-        hipGraph_t graph = nullptr;
-        const hipError_t end = hipStreamEndCapture(st, &graph);         // always ended, whatever happened in between
-        auto give_up = [&](hipGraph_t a, hipGraph_t b, hipGraphExec_t ex) {
-            if (ex) (void)hipGraphExecDestroy(ex);
-            if (a) (void)hipGraphDestroy(a);
-            if (b) (void)hipGraphDestroy(b);
-            (void)hipGetLastError();
-            net->graph_failed = true;
-            return false;                                   // nothing has run yet: the frame is launched the ordinary way
-        };
-        if (err != hipSuccess || lrc != MDCNN_OK || end != hipSuccess || !graph) return give_up(graph, nullptr, nullptr);
-        // the nodes in launch order: follow the chain from its root
-        std::vector<hipGraphNode_t> order;
-        {
-            size_t nr = 0;
-            hipGraphNode_t cur = nullptr;
-            if (hipGraphGetRootNodes(graph, nullptr, &nr) != hipSuccess || nr != 1) return give_up(graph, nullptr, nullptr);
-            if (hipGraphGetRootNodes(graph, &cur, &nr) != hipSuccess) return give_up(graph, nullptr, nullptr);
-            size_t total = 0;
-            if (hipGraphGetNodes(graph, nullptr, &total) != hipSuccess) return give_up(graph, nullptr, nullptr);
-            while (cur && order.size() < total) {
-                hipGraphNodeType ty;
-                if (hipGraphNodeGetType(cur, &ty) != hipSuccess || ty != hipGraphNodeTypeKernel) return give_up(graph, nullptr, nullptr);
-                order.push_back(cur);
-                size_t nd = 0;
-                if (hipGraphNodeGetDependentNodes(cur, nullptr, &nd) != hipSuccess || nd > 1) return give_up(graph, nullptr, nullptr);
-                hipGraphNode_t next = nullptr;
-                if (nd == 1 && hipGraphNodeGetDependentNodes(cur, &next, &nd) != hipSuccess) return give_up(graph, nullptr, nullptr);
-                cur = next;
-            }
-            if (order.size() != total) return give_up(graph, nullptr, nullptr);
-        }
-        ensure_plan(net);
-        const Plan& plan = net->plan;
-        const size_t nf = fbs.size(), np = g_streams == 1 ? 0 : plan.nodes.size();
-        int n_out = 0;
-        for (const mdcnn_buffer* b : net->sites) n_out += b->d.kind == MDCNN_SITE_OUTPUT;
-        hipGraph_t use = graph;                             // the graph that is instantiated and owns the node handles
-        std::vector<hipGraphNode_t> fill(order.begin(), order.begin() + (order.size() >= nf ? nf : 0));
-        if (g_streams != 1 && plan.streams > 1) {
-            // the same launches with the dependencies of the plan instead of a chain: launches of one
-            // stream of the plan in a row, the waits of the plan, everything after the initialisation
-            // launches, the readouts after the last launch of every stream
-            if (order.size() != nf + np + (size_t)n_out) return give_up(graph, nullptr, nullptr);
-            hipGraph_t par = nullptr;
-            if (hipGraphCreate(&par, 0) != hipSuccess) return give_up(graph, nullptr, nullptr);
-            std::vector<hipGraphNode_t> made(order.size(), nullptr);
-            hipGraphNode_t tail[kMaxStreams] = {};
-            for (size_t i = 0; i < order.size(); ++i) {
-                hipKernelNodeParams kp{};
-                if (hipGraphKernelNodeGetParams(order[i], &kp) != hipSuccess) return give_up(graph, par, nullptr);
-                std::vector<hipGraphNode_t> deps;
-                if (i < nf) {
-                    if (i) deps.push_back(made[i - 1]);
-                } else if (i < nf + np) {
-                    const PlanNode& nd = plan.nodes[i - nf];
-                    deps.push_back(tail[nd.stream] ? tail[nd.stream] : made[nf - 1]);
-                    for (int w : nd.wait) deps.push_back(made[nf + w]);
-                } else {
-                    for (int k = 0; k < plan.streams; ++k)
-                        if (tail[k]) deps.push_back(tail[k]);
-                }
-                if (hipGraphAddKernelNode(&made[i], par, deps.data(), deps.size(), &kp) != hipSuccess) return give_up(graph, par, nullptr);
-                if (i >= nf && i < nf + np) tail[plan.nodes[i - nf].stream] = made[i];
-            }
-            (void)hipGraphDestroy(graph);
-            graph = nullptr;
-            use = par;
-            fill.assign(made.begin(), made.begin() + nf);
-        }
-        if (fill.size() != nf) return give_up(use, nullptr, nullptr);
-        hipGraphExec_t exec = nullptr;
-        if (hipGraphInstantiate(&exec, use, nullptr, nullptr, 0) != hipSuccess || !exec) return give_up(use, nullptr, exec);
-        hipGraph_t graph_kept = use;
-        // the executable graph keeps node handles of `graph` valid for parameter updates only while
-        // `graph` lives: it is kept with the network
-        net->gexec = exec;
-        net->gfill = fill;
-        net->gfill_grid = grids;
-        net->gkey = key;
-        net->ggraph_keep.push_back(graph_kept);
-    } else {
-        for (size_t q = 0; q < fbs.size(); ++q) {
-            FillBatch fb = fbs[q];
-            void* args[1] = {&fb};
-            hipKernelNodeParams kp{};
-            kp.func = const_cast<void*>(shift_fill_function());
-            kp.gridDim = dim3(net->gfill_grid[q]);
-            kp.blockDim = dim3(256);
-            kp.sharedMemBytes = 0;
-            kp.kernelParams = args;
-            kp.extra = nullptr;
-            const hipError_t err = hipGraphExecKernelNodeSetParams(net->gexec, net->gfill[q], &kp);
-            if (err != hipSuccess) {                        // nothing has run yet: back to ordinary launches for good
-                (void)hipGetLastError();
-                drop_graph(net);
-                net->graph_failed = true;
-                return false;
-            }
-        }
-    }
-    const hipError_t err = hipGraphLaunch(net->gexec, st);
-    if (err != hipSuccess) *rc = fail(MDCNN_ERR_HIP, "replaying the recorded frame: %s", hipGetErrorString(err));
-    return true;
-}
-
-// Shift, forward over all non-terminal sites, readout: for n streams at once.
-mdcnn_status frame_batch(mdcnn_net* const* nets, int n, const void* const* frames, const uint8_t* const* forced,
-                         const int* dty, const int* dtx, void* const* outs_dev, void* stream, int* did_full_reset) {
-    hipStream_t st = (hipStream_t)stream;
-    mdcnn_net* net = nets[0];
-    const bool graph = g_graph && n == 1 && !g_profile && !net->graph_failed && net->frames_seen > 0 && !net->sites[0]->d.crops;
-    net->frames_seen += net->frames_seen < 2;
-    for (int b = 0; b < n; ++b) {
-        std::vector<FillBatch> fbs;
-        FrameIO io{frames[b], forced ? forced[b] : nullptr, (char*)outs_dev[b]};
-        mdcnn_status rc = shift_jobs(nets[b]->sites.data(), (int)nets[b]->sites.size(), dty[b], dtx[b], &io, fbs,
-                                     did_full_reset ? did_full_reset + b : nullptr);
-        if (rc) return rc;
-        if (graph && frame_graph(net, fbs, frames[0], forced ? forced[0] : nullptr, outs_dev[0], st, &rc)) return rc;
-        for (const FillBatch& fb : fbs) {
-            hipError_t err = timed(kClsShift, st, [&] { return launch_shift_fill(fb, 0, st); });
-            if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "shift launch: %s", hipGetErrorString(err));
-        }
-    }
-    return frame_launches(nets, n, frames, forced, outs_dev, st, false);
 }
 
 }  // namespace
@@ -879,8 +597,6 @@ const char* mdcnn_last_error(void) { return g_err; }
 const char* mdcnn_version(void) { return "mdcnn 0.1 (gfx950)"; }
 
 mdcnn_status mdcnn_set_option(int option, int value) {
-    ++g_epoch;                                             // recorded frames are made anew after any change
-    if (option == MDCNN_OPT_GRAPH && (value == 0 || value == 1)) { g_graph = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_CONV_PATH && value >= 0 && value <= 3) { g_conv_path = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_CONV_HALO && value >= 0 && value <= 2) { g_halo = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_STREAMS && value >= 0 && value <= kMaxStreams) { g_streams = value; return MDCNN_OK; }
@@ -990,14 +706,91 @@ mdcnn_status mdcnn_destroy_buffer(mdcnn_buffer* buf) {
 }
 
 mdcnn_status mdcnn_shift_camera(mdcnn_buffer* const* bufs, int n, int dty, int dtx, void* stream, int* did_full_reset) {
-    std::vector<FillBatch> fbs;
-    mdcnn_status rc = shift_jobs(bufs, n, dty, dtx, nullptr, fbs, did_full_reset);
-    if (rc) return rc;
+    if (!bufs || n < 1) return fail(MDCNN_ERR_NULL, "no buffers");
+    for (int i = 0; i < n; ++i) {
+        if (!bufs[i]) return fail(MDCNN_ERR_NULL, "buffer %d is NULL", i);
+        const mdcnn_buffer *a = bufs[0], *b = bufs[i];
+        if (a->fresh != b->fresh || a->r_up != b->r_up || a->r_down != b->r_down || a->r_left != b->r_left ||
+            a->r_right != b->r_right)
+            return fail(MDCNN_ERR_STATE, "buffer %d has a different shift history than buffer 0", i);
+    }
+    const mdcnn_buffer* f = bufs[0];
+    bool full = f->fresh;
+    full |= (dtx > 0 && f->r_right) || (dtx < 0 && f->r_left) || (dty > 0 && f->r_down) || (dty < 0 && f->r_up);
+    for (int i = 0; i < n; ++i) {
+        const mdcnn_buffer_desc& d = bufs[i]->d;
+        const long long sy = (long long)dty * d.tile, sx = (long long)dtx * d.tile;
+        full |= (sy >= d.H || -sy >= d.H || sx >= d.W || -sx >= d.W);
+    }
     hipStream_t st = (hipStream_t)stream;
-    for (const FillBatch& fb : fbs) {
-        hipError_t err = timed(kClsShift, st, [&] { return launch_shift_fill(fb, 0, st); });
+    FillBatch fb{};
+    auto flush = [&]() -> hipError_t {
+        hipError_t err = timed(kClsShift, st, [&] { return launch_shift_fill(fb, st); });
+        fb.n = 0;
+        fb.total_blocks = 0;
+        return err;
+    };
+    for (int i = 0; i < n; ++i) {
+        mdcnn_buffer* b = bufs[i];
+        const mdcnn_buffer_desc& d = b->d;
+        const long long sy = (long long)dty * d.tile, sx = (long long)dtx * d.tile;
+        b->gy += sy;
+        b->gx += sx;
+        refresh_origins(b);
+        FillJob j{};
+        j.A = b->dev.A; j.P = b->dev.P; j.flags = b->dev.flags; j.bias = b->dev.bias; j.counters = b->dev.counters;
+        j.lacc = b->dev.lacc; j.cacc = b->dev.cacc; j.lcnt = b->dev.lcnt; j.ccnt = b->dev.ccnt;
+        j.n_lacc = 2 * b->L.nseg_l; j.n_cacc = b->L.nseg_c;
+        j.s_off = b->dev.s_off;
+        j.y_off = d.crops && d.pool_prev ? (unsigned)((b->L.Y - b->L.A) / 256) : 0u;
+        j.H = d.H; j.W = d.W; j.C = d.C; j.Hp = b->L.Hp; j.Wp = b->L.Wp;
+        j.a_oy = b->dev.a_oy; j.a_ox = b->dev.a_ox; j.p_oy = b->dev.p_oy; j.p_ox = b->dev.p_ox;
+        j.dtype = d.dtype;
+        if (!full) {
+            // the old window, expressed in coordinates of the new one, is shifted by (-sy, -sx)
+            auto keep = [](int ext, long long s, int& lo, int& hi) {   // |s| < ext here
+                lo = -s > 0 ? (int)-s : 0;
+                hi = ext - s < ext ? (int)(ext - s) : ext;
+                if (hi < lo) hi = lo;
+            };
+            keep(j.Hp, sy, j.py0, j.py1);
+            keep(j.Wp, sx, j.px0, j.px1);
+            keep(j.H, sy, j.ay0, j.ay1);
+            keep(j.W, sx, j.ax0, j.ax1);
+        }
+        auto outside = [](int Hn, int Wn, int y0, int y1, int x0, int x1) {
+            return (y0 + (Hn - y1)) * Wn + (y1 - y0) * (x0 + (Wn - x1));
+        };
+        j.nP = j.P ? outside(j.Hp, j.Wp, j.py0, j.py1, j.px0, j.px1) : 0;
+        j.nA = j.A ? outside(j.H, j.W, j.ay0, j.ay1, j.ax0, j.ax1) : 0;
+        j.reset_counters = b->fresh ? 2 : 1;             // per-frame counters start at zero every frame
+        const int vec = d.dtype == MDCNN_F16 ? 8 : 4;
+        const long long items = (long long)(j.nP + j.nA) * (d.C % vec == 0 ? d.C / vec : d.C);
+        long long blocks = (items + kFillItemsPerBlock - 1) / kFillItemsPerBlock;
+        if (blocks < 1) blocks = 1;
+        j.block_begin = fb.total_blocks;
+        fb.j[fb.n++] = j;
+        fb.total_blocks += (unsigned)blocks;
+        if (fb.n == kMaxFillJobs) {
+            hipError_t err = flush();
+            if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "shift launch: %s", hipGetErrorString(err));
+        }
+        if (full) {
+            b->r_up = b->r_down = b->r_left = b->r_right = false;
+            b->fresh = false;
+        } else {
+            // growing in one direction overwrites the stash of the opposite side
+            if (dtx > 0) b->r_left = true;
+            if (dtx < 0) b->r_right = true;
+            if (dty > 0) b->r_up = true;
+            if (dty < 0) b->r_down = true;
+        }
+    }
+    if (fb.n) {
+        hipError_t err = flush();
         if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "shift launch: %s", hipGetErrorString(err));
     }
+    if (did_full_reset) *did_full_reset = full ? 1 : 0;
     return MDCNN_OK;
 }
 
@@ -1060,10 +853,6 @@ mdcnn_status mdcnn_net_create(mdcnn_buffer* const* sites, int n_sites, const int
 }
 
 mdcnn_status mdcnn_net_destroy(mdcnn_net* net) {
-    if (net) {
-        drop_graph(net);
-        for (hipGraph_t g : net->ggraph_keep) (void)hipGraphDestroy(g);
-    }
     delete net;
     return MDCNN_OK;
 }

@@ -33,20 +33,6 @@ constexpr int kAccMacsPlain = 8;    // multiply-accumulates of the plain-FMA ker
 constexpr int kAccMacsSpread = 16;  // [16, 24): MFMA partials, [24, 32): plain partials
 constexpr int kNumCounters = 64;
 
-// Per-frame state of a site, kept in the site's own memory right behind its counters
-// (kNumCounters ints further) and rewritten by every camera shift.  A launch whose
-// descriptors say use_vars takes the ring origins and the frame / mask / readout pointers
-// from here instead of from its arguments, so that the arguments of a recorded launch stay
-// valid from frame to frame.
-struct SiteVars {
-    int a_oy, a_ox, p_oy, p_ox;
-    const void* io;            // INPUT site: the frame; OUTPUT site: destination of the readout
-    const uint8_t* forced;     // INPUT site: forced mask or nullptr
-};
-__host__ __device__ inline const SiteVars* vars_of(const int* counters) {
-    return reinterpret_cast<const SiteVars*>(counters + kNumCounters);
-}
-
 // Lists are compacted per segment of kSegPixels consecutive linear indices:
 // entries of segment g sit at list[g * kSegPixels ...], their number in cnt[g].
 // Concatenating the segments in order gives the ascending list.
@@ -72,8 +58,9 @@ struct SiteDev {
     int a_oy, a_ox;       // physical ring position of view pixel (0,0) in A
     int p_oy, p_ox;       // physical ring position of window pixel (0,0) in P
     float theta;
-    uint8_t relu, kind, dtype;
-    uint8_t use_vars;     // origins, frame and mask pointers come from vars_of(counters)
+    int relu;
+    int kind;
+    int dtype;
     // Sites with crops (H, W < 65536).  s_off: their state ring S (H x W bytes, kStateUnseen | kStateDirty per
     // pixel, ring order of A) as an offset from A in units of 256 bytes, 0: no crops.  cy, cx: the rows / columns
     // of the view the frame covers, first in the low and end in the high 16 bits (whole view by default).
@@ -92,7 +79,6 @@ struct SkipDev {
     void* P;
     uint8_t* dflags;          // nullptr for OUTPUT sites
     int Hp, Wp, by0, bx0, p_oy, p_ox;
-    const SiteVars* vars;     // non-null: p_oy, p_ox come from there
 };
 
 // Initialisation job of one site for one camera shift: everything outside the
@@ -108,8 +94,6 @@ struct FillJob {
     unsigned long long* cacc;
     int* lcnt;                  // per-segment counts of the frame (n_lacc / n_cacc entries), cleared with them:
     int* ccnt;                  // a site no edge publishes a compute list for must still read as empty
-    const void* io;             // written to the site's SiteVars together with the origins: the frame (INPUT site),
-    const uint8_t* forced;      // its forced mask, the destination of the readout (OUTPUT site); nullptr if not known
     unsigned s_off, y_off;      // S and Y of the site as offsets from A in units of 256 bytes (0: none): pixels that
                                 // enter the view get S = unseen and Y = 0
     int n_lacc, n_cacc;
@@ -122,7 +106,7 @@ struct FillJob {
     int reset_counters;         // 1: per-frame slots, 2: all (first reset)
     unsigned block_begin;       // first block of the launch that works on this job
 };
-constexpr int kMaxFillJobs = 20;
+constexpr int kMaxFillJobs = 22;
 struct FillBatch {
     FillJob j[kMaxFillJobs];
     int n;
@@ -157,7 +141,6 @@ struct EdgeDev {
     const void* sA;
     void* dY;
     int s_aoy, s_aox, s_relu, d_aoy, d_aox, op;
-    int use_vars;             // ring origins come from vars_of(dcounters) / vars_of(scounters)
 };
 
 // Several independent streams (same network, own buffers and camera paths) share
@@ -176,8 +159,7 @@ static_assert(sizeof(EdgeBatch) <= 3800 && sizeof(Step1Batch) <= 3800, "kernel a
 
 enum KernelClass { kClsShift = 0, kClsStep1, kClsLists, kClsConvMfma, kClsConvPlain, kClsIdentity, kClsReadout, kClsPool, kNumClasses };
 
-hipError_t launch_shift_fill(const FillBatch& fb, unsigned grid, hipStream_t st);
-const void* shift_fill_function();                  // the kernel behind launch_shift_fill, to find its nodes in a captured graph
+hipError_t launch_shift_fill(const FillBatch& fb, hipStream_t st);
 // n streams; geometry and dtype are those of stream 0 (the host checks that all agree)
 hipError_t launch_step1(const Step1Batch& b, int n, hipStream_t st);
 // e.k < 0: no operator, only the compaction of the source's update mask.
