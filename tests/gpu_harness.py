@@ -118,19 +118,15 @@ def teacher_forced(net, frames, shifts, forced=None, origins=None, log=None, cro
                 errs = [maxerr(g.read(i, B.MDCNN_VIEW_A), s.get_A()), maxerr(g.read(i, B.MDCNN_VIEW_DELTA), s.delta)]
                 if s.spec.kind != "input":
                     errs.append(maxerr(g.read(i, B.MDCNN_VIEW_P), s.get_P()))
-                seen = set()
                 for e, lst in zip(edges, lists):
                     d = o.sites[e.dst]
                     w2 = where + f" -> site {e.dst}"
-                    if not e.up and e.dst not in seen:
-                        pass
                     errs.append(maxerr(g.read(e.dst, B.MDCNN_VIEW_P), d.get_P()))
                     if getattr(e, "pool", False):   # a maximum of stored values: exact
                         assert np.array_equal(g.read(e.dst, B.MDCNN_VIEW_POOL_PREV), d.get_Y()), w2 + ": previous pooling output"
                     if d.spec.kind != "output":
                         fl = g.read(e.dst, B.MDCNN_VIEW_FLAGS)
                         assert np.array_equal(fl & (B.FLAG_N | B.FLAG_U), oracle_flags(d)), w2 + ": U flags"
-                    seen.add(e.dst)
                 # compute list: the last non-upsampling edge into each destination
                 last = {}
                 for e, lst in zip(edges, lists):

@@ -125,6 +125,16 @@ class CanvasReference:
             self.canvas[i][v] = val[v]
         return [self.canvas[i][self._view(i)].copy() for i in net.terminal_sites()]
 
+    def _pool(self, i, src, e):
+        """Library max pooling of site i's canvas.  A pooling window takes the pixels of the source's
+        current view only (what lies outside takes no part), so everything else is masked out; outputs
+        whose window holds no view pixel are not used by the callers."""
+        vy, vx = self._view(i)
+        masked = np.full_like(src, -np.inf)
+        masked[vy, vx] = src[vy, vx]
+        out = maxpool64(masked, e.k, e.stride, e.pad)
+        return np.where(np.isfinite(out), out, 0.0)
+
     def _frame_crop(self, X, crop):
         """Cropped frame: the same recomputation, but a site's canvas takes the new
         values inside the crop only (scaled to the site); everything else, inside or
@@ -136,7 +146,10 @@ class CanvasReference:
             for e in net.edges:
                 if e.dst == i:
                     src = self.canvas[e.src]
-                    acc = acc + (src if e.k == 0 else _conv64(src, e))
+                    if getattr(e, "pool", False):
+                        acc = acc + self._pool(e.src, src, e)
+                    else:
+                        acc = acc + (src if e.k == 0 else _conv64(src, e))
             val = np.maximum(acc, 0) if net.sites[i].relu else acc
             v = self._crop(i, crop)
             self.canvas[i][v] = val[v]

@@ -212,3 +212,30 @@ def test_full_size_cropped_frames(cfg, n):
     log(f"config {cfg} cropped free-running: out_err {r['out_err']:.2e} mask mismatch {r['mask_mismatch']:.2e} resets {r['resets']}")
     assert r["mask_mismatch"] < 0.02
     assert r["out_err"] < 0.15 + 4 * H.TOL["f16"]
+
+
+def test_config3_full_512_input_masks():
+    """mdcnn_input_mask at the headline frame size: bit-exact against the oracle, first-layer dilation of 10 pixels included."""
+    import gpu_harness as H
+    from oracle.mdcnn_oracle import OracleNet
+    from paper_2210_09887_amd.runtime import GpuNet
+    net = build_net(3)
+    seq = build_sequence(3, n_frames=3)
+    g, o = GpuNet(net), OracleNet(net)
+    try:
+        for t, X in enumerate(seq.frames):
+            dy, dx = (int(v) for v in seq.shifts[t])
+            Xd = H.dev(X)
+            assert g.shift_camera(dy, dx) == o.shift_camera(dy, dx)
+            for kw in [dict(), dict(suppress=True, dilate=2), dict(dilate=10), dict(pool=4, suppress=True, dilate=10, theta=0.01)]:
+                want = o.input_mask(X, **kw)
+                got = g.input_mask(Xd, **kw).cpu().numpy()
+                assert np.array_equal(got, want), f"frame {t} {kw}"
+            fm = o.input_mask(X, suppress=True, dilate=2)
+            g.layer_forward(0, Xd, H.dev(fm))
+            o.layer_forward(0, X, fm)
+            torch.cuda.synchronize()
+            assert np.array_equal(g.read(0, 4), o.sites[0].L)
+            log(f"config 3 input masks frame {t}: {int(fm.sum())} of {fm.size} pixels")
+    finally:
+        g.close()

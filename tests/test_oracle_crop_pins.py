@@ -166,3 +166,26 @@ def test_pins_catch_forgotten_updates_outside_the_crop():
         o.frame(cut(net, X, crop), 0, 0, crop=crop)
     outs, _ = o.frame(image, 0, 0, crop=(0, 0, Ht, Wt))
     assert np.abs(outs[0].astype(np.float64) - refs.dense_cnn(net, image)[0]).max() > 1e-3
+
+
+# ---- the same with max pooling (static camera: a pooled value is refreshed only when its window changes)
+@pytest.mark.parametrize("kind", ["pool", "resnet_poolstem"])
+def test_crop_canvas_invariant_with_max_pooling(kind):
+    if kind == "pool":
+        net = pool_net("f32", 32, 32, (2, 4, 3), 3, 2, 1, theta=0.0, seed=4)
+    else:
+        net = set_theta(as_f32(build_net(3, H=64, W=64, widths=(4, 8, 8, 16), pool_stem=True)), 0.0)
+    o = OracleNet(net, crops=True)
+    cv = refs.CanvasReference(net, 2)
+    rng = np.random.default_rng(12)
+    Ht, Wt = tiles_of(net)
+    for t, X in enumerate(rand_frames(net, 8, 31, walk=0.3)):
+        crop = (0, 0, Ht, Wt) if t == 0 else rand_crop(rng, Ht, Wt)
+        outs, r = o.frame(cut(net, X, crop), 0, 0, crop=crop)
+        ref = cv.frame(cut(net, X, crop), 0, 0, r, crop=crop)
+        assert np.abs(outs[0].astype(np.float64) - ref[0]).max() < 1e-4
+        for i, s in enumerate(o.sites):
+            if s.spec.kind == "preact":
+                fa = s.get_A().astype(np.float64)
+                fa = np.maximum(fa, 0) if s.spec.relu else fa
+                assert np.abs(fa - cv.canvas[i][cv._view(i)]).max() < 1e-4, (t, i)
