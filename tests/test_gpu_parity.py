@@ -258,3 +258,37 @@ def test_conv_kernel_shapes(cin, cout, H, W, k, stride):
         frames.append(x.astype(np.float16))
     worst = H_.teacher_forced(net, frames, [(0, 0), (0, 0), (1, -1)], log=log)
     log(f"[conv shapes] {cin}->{cout} {H}x{W} k{k} s{stride}: worst {worst:.3e}")
+
+
+def random_conv_cases(n=28, seed=2210):
+    """Seeded single-convolution networks over the corners no named workload reaches: odd channel
+    counts, 5x5 kernels, strides 3 and 4, 1x1 strided, both storage types."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        k = int(rng.choice([1, 3, 5]))
+        stride = int(rng.choice([1, 2, 3, 4]))
+        cin = int(rng.choice([1, 3, 5, 8, 12, 16, 24, 32, 40, 64]))
+        cout = int(rng.choice([1, 4, 7, 8, 16, 24, 32, 48, 64, 96]))
+        dtype = "f16" if i % 2 else "f32"
+        H = stride * int(rng.integers(6, 22))
+        W = stride * int(rng.integers(6, 22))
+        cases.append((dtype, cin, cout, H, W, k, stride))
+    return cases
+
+
+@pytest.mark.parametrize("case", random_conv_cases(), ids=lambda c: "{}_{}to{}_{}x{}_k{}s{}".format(*c))
+def test_random_single_convs(case):
+    import gpu_harness as H_
+    from inputs.nets import tiny_net
+    dtype, cin, cout, H, W, k, stride = case
+    net = tiny_net(dtype, H, W, (cin, cout), k=k, stride=stride, theta=0.05, seed=cin * 7 + cout, total_stride=stride)
+    rng = np.random.default_rng(cin * 131 + cout * 17 + H)
+    x = rng.normal(0, 1, (H, W, cin)).astype(np.float32)
+    frames = [x.astype(net.np_dtype)]
+    for _ in range(3):
+        x = x.copy()
+        x[rng.random((H, W)) < 0.15] += rng.normal(0, 1, cin).astype(np.float32)
+        frames.append(x.astype(net.np_dtype))
+    worst = H_.teacher_forced(net, frames, [(0, 0), (0, 0), (1, -1), (-1, 0)])
+    log(f"[random conv] {case}: worst {worst:.3e}")
