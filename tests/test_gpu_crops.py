@@ -171,3 +171,34 @@ def test_crop_argument_checks():
     finally:
         plain.close()
         g.close()
+
+
+def random_chain_cases(n=10, seed=909):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        k = int(rng.choice([1, 3, 5]))
+        stride = int(rng.choice([1, 2, 3]))
+        C = tuple(int(rng.choice([3, 5, 8, 16, 32, 40])) for _ in range(3))
+        T = stride * stride
+        cases.append(("f16" if i % 2 else "f32", C, T * int(rng.integers(3, 9)), T * int(rng.integers(3, 9)), k, stride))
+    return cases
+
+
+@pytest.mark.parametrize("case", random_chain_cases(), ids=lambda c: "{}_{}_{}x{}_k{}s{}".format(c[0], "-".join(map(str, c[1])), *c[2:]))
+def test_random_chains_with_crops(case):
+    """Seeded two-convolution chains (odd channels, 5x5, stride 3) with a different crop every frame."""
+    import gpu_harness as H
+    from inputs.nets import tiny_net
+    dtype, C, Hh, Ww, k, stride = case
+    net = tiny_net(dtype, Hh, Ww, C, k=k, stride=stride, theta=0.05, seed=sum(C))
+    rng = np.random.default_rng(Hh * 31 + Ww)
+    x = rng.normal(0, 1, (Hh, Ww, C[0])).astype(np.float32)
+    frames = []
+    for _ in range(6):
+        x = x.copy()
+        x[rng.random((Hh, Ww)) < 0.2] += rng.normal(0, 1, C[0]).astype(np.float32)
+        frames.append(x.astype(net.np_dtype))
+    shifts = [(0, 0), (0, 1), (1, 0), (0, 0), (-1, 0), (0, 0)]        # frame 4 reverses: full reset
+    worst = H.teacher_forced(net, frames, shifts, crops=rand_crops(net, 6, sum(C) + k, full_first=bool(k % 2 == 1 and stride < 3)))
+    log(f"[random chains with crops] {case}: worst {worst:.3e}")
