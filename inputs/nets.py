@@ -341,3 +341,76 @@ def pool_front_net(dtype="f32", H=16, W=16, C=(3, 2), k=3, stride=2, pad=1, thet
     b.maxpool(x, p, k, stride, pad)
     b.conv(p, y, 1, 1, pad=0)
     return net
+
+
+def random_dag_net(seed: int, dtype="f32", tiles=(5, 4), theta=0.05, n_inner=7) -> NetSpec:
+    """A seeded random network for differential tests: sites at strides 1 / 2 / 4 with one to
+    three producers each - convolutions (1x1, 3x3, strided 3x3 and 5x5), residual skips, 1x1
+    convolutions with nearest upsampling, max pooling - and one or two outputs.  Every site but
+    the input has a producer and every inner site a consumer; edges go from lower to higher
+    site indices and are grouped by source."""
+    rng = np.random.default_rng(seed)
+    T = 4
+    net = NetSpec(f"dag{seed}", dtype, tiles[0] * T, tiles[1] * T, T)
+    b = _Builder(net, rng, 0.1)
+    chans = [8, 16, 24, 32] if dtype == "f16" else [3, 5, 8, 16]
+    b.site("in", int(rng.choice([3, 4, 8])), 1, "input", False, theta)
+    pooled = set()
+
+    def connect(src, dst):
+        s, d = net.sites[src], net.sites[dst]
+        if d.stride == s.stride:
+            if s.C == d.C and dst not in pooled and rng.random() < 0.4:
+                b.identity(src, dst)
+            else:
+                k = int(rng.choice([1, 3]))
+                b.conv(src, dst, k, 1, gain=0.7)
+        elif d.stride > s.stride:
+            f = d.stride // s.stride
+            if f == 2 and s.C == d.C and s.kind != "input" and dst in pooled:
+                k = int(rng.choice([2, 3]))
+                b.maxpool(src, dst, k, 2, 0 if k == 2 else 1)
+            else:
+                b.conv(src, dst, 3 if f == 2 else 5, f, gain=0.7)
+        else:
+            up = {2: 1, 4: 2}[s.stride // d.stride]
+            b.conv(src, dst, 1, 1, pad=0, up=up, gain=0.7)
+
+    for i in range(n_inner):
+        stride = int(rng.choice([1, 2, 4]))
+        last = i >= n_inner - int(rng.integers(1, 3))
+        C = int(rng.choice(chans))
+        prods = sorted(set(int(v) for v in rng.choice(len(net.sites), size=int(rng.integers(1, 4)))))
+        prods = [p for p in prods if net.sites[p].kind != "output"] or [0]
+        # a pooled site takes a pooling from a producer at half its stride with the same channels
+        cand = [p for p in prods if net.sites[p].stride * 2 == stride and net.sites[p].kind == "preact"]
+        if cand and not last and rng.random() < 0.5:
+            C = net.sites[cand[0]].C
+        dst = b.site(f"s{i}", C, stride, "output" if last else "preact", bool(rng.random() < 0.7) and not last, 0.0 if last else theta)
+        if cand and not last and net.sites[cand[0]].C == C and rng.random() < 0.7:
+            pooled.add(dst)
+        for p in prods:
+            if dst in pooled and p != cand[0] and rng.random() < 0.5:
+                continue
+            connect(p, dst)
+        if dst in pooled and not any(e.pool for e in net.edges if e.dst == dst):
+            pooled.discard(dst)
+    # inner sites without a consumer feed the last output
+    outs = net.terminal_sites()
+    for i, s in enumerate(net.sites):
+        if s.kind == "preact" and not net.out_edges(i):
+            tgt = [o for o in outs if o > i]
+            if tgt:
+                connect(i, tgt[-1])
+            else:
+                s.kind, s.relu, s.theta = "output", False, 0.0
+    # a pooling edge needs a destination that keeps its previous outputs: PREACT only
+    for e in net.edges:
+        if e.pool and net.sites[e.dst].kind != "preact":
+            e.pool, e.k, e.stride, e.pad = False, 3, 2, 1
+            std = np.sqrt(2.0 / (9 * net.sites[e.src].C)) * 0.7
+            e.w = (rng.standard_normal((9, net.sites[e.dst].C, net.sites[e.src].C)) * std).astype(np.float32).astype(net.np_dtype)
+    _sort_edges(net)
+    for e in net.edges:
+        assert e.src < e.dst
+    return net

@@ -292,3 +292,40 @@ def test_random_single_convs(case):
         frames.append(x.astype(net.np_dtype))
     worst = H_.teacher_forced(net, frames, [(0, 0), (0, 0), (1, -1), (-1, 0)])
     log(f"[random conv] {case}: worst {worst:.3e}")
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_networks(seed):
+    """Seeded random networks (several producers per site, skips, upsampling, pooling, two outputs) under a
+    moving camera with a reset: teacher-forced against the oracle, then mdcnn_frame on 1 and 4 streams bit for bit."""
+    import gpu_harness as H_
+    from inputs.nets import random_dag_net
+    from paper_2210_09887_amd import binding as B
+    from paper_2210_09887_amd.runtime import GpuNet
+    net = random_dag_net(seed, "f16" if seed % 2 else "f32")
+    rng = np.random.default_rng(seed)
+    x = rng.normal(0, 1, (net.H, net.W, net.sites[0].C)).astype(np.float32)
+    frames = []
+    for _ in range(6):
+        x = x.copy()
+        x[rng.random((net.H, net.W)) < 0.15] += rng.normal(0, 0.7, net.sites[0].C).astype(np.float32)
+        frames.append(x.astype(net.np_dtype))
+    shifts = [(0, 0), (1, 0), (0, -1), (0, 0), (-1, 0), (0, 1)]        # frame 4 reverses: full reset
+    worst = H_.teacher_forced(net, frames, shifts)
+    log(f"[random network {seed}] {len(net.sites)} sites, {len(net.edges)} edges: worst {worst:.3e}")
+    outs = {}
+    for ns in (1, 4):
+        B.mdcnn_set_option(B.MDCNN_OPT_STREAMS, ns)
+        g = GpuNet(net)
+        try:
+            res = []
+            for X, (dy, dx) in zip(frames, shifts):
+                o, _ = g.frame(H_.dev(X), dy, dx)
+                torch.cuda.synchronize()
+                res.append(o.clone())
+            outs[ns] = res
+        finally:
+            B.mdcnn_set_option(B.MDCNN_OPT_STREAMS, 0)
+            g.close()
+    for a, b in zip(outs[1], outs[4]):
+        assert torch.equal(a, b)

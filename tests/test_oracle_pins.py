@@ -452,3 +452,20 @@ def test_pins_catch_a_dropped_border(monkeypatch):
             return
         worst = max(worst, np.abs(outs[0] - cv.frame(seq.frames[t], *seq.shifts[t], r)[0]).max())
     assert worst > 1e-2
+
+
+# ---- random networks: threshold 0 on a static camera equals the dense network, every site
+@pytest.mark.parametrize("seed", range(10))
+def test_random_networks_theta0_static_equal_dense(seed):
+    from inputs.nets import random_dag_net
+    net = set_theta(random_dag_net(seed, "f32"), 0.0)
+    o = OracleNet(net)
+    for X in rand_frames(net, 4, seed + 50, walk=0.2):
+        outs, _ = o.frame(X, 0, 0)
+        vals = refs.dense_cnn(net, X, return_all=True)
+        for a, i in zip(outs, net.terminal_sites()):
+            assert np.abs(a.astype(np.float64) - vals[i]).max() < 1e-4
+        for i, s in enumerate(o.sites):
+            if s.spec.kind == "preact":
+                fa = s.get_A().astype(np.float64)
+                assert np.abs((np.maximum(fa, 0) if s.spec.relu else fa) - vals[i]).max() < 1e-4

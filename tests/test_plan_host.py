@@ -6,7 +6,7 @@ network description alone; no GPU is needed (buffers wrap a fake address)."""
 import pytest
 
 from inputs import build_net
-from inputs.nets import pool_net
+from inputs.nets import pool_net, random_dag_net
 from paper_2210_09887_amd import binding as B
 
 FAKE = 0x7F0000000000
@@ -87,6 +87,7 @@ NETS = {
     "cnn5": lambda: build_net(2, H=64, W=64),
     "pool": lambda: pool_net("f16", 16, 16, (8, 16, 8), 3, 2, 1),
 }
+NETS.update({f"dag{seed}": (lambda seed=seed: random_dag_net(seed, "f16" if seed % 2 else "f32")) for seed in range(12)})
 
 
 @pytest.mark.parametrize("name", list(NETS))
@@ -117,7 +118,7 @@ def test_conflicting_launches_are_ordered(name, streams):
 
 def test_streams_are_used_where_the_network_has_branches():
     used = {}
-    for name in ("resnet", "hrnet_full", "cnn5"):
+    for name in ("resnet", "hrnet_full", "cnn5"):   # (random networks: whatever the plan decides)
         net, bufs = host_net(NETS[name]())
         used[name] = (B.mdcnn_frame_plan(net, 0)[2], B.mdcnn_frame_plan(net, 4)[2])
         B.mdcnn_net_destroy(net)
