@@ -496,7 +496,10 @@ struct HaloCfg {
     static constexpr int MB = KB / WK;               // blocks per tap and wave
     static constexpr int NS = KS * KS * MB;          // steps per chunk and wave
     static constexpr int RING = RING_;               // weight-fragment sets in flight; divides NS, so the
-                                                     // ring carries over from chunk to chunk
+                                                     // ring carries over from chunk to chunk.  Above 3 the
+                                                     // registers go to the ring and the next chunk of the
+                                                     // rectangle is fetched at the chunk boundary instead of
+                                                     // being prefetched into registers during the chunk
     static_assert(NS % RING == 0, "static ring slots");
     static constexpr int CPR = KC / 8;               // 16-byte pieces per staged pixel
     static constexpr int NLD = NLD_;                 // pieces per thread and chunk
@@ -644,7 +647,7 @@ void k_conv_halo(EdgeBatch eb, int NT, int work_items) {
                 for (int i = 0; i < FBR - 1; ++i) load_b(i, i);
 #pragma unroll
                 for (int i = 0; i < NS; ++i) {
-                    if (i < Cfg::NLS) {                   // staging loads of the next chunk, a few per step
+                    if (Cfg::RING <= 3 && i < Cfg::NLS) { // staging loads of the next chunk, a few per step
 #pragma unroll
                         for (int j = i * Cfg::LPS; j < (i + 1) * Cfg::LPS && j < NLD; ++j)
                             hreg[j] = *reinterpret_cast<const f16x8*>(delta + hsrc[j] + hc);
@@ -668,6 +671,11 @@ void k_conv_halo(EdgeBatch eb, int NT, int work_items) {
                 }
                 __syncthreads();                          // everyone is done reading the staged chunk
                 if (c + 1 < nchunks) {
+                    if constexpr (Cfg::RING > 3) {        // deep weight ring: the registers go to it, the next chunk is
+                                                          // fetched here (the weight loads of its first steps are in flight)
+#pragma unroll
+                        for (int j = 0; j < NLD; ++j) hreg[j] = *reinterpret_cast<const f16x8*>(delta + hsrc[j] + hc);
+                    }
                     halo_store();
                     __syncthreads();
                 }
@@ -1298,11 +1306,11 @@ static hipError_t launch_halo_n(const EdgeBatch& eb, int nb, long long nseg, hip
             if (c64 && worst <= HaloCfg<1, 2, 2, 4, TN, 64, 16, 3>::CAP) return launch_halo_t<1, 2, 2, 4, TN, 64, 16>(eb, nb, nseg, st);
             if (c32 && worst <= HaloCfg<1, 2, 2, 4, TN, 32, 12, 3>::CAP) return launch_halo_t<1, 2, 2, 4, TN, 32, 12>(eb, nb, nseg, st);
         } else if (nsub == 2) {
-            if (c64 && worst <= HaloCfg<2, 2, 2, 2, TN, 64, 11, 3>::CAP) return launch_halo_t<2, 2, 2, 2, TN, 64, 11>(eb, nb, nseg, st);
+            if (c64 && worst <= HaloCfg<2, 2, 2, 2, TN, 64, 11, 3>::CAP) return launch_halo_t<2, 2, 2, 2, TN, 64, 11, 6>(eb, nb, nseg, st);
             if (c32 && worst <= HaloCfg<2, 2, 2, 2, TN, 32, 9, 3>::CAP) return launch_halo_t<2, 2, 2, 2, TN, 32, 9>(eb, nb, nseg, st);
         } else {
-            if (c64 && worst <= HaloCfg<4, 1, 4, 2, TN, 64, 9, 3>::CAP) return launch_halo_t<4, 1, 4, 2, TN, 64, 9>(eb, nb, nseg, st);
-            if (c32 && worst <= HaloCfg<4, 2, 2, 1, TN, 32, 6, 3>::CAP) return launch_halo_t<4, 2, 2, 1, TN, 32, 6>(eb, nb, nseg, st);
+            if (c64 && worst <= HaloCfg<4, 1, 4, 2, TN, 64, 9, 3>::CAP) return launch_halo_t<4, 1, 4, 2, TN, 64, 9, 9>(eb, nb, nseg, st);
+            if (c32 && worst <= HaloCfg<4, 2, 2, 1, TN, 32, 6, 3>::CAP) return launch_halo_t<4, 2, 2, 1, TN, 32, 6, 9>(eb, nb, nseg, st);
         }
     }
     *done = false;
