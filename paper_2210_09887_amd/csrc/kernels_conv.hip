@@ -403,6 +403,33 @@ __global__ __launch_bounds__(256) void k_conv_mfma_tiled(EdgeBatch eb, int NT, i
         constexpr int TPR = BN / 8;                        // threads per pixel row, 8 couts each
         const int c8 = (tid % TPR) * 8;
         const int f = 1 << e.up;
+        if (f == 1) {
+            // P <- P + sum: all reads of P go out first (their latency is paid once), then the stores
+            constexpr int RPP = 256 / TPR, NPASS = (BM + RPP - 1) / RPP;
+            f16x8 pold[NPASS];
+            f16* pp[NPASS];
+#pragma unroll
+            for (int t = 0; t < NPASS; ++t) {
+                const int row = tid / TPR + t * RPP;
+                const int rr = row < live ? row : 0;        // dead rows read entry 0 and store nothing
+                pp[t] = (f16*)e.P + pdst_offset(e, s_wy[rr], s_wx[rr]) + n0 + c8;
+                pold[t] = *reinterpret_cast<const f16x8*>(pp[t]);
+            }
+#pragma unroll
+            for (int t = 0; t < NPASS; ++t) {
+                const int row = tid / TPR + t * RPP;
+                if (row < live) {
+                    const float4 v0 = *reinterpret_cast<const float4*>(sC + row * LDC + c8);
+                    const float4 v1 = *reinterpret_cast<const float4*>(sC + row * LDC + c8 + 4);
+                    const float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+                    f16x8 o = pold[t];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) o[q] = (f16)((float)o[q] + v[q]);
+                    *reinterpret_cast<f16x8*>(pp[t]) = o;
+                }
+            }
+            continue;
+        }
         for (int row = tid / TPR; row < BM && row < live; row += 256 / TPR) {
             const float4 v0 = *reinterpret_cast<const float4*>(sC + row * LDC + c8);
             const float4 v1 = *reinterpret_cast<const float4*>(sC + row * LDC + c8 + 4);
