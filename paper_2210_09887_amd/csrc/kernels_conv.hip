@@ -874,21 +874,25 @@ __global__ __launch_bounds__(256) void k_conv_mfma_f16(EdgeBatch eb) {
 
 template <typename T> struct Row8;
 template <> struct Row8<f16> {
-    __device__ static void add(f16* p, const float* v) {
-        f16x8 o = *reinterpret_cast<f16x8*>(p);
+    typedef f16x8 reg;                                      // eight stored values, fetched ahead of their use
+    __device__ static reg load(const f16* p) { return *reinterpret_cast<const f16x8*>(p); }
+    __device__ static void add_store(f16* p, reg o, const float* v) {
 #pragma unroll
         for (int q = 0; q < 8; ++q) o[q] = (f16)((float)o[q] + v[q]);
         *reinterpret_cast<f16x8*>(p) = o;
     }
+    __device__ static void add(f16* p, const float* v) { add_store(p, load(p), v); }
 };
 template <> struct Row8<float> {
-    __device__ static void add(float* p, const float* v) {
-        float4 a = *reinterpret_cast<float4*>(p), b = *reinterpret_cast<float4*>(p + 4);
-        a.x += v[0]; a.y += v[1]; a.z += v[2]; a.w += v[3];
-        b.x += v[4]; b.y += v[5]; b.z += v[6]; b.w += v[7];
-        *reinterpret_cast<float4*>(p) = a;
-        *reinterpret_cast<float4*>(p + 4) = b;
+    struct reg { float4 a, b; };
+    __device__ static reg load(const float* p) { return reg{*reinterpret_cast<const float4*>(p), *reinterpret_cast<const float4*>(p + 4)}; }
+    __device__ static void add_store(float* p, reg o, const float* v) {
+        o.a.x += v[0]; o.a.y += v[1]; o.a.z += v[2]; o.a.w += v[3];
+        o.b.x += v[4]; o.b.y += v[5]; o.b.z += v[6]; o.b.w += v[7];
+        *reinterpret_cast<float4*>(p) = o.a;
+        *reinterpret_cast<float4*>(p + 4) = o.b;
     }
+    __device__ static void add(float* p, const float* v) { add_store(p, load(p), v); }
 };
 
 // ---------------------------------------------------------------------------
@@ -1005,6 +1009,14 @@ __global__ __launch_bounds__(256) void k_conv_small(EdgeBatch eb, int groups, in
             if (!((vmask >> tap) & 1u))
 #pragma unroll
                 for (int ci = 0; ci < CIN; ++ci) in[tap * CIN + ci] = 0.f;
+        // the pending values this thread adds to travel while it multiplies (no upsampling: one pixel)
+        const int f = 1 << e.up;
+        T* pp0 = (T*)e.P + pdst_offset(e, s_wy[pl], s_wx[pl]) + cg * CPT;
+        typename Row8<T>::reg pold[CPT / 8];
+        if (f == 1) {
+#pragma unroll
+            for (int q = 0; q < CPT; q += 8) pold[q / 8] = Row8<T>::load(pp0 + q);
+        }
         float acc[CPT];
 #pragma unroll
         for (int q = 0; q < CPT; ++q) acc[q] = 0.f;
@@ -1019,7 +1031,11 @@ __global__ __launch_bounds__(256) void k_conv_small(EdgeBatch eb, int groups, in
                 acc[q + 2] = fmaf(a, w4.z, acc[q + 2]); acc[q + 3] = fmaf(a, w4.w, acc[q + 3]);
             }
         }
-        const int f = 1 << e.up;
+        if (f == 1) {
+#pragma unroll
+            for (int q = 0; q < CPT; q += 8) Row8<T>::add_store(pp0 + q, pold[q / 8], acc + q);
+            continue;
+        }
         for (int ua = 0; ua < f; ++ua)
             for (int ub = 0; ub < f; ++ub) {
                 T* pp = (T*)e.P + pdst_offset(e, s_wy[pl] + ua, s_wx[pl] + ub) + cg * CPT;
