@@ -3,11 +3,15 @@
 
 One step = one frame of the whole per-frame path (camera shift + dynamic
 initialisation, delta/truncation/mask, compaction, padded sparse convolutions,
-residual adds, readout) through `mdcnn_frame` on the headline workload: the
-ResNet-18-style 512x512 fp16 network on the seeded 60-frame moving-camera
-sequence, all frames resident in HBM before the timed region starts.  The
-sequence is replayed cyclically (the jump back to its start is one more camera
-shift, which the buffer manager answers with a full reset).
+residual adds, readout) on the headline workload: the ResNet-18-style 512x512
+fp16 network on the seeded 60-frame moving-camera sequence, all frames resident
+in HBM before the timed region starts.  The sequence is replayed cyclically (the
+jump back to its start is one more camera shift, which the buffer manager
+answers with a full reset).  The video goes through `mdcnn_frames`, one call per
+pass over the sequence, which keeps up to --frames-in-flight consecutive frames
+in flight (same launches, same results bit for bit as one `mdcnn_frame` call per
+frame; that rate is reported next to it as "frame_at_a_time" and is the headline
+with --frames-in-flight 1 and in the modes that have no such call).
 
 Prints ONE JSON line.  Besides the throughput it carries
   roofline     -- the dominant kernel class, timed with HIP events recorded by
@@ -51,6 +55,8 @@ def parse():
     ap.add_argument("--front-end", action="store_true",
                     help="the input update mask of every frame comes from mdcnn_input_mask (isolated updates suppressed, "
                          "dilation by 2 pixels) and is forced; one stream only")
+    ap.add_argument("--frames-in-flight", type=int, default=4,
+                    help="consecutive frames of the video that mdcnn_frames keeps in flight (1..4); 1: one mdcnn_frame call per frame")
     ap.add_argument("--streams", type=int, default=8,
                     help="after the headline run, the same workload as a batch of this many independent streams "
                          "(mdcnn_frame_batch; reported under \"batched\"); 0 disables it")
@@ -296,16 +302,41 @@ def main():
         state["t"] += 1
         state["resets"] += int(r)
 
-    for _ in range(a.warmup):
-        step()
-    torch.cuda.synchronize()
-    state["resets"] = 0
-    t0 = time.perf_counter()
-    for _ in range(a.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    resets_timed = state["resets"]
+    in_flight = a.frames_in_flight if crops is None and not a.front_end else 1
+    outs_pool = [torch.empty_like(g.out) for _ in range(min(T, max(a.steps, a.warmup)))] if in_flight > 1 else []
+
+    def run_frames(n):
+        """n frames of the video through mdcnn_frames, one call per pass over the sequence."""
+        done = 0
+        while done < n:
+            t0_ = state["t"]
+            m = min(T - t0_ % T, n - done, len(outs_pool))
+            idx = [(t0_ + k) % T for k in range(m)]
+            sh = [(0, 0) if t0_ + k == 0 else (int(shifts[i][0]), int(shifts[i][1])) for k, i in enumerate(idx)]
+            _, rs = g.frames([frames[i] for i in idx], [v[0] for v in sh], [v[1] for v in sh],
+                             None if forced is None else [forced[i] for i in idx], outs=outs_pool[:m], depth=in_flight)
+            state["t"] += m
+            state["resets"] += sum(int(r) for r in rs)
+            done += m
+
+    def timed_region(run):
+        run(a.warmup)
+        torch.cuda.synchronize()
+        state["resets"] = 0
+        t0 = time.perf_counter()
+        run(a.steps)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    one_by_one = lambda n: [step() for _ in range(n)]
+    dt_each = None
+    if in_flight > 1:
+        dt = timed_region(run_frames)
+        resets_timed = state["resets"]
+        dt_each = timed_region(one_by_one)
+    else:
+        dt = timed_region(one_by_one)
+        resets_timed = state["resets"]
 
     # ---- instrumented pass: per-class kernel time (HIP events around every launch)
     before = g.totals()
@@ -376,7 +407,9 @@ def main():
                                + (f", density {a.density}" if cfg == 5 else ""),
                    "input": [net.H, net.W, net.sites[0].C], "sites": len(net.sites), "edges": len(net.edges),
                    "resets_in_timed_steps": resets_timed, "mean_update_density": round(float(np.mean(dens)), 4),
-                   "input_update_density": round(dens[0], 4)},
+                   "input_update_density": round(dens[0], 4), "frames_in_flight": in_flight,
+                   "entry_point": "mdcnn_frames, one call per pass over the sequence" if in_flight > 1 else
+                                  "mdcnn_frame_crop" if crops is not None else "mdcnn_shift_camera + mdcnn_input_mask + mdcnn_layer_forward" if a.front_end else "mdcnn_frame"},
         "roofline": roofline,
         "roofline_all": rl_all,
         "kernel_classes": classes,
@@ -384,6 +417,17 @@ def main():
         "instrumented_ms_per_step": round(1e3 * dt_prof / n_prof, 4),
         "cpu_baseline": cpu,
     }
+    # the whole path against the chip: algorithmic flops and bytes of a frame (instrumented pass) at the frame rate
+    per_frame_flops = (flops_mfma + flops_plain) / n_prof
+    per_frame_bytes = sum(ab.values()) / n_prof
+    out["whole_path"] = {"tflops": round(per_frame_flops * out["value"] / 1e12, 2),
+                         "mfma_frac": round(flops_mfma / n_prof * out["value"] / 1e12 / PEAK_MFMA_F16_TFLOPS, 4),
+                         "algorithmic_gbs": round(per_frame_bytes * out["value"] / 1e9, 1),
+                         "hbm_frac": round(per_frame_bytes * out["value"] / 1e9 / PEAK_HBM_GBS, 4),
+                         "gflop_per_frame": round(per_frame_flops / 1e9, 2), "mbytes_per_frame": round(per_frame_bytes / 1e6, 2)}
+    if dt_each is not None:
+        out["frame_at_a_time"] = {"value": round(a.steps / dt_each, 2), "unit": "frames/s", "ms_per_step": round(1e3 * dt_each / a.steps, 4),
+                                  "entry_point": "mdcnn_frame"}
     if a.front_end:
         # the mask kernel alone, HIP events on the stream it is launched on (torch's current stream)
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -242,6 +242,60 @@ mdcnn_status mdcnn_frame_batch(mdcnn_net* const* nets, int n_streams, const void
                                const uint8_t* const* forced_masks_dev, const int* dty, const int* dtx,
                                void* const* outs_dev, size_t out_bytes, void* stream, int* did_full_reset);
 
+/* A run of n_frames consecutive frames of ONE video in one call, frame f being what
+ * mdcnn_frame(net, frames_dev[f], forced_masks_dev[f], dty[f], dtx[f], outs_dev[f])
+ * does: the frames are taken in order and every result - outputs and all state of the
+ * sites - is identical, bit for bit, to n_frames calls of mdcnn_frame  [Method, Fig. 3].
+ * What changes is when the launches run: several frames are in flight on `depth`
+ * streams (stream 0 is the caller's, the others are the library's own, as for
+ * MDCNN_OPT_STREAMS).  By default frame f as a whole goes to stream f % depth and
+ * follows the frame before it at a distance of a few layers.  With MDCNN_OPT_PIPE_MODE
+ * 0 the forward calls of the network are cut into `depth` runs of about equal cost
+ * and run k of every frame goes to stream k, so that run k of frame f works next to
+ * run k - 1 of frame f + 1.  Either way a frame touches a site only after the frame
+ * before has finished with it: two launches on one site are either on one stream or
+ * ordered by an event.  The initialisation of a camera shift is split by groups of
+ * calls for this and done by spare blocks of the delta launches (MDCNN_OPT_PIPE_GROUP,
+ * mdcnn_frames_plan).
+ * These launches are bound by their latency, not by the size of the GPU, so overlapping
+ * frames raises the frame rate of a single video the way a batch does for several; the
+ * latency of a frame does not improve.
+ * All arrays are host arrays of n_frames entries (1 <= n_frames <= 4096): frames_dev[f]
+ * and outs_dev[f] device pointers as in mdcnn_frame (out_bytes each; the output buffers
+ * must not overlap each other), forced_masks_dev NULL or with NULL entries,
+ * did_full_reset n_frames ints or NULL.  depth: 1..4 streams, 0 for the library's
+ * default (4); with 1 everything runs on the caller's stream.
+ * The caller's stream forks into the others at the start and waits for them at the end,
+ * so the call as a whole stays in stream order; nothing is synchronised with the host.
+ * Errors: MDCNN_ERR_SIZE for n_frames, depth or out_bytes out of range, MDCNN_ERR_STATE
+ * if outputs overlap or the network has a crop smaller than its view, MDCNN_ERR_NULL /
+ * MDCNN_ERR_ALIGN as for mdcnn_frame (checked for all frames before anything runs). */
+mdcnn_status mdcnn_frames(mdcnn_net* net, int n_frames, const void* const* frames_dev,
+                          const uint8_t* const* forced_masks_dev, const int* dty, const int* dtx,
+                          void* const* outs_dev, size_t out_bytes, int depth, void* stream,
+                          int* did_full_reset);
+
+/* Host-only.  The plan mdcnn_frames follows for `net` on `depth` streams (0: default).
+ * The forward calls of a frame (non-terminal sites in order) are numbered 0 ..
+ * *n_calls - 1; the readout counts as call *n_calls.  stream_of_call[c] (c <= *n_calls):
+ * the stream of call c in every frame (MDCNN_OPT_PIPE_MODE 0; -1 in mode 1, where frame
+ * f is on stream f % depth).  Where the stream changes between two consecutive calls, the later
+ * one waits for the earlier one of the same frame.  The calls are also cut into groups of
+ * MDCNN_OPT_PIPE_GROUP calls: first_call[g]: first call of group g; group_of_site[i]: the
+ * group the initialisation of site i belongs to (the first group with a launch that
+ * touches the site); init_call[g]: the call whose delta launch carries that
+ * initialisation in spare blocks (the last call of group g - 1, which does not touch
+ * those sites; -1 for group 0, whose sites get a launch of their own ahead of call 0);
+ * wait_call[g]: the call of the frame BEFORE that must have finished before that launch
+ * starts (-1 for none) - the library waits for it with an event unless it is on the
+ * same stream, where it comes earlier anyway.  The arrays are caller-owned with room for
+ * cap_groups groups / cap_sites sites / cap_calls calls (*n_calls + 1 needed) and may
+ * be NULL; *n_groups and *n_calls are optional.
+ * Errors: MDCNN_ERR_SIZE if an array is too small or depth out of range. */
+mdcnn_status mdcnn_frames_plan(mdcnn_net* net, int depth, int* first_call, int* wait_call,
+                               int* init_call, int cap_groups, int* group_of_site, int cap_sites,
+                               int* stream_of_call, int cap_calls, int* n_groups, int* n_calls);
+
 /* Optional post-processing of the input update mask.  Writes, for the frame
  * `frame_dev` (not yet passed to a forward call), the mask that the threshold
  * test of the INPUT site `in` would give after these steps, as bytes 0/1 to be
@@ -317,6 +371,10 @@ typedef enum {
                              /* residual skip (identity edge) instead of a launch of its own; */
                              /* such an edge then adds nothing to the compute-list statistics  */
                              /* of its destination.  0: one launch per edge                  */
+    MDCNN_OPT_PIPE_GROUP = 10, /* mdcnn_frames: forward calls per group of the frame pipeline (1..64, */
+                             /* default 1): smaller groups let a frame follow the one before it more */
+                             /* closely, at one more event and wait per group and frame            */
+    MDCNN_OPT_PIPE_MODE = 11, /* mdcnn_frames: 1 (default) whole frames on streams, 0 runs of calls on streams */
     MDCNN_OPT_STREAMS = 9    /* 2..4: mdcnn_frame, mdcnn_frame_crop and mdcnn_frame_batch put       */
                              /* independent branches of the network on up to this many streams:     */
                              /* the caller's plus the library's own (per host thread, default     */

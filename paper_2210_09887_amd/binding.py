@@ -20,7 +20,7 @@ MDCNN_SITE_INPUT, MDCNN_SITE_PREACT, MDCNN_SITE_OUTPUT = 0, 1, 2
  MDCNN_VIEW_CLIST, MDCNN_VIEW_STATS, MDCNN_VIEW_OUT, MDCNN_VIEW_POOL_PREV, MDCNN_VIEW_CROP_OUT,
  MDCNN_VIEW_PENDING) = range(11)
 MDCNN_OPT_CONV_PATH, MDCNN_OPT_PROFILE, MDCNN_OPT_CONV_TILE, MDCNN_OPT_CONV_PIPE, MDCNN_OPT_CONV_XCD, MDCNN_OPT_CONV_KC, \
-    MDCNN_OPT_CONV_HALO, MDCNN_OPT_CONV_HALO_SUB, MDCNN_OPT_FUSE_SKIP, MDCNN_OPT_STREAMS = range(10)
+    MDCNN_OPT_CONV_HALO, MDCNN_OPT_CONV_HALO_SUB, MDCNN_OPT_FUSE_SKIP, MDCNN_OPT_STREAMS, MDCNN_OPT_PIPE_GROUP, MDCNN_OPT_PIPE_MODE = range(12)
 KERNEL_CLASSES = ["shift", "step1", "lists", "conv_mfma", "conv_plain", "identity", "readout", "pool"]
 FLAG_N, FLAG_U, FLAG_M = 1, 2, 4
 STATE_UNSEEN, STATE_DIRTY = 1, 2
@@ -30,7 +30,7 @@ STATUS_NAMES = {0: "OK", 1: "ERR_NULL", 2: "ERR_SHAPE", 3: "ERR_DTYPE", 4: "ERR_
 
 EXPORTS = ["mdcnn_conv_border", "mdcnn_buffer_bytes", "mdcnn_create_buffer", "mdcnn_destroy_buffer",
            "mdcnn_shift_camera", "mdcnn_set_crop", "mdcnn_layer_forward", "mdcnn_net_create", "mdcnn_net_destroy",
-           "mdcnn_frame", "mdcnn_frame_crop", "mdcnn_frame_batch", "mdcnn_frame_plan", "mdcnn_input_mask", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read",
+           "mdcnn_frame", "mdcnn_frame_crop", "mdcnn_frame_batch", "mdcnn_frame_plan", "mdcnn_frames", "mdcnn_frames_plan", "mdcnn_input_mask", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read",
            "mdcnn_pack_weights", "mdcnn_last_error", "mdcnn_version"]
 
 
@@ -81,6 +81,8 @@ def lib():
         L.mdcnn_frame.argtypes = [vp, vp, vp, C.c_int, C.c_int, vp, sz, vp, ip]
         L.mdcnn_frame_batch.argtypes = [C.POINTER(vp), C.c_int, C.POINTER(vp), C.POINTER(vp), ip, ip, C.POINTER(vp), sz, vp, ip]
         L.mdcnn_frame_plan.argtypes = [vp, C.c_int, ip, ip, C.c_int, ip, ip]
+        L.mdcnn_frames.argtypes = [vp, C.c_int, C.POINTER(vp), C.POINTER(vp), ip, ip, C.POINTER(vp), sz, C.c_int, vp, ip]
+        L.mdcnn_frames_plan.argtypes = [vp, C.c_int, ip, ip, ip, C.c_int, ip, C.c_int, ip, C.c_int, ip, ip]
         L.mdcnn_input_mask.argtypes = [vp, vp, vp, C.POINTER(mdcnn_mask_params), vp, sz, vp]
         L.mdcnn_read_view.argtypes = [vp, C.c_int, vp, sz, vp]
         L.mdcnn_write_view.argtypes = [vp, C.c_int, vp, sz, vp]
@@ -215,6 +217,30 @@ def mdcnn_frame_plan(net: int, streams: int = 0):
     _check(lib().mdcnn_frame_plan(net, int(streams), so, wo, n.value, None, None))
     waits = [[w for w in (wo[2 * i], wo[2 * i + 1]) if w >= 0] for i in range(n.value)]
     return list(so), waits, ns.value
+
+
+def mdcnn_frames(net: int, frame_ptrs, forced_ptrs, dty, dtx, out_ptrs, out_bytes: int, depth: int = 0, stream: int = 0):
+    """len(frame_ptrs) consecutive frames of one video, up to `depth` in flight; returns the reset decisions."""
+    n = len(frame_ptrs)
+    r = (C.c_int * n)()
+    forced = None if forced_ptrs is None else (C.c_void_p * n)(*forced_ptrs)
+    _check(lib().mdcnn_frames(net, n, (C.c_void_p * n)(*frame_ptrs), forced,
+                              (C.c_int * n)(*[int(v) for v in dty]), (C.c_int * n)(*[int(v) for v in dtx]),
+                              (C.c_void_p * n)(*out_ptrs), out_bytes, int(depth), stream, r))
+    return [bool(v) for v in r]
+
+
+def mdcnn_frames_plan(net: int, n_sites: int, depth: int = 0):
+    """Frame pipeline of `net` as a dict: per group `first_call`, `wait_call` (call of the frame before it waits for)
+    and `init_call` (call whose delta launch carries its initialisation, -1: own launch); `group_of_site`;
+    `stream_of_call` (one more entry for the readout; -1: frame f on stream f % depth); `n_calls`."""
+    n, nc = C.c_int(), C.c_int()
+    _check(lib().mdcnn_frames_plan(net, int(depth), None, None, None, 0, None, 0, None, 0, C.byref(n), C.byref(nc)))
+    a, b, c = (C.c_int * n.value)(), (C.c_int * n.value)(), (C.c_int * n.value)()
+    g, so = (C.c_int * n_sites)(*([-1] * n_sites)), (C.c_int * (nc.value + 1))()
+    _check(lib().mdcnn_frames_plan(net, int(depth), a, b, c, n.value, g, n_sites, so, nc.value + 1, None, None))
+    return dict(first_call=list(a), wait_call=list(b), init_call=list(c), group_of_site=list(g), stream_of_call=list(so),
+                n_calls=nc.value)
 
 
 def mdcnn_input_mask(buf: int, frame_ptr: int, roi_ptr, prm: mdcnn_mask_params, mask_ptr: int, mask_bytes: int, stream: int = 0):

@@ -167,11 +167,8 @@ __device__ __forceinline__ void fill_items(const FillJob& j, unsigned lb) {
     }
 }
 
-__global__ __launch_bounds__(256) void k_shift_fill(FillBatch fb) {
-    int ji = 0;
-    while (ji + 1 < fb.n && blockIdx.x >= fb.j[ji + 1].block_begin) ++ji;
-    const FillJob& j = fb.j[ji];
-    const unsigned lb = blockIdx.x - j.block_begin;
+// Block lb of the initialisation job j.
+__device__ __forceinline__ void fill_block(const FillJob& j, unsigned lb) {
     if (lb == 0 && j.reset_counters && (int)threadIdx.x < (j.reset_counters == 2 ? kNumCounters : kNumPerFrame))
         j.counters[threadIdx.x] = 0;
     if (lb == 0 && j.reset_counters == 2) {                // first reset: clear the per-segment running sums
@@ -183,6 +180,13 @@ __global__ __launch_bounds__(256) void k_shift_fill(FillBatch fb) {
     } else {
         if (j.C % 4 == 0) fill_items<float, 4>(j, lb); else fill_items<float, 1>(j, lb);
     }
+}
+
+__global__ __launch_bounds__(256) void k_shift_fill(FillBatch fb) {
+    int ji = 0;
+    while (ji + 1 < fb.n && blockIdx.x >= fb.j[ji + 1].block_begin) ++ji;
+    const FillJob& j = fb.j[ji];
+    fill_block(j, blockIdx.x - j.block_begin);
 }
 
 hipError_t launch_shift_fill(const FillBatch& fb, hipStream_t st) {
@@ -225,11 +229,8 @@ __device__ __forceinline__ bool crop_state(const SiteDev& s, int pix, bool write
 }
 
 template <typename T, int G, int CH>
-__global__ __launch_bounds__(256) void k_step1(Step1Batch bt) {
-    const SiteDev& s = bt.s[blockIdx.z];
-    const SkipDev& skip = bt.skip[blockIdx.z];
-    const T* __restrict__ X = (const T*)bt.X[blockIdx.z];
-    const uint8_t* __restrict__ forced = bt.forced[blockIdx.z];
+__device__ __forceinline__ void step1_block(const SiteDev& s, const SkipDev& skip, const T* __restrict__ X,
+                                            const uint8_t* __restrict__ forced) {
     constexpr int VEC = V16<T>::N;
     constexpr int PPB = 256 / G;
     const int tid = threadIdx.x;
@@ -307,13 +308,28 @@ __global__ __launch_bounds__(256) void k_step1(Step1Batch bt) {
     }
 }
 
+template <typename T, int G, int CH>
+__global__ __launch_bounds__(256) void k_step1(Step1Batch bt) {
+    step1_block<T, G, CH>(bt.s[blockIdx.z], bt.skip[blockIdx.z], (const T*)bt.X[blockIdx.z], bt.forced[blockIdx.z]);
+}
+
+// One site, and in the same launch the initialisation jobs of other sites (blocks past the site's own).
+template <typename T, int G, int CH>
+__global__ __launch_bounds__(256) void k_step1_fill(Step1Fill a) {
+    if (blockIdx.x < a.step1_blocks) {
+        step1_block<T, G, CH>(a.s, a.skip, (const T*)a.X, a.forced);
+        return;
+    }
+    const unsigned b = blockIdx.x - a.step1_blocks;
+    int ji = 0;
+    while (ji + 1 < a.n && b >= a.j[ji + 1].block_begin) ++ji;
+    fill_block(a.j[ji], b - a.j[ji].block_begin);
+}
+
 // Any channel count: one lane per pixel, scalar accesses.
 template <typename T>
-__global__ __launch_bounds__(256) void k_step1_scalar(Step1Batch bt) {
-    const SiteDev& s = bt.s[blockIdx.z];
-    const SkipDev& skip = bt.skip[blockIdx.z];
-    const T* __restrict__ X = (const T*)bt.X[blockIdx.z];
-    const uint8_t* __restrict__ forced = bt.forced[blockIdx.z];
+__device__ __forceinline__ void step1_scalar_block(const SiteDev& s, const SkipDev& skip, const T* __restrict__ X,
+                                                   const uint8_t* __restrict__ forced) {
     const int tid = threadIdx.x;
     const int pix = blockIdx.x * 256 + tid;
     const int HW = s.H * s.W;
@@ -368,6 +384,23 @@ __global__ __launch_bounds__(256) void k_step1_scalar(Step1Batch bt) {
     }
 }
 
+template <typename T>
+__global__ __launch_bounds__(256) void k_step1_scalar(Step1Batch bt) {
+    step1_scalar_block<T>(bt.s[blockIdx.z], bt.skip[blockIdx.z], (const T*)bt.X[blockIdx.z], bt.forced[blockIdx.z]);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_step1_scalar_fill(Step1Fill a) {
+    if (blockIdx.x < a.step1_blocks) {
+        step1_scalar_block<T>(a.s, a.skip, (const T*)a.X, a.forced);
+        return;
+    }
+    const unsigned b = blockIdx.x - a.step1_blocks;
+    int ji = 0;
+    while (ji + 1 < a.n && b >= a.j[ji + 1].block_begin) ++ji;
+    fill_block(a.j[ji], b - a.j[ji].block_begin);
+}
+
 // Split C/VEC chunks into G lanes x CH chunks per lane (G a power of two <= 64,
 // CH <= 4); returns false when the scalar kernel has to be used.
 static bool step1_shape(int C, int vec, int& G, int& CH) {
@@ -390,32 +423,63 @@ static void step1_g(const Step1Batch& bt, int CH, dim3 grid, hipStream_t st) {
         default: k_step1<T, G, 4><<<grid, dim3(256), 0, st>>>(bt); break;
     }
 }
+template <typename T, int G>
+static void step1_g(const Step1Fill& a, int CH, dim3 grid, hipStream_t st) {
+    switch (CH) {
+        case 1: k_step1_fill<T, G, 1><<<grid, dim3(256), 0, st>>>(a); break;
+        case 2: k_step1_fill<T, G, 2><<<grid, dim3(256), 0, st>>>(a); break;
+        case 3: k_step1_fill<T, G, 3><<<grid, dim3(256), 0, st>>>(a); break;
+        default: k_step1_fill<T, G, 4><<<grid, dim3(256), 0, st>>>(a); break;
+    }
+}
+static void step1_scalar(const Step1Batch& bt, dim3 grid, hipStream_t st, float) { k_step1_scalar<float><<<grid, dim3(256), 0, st>>>(bt); }
+static void step1_scalar(const Step1Batch& bt, dim3 grid, hipStream_t st, f16) { k_step1_scalar<f16><<<grid, dim3(256), 0, st>>>(bt); }
+static void step1_scalar(const Step1Fill& a, dim3 grid, hipStream_t st, float) { k_step1_scalar_fill<float><<<grid, dim3(256), 0, st>>>(a); }
+static void step1_scalar(const Step1Fill& a, dim3 grid, hipStream_t st, f16) { k_step1_scalar_fill<f16><<<grid, dim3(256), 0, st>>>(a); }
 
-template <typename T>
-static hipError_t step1_t(const Step1Batch& bt, int n, hipStream_t st) {
+// Blocks the step-1 kernel of a site takes per grid layer.
+static unsigned step1_blocks_of(const SiteDev& s) {
     int G = 0, CH = 0;
-    const SiteDev& s = bt.s[0];
     const int HW = s.H * s.W;
+    if (!step1_shape(s.C, s.dtype == MDCNN_F16 ? V16<f16>::N : V16<float>::N, G, CH)) return (unsigned)((HW + 255) / 256);
+    const int ppb = 256 / G;
+    return (unsigned)((HW + ppb - 1) / ppb);
+}
+
+// Args: Step1Batch (n grid layers) or Step1Fill (one site; `extra` blocks of initialisation jobs follow its own)
+template <typename T, typename Args>
+static hipError_t step1_t(const Args& a, const SiteDev& s, int n, unsigned extra, hipStream_t st) {
+    int G = 0, CH = 0;
+    const dim3 grid(step1_blocks_of(s) + extra, 1, n);
     if (!step1_shape(s.C, V16<T>::N, G, CH)) {
-        k_step1_scalar<T><<<dim3((HW + 255) / 256, 1, n), dim3(256), 0, st>>>(bt);
+        step1_scalar(a, grid, st, T{});
         return hipGetLastError();
     }
-    const int ppb = 256 / G;
-    dim3 grid((HW + ppb - 1) / ppb, 1, n);
     switch (G) {
-        case 1: step1_g<T, 1>(bt, CH, grid, st); break;
-        case 2: step1_g<T, 2>(bt, CH, grid, st); break;
-        case 4: step1_g<T, 4>(bt, CH, grid, st); break;
-        case 8: step1_g<T, 8>(bt, CH, grid, st); break;
-        case 16: step1_g<T, 16>(bt, CH, grid, st); break;
-        case 32: step1_g<T, 32>(bt, CH, grid, st); break;
-        default: step1_g<T, 64>(bt, CH, grid, st); break;
+        case 1: step1_g<T, 1>(a, CH, grid, st); break;
+        case 2: step1_g<T, 2>(a, CH, grid, st); break;
+        case 4: step1_g<T, 4>(a, CH, grid, st); break;
+        case 8: step1_g<T, 8>(a, CH, grid, st); break;
+        case 16: step1_g<T, 16>(a, CH, grid, st); break;
+        case 32: step1_g<T, 32>(a, CH, grid, st); break;
+        default: step1_g<T, 64>(a, CH, grid, st); break;
     }
     return hipGetLastError();
 }
 
 hipError_t launch_step1(const Step1Batch& bt, int n, hipStream_t st) {
-    return bt.s[0].dtype == MDCNN_F16 ? step1_t<f16>(bt, n, st) : step1_t<float>(bt, n, st);
+    return bt.s[0].dtype == MDCNN_F16 ? step1_t<f16>(bt, bt.s[0], n, 0u, st) : step1_t<float>(bt, bt.s[0], n, 0u, st);
+}
+
+hipError_t launch_step1_fill(Step1Fill& a, hipStream_t st) {
+    if (a.n < 0 || a.n > kMaxRiders) return hipErrorInvalidValue;
+    a.step1_blocks = step1_blocks_of(a.s);
+    unsigned extra = 0;
+    for (int k = 0; k < a.n; ++k) {
+        a.j[k].block_begin = extra;
+        extra += fill_blocks(a.j[k]);
+    }
+    return a.s.dtype == MDCNN_F16 ? step1_t<f16>(a, a.s, 1, extra, st) : step1_t<float>(a, a.s, 1, extra, st);
 }
 
 // ---------------------------------------------------------------------------

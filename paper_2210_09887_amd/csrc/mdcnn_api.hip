@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 #include <vector>
 
@@ -19,6 +20,8 @@ int g_conv_path = 0;
 int g_fuse_skip = 1;      // mdcnn_frame: residual skips are added by the step-1 kernel of their source
 int g_profile = 0;
 int g_streams = 0;        // mdcnn_frame: independent branches of the network go to up to this many streams; 0: decide per network
+int g_pipe_group = 1;     // mdcnn_frames: forward calls per group of the frame pipeline
+int g_pipe_mode = 1;      // mdcnn_frames: 1 whole frames on streams, 0 runs of layers on streams
 
 // Profiling mode: every kernel launch is bracketed by a pair of events on its
 // own stream; mdcnn_profile_read waits for them and sums the times per class.
@@ -132,12 +135,42 @@ struct Plan {
     std::vector<PlanNode> nodes;
 };
 
+// Plan of a run of frames that overlap in time (mdcnn_frames).  The forward calls of a frame, in
+// site order, are cut into groups of `group_calls`.  The sites a group is the first to touch are
+// initialised just before it: by a launch of their own at the head of the frame for the first group,
+// by spare blocks of the step-1 launch of the call before the group for the others (that launch and
+// the rest of its call do not touch them, or the group would not be the first).  The initialisation,
+// and with it everything the frame does to those sites, has to follow whatever the frame before
+// does to them, the last of which is the forward call of the highest such site (the readout for an
+// OUTPUT site): the stream waits for that before the launch that carries the initialisation.
+struct PipeGroup {
+    int call0, call1;          // forward calls [call0, call1)
+    std::vector<int> fill;     // sites initialised for the group
+    int wait_call;             // call of the frame before that must have finished (n_calls: its readout), -1: none
+};
+struct PipePlan {
+    int key = -1;              // group size, streams and mode the plan was made for (-1: no plan yet)
+    std::vector<int> call_site, call_e0, call_e1;
+    std::vector<PipeGroup> groups;
+    // Streams.  Mode 1, frames: frame f goes to stream f % streams as a whole (seg_of_call is all zero).
+    // Mode 0, stages: the calls are cut into as many runs as there are streams, of about equal cost, and
+    // run k of every frame goes to stream k - frames follow each other on a stream in order, so only what
+    // crosses from one run to another needs an event.
+    int streams = 1, mode = 0;
+    std::vector<int> seg_of_call;      // per call, and one more entry for the readout
+    std::vector<int> event_of_call;    // per call (and the readout): slot of the event recorded after it, or -1
+    std::vector<char> forward;         // per call: its stream differs from that of the call before (same frame)
+    int n_events = 0;
+    int stream_of(int frame, int call) const { return mode ? frame % streams : seg_of_call[(size_t)call]; }
+};
+
 struct mdcnn_net {
     std::vector<mdcnn_buffer*> sites;
     std::vector<int> esrc, edst;
     std::vector<mdcnn_conv_desc> edges;
     size_t out_bytes;
     Plan plan;
+    PipePlan pipe;
 };
 
 namespace {
@@ -251,6 +284,7 @@ mdcnn_status validate_forward(const mdcnn_buffer* in, const void* frame, const m
 // from ins[b] along edges[b][0 .. n_edges) to outs[b][0 .. n_edges).
 // fuse_skip: index of an identity edge whose add is done by the step-1 kernel (its
 // destination is touched there and the edge gets no launch of its own), or -1.
+// riders (n == 1 only): jobs[riders[0 .. n_riders)] are run by spare blocks of the step-1 launch.
 // Streams and events of one multi-stream frame.  Every wait is on an event that was recorded
 // earlier in the same call, so no stream can wait for something that never happens.
 constexpr int kMaxStreams = 4;
@@ -280,7 +314,8 @@ struct Sched {
 
 mdcnn_status do_forward(int n, mdcnn_buffer* const* ins, const void* const* frames, const uint8_t* const* forced,
                         const mdcnn_conv_desc* const* edges, mdcnn_buffer* const* const* outs, int n_edges,
-                        hipStream_t st, int fuse_skip = -1, Sched* sc = nullptr) {
+                        hipStream_t st, int fuse_skip = -1, Sched* sc = nullptr, const FillJob* jobs = nullptr,
+                        const int* riders = nullptr, int n_riders = 0) {
     static thread_local Step1Batch sb;                     // 3.4 KiB each: kept off the stack
     static thread_local EdgeBatch eb;
     for (int b = 0; b < n; ++b) {
@@ -298,7 +333,17 @@ mdcnn_status do_forward(int n, mdcnn_buffer* const* ins, const void* const* fram
         }
     }
     if (sc) st = sc->begin();
-    hipError_t err = timed(kClsStep1, st, [&] { return launch_step1(sb, n, st); });
+    hipError_t err;
+    if (n == 1 && n_riders > 0) {
+        // initialisation jobs of other sites, which nothing in this launch touches, ride along
+        static thread_local Step1Fill sf;
+        sf.s = sb.s[0]; sf.skip = sb.skip[0]; sf.X = sb.X[0]; sf.forced = sb.forced[0];
+        sf.n = n_riders;
+        for (int k = 0; k < n_riders; ++k) sf.j[k] = jobs[riders[k]];
+        err = timed(kClsStep1, st, [&] { return launch_step1_fill(sf, st); });
+    } else {
+        err = timed(kClsStep1, st, [&] { return launch_step1(sb, n, st); });
+    }
     if (sc) sc->end();
     if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "step-1 launch: %s", hipGetErrorString(err));
     auto launch_edge = [&](int idx) -> mdcnn_status {
@@ -492,6 +537,99 @@ hipError_t aux_prepare(int streams, size_t events) {
     return hipSuccess;
 }
 
+// Host part of a camera shift: decides between growth and full reset, moves the buffers and
+// makes the initialisation job of every buffer (jobs[i] for bufs[i]; block_begin is left to the
+// launch).  Nothing is launched.
+mdcnn_status shift_jobs(mdcnn_buffer* const* bufs, int n, int dty, int dtx, std::vector<FillJob>& jobs, bool* full_out) {
+    if (!bufs || n < 1) return fail(MDCNN_ERR_NULL, "no buffers");
+    for (int i = 0; i < n; ++i) {
+        if (!bufs[i]) return fail(MDCNN_ERR_NULL, "buffer %d is NULL", i);
+        const mdcnn_buffer *a = bufs[0], *b = bufs[i];
+        if (a->fresh != b->fresh || a->r_up != b->r_up || a->r_down != b->r_down || a->r_left != b->r_left ||
+            a->r_right != b->r_right)
+            return fail(MDCNN_ERR_STATE, "buffer %d has a different shift history than buffer 0", i);
+    }
+    const mdcnn_buffer* f = bufs[0];
+    bool full = f->fresh;
+    full |= (dtx > 0 && f->r_right) || (dtx < 0 && f->r_left) || (dty > 0 && f->r_down) || (dty < 0 && f->r_up);
+    for (int i = 0; i < n; ++i) {
+        const mdcnn_buffer_desc& d = bufs[i]->d;
+        const long long sy = (long long)dty * d.tile, sx = (long long)dtx * d.tile;
+        full |= (sy >= d.H || -sy >= d.H || sx >= d.W || -sx >= d.W);
+    }
+    jobs.resize((size_t)n);
+    for (int i = 0; i < n; ++i) {
+        mdcnn_buffer* b = bufs[i];
+        const mdcnn_buffer_desc& d = b->d;
+        const long long sy = (long long)dty * d.tile, sx = (long long)dtx * d.tile;
+        b->gy += sy;
+        b->gx += sx;
+        refresh_origins(b);
+        FillJob j{};
+        j.A = b->dev.A; j.P = b->dev.P; j.flags = b->dev.flags; j.bias = b->dev.bias; j.counters = b->dev.counters;
+        j.lacc = b->dev.lacc; j.cacc = b->dev.cacc; j.lcnt = b->dev.lcnt; j.ccnt = b->dev.ccnt;
+        j.n_lacc = 2 * b->L.nseg_l; j.n_cacc = b->L.nseg_c;
+        j.s_off = b->dev.s_off;
+        j.y_off = d.crops && d.pool_prev ? (unsigned)((b->L.Y - b->L.A) / 256) : 0u;
+        j.H = d.H; j.W = d.W; j.C = d.C; j.Hp = b->L.Hp; j.Wp = b->L.Wp;
+        j.a_oy = b->dev.a_oy; j.a_ox = b->dev.a_ox; j.p_oy = b->dev.p_oy; j.p_ox = b->dev.p_ox;
+        j.dtype = d.dtype;
+        if (!full) {
+            // the old window, expressed in coordinates of the new one, is shifted by (-sy, -sx)
+            auto keep = [](int ext, long long s, int& lo, int& hi) {   // |s| < ext here
+                lo = -s > 0 ? (int)-s : 0;
+                hi = ext - s < ext ? (int)(ext - s) : ext;
+                if (hi < lo) hi = lo;
+            };
+            keep(j.Hp, sy, j.py0, j.py1);
+            keep(j.Wp, sx, j.px0, j.px1);
+            keep(j.H, sy, j.ay0, j.ay1);
+            keep(j.W, sx, j.ax0, j.ax1);
+        }
+        auto outside = [](int Hn, int Wn, int y0, int y1, int x0, int x1) {
+            return (y0 + (Hn - y1)) * Wn + (y1 - y0) * (x0 + (Wn - x1));
+        };
+        j.nP = j.P ? outside(j.Hp, j.Wp, j.py0, j.py1, j.px0, j.px1) : 0;
+        j.nA = j.A ? outside(j.H, j.W, j.ay0, j.ay1, j.ax0, j.ax1) : 0;
+        j.reset_counters = b->fresh ? 2 : 1;             // per-frame counters start at zero every frame
+        jobs[(size_t)i] = j;
+        if (full) {
+            b->r_up = b->r_down = b->r_left = b->r_right = false;
+            b->fresh = false;
+        } else {
+            // growing in one direction overwrites the stash of the opposite side
+            if (dtx > 0) b->r_left = true;
+            if (dtx < 0) b->r_right = true;
+            if (dty > 0) b->r_up = true;
+            if (dty < 0) b->r_down = true;
+        }
+    }
+    *full_out = full;
+    return MDCNN_OK;
+}
+
+// Launches jobs[which[0 .. count)] (which == nullptr: jobs[0 .. count)), kMaxFillJobs to a launch.
+hipError_t launch_fill_jobs(const FillJob* jobs, const int* which, int count, hipStream_t st) {
+    FillBatch fb{};
+    auto flush = [&]() -> hipError_t {
+        hipError_t err = timed(kClsShift, st, [&] { return launch_shift_fill(fb, st); });
+        fb.n = 0;
+        fb.total_blocks = 0;
+        return err;
+    };
+    for (int k = 0; k < count; ++k) {
+        FillJob j = jobs[which ? which[k] : k];
+        j.block_begin = fb.total_blocks;
+        fb.j[fb.n++] = j;
+        fb.total_blocks += fill_blocks(j);
+        if (fb.n == kMaxFillJobs) {
+            hipError_t err = flush();
+            if (err != hipSuccess) return err;
+        }
+    }
+    return fb.n ? flush() : hipSuccess;
+}
+
 size_t crop_pixels(const mdcnn_buffer* b) {                // sites without crops: the view
     if (!b->d.crops) return (size_t)b->d.H * b->d.W;
     return (size_t)(b->dev.cy1() - b->dev.cy0()) * (size_t)(b->dev.cx1() - b->dev.cx0());
@@ -589,6 +727,206 @@ mdcnn_status frame_batch(mdcnn_net* const* nets, int n, const void* const* frame
     return MDCNN_OK;
 }
 
+void make_pipe_plan(const mdcnn_net* net, int group_calls, int streams, int mode, PipePlan& pp) {
+    const int n_sites = (int)net->sites.size(), n_edges = (int)net->edges.size();
+    pp = PipePlan{};
+    pp.key = (group_calls * 8 + streams) * 2 + mode;
+    pp.streams = streams;
+    pp.mode = mode;
+    std::vector<int> call_of(n_sites, -1);
+    std::vector<double> cost;
+    int e0 = 0;
+    for (int i = 0; i < n_sites; ++i) {
+        if (net->sites[i]->d.kind == MDCNN_SITE_OUTPUT) continue;
+        int e1 = e0;
+        while (e1 < n_edges && net->esrc[e1] == i) ++e1;
+        call_of[i] = (int)pp.call_site.size();
+        pp.call_site.push_back(i);
+        pp.call_e0.push_back(e0);
+        pp.call_e1.push_back(e1);
+        // a delta launch counts one, a convolution launch four (measured on the benchmark networks: 5-8 us against 13-27 us)
+        const int fuse = fused_skip(net, e0, e1);
+        cost.push_back(1.0 + 4.0 * ((e1 - e0) - (fuse >= 0 ? 1 : 0)));
+        e0 = e1;
+    }
+    const int n_calls = (int)pp.call_site.size();
+    // runs of calls of about equal cost: the smallest possible largest run (dynamic programme over the cut positions)
+    pp.seg_of_call.assign((size_t)n_calls + 1, 0);
+    if (mode == 0 && streams > 1) {
+        const int S = streams < n_calls ? streams : n_calls;
+        std::vector<double> pre((size_t)n_calls + 1, 0.0);
+        for (int c = 0; c < n_calls; ++c) pre[(size_t)c + 1] = pre[(size_t)c] + cost[(size_t)c];
+        std::vector<std::vector<double>> best((size_t)S + 1, std::vector<double>((size_t)n_calls + 1, 1e300));
+        std::vector<std::vector<int>> cut((size_t)S + 1, std::vector<int>((size_t)n_calls + 1, 0));
+        best[0][0] = 0.0;
+        for (int k = 1; k <= S; ++k)
+            for (int c = k; c <= n_calls; ++c)
+                for (int b = k - 1; b < c; ++b) {
+                    const double run = pre[(size_t)c] - pre[(size_t)b];
+                    const double v = best[(size_t)k - 1][(size_t)b] > run ? best[(size_t)k - 1][(size_t)b] : run;
+                    if (v < best[(size_t)k][(size_t)c]) { best[(size_t)k][(size_t)c] = v; cut[(size_t)k][(size_t)c] = b; }
+                }
+        int c = n_calls;
+        for (int k = S; k >= 1; --k) {
+            const int b = cut[(size_t)k][(size_t)c];
+            for (int q = b; q < c; ++q) pp.seg_of_call[(size_t)q] = k - 1;
+            c = b;
+        }
+        pp.seg_of_call[(size_t)n_calls] = S - 1;              // the readout follows the last call
+    }
+    pp.forward.assign((size_t)n_calls, 0);
+    for (int c = 1; c < n_calls; ++c) pp.forward[(size_t)c] = pp.seg_of_call[(size_t)c] != pp.seg_of_call[(size_t)c - 1];
+    pp.event_of_call.assign((size_t)n_calls + 1, -1);
+    std::vector<char> filled(n_sites, 0);
+    for (int c0 = 0; c0 < n_calls; c0 += group_calls) {
+        PipeGroup g{c0, c0 + group_calls < n_calls ? c0 + group_calls : n_calls, {}, -1};
+        const bool last = g.call1 == n_calls;
+        for (int c = g.call0; c < g.call1; ++c) {
+            auto touch = [&](int site) {
+                if (filled[site]) return;
+                filled[site] = 1;
+                g.fill.push_back(site);
+                const int w = call_of[site] >= 0 ? call_of[site] : n_calls;
+                g.wait_call = w > g.wait_call ? w : g.wait_call;
+            };
+            touch(pp.call_site[c]);
+            for (int e = pp.call_e0[c]; e < pp.call_e1[c]; ++e) touch(net->edst[e]);
+        }
+        if (last)                                              // sites nothing leads to are still initialised
+            for (int i = 0; i < n_sites; ++i)
+                if (!filled[i]) {
+                    filled[i] = 1;
+                    g.fill.push_back(i);
+                    g.wait_call = n_calls;
+                }
+        if (g.wait_call >= 0 && pp.event_of_call[g.wait_call] < 0) pp.event_of_call[g.wait_call] = pp.n_events++;
+        pp.groups.push_back(g);
+    }
+    for (int c = 1; c < n_calls; ++c)                         // the end of a run of calls is waited for by the next run
+        if (pp.forward[(size_t)c] && pp.event_of_call[(size_t)c - 1] < 0) pp.event_of_call[(size_t)c - 1] = pp.n_events++;
+}
+
+constexpr int kMaxFrames = 4096;
+constexpr int kDefaultDepth = 4;
+
+// n_frames consecutive frames of one network on `depth` streams (stream 0 is the caller's).  The
+// launches of a frame are those of mdcnn_frame on one stream, in the same order, except that the
+// initialisation of a camera shift is split up and rides along (see PipeGroup).  Frames are issued
+// one after the other; two launches that touch the same site are ordered by being on the same
+// stream or by an event: within a frame where the stream changes between two calls, across frames
+// by the waits of the plan.  Every site sees the same sequence of launches as with one frame at a
+// time, so the results are the same bit for bit.
+mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, const uint8_t* const* forced,
+                       const int* dty, const int* dtx, void* const* outs_dev, int depth, hipStream_t user, int* did_full_reset) {
+    const int key = (g_pipe_group * 8 + depth) * 2 + g_pipe_mode;
+    if (net->pipe.key != key) make_pipe_plan(net, g_pipe_group, depth, g_pipe_mode, net->pipe);
+    const PipePlan& pp = net->pipe;
+    const int n_calls = (int)pp.call_site.size(), ring = 3;
+    // events: ring x n_events for the plan, then one per stream for fork and join
+    const size_t ev_sync = (size_t)ring * pp.n_events;
+    hipError_t err = aux_prepare(depth, ev_sync + kMaxStreams);
+    hipStream_t s[kMaxStreams];
+    s[0] = user;
+    for (int k = 1; k < depth; ++k) s[k] = g_aux.s[k - 1];
+    if (err == hipSuccess && depth > 1) err = hipEventRecord(g_aux.events[ev_sync], user);
+    for (int k = 1; k < depth && err == hipSuccess; ++k) err = hipStreamWaitEvent(s[k], g_aux.events[ev_sync], 0);
+    if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "stream set-up: %s", hipGetErrorString(err));
+    // whatever happens below, the caller's stream waits for the other streams before the call returns
+    struct Join {
+        hipStream_t* s; int depth; size_t base; bool done;
+        hipError_t run() {
+            hipError_t err = hipSuccess;
+            for (int k = 1; !done && k < depth; ++k) {
+                hipError_t e = hipEventRecord(g_aux.events[base + k], s[k]);
+                if (e == hipSuccess) e = hipStreamWaitEvent(s[0], g_aux.events[base + k], 0);
+                if (e != hipSuccess && err == hipSuccess) err = e;
+            }
+            done = true;
+            return err;
+        }
+        ~Join() { (void)run(); }
+    } join{s, depth, ev_sync, false};
+    static thread_local std::vector<FillJob> jobs;
+    std::vector<mdcnn_buffer*> outs_flat;
+    // which events of a frame somebody on another stream waits for (those recorded for nobody cost host time)
+    std::vector<char> wanted((size_t)n_calls + 1, 0);
+    for (size_t gi = 0; gi < pp.groups.size(); ++gi) {
+        const PipeGroup& g = pp.groups[gi];
+        const int carrier = gi ? pp.groups[gi - 1].call1 - 1 : 0;
+        if (g.wait_call >= 0 && (pp.mode == 1 || pp.seg_of_call[(size_t)g.wait_call] != pp.seg_of_call[(size_t)carrier])) wanted[(size_t)g.wait_call] = 1;
+    }
+    for (int c = 1; c < n_calls; ++c)
+        if (pp.forward[(size_t)c]) wanted[(size_t)c - 1] = 1;
+    for (int f = 0; f < n_frames; ++f) {
+        bool full = false;
+        mdcnn_status rc = shift_jobs(net->sites.data(), (int)net->sites.size(), dty[f], dtx[f], jobs, &full);
+        if (rc) return rc;
+        if (did_full_reset) did_full_reset[f] = full ? 1 : 0;
+        hipEvent_t* ev_prev = g_aux.events.data() + (size_t)((f + ring - 1) % ring) * pp.n_events;
+        hipEvent_t* ev_mine = g_aux.events.data() + (size_t)(f % ring) * pp.n_events;
+        auto record = [&](int call) {
+            return depth > 1 && wanted[(size_t)call] ? hipEventRecord(ev_mine[pp.event_of_call[(size_t)call]], s[pp.stream_of(f, call)]) : hipSuccess;
+        };
+        // the stream that is about to initialise the sites of group g waits for the frame before to be done with them
+        auto wait_for = [&](const PipeGroup& g, int carrier) {
+            if (f == 0 || depth == 1 || g.wait_call < 0) return hipSuccess;
+            const int mine = pp.stream_of(f, carrier);
+            if (pp.stream_of(f - 1, g.wait_call) == mine) return hipSuccess;      // same stream: in order anyway
+            return hipStreamWaitEvent(s[mine], ev_prev[pp.event_of_call[(size_t)g.wait_call]], 0);
+        };
+        for (size_t gi = 0; gi < pp.groups.size(); ++gi) {
+            const PipeGroup& g = pp.groups[gi];
+            if (gi == 0) {
+                err = wait_for(g, 0);
+                if (err == hipSuccess) err = launch_fill_jobs(jobs.data(), g.fill.data(), (int)g.fill.size(), s[pp.stream_of(f, 0)]);
+                if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: shift launch: %s", f, hipGetErrorString(err));
+            }
+            for (int c = g.call0; c < g.call1; ++c) {
+                hipStream_t st = s[pp.stream_of(f, c)];
+                if (c > 0 && pp.forward[(size_t)c] && depth > 1) {            // the calls so far ran on another stream
+                    err = hipStreamWaitEvent(st, ev_mine[pp.event_of_call[(size_t)c - 1]], 0);
+                    if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: event: %s", f, hipGetErrorString(err));
+                }
+                const int* riders = nullptr;
+                int n_riders = 0;
+                if (c == g.call1 - 1 && gi + 1 < pp.groups.size()) {          // the next group's sites are initialised here
+                    const PipeGroup& nx = pp.groups[gi + 1];
+                    err = wait_for(nx, c);
+                    if (err == hipSuccess && (int)nx.fill.size() > kMaxRiders) err = launch_fill_jobs(jobs.data(), nx.fill.data(), (int)nx.fill.size(), st);
+                    else { riders = nx.fill.data(); n_riders = (int)nx.fill.size(); }
+                    if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: shift launch: %s", f, hipGetErrorString(err));
+                }
+                const int i = pp.call_site[c], e0 = pp.call_e0[c], e1 = pp.call_e1[c], ne = e1 - e0;
+                outs_flat.resize((size_t)(ne > 0 ? ne : 1));
+                for (int e = e0; e < e1; ++e) outs_flat[(size_t)(e - e0)] = net->sites[net->edst[e]];
+                mdcnn_buffer* in = net->sites[i];
+                const mdcnn_conv_desc* edges = net->edges.data() + e0;
+                mdcnn_buffer* const* outs = outs_flat.data();
+                const void* X = frames[f];
+                const uint8_t* fm = forced ? forced[f] : nullptr;
+                rc = do_forward(1, &in, i == 0 ? &X : nullptr, i == 0 ? &fm : nullptr, &edges, &outs, ne, st, fused_skip(net, e0, e1), nullptr,
+                                jobs.data(), riders, n_riders);
+                if (rc) return rc;
+                err = record(c);
+                if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: event: %s", f, hipGetErrorString(err));
+            }
+        }
+        hipStream_t st = s[pp.stream_of(f, n_calls)];
+        char* o = (char*)outs_dev[f];
+        for (mdcnn_buffer* b : net->sites) {
+            if (b->d.kind != MDCNN_SITE_OUTPUT) continue;
+            err = timed(kClsReadout, st, [&] { return launch_read_view(b->dev, MDCNN_VIEW_OUT, o, st); });
+            if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: readout launch: %s", f, hipGetErrorString(err));
+            o += (size_t)b->d.H * b->d.W * b->d.C * esize(b->d.dtype);
+        }
+        err = record(n_calls);
+        if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: event: %s", f, hipGetErrorString(err));
+    }
+    err = join.run();
+    if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "stream synchronisation: %s", hipGetErrorString(err));
+    return MDCNN_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -600,6 +938,8 @@ mdcnn_status mdcnn_set_option(int option, int value) {
     if (option == MDCNN_OPT_CONV_PATH && value >= 0 && value <= 3) { g_conv_path = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_CONV_HALO && value >= 0 && value <= 2) { g_halo = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_STREAMS && value >= 0 && value <= kMaxStreams) { g_streams = value; return MDCNN_OK; }
+    if (option == MDCNN_OPT_PIPE_GROUP && value >= 1 && value <= 64) { g_pipe_group = value; return MDCNN_OK; }
+    if (option == MDCNN_OPT_PIPE_MODE && (value == 0 || value == 1)) { g_pipe_mode = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_FUSE_SKIP && (value == 0 || value == 1)) { g_fuse_skip = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_CONV_HALO_SUB && (value == 0 || value == 1 || value == 2 || value == 4)) { g_halo_sub = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_PROFILE && (value == 0 || value == 1)) { g_profile = value; return MDCNN_OK; }
@@ -706,90 +1046,12 @@ mdcnn_status mdcnn_destroy_buffer(mdcnn_buffer* buf) {
 }
 
 mdcnn_status mdcnn_shift_camera(mdcnn_buffer* const* bufs, int n, int dty, int dtx, void* stream, int* did_full_reset) {
-    if (!bufs || n < 1) return fail(MDCNN_ERR_NULL, "no buffers");
-    for (int i = 0; i < n; ++i) {
-        if (!bufs[i]) return fail(MDCNN_ERR_NULL, "buffer %d is NULL", i);
-        const mdcnn_buffer *a = bufs[0], *b = bufs[i];
-        if (a->fresh != b->fresh || a->r_up != b->r_up || a->r_down != b->r_down || a->r_left != b->r_left ||
-            a->r_right != b->r_right)
-            return fail(MDCNN_ERR_STATE, "buffer %d has a different shift history than buffer 0", i);
-    }
-    const mdcnn_buffer* f = bufs[0];
-    bool full = f->fresh;
-    full |= (dtx > 0 && f->r_right) || (dtx < 0 && f->r_left) || (dty > 0 && f->r_down) || (dty < 0 && f->r_up);
-    for (int i = 0; i < n; ++i) {
-        const mdcnn_buffer_desc& d = bufs[i]->d;
-        const long long sy = (long long)dty * d.tile, sx = (long long)dtx * d.tile;
-        full |= (sy >= d.H || -sy >= d.H || sx >= d.W || -sx >= d.W);
-    }
-    hipStream_t st = (hipStream_t)stream;
-    FillBatch fb{};
-    auto flush = [&]() -> hipError_t {
-        hipError_t err = timed(kClsShift, st, [&] { return launch_shift_fill(fb, st); });
-        fb.n = 0;
-        fb.total_blocks = 0;
-        return err;
-    };
-    for (int i = 0; i < n; ++i) {
-        mdcnn_buffer* b = bufs[i];
-        const mdcnn_buffer_desc& d = b->d;
-        const long long sy = (long long)dty * d.tile, sx = (long long)dtx * d.tile;
-        b->gy += sy;
-        b->gx += sx;
-        refresh_origins(b);
-        FillJob j{};
-        j.A = b->dev.A; j.P = b->dev.P; j.flags = b->dev.flags; j.bias = b->dev.bias; j.counters = b->dev.counters;
-        j.lacc = b->dev.lacc; j.cacc = b->dev.cacc; j.lcnt = b->dev.lcnt; j.ccnt = b->dev.ccnt;
-        j.n_lacc = 2 * b->L.nseg_l; j.n_cacc = b->L.nseg_c;
-        j.s_off = b->dev.s_off;
-        j.y_off = d.crops && d.pool_prev ? (unsigned)((b->L.Y - b->L.A) / 256) : 0u;
-        j.H = d.H; j.W = d.W; j.C = d.C; j.Hp = b->L.Hp; j.Wp = b->L.Wp;
-        j.a_oy = b->dev.a_oy; j.a_ox = b->dev.a_ox; j.p_oy = b->dev.p_oy; j.p_ox = b->dev.p_ox;
-        j.dtype = d.dtype;
-        if (!full) {
-            // the old window, expressed in coordinates of the new one, is shifted by (-sy, -sx)
-            auto keep = [](int ext, long long s, int& lo, int& hi) {   // |s| < ext here
-                lo = -s > 0 ? (int)-s : 0;
-                hi = ext - s < ext ? (int)(ext - s) : ext;
-                if (hi < lo) hi = lo;
-            };
-            keep(j.Hp, sy, j.py0, j.py1);
-            keep(j.Wp, sx, j.px0, j.px1);
-            keep(j.H, sy, j.ay0, j.ay1);
-            keep(j.W, sx, j.ax0, j.ax1);
-        }
-        auto outside = [](int Hn, int Wn, int y0, int y1, int x0, int x1) {
-            return (y0 + (Hn - y1)) * Wn + (y1 - y0) * (x0 + (Wn - x1));
-        };
-        j.nP = j.P ? outside(j.Hp, j.Wp, j.py0, j.py1, j.px0, j.px1) : 0;
-        j.nA = j.A ? outside(j.H, j.W, j.ay0, j.ay1, j.ax0, j.ax1) : 0;
-        j.reset_counters = b->fresh ? 2 : 1;             // per-frame counters start at zero every frame
-        const int vec = d.dtype == MDCNN_F16 ? 8 : 4;
-        const long long items = (long long)(j.nP + j.nA) * (d.C % vec == 0 ? d.C / vec : d.C);
-        long long blocks = (items + kFillItemsPerBlock - 1) / kFillItemsPerBlock;
-        if (blocks < 1) blocks = 1;
-        j.block_begin = fb.total_blocks;
-        fb.j[fb.n++] = j;
-        fb.total_blocks += (unsigned)blocks;
-        if (fb.n == kMaxFillJobs) {
-            hipError_t err = flush();
-            if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "shift launch: %s", hipGetErrorString(err));
-        }
-        if (full) {
-            b->r_up = b->r_down = b->r_left = b->r_right = false;
-            b->fresh = false;
-        } else {
-            // growing in one direction overwrites the stash of the opposite side
-            if (dtx > 0) b->r_left = true;
-            if (dtx < 0) b->r_right = true;
-            if (dty > 0) b->r_up = true;
-            if (dty < 0) b->r_down = true;
-        }
-    }
-    if (fb.n) {
-        hipError_t err = flush();
-        if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "shift launch: %s", hipGetErrorString(err));
-    }
+    static thread_local std::vector<FillJob> jobs;
+    bool full = false;
+    mdcnn_status rc = shift_jobs(bufs, n, dty, dtx, jobs, &full);
+    if (rc) return rc;
+    const hipError_t err = launch_fill_jobs(jobs.data(), nullptr, n, (hipStream_t)stream);
+    if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "shift launch: %s", hipGetErrorString(err));
     if (did_full_reset) *did_full_reset = full ? 1 : 0;
     return MDCNN_OK;
 }
@@ -926,6 +1188,51 @@ mdcnn_status mdcnn_frame_batch(mdcnn_net* const* nets, int n_streams, const void
                 return fail(MDCNN_ERR_STATE, "frame_batch: streams %d and %d share a network or buffers", c, b);
     }
     return frame_batch(nets, n_streams, frames_dev, forced_masks_dev ? forced_masks_dev : no_forced, dty, dtx, outs_dev, stream, did_full_reset);
+}
+
+mdcnn_status mdcnn_frames(mdcnn_net* net, int n_frames, const void* const* frames_dev, const uint8_t* const* forced_masks_dev,
+                          const int* dty, const int* dtx, void* const* outs_dev, size_t out_bytes, int depth, void* stream,
+                          int* did_full_reset) {
+    if (!net || !frames_dev || !dty || !dtx || !outs_dev) return fail(MDCNN_ERR_NULL, "frames: NULL argument");
+    if (n_frames < 1 || n_frames > kMaxFrames) return fail(MDCNN_ERR_SIZE, "frames: 1 <= n_frames <= %d", kMaxFrames);
+    if (depth < 0 || depth > kMaxStreams) return fail(MDCNN_ERR_SIZE, "frames: 0 <= depth <= %d", kMaxStreams);
+    if (out_bytes != net->out_bytes) return fail(MDCNN_ERR_SIZE, "frames: out_bytes is %zu, the outputs take %zu", out_bytes, net->out_bytes);
+    if (!whole_view(net->sites[0])) return fail(MDCNN_ERR_STATE, "frames: the network has a crop smaller than its view");
+    for (int f = 0; f < n_frames; ++f) {
+        if (!frames_dev[f] || !outs_dev[f]) return fail(MDCNN_ERR_NULL, "frames: frame %d: frame/out is NULL", f);
+        if (((uintptr_t)frames_dev[f] | (uintptr_t)outs_dev[f]) & 15) return fail(MDCNN_ERR_ALIGN, "frames: frame %d: frame/out must be 16-byte aligned", f);
+    }
+    // frames in flight write their outputs in no fixed order: no two may share memory
+    std::vector<const char*> o((const char* const*)outs_dev, (const char* const*)outs_dev + n_frames);
+    std::sort(o.begin(), o.end());
+    for (int f = 1; f < n_frames; ++f)
+        if (o[f] < o[f - 1] + out_bytes) return fail(MDCNN_ERR_STATE, "frames: two output buffers overlap");
+    if (depth == 0) depth = kDefaultDepth;
+    if (n_frames == 1) depth = 1;
+    return frame_seq(net, n_frames, frames_dev, forced_masks_dev, dty, dtx, outs_dev, depth, (hipStream_t)stream, did_full_reset);
+}
+
+mdcnn_status mdcnn_frames_plan(mdcnn_net* net, int depth, int* first_call, int* wait_call, int* init_call, int cap_groups,
+                               int* group_of_site, int cap_sites, int* stream_of_call, int cap_calls, int* n_groups, int* n_calls) {
+    if (!net) return fail(MDCNN_ERR_NULL, "net is NULL");
+    if (depth < 0 || depth > kMaxStreams) return fail(MDCNN_ERR_SIZE, "frames_plan: 0 <= depth <= %d", kMaxStreams);
+    PipePlan pp;
+    make_pipe_plan(net, g_pipe_group, depth ? depth : kDefaultDepth, g_pipe_mode, pp);
+    const int n = (int)pp.groups.size(), n_sites = (int)net->sites.size(), nc = (int)pp.call_site.size();
+    if ((first_call || wait_call || init_call) && cap_groups < n) return fail(MDCNN_ERR_SIZE, "frames_plan: %d groups, room for %d", n, cap_groups);
+    if (group_of_site && cap_sites < n_sites) return fail(MDCNN_ERR_SIZE, "frames_plan: %d sites, room for %d", n_sites, cap_sites);
+    if (stream_of_call && cap_calls < nc + 1) return fail(MDCNN_ERR_SIZE, "frames_plan: %d calls and the readout, room for %d", nc, cap_calls);
+    for (int g = 0; g < n; ++g) {
+        if (first_call) first_call[g] = pp.groups[g].call0;
+        if (wait_call) wait_call[g] = pp.groups[g].wait_call;
+        if (init_call) init_call[g] = g ? pp.groups[g - 1].call1 - 1 : -1;
+        if (group_of_site)
+            for (int site : pp.groups[g].fill) group_of_site[site] = g;
+    }
+    for (int c = 0; stream_of_call && c <= nc; ++c) stream_of_call[c] = pp.mode ? -1 : pp.seg_of_call[(size_t)c];
+    if (n_groups) *n_groups = n;
+    if (n_calls) *n_calls = nc;
+    return MDCNN_OK;
 }
 
 mdcnn_status mdcnn_input_mask(const mdcnn_buffer* in, const void* frame_dev, const float* roi_dev,

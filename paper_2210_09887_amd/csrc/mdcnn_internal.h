@@ -113,6 +113,12 @@ struct FillBatch {
     unsigned total_blocks;
 };
 constexpr int kFillItemsPerBlock = 2048;     // 16-byte chunks (or single elements) per block
+inline unsigned fill_blocks(const FillJob& j) {   // blocks a job takes in a launch (at least one: it clears the counters)
+    const int vec = j.dtype == MDCNN_F16 ? 8 : 4;
+    const long long items = (long long)(j.nP + j.nA) * (j.C % vec == 0 ? j.C / vec : j.C);
+    const long long blocks = (items + kFillItemsPerBlock - 1) / kFillItemsPerBlock;
+    return (unsigned)(blocks < 1 ? 1 : blocks);
+}
 
 // One edge as seen by the list and convolution kernels.
 struct EdgeDev {
@@ -154,7 +160,19 @@ struct Step1Batch {
     const void* X[kMaxBatch];
     const uint8_t* forced[kMaxBatch];
 };
-static_assert(sizeof(FillBatch) <= 4000, "kernel arguments stay below 4 KiB");
+// One site's step 1 and, in the same launch, initialisation jobs of OTHER sites that nothing in this
+// launch touches (blocks [step1_blocks, ...) of the grid).
+constexpr int kMaxRiders = 6;
+struct Step1Fill {
+    SiteDev s;
+    SkipDev skip;
+    const void* X;
+    const uint8_t* forced;
+    FillJob j[kMaxRiders];
+    int n;
+    unsigned step1_blocks;
+};
+static_assert(sizeof(FillBatch) <= 4000 && sizeof(Step1Fill) <= 4000, "kernel arguments stay below 4 KiB");
 static_assert(sizeof(EdgeBatch) <= 3800 && sizeof(Step1Batch) <= 3800, "kernel arguments stay below 4 KiB");
 
 enum KernelClass { kClsShift = 0, kClsStep1, kClsLists, kClsConvMfma, kClsConvPlain, kClsIdentity, kClsReadout, kClsPool, kNumClasses };
@@ -162,6 +180,8 @@ enum KernelClass { kClsShift = 0, kClsStep1, kClsLists, kClsConvMfma, kClsConvPl
 hipError_t launch_shift_fill(const FillBatch& fb, hipStream_t st);
 // n streams; geometry and dtype are those of stream 0 (the host checks that all agree)
 hipError_t launch_step1(const Step1Batch& b, int n, hipStream_t st);
+// fills in step1_blocks and the jobs' block_begin
+hipError_t launch_step1_fill(Step1Fill& a, hipStream_t st);
 // e.k < 0: no operator, only the compaction of the source's update mask.
 // returns the kernel class that was launched in *cls
 hipError_t launch_conv(const EdgeBatch& eb, int n, int dtype, int conv_path, hipStream_t st, int* cls);

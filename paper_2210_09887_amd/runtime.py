@@ -163,6 +163,15 @@ class GpuNet:
                           out.data_ptr(), out.numel() * self.esize, self._stream())
         return out, r
 
+    def frames(self, Xs, dty, dtx, forced=None, outs=None, depth=0):
+        """Xs: consecutive frames of the video (device tensors [H, W, C]).  Returns (list of flat outputs, reset flags)."""
+        if outs is None:
+            outs = [torch.empty_like(self.out) for _ in Xs]
+        r = B.mdcnn_frames(self.net, [x.data_ptr() for x in Xs],
+                           None if forced is None else [None if f is None else f.data_ptr() for f in forced],
+                           dty, dtx, [o.data_ptr() for o in outs], self.out.numel() * self.esize, depth, self._stream())
+        return outs, r
+
     def split_outputs(self, out):
         res, o = [], 0
         for i in self.terminals:

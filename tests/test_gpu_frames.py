@@ -1,0 +1,151 @@
+"""mdcnn_frames runs consecutive frames of one video with several of them in flight.
+A frame touches a site only after the frame before has finished with it, so outputs
+and every piece of state must be the same, bit for bit, as with one mdcnn_frame call
+per frame - for every number of streams, both ways of using them (runs of layers on
+streams, whole frames on streams), every group size of the pipeline and every way of
+cutting the video into calls."""
+import numpy as np
+import pytest
+import torch
+
+from inputs import build_net, build_sequence
+from inputs.nets import random_dag_net
+
+pytestmark = pytest.mark.gpu
+
+CASES = {
+    "c2_cnn5_96": (2, dict(H=96, W=96), dict(n_frames=7, H=96, W=96)),
+    "c3_resnet_96": (3, dict(H=96, W=96, widths=(32, 64, 64, 128)), dict(n_frames=9, H=96, W=96)),
+    "c3_resnet_poolstem_128": (3, dict(H=128, W=128, widths=(32, 64, 64, 128), pool_stem=True), dict(n_frames=6, H=128, W=128, tile=16)),
+    "c4_hrnet_128x96": (4, dict(H=128, W=96, widths=(32, 64, 64, 128), blocks=2), dict(n_frames=8, H=128, W=96)),
+    "c5_bottleneck_40": (5, dict(H=40, W=40, C=128, Cm=32), dict(n_frames=8, H=40, W=40, C=128, density=0.2, shift_every=3, shift=8)),
+}
+
+
+def state_of(g, net):
+    from paper_2210_09887_amd import binding as B
+    state = []
+    for i, s in enumerate(net.sites):
+        views = [B.MDCNN_VIEW_A, B.MDCNN_VIEW_DELTA, B.MDCNN_VIEW_FLAGS, B.MDCNN_VIEW_LIST, B.MDCNN_VIEW_STATS] if s.kind != "output" else []
+        views += [B.MDCNN_VIEW_P, B.MDCNN_VIEW_CLIST] if s.kind != "input" else []
+        state += [g.read(i, v) for v in views]
+    return state
+
+
+def one_by_one(net, seq):
+    import gpu_harness as H
+    from paper_2210_09887_amd.runtime import GpuNet
+    g = GpuNet(net)
+    try:
+        outs, resets = [], []
+        for t, X in enumerate(seq.frames):
+            fd = H.dev(seq.forced[t]) if seq.forced is not None else None
+            o, r = g.frame(H.dev(X), int(seq.shifts[t][0]), int(seq.shifts[t][1]), fd)
+            torch.cuda.synchronize()
+            outs.append(o.clone())
+            resets.append(r)
+        return outs, resets, state_of(g, net)
+    finally:
+        g.close()
+
+
+def in_flight(net, seq, depth, group, cuts, mode=1):
+    """The video in calls of cuts[0], cuts[1], ... frames (the last call takes the rest)."""
+    import gpu_harness as H
+    from paper_2210_09887_amd import binding as B
+    from paper_2210_09887_amd.runtime import GpuNet
+    B.mdcnn_set_option(B.MDCNN_OPT_PIPE_GROUP, group)
+    B.mdcnn_set_option(B.MDCNN_OPT_PIPE_MODE, mode)
+    g = GpuNet(net)
+    try:
+        Xs = [H.dev(X) for X in seq.frames]
+        Fs = None if seq.forced is None else [H.dev(f) for f in seq.forced]
+        outs, resets, t = [], [], 0
+        cuts = list(cuts)
+        while t < len(Xs):
+            n = min(cuts.pop(0), len(Xs) - t) if cuts else len(Xs) - t
+            o, r = g.frames(Xs[t:t + n], [int(s[0]) for s in seq.shifts[t:t + n]], [int(s[1]) for s in seq.shifts[t:t + n]],
+                            None if Fs is None else Fs[t:t + n], depth=depth)
+            outs += o
+            resets += r
+            t += n
+        torch.cuda.synchronize()
+        return outs, resets, state_of(g, net)
+    finally:
+        B.mdcnn_set_option(B.MDCNN_OPT_PIPE_GROUP, 1)
+        B.mdcnn_set_option(B.MDCNN_OPT_PIPE_MODE, 1)
+        g.close()
+
+
+def same(a, b, what):
+    (oa, ra, sa), (ob, rb, sb) = a, b
+    assert ra == rb, f"{what}: reset decisions differ"
+    assert len(oa) == len(ob) and len(sa) == len(sb)
+    for t, (x, y) in enumerate(zip(oa, ob)):
+        assert torch.equal(x, y), f"{what}: output of frame {t} differs"
+    for k, (u, v) in enumerate(zip(sa, sb)):
+        assert np.array_equal(u, v), f"{what}: state view {k} differs"
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_frames_in_flight_do_not_change_a_bit(name):
+    cfg, kn, ks = CASES[name]
+    net, seq = build_net(cfg, **kn), build_sequence(cfg, **ks)
+    ref = one_by_one(net, seq)
+    for depth, group, cuts in [(1, 2, ()), (2, 1, ()), (2, 2, (3,)), (3, 2, ()), (3, 1, (1, 2)), (4, 1, ()), (4, 3, (4,)), (0, 2, ()), (4, 64, ())]:
+        for mode in (0, 1):
+            print(f"{name}: depth {depth}, groups of {group}, calls {cuts or 'one'}, mode {mode}", flush=True)
+            same(ref, in_flight(net, seq, depth, group, cuts, mode), f"depth {depth}, groups of {group}, cuts {cuts}, mode {mode}")
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_frames_in_flight_random_networks(seed):
+    dtype = "f16" if seed % 2 else "f32"
+    net = random_dag_net(seed, dtype)
+    rng = np.random.default_rng(100 + seed)
+
+    class Seq:
+        forced = None
+    seq = Seq()
+    x = rng.normal(0, 1, (net.H, net.W, net.sites[0].C)).astype(np.float32)
+    seq.frames = []
+    for _ in range(7):
+        x = x.copy()
+        x[rng.random((net.H, net.W)) < 0.15] += rng.normal(0, 0.7, net.sites[0].C).astype(np.float32)
+        seq.frames.append(x.astype(net.np_dtype))
+    seq.shifts = [(0, 0), (1, 0), (0, -1), (0, 0), (-1, 0), (0, 1), (0, 1)]       # frame 4 reverses: full reset
+    ref = one_by_one(net, seq)
+    for depth, group, mode in [(2, 1, 0), (4, 1, 0), (4, 1, 1), (3, 2, 0), (3, 2, 1), (4, 4, 0)]:
+        print(f"dag {seed}: depth {depth}, groups of {group}, mode {mode}", flush=True)
+        same(ref, in_flight(net, seq, depth, group, (3,), mode), f"depth {depth}, groups of {group}, mode {mode}")
+
+
+def test_frames_argument_checks():
+    import gpu_harness as H
+    from paper_2210_09887_amd import binding as B
+    from paper_2210_09887_amd.runtime import GpuNet
+    cfg, kn, ks = CASES["c2_cnn5_96"]
+    net, seq = build_net(cfg, **kn), build_sequence(cfg, **ks)
+    g = GpuNet(net)
+    try:
+        Xs = [H.dev(X) for X in seq.frames[:3]]
+        nb = g.out.numel() * g.esize
+        outs = [torch.empty_like(g.out) for _ in Xs]
+        ptr = lambda ts: [t.data_ptr() for t in ts]
+        with pytest.raises(B.MdcnnError) as e:
+            B.mdcnn_frames(g.net, ptr(Xs), None, [0] * 3, [0] * 3, ptr([outs[0], outs[1], outs[0]]), nb)
+        assert e.value.status == 6          # ERR_STATE: two outputs share memory
+        with pytest.raises(B.MdcnnError) as e:
+            B.mdcnn_frames(g.net, ptr(Xs), None, [0] * 3, [0] * 3, ptr(outs), nb, depth=5)
+        assert e.value.status == 5          # ERR_SIZE
+        with pytest.raises(B.MdcnnError) as e:
+            B.mdcnn_frames(g.net, ptr(Xs), None, [0] * 3, [0] * 3, ptr(outs), nb - 2)
+        assert e.value.status == 5
+        with pytest.raises(B.MdcnnError) as e:
+            B.mdcnn_frames(g.net, [Xs[0].data_ptr(), None, Xs[2].data_ptr()], None, [0] * 3, [0] * 3, ptr(outs), nb)
+        assert e.value.status == 1          # ERR_NULL
+        # a refused call has changed nothing: the first frame is still the first
+        o, r = g.frames(Xs, [0] * 3, [0] * 3)
+        assert r == [True, False, False]
+    finally:
+        g.close()

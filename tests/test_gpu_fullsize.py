@@ -239,3 +239,17 @@ def test_config3_full_512_input_masks():
             log(f"config 3 input masks frame {t}: {int(fm.sum())} of {fm.size} pixels")
     finally:
         g.close()
+
+
+@pytest.mark.parametrize("cfg,n", [(3, 24), (4, 20), (5, 25)])
+def test_full_size_frames_in_flight(cfg, n):
+    """The launch configuration bench.py times: the video through mdcnn_frames on four streams, against one
+    mdcnn_frame call per frame (itself checked against the oracle above) - outputs, reset decisions and all state."""
+    import test_gpu_frames as F
+    net = build_net(cfg)
+    seq = build_sequence(cfg, n_frames=n)
+    ref = F.one_by_one(net, seq)
+    assert sum(ref[1]) >= 1
+    for depth, cuts, mode in [(4, (), 0), (3, (n // 2,), 0), (4, (), 1)]:
+        log(f"config {cfg}: {n} frames, {depth} streams, calls {cuts or 'one'}, mode {mode}")
+        F.same(ref, F.in_flight(net, seq, depth, 1, cuts, mode), f"config {cfg}, depth {depth}, mode {mode}")

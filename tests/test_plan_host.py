@@ -127,3 +127,66 @@ def test_streams_are_used_where_the_network_has_branches():
     assert used["cnn5"] == (1, 1)                  # a chain
     assert used["resnet"][0] == 1 and used["resnet"][1] > 1      # three projection branches do not pay for the waits
     assert used["hrnet_full"] == (4, 4)            # four branches
+
+
+@pytest.mark.parametrize("name", list(NETS))
+@pytest.mark.parametrize("group,depth,mode", [(1, 4, 0), (2, 4, 0), (1, 2, 0), (3, 3, 0), (64, 4, 0), (1, 1, 0),
+                                              (1, 4, 1), (2, 2, 1), (5, 3, 1), (64, 4, 1)])
+def test_frames_in_flight_never_share_a_site(name, group, depth, mode):
+    """mdcnn_frames keeps several frames in flight on several streams.  Whatever touches a site - its initialisation
+    (which runs inside the first launch of another forward call, or ahead of the frame), forward calls, the readout -
+    must be ordered against everything else that touches it, in the same and in the neighbouring frames: by being on
+    the same stream or through the waits the library documents.  Three frames are laid out here as the library
+    issues them and every pair of steps on a common site is checked."""
+    spec = NETS[name]()
+    net, bufs = host_net(spec)
+    B.mdcnn_set_option(B.MDCNN_OPT_PIPE_GROUP, group)
+    B.mdcnn_set_option(B.MDCNN_OPT_PIPE_MODE, mode)
+    try:
+        p = B.mdcnn_frames_plan(net, len(spec.sites), depth)
+        first, wait, init, gos, soc, n_calls = (p[k] for k in ("first_call", "wait_call", "init_call", "group_of_site", "stream_of_call", "n_calls"))
+        calls = [i for i, s in enumerate(spec.sites) if s.kind != "output"]
+        assert n_calls == len(calls) and len(soc) == n_calls + 1
+        assert first == list(range(0, n_calls, group))
+        assert all(0 <= g < len(first) for g in gos)                          # every site is initialised once a frame
+        assert init[0] == -1 and all(0 <= init[g] < first[g] for g in range(1, len(first)))
+        if mode == 0:
+            assert soc[0] == 0 and all(0 <= b - a <= 1 for a, b in zip(soc, soc[1:])) and soc[-1] < depth
+            assert soc[-1] == min(depth, n_calls) - 1                         # every stream gets a run of calls
+        stream = (lambda f, c: f % depth) if mode else (lambda f, c: soc[c])
+        touched = [{i} | {e.dst for e in spec.edges if e.src == i} for i in calls]
+        outputs = {i for i, s in enumerate(spec.sites) if s.kind == "output"}
+        sites_of = [{i for i, gg in enumerate(gos) if gg == g} for g in range(len(first))]
+        # steps in the order of issue: (frame, call or None for an initialisation, stream, sites, waits [(frame, call)])
+        steps = []
+        for f in range(3):
+            for c in range(n_calls + 1):
+                waits = []
+                if 0 < c < n_calls and stream(f, c) != stream(f, c - 1):
+                    waits.append((f, c - 1))
+                for g in range(len(first)):
+                    if init[g] == c or (c == 0 and init[g] == -1):
+                        st = stream(f, c)
+                        if f and wait[g] >= 0 and stream(f - 1, wait[g]) != st:
+                            waits.append((f - 1, wait[g]))
+                        assert init[g] == -1 or not (sites_of[g] & touched[c]), f"call {c} touches sites initialised in its own launch"
+                        steps.append((f, None, st, sites_of[g], waits))
+                        waits = []                                             # issued once; the call follows on the same stream
+                steps.append((f, c, stream(f, c), touched[c] if c < n_calls else outputs, waits))
+        index = {(f, c): k for k, (f, c, _, _, _) in enumerate(steps) if c is not None}
+        reach = ordered_before([st for _, _, st, _, _ in steps], [[index[w] for w in ws] for _, _, _, _, ws in steps])
+        for b, (fb, cb, _, sb, _) in enumerate(steps):
+            for a in range(b):
+                fa, ca, _, sa, _ = steps[a]
+                if sa & sb:
+                    assert a in reach[b], f"frame {fa} call {ca} and frame {fb} call {cb} touch {sa & sb} unordered"
+        # within a frame a site is initialised before anything else touches it
+        frame0 = [(c, t) for f, c, _, t, _ in steps if f == 0]
+        for i in range(len(spec.sites)):
+            assert [c for c, t in frame0 if i in t][0] is None, f"site {i} is used before it is initialised"
+    finally:
+        B.mdcnn_set_option(B.MDCNN_OPT_PIPE_GROUP, 1)
+        B.mdcnn_set_option(B.MDCNN_OPT_PIPE_MODE, 1)
+        B.mdcnn_net_destroy(net)
+        for b in bufs:
+            B.mdcnn_destroy_buffer(b)
