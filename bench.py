@@ -55,8 +55,9 @@ def parse():
     ap.add_argument("--front-end", action="store_true",
                     help="the input update mask of every frame comes from mdcnn_input_mask (isolated updates suppressed, "
                          "dilation by 2 pixels) and is forced; one stream only")
-    ap.add_argument("--frames-in-flight", type=int, default=4,
-                    help="consecutive frames of the video that mdcnn_frames keeps in flight (1..4); 1: one mdcnn_frame call per frame")
+    ap.add_argument("--frames-in-flight", type=int, default=0,
+                    help="streams on which mdcnn_frames keeps consecutive frames of the video in flight (1..4); 1: one mdcnn_frame "
+                         "call per frame; 0 (default): the library's own rule, 4 if a frame has at least 10 launches, else 1")
     ap.add_argument("--streams", type=int, default=8,
                     help="after the headline run, the same workload as a batch of this many independent streams "
                          "(mdcnn_frame_batch; reported under \"batched\"); 0 disables it")
@@ -302,7 +303,9 @@ def main():
         state["t"] += 1
         state["resets"] += int(r)
 
-    in_flight = a.frames_in_flight if crops is None and not a.front_end else 1
+    in_flight = a.frames_in_flight or (4 if len(B.mdcnn_frame_plan(g.net, 1)[0]) >= 10 else 1)
+    if crops is not None or a.front_end:
+        in_flight = 1
     outs_pool = [torch.empty_like(g.out) for _ in range(min(T, max(a.steps, a.warmup)))] if in_flight > 1 else []
 
     def run_frames(n):

@@ -83,8 +83,8 @@ __device__ __forceinline__ void fill_items(const FillJob& j, unsigned lb) {
     const long long total = (long long)(j.nP + j.nA) * chunks;
     // a full reset (empty kept rectangles) needs no ring arithmetic
     const bool full = j.py0 == j.py1 && j.px0 == j.px1 && j.ay0 == j.ay1 && j.ax0 == j.ax1 && j.py0 == 0 && j.ay0 == 0;
-    const long long begin = (long long)lb * kFillItemsPerBlock;
-    long long end = begin + kFillItemsPerBlock;
+    const long long begin = (long long)lb * j.per_block;
+    long long end = begin + j.per_block;
     if (end > total) end = total;
     uint8_t* const Sr = j.s_off ? (uint8_t*)j.A + (size_t)j.s_off * 256 : nullptr;   // rings like A
     T* const Yr = j.y_off ? (T*)((char*)j.A + (size_t)j.y_off * 256) : nullptr;
@@ -230,12 +230,12 @@ __device__ __forceinline__ bool crop_state(const SiteDev& s, int pix, bool write
 
 template <typename T, int G, int CH>
 __device__ __forceinline__ void step1_block(const SiteDev& s, const SkipDev& skip, const T* __restrict__ X,
-                                            const uint8_t* __restrict__ forced) {
+                                            const uint8_t* __restrict__ forced, unsigned blk) {
     constexpr int VEC = V16<T>::N;
     constexpr int PPB = 256 / G;
     const int tid = threadIdx.x;
     const int lp = tid % G;
-    const int pix = blockIdx.x * PPB + tid / G;
+    const int pix = (int)blk * PPB + tid / G;
     const int HW = s.H * s.W;
     bool m = false, cand = false;
     if (pix < HW) {
@@ -310,28 +310,28 @@ __device__ __forceinline__ void step1_block(const SiteDev& s, const SkipDev& ski
 
 template <typename T, int G, int CH>
 __global__ __launch_bounds__(256) void k_step1(Step1Batch bt) {
-    step1_block<T, G, CH>(bt.s[blockIdx.z], bt.skip[blockIdx.z], (const T*)bt.X[blockIdx.z], bt.forced[blockIdx.z]);
+    step1_block<T, G, CH>(bt.s[blockIdx.z], bt.skip[blockIdx.z], (const T*)bt.X[blockIdx.z], bt.forced[blockIdx.z], blockIdx.x);
 }
 
-// One site, and in the same launch the initialisation jobs of other sites (blocks past the site's own).
+// One site, and in the same launch the initialisation jobs of other sites: the first fill_blocks
+// blocks of the grid, so that they start with the launch and not in its tail.
 template <typename T, int G, int CH>
 __global__ __launch_bounds__(256) void k_step1_fill(Step1Fill a) {
-    if (blockIdx.x < a.step1_blocks) {
-        step1_block<T, G, CH>(a.s, a.skip, (const T*)a.X, a.forced);
+    if (blockIdx.x >= a.fill_blocks) {
+        step1_block<T, G, CH>(a.s, a.skip, (const T*)a.X, a.forced, blockIdx.x - a.fill_blocks);
         return;
     }
-    const unsigned b = blockIdx.x - a.step1_blocks;
     int ji = 0;
-    while (ji + 1 < a.n && b >= a.j[ji + 1].block_begin) ++ji;
-    fill_block(a.j[ji], b - a.j[ji].block_begin);
+    while (ji + 1 < a.n && blockIdx.x >= a.j[ji + 1].block_begin) ++ji;
+    fill_block(a.j[ji], blockIdx.x - a.j[ji].block_begin);
 }
 
 // Any channel count: one lane per pixel, scalar accesses.
 template <typename T>
 __device__ __forceinline__ void step1_scalar_block(const SiteDev& s, const SkipDev& skip, const T* __restrict__ X,
-                                                   const uint8_t* __restrict__ forced) {
+                                                   const uint8_t* __restrict__ forced, unsigned blk) {
     const int tid = threadIdx.x;
-    const int pix = blockIdx.x * 256 + tid;
+    const int pix = (int)blk * 256 + tid;
     const int HW = s.H * s.W;
     bool m = false, cand = false;
     if (pix < HW) {
@@ -386,19 +386,18 @@ __device__ __forceinline__ void step1_scalar_block(const SiteDev& s, const SkipD
 
 template <typename T>
 __global__ __launch_bounds__(256) void k_step1_scalar(Step1Batch bt) {
-    step1_scalar_block<T>(bt.s[blockIdx.z], bt.skip[blockIdx.z], (const T*)bt.X[blockIdx.z], bt.forced[blockIdx.z]);
+    step1_scalar_block<T>(bt.s[blockIdx.z], bt.skip[blockIdx.z], (const T*)bt.X[blockIdx.z], bt.forced[blockIdx.z], blockIdx.x);
 }
 
 template <typename T>
 __global__ __launch_bounds__(256) void k_step1_scalar_fill(Step1Fill a) {
-    if (blockIdx.x < a.step1_blocks) {
-        step1_scalar_block<T>(a.s, a.skip, (const T*)a.X, a.forced);
+    if (blockIdx.x >= a.fill_blocks) {
+        step1_scalar_block<T>(a.s, a.skip, (const T*)a.X, a.forced, blockIdx.x - a.fill_blocks);
         return;
     }
-    const unsigned b = blockIdx.x - a.step1_blocks;
     int ji = 0;
-    while (ji + 1 < a.n && b >= a.j[ji + 1].block_begin) ++ji;
-    fill_block(a.j[ji], b - a.j[ji].block_begin);
+    while (ji + 1 < a.n && blockIdx.x >= a.j[ji + 1].block_begin) ++ji;
+    fill_block(a.j[ji], blockIdx.x - a.j[ji].block_begin);
 }
 
 // Split C/VEC chunks into G lanes x CH chunks per lane (G a power of two <= 64,
@@ -473,12 +472,12 @@ hipError_t launch_step1(const Step1Batch& bt, int n, hipStream_t st) {
 
 hipError_t launch_step1_fill(Step1Fill& a, hipStream_t st) {
     if (a.n < 0 || a.n > kMaxRiders) return hipErrorInvalidValue;
-    a.step1_blocks = step1_blocks_of(a.s);
     unsigned extra = 0;
     for (int k = 0; k < a.n; ++k) {
         a.j[k].block_begin = extra;
         extra += fill_blocks(a.j[k]);
     }
+    a.fill_blocks = extra;
     return a.s.dtype == MDCNN_F16 ? step1_t<f16>(a, a.s, 1, extra, st) : step1_t<float>(a, a.s, 1, extra, st);
 }
 

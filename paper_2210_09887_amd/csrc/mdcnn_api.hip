@@ -592,6 +592,7 @@ mdcnn_status shift_jobs(mdcnn_buffer* const* bufs, int n, int dty, int dtx, std:
         j.nP = j.P ? outside(j.Hp, j.Wp, j.py0, j.py1, j.px0, j.px1) : 0;
         j.nA = j.A ? outside(j.H, j.W, j.ay0, j.ay1, j.ax0, j.ax1) : 0;
         j.reset_counters = b->fresh ? 2 : 1;             // per-frame counters start at zero every frame
+        j.per_block = full ? kFillItemsPerBlockFull : kFillItemsPerBlockStrip;
         jobs[(size_t)i] = j;
         if (full) {
             b->r_up = b->r_down = b->r_left = b->r_right = false;
@@ -808,6 +809,7 @@ void make_pipe_plan(const mdcnn_net* net, int group_calls, int streams, int mode
 
 constexpr int kMaxFrames = 4096;
 constexpr int kDefaultDepth = 4;
+constexpr int kMinLaunchesInFlight = 10;   // launches of a frame from which on the default is kDefaultDepth streams
 
 // n_frames consecutive frames of one network on `depth` streams (stream 0 is the caller's).  The
 // launches of a frame are those of mdcnn_frame on one stream, in the same order, except that the
@@ -1207,7 +1209,12 @@ mdcnn_status mdcnn_frames(mdcnn_net* net, int n_frames, const void* const* frame
     std::sort(o.begin(), o.end());
     for (int f = 1; f < n_frames; ++f)
         if (o[f] < o[f - 1] + out_bytes) return fail(MDCNN_ERR_STATE, "frames: two output buffers overlap");
-    if (depth == 0) depth = kDefaultDepth;
+    if (depth == 0) {
+        // frames of a short network are too small a unit: the events cost more than the overlap gains
+        Plan one;
+        make_plan(net, 1, one);
+        depth = (int)one.nodes.size() >= kMinLaunchesInFlight ? kDefaultDepth : 1;
+    }
     if (n_frames == 1) depth = 1;
     return frame_seq(net, n_frames, frames_dev, forced_masks_dev, dty, dtx, outs_dev, depth, (hipStream_t)stream, did_full_reset);
 }

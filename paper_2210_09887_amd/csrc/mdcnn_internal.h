@@ -104,21 +104,26 @@ struct FillJob {
     int nP, nA;                 // pixels to initialise in P / in A
     int dtype;
     int reset_counters;         // 1: per-frame slots, 2: all (first reset)
+    int per_block;              // items a block initialises
     unsigned block_begin;       // first block of the launch that works on this job
 };
-constexpr int kMaxFillJobs = 22;
+constexpr int kMaxFillJobs = 21;
 struct FillBatch {
     FillJob j[kMaxFillJobs];
     int n;
     unsigned total_blocks;
 };
-constexpr int kFillItemsPerBlock = 2048;     // 16-byte chunks (or single elements) per block
+// 16-byte chunks (or single elements) a block initialises.  A full reset is a plain fill, bound by the
+// number of blocks; after a camera shift a block's time is latency (bias loads, ring arithmetic per item), so
+// the strips get more, smaller blocks.
+constexpr int kFillItemsPerBlockFull = 2048, kFillItemsPerBlockStrip = 512;
 inline unsigned fill_blocks(const FillJob& j) {   // blocks a job takes in a launch (at least one: it clears the counters)
     const int vec = j.dtype == MDCNN_F16 ? 8 : 4;
     const long long items = (long long)(j.nP + j.nA) * (j.C % vec == 0 ? j.C / vec : j.C);
-    const long long blocks = (items + kFillItemsPerBlock - 1) / kFillItemsPerBlock;
+    const long long blocks = (items + j.per_block - 1) / j.per_block;
     return (unsigned)(blocks < 1 ? 1 : blocks);
 }
+static_assert(sizeof(FillBatch) <= 4000, "kernel arguments stay below 4 KiB");
 
 // One edge as seen by the list and convolution kernels.
 struct EdgeDev {
@@ -161,7 +166,7 @@ struct Step1Batch {
     const uint8_t* forced[kMaxBatch];
 };
 // One site's step 1 and, in the same launch, initialisation jobs of OTHER sites that nothing in this
-// launch touches (blocks [step1_blocks, ...) of the grid).
+// launch touches (blocks [0, fill_blocks) of the grid; the site's own blocks follow).
 constexpr int kMaxRiders = 6;
 struct Step1Fill {
     SiteDev s;
@@ -170,9 +175,9 @@ struct Step1Fill {
     const uint8_t* forced;
     FillJob j[kMaxRiders];
     int n;
-    unsigned step1_blocks;
+    unsigned fill_blocks;
 };
-static_assert(sizeof(FillBatch) <= 4000 && sizeof(Step1Fill) <= 4000, "kernel arguments stay below 4 KiB");
+static_assert(sizeof(Step1Fill) <= 4000, "kernel arguments stay below 4 KiB");
 static_assert(sizeof(EdgeBatch) <= 3800 && sizeof(Step1Batch) <= 3800, "kernel arguments stay below 4 KiB");
 
 enum KernelClass { kClsShift = 0, kClsStep1, kClsLists, kClsConvMfma, kClsConvPlain, kClsIdentity, kClsReadout, kClsPool, kNumClasses };
@@ -180,7 +185,7 @@ enum KernelClass { kClsShift = 0, kClsStep1, kClsLists, kClsConvMfma, kClsConvPl
 hipError_t launch_shift_fill(const FillBatch& fb, hipStream_t st);
 // n streams; geometry and dtype are those of stream 0 (the host checks that all agree)
 hipError_t launch_step1(const Step1Batch& b, int n, hipStream_t st);
-// fills in step1_blocks and the jobs' block_begin
+// fills in fill_blocks and the jobs' block_begin
 hipError_t launch_step1_fill(Step1Fill& a, hipStream_t st);
 // e.k < 0: no operator, only the compaction of the source's update mask.
 // returns the kernel class that was launched in *cls
