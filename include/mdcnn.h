@@ -277,6 +277,18 @@ mdcnn_status mdcnn_frames(mdcnn_net* net, int n_frames, const void* const* frame
                           void* const* outs_dev, size_t out_bytes, int depth, void* stream,
                           int* did_full_reset);
 
+/* mdcnn_frames for cropped frames: frame f is what mdcnn_frame_crop does with the crop
+ * (crops[4f .. 4f+3] = ty0, tx0, th, tw in tiles of the view); frames_dev[f], the forced
+ * mask and outs_dev[f] have that crop's extent, out_bytes[f] the summed crop sizes of the
+ * OUTPUT sites.  All sites need crops == 1; the last crop stays in force afterwards.
+ * Everything else as for mdcnn_frames, results bit-identical to n_frames calls of
+ * mdcnn_frame_crop.  Errors: also MDCNN_ERR_SHAPE for a crop that leaves the view; all
+ * frames are checked before anything runs or changes. */
+mdcnn_status mdcnn_frames_crop(mdcnn_net* net, int n_frames, const void* const* frames_dev,
+                               const uint8_t* const* forced_masks_dev, const int* dty, const int* dtx,
+                               const int* crops, void* const* outs_dev, const size_t* out_bytes,
+                               int depth, void* stream, int* did_full_reset);
+
 /* Host-only.  The plan mdcnn_frames follows for `net` on `depth` streams (0: default).
  * The forward calls of a frame (non-terminal sites in order) are numbered 0 ..
  * *n_calls - 1; the readout counts as call *n_calls.  stream_of_call[c] (c <= *n_calls):

@@ -7,6 +7,7 @@
 
 #include <algorithm>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "mdcnn_internal.h"
@@ -819,7 +820,8 @@ constexpr int kMinLaunchesInFlight = 10;   // launches of a frame from which on 
 // by the waits of the plan.  Every site sees the same sequence of launches as with one frame at a
 // time, so the results are the same bit for bit.
 mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, const uint8_t* const* forced,
-                       const int* dty, const int* dtx, void* const* outs_dev, int depth, hipStream_t user, int* did_full_reset) {
+                       const int* dty, const int* dtx, const int* crops, void* const* outs_dev, int depth, hipStream_t user,
+                       int* did_full_reset) {
     const int key = (g_pipe_group * 8 + depth) * 2 + g_pipe_mode;
     if (net->pipe.key != key) make_pipe_plan(net, g_pipe_group, depth, g_pipe_mode, net->pipe);
     const PipePlan& pp = net->pipe;
@@ -864,6 +866,10 @@ mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, 
         mdcnn_status rc = shift_jobs(net->sites.data(), (int)net->sites.size(), dty[f], dtx[f], jobs, &full);
         if (rc) return rc;
         if (did_full_reset) did_full_reset[f] = full ? 1 : 0;
+        if (crops) {                                           // the descriptors of this frame's launches carry its crop
+            rc = mdcnn_set_crop(net->sites.data(), (int)net->sites.size(), crops[4 * f], crops[4 * f + 1], crops[4 * f + 2], crops[4 * f + 3]);
+            if (rc) return rc;
+        }
         hipEvent_t* ev_prev = g_aux.events.data() + (size_t)((f + ring - 1) % ring) * pp.n_events;
         hipEvent_t* ev_mine = g_aux.events.data() + (size_t)(f % ring) * pp.n_events;
         auto record = [&](int call) {
@@ -917,9 +923,9 @@ mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, 
         char* o = (char*)outs_dev[f];
         for (mdcnn_buffer* b : net->sites) {
             if (b->d.kind != MDCNN_SITE_OUTPUT) continue;
-            err = timed(kClsReadout, st, [&] { return launch_read_view(b->dev, MDCNN_VIEW_OUT, o, st); });
+            err = timed(kClsReadout, st, [&] { return launch_read_view(b->dev, crops ? MDCNN_VIEW_CROP_OUT : MDCNN_VIEW_OUT, o, st); });
             if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: readout launch: %s", f, hipGetErrorString(err));
-            o += (size_t)b->d.H * b->d.W * b->d.C * esize(b->d.dtype);
+            o += crop_pixels(b) * b->d.C * esize(b->d.dtype);
         }
         err = record(n_calls);
         if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: event: %s", f, hipGetErrorString(err));
@@ -1192,23 +1198,36 @@ mdcnn_status mdcnn_frame_batch(mdcnn_net* const* nets, int n_streams, const void
     return frame_batch(nets, n_streams, frames_dev, forced_masks_dev ? forced_masks_dev : no_forced, dty, dtx, outs_dev, stream, did_full_reset);
 }
 
-mdcnn_status mdcnn_frames(mdcnn_net* net, int n_frames, const void* const* frames_dev, const uint8_t* const* forced_masks_dev,
-                          const int* dty, const int* dtx, void* const* outs_dev, size_t out_bytes, int depth, void* stream,
-                          int* did_full_reset) {
-    if (!net || !frames_dev || !dty || !dtx || !outs_dev) return fail(MDCNN_ERR_NULL, "frames: NULL argument");
+// Checks shared by mdcnn_frames and mdcnn_frames_crop; out_bytes[f] (crops) or out_bytes[0] (none) per frame.
+static mdcnn_status frames_checked(mdcnn_net* net, int n_frames, const void* const* frames_dev, const uint8_t* const* forced_masks_dev,
+                                   const int* dty, const int* dtx, const int* crops, void* const* outs_dev, const size_t* out_bytes,
+                                   int depth, void* stream, int* did_full_reset) {
+    if (!net || !frames_dev || !dty || !dtx || !outs_dev || !out_bytes) return fail(MDCNN_ERR_NULL, "frames: NULL argument");
     if (n_frames < 1 || n_frames > kMaxFrames) return fail(MDCNN_ERR_SIZE, "frames: 1 <= n_frames <= %d", kMaxFrames);
     if (depth < 0 || depth > kMaxStreams) return fail(MDCNN_ERR_SIZE, "frames: 0 <= depth <= %d", kMaxStreams);
-    if (out_bytes != net->out_bytes) return fail(MDCNN_ERR_SIZE, "frames: out_bytes is %zu, the outputs take %zu", out_bytes, net->out_bytes);
-    if (!whole_view(net->sites[0])) return fail(MDCNN_ERR_STATE, "frames: the network has a crop smaller than its view");
+    if (!crops && out_bytes[0] != net->out_bytes) return fail(MDCNN_ERR_SIZE, "frames: out_bytes is %zu, the outputs take %zu", out_bytes[0], net->out_bytes);
+    if (!crops && !whole_view(net->sites[0])) return fail(MDCNN_ERR_STATE, "frames: the network has a crop smaller than its view: use mdcnn_frames_crop");
     for (int f = 0; f < n_frames; ++f) {
         if (!frames_dev[f] || !outs_dev[f]) return fail(MDCNN_ERR_NULL, "frames: frame %d: frame/out is NULL", f);
         if (((uintptr_t)frames_dev[f] | (uintptr_t)outs_dev[f]) & 15) return fail(MDCNN_ERR_ALIGN, "frames: frame %d: frame/out must be 16-byte aligned", f);
+        if (!crops) continue;
+        const int ty0 = crops[4 * f], tx0 = crops[4 * f + 1], th = crops[4 * f + 2], tw = crops[4 * f + 3];
+        size_t need = 0;
+        for (const mdcnn_buffer* b : net->sites) {
+            const mdcnn_buffer_desc& d = b->d;
+            if (!d.crops) return fail(MDCNN_ERR_STATE, "frames: the network was created without crops");
+            if (ty0 < 0 || tx0 < 0 || th < 1 || tw < 1 || ((long long)ty0 + th) * d.tile > d.H || ((long long)tx0 + tw) * d.tile > d.W)
+                return fail(MDCNN_ERR_SHAPE, "frames: frame %d: crop of %dx%d tiles at (%d, %d) leaves a view of %dx%d pixels (tile %d)", f, th, tw, ty0, tx0, d.H, d.W, d.tile);
+            if (d.kind == MDCNN_SITE_OUTPUT) need += (size_t)th * d.tile * tw * d.tile * d.C * esize(d.dtype);
+        }
+        if (out_bytes[f] != need) return fail(MDCNN_ERR_SIZE, "frames: frame %d: out_bytes is %zu, the cropped outputs take %zu", f, out_bytes[f], need);
     }
     // frames in flight write their outputs in no fixed order: no two may share memory
-    std::vector<const char*> o((const char* const*)outs_dev, (const char* const*)outs_dev + n_frames);
+    std::vector<std::pair<const char*, size_t>> o((size_t)n_frames);
+    for (int f = 0; f < n_frames; ++f) o[(size_t)f] = {(const char*)outs_dev[f], out_bytes[crops ? f : 0]};
     std::sort(o.begin(), o.end());
     for (int f = 1; f < n_frames; ++f)
-        if (o[f] < o[f - 1] + out_bytes) return fail(MDCNN_ERR_STATE, "frames: two output buffers overlap");
+        if (o[(size_t)f].first < o[(size_t)f - 1].first + o[(size_t)f - 1].second) return fail(MDCNN_ERR_STATE, "frames: two output buffers overlap");
     if (depth == 0) {
         // frames of a short network are too small a unit: the events cost more than the overlap gains
         Plan one;
@@ -1216,7 +1235,20 @@ mdcnn_status mdcnn_frames(mdcnn_net* net, int n_frames, const void* const* frame
         depth = (int)one.nodes.size() >= kMinLaunchesInFlight ? kDefaultDepth : 1;
     }
     if (n_frames == 1) depth = 1;
-    return frame_seq(net, n_frames, frames_dev, forced_masks_dev, dty, dtx, outs_dev, depth, (hipStream_t)stream, did_full_reset);
+    return frame_seq(net, n_frames, frames_dev, forced_masks_dev, dty, dtx, crops, outs_dev, depth, (hipStream_t)stream, did_full_reset);
+}
+
+mdcnn_status mdcnn_frames(mdcnn_net* net, int n_frames, const void* const* frames_dev, const uint8_t* const* forced_masks_dev,
+                          const int* dty, const int* dtx, void* const* outs_dev, size_t out_bytes, int depth, void* stream,
+                          int* did_full_reset) {
+    return frames_checked(net, n_frames, frames_dev, forced_masks_dev, dty, dtx, nullptr, outs_dev, &out_bytes, depth, stream, did_full_reset);
+}
+
+mdcnn_status mdcnn_frames_crop(mdcnn_net* net, int n_frames, const void* const* frames_dev, const uint8_t* const* forced_masks_dev,
+                               const int* dty, const int* dtx, const int* crops, void* const* outs_dev, const size_t* out_bytes,
+                               int depth, void* stream, int* did_full_reset) {
+    if (!crops) return fail(MDCNN_ERR_NULL, "frames_crop: crops is NULL");
+    return frames_checked(net, n_frames, frames_dev, forced_masks_dev, dty, dtx, crops, outs_dev, out_bytes, depth, stream, did_full_reset);
 }
 
 mdcnn_status mdcnn_frames_plan(mdcnn_net* net, int depth, int* first_call, int* wait_call, int* init_call, int cap_groups,

@@ -140,6 +140,27 @@ class GpuNet:
             o += m
         return res, r
 
+    def frames_crop(self, Xs, dty, dtx, crops, forced=None, outs=None, depth=0):
+        """Consecutive cropped frames of the video in one call.  Returns (per frame the list of output tensors in
+        crop order, reset flags)."""
+        ns = [sum(int(c[2]) * self.tile[i] * int(c[3]) * self.tile[i] * self.shape[i][2] for i in self.terminals) for c in crops]
+        if outs is None:
+            outs = [torch.empty_like(self.out) for _ in Xs]
+        r = B.mdcnn_frames_crop(self.net, [x.data_ptr() for x in Xs],
+                                None if forced is None else [None if f is None else f.data_ptr() for f in forced],
+                                dty, dtx, crops, [o.data_ptr() for o in outs], [n * self.esize for n in ns], depth, self._stream())
+        self.crop = tuple(int(v) for v in crops[-1])
+        res = []
+        for c, out in zip(crops, outs):
+            per, o = [], 0
+            for i in self.terminals:
+                shp = (int(c[2]) * self.tile[i], int(c[3]) * self.tile[i], self.shape[i][2])
+                m = int(np.prod(shp))
+                per.append(out[o:o + m].reshape(shp))
+                o += m
+            res.append(per)
+        return res, r
+
     def input_mask(self, X, roi=None, theta=None, base=0.4, gain=0.6, pool=1, suppress=False, dilate=0):
         """Post-processed update mask of the input site for frame X (device tensor over the crop): a uint8
         device tensor to pass as the forced mask of that frame."""

@@ -87,7 +87,7 @@ def same(a, b, what):
         assert np.array_equal(u, v), f"{what}: state view {k} differs"
 
 
-@pytest.mark.parametrize("name", list(CASES))
+@pytest.mark.parametrize("name", [k for k in CASES if k != "c3_full_512"])
 def test_frames_in_flight_do_not_change_a_bit(name):
     cfg, kn, ks = CASES[name]
     net, seq = build_net(cfg, **kn), build_sequence(cfg, **ks)
@@ -149,3 +149,64 @@ def test_frames_argument_checks():
         assert r == [True, False, False]
     finally:
         g.close()
+
+
+def crops_of(net, n):
+    Ht, Wt = net.H // net.total_stride, net.W // net.total_stride
+    return [(0, 0, Ht, Wt) if t == 0 else (t % 2, (t + 1) % 2, Ht - 1 - t % 2, Wt - 1 - (t // 2) % 2) for t in range(n)]
+
+
+CASES["c3_full_512"] = (3, {}, dict(n_frames=8))
+
+
+@pytest.mark.parametrize("name", ["c3_resnet_96", "c3_resnet_poolstem_128", "c4_hrnet_128x96", "c3_full_512"])
+def test_cropped_frames_in_flight(name):
+    """mdcnn_frames_crop against one mdcnn_frame_crop call per frame: outputs, reset decisions, all state incl. the
+    per-pixel crop state."""
+    import gpu_harness as H
+    from paper_2210_09887_amd import binding as B
+    from paper_2210_09887_amd.runtime import GpuNet
+    cfg, kn, ks = CASES[name]
+    net, seq = build_net(cfg, **kn), build_sequence(cfg, **ks)
+    n = len(seq.frames)
+    crops = crops_of(net, n)
+    Xs = [H.dev(H.cut(net, X, c)) for X, c in zip(seq.frames, crops)]
+    dys, dxs = [int(s[0]) for s in seq.shifts], [int(s[1]) for s in seq.shifts]
+
+    def state(g):
+        return state_of(g, net) + [g.read(i, B.MDCNN_VIEW_PENDING) for i, s in enumerate(net.sites) if s.kind != "output"]
+
+    g = GpuNet(net, crops=True)
+    try:
+        ref_o, ref_r = [], []
+        for t in range(n):
+            o, r = g.frame_crop(Xs[t], dys[t], dxs[t], crops[t])
+            torch.cuda.synchronize()
+            ref_o.append([x.clone() for x in o])
+            ref_r.append(r)
+        ref_s = state(g)
+    finally:
+        g.close()
+    for depth, group, mode, cut in [(4, 1, 1, n), (3, 2, 1, 3), (4, 1, 0, n), (2, 3, 0, 2), (1, 1, 1, n)]:
+        print(f"{name}: depth {depth}, groups of {group}, mode {mode}, calls of {cut}", flush=True)
+        B.mdcnn_set_option(B.MDCNN_OPT_PIPE_GROUP, group)
+        B.mdcnn_set_option(B.MDCNN_OPT_PIPE_MODE, mode)
+        g = GpuNet(net, crops=True)
+        try:
+            got_o, got_r = [], []
+            for t0 in range(0, n, cut):
+                sl = slice(t0, min(t0 + cut, n))
+                o, r = g.frames_crop(Xs[sl], dys[sl], dxs[sl], crops[sl], depth=depth)
+                got_o += o
+                got_r += r
+            torch.cuda.synchronize()
+            assert got_r == ref_r
+            for t in range(n):
+                for a, b in zip(ref_o[t], got_o[t]):
+                    assert torch.equal(a, b), f"frame {t}: cropped outputs differ"
+            for k, (u, v) in enumerate(zip(ref_s, state(g))):
+                assert np.array_equal(u, v), f"state view {k} differs"
+        finally:
+            B.mdcnn_set_option(B.MDCNN_OPT_PIPE_GROUP, 1)
+            B.mdcnn_set_option(B.MDCNN_OPT_PIPE_MODE, 1)
+            g.close()
