@@ -269,6 +269,8 @@ mdcnn_status mdcnn_frame_batch(mdcnn_net* const* nets, int n_streams, const void
  * the events cost more than the overlap gains.
  * The caller's stream forks into the others at the start and waits for them at the end,
  * so the call as a whole stays in stream order; nothing is synchronised with the host.
+ * With depth > 1 `stream` must not be capturing into a HIP graph (the fork into the
+ * library's streams would be captured with it).
  * Errors: MDCNN_ERR_SIZE for n_frames, depth or out_bytes out of range, MDCNN_ERR_STATE
  * if outputs overlap or the network has a crop smaller than its view, MDCNN_ERR_NULL /
  * MDCNN_ERR_ALIGN as for mdcnn_frame (checked for all frames before anything runs). */
