@@ -11,8 +11,8 @@ answers with a full reset).  The video goes through `mdcnn_frames`, one call per
 pass over the sequence, which keeps up to --frames-in-flight consecutive frames
 in flight (same launches, same results bit for bit as one `mdcnn_frame` call per
 frame; that rate is reported next to it as "frame_at_a_time" and is the headline
-with --frames-in-flight 1, for networks of fewer than ten launches per frame and in
-the --front-end mode, which has no such call; --crops uses mdcnn_frames_crop).
+with --frames-in-flight 1 and for networks of fewer than ten launches per frame;
+--crops uses mdcnn_frames_crop, --front-end mdcnn_frames_masked).
 
 Prints ONE JSON line.  Besides the throughput it carries
   roofline     -- the dominant kernel class, timed with HIP events recorded by
@@ -305,9 +305,8 @@ def main():
         state["resets"] += int(r)
 
     in_flight = a.frames_in_flight or (4 if len(B.mdcnn_frame_plan(g.net, 1)[0]) >= 10 else 1)
-    if a.front_end:
-        in_flight = 1
     outs_pool = [torch.empty_like(g.out) for _ in range(min(T, max(a.steps, a.warmup)))] if in_flight > 1 else []
+    masks_pool = [torch.empty((net.H, net.W), dtype=torch.uint8, device="cuda") for _ in outs_pool] if a.front_end else []
 
     def run_frames(n):
         """n frames of the video through mdcnn_frames, one call per pass over the sequence."""
@@ -317,7 +316,10 @@ def main():
             m = min(T - t0_ % T, n - done, len(outs_pool))
             idx = [(t0_ + k) % T for k in range(m)]
             sh = [(0, 0) if t0_ + k == 0 else (int(shifts[i][0]), int(shifts[i][1])) for k, i in enumerate(idx)]
-            if crops is not None:
+            if a.front_end:
+                _, _, rs = g.frames_masked([frames[i] for i in idx], [v[0] for v in sh], [v[1] for v in sh], outs=outs_pool[:m],
+                                           masks=masks_pool[:m], depth=in_flight, **FE)
+            elif crops is not None:
                 _, rs = g.frames_crop([frames_c[i] for i in idx], [v[0] for v in sh], [v[1] for v in sh], [crops[i] for i in idx],
                                       None if forced is None else [forced_c[i] for i in idx], outs=outs_pool[:m], depth=in_flight)
             else:
@@ -416,7 +418,7 @@ def main():
                    "input": [net.H, net.W, net.sites[0].C], "sites": len(net.sites), "edges": len(net.edges),
                    "resets_in_timed_steps": resets_timed, "mean_update_density": round(float(np.mean(dens)), 4),
                    "input_update_density": round(dens[0], 4), "frames_in_flight": in_flight,
-                   "entry_point": ("mdcnn_frames_crop" if crops is not None else "mdcnn_frames") + ", one call per pass over the sequence" if in_flight > 1 else
+                   "entry_point": ("mdcnn_frames_masked" if a.front_end else "mdcnn_frames_crop" if crops is not None else "mdcnn_frames") + ", one call per pass over the sequence" if in_flight > 1 else
                                   "mdcnn_frame_crop" if crops is not None else "mdcnn_shift_camera + mdcnn_input_mask + mdcnn_layer_forward" if a.front_end else "mdcnn_frame"},
         "roofline": roofline,
         "roofline_all": rl_all,
@@ -435,7 +437,7 @@ def main():
                          "gflop_per_frame": round(per_frame_flops / 1e9, 2), "mbytes_per_frame": round(per_frame_bytes / 1e6, 2)}
     if dt_each is not None:
         out["frame_at_a_time"] = {"value": round(a.steps / dt_each, 2), "unit": "frames/s", "ms_per_step": round(1e3 * dt_each / a.steps, 4),
-                                  "entry_point": "mdcnn_frame_crop" if crops is not None else "mdcnn_frame"}
+                                  "entry_point": "mdcnn_shift_camera + mdcnn_input_mask + mdcnn_layer_forward" if a.front_end else "mdcnn_frame_crop" if crops is not None else "mdcnn_frame"}
     if a.front_end:
         # the mask kernel alone, HIP events on the stream it is launched on (torch's current stream)
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

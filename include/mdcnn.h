@@ -344,6 +344,22 @@ mdcnn_status mdcnn_input_mask(const mdcnn_buffer* in, const void* frame_dev, con
                               const mdcnn_mask_params* prm, uint8_t* mask_dev, size_t mask_bytes,
                               void* stream);
 
+/* mdcnn_frames with the mask front end: for frame f, after the camera shift, the library
+ * runs mdcnn_input_mask(input site, frames_dev[f], roi_dev ? roi_dev[f] : NULL, prm) into
+ * masks_dev[f] (mask_bytes = H*W of the input site each; n_frames caller-owned buffers that
+ * must not overlap, kept as results) and forces that mask at the input site of frame f.
+ * roi_dev may be NULL or hold NULL entries (maps that depend on earlier results of the same
+ * call cannot be given: cut the video into shorter calls).  Everything else as for
+ * mdcnn_frames; results bit-identical to mdcnn_shift_camera, mdcnn_input_mask,
+ * mdcnn_layer_forward over all non-terminal sites and the readout, frame by frame.  Networks
+ * without crops only.  Errors: those of mdcnn_frames and of mdcnn_input_mask, all
+ * checked before anything runs; MDCNN_ERR_STATE also if two mask buffers overlap. */
+mdcnn_status mdcnn_frames_masked(mdcnn_net* net, int n_frames, const void* const* frames_dev,
+                                 const float* const* roi_dev, const mdcnn_mask_params* prm,
+                                 uint8_t* const* masks_dev, size_t mask_bytes, const int* dty,
+                                 const int* dtx, void* const* outs_dev, size_t out_bytes, int depth,
+                                 void* stream, int* did_full_reset);
+
 /* View-ordered access to a site's state (independent of the ring origin). */
 typedef enum {
     MDCNN_VIEW_A = 0,        /* H*W*C storage dtype: accumulated values                     */

@@ -30,7 +30,7 @@ STATUS_NAMES = {0: "OK", 1: "ERR_NULL", 2: "ERR_SHAPE", 3: "ERR_DTYPE", 4: "ERR_
 
 EXPORTS = ["mdcnn_conv_border", "mdcnn_buffer_bytes", "mdcnn_create_buffer", "mdcnn_destroy_buffer",
            "mdcnn_shift_camera", "mdcnn_set_crop", "mdcnn_layer_forward", "mdcnn_net_create", "mdcnn_net_destroy",
-           "mdcnn_frame", "mdcnn_frame_crop", "mdcnn_frame_batch", "mdcnn_frame_plan", "mdcnn_frames", "mdcnn_frames_crop", "mdcnn_frames_plan", "mdcnn_input_mask", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read",
+           "mdcnn_frame", "mdcnn_frame_crop", "mdcnn_frame_batch", "mdcnn_frame_plan", "mdcnn_frames", "mdcnn_frames_crop", "mdcnn_frames_masked", "mdcnn_frames_plan", "mdcnn_input_mask", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read",
            "mdcnn_pack_weights", "mdcnn_last_error", "mdcnn_version"]
 
 
@@ -83,6 +83,8 @@ def lib():
         L.mdcnn_frame_plan.argtypes = [vp, C.c_int, ip, ip, C.c_int, ip, ip]
         L.mdcnn_frames.argtypes = [vp, C.c_int, C.POINTER(vp), C.POINTER(vp), ip, ip, C.POINTER(vp), sz, C.c_int, vp, ip]
         L.mdcnn_frames_crop.argtypes = [vp, C.c_int, C.POINTER(vp), C.POINTER(vp), ip, ip, ip, C.POINTER(vp), C.POINTER(sz), C.c_int, vp, ip]
+        L.mdcnn_frames_masked.argtypes = [vp, C.c_int, C.POINTER(vp), C.POINTER(vp), C.POINTER(mdcnn_mask_params), C.POINTER(vp), sz, ip, ip,
+                                          C.POINTER(vp), sz, C.c_int, vp, ip]
         L.mdcnn_frames_plan.argtypes = [vp, C.c_int, ip, ip, ip, C.c_int, ip, C.c_int, ip, C.c_int, ip, ip]
         L.mdcnn_input_mask.argtypes = [vp, vp, vp, C.POINTER(mdcnn_mask_params), vp, sz, vp]
         L.mdcnn_read_view.argtypes = [vp, C.c_int, vp, sz, vp]
@@ -240,6 +242,18 @@ def mdcnn_frames_crop(net: int, frame_ptrs, forced_ptrs, dty, dtx, crops, out_pt
     _check(lib().mdcnn_frames_crop(net, n, (C.c_void_p * n)(*frame_ptrs), forced,
                                    (C.c_int * n)(*[int(v) for v in dty]), (C.c_int * n)(*[int(v) for v in dtx]), (C.c_int * (4 * n))(*flat),
                                    (C.c_void_p * n)(*out_ptrs), (C.c_size_t * n)(*[int(v) for v in out_bytes]), int(depth), stream, r))
+    return [bool(v) for v in r]
+
+
+def mdcnn_frames_masked(net: int, frame_ptrs, roi_ptrs, prm: mdcnn_mask_params, mask_ptrs, mask_bytes: int, dty, dtx, out_ptrs,
+                        out_bytes: int, depth: int = 0, stream: int = 0):
+    """mdcnn_frames with the input masks made by the library (mdcnn_input_mask) into mask_ptrs."""
+    n = len(frame_ptrs)
+    r = (C.c_int * n)()
+    roi = None if roi_ptrs is None else (C.c_void_p * n)(*roi_ptrs)
+    _check(lib().mdcnn_frames_masked(net, n, (C.c_void_p * n)(*frame_ptrs), roi, C.byref(prm), (C.c_void_p * n)(*mask_ptrs), mask_bytes,
+                                     (C.c_int * n)(*[int(v) for v in dty]), (C.c_int * n)(*[int(v) for v in dtx]),
+                                     (C.c_void_p * n)(*out_ptrs), out_bytes, int(depth), stream, r))
     return [bool(v) for v in r]
 
 

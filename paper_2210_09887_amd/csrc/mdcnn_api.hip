@@ -812,6 +812,24 @@ constexpr int kMaxFrames = 4096;
 constexpr int kDefaultDepth = 4;
 constexpr int kMinLaunchesInFlight = 10;   // launches of a frame from which on the default is kDefaultDepth streams
 
+// Masks made by the library itself for the frames of mdcnn_frames_masked.
+struct FrontEnd {
+    const mdcnn_mask_params* prm;
+    const float* const* roi;       // per frame, or nullptr
+    uint8_t* const* masks;         // per frame, written by the mask kernel, then forced at the input site
+    size_t mask_bytes;
+};
+
+mdcnn_status check_mask_params(const mdcnn_mask_params* prm, int Hc, int Wc, size_t mask_bytes) {
+    const int q = prm->pool;
+    if ((q != 1 && q != 2 && q != 4 && q != 8) || Hc % q || Wc % q)
+        return fail(MDCNN_ERR_SHAPE, "input_mask: pool must be 1, 2, 4 or 8 and divide the frame of %dx%d pixels", Hc, Wc);
+    if (prm->dilate < 0 || prm->dilate > kMaskMaxDilate || (prm->suppress != 0 && prm->suppress != 1))
+        return fail(MDCNN_ERR_SHAPE, "input_mask: 0 <= dilate <= %d, suppress is 0 or 1", kMaskMaxDilate);
+    if (mask_bytes != (size_t)Hc * Wc) return fail(MDCNN_ERR_SIZE, "input_mask: mask_bytes is %zu, the frame has %zu pixels", mask_bytes, (size_t)Hc * Wc);
+    return MDCNN_OK;
+}
+
 // n_frames consecutive frames of one network on `depth` streams (stream 0 is the caller's).  The
 // launches of a frame are those of mdcnn_frame on one stream, in the same order, except that the
 // initialisation of a camera shift is split up and rides along (see PipeGroup).  Frames are issued
@@ -820,8 +838,8 @@ constexpr int kMinLaunchesInFlight = 10;   // launches of a frame from which on 
 // by the waits of the plan.  Every site sees the same sequence of launches as with one frame at a
 // time, so the results are the same bit for bit.
 mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, const uint8_t* const* forced,
-                       const int* dty, const int* dtx, const int* crops, void* const* outs_dev, int depth, hipStream_t user,
-                       int* did_full_reset) {
+                       const int* dty, const int* dtx, const int* crops, const FrontEnd* fe, void* const* outs_dev, int depth,
+                       hipStream_t user, int* did_full_reset) {
     const int key = (g_pipe_group * 8 + depth) * 2 + g_pipe_mode;
     if (net->pipe.key != key) make_pipe_plan(net, g_pipe_group, depth, g_pipe_mode, net->pipe);
     const PipePlan& pp = net->pipe;
@@ -888,6 +906,11 @@ mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, 
                 err = wait_for(g, 0);
                 if (err == hipSuccess) err = launch_fill_jobs(jobs.data(), g.fill.data(), (int)g.fill.size(), s[pp.stream_of(f, 0)]);
                 if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: shift launch: %s", f, hipGetErrorString(err));
+                if (fe) {                                      // the input site is initialised: its mask for this frame
+                    rc = mdcnn_input_mask(net->sites[0], frames[f], fe->roi ? fe->roi[f] : nullptr, fe->prm, fe->masks[f], fe->mask_bytes,
+                                          s[pp.stream_of(f, 0)]);
+                    if (rc) return rc;
+                }
             }
             for (int c = g.call0; c < g.call1; ++c) {
                 hipStream_t st = s[pp.stream_of(f, c)];
@@ -911,7 +934,7 @@ mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, 
                 const mdcnn_conv_desc* edges = net->edges.data() + e0;
                 mdcnn_buffer* const* outs = outs_flat.data();
                 const void* X = frames[f];
-                const uint8_t* fm = forced ? forced[f] : nullptr;
+                const uint8_t* fm = fe ? fe->masks[f] : forced ? forced[f] : nullptr;
                 rc = do_forward(1, &in, i == 0 ? &X : nullptr, i == 0 ? &fm : nullptr, &edges, &outs, ne, st, fused_skip(net, e0, e1), nullptr,
                                 jobs.data(), riders, n_riders);
                 if (rc) return rc;
@@ -1200,8 +1223,8 @@ mdcnn_status mdcnn_frame_batch(mdcnn_net* const* nets, int n_streams, const void
 
 // Checks shared by mdcnn_frames and mdcnn_frames_crop; out_bytes[f] (crops) or out_bytes[0] (none) per frame.
 static mdcnn_status frames_checked(mdcnn_net* net, int n_frames, const void* const* frames_dev, const uint8_t* const* forced_masks_dev,
-                                   const int* dty, const int* dtx, const int* crops, void* const* outs_dev, const size_t* out_bytes,
-                                   int depth, void* stream, int* did_full_reset) {
+                                   const int* dty, const int* dtx, const int* crops, const FrontEnd* fe, void* const* outs_dev,
+                                   const size_t* out_bytes, int depth, void* stream, int* did_full_reset) {
     if (!net || !frames_dev || !dty || !dtx || !outs_dev || !out_bytes) return fail(MDCNN_ERR_NULL, "frames: NULL argument");
     if (n_frames < 1 || n_frames > kMaxFrames) return fail(MDCNN_ERR_SIZE, "frames: 1 <= n_frames <= %d", kMaxFrames);
     if (depth < 0 || depth > kMaxStreams) return fail(MDCNN_ERR_SIZE, "frames: 0 <= depth <= %d", kMaxStreams);
@@ -1222,6 +1245,21 @@ static mdcnn_status frames_checked(mdcnn_net* net, int n_frames, const void* con
         }
         if (out_bytes[f] != need) return fail(MDCNN_ERR_SIZE, "frames: frame %d: out_bytes is %zu, the cropped outputs take %zu", f, out_bytes[f], need);
     }
+    if (fe) {
+        const mdcnn_buffer* in = net->sites[0];
+        if (!fe->prm || !fe->masks) return fail(MDCNN_ERR_NULL, "frames: mask parameters / mask buffers missing");
+        mdcnn_status rc = check_mask_params(fe->prm, in->d.H, in->d.W, fe->mask_bytes);
+        if (rc) return rc;
+        std::vector<const uint8_t*> m((size_t)n_frames);
+        for (int f = 0; f < n_frames; ++f) {
+            if (!fe->masks[f]) return fail(MDCNN_ERR_NULL, "frames: frame %d: mask buffer is NULL", f);
+            if (fe->roi && ((uintptr_t)fe->roi[f] & 3)) return fail(MDCNN_ERR_ALIGN, "frames: frame %d: misaligned roi", f);
+            m[(size_t)f] = fe->masks[f];
+        }
+        std::sort(m.begin(), m.end());
+        for (int f = 1; f < n_frames; ++f)
+            if (m[(size_t)f] < m[(size_t)f - 1] + fe->mask_bytes) return fail(MDCNN_ERR_STATE, "frames: two mask buffers overlap");
+    }
     // frames in flight write their outputs in no fixed order: no two may share memory
     std::vector<std::pair<const char*, size_t>> o((size_t)n_frames);
     for (int f = 0; f < n_frames; ++f) o[(size_t)f] = {(const char*)outs_dev[f], out_bytes[crops ? f : 0]};
@@ -1235,20 +1273,28 @@ static mdcnn_status frames_checked(mdcnn_net* net, int n_frames, const void* con
         depth = (int)one.nodes.size() >= kMinLaunchesInFlight ? kDefaultDepth : 1;
     }
     if (n_frames == 1) depth = 1;
-    return frame_seq(net, n_frames, frames_dev, forced_masks_dev, dty, dtx, crops, outs_dev, depth, (hipStream_t)stream, did_full_reset);
+    return frame_seq(net, n_frames, frames_dev, forced_masks_dev, dty, dtx, crops, fe, outs_dev, depth, (hipStream_t)stream, did_full_reset);
 }
 
 mdcnn_status mdcnn_frames(mdcnn_net* net, int n_frames, const void* const* frames_dev, const uint8_t* const* forced_masks_dev,
                           const int* dty, const int* dtx, void* const* outs_dev, size_t out_bytes, int depth, void* stream,
                           int* did_full_reset) {
-    return frames_checked(net, n_frames, frames_dev, forced_masks_dev, dty, dtx, nullptr, outs_dev, &out_bytes, depth, stream, did_full_reset);
+    return frames_checked(net, n_frames, frames_dev, forced_masks_dev, dty, dtx, nullptr, nullptr, outs_dev, &out_bytes, depth, stream, did_full_reset);
 }
 
 mdcnn_status mdcnn_frames_crop(mdcnn_net* net, int n_frames, const void* const* frames_dev, const uint8_t* const* forced_masks_dev,
                                const int* dty, const int* dtx, const int* crops, void* const* outs_dev, const size_t* out_bytes,
                                int depth, void* stream, int* did_full_reset) {
     if (!crops) return fail(MDCNN_ERR_NULL, "frames_crop: crops is NULL");
-    return frames_checked(net, n_frames, frames_dev, forced_masks_dev, dty, dtx, crops, outs_dev, out_bytes, depth, stream, did_full_reset);
+    return frames_checked(net, n_frames, frames_dev, forced_masks_dev, dty, dtx, crops, nullptr, outs_dev, out_bytes, depth, stream, did_full_reset);
+}
+
+mdcnn_status mdcnn_frames_masked(mdcnn_net* net, int n_frames, const void* const* frames_dev, const float* const* roi_dev,
+                                 const mdcnn_mask_params* prm, uint8_t* const* masks_dev, size_t mask_bytes, const int* dty, const int* dtx,
+                                 void* const* outs_dev, size_t out_bytes, int depth, void* stream, int* did_full_reset) {
+    if (!prm || !masks_dev) return fail(MDCNN_ERR_NULL, "frames_masked: mask parameters / mask buffers missing");
+    const FrontEnd fe{prm, roi_dev, masks_dev, mask_bytes};
+    return frames_checked(net, n_frames, frames_dev, nullptr, dty, dtx, nullptr, &fe, outs_dev, &out_bytes, depth, stream, did_full_reset);
 }
 
 mdcnn_status mdcnn_frames_plan(mdcnn_net* net, int depth, int* first_call, int* wait_call, int* init_call, int cap_groups,
@@ -1285,12 +1331,9 @@ mdcnn_status mdcnn_input_mask(const mdcnn_buffer* in, const void* frame_dev, con
     j.x0 = in->d.crops ? in->dev.cx0() : 0;
     j.Hc = in->d.crops ? in->dev.cy1() - j.y0 : in->d.H;
     j.Wc = in->d.crops ? in->dev.cx1() - j.x0 : in->d.W;
+    const mdcnn_status rc = check_mask_params(prm, j.Hc, j.Wc, mask_bytes);
+    if (rc) return rc;
     const int q = prm->pool;
-    if ((q != 1 && q != 2 && q != 4 && q != 8) || j.Hc % q || j.Wc % q)
-        return fail(MDCNN_ERR_SHAPE, "input_mask: pool must be 1, 2, 4 or 8 and divide the frame of %dx%d pixels", j.Hc, j.Wc);
-    if (prm->dilate < 0 || prm->dilate > kMaskMaxDilate || (prm->suppress != 0 && prm->suppress != 1))
-        return fail(MDCNN_ERR_SHAPE, "input_mask: 0 <= dilate <= %d, suppress is 0 or 1", kMaskMaxDilate);
-    if (mask_bytes != (size_t)j.Hc * j.Wc) return fail(MDCNN_ERR_SIZE, "input_mask: mask_bytes is %zu, the frame has %zu pixels", mask_bytes, (size_t)j.Hc * j.Wc);
     if ((uintptr_t)frame_dev & (esize(in->d.dtype) - 1) || (uintptr_t)roi_dev & 3) return fail(MDCNN_ERR_ALIGN, "input_mask: misaligned frame or roi");
     j.X = frame_dev; j.roi = roi_dev; j.mask = mask_dev;
     j.theta = prm->theta; j.base = prm->sens_base; j.gain = prm->sens_gain;

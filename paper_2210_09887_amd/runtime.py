@@ -171,6 +171,22 @@ class GpuNet:
                            mask.numel(), self._stream())
         return mask
 
+    def frames_masked(self, Xs, dty, dtx, rois=None, outs=None, masks=None, depth=0, theta=None, base=0.4, gain=0.6, pool=1,
+                      suppress=False, dilate=0):
+        """Consecutive frames with the input masks made by mdcnn_input_mask inside the call.  Returns (outputs, masks,
+        reset flags)."""
+        prm = B.mdcnn_mask_params(float(self.spec.sites[0].theta if theta is None else theta), float(base), float(gain),
+                                  int(pool), int(bool(suppress)), int(dilate))
+        if outs is None:
+            outs = [torch.empty_like(self.out) for _ in Xs]
+        if masks is None:
+            masks = [torch.empty(x.shape[:2], dtype=torch.uint8, device=self.dev) for x in Xs]
+        r = B.mdcnn_frames_masked(self.net, [x.data_ptr() for x in Xs],
+                                  None if rois is None else [None if q is None else q.data_ptr() for q in rois], prm,
+                                  [m.data_ptr() for m in masks], masks[0].numel(), dty, dtx, [o.data_ptr() for o in outs],
+                                  self.out.numel() * self.esize, depth, self._stream())
+        return outs, masks, r
+
     def layer_forward(self, i, frame=None, forced=None):
         idx = [j for j, s in enumerate(self.esrc) if s == i]
         B.mdcnn_layer_forward(self.bufs[i], None if frame is None else frame.data_ptr(),

@@ -22,12 +22,16 @@ CASES = {
 }
 
 
-def state_of(g, net):
+def state_of(g, net, statistics=True):
+    """All state views; statistics=False leaves out the counters and the compute list of the last producer, which
+    depend on whether a residual skip had a launch of its own."""
     from paper_2210_09887_amd import binding as B
     state = []
     for i, s in enumerate(net.sites):
-        views = [B.MDCNN_VIEW_A, B.MDCNN_VIEW_DELTA, B.MDCNN_VIEW_FLAGS, B.MDCNN_VIEW_LIST, B.MDCNN_VIEW_STATS] if s.kind != "output" else []
-        views += [B.MDCNN_VIEW_P, B.MDCNN_VIEW_CLIST] if s.kind != "input" else []
+        views = [B.MDCNN_VIEW_A, B.MDCNN_VIEW_DELTA, B.MDCNN_VIEW_FLAGS, B.MDCNN_VIEW_LIST] if s.kind != "output" else []
+        views += [B.MDCNN_VIEW_STATS] if s.kind != "output" and statistics else []
+        views += [B.MDCNN_VIEW_P] if s.kind != "input" else []
+        views += [B.MDCNN_VIEW_CLIST] if s.kind != "input" and statistics else []
         state += [g.read(i, v) for v in views]
     return state
 
@@ -210,3 +214,70 @@ def test_cropped_frames_in_flight(name):
             B.mdcnn_set_option(B.MDCNN_OPT_PIPE_GROUP, 1)
             B.mdcnn_set_option(B.MDCNN_OPT_PIPE_MODE, 1)
             g.close()
+
+
+@pytest.mark.parametrize("name", ["c2_cnn5_96", "c3_resnet_96", "c4_hrnet_128x96"])
+def test_masked_frames_in_flight(name):
+    """mdcnn_frames_masked against shift, mdcnn_input_mask, the forward calls and the readout frame by frame: masks,
+    outputs, reset decisions and all state, with and without a sensitivity map."""
+    import gpu_harness as H
+    from paper_2210_09887_amd import binding as B
+    from paper_2210_09887_amd.runtime import GpuNet
+    cfg, kn, ks = CASES[name]
+    net, seq = build_net(cfg, **kn), build_sequence(cfg, **ks)
+    n = len(seq.frames)
+    Xs = [H.dev(X) for X in seq.frames]
+    dys, dxs = [int(s[0]) for s in seq.shifts], [int(s[1]) for s in seq.shifts]
+    rng = np.random.default_rng(7)
+    # the forward calls of the reference give every residual skip a launch of its own; mdcnn_frames_masked lets the delta
+    # kernel add it (same values, other statistics) unless told otherwise: compare everything with the option off, and
+    # everything but the statistics with the default
+    for fe, with_roi, fuse in [(dict(suppress=True, dilate=2), False, 0), (dict(pool=2, dilate=1, base=0.4, gain=0.6), True, 0),
+                               (dict(suppress=True, dilate=2), False, 1)]:
+        rois = [torch.from_numpy(rng.random((net.H, net.W), dtype=np.float32)).cuda() if with_roi and t % 2 else None for t in range(n)] if with_roi else None
+        g = GpuNet(net)
+        try:
+            ref_o, ref_m, ref_r = [], [], []
+            for t in range(n):
+                r = g.shift_camera(dys[t], dxs[t])
+                fm = g.input_mask(Xs[t], roi=None if rois is None else rois[t], **fe)
+                for i, sp in enumerate(net.sites):
+                    if sp.kind != "output":
+                        g.layer_forward(i, Xs[t] if i == 0 else None, fm if i == 0 else None)
+                o = torch.empty_like(g.out)
+                off = 0
+                for i in g.terminals:
+                    m = int(np.prod(g.shape[i]))
+                    B.mdcnn_read_view(g.bufs[i], B.MDCNN_VIEW_OUT, o[off:off + m].data_ptr(), m * g.esize, g._stream())
+                    off += m
+                torch.cuda.synchronize()
+                ref_o.append(o)
+                ref_m.append(fm.clone())
+                ref_r.append(r)
+            ref_s = state_of(g, net, statistics=not fuse)
+        finally:
+            g.close()
+        for depth, mode, cut in [(4, 1, n), (3, 0, 3), (1, 1, n)]:
+            print(f"{name}: front end {fe}, depth {depth}, mode {mode}, calls of {cut}, fused skips {fuse}", flush=True)
+            B.mdcnn_set_option(B.MDCNN_OPT_PIPE_MODE, mode)
+            B.mdcnn_set_option(B.MDCNN_OPT_FUSE_SKIP, fuse)
+            g = GpuNet(net)
+            try:
+                got_o, got_m, got_r = [], [], []
+                for t0 in range(0, n, cut):
+                    sl = slice(t0, min(t0 + cut, n))
+                    o, m, r = g.frames_masked(Xs[sl], dys[sl], dxs[sl], None if rois is None else rois[sl], depth=depth, **fe)
+                    got_o += o
+                    got_m += m
+                    got_r += r
+                torch.cuda.synchronize()
+                assert got_r == ref_r
+                for t in range(n):
+                    assert torch.equal(ref_m[t], got_m[t]), f"frame {t}: masks differ"
+                    assert torch.equal(ref_o[t], got_o[t]), f"frame {t}: outputs differ"
+                for k, (u, v) in enumerate(zip(ref_s, state_of(g, net, statistics=not fuse))):
+                    assert np.array_equal(u, v), f"state view {k} differs"
+            finally:
+                B.mdcnn_set_option(B.MDCNN_OPT_PIPE_MODE, 1)
+                B.mdcnn_set_option(B.MDCNN_OPT_FUSE_SKIP, 1)
+                g.close()
