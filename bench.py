@@ -7,8 +7,8 @@ residual adds, readout) on the headline workload: the ResNet-18-style 512x512
 fp16 network on the seeded 60-frame moving-camera sequence, all frames resident
 in HBM before the timed region starts.  The sequence is replayed cyclically (the
 jump back to its start is one more camera shift, which the buffer manager
-answers with a full reset).  The video goes through `mdcnn_frames`, one call per
-pass over the sequence, which keeps up to --frames-in-flight consecutive frames
+answers with a full reset).  The video goes through `mdcnn_frames`, in calls of as
+many frames as the sequence has, which keeps up to --frames-in-flight consecutive frames
 in flight (same launches, same results bit for bit as one `mdcnn_frame` call per
 frame; that rate is reported next to it as "frame_at_a_time" and is the headline
 with --frames-in-flight 1 and for networks of fewer than ten launches per frame;
@@ -309,11 +309,11 @@ def main():
     masks_pool = [torch.empty((net.H, net.W), dtype=torch.uint8, device="cuda") for _ in outs_pool] if a.front_end else []
 
     def run_frames(n):
-        """n frames of the video through mdcnn_frames, one call per pass over the sequence."""
+        """n frames of the video through mdcnn_frames, in calls of as many frames as the sequence has."""
         done = 0
         while done < n:
             t0_ = state["t"]
-            m = min(T - t0_ % T, n - done, len(outs_pool))
+            m = min(n - done, len(outs_pool))
             idx = [(t0_ + k) % T for k in range(m)]
             sh = [(0, 0) if t0_ + k == 0 else (int(shifts[i][0]), int(shifts[i][1])) for k, i in enumerate(idx)]
             if a.front_end:
@@ -418,7 +418,7 @@ def main():
                    "input": [net.H, net.W, net.sites[0].C], "sites": len(net.sites), "edges": len(net.edges),
                    "resets_in_timed_steps": resets_timed, "mean_update_density": round(float(np.mean(dens)), 4),
                    "input_update_density": round(dens[0], 4), "frames_in_flight": in_flight,
-                   "entry_point": ("mdcnn_frames_masked" if a.front_end else "mdcnn_frames_crop" if crops is not None else "mdcnn_frames") + ", one call per pass over the sequence" if in_flight > 1 else
+                   "entry_point": ("mdcnn_frames_masked" if a.front_end else "mdcnn_frames_crop" if crops is not None else "mdcnn_frames") + f", calls of {len(outs_pool)} frames" if in_flight > 1 else
                                   "mdcnn_frame_crop" if crops is not None else "mdcnn_shift_camera + mdcnn_input_mask + mdcnn_layer_forward" if a.front_end else "mdcnn_frame"},
         "roofline": roofline,
         "roofline_all": rl_all,

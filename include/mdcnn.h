@@ -403,9 +403,14 @@ typedef enum {
                              /* residual skip (identity edge) instead of a launch of its own; */
                              /* such an edge then adds nothing to the compute-list statistics  */
                              /* of its destination.  0: one launch per edge                  */
-    MDCNN_OPT_PIPE_GROUP = 10, /* mdcnn_frames: forward calls per group of the frame pipeline (1..64, */
-                             /* default 1): smaller groups let a frame follow the one before it more */
-                             /* closely, at one more event and wait per group and frame            */
+    MDCNN_OPT_PIPE_GROUP = 10, /* mdcnn_frames: forward calls per group of the frame pipeline (1..64): smaller */
+                             /* groups let a frame follow the one before it more closely, at one more event   */
+                             /* and wait per group and frame.  0 (default): about twenty groups per frame,    */
+                             /* four calls per group at most                                                 */
+    MDCNN_OPT_PIPE_THREADS = 12, /* mdcnn_frames: 1 (default) in mode 1, runs of at least 4 x depth frames are    */
+                             /* issued by one host thread per stream (started and joined inside the call; a   */
+                             /* frame is issued after the events it waits for have been recorded); 0: the     */
+                             /* calling thread issues everything                                             */
     MDCNN_OPT_PIPE_MODE = 11, /* mdcnn_frames: 1 (default) whole frames on streams, 0 runs of calls on streams */
     MDCNN_OPT_STREAMS = 9    /* 2..4: mdcnn_frame, mdcnn_frame_crop and mdcnn_frame_batch put       */
                              /* independent branches of the network on up to this many streams:     */

@@ -6,7 +6,10 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
 #include <new>
+#include <string>
+#include <thread>
 #include <utility>
 #include <vector>
 
@@ -21,8 +24,9 @@ int g_conv_path = 0;
 int g_fuse_skip = 1;      // mdcnn_frame: residual skips are added by the step-1 kernel of their source
 int g_profile = 0;
 int g_streams = 0;        // mdcnn_frame: independent branches of the network go to up to this many streams; 0: decide per network
-int g_pipe_group = 1;     // mdcnn_frames: forward calls per group of the frame pipeline
+int g_pipe_group = 0;     // mdcnn_frames: forward calls per group of the frame pipeline, 0: by the length of the network
 int g_pipe_mode = 1;      // mdcnn_frames: 1 whole frames on streams, 0 runs of layers on streams
+int g_pipe_threads = 1;   // mdcnn_frames: one issuing host thread per stream (mode 1, long runs)
 
 // Profiling mode: every kernel launch is bracketed by a pair of events on its
 // own stream; mdcnn_profile_read waits for them and sums the times per class.
@@ -837,19 +841,66 @@ mdcnn_status check_mask_params(const mdcnn_mask_params* prm, int Hc, int Wc, siz
 // stream or by an event: within a frame where the stream changes between two calls, across frames
 // by the waits of the plan.  Every site sees the same sequence of launches as with one frame at a
 // time, so the results are the same bit for bit.
+// Forward calls per group.  Left to itself the library cuts a frame into about twenty groups, four calls at
+// most: every group costs an event and a wait per frame, and a long network (config 4: 85 calls) is
+// bound by those, while a short one needs the frames to follow each other closely (measured: config 3,
+// 18 calls, 3.3 k frames/s with groups of 1 and 2.8 k with groups of 4; config 4 1.45 k and 1.6 k).
+int pipe_group(const mdcnn_net* net) {
+    if (g_pipe_group) return g_pipe_group;
+    int n_calls = 0;
+    for (const mdcnn_buffer* b : net->sites) n_calls += b->d.kind != MDCNN_SITE_OUTPUT;
+    const int g = (n_calls + 10) / 20;
+    return g < 1 ? 1 : g > 4 ? 4 : g;
+}
+
+// What the issue of one frame needs, fixed before anything is issued: the sites as they stand after the
+// frame's camera shift (ring origins, crop) and their initialisation jobs.  With these, frames can be issued
+// by different host threads although the camera state of the network moves on from frame to frame.
+struct FrameWork {
+    std::vector<mdcnn_buffer> sites;
+    std::vector<FillJob> jobs;
+};
+
+// Progress of the issue of frame f, for the threads that issue other frames: done[f] = c + 1 once everything
+// up to and including forward call c (the readout: n_calls) has been issued, events included.
+struct IssueShared {
+    std::vector<std::atomic<int>> done;
+    std::atomic<bool> abort{false};
+    explicit IssueShared(int n) : done((size_t)n) { for (auto& d : done) d.store(0, std::memory_order_relaxed); }
+};
+
 mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, const uint8_t* const* forced,
                        const int* dty, const int* dtx, const int* crops, const FrontEnd* fe, void* const* outs_dev, int depth,
                        hipStream_t user, int* did_full_reset) {
-    const int key = (g_pipe_group * 8 + depth) * 2 + g_pipe_mode;
-    if (net->pipe.key != key) make_pipe_plan(net, g_pipe_group, depth, g_pipe_mode, net->pipe);
+    const int group = pipe_group(net), key = (group * 8 + depth) * 2 + g_pipe_mode;
+    if (net->pipe.key != key) make_pipe_plan(net, group, depth, g_pipe_mode, net->pipe);
     const PipePlan& pp = net->pipe;
-    const int n_calls = (int)pp.call_site.size(), ring = 3;
+    const int n_calls = (int)pp.call_site.size(), n_sites = (int)net->sites.size(), ring = 3;
     // events: ring x n_events for the plan, then one per stream for fork and join
     const size_t ev_sync = (size_t)ring * pp.n_events;
     hipError_t err = aux_prepare(depth, ev_sync + kMaxStreams);
     hipStream_t s[kMaxStreams];
     s[0] = user;
     for (int k = 1; k < depth; ++k) s[k] = g_aux.s[k - 1];
+    // the camera path of the whole run, on the host: every frame gets its own copy of the sites
+    std::vector<FrameWork> work((size_t)n_frames);
+    {
+        std::vector<FillJob> jobs;
+        for (int f = 0; f < n_frames; ++f) {
+            bool full = false;
+            mdcnn_status rc = shift_jobs(net->sites.data(), n_sites, dty[f], dtx[f], jobs, &full);
+            if (rc) return rc;
+            if (did_full_reset) did_full_reset[f] = full ? 1 : 0;
+            if (crops) {
+                rc = mdcnn_set_crop(net->sites.data(), n_sites, crops[4 * f], crops[4 * f + 1], crops[4 * f + 2], crops[4 * f + 3]);
+                if (rc) return rc;
+            }
+            FrameWork& w = work[(size_t)f];
+            w.sites.reserve((size_t)n_sites);
+            for (int i = 0; i < n_sites; ++i) w.sites.push_back(*net->sites[(size_t)i]);
+            w.jobs = jobs;
+        }
+    }
     if (err == hipSuccess && depth > 1) err = hipEventRecord(g_aux.events[ev_sync], user);
     for (int k = 1; k < depth && err == hipSuccess; ++k) err = hipStreamWaitEvent(s[k], g_aux.events[ev_sync], 0);
     if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "stream set-up: %s", hipGetErrorString(err));
@@ -868,8 +919,6 @@ mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, 
         }
         ~Join() { (void)run(); }
     } join{s, depth, ev_sync, false};
-    static thread_local std::vector<FillJob> jobs;
-    std::vector<mdcnn_buffer*> outs_flat;
     // which events of a frame somebody on another stream waits for (those recorded for nobody cost host time)
     std::vector<char> wanted((size_t)n_calls + 1, 0);
     for (size_t gi = 0; gi < pp.groups.size(); ++gi) {
@@ -879,36 +928,43 @@ mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, 
     }
     for (int c = 1; c < n_calls; ++c)
         if (pp.forward[(size_t)c]) wanted[(size_t)c - 1] = 1;
-    for (int f = 0; f < n_frames; ++f) {
-        bool full = false;
-        mdcnn_status rc = shift_jobs(net->sites.data(), (int)net->sites.size(), dty[f], dtx[f], jobs, &full);
-        if (rc) return rc;
-        if (did_full_reset) did_full_reset[f] = full ? 1 : 0;
-        if (crops) {                                           // the descriptors of this frame's launches carry its crop
-            rc = mdcnn_set_crop(net->sites.data(), (int)net->sites.size(), crops[4 * f], crops[4 * f + 1], crops[4 * f + 2], crops[4 * f + 3]);
-            if (rc) return rc;
-        }
-        hipEvent_t* ev_prev = g_aux.events.data() + (size_t)((f + ring - 1) % ring) * pp.n_events;
-        hipEvent_t* ev_mine = g_aux.events.data() + (size_t)(f % ring) * pp.n_events;
-        auto record = [&](int call) {
-            return depth > 1 && wanted[(size_t)call] ? hipEventRecord(ev_mine[pp.event_of_call[(size_t)call]], s[pp.stream_of(f, call)]) : hipSuccess;
+    hipEvent_t* const events = g_aux.events.data();          // (thread-local storage of the calling thread)
+    IssueShared shared(n_frames);
+
+    // Issues frame f.  `threaded`: frame f - 1 is being issued by another thread, so an event of it is
+    // waited for only after that thread has recorded it.
+    auto issue_frame = [&](int f, bool threaded) -> mdcnn_status {
+        FrameWork& w = work[(size_t)f];
+        const FillJob* jobs = w.jobs.data();
+        hipEvent_t* ev_prev = events + (size_t)((f + ring - 1) % ring) * pp.n_events;
+        hipEvent_t* ev_mine = events + (size_t)(f % ring) * pp.n_events;
+        std::vector<mdcnn_buffer*> outs_flat;
+        hipError_t err = hipSuccess;
+        auto issued = [&](int call) {                          // everything up to `call` is issued
+            if (depth > 1 && wanted[(size_t)call]) err = hipEventRecord(ev_mine[pp.event_of_call[(size_t)call]], s[pp.stream_of(f, call)]);
+            shared.done[(size_t)f].store(call + 1, std::memory_order_release);
+            return err;
         };
         // the stream that is about to initialise the sites of group g waits for the frame before to be done with them
         auto wait_for = [&](const PipeGroup& g, int carrier) {
             if (f == 0 || depth == 1 || g.wait_call < 0) return hipSuccess;
             const int mine = pp.stream_of(f, carrier);
             if (pp.stream_of(f - 1, g.wait_call) == mine) return hipSuccess;      // same stream: in order anyway
+            while (threaded && shared.done[(size_t)f - 1].load(std::memory_order_acquire) <= g.wait_call) {
+                if (shared.abort.load(std::memory_order_relaxed)) return hipErrorUnknown;
+                std::this_thread::yield();
+            }
             return hipStreamWaitEvent(s[mine], ev_prev[pp.event_of_call[(size_t)g.wait_call]], 0);
         };
         for (size_t gi = 0; gi < pp.groups.size(); ++gi) {
             const PipeGroup& g = pp.groups[gi];
             if (gi == 0) {
                 err = wait_for(g, 0);
-                if (err == hipSuccess) err = launch_fill_jobs(jobs.data(), g.fill.data(), (int)g.fill.size(), s[pp.stream_of(f, 0)]);
+                if (err == hipSuccess) err = launch_fill_jobs(jobs, g.fill.data(), (int)g.fill.size(), s[pp.stream_of(f, 0)]);
                 if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: shift launch: %s", f, hipGetErrorString(err));
                 if (fe) {                                      // the input site is initialised: its mask for this frame
-                    rc = mdcnn_input_mask(net->sites[0], frames[f], fe->roi ? fe->roi[f] : nullptr, fe->prm, fe->masks[f], fe->mask_bytes,
-                                          s[pp.stream_of(f, 0)]);
+                    mdcnn_status rc = mdcnn_input_mask(&w.sites[0], frames[f], fe->roi ? fe->roi[f] : nullptr, fe->prm, fe->masks[f],
+                                                       fe->mask_bytes, s[pp.stream_of(f, 0)]);
                     if (rc) return rc;
                 }
             }
@@ -923,36 +979,72 @@ mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, 
                 if (c == g.call1 - 1 && gi + 1 < pp.groups.size()) {          // the next group's sites are initialised here
                     const PipeGroup& nx = pp.groups[gi + 1];
                     err = wait_for(nx, c);
-                    if (err == hipSuccess && (int)nx.fill.size() > kMaxRiders) err = launch_fill_jobs(jobs.data(), nx.fill.data(), (int)nx.fill.size(), st);
+                    if (err == hipSuccess && (int)nx.fill.size() > kMaxRiders) err = launch_fill_jobs(jobs, nx.fill.data(), (int)nx.fill.size(), st);
                     else { riders = nx.fill.data(); n_riders = (int)nx.fill.size(); }
                     if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: shift launch: %s", f, hipGetErrorString(err));
                 }
                 const int i = pp.call_site[c], e0 = pp.call_e0[c], e1 = pp.call_e1[c], ne = e1 - e0;
                 outs_flat.resize((size_t)(ne > 0 ? ne : 1));
-                for (int e = e0; e < e1; ++e) outs_flat[(size_t)(e - e0)] = net->sites[net->edst[e]];
-                mdcnn_buffer* in = net->sites[i];
+                for (int e = e0; e < e1; ++e) outs_flat[(size_t)(e - e0)] = &w.sites[(size_t)net->edst[e]];
+                mdcnn_buffer* in = &w.sites[(size_t)i];
                 const mdcnn_conv_desc* edges = net->edges.data() + e0;
                 mdcnn_buffer* const* outs = outs_flat.data();
                 const void* X = frames[f];
                 const uint8_t* fm = fe ? fe->masks[f] : forced ? forced[f] : nullptr;
-                rc = do_forward(1, &in, i == 0 ? &X : nullptr, i == 0 ? &fm : nullptr, &edges, &outs, ne, st, fused_skip(net, e0, e1), nullptr,
-                                jobs.data(), riders, n_riders);
+                mdcnn_status rc = do_forward(1, &in, i == 0 ? &X : nullptr, i == 0 ? &fm : nullptr, &edges, &outs, ne, st,
+                                             fused_skip(net, e0, e1), nullptr, jobs, riders, n_riders);
                 if (rc) return rc;
-                err = record(c);
-                if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: event: %s", f, hipGetErrorString(err));
+                if (issued(c) != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: event: %s", f, hipGetErrorString(err));
             }
         }
         hipStream_t st = s[pp.stream_of(f, n_calls)];
         char* o = (char*)outs_dev[f];
-        for (mdcnn_buffer* b : net->sites) {
-            if (b->d.kind != MDCNN_SITE_OUTPUT) continue;
-            err = timed(kClsReadout, st, [&] { return launch_read_view(b->dev, crops ? MDCNN_VIEW_CROP_OUT : MDCNN_VIEW_OUT, o, st); });
+        for (mdcnn_buffer& b : w.sites) {
+            if (b.d.kind != MDCNN_SITE_OUTPUT) continue;
+            err = timed(kClsReadout, st, [&] { return launch_read_view(b.dev, crops ? MDCNN_VIEW_CROP_OUT : MDCNN_VIEW_OUT, o, st); });
             if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: readout launch: %s", f, hipGetErrorString(err));
-            o += crop_pixels(b) * b->d.C * esize(b->d.dtype);
+            o += crop_pixels(&b) * b.d.C * esize(b.d.dtype);
         }
-        err = record(n_calls);
-        if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: event: %s", f, hipGetErrorString(err));
+        if (issued(n_calls) != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: event: %s", f, hipGetErrorString(err));
+        return MDCNN_OK;
+    };
+
+    // One issuing thread per stream where whole frames go to streams and the run is long enough to pay for
+    // starting them; the profiling mode keeps its event lists on the calling thread.  Frame 0 is issued first
+    // and alone: it takes every kernel of the network through its first launch on this thread.
+    const bool threads = g_pipe_threads && pp.mode == 1 && depth > 1 && n_frames >= 4 * depth && !g_profile;
+    mdcnn_status rc = MDCNN_OK;
+    if (!threads) {
+        for (int f = 0; f < n_frames && rc == MDCNN_OK; ++f) rc = issue_frame(f, false);
+    } else {
+        rc = issue_frame(0, false);
+        if (rc == MDCNN_OK) {
+            int device = 0;
+            (void)hipGetDevice(&device);
+            std::vector<mdcnn_status> st_of((size_t)depth, MDCNN_OK);
+            std::vector<std::string> msg_of((size_t)depth);
+            auto worker = [&](int k) {
+                if (k) (void)hipSetDevice(device);
+                for (int f = k ? k : depth; f < n_frames; f += depth) {
+                    if (shared.abort.load(std::memory_order_relaxed)) break;
+                    const mdcnn_status r = issue_frame(f, true);
+                    if (r != MDCNN_OK) {
+                        st_of[(size_t)k] = r;
+                        msg_of[(size_t)k] = g_err;               // the message is in this thread's buffer
+                        shared.abort.store(true, std::memory_order_relaxed);
+                        break;
+                    }
+                }
+            };
+            std::vector<std::thread> pool;
+            for (int k = 1; k < depth; ++k) pool.emplace_back(worker, k);
+            worker(0);
+            for (std::thread& t : pool) t.join();
+            for (int k = 0; k < depth && rc == MDCNN_OK; ++k)
+                if (st_of[(size_t)k] != MDCNN_OK) rc = fail(st_of[(size_t)k], "%s", msg_of[(size_t)k].c_str());
+        }
     }
+    if (rc) return rc;
     err = join.run();
     if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "stream synchronisation: %s", hipGetErrorString(err));
     return MDCNN_OK;
@@ -969,8 +1061,9 @@ mdcnn_status mdcnn_set_option(int option, int value) {
     if (option == MDCNN_OPT_CONV_PATH && value >= 0 && value <= 3) { g_conv_path = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_CONV_HALO && value >= 0 && value <= 2) { g_halo = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_STREAMS && value >= 0 && value <= kMaxStreams) { g_streams = value; return MDCNN_OK; }
-    if (option == MDCNN_OPT_PIPE_GROUP && value >= 1 && value <= 64) { g_pipe_group = value; return MDCNN_OK; }
+    if (option == MDCNN_OPT_PIPE_GROUP && value >= 0 && value <= 64) { g_pipe_group = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_PIPE_MODE && (value == 0 || value == 1)) { g_pipe_mode = value; return MDCNN_OK; }
+    if (option == MDCNN_OPT_PIPE_THREADS && (value == 0 || value == 1)) { g_pipe_threads = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_FUSE_SKIP && (value == 0 || value == 1)) { g_fuse_skip = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_CONV_HALO_SUB && (value == 0 || value == 1 || value == 2 || value == 4)) { g_halo_sub = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_PROFILE && (value == 0 || value == 1)) { g_profile = value; return MDCNN_OK; }
@@ -1302,7 +1395,7 @@ mdcnn_status mdcnn_frames_plan(mdcnn_net* net, int depth, int* first_call, int* 
     if (!net) return fail(MDCNN_ERR_NULL, "net is NULL");
     if (depth < 0 || depth > kMaxStreams) return fail(MDCNN_ERR_SIZE, "frames_plan: 0 <= depth <= %d", kMaxStreams);
     PipePlan pp;
-    make_pipe_plan(net, g_pipe_group, depth ? depth : kDefaultDepth, g_pipe_mode, pp);
+    make_pipe_plan(net, pipe_group(net), depth ? depth : kDefaultDepth, g_pipe_mode, pp);
     const int n = (int)pp.groups.size(), n_sites = (int)net->sites.size(), nc = (int)pp.call_site.size();
     if ((first_call || wait_call || init_call) && cap_groups < n) return fail(MDCNN_ERR_SIZE, "frames_plan: %d groups, room for %d", n, cap_groups);
     if (group_of_site && cap_sites < n_sites) return fail(MDCNN_ERR_SIZE, "frames_plan: %d sites, room for %d", n_sites, cap_sites);

@@ -76,7 +76,7 @@ def in_flight(net, seq, depth, group, cuts, mode=1):
         torch.cuda.synchronize()
         return outs, resets, state_of(g, net)
     finally:
-        B.mdcnn_set_option(B.MDCNN_OPT_PIPE_GROUP, 1)
+        B.mdcnn_set_option(B.MDCNN_OPT_PIPE_GROUP, 0)
         B.mdcnn_set_option(B.MDCNN_OPT_PIPE_MODE, 1)
         g.close()
 
@@ -211,7 +211,7 @@ def test_cropped_frames_in_flight(name):
             for k, (u, v) in enumerate(zip(ref_s, state(g))):
                 assert np.array_equal(u, v), f"state view {k} differs"
         finally:
-            B.mdcnn_set_option(B.MDCNN_OPT_PIPE_GROUP, 1)
+            B.mdcnn_set_option(B.MDCNN_OPT_PIPE_GROUP, 0)
             B.mdcnn_set_option(B.MDCNN_OPT_PIPE_MODE, 1)
             g.close()
 
@@ -281,3 +281,23 @@ def test_masked_frames_in_flight(name):
                 B.mdcnn_set_option(B.MDCNN_OPT_PIPE_MODE, 1)
                 B.mdcnn_set_option(B.MDCNN_OPT_FUSE_SKIP, 1)
                 g.close()
+
+
+@pytest.mark.parametrize("name,n", [("c3_resnet_96", 40), ("c4_hrnet_128x96", 26), ("c2_cnn5_96", 33)])
+def test_long_runs_issued_by_one_thread_per_stream(name, n):
+    """Runs of at least 4 x depth frames are issued by one host thread per stream (a frame is issued only after the
+    events it waits for have been recorded by the thread of the frame before).  Same bits as one call per frame and
+    as the single-threaded issue; several calls in a row, so that threads start and end more than once."""
+    from paper_2210_09887_amd import binding as B
+    cfg, kn, ks = CASES[name]
+    net, seq = build_net(cfg, **kn), build_sequence(cfg, **dict(ks, n_frames=n))
+    ref = one_by_one(net, seq)
+    assert sum(ref[1]) >= 1
+    try:
+        for threads in (1, 0):
+            B.mdcnn_set_option(B.MDCNN_OPT_PIPE_THREADS, threads)
+            for depth, cuts in [(4, ()), (2, (n // 2,)), (3, (12, 12))]:
+                print(f"{name}: {n} frames, depth {depth}, calls {cuts or 'one'}, threads {threads}", flush=True)
+                same(ref, in_flight(net, seq, depth, 1, cuts), f"depth {depth}, cuts {cuts}, threads {threads}")
+    finally:
+        B.mdcnn_set_option(B.MDCNN_OPT_PIPE_THREADS, 1)

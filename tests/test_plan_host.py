@@ -185,7 +185,7 @@ def test_frames_in_flight_never_share_a_site(name, group, depth, mode):
         for i in range(len(spec.sites)):
             assert [c for c, t in frame0 if i in t][0] is None, f"site {i} is used before it is initialised"
     finally:
-        B.mdcnn_set_option(B.MDCNN_OPT_PIPE_GROUP, 1)
+        B.mdcnn_set_option(B.MDCNN_OPT_PIPE_GROUP, 0)
         B.mdcnn_set_option(B.MDCNN_OPT_PIPE_MODE, 1)
         B.mdcnn_net_destroy(net)
         for b in bufs:
