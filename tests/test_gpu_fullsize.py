@@ -241,7 +241,7 @@ def test_config3_full_512_input_masks():
         g.close()
 
 
-@pytest.mark.parametrize("cfg,n", [(3, 24), (4, 20), (5, 25)])
+@pytest.mark.parametrize("cfg,n", [(2, 30), (3, 24), (4, 20), (5, 25)])
 def test_full_size_frames_in_flight(cfg, n):
     """The launch configuration bench.py times: the video through mdcnn_frames on four streams, against one
     mdcnn_frame call per frame (itself checked against the oracle above) - outputs, reset decisions and all state."""
