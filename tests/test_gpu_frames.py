@@ -14,6 +14,7 @@ from inputs.nets import random_dag_net
 pytestmark = pytest.mark.gpu
 
 CASES = {
+    "c1_single_conv": (1, {}, {}),
     "c2_cnn5_96": (2, dict(H=96, W=96), dict(n_frames=7, H=96, W=96)),
     "c3_resnet_96": (3, dict(H=96, W=96, widths=(32, 64, 64, 128)), dict(n_frames=9, H=96, W=96)),
     "c3_resnet_poolstem_128": (3, dict(H=128, W=128, widths=(32, 64, 64, 128), pool_stem=True), dict(n_frames=6, H=128, W=128, tile=16)),
