@@ -513,6 +513,19 @@ __device__ __forceinline__ int tile_prologue_sub(const EdgeDev& e, int seg, int 
 // through LDS, so the result does not depend on timing; P is then updated with
 // 16-byte accesses.
 // ---------------------------------------------------------------------------
+// Buffer loads: the address is a resource (base, size) in scalar registers + a per-lane byte offset + a
+// scalar byte offset, so a wave spends one vector register on all the addresses of a tensor instead of a
+// 64-bit pointer per load (reads past `bytes` return zero instead of faulting).
+using rsrc_t = __amdgpu_buffer_rsrc_t;
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ rsrc_t make_rsrc(const void* p, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ f16x8 buf_load16(rsrc_t r, unsigned lane_bytes, unsigned wave_bytes) {
+    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_bytes, (int)wave_bytes, 0);
+    return __builtin_bit_cast(f16x8, v);
+}
+
 template <int NSUB, int WMV, int WK, int TM, int TN, int KC, int NLD_, int KS, int RING_ = 3, int MINB_ = (NSUB >= 2 ? 2 : 1)>
 struct HaloCfg {
     static constexpr int SUB = kSegPixels / NSUB;    // indices (and at most entries) per tile
@@ -564,9 +577,11 @@ void k_conv_halo(EdgeBatch eb, int NT, int work_items) {
     const int ntiles = edge_segments(e) * NSUB;
     const int nchunks = e.Cin / KC;
     const int nwin = e.Hp * e.Wp;
-    const f16* __restrict__ delta = (const f16*)e.delta;
-    const long long tap_stride = (long long)(e.Cin / 16) * e.Cout * 16;   // packed weights: halves per tap
-    const long long blk_stride = (long long)e.Cout * 16;                  //                 per 16-channel block
+    // (the host checks that both tensors are smaller than 2 GiB)
+    const rsrc_t drs = make_rsrc(e.delta, (unsigned)e.sH * (unsigned)e.sW * (unsigned)e.Cin * 2u);
+    const rsrc_t wrs = make_rsrc(e.wp, (unsigned)(KS * KS) * (unsigned)e.Cin * (unsigned)e.Cout * 2u);
+    const unsigned tap_stride = (unsigned)(e.Cin / 16) * (unsigned)e.Cout * 32u;   // packed weights: bytes per tap
+    const unsigned blk_stride = (unsigned)e.Cout * 32u;                            //                 per 16-channel block
 
     carry_source_compaction(e, sh);
 
@@ -603,14 +618,14 @@ void k_conv_halo(EdgeBatch eb, int NT, int work_items) {
         // pixel 0 and never stored; their rows are zeroed once per tile.
         f16x8 hreg[NLD];
         unsigned hval = 0;
-        unsigned hsrc[NLD];                               // element offsets (the host checks they fit 32 bits)
+        unsigned hsrc[NLD];                               // byte offsets into the delta map
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
             const int q = tid + 256 * j, pos = q / CPR;
             const bool inr = pos < npos;
             const int pix = inr ? s_pix[pos] : -1;
             hval |= (pix >= 0 ? 1u : 0u) << j;
-            hsrc[j] = (unsigned)(pix >= 0 ? pix : 0) * (unsigned)e.Cin + (q % CPR) * 8;
+            hsrc[j] = ((unsigned)(pix >= 0 ? pix : 0) * (unsigned)e.Cin + (q % CPR) * 8) * 2u;
             if (inr && pix < 0) {
                 f16x8 z;
 #pragma unroll
@@ -627,7 +642,7 @@ void k_conv_halo(EdgeBatch eb, int NT, int work_items) {
                 }
         };
 #pragma unroll
-        for (int j = 0; j < NLD; ++j) hreg[j] = *reinterpret_cast<const f16x8*>(delta + hsrc[j]);
+        for (int j = 0; j < NLD; ++j) hreg[j] = buf_load16(drs, hsrc[j], 0u);
         halo_store();
 
         f32x16 acc[TM][TN];
@@ -643,7 +658,8 @@ void k_conv_halo(EdgeBatch eb, int NT, int work_items) {
             const int r = (i * WMV + wm) * 32 + r32;
             rowoff[i] = kh * 8 + wk * 16 + (r < tot ? ((s_wy[r] - e.by0 - e.pad - iy0) * RW + (s_wx[r] - e.bx0 - e.pad - ix0)) * LDK : 0);
         }
-        const f16* wlane = (const f16*)e.wp + ((long long)wk * e.Cout + n0 + r32) * 16 + kh * 8;
+        const unsigned wlane = (unsigned)(r32 * 16 + kh * 8) * 2u;                      // this lane's bytes within a fragment
+        const unsigned wwave = ((unsigned)wk * (unsigned)e.Cout + (unsigned)n0) * 32u;   // this wave's K block and cout tile
         __syncthreads();
 
         // The K loop for L live row tiles of this wave.  Step i of a chunk: tap i / MB,
@@ -655,9 +671,9 @@ void k_conv_halo(EdgeBatch eb, int NT, int work_items) {
             f16x8 fa[D][TN], fb[FBR][L > 0 ? L : 1];
             auto load_a = [&](int slot, int c, int i) {              // i may run into the next chunk
                 const int cc = i < NS ? c : (c + 1 < nchunks ? c + 1 : c), ii = i < NS ? i : i - NS;
-                const f16* src = wlane + (ii / MB) * tap_stride + (cc * KB + WK * (ii % MB)) * blk_stride;
+                const unsigned src = wwave + (unsigned)(ii / MB) * tap_stride + (unsigned)(cc * KB + WK * (ii % MB)) * blk_stride;
 #pragma unroll
-                for (int j = 0; j < TN; ++j) fa[slot][j] = *reinterpret_cast<const f16x8*>(src + j * 32 * 16);
+                for (int j = 0; j < TN; ++j) fa[slot][j] = buf_load16(wrs, wlane, src + (unsigned)j * 32u * 32u);
             };
             auto load_b = [&](int slot, int i) {
                 const int tap = i / MB;
@@ -669,7 +685,7 @@ void k_conv_halo(EdgeBatch eb, int NT, int work_items) {
             for (int i = 0; i < D - 1; ++i) load_a(i, 0, i);
             for (int c = 0; c < nchunks; ++c) {
                 const int cn = c + 1 < nchunks ? c + 1 : c;          // the last chunk re-reads itself: no branch
-                const unsigned hc = (unsigned)cn * KC;
+                const unsigned hc = (unsigned)cn * KC * 2u;
 #pragma unroll
                 for (int i = 0; i < FBR - 1; ++i) load_b(i, i);
 #pragma unroll
@@ -677,7 +693,7 @@ void k_conv_halo(EdgeBatch eb, int NT, int work_items) {
                     if (Cfg::RING <= 3 && i < Cfg::NLS) { // staging loads of the next chunk, a few per step
 #pragma unroll
                         for (int j = i * Cfg::LPS; j < (i + 1) * Cfg::LPS && j < NLD; ++j)
-                            hreg[j] = *reinterpret_cast<const f16x8*>(delta + hsrc[j] + hc);
+                            hreg[j] = buf_load16(drs, hsrc[j], hc);
                     }
                     load_a((i + D - 1) % D, c, i + D - 1);
                     if (i + FBR - 1 < NS) load_b((i + FBR - 1) % FBR, i + FBR - 1);
@@ -701,7 +717,7 @@ void k_conv_halo(EdgeBatch eb, int NT, int work_items) {
                     if constexpr (Cfg::RING > 3) {        // deep weight ring: the registers go to it, the next chunk is
                                                           // fetched here (the weight loads of its first steps are in flight)
 #pragma unroll
-                        for (int j = 0; j < NLD; ++j) hreg[j] = *reinterpret_cast<const f16x8*>(delta + hsrc[j] + hc);
+                        for (int j = 0; j < NLD; ++j) hreg[j] = buf_load16(drs, hsrc[j], hc);
                     }
                     halo_store();
                     __syncthreads();
@@ -1364,7 +1380,8 @@ static hipError_t launch_halo(const EdgeBatch& eb, int nb, long long nseg, hipSt
     const EdgeDev& e = eb.d[0];
     *done = false;
     if (!g_halo || !e.wp || e.k != 3 || e.stride != 1 || e.up != 0 || e.Cin % 16 || e.Cout % 32) return hipSuccess;
-    if ((long long)e.sH * e.sW * e.Cin >= (1ll << 31)) return hipSuccess;      // 32-bit staging offsets
+    if ((long long)e.sH * e.sW * e.Cin >= (1ll << 30) || (long long)e.k * e.k * e.Cin * e.Cout >= (1ll << 30))
+        return hipSuccess;                                                     // 32-bit byte offsets into deltas and weights
     return e.Cout % 64 == 0 && g_halo != 2 ? launch_halo_n<2>(eb, nb, nseg, st, done) : launch_halo_n<1>(eb, nb, nseg, st, done);
 }
 
