@@ -182,6 +182,19 @@ __device__ __forceinline__ void carry_source_compaction(const EdgeDev& e, int* s
     __syncthreads();
 }
 
+// Buffer loads: the address is a resource (base, size) in scalar registers + a per-lane byte offset + a
+// scalar byte offset, so a wave spends one vector register on all the addresses of a tensor instead of a
+// 64-bit pointer per load (reads past `bytes` return zero instead of faulting).
+using rsrc_t = __amdgpu_buffer_rsrc_t;
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ rsrc_t make_rsrc(const void* p, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ f16x8 buf_load16(rsrc_t r, unsigned lane_bytes, unsigned wave_bytes) {
+    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_bytes, (int)wave_bytes, 0);
+    return __builtin_bit_cast(f16x8, v);
+}
+
 // ---------------------------------------------------------------------------
 // Tiled MFMA gather-GEMM (the fast path for fp16 layers with Cin % 32 == 0).
 // Block tile = BM list entries (pixels) x BN couts, 4 waves arranged WM x WN,
@@ -245,8 +258,9 @@ __global__ __launch_bounds__(256) void k_conv_mfma_tiled(EdgeBatch eb, int NT, i
     const int wm = wave % WM, wn = wave / WM;
     const int r32 = lane & 31, kh = lane >> 5;
     const int MT = edge_segments(e) * TPS;
-    const f16* __restrict__ delta = (const f16*)e.delta;
-    const f16* __restrict__ w = (const f16*)e.w;
+    // (the host checks that both tensors are smaller than 2 GiB)
+    const rsrc_t drs = make_rsrc(e.delta, (unsigned)e.sH * (unsigned)e.sW * (unsigned)e.Cin * 2u);
+    const rsrc_t wrs = make_rsrc(e.w, (unsigned)(e.k * e.k) * (unsigned)e.Cin * (unsigned)e.Cout * 2u);
 
     carry_source_compaction(e, sh);
 
@@ -274,16 +288,18 @@ __global__ __launch_bounds__(256) void k_conv_mfma_tiled(EdgeBatch eb, int NT, i
 
         // Per-thread chunk descriptors of this tile: which slab rows this thread
         // moves, their source offsets (elements) and tap masks.  Per step only a
-        // block-uniform offset is added, and rows whose tap misses the update mask
-        // are zeroed with selects (no divergent branches in the K loop).
-        long long offB[NB], offA[NA];
+        // block-uniform offset is added; a row whose tap misses the update mask is
+        // loaded from beyond the end of the tensor, which a buffer load answers with
+        // zeros (no divergent branches and no selects on the data in the K loop).
+        int offB[NB];
+        unsigned offA[NA];
         unsigned vmB[NB];
         int ldsB[NB], ldsA[NA];
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             const int ch = tid + 256 * i;
             const int row = (ch / CPR) % BM, cc = ch % CPR;          // % BM: keep partial last rounds in range
-            offB[i] = (long long)s_base[row] * e.Cin + cc * 8;
+            offB[i] = (s_base[row] * e.Cin + cc * 8) * 2;      // bytes; may be negative: the top left tap of a border pixel
             vmB[i] = (BM * CPR) % 256 == 0 || ch < BM * CPR ? s_vm[row] : 0u;
             ldsB[i] = row * LDK + cc * 8;
         }
@@ -291,32 +307,28 @@ __global__ __launch_bounds__(256) void k_conv_mfma_tiled(EdgeBatch eb, int NT, i
         for (int i = 0; i < NA; ++i) {
             const int ch = tid + 256 * i;
             const int row = (ch / CPR) % BN, cc = ch % CPR;
-            offA[i] = (long long)(n0 + row) * e.Cin + cc * 8;
+            offA[i] = ((unsigned)(n0 + row) * (unsigned)e.Cin + cc * 8) * 2u;      // bytes
             ldsA[i] = row * LDK + cc * 8;
         }
-        const long long tap_stride_w = (long long)e.Cout * e.Cin;
+        const unsigned tap_stride_w = (unsigned)e.Cout * (unsigned)e.Cin * 2u;    // bytes
 
         // the load iterator runs PIPE steps ahead of the multiplication
         unsigned ld_rem = tilemask;
         int ld_tap = ld_rem ? __ffs(ld_rem) - 1 : -1, ld_c0 = 0;
         f16x8 rb[PIPE][NB], ra[PIPE][NA];
-        bool okB[PIPE][NB];                                  // zeroing happens when the stage is stored,
-        auto load_next = [&](auto stage) {                   // so that nothing waits on a load just issued
+        auto load_next = [&](auto stage) {
             constexpr int S = decltype(stage)::value;
             if (ld_tap < 0) return;
             const int jy = ld_tap / e.k, jx = ld_tap - jy * e.k;
-            const long long stepB = (long long)(jy * e.sW + jx) * e.Cin + ld_c0;     // block-uniform
-            const long long stepA = ld_tap * tap_stride_w + ld_c0;
+            const int stepB = ((jy * e.sW + jx) * e.Cin + ld_c0) * 2;                 // block-uniform, bytes
+            const unsigned stepA = (unsigned)ld_tap * tap_stride_w + (unsigned)ld_c0 * 2u;
 #pragma unroll
             for (int i = 0; i < NB; ++i) {
-                const bool valid = (vmB[i] >> ld_tap) & 1u;
-                const f16* src = valid ? delta + offB[i] + stepB : delta;           // always a readable address
-                rb[S][i] = *reinterpret_cast<const f16x8*>(src);
-                okB[S][i] = valid;
+                const bool valid = (vmB[i] >> ld_tap) & 1u;                           // then offB + stepB is a pixel of the source
+                rb[S][i] = buf_load16(drs, valid ? (unsigned)(offB[i] + stepB) : 0x80000000u, 0u);
             }
 #pragma unroll
-            for (int i = 0; i < NA; ++i)
-                ra[S][i] = *reinterpret_cast<const f16x8*>(w + offA[i] + stepA);
+            for (int i = 0; i < NA; ++i) ra[S][i] = buf_load16(wrs, offA[i], stepA);
             ld_c0 += KC;
             if (ld_c0 >= e.Cin) { ld_c0 = 0; ld_rem &= ld_rem - 1; ld_tap = ld_rem ? __ffs(ld_rem) - 1 : -1; }
         };
@@ -326,10 +338,7 @@ __global__ __launch_bounds__(256) void k_conv_mfma_tiled(EdgeBatch eb, int NT, i
             f16* sA = sB + BM * LDK;
 #pragma unroll
             for (int i = 0; i < NB; ++i) {
-                f16x8 v = rb[S][i];
-#pragma unroll
-                for (int q = 0; q < 8; ++q) v[q] = okB[S][i] ? v[q] : (f16)0.f;
-                if ((BM * CPR) % 256 == 0 || tid + 256 * i < BM * CPR) *reinterpret_cast<f16x8*>(sB + ldsB[i]) = v;
+                if ((BM * CPR) % 256 == 0 || tid + 256 * i < BM * CPR) *reinterpret_cast<f16x8*>(sB + ldsB[i]) = rb[S][i];
             }
 #pragma unroll
             for (int i = 0; i < NA; ++i)
@@ -513,19 +522,6 @@ __device__ __forceinline__ int tile_prologue_sub(const EdgeDev& e, int seg, int 
 // through LDS, so the result does not depend on timing; P is then updated with
 // 16-byte accesses.
 // ---------------------------------------------------------------------------
-// Buffer loads: the address is a resource (base, size) in scalar registers + a per-lane byte offset + a
-// scalar byte offset, so a wave spends one vector register on all the addresses of a tensor instead of a
-// 64-bit pointer per load (reads past `bytes` return zero instead of faulting).
-using rsrc_t = __amdgpu_buffer_rsrc_t;
-typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ rsrc_t make_rsrc(const void* p, unsigned bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
-}
-__device__ __forceinline__ f16x8 buf_load16(rsrc_t r, unsigned lane_bytes, unsigned wave_bytes) {
-    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_bytes, (int)wave_bytes, 0);
-    return __builtin_bit_cast(f16x8, v);
-}
-
 template <int NSUB, int WMV, int WK, int TM, int TN, int KC, int NLD_, int KS, int RING_ = 3, int MINB_ = (NSUB >= 2 ? 2 : 1)>
 struct HaloCfg {
     static constexpr int SUB = kSegPixels / NSUB;    // indices (and at most entries) per tile
@@ -1451,7 +1447,9 @@ hipError_t launch_conv(const EdgeBatch& eb, int nb, int dtype, int conv_path, hi
         const hipError_t err = launch_halo(eb, nb, nseg, st, &done);
         if (done) { *cls = kClsConvMfma; return err; }
     }
-    if (mfma_ok && (conv_path == 0 || conv_path == 3) && e.Cin % 32 == 0) {
+    // (the tiled kernel addresses deltas and weights with 32-bit byte offsets)
+    const bool small32 = (long long)e.sH * e.sW * e.Cin < (1ll << 30) && (long long)e.k * e.k * e.Cin * e.Cout < (1ll << 30);
+    if (mfma_ok && (conv_path == 0 || conv_path == 3) && e.Cin % 32 == 0 && small32) {
         *cls = kClsConvMfma;
         if (e.Cin % 128 == 0 && g_kc != 64) return launch_tiled_kc<128>(eb, nb, max_entries, st);
         return e.Cin % 64 == 0 ? launch_tiled_kc<64>(eb, nb, max_entries, st) : launch_tiled_kc<32>(eb, nb, max_entries, st);
