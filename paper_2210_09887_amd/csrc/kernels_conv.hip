@@ -609,33 +609,23 @@ void k_conv_halo(EdgeBatch eb, int NT, int work_items) {
         const int nrt = (tot + 31) >> 5;                  // live 32-entry row tiles of the tile
         const int mylive = nrt > wm ? (nrt - wm + WMV - 1) / WMV : 0;      // of this wave: row tiles wm, wm + WMV, ...
 
-        // staging: piece q = tid + 256 j is 16 bytes of staged pixel q / CPR.  Dead
-        // pieces (outside the rectangle, out of view, not updated) are loaded from
-        // pixel 0 and never stored; their rows are zeroed once per tile.
+        // staging: piece q = tid + 256 j is 16 bytes of staged pixel q / CPR (q / CPR < CAP: inside the buffer).
+        // Dead pieces (outside the rectangle, out of view, not updated) are loaded from beyond the end of the
+        // delta map, which a buffer load answers with zeros, and stored like the others: no predicates.
         f16x8 hreg[NLD];
-        unsigned hval = 0;
         unsigned hsrc[NLD];                               // byte offsets into the delta map
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
             const int q = tid + 256 * j, pos = q / CPR;
-            const bool inr = pos < npos;
-            const int pix = inr ? s_pix[pos] : -1;
-            hval |= (pix >= 0 ? 1u : 0u) << j;
-            hsrc[j] = ((unsigned)(pix >= 0 ? pix : 0) * (unsigned)e.Cin + (q % CPR) * 8) * 2u;
-            if (inr && pix < 0) {
-                f16x8 z;
-#pragma unroll
-                for (int t = 0; t < 8; ++t) z[t] = (f16)0.f;
-                *reinterpret_cast<f16x8*>(halo + pos * LDK + (q % CPR) * 8) = z;
-            }
+            const int pix = pos < npos ? s_pix[pos] : -1;
+            hsrc[j] = pix >= 0 ? ((unsigned)pix * (unsigned)e.Cin + (q % CPR) * 8) * 2u : 0x80000000u;
         }
         auto halo_store = [&]() {
 #pragma unroll
-            for (int j = 0; j < NLD; ++j)
-                if ((hval >> j) & 1u) {
-                    const int q = tid + 256 * j;
-                    *reinterpret_cast<f16x8*>(halo + (q / CPR) * LDK + (q % CPR) * 8) = hreg[j];
-                }
+            for (int j = 0; j < NLD; ++j) {
+                const int q = tid + 256 * j;
+                *reinterpret_cast<f16x8*>(halo + (q / CPR) * LDK + (q % CPR) * 8) = hreg[j];
+            }
         };
 #pragma unroll
         for (int j = 0; j < NLD; ++j) hreg[j] = buf_load16(drs, hsrc[j], 0u);
