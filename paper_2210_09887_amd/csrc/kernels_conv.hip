@@ -51,7 +51,32 @@ __device__ __forceinline__ void decode_entry(const EdgeDev& e, int idx, int& cy,
     }
 }
 
+// Update flags of the K x K footprint of output (cy, cx) as a bit mask.  All loads go out together
+// (a pixel outside the source reads flag 0 of the site and is masked afterwards).
+template <int K>
+__device__ __forceinline__ unsigned tap_mask_k(const EdgeDev& e, int cy, int cx) {
+    const int y0 = cy * e.stride - e.pad, x0 = cx * e.stride - e.pad;
+    unsigned f[K * K];
+#pragma unroll
+    for (int t = 0; t < K * K; ++t) {
+        const int iy = y0 + t / K, ix = x0 + t % K;
+        const bool ok = iy >= 0 && iy < e.sH && ix >= 0 && ix < e.sW;
+        const unsigned v = e.sflags[ok ? iy * e.sW + ix : 0];
+        f[t] = ok ? v : 0u;
+    }
+    unsigned m = 0;
+#pragma unroll
+    for (int t = 0; t < K * K; ++t) m |= ((f[t] >> 2) & 1u) << t;      // kFlagM == 4
+    return m;
+}
+
 __device__ __forceinline__ unsigned tap_mask(const EdgeDev& e, int cy, int cx) {
+    switch (e.k) {
+        case 1: return tap_mask_k<1>(e, cy, cx);
+        case 3: return tap_mask_k<3>(e, cy, cx);
+        case 5: return tap_mask_k<5>(e, cy, cx);
+        default: break;
+    }
     unsigned m = 0;
     const int y0 = cy * e.stride - e.pad, x0 = cx * e.stride - e.pad;
     for (int jy = 0; jy < e.k; ++jy) {
@@ -61,7 +86,7 @@ __device__ __forceinline__ unsigned tap_mask(const EdgeDev& e, int cy, int cx) {
             const int ix = x0 + jx;
             const bool ok = yok && ix >= 0 && ix < e.sW;
             const unsigned f = ok ? e.sflags[iy * e.sW + ix] : 0u;
-            m |= ((f >> 2) & 1u) << (jy * e.k + jx);                  // kFlagM == 4
+            m |= ((f >> 2) & 1u) << (jy * e.k + jx);
         }
     }
     return m;
