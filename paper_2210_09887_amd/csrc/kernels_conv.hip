@@ -967,14 +967,26 @@ __global__ __launch_bounds__(256) void k_conv_ldsw(EdgeBatch eb, int groups, int
             const int jy = tap / e.k, jx = tap - jy * e.k;
             const T* drow = delta + (size_t)(base + jy * e.sW + jx) * e.Cin;
             const float* wt = sW + tap * cc + cg * 8;
-            for (int ci = 0; ci < e.Cin; ++ci) {
-                const float a = (float)drow[ci];
+            auto mac = [&](float a, int ci) {               // channels in ascending order: the sum does not change
                 const float4 w0 = *reinterpret_cast<const float4*>(wt + ci * e.Cout);
                 const float4 w1 = *reinterpret_cast<const float4*>(wt + ci * e.Cout + 4);
                 acc[0] = fmaf(a, w0.x, acc[0]); acc[1] = fmaf(a, w0.y, acc[1]);
                 acc[2] = fmaf(a, w0.z, acc[2]); acc[3] = fmaf(a, w0.w, acc[3]);
                 acc[4] = fmaf(a, w1.x, acc[4]); acc[5] = fmaf(a, w1.y, acc[5]);
                 acc[6] = fmaf(a, w1.z, acc[6]); acc[7] = fmaf(a, w1.w, acc[7]);
+            };
+            constexpr int V = 16 / (int)sizeof(T);           // a row is read in 16-byte pieces, several of them in flight
+            if (e.Cin % V == 0) {
+#pragma unroll 4
+                for (int ci = 0; ci < e.Cin; ci += V) {
+                    const u32x4_t raw = *reinterpret_cast<const u32x4_t*>(drow + ci);
+                    T a[V];
+                    __builtin_memcpy(a, &raw, 16);
+#pragma unroll
+                    for (int v = 0; v < V; ++v) mac((float)a[v], ci + v);
+                }
+            } else {
+                for (int ci = 0; ci < e.Cin; ++ci) mac((float)drow[ci], ci);
             }
         }
         const int f = 1 << e.up;
