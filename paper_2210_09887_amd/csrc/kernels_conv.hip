@@ -944,10 +944,26 @@ __global__ __launch_bounds__(256) void k_conv_ldsw(EdgeBatch eb, int groups, int
     const int taps = e.k * e.k;
     const int cc = e.Cin * e.Cout;
     carry_source_compaction(e, sh);
-    for (int i = tid; i < taps * cc; i += 256) {
-        const int tap = i / cc, r = i - tap * cc;
-        const int co = r / e.Cin, ci = r - co * e.Cin;
-        sW[tap * cc + ci * e.Cout + co] = (float)w[i];
+    // weights [tap][cout][cin] -> LDS [tap][cin][cout] as fp32.  Neighbouring threads take neighbouring couts, so
+    // their LDS stores fall into different banks; a thread reads 16 bytes of its weight row at a time.
+    constexpr int WV = 16 / (int)sizeof(T);
+    if (e.Cin % WV == 0) {
+        const int pieces = e.Cin / WV;
+        for (int i = tid; i < taps * pieces * e.Cout; i += 256) {
+            const int co = i % e.Cout, q = i / e.Cout;
+            const int piece = q % pieces, tap = q / pieces;
+            const u32x4_t raw = *reinterpret_cast<const u32x4_t*>(w + ((size_t)tap * e.Cout + co) * e.Cin + piece * WV);
+            T a[WV];
+            __builtin_memcpy(a, &raw, 16);
+#pragma unroll
+            for (int v = 0; v < WV; ++v) sW[tap * cc + (piece * WV + v) * e.Cout + co] = (float)a[v];
+        }
+    } else {
+        for (int i = tid; i < taps * cc; i += 256) {
+            const int tap = i / cc, r = i - tap * cc;
+            const int co = r / e.Cin, ci = r - co * e.Cin;
+            sW[tap * cc + ci * e.Cout + co] = (float)w[i];
+        }
     }
     long long block_taps = 0;                               // statistics (thread 0 only)
     const int tps = (kSegPixels + ppb - 1) / ppb;           // tiles per segment
@@ -977,7 +993,7 @@ __global__ __launch_bounds__(256) void k_conv_ldsw(EdgeBatch eb, int groups, int
             };
             constexpr int V = 16 / (int)sizeof(T);           // a row is read in 16-byte pieces, several of them in flight
             if (e.Cin % V == 0) {
-#pragma unroll 4
+#pragma unroll 8
                 for (int ci = 0; ci < e.Cin; ci += V) {
                     const u32x4_t raw = *reinterpret_cast<const u32x4_t*>(drow + ci);
                     T a[V];
