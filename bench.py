@@ -36,6 +36,7 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_F16_TFLOPS = 2500.0
+PEAK_MFMA_F32_TFLOPS = 157.3      # fp32 networks: their layers run on v_mfma_f32_32x32x2_f32
 PEAK_FP32_VALU_TFLOPS = 157.3
 
 
@@ -128,7 +129,7 @@ def measured_traffic(cfg, cls):
         return None
 
 
-def rooflines(prof, flops_mfma, flops_plain, ab, cfg, with_traffic=True):
+def rooflines(prof, flops_mfma, flops_plain, ab, cfg, with_traffic=True, mfma_peak=PEAK_MFMA_F16_TFLOPS):
     """Per-class kernel times (from the library's HIP events) and the roofline entries."""
     tr = (lambda c: measured_traffic(cfg, c)) if with_traffic else (lambda c: None)
     classes = {}
@@ -141,12 +142,12 @@ def rooflines(prof, flops_mfma, flops_plain, ab, cfg, with_traffic=True):
     if prof["conv_mfma"][1]:
         ms, cnt = prof["conv_mfma"]
         ach = flops_mfma / (ms * 1e-3) / 1e12
-        rl_all["conv_mfma"] = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
-                               "frac": round(ach / PEAK_MFMA_F16_TFLOPS, 4), "traffic": tr("conv_mfma"),
+        rl_all["conv_mfma"] = {"bound": "mfma", "achieved": round(ach, 2), "peak": mfma_peak, "unit": "TFLOP/s",
+                               "frac": round(ach / mfma_peak, 4), "traffic": tr("conv_mfma"),
                                "flop_per_launch": round(flops_mfma / cnt), "avg_us": round(1e3 * ms / cnt, 2), "launches": int(cnt),
                                "algorithmic_bytes_per_launch": round(ab["conv"] / (cnt + prof["conv_plain"][1])),
                                "hbm_bound_us": round(ab["conv"] / (cnt + prof["conv_plain"][1]) / PEAK_HBM_GBS / 1e3, 2),
-                               "mfma_bound_us": round(flops_mfma / cnt / PEAK_MFMA_F16_TFLOPS / 1e6, 2)}
+                               "mfma_bound_us": round(flops_mfma / cnt / mfma_peak / 1e6, 2)}
     if prof["conv_plain"][1]:
         ms, cnt = prof["conv_plain"]
         ach = flops_plain / (ms * 1e-3) / 1e12
@@ -216,7 +217,8 @@ def run_batched(a, cfg, net, T, frames, shifts, forced, fused):
     after = sum_totals([g.totals() for g in gb.streams])
     ab = algorithmic_bytes(gb.streams[0], net, before, after, n_prof * n, fused_skips=fused)
     classes, kernel_ms, rl_all, _ = rooflines(prof, 2.0 * (after["macs_mfma"] - before["macs_mfma"]),
-                                              2.0 * (after["macs_plain"] - before["macs_plain"]), ab, cfg, with_traffic=False)
+                                              2.0 * (after["macs_plain"] - before["macs_plain"]), ab, cfg, with_traffic=False,
+                                              mfma_peak=PEAK_MFMA_F32_TFLOPS if net.dtype == "f32" else PEAK_MFMA_F16_TFLOPS)
     gb.close()
     return {"streams": n, "value": round(n * steps / dt, 2), "unit": "frames/s", "batch_steps": steps,
             "ms_per_batch_step": round(1e3 * dt / steps, 4), "roofline_all": rl_all, "kernel_classes": classes,
@@ -364,7 +366,8 @@ def main():
     flops_mfma = 2.0 * (after["macs_mfma"] - before["macs_mfma"])
     flops_plain = 2.0 * (after["macs_plain"] - before["macs_plain"])
     ab = algorithmic_bytes(g, net, before, after, n_prof, fused_skips="8=0" not in a.opt)
-    classes, kernel_ms, rl_all, roofline = rooflines(prof, flops_mfma, flops_plain, ab, cfg)
+    mfma_peak = PEAK_MFMA_F32_TFLOPS if net.dtype == "f32" else PEAK_MFMA_F16_TFLOPS
+    classes, kernel_ms, rl_all, roofline = rooflines(prof, flops_mfma, flops_plain, ab, cfg, mfma_peak=mfma_peak)
 
     # ---- CPU baseline: the oracle as it stands, on the first frames of the same sequence
     cpu = None
@@ -431,7 +434,7 @@ def main():
     per_frame_flops = (flops_mfma + flops_plain) / n_prof
     per_frame_bytes = sum(ab.values()) / n_prof
     out["whole_path"] = {"tflops": round(per_frame_flops * out["value"] / 1e12, 2),
-                         "mfma_frac": round(flops_mfma / n_prof * out["value"] / 1e12 / PEAK_MFMA_F16_TFLOPS, 4),
+                         "mfma_frac": round(flops_mfma / n_prof * out["value"] / 1e12 / mfma_peak, 4),
                          "algorithmic_gbs": round(per_frame_bytes * out["value"] / 1e9, 1),
                          "hbm_frac": round(per_frame_bytes * out["value"] / 1e9 / PEAK_HBM_GBS, 4),
                          "gflop_per_frame": round(per_frame_flops / 1e9, 2), "mbytes_per_frame": round(per_frame_bytes / 1e6, 2)}

@@ -20,7 +20,7 @@ MDCNN_SITE_INPUT, MDCNN_SITE_PREACT, MDCNN_SITE_OUTPUT = 0, 1, 2
  MDCNN_VIEW_CLIST, MDCNN_VIEW_STATS, MDCNN_VIEW_OUT, MDCNN_VIEW_POOL_PREV, MDCNN_VIEW_CROP_OUT,
  MDCNN_VIEW_PENDING) = range(11)
 MDCNN_OPT_CONV_PATH, MDCNN_OPT_PROFILE, MDCNN_OPT_CONV_TILE, MDCNN_OPT_CONV_PIPE, MDCNN_OPT_CONV_XCD, MDCNN_OPT_CONV_KC, \
-    MDCNN_OPT_CONV_HALO, MDCNN_OPT_CONV_HALO_SUB, MDCNN_OPT_FUSE_SKIP, MDCNN_OPT_STREAMS, MDCNN_OPT_PIPE_GROUP, MDCNN_OPT_PIPE_MODE, MDCNN_OPT_PIPE_THREADS = range(13)
+    MDCNN_OPT_CONV_HALO, MDCNN_OPT_CONV_HALO_SUB, MDCNN_OPT_FUSE_SKIP, MDCNN_OPT_STREAMS, MDCNN_OPT_PIPE_GROUP, MDCNN_OPT_PIPE_MODE, MDCNN_OPT_PIPE_THREADS, MDCNN_OPT_CONV_F32_MFMA = range(14)
 KERNEL_CLASSES = ["shift", "step1", "lists", "conv_mfma", "conv_plain", "identity", "readout", "pool"]
 FLAG_N, FLAG_U, FLAG_M = 1, 2, 4
 STATE_UNSEEN, STATE_DIRTY = 1, 2

@@ -948,15 +948,32 @@ __global__ __launch_bounds__(256) void k_conv_ldsw(EdgeBatch eb, int groups, int
     // their LDS stores fall into different banks; a thread reads 16 bytes of its weight row at a time.
     constexpr int WV = 16 / (int)sizeof(T);
     if (e.Cin % WV == 0) {
-        const int pieces = e.Cin / WV;
-        for (int i = tid; i < taps * pieces * e.Cout; i += 256) {
-            const int co = i % e.Cout, q = i / e.Cout;
-            const int piece = q % pieces, tap = q / pieces;
-            const u32x4_t raw = *reinterpret_cast<const u32x4_t*>(w + ((size_t)tap * e.Cout + co) * e.Cin + piece * WV);
-            T a[WV];
-            __builtin_memcpy(a, &raw, 16);
+        // Eight reads of a thread are in flight at a time (the copy is a chain of round trips otherwise, and it is
+        // the larger part of a launch on sparse frames); a read past the end of the tensor returns zeros and is dropped.
+        const int pieces = e.Cin / WV, total = taps * pieces * e.Cout;
+        const rsrc_t wrs = make_rsrc(w, (unsigned)(taps * cc) * (unsigned)sizeof(T));
+        constexpr int WU = 8;
+        for (int i0 = tid; i0 < total; i0 += 256 * WU) {
+            u32x4_t raw[WU];
+            int dst[WU];
 #pragma unroll
-            for (int v = 0; v < WV; ++v) sW[tap * cc + (piece * WV + v) * e.Cout + co] = (float)a[v];
+            for (int u = 0; u < WU; ++u) {
+                const int i = i0 + u * 256;
+                const int co = i % e.Cout, q = i / e.Cout;
+                const int piece = q % pieces, tap = q / pieces;
+                const bool in = i < total;
+                dst[u] = in ? tap * cc + piece * WV * e.Cout + co : -1;
+                raw[u] = __builtin_amdgcn_raw_buffer_load_b128(
+                    wrs, in ? (int)(((unsigned)(tap * e.Cout + co) * (unsigned)e.Cin + (unsigned)(piece * WV)) * (unsigned)sizeof(T)) : (int)0x80000000u, 0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < WU; ++u) {
+                if (dst[u] < 0) continue;
+                T a[WV];
+                __builtin_memcpy(a, &raw[u], 16);
+#pragma unroll
+                for (int v = 0; v < WV; ++v) sW[dst[u] + v * e.Cout] = (float)a[v];
+            }
         }
     } else {
         for (int i = tid; i < taps * cc; i += 256) {
@@ -1011,6 +1028,119 @@ __global__ __launch_bounds__(256) void k_conv_ldsw(EdgeBatch eb, int groups, int
                 Row8<T>::add((T*)e.P + pdst_offset(e, s_wy[pl] + ua, s_wx[pl] + ub) + cg * 8, acc);
     }
     if (tid == 0) add_macs(e, block_taps, 1);               // statistics: one atomic per block
+}
+
+// ---------------------------------------------------------------------------
+// fp32 layers on the matrix cores (v_mfma_f32_32x32x2_f32), Cin and footprint at
+// compile time, Cout 32, 64 or 128, no upsampling.  All weights sit in LDS as
+// [tap][cin][cout] (as in k_conv_ldsw); a wave owns 32 list entries x 32 couts,
+// the four waves of a block are `pgs` entry groups x 4 / pgs cout tiles.  The
+// matrix instruction takes the couts as rows and the entries as columns: a lane
+// holds entry lane % 32 and half lane / 32 of the K pair, which is channel
+// (lane / 32) * CIN / 2 + step - so a lane reads CIN / 2 consecutive channels
+// of its entry's source row per tap, in 16-byte pieces, one tap ahead of the
+// multiplication, and one weight per instruction from LDS (32 consecutive
+// floats per half wave).  Taps outside an entry's mask are read from beyond
+// the end of the tensor (zeros); the tap loop has no branches.
+// ---------------------------------------------------------------------------
+template <int KK, int CIN>
+__global__ __launch_bounds__(256) void k_conv_mfma_f32(EdgeBatch eb, int pgs) {
+    const EdgeDev& e = eb.d[blockIdx.z];                  // blockIdx.z: stream of the batch
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* sW = reinterpret_cast<float*>(smem);             // [tap][CIN][Cout]
+    __shared__ int s_base[128], s_wy[128], s_wx[128];
+    __shared__ unsigned s_vm[128];
+    __shared__ int sh[8];
+    constexpr int TAPS = KK * KK, HALF = CIN / 2, NP = HALF / 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int p32 = lane & 31, h = lane >> 5;
+    const int pg = wave % pgs, nt = wave / pgs;             // entry group, cout tile
+    const int bm = pgs * 32;                                // entries per tile
+    const int cc = CIN * e.Cout;
+    const float* __restrict__ w = (const float*)e.w;
+    carry_source_compaction(e, sh);
+    {   // weights [tap][cout][cin] -> LDS [tap][cin][cout]; eight 16-byte reads of a thread in flight
+        constexpr int pieces = CIN / 4, WU = 8;
+        const int total = TAPS * pieces * e.Cout;
+        const rsrc_t wrs = make_rsrc(w, (unsigned)(TAPS * cc) * 4u);
+        for (int i0 = tid; i0 < total; i0 += 256 * WU) {
+            u32x4_t raw[WU];
+            int dst[WU];
+#pragma unroll
+            for (int u = 0; u < WU; ++u) {
+                const int i = i0 + u * 256;
+                const int co = i % e.Cout, q = i / e.Cout;
+                const int piece = q % pieces, tap = q / pieces;
+                const bool in = i < total;
+                dst[u] = in ? tap * cc + piece * 4 * e.Cout + co : -1;
+                raw[u] = __builtin_amdgcn_raw_buffer_load_b128(
+                    wrs, in ? (int)(((unsigned)(tap * e.Cout + co) * (unsigned)CIN + (unsigned)(piece * 4)) * 4u) : (int)0x80000000u, 0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < WU; ++u) {
+                if (dst[u] < 0) continue;
+                float a[4];
+                __builtin_memcpy(a, &raw[u], 16);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) sW[dst[u] + v * e.Cout] = a[v];
+            }
+        }
+    }
+    const rsrc_t drs = make_rsrc(e.delta, (unsigned)e.sH * (unsigned)e.sW * (unsigned)CIN * 4u);
+    long long block_taps = 0;                               // statistics (thread 0 only)
+    const int tps = kSegPixels / bm;                        // tiles per segment
+    const int MT = edge_segments(e) * tps;
+    for (int tile = blockIdx.x; tile < MT; tile += gridDim.x) {
+        const int seg = tile / tps, first = (tile - seg * tps) * bm;
+        __syncthreads();
+        const int tot = tile_prologue(e, seg, first, bm, first == 0, true, s_base, s_wy, s_wx, s_vm, sh);
+        if (first >= tot) continue;
+        if (tid == 0) block_taps += sh[4];
+        if (first + pg * 32 >= tot) continue;               // no entry for this wave
+        const int pl = pg * 32 + p32;
+        const bool act = first + pl < tot;
+        const unsigned vmask = act ? s_vm[pl] : 0u;
+        const int rowb = act ? (s_base[pl] * CIN + h * HALF) * 4 : 0;      // bytes; negative for a border entry's first taps
+        auto load_tap = [&](int tap, u32x4_t* r) {
+            const bool v = (vmask >> tap) & 1u;
+            const int tb = rowb + ((tap / KK) * e.sW + (tap % KK)) * CIN * 4;
+#pragma unroll
+            for (int i = 0; i < NP; ++i)
+                r[i] = __builtin_amdgcn_raw_buffer_load_b128(drs, v ? tb + i * 16 : (int)0x80000000u, 0, 0);
+        };
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+        u32x4_t rows[2][NP];
+        load_tap(0, rows[0]);
+        const float* wl = sW + h * HALF * e.Cout + nt * 32 + p32;
+#pragma unroll
+        for (int tap = 0; tap < TAPS; ++tap) {
+            if (tap + 1 < TAPS) load_tap(tap + 1, rows[(tap + 1) & 1]);
+            const float* wt = wl + tap * cc;
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                float b[4];
+                __builtin_memcpy(b, &rows[tap & 1][i], 16);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wt[(i * 4 + j) * e.Cout], b[j], acc, 0, 0, 0);
+            }
+        }
+        // register r of a lane: cout 8 * (r / 4) + 4 * (lane / 32) + r % 4 of the tile, entry lane % 32
+        if (act) {
+            float* pp = (float*)e.P + pdst_offset(e, s_wy[pl], s_wx[pl]) + nt * 32 + 4 * h;
+            float4 o[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) o[g] = *reinterpret_cast<const float4*>(pp + 8 * g);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                o[g].x += acc[4 * g]; o[g].y += acc[4 * g + 1]; o[g].z += acc[4 * g + 2]; o[g].w += acc[4 * g + 3];
+                *reinterpret_cast<float4*>(pp + 8 * g) = o[g];
+            }
+        }
+    }
+    if (tid == 0) add_macs(e, block_taps, 0);               // statistics: one atomic per block
 }
 
 // ---------------------------------------------------------------------------
@@ -1292,6 +1422,7 @@ static unsigned cap_blocks(long long b, long long cap) {
 
 // Tuning knobs (mdcnn_set_option): forced tile shape, pipeline depth, XCD mapping.
 int g_tile = 0, g_pipe = 0, g_xcd = 1, g_kc = 0;
+int g_f32_mfma = 1;     // 1: fp32 layers go to the matrix cores where k_conv_mfma_f32 applies, 0: plain FMA kernels
 
 template <int WM, int WN, int TM, int TN, int KC, int PIPE>
 static hipError_t launch_tiled(const EdgeBatch& eb, int nb, long long max_entries, hipStream_t st) {
@@ -1450,6 +1581,36 @@ static hipError_t launch_ldsw(const EdgeBatch& eb, int nb, long long max_entries
     return hipGetLastError();
 }
 
+// fp32 layers the matrix cores take (k_conv_mfma_f32); *done = false: not this layer
+template <int KK, int CIN>
+static hipError_t launch_mfma_f32_inst(const EdgeBatch& eb, int nb, long long nseg, size_t smem, hipStream_t st) {
+    const EdgeDev& e = eb.d[0];
+    static size_t attr_bytes = 0;
+    auto kern = k_conv_mfma_f32<KK, CIN>;
+    if (smem > 65536 && smem > attr_bytes) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (err != hipSuccess) return err;
+        attr_bytes = smem;
+    }
+    const int pgs = 4 / (e.Cout / 32);
+    const long long tps = kSegPixels / (pgs * 32);
+    // weights are staged once per block: keep the blocks few and persistent
+    const unsigned g = cap_blocks(nseg * tps, smem > 32768 ? 256 : 768);
+    kern<<<dim3(g, 1, nb), dim3(256), smem, st>>>(eb, pgs);
+    return hipGetLastError();
+}
+static hipError_t launch_mfma_f32(const EdgeBatch& eb, int nb, long long nseg, hipStream_t st, bool* done) {
+    const EdgeDev& e = eb.d[0];
+    *done = false;
+    const size_t smem = (size_t)e.k * e.k * e.Cin * e.Cout * 4;
+    if (e.up || (e.k != 1 && e.k != 3) || (e.Cin != 32 && e.Cin != 64) || (e.Cout != 32 && e.Cout != 64 && e.Cout != 128) ||
+        smem > 150 * 1024 || (long long)e.sH * e.sW * e.Cin >= (1ll << 29))
+        return hipSuccess;
+    *done = true;
+    if (e.k == 3) return e.Cin == 32 ? launch_mfma_f32_inst<3, 32>(eb, nb, nseg, smem, st) : launch_mfma_f32_inst<3, 64>(eb, nb, nseg, smem, st);
+    return e.Cin == 32 ? launch_mfma_f32_inst<1, 32>(eb, nb, nseg, smem, st) : launch_mfma_f32_inst<1, 64>(eb, nb, nseg, smem, st);
+}
+
 hipError_t launch_conv(const EdgeBatch& eb, int nb, int dtype, int conv_path, hipStream_t st, int* cls) {
     const EdgeDev& e = eb.d[0];                            // geometry and weights layout are the same for all streams
     const long long max_entries = e.up ? (long long)e.sH * e.sW : (long long)e.Hp * e.Wp;
@@ -1504,6 +1665,11 @@ hipError_t launch_conv(const EdgeBatch& eb, int nb, int dtype, int conv_path, hi
         else
             k_conv_mfma_f16<1><<<dim3(cap_blocks(nseg * (kSegPixels / 128), 4096), e.Cout / 32, nb), dim3(256), 0, st>>>(eb);
         return hipGetLastError();
+    }
+    if (dtype == MDCNN_F32 && (conv_path == 0 || conv_path == 3) && g_f32_mfma) {
+        bool done = false;
+        const hipError_t err = launch_mfma_f32(eb, nb, nseg, st, &done);
+        if (done) { *cls = kClsConvMfma; return err; }
     }
     *cls = kClsConvPlain;
     if ((conv_path == 0 || conv_path == 3) && e.k == 3 && e.Cin == 3 && e.Cout % 32 == 0 && e.Cout <= 256) {

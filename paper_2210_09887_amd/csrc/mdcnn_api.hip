@@ -1071,6 +1071,7 @@ mdcnn_status mdcnn_set_option(int option, int value) {
     if (option == MDCNN_OPT_CONV_PIPE && value >= 0 && value <= 2) { g_pipe = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_CONV_XCD && (value == 0 || value == 1)) { g_xcd = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_CONV_KC && (value == 0 || value == 64)) { g_kc = value; return MDCNN_OK; }
+    if (option == MDCNN_OPT_CONV_F32_MFMA && (value == 0 || value == 1)) { g_f32_mfma = value; return MDCNN_OK; }
     return fail(MDCNN_ERR_SIZE, "unknown option %d / value %d", option, value);
 }
 

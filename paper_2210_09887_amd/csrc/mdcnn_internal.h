@@ -190,7 +190,7 @@ hipError_t launch_step1_fill(Step1Fill& a, hipStream_t st);
 // e.k < 0: no operator, only the compaction of the source's update mask.
 // returns the kernel class that was launched in *cls
 hipError_t launch_conv(const EdgeBatch& eb, int n, int dtype, int conv_path, hipStream_t st, int* cls);
-extern int g_tile, g_pipe, g_xcd, g_kc, g_halo, g_halo_sub;   // convolution tuning knobs
+extern int g_tile, g_pipe, g_xcd, g_kc, g_halo, g_halo_sub, g_f32_mfma;   // convolution tuning knobs
 hipError_t launch_pack_weights(const void* src, void* dst, int taps, int Cout, int Cin, hipStream_t st);
 // Post-processed update mask of an INPUT site over the rectangle (y0, x0, Hc, Wc) of its view.
 struct MaskJob {

@@ -130,6 +130,20 @@ def test_fallback_conv_paths_on_f16(path):
         B.mdcnn_set_option(B.MDCNN_OPT_CONV_PATH, 0)
 
 
+def test_fp32_layers_on_the_plain_fma_kernels():
+    """fp32 layers with 32 or 64 input channels run on the matrix cores by default; with
+    that switched off the plain FMA kernels take them and agree with the oracle too."""
+    import gpu_harness as H
+    from paper_2210_09887_amd import binding as B
+    net, seq = load_case("c2_cnn5_88x72")
+    B.mdcnn_set_option(B.MDCNN_OPT_CONV_F32_MFMA, 0)
+    try:
+        H.teacher_forced(net, seq.frames, seq.shifts, log=log)
+        H.mask_forced(net, seq.frames, seq.shifts, seq.forced, log=log)
+    finally:
+        B.mdcnn_set_option(B.MDCNN_OPT_CONV_F32_MFMA, 1)
+
+
 @pytest.mark.parametrize("name", ["c3_resnet_96", "c3_resnet_plain_80x112", "c4_hrnet_128x96", "c5_bottleneck_40"])
 def test_fused_skip_equals_separate_launch(name):
     """mdcnn_frame adds residual skips inside the delta kernel of their source; the
