@@ -392,7 +392,8 @@ typedef enum {
     MDCNN_OPT_CONV_PATH = 0, /* 0 auto; fallbacks for testing: 1 plain FMA, 2 MFMA w/o LDS, */
                              /* 3 auto but never the packed-weights kernel                */
     MDCNN_OPT_PROFILE = 1,   /* 1: bracket every kernel launch with a pair of HIP events  */
-    MDCNN_OPT_CONV_TILE = 2, /* tuning: 0 auto, 1..10 force a tile shape of the MFMA kernel */
+    MDCNN_OPT_CONV_TILE = 2, /* tuning: 0 auto, 1..14 force a tile shape of the fp16 MFMA kernel; */
+                             /* fp32 3x3 layers: 1 / 2 / 4 waves share the taps of a tile         */
     MDCNN_OPT_CONV_PIPE = 3, /* tuning: 0 auto, 1 / 2 prefetch depth of the MFMA kernel    */
     MDCNN_OPT_CONV_XCD = 4,  /* tuning: 1 (default) tie cout tiles to XCDs, 0 plain order  */
     MDCNN_OPT_CONV_KC = 5,   /* tuning: 0 auto, 64 cap the K step at 64 channels           */

@@ -1032,49 +1032,52 @@ __global__ __launch_bounds__(256) void k_conv_ldsw(EdgeBatch eb, int groups, int
 
 // ---------------------------------------------------------------------------
 // fp32 layers on the matrix cores (v_mfma_f32_32x32x2_f32), Cin and footprint at
-// compile time, Cout 32, 64 or 128, no upsampling.  All weights sit in LDS as
-// [tap][cin][cout] (as in k_conv_ldsw); a wave owns 32 list entries x 32 couts,
-// the four waves of a block are `pgs` entry groups x 4 / pgs cout tiles.  The
-// matrix instruction takes the couts as rows and the entries as columns: a lane
-// holds entry lane % 32 and half lane / 32 of the K pair, which is channel
-// (lane / 32) * CIN / 2 + step - so a lane reads CIN / 2 consecutive channels
-// of its entry's source row per tap, in 16-byte pieces, one tap ahead of the
-// multiplication, and one weight per instruction from LDS (32 consecutive
-// floats per half wave).  Taps outside an entry's mask are read from beyond
-// the end of the tensor (zeros); the tap loop has no branches.
+// compile time, Cout a multiple of 32, no upsampling.  A block owns one tile of
+// 32 couts (blockIdx.y) and keeps its weights in LDS as [tap][cin][32]; its four
+// waves are 4 / KS groups of 32 list entries x KS shares of the taps (wave k
+// of a group takes taps k, k + KS, ...), and the partial sums of a group are
+// added through LDS in a fixed order.  The matrix instruction takes the couts
+// as rows and the entries as columns: a lane holds entry lane % 32 and half
+// lane / 32 of the K pair, which is channel (lane / 32) * CIN / 2 + step - so a
+// lane reads CIN / 2 consecutive channels of its entry's source row per tap, in
+// 16-byte pieces, one tap ahead of the multiplication, and one weight per
+// instruction from LDS (32 consecutive floats per half wave).  Taps outside an
+// entry's mask are read from beyond the end of the tensor (zeros); the tap loop
+// has no branches.
 // ---------------------------------------------------------------------------
-template <int KK, int CIN>
-__global__ __launch_bounds__(256) void k_conv_mfma_f32(EdgeBatch eb, int pgs) {
+template <int KK, int CIN, int KS>
+__global__ __launch_bounds__(256) void k_conv_mfma_f32(EdgeBatch eb) {
     const EdgeDev& e = eb.d[blockIdx.z];                  // blockIdx.z: stream of the batch
     extern __shared__ __align__(16) unsigned char smem[];
-    float* sW = reinterpret_cast<float*>(smem);             // [tap][CIN][Cout]
-    __shared__ int s_base[128], s_wy[128], s_wx[128];
-    __shared__ unsigned s_vm[128];
+    float* sW = reinterpret_cast<float*>(smem);             // [tap][CIN][32]
+    constexpr int TAPS = KK * KK, HALF = CIN / 2, NP = HALF / 4, PGS = 4 / KS, BM = PGS * 32, NQ = (TAPS + KS - 1) / KS;
+    constexpr int CC = CIN * 32;                            // floats per tap in LDS
+    __shared__ int s_base[BM], s_wy[BM], s_wx[BM];
+    __shared__ unsigned s_vm[BM];
     __shared__ int sh[8];
-    constexpr int TAPS = KK * KK, HALF = CIN / 2, NP = HALF / 4;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __shared__ float s_red[KS > 1 ? PGS * (KS - 1) * 1024 : 1];    // partial sums of the waves that do not write P
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int p32 = lane & 31, h = lane >> 5;
-    const int pg = wave % pgs, nt = wave / pgs;             // entry group, cout tile
-    const int bm = pgs * 32;                                // entries per tile
-    const int cc = CIN * e.Cout;
+    const int pg = wave % PGS, ks = wave / PGS;             // entry group, share of the taps
+    const int nt = blockIdx.y;                              // cout tile
     const float* __restrict__ w = (const float*)e.w;
     carry_source_compaction(e, sh);
-    {   // weights [tap][cout][cin] -> LDS [tap][cin][cout]; eight 16-byte reads of a thread in flight
-        constexpr int pieces = CIN / 4, WU = 8;
-        const int total = TAPS * pieces * e.Cout;
-        const rsrc_t wrs = make_rsrc(w, (unsigned)(TAPS * cc) * 4u);
+    {   // weights [tap][cout][cin] -> LDS [tap][cin][32]; eight 16-byte reads of a thread in flight
+        constexpr int pieces = CIN / 4, WU = 8, total = TAPS * pieces * 32;
+        const rsrc_t wrs = make_rsrc(w, (unsigned)(TAPS * CIN) * (unsigned)e.Cout * 4u);
         for (int i0 = tid; i0 < total; i0 += 256 * WU) {
             u32x4_t raw[WU];
             int dst[WU];
 #pragma unroll
             for (int u = 0; u < WU; ++u) {
                 const int i = i0 + u * 256;
-                const int co = i % e.Cout, q = i / e.Cout;
+                const int co = i % 32, q = i / 32;
                 const int piece = q % pieces, tap = q / pieces;
                 const bool in = i < total;
-                dst[u] = in ? tap * cc + piece * 4 * e.Cout + co : -1;
+                dst[u] = in ? tap * CC + piece * 4 * 32 + co : -1;
                 raw[u] = __builtin_amdgcn_raw_buffer_load_b128(
-                    wrs, in ? (int)(((unsigned)(tap * e.Cout + co) * (unsigned)CIN + (unsigned)(piece * 4)) * 4u) : (int)0x80000000u, 0, 0);
+                    wrs, in ? (int)(((unsigned)(tap * e.Cout + nt * 32 + co) * (unsigned)CIN + (unsigned)(piece * 4)) * 4u) : (int)0x80000000u, 0, 0);
             }
 #pragma unroll
             for (int u = 0; u < WU; ++u) {
@@ -1082,53 +1085,73 @@ __global__ __launch_bounds__(256) void k_conv_mfma_f32(EdgeBatch eb, int pgs) {
                 float a[4];
                 __builtin_memcpy(a, &raw[u], 16);
 #pragma unroll
-                for (int v = 0; v < 4; ++v) sW[dst[u] + v * e.Cout] = a[v];
+                for (int v = 0; v < 4; ++v) sW[dst[u] + v * 32] = a[v];
             }
         }
     }
     const rsrc_t drs = make_rsrc(e.delta, (unsigned)e.sH * (unsigned)e.sW * (unsigned)CIN * 4u);
-    long long block_taps = 0;                               // statistics (thread 0 only)
-    const int tps = kSegPixels / bm;                        // tiles per segment
-    const int MT = edge_segments(e) * tps;
+    long long block_taps = 0;                               // statistics (thread 0 of the blocks of cout tile 0)
+    constexpr int TPS = kSegPixels / BM;                    // tiles per segment
+    const int MT = edge_segments(e) * TPS;
     for (int tile = blockIdx.x; tile < MT; tile += gridDim.x) {
-        const int seg = tile / tps, first = (tile - seg * tps) * bm;
+        const int seg = tile / TPS, first = (tile - seg * TPS) * BM;
         __syncthreads();
-        const int tot = tile_prologue(e, seg, first, bm, first == 0, true, s_base, s_wy, s_wx, s_vm, sh);
-        if (first >= tot) continue;
-        if (tid == 0) block_taps += sh[4];
-        if (first + pg * 32 >= tot) continue;               // no entry for this wave
+        const int tot = tile_prologue(e, seg, first, BM, nt == 0 && first == 0, nt == 0, s_base, s_wy, s_wx, s_vm, sh);
+        if (first >= tot) continue;                         // block-uniform
+        if (tid == 0 && nt == 0) block_taps += sh[4];
+        const bool wave_on = first + pg * 32 < tot;         // wave-uniform: the group has entries
         const int pl = pg * 32 + p32;
         const bool act = first + pl < tot;
-        const unsigned vmask = act ? s_vm[pl] : 0u;
-        const int rowb = act ? (s_base[pl] * CIN + h * HALF) * 4 : 0;      // bytes; negative for a border entry's first taps
-        auto load_tap = [&](int tap, u32x4_t* r) {
-            const bool v = (vmask >> tap) & 1u;
-            const int tb = rowb + ((tap / KK) * e.sW + (tap % KK)) * CIN * 4;
-#pragma unroll
-            for (int i = 0; i < NP; ++i)
-                r[i] = __builtin_amdgcn_raw_buffer_load_b128(drs, v ? tb + i * 16 : (int)0x80000000u, 0, 0);
-        };
         f32x16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-        u32x4_t rows[2][NP];
-        load_tap(0, rows[0]);
-        const float* wl = sW + h * HALF * e.Cout + nt * 32 + p32;
+        if (wave_on) {
+            const unsigned vmask = act ? s_vm[pl] : 0u;
+            const int rowb = act ? (s_base[pl] * CIN + h * HALF) * 4 : 0;  // bytes; negative for a border entry's first taps
+            auto load_tap = [&](int tap, u32x4_t* r) {      // tap >= TAPS (the last round of some waves): zeros
+                const bool v = tap < TAPS && ((vmask >> tap) & 1u);
+                const int jy = tap / KK, jx = tap - jy * KK;
+                const int tb = rowb + (jy * e.sW + jx) * CIN * 4;
 #pragma unroll
-        for (int tap = 0; tap < TAPS; ++tap) {
-            if (tap + 1 < TAPS) load_tap(tap + 1, rows[(tap + 1) & 1]);
-            const float* wt = wl + tap * cc;
+                for (int i = 0; i < NP; ++i)
+                    r[i] = __builtin_amdgcn_raw_buffer_load_b128(drs, v ? tb + i * 16 : (int)0x80000000u, 0, 0);
+            };
+            u32x4_t rows[2][NP];
+            load_tap(ks, rows[0]);
+            const float* wl = sW + h * HALF * 32 + p32;
 #pragma unroll
-            for (int i = 0; i < NP; ++i) {
-                float b[4];
-                __builtin_memcpy(b, &rows[tap & 1][i], 16);
+            for (int q = 0; q < NQ; ++q) {
+                const int tap = ks + KS * q;
+                if (q + 1 < NQ) load_tap(tap + KS, rows[(q + 1) & 1]);
+                const float* wt = wl + (tap < TAPS ? tap : TAPS - 1) * CC;
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wt[(i * 4 + j) * e.Cout], b[j], acc, 0, 0, 0);
+                for (int i = 0; i < NP; ++i) {
+                    float b[4];
+                    __builtin_memcpy(b, &rows[q & 1][i], 16);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wt[(i * 4 + j) * 32], b[j], acc, 0, 0, 0);
+                }
+            }
+        }
+        if constexpr (KS > 1) {
+            if (wave_on && ks > 0) {
+                float* red = s_red + (pg * (KS - 1) + ks - 1) * 1024 + lane;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) red[r * 64] = acc[r];
+            }
+            __syncthreads();                                // all threads of the block, whatever their wave does
+            if (wave_on && ks == 0) {
+#pragma unroll
+                for (int k = 1; k < KS; ++k) {
+                    const float* red = s_red + (pg * (KS - 1) + k - 1) * 1024 + lane;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[r] += red[r * 64];
+                }
             }
         }
         // register r of a lane: cout 8 * (r / 4) + 4 * (lane / 32) + r % 4 of the tile, entry lane % 32
-        if (act) {
+        if (act && ks == 0) {
             float* pp = (float*)e.P + pdst_offset(e, s_wy[pl], s_wx[pl]) + nt * 32 + 4 * h;
             float4 o[4];
 #pragma unroll
@@ -1582,33 +1605,50 @@ static hipError_t launch_ldsw(const EdgeBatch& eb, int nb, long long max_entries
 }
 
 // fp32 layers the matrix cores take (k_conv_mfma_f32); *done = false: not this layer
-template <int KK, int CIN>
-static hipError_t launch_mfma_f32_inst(const EdgeBatch& eb, int nb, long long nseg, size_t smem, hipStream_t st) {
+template <int KK, int CIN, int KS>
+static hipError_t launch_mfma_f32_inst(const EdgeBatch& eb, int nb, long long nseg, hipStream_t st) {
     const EdgeDev& e = eb.d[0];
-    static size_t attr_bytes = 0;
-    auto kern = k_conv_mfma_f32<KK, CIN>;
-    if (smem > 65536 && smem > attr_bytes) {
+    static bool attr_set = false;
+    auto kern = k_conv_mfma_f32<KK, CIN, KS>;
+    const size_t smem = (size_t)KK * KK * CIN * 32 * 4;
+    if (smem > 49152 && !attr_set) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (err != hipSuccess) return err;
-        attr_bytes = smem;
+        attr_set = true;
     }
-    const int pgs = 4 / (e.Cout / 32);
-    const long long tps = kSegPixels / (pgs * 32);
-    // weights are staged once per block: keep the blocks few and persistent
-    const unsigned g = cap_blocks(nseg * tps, smem > 32768 ? 256 : 768);
-    kern<<<dim3(g, 1, nb), dim3(256), smem, st>>>(eb, pgs);
+    const int nts = e.Cout / 32;
+    const long long tiles = nseg * (kSegPixels / (32 * (4 / KS)));
+    // weights are staged once per block: a bounded number of persistent blocks
+    const long long cap = (smem > 49152 ? 512 : 1024) / nts;
+    const unsigned g = cap_blocks(tiles, cap > 0 ? cap : 1);
+    kern<<<dim3(g, nts, nb), dim3(256), smem, st>>>(eb);
     return hipGetLastError();
+}
+template <int KK, int CIN>
+static hipError_t launch_mfma_f32_ks(const EdgeBatch& eb, int nb, long long nseg, hipStream_t st) {
+    const EdgeDev& e = eb.d[0];
+    if constexpr (KK == 1) {
+        return launch_mfma_f32_inst<KK, CIN, 1>(eb, nb, nseg, st);
+    } else {
+        // two waves share the taps of a 64-entry tile unless 128-entry tiles already give every compute unit four
+        // blocks (config 2, 66 and 17 segments: 10.5 k frames/s with one wave per tile, 11.7 k with two, 10.4 k with four)
+        const long long nts = e.Cout / 32;
+        int ks = nseg * 2 * nts >= 1024 ? 1 : 2;
+        if (g_tile == 1 || g_tile == 2 || g_tile == 4) ks = g_tile;
+        if (ks == 1) return launch_mfma_f32_inst<KK, CIN, 1>(eb, nb, nseg, st);
+        if (ks == 2) return launch_mfma_f32_inst<KK, CIN, 2>(eb, nb, nseg, st);
+        return launch_mfma_f32_inst<KK, CIN, 4>(eb, nb, nseg, st);
+    }
 }
 static hipError_t launch_mfma_f32(const EdgeBatch& eb, int nb, long long nseg, hipStream_t st, bool* done) {
     const EdgeDev& e = eb.d[0];
     *done = false;
-    const size_t smem = (size_t)e.k * e.k * e.Cin * e.Cout * 4;
-    if (e.up || (e.k != 1 && e.k != 3) || (e.Cin != 32 && e.Cin != 64) || (e.Cout != 32 && e.Cout != 64 && e.Cout != 128) ||
-        smem > 150 * 1024 || (long long)e.sH * e.sW * e.Cin >= (1ll << 29))
+    if (e.up || (e.k != 1 && e.k != 3) || (e.Cin != 32 && e.Cin != 64) || e.Cout % 32 != 0 || e.Cout > 1024 ||
+        (long long)e.sH * e.sW * e.Cin >= (1ll << 29) || (long long)e.k * e.k * e.Cin * e.Cout >= (1ll << 29))
         return hipSuccess;
     *done = true;
-    if (e.k == 3) return e.Cin == 32 ? launch_mfma_f32_inst<3, 32>(eb, nb, nseg, smem, st) : launch_mfma_f32_inst<3, 64>(eb, nb, nseg, smem, st);
-    return e.Cin == 32 ? launch_mfma_f32_inst<1, 32>(eb, nb, nseg, smem, st) : launch_mfma_f32_inst<1, 64>(eb, nb, nseg, smem, st);
+    if (e.k == 3) return e.Cin == 32 ? launch_mfma_f32_ks<3, 32>(eb, nb, nseg, st) : launch_mfma_f32_ks<3, 64>(eb, nb, nseg, st);
+    return e.Cin == 32 ? launch_mfma_f32_ks<1, 32>(eb, nb, nseg, st) : launch_mfma_f32_ks<1, 64>(eb, nb, nseg, st);
 }
 
 hipError_t launch_conv(const EdgeBatch& eb, int nb, int dtype, int conv_path, hipStream_t st, int* cls) {
