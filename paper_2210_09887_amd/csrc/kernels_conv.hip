@@ -1032,7 +1032,7 @@ __global__ __launch_bounds__(256) void k_conv_ldsw(EdgeBatch eb, int groups, int
 
 // ---------------------------------------------------------------------------
 // fp32 layers on the matrix cores (v_mfma_f32_32x32x2_f32), Cin and footprint at
-// compile time, Cout a multiple of 32, no upsampling.  A block owns one tile of
+// compile time, Cout 16 or a multiple of 32, no upsampling.  A block owns one tile of
 // 32 couts (blockIdx.y) and keeps its weights in LDS as [tap][cin][32]; its four
 // waves are 4 / KS groups of 32 list entries x KS shares of the taps (wave k
 // of a group takes taps k, k + KS, ...), and the partial sums of a group are
@@ -1061,6 +1061,7 @@ __global__ __launch_bounds__(256) void k_conv_mfma_f32(EdgeBatch eb) {
     const int p32 = lane & 31, h = lane >> 5;
     const int pg = wave % PGS, ks = wave / PGS;             // entry group, share of the taps
     const int nt = blockIdx.y;                              // cout tile
+    const int ncout = e.Cout - nt * 32 < 32 ? e.Cout - nt * 32 : 32;      // 16 for a 16-cout layer: the other rows of the tile are not stored
     const float* __restrict__ w = (const float*)e.w;
     carry_source_compaction(e, sh);
     {   // weights [tap][cout][cin] -> LDS [tap][cin][32]; eight 16-byte reads of a thread in flight
@@ -1074,7 +1075,7 @@ __global__ __launch_bounds__(256) void k_conv_mfma_f32(EdgeBatch eb) {
                 const int i = i0 + u * 256;
                 const int co = i % 32, q = i / 32;
                 const int piece = q % pieces, tap = q / pieces;
-                const bool in = i < total;
+                const bool in = i < total && co < ncout;
                 dst[u] = in ? tap * CC + piece * 4 * 32 + co : -1;
                 raw[u] = __builtin_amdgcn_raw_buffer_load_b128(
                     wrs, in ? (int)(((unsigned)(tap * e.Cout + nt * 32 + co) * (unsigned)CIN + (unsigned)(piece * 4)) * 4u) : (int)0x80000000u, 0, 0);
@@ -1155,9 +1156,11 @@ __global__ __launch_bounds__(256) void k_conv_mfma_f32(EdgeBatch eb) {
             float* pp = (float*)e.P + pdst_offset(e, s_wy[pl], s_wx[pl]) + nt * 32 + 4 * h;
             float4 o[4];
 #pragma unroll
-            for (int g = 0; g < 4; ++g) o[g] = *reinterpret_cast<const float4*>(pp + 8 * g);
+            for (int g = 0; g < 4; ++g)
+                if (8 * g < ncout) o[g] = *reinterpret_cast<const float4*>(pp + 8 * g);
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
+                if (8 * g >= ncout) continue;
                 o[g].x += acc[4 * g]; o[g].y += acc[4 * g + 1]; o[g].z += acc[4 * g + 2]; o[g].w += acc[4 * g + 3];
                 *reinterpret_cast<float4*>(pp + 8 * g) = o[g];
             }
@@ -1616,7 +1619,7 @@ static hipError_t launch_mfma_f32_inst(const EdgeBatch& eb, int nb, long long ns
         if (err != hipSuccess) return err;
         attr_set = true;
     }
-    const int nts = e.Cout / 32;
+    const int nts = (e.Cout + 31) / 32;
     const long long tiles = nseg * (kSegPixels / (32 * (4 / KS)));
     // weights are staged once per block: a bounded number of persistent blocks
     const long long cap = (smem > 49152 ? 512 : 1024) / nts;
@@ -1632,7 +1635,7 @@ static hipError_t launch_mfma_f32_ks(const EdgeBatch& eb, int nb, long long nseg
     } else {
         // two waves share the taps of a 64-entry tile unless 128-entry tiles already give every compute unit four
         // blocks (config 2, 66 and 17 segments: 10.5 k frames/s with one wave per tile, 11.7 k with two, 10.4 k with four)
-        const long long nts = e.Cout / 32;
+        const long long nts = (e.Cout + 31) / 32;
         int ks = nseg * 2 * nts >= 1024 ? 1 : 2;
         if (g_tile == 1 || g_tile == 2 || g_tile == 4) ks = g_tile;
         if (ks == 1) return launch_mfma_f32_inst<KK, CIN, 1>(eb, nb, nseg, st);
@@ -1643,12 +1646,15 @@ static hipError_t launch_mfma_f32_ks(const EdgeBatch& eb, int nb, long long nseg
 static hipError_t launch_mfma_f32(const EdgeBatch& eb, int nb, long long nseg, hipStream_t st, bool* done) {
     const EdgeDev& e = eb.d[0];
     *done = false;
-    if (e.up || (e.k != 1 && e.k != 3) || (e.Cin != 32 && e.Cin != 64) || e.Cout % 32 != 0 || e.Cout > 1024 ||
+    if (e.up || (e.k != 1 && e.k != 3) || (e.Cin != 16 && e.Cin != 32 && e.Cin != 64) || (e.Cout % 32 != 0 && e.Cout != 16) || e.Cout > 1024 ||
         (long long)e.sH * e.sW * e.Cin >= (1ll << 29) || (long long)e.k * e.k * e.Cin * e.Cout >= (1ll << 29))
         return hipSuccess;
     *done = true;
-    if (e.k == 3) return e.Cin == 32 ? launch_mfma_f32_ks<3, 32>(eb, nb, nseg, st) : launch_mfma_f32_ks<3, 64>(eb, nb, nseg, st);
-    return e.Cin == 32 ? launch_mfma_f32_ks<1, 32>(eb, nb, nseg, st) : launch_mfma_f32_ks<1, 64>(eb, nb, nseg, st);
+    if (e.k == 3)
+        return e.Cin == 16 ? launch_mfma_f32_ks<3, 16>(eb, nb, nseg, st)
+             : e.Cin == 32 ? launch_mfma_f32_ks<3, 32>(eb, nb, nseg, st) : launch_mfma_f32_ks<3, 64>(eb, nb, nseg, st);
+    return e.Cin == 16 ? launch_mfma_f32_ks<1, 16>(eb, nb, nseg, st)
+         : e.Cin == 32 ? launch_mfma_f32_ks<1, 32>(eb, nb, nseg, st) : launch_mfma_f32_ks<1, 64>(eb, nb, nseg, st);
 }
 
 hipError_t launch_conv(const EdgeBatch& eb, int nb, int dtype, int conv_path, hipStream_t st, int* cls) {
