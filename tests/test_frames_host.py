@@ -70,3 +70,23 @@ def test_frames_masked_refuses_bad_arguments(net):
     assert status_of(B.mdcnn_frames_masked, h, X, None, ok, [M[0], M[0] + 16], hw, z, z, O, nb) == ERR_STATE                               # masks overlap
     assert status_of(B.mdcnn_frames_masked, h, X, None, ok, [M[0], None], hw, z, z, O, nb) == ERR_NULL
     assert status_of(B.mdcnn_frames_masked, h, X, [None, M[1] + 2], ok, M, hw, z, z, O, nb) == ERR_ALIGN                                   # roi
+
+
+def test_options_accept_their_documented_values_only():
+    """mdcnn_set_option is host-only: every option takes its documented range and refuses the next value."""
+    ranges = {
+        B.MDCNN_OPT_CONV_PATH: (0, 3), B.MDCNN_OPT_PROFILE: (0, 1), B.MDCNN_OPT_CONV_XCD: (0, 1),
+        B.MDCNN_OPT_CONV_HALO: (0, 2), B.MDCNN_OPT_FUSE_SKIP: (0, 1), B.MDCNN_OPT_PIPE_MODE: (0, 1),
+        B.MDCNN_OPT_PIPE_THREADS: (0, 1), B.MDCNN_OPT_CONV_F32_MFMA: (0, 1), B.MDCNN_OPT_PIPE_GROUP: (0, 64),
+    }
+    defaults = {B.MDCNN_OPT_CONV_XCD: 1, B.MDCNN_OPT_CONV_HALO: 1, B.MDCNN_OPT_FUSE_SKIP: 1, B.MDCNN_OPT_PIPE_MODE: 1,
+                B.MDCNN_OPT_PIPE_THREADS: 1, B.MDCNN_OPT_CONV_F32_MFMA: 1}
+    for opt, (lo, hi) in ranges.items():
+        try:
+            for v in (lo, hi):
+                B.mdcnn_set_option(opt, v)
+            assert status_of(B.mdcnn_set_option, opt, hi + 1) == ERR_SIZE
+            assert status_of(B.mdcnn_set_option, opt, lo - 1) == ERR_SIZE
+        finally:
+            B.mdcnn_set_option(opt, defaults.get(opt, 0))
+    assert status_of(B.mdcnn_set_option, 99, 0) == ERR_SIZE
