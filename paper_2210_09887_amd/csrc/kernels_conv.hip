@@ -1170,6 +1170,96 @@ __global__ __launch_bounds__(256) void k_conv_mfma_f32(EdgeBatch eb) {
 }
 
 // ---------------------------------------------------------------------------
+// 3x3 stems with 3 input channels on the matrix cores, fp32 or fp16 storage
+// (fp16 values are exact in fp32, so both use v_mfma_f32_32x32x2_f32 with the
+// weights as fp32 in LDS).  K = 27 products per output, padded to 28: lane half
+// h of a wave holds k = 14 h + step, k = 9 jy + 3 jx + ci, which is element
+// (k / 9) * 3 sW + k % 9 after the entry's first tap - the three pixels of a
+// footprint row are nine consecutive values.  A block owns 128 list entries and
+// one tile of 32 couts (blockIdx.y), a wave 32 entries; a lane fetches its 14
+// values with single-element buffer loads that all go out together (a tap
+// outside the entry's mask reads beyond the tensor: zero).
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void k_conv_stem_mfma(EdgeBatch eb) {
+    const EdgeDev& e = eb.d[blockIdx.z];                  // blockIdx.z: stream of the batch
+    constexpr int BM = 128, KH = 14;
+    __shared__ float sW[2 * KH * 32];                       // [k][32 couts], row 27 zero
+    __shared__ int s_base[BM], s_wy[BM], s_wx[BM];
+    __shared__ unsigned s_vm[BM];
+    __shared__ int sh[8];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int p32 = lane & 31, h = lane >> 5;
+    const int nt = blockIdx.y;
+    const T* __restrict__ w = (const T*)e.w;
+    carry_source_compaction(e, sh);
+    for (int i = tid; i < 28 * 32; i += 256) {              // weights [tap][cout][3] -> LDS [k = 3 tap + ci][cout of the tile]
+        const int k = i >> 5, co = i & 31;
+        sW[i] = k < 27 ? (float)w[((k / 3) * e.Cout + nt * 32 + co) * 3 + k % 3] : 0.f;
+    }
+    const rsrc_t drs = make_rsrc(e.delta, (unsigned)e.sH * (unsigned)e.sW * 3u * (unsigned)sizeof(T));
+    long long block_taps = 0;                               // statistics (thread 0 of the blocks of cout tile 0)
+    constexpr int TPS = kSegPixels / BM;
+    const int MT = edge_segments(e) * TPS;
+    for (int tile = blockIdx.x; tile < MT; tile += gridDim.x) {
+        const int seg = tile / TPS, first = (tile - seg * TPS) * BM;
+        __syncthreads();
+        const int tot = tile_prologue(e, seg, first, BM, nt == 0 && first == 0, nt == 0, s_base, s_wy, s_wx, s_vm, sh);
+        if (first >= tot) continue;                         // block-uniform
+        if (tid == 0 && nt == 0) block_taps += sh[4];
+        if (first + wave * 32 >= tot) continue;             // no entry for this wave (no barrier until the next tile)
+        const int pl = wave * 32 + p32;
+        const bool act = first + pl < tot;
+        const unsigned vmask = act ? s_vm[pl] : 0u;
+        const int base3 = act ? s_base[pl] * 3 : 0;         // elements; negative for a border entry's first taps
+        float in[KH];
+#pragma unroll
+        for (int st = 0; st < KH; ++st) {
+            const int k0 = st, k1 = KH + st;                // the two halves of the wave
+            const int off = h ? (k1 / 9) * 3 * e.sW + k1 % 9 : (k0 / 9) * 3 * e.sW + k0 % 9;
+            const bool v = h ? (k1 < 27 && ((vmask >> (k1 < 27 ? k1 / 3 : 0)) & 1u)) : ((vmask >> (k0 / 3)) & 1u);
+            const int byte = v ? (base3 + off) * (int)sizeof(T) : (int)0x80000000u;
+            if constexpr (sizeof(T) == 2)
+                in[st] = (float)__builtin_bit_cast(f16, __builtin_amdgcn_raw_buffer_load_b16(drs, byte, 0, 0));
+            else
+                in[st] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(drs, byte, 0, 0));
+        }
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+        const float* wl = sW + h * KH * 32 + p32;
+#pragma unroll
+        for (int st = 0; st < KH; ++st) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wl[st * 32], in[st], acc, 0, 0, 0);
+        // register r of a lane: cout 8 * (r / 4) + 4 * (lane / 32) + r % 4 of the tile, entry lane % 32
+        if (act) {
+            T* pp = (T*)e.P + pdst_offset(e, s_wy[pl], s_wx[pl]) + nt * 32 + 4 * h;
+            if constexpr (sizeof(T) == 2) {
+                f16x4 o[4];
+#pragma unroll
+                for (int g = 0; g < 4; ++g) o[g] = *reinterpret_cast<const f16x4*>(pp + 8 * g);
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) o[g][q] = (f16)((float)o[g][q] + acc[4 * g + q]);
+                    *reinterpret_cast<f16x4*>(pp + 8 * g) = o[g];
+                }
+            } else {
+                float4 o[4];
+#pragma unroll
+                for (int g = 0; g < 4; ++g) o[g] = *reinterpret_cast<const float4*>(pp + 8 * g);
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    o[g].x += acc[4 * g]; o[g].y += acc[4 * g + 1]; o[g].z += acc[4 * g + 2]; o[g].w += acc[4 * g + 3];
+                    *reinterpret_cast<float4*>(pp + 8 * g) = o[g];
+                }
+            }
+        }
+    }
+    if (tid == 0) add_macs(e, block_taps, 0);               // statistics: one atomic per block
+}
+
+// ---------------------------------------------------------------------------
 // Stem-type layers (few input channels, e.g. RGB): compile-time footprint
 // KK x KK x CIN.  A thread owns one list entry and CPT couts; all of its
 // KK*KK*CIN inputs are fetched up front (independent loads), the weights are
@@ -1716,6 +1806,14 @@ hipError_t launch_conv(const EdgeBatch& eb, int nb, int dtype, int conv_path, hi
         bool done = false;
         const hipError_t err = launch_mfma_f32(eb, nb, nseg, st, &done);
         if (done) { *cls = kClsConvMfma; return err; }
+    }
+    if ((conv_path == 0 || conv_path == 3) && g_f32_mfma && e.k == 3 && e.Cin == 3 && e.Cout % 32 == 0 && e.Cout <= 1024 && !e.up &&
+        (long long)e.sH * e.sW * 3 < (1ll << 29)) {
+        *cls = kClsConvMfma;
+        const unsigned g = cap_blocks(nseg * (kSegPixels / 128), 2048);
+        if (dtype == MDCNN_F16) k_conv_stem_mfma<f16><<<dim3(g, e.Cout / 32, nb), dim3(256), 0, st>>>(eb);
+        else k_conv_stem_mfma<float><<<dim3(g, e.Cout / 32, nb), dim3(256), 0, st>>>(eb);
+        return hipGetLastError();
     }
     *cls = kClsConvPlain;
     if ((conv_path == 0 || conv_path == 3) && e.k == 3 && e.Cin == 3 && e.Cout % 32 == 0 && e.Cout <= 256) {
