@@ -11,7 +11,7 @@ answers with a full reset).  The video goes through `mdcnn_frames`, in calls of 
 many frames as the sequence has, which keeps up to --frames-in-flight consecutive frames
 in flight (same launches, same results bit for bit as one `mdcnn_frame` call per
 frame; that rate is reported next to it as "frame_at_a_time" and is the headline
-with --frames-in-flight 1 and for networks of fewer than ten launches per frame;
+with --frames-in-flight 1 and for networks of fewer than 16 launches per frame;
 --crops uses mdcnn_frames_crop, --front-end mdcnn_frames_masked).
 
 Prints ONE JSON line.  Besides the throughput it carries
@@ -59,7 +59,7 @@ def parse():
                          "dilation by 2 pixels) and is forced; one stream only")
     ap.add_argument("--frames-in-flight", type=int, default=0,
                     help="streams on which mdcnn_frames keeps consecutive frames of the video in flight (1..4); 1: one mdcnn_frame "
-                         "call per frame; 0 (default): the library's own rule, 4 if a frame has at least 10 launches, else 1")
+                         "call per frame; 0 (default): the library's own rule, 4 if a frame has at least 16 launches, else 1")
     ap.add_argument("--streams", type=int, default=8,
                     help="after the headline run, the same workload as a batch of this many independent streams "
                          "(mdcnn_frame_batch; reported under \"batched\"); 0 disables it")
@@ -306,7 +306,7 @@ def main():
         state["t"] += 1
         state["resets"] += int(r)
 
-    in_flight = a.frames_in_flight or (4 if len(B.mdcnn_frame_plan(g.net, 1)[0]) >= 10 else 1)
+    in_flight = a.frames_in_flight or (4 if len(B.mdcnn_frame_plan(g.net, 1)[0]) >= 16 else 1)
     outs_pool = [torch.empty_like(g.out) for _ in range(min(T, max(a.steps, a.warmup)))] if in_flight > 1 else []
     masks_pool = [torch.empty((net.H, net.W), dtype=torch.uint8, device="cuda") for _ in outs_pool] if a.front_end else []
 

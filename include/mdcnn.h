@@ -264,7 +264,7 @@ mdcnn_status mdcnn_frame_batch(mdcnn_net* const* nets, int n_streams, const void
  * and outs_dev[f] device pointers as in mdcnn_frame (out_bytes each; the output buffers
  * must not overlap each other), forced_masks_dev NULL or with NULL entries,
  * did_full_reset n_frames ints or NULL.  depth: 1..4 streams; with 1 everything runs
- * on the caller's stream.  0: the library's default - 4 if a frame has at least 10
+ * on the caller's stream.  0: the library's default - 4 if a frame has at least 16
  * launches (mdcnn_frame_plan), else 1: on the benchmark networks with fewer launches
  * the events cost more than the overlap gains.
  * The caller's stream forks into the others at the start and waits for them at the end,

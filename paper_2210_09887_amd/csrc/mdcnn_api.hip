@@ -814,7 +814,7 @@ void make_pipe_plan(const mdcnn_net* net, int group_calls, int streams, int mode
 
 constexpr int kMaxFrames = 4096;
 constexpr int kDefaultDepth = 4;
-constexpr int kMinLaunchesInFlight = 10;   // launches of a frame from which on the default is kDefaultDepth streams
+constexpr int kMinLaunchesInFlight = 16;   // launches of a frame from which on the default is kDefaultDepth streams
 
 // Masks made by the library itself for the frames of mdcnn_frames_masked.
 struct FrontEnd {
