@@ -413,7 +413,9 @@ typedef enum {
                              /* frame is issued after the events it waits for have been recorded); 0: the     */
                              /* calling thread issues everything                                             */
     MDCNN_OPT_CONV_F32_MFMA = 13, /* 1 (default): fp32 layers with 16, 32 or 64 input and 16 or n x 32 output channels */
-                             /* (1x1 or 3x3, no upsampling) run on the matrix cores; 0: plain FMA kernels    */
+                             /* (1x1 or 3x3, no upsampling), and 3x3 stems with 3 input and n x 32 output    */
+                             /* channels of either storage type, run on the matrix cores with the fp32       */
+                             /* instruction; 0: plain FMA kernels (another summation order, same tolerance)  */
     MDCNN_OPT_PIPE_MODE = 11, /* mdcnn_frames: 1 (default) whole frames on streams, 0 runs of calls on streams */
     MDCNN_OPT_STREAMS = 9    /* 2..4: mdcnn_frame, mdcnn_frame_crop and mdcnn_frame_batch put       */
                              /* independent branches of the network on up to this many streams:     */
