@@ -1064,32 +1064,36 @@ __global__ __launch_bounds__(256) void k_conv_mfma_f32(EdgeBatch eb) {
     const int ncout = e.Cout - nt * 32 < 32 ? e.Cout - nt * 32 : 32;      // 16 for a 16-cout layer: the other rows of the tile are not stored
     const float* __restrict__ w = (const float*)e.w;
     carry_source_compaction(e, sh);
-    {   // weights [tap][cout][cin] -> LDS [tap][cin][32]; eight 16-byte reads of a thread in flight
-        constexpr int pieces = CIN / 4, WU = 8, total = TAPS * pieces * 32;
-        const rsrc_t wrs = make_rsrc(w, (unsigned)(TAPS * CIN) * (unsigned)e.Cout * 4u);
-        for (int i0 = tid; i0 < total; i0 += 256 * WU) {
-            u32x4_t raw[WU];
-            int dst[WU];
+    // weights [tap][cout][cin] -> LDS [tap][cin][32], eight 16-byte reads of a thread in flight.  The first eight are
+    // requested here and stored after the prologue of the block's first tile, whose flag reads they travel with.
+    constexpr int pieces = CIN / 4, WU = 8, wtotal = TAPS * pieces * 32;
+    const rsrc_t wrs = make_rsrc(w, (unsigned)(TAPS * CIN) * (unsigned)e.Cout * 4u);
+    auto request = [&](int i0, u32x4_t* raw, int* dst) {
 #pragma unroll
-            for (int u = 0; u < WU; ++u) {
-                const int i = i0 + u * 256;
-                const int co = i % 32, q = i / 32;
-                const int piece = q % pieces, tap = q / pieces;
-                const bool in = i < total && co < ncout;
-                dst[u] = in ? tap * CC + piece * 4 * 32 + co : -1;
-                raw[u] = __builtin_amdgcn_raw_buffer_load_b128(
-                    wrs, in ? (int)(((unsigned)(tap * e.Cout + nt * 32 + co) * (unsigned)CIN + (unsigned)(piece * 4)) * 4u) : (int)0x80000000u, 0, 0);
-            }
-#pragma unroll
-            for (int u = 0; u < WU; ++u) {
-                if (dst[u] < 0) continue;
-                float a[4];
-                __builtin_memcpy(a, &raw[u], 16);
-#pragma unroll
-                for (int v = 0; v < 4; ++v) sW[dst[u] + v * 32] = a[v];
-            }
+        for (int u = 0; u < WU; ++u) {
+            const int i = i0 + u * 256;
+            const int co = i % 32, q = i / 32;
+            const int piece = q % pieces, tap = q / pieces;
+            const bool in = i < wtotal && co < ncout;
+            dst[u] = in ? tap * CC + piece * 4 * 32 + co : -1;
+            raw[u] = __builtin_amdgcn_raw_buffer_load_b128(
+                wrs, in ? (int)(((unsigned)(tap * e.Cout + nt * 32 + co) * (unsigned)CIN + (unsigned)(piece * 4)) * 4u) : (int)0x80000000u, 0, 0);
         }
-    }
+    };
+    auto store = [&](const u32x4_t* raw, const int* dst) {
+#pragma unroll
+        for (int u = 0; u < WU; ++u) {
+            if (dst[u] < 0) continue;
+            float a[4];
+            __builtin_memcpy(a, &raw[u], 16);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) sW[dst[u] + v * 32] = a[v];
+        }
+    };
+    u32x4_t raw0[WU];
+    int dst0[WU];
+    request(tid, raw0, dst0);
+    bool weights_in = false;
     const rsrc_t drs = make_rsrc(e.delta, (unsigned)e.sH * (unsigned)e.sW * (unsigned)CIN * 4u);
     long long block_taps = 0;                               // statistics (thread 0 of the blocks of cout tile 0)
     constexpr int TPS = kSegPixels / BM;                    // tiles per segment
@@ -1098,6 +1102,17 @@ __global__ __launch_bounds__(256) void k_conv_mfma_f32(EdgeBatch eb) {
         const int seg = tile / TPS, first = (tile - seg * TPS) * BM;
         __syncthreads();
         const int tot = tile_prologue(e, seg, first, BM, nt == 0 && first == 0, nt == 0, s_base, s_wy, s_wx, s_vm, sh);
+        if (!weights_in) {                                  // first tile of the block (block-uniform)
+            store(raw0, dst0);
+            for (int i0 = tid + 256 * WU; i0 < wtotal; i0 += 256 * WU) {
+                u32x4_t raw[WU];
+                int dst[WU];
+                request(i0, raw, dst);
+                store(raw, dst);
+            }
+            weights_in = true;
+            __syncthreads();
+        }
         if (first >= tot) continue;                         // block-uniform
         if (tid == 0 && nt == 0) block_taps += sh[4];
         const bool wave_on = first + pg * 32 < tot;         // wave-uniform: the group has entries
