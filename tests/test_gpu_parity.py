@@ -130,6 +130,45 @@ def test_fallback_conv_paths_on_f16(path):
         B.mdcnn_set_option(B.MDCNN_OPT_CONV_PATH, 0)
 
 
+def _fp32_shapes_net():
+    """fp32 network over the layer shapes of the matrix-core kernels that the benchmark networks lack: a 96-cout stem
+    (three cout tiles), 16-cout and 16-cin layers (half-used cout tile), a strided 64 -> 128 layer, a 1x1 with 64 inputs."""
+    from inputs.nets import NetSpec, _Builder
+    net = NetSpec("fp32_shapes", "f32", 64, 48, 4)
+    b = _Builder(net, np.random.default_rng(77), bias_amp=0.1)
+    th = 0.02
+    x = b.site("in", 3, 1, "input", False, th)
+    s1 = b.site("stem", 96, 1, theta=th)
+    s2 = b.site("a", 64, 1, theta=th)
+    s3 = b.site("b", 16, 1, theta=th)
+    s4 = b.site("c", 64, 2, theta=th)
+    s5 = b.site("d", 128, 4, theta=th)
+    y = b.site("out", 16, 4, "output", False, 0.0)
+    b.conv(x, s1, 3, 1)
+    b.conv(s1, s2, 1, 1, pad=0)          # 96 inputs: stays on the FMA kernel
+    b.conv(s2, s3, 3, 1)                 # 64 -> 16
+    b.conv(s3, s4, 3, 2)                 # 16 -> 64, stride 2
+    b.conv(s4, s5, 3, 2)                 # 64 -> 128, stride 2
+    b.conv(s5, y, 1, 1, pad=0)           # 128 inputs: FMA kernel
+    return net
+
+
+@pytest.mark.parametrize("waves_per_tile", [0, 1, 2, 4])
+def test_fp32_matrix_core_kernels_other_shapes(waves_per_tile):
+    """Teacher-forced parity of the fp32 matrix-core kernels on shapes the benchmark networks do not have, with the
+    taps of a tile on one, two or four waves (0: the library's choice)."""
+    import gpu_harness as H
+    from paper_2210_09887_amd import binding as B
+    net = _fp32_shapes_net()
+    seq = build_sequence(2, n_frames=5, H=64, W=48)
+    B.mdcnn_set_option(B.MDCNN_OPT_CONV_TILE, waves_per_tile)
+    try:
+        worst = H.teacher_forced(net, seq.frames, seq.shifts, log=log)
+        log(f"[fp32 shapes, {waves_per_tile} waves per tile] worst fp error {worst:.3e}")
+    finally:
+        B.mdcnn_set_option(B.MDCNN_OPT_CONV_TILE, 0)
+
+
 def test_fp32_layers_on_the_plain_fma_kernels():
     """fp32 layers with 32 or 64 input channels run on the matrix cores by default; with
     that switched off the plain FMA kernels take them and agree with the oracle too."""
