@@ -27,8 +27,12 @@
  *    (a hipStream_t passed as void*; NULL = the default stream).
  *  - Handles (mdcnn_buffer*, mdcnn_net*) are small HOST objects owned by the
  *    library; destroy them with the matching call.
- *  - Errors are return codes; on error nothing is enqueued.  mdcnn_last_error()
- *    gives a thread-local description of the last failure.
+ *  - Errors are return codes.  Argument, shape and state errors are found before
+ *    anything is enqueued or changed.  A HIP failure in the middle of a call
+ *    (MDCNN_ERR_HIP) may leave launches enqueued: mdcnn_frame and its variants then
+ *    mark every site of the network as never reset, so that the next camera shift
+ *    re-initialises all buffers.  mdcnn_last_error() gives a thread-local
+ *    description of the last failure.
  *  - One camera shift per frame: after mdcnn_shift_camera every non-terminal
  *    site must be passed through mdcnn_layer_forward (in topological order)
  *    before the next shift.  mdcnn_frame does exactly that.

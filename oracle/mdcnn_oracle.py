@@ -307,10 +307,16 @@ class OracleNet:
             else:
                 out = acc - a
             newA = acc.astype(s.dtype)
+        mag = np.abs(out).max(axis=2)
+        # diagnostics for the comparison protocols (no effect on the state): the magnitude the
+        # threshold test looks at, and the decision that test takes on the site's own candidates
+        # -- also when a forced mask replaces it below
+        s.mag = mag
+        s.own = (inside if s.spec.kind == "input" else (s.U | s.N)) & (s.N | (mag > theta))
         if forced is not None:
             hit = forced.astype(bool)
         else:
-            hit = np.abs(out).max(axis=2) > theta
+            hit = mag > theta
         M = cand & (s.N | hit)
         A[M] = newA[M]
         s.set_A(A)

@@ -21,6 +21,8 @@
 //   k_identity        : residual skip, P_dst[q] += delta[q] (when it is not fused into step 1)
 //   k_pool            : max pooling in delta form against a previous-output ring
 //   k_pack_weights    : [tap][cout][cin] -> [tap][cin/16][cout][16]
+#include <atomic>
+#include <mutex>
 #include <type_traits>
 
 #include "mdcnn_internal.h"
@@ -1559,12 +1561,13 @@ template <int WM, int WN, int TM, int TN, int KC, int PIPE>
 static hipError_t launch_tiled(const EdgeBatch& eb, int nb, long long max_entries, hipStream_t st) {
     const EdgeDev& e = eb.d[0];
     using Cfg = TiledCfg<WM, WN, TM, TN, KC, PIPE>;
-    static bool attr_set = false;
     auto kern = k_conv_mfma_tiled<WM, WN, TM, TN, KC, PIPE>;
-    if (!attr_set) {
+    // launches come from several host threads (frames in flight): the attribute is set once, by whoever is first
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::SMEM);
         if (err != hipSuccess) { (void)hipGetLastError(); return err; }    // do not leave it for the next call to report
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     const long long nseg = (max_entries + kSegPixels - 1) / kSegPixels;
     const long long MT = nseg * Cfg::TPS;
@@ -1626,12 +1629,12 @@ template <int NSUB, int WMV, int WK, int TM, int TN, int KC, int NLD, int RING =
 static hipError_t launch_halo_t(const EdgeBatch& eb, int nb, long long nseg, hipStream_t st) {
     const EdgeDev& e = eb.d[0];
     using Cfg = HaloCfg<NSUB, WMV, WK, TM, TN, KC, NLD, 3, RING, MINB>;
-    static bool attr_set = false;
     auto kern = k_conv_halo<NSUB, WMV, WK, TM, TN, KC, NLD, 3, RING, MINB>;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::SMEM);
         if (err != hipSuccess) { (void)hipGetLastError(); return err; }    // do not leave it for the next call to report
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     const int NT = e.Cout / Cfg::BN;
     const long long items = nseg * NSUB * NT;
@@ -1695,14 +1698,19 @@ hipError_t launch_pack_weights(const void* src, void* dst, int taps, int Cout, i
 template <typename T>
 static hipError_t launch_ldsw(const EdgeBatch& eb, int nb, long long max_entries, hipStream_t st) {
     const EdgeDev& e = eb.d[0];
-    static size_t attr_bytes = 0;
     const int groups = e.Cout / 8, ppb = 256 / groups;
     const size_t smem = (size_t)e.k * e.k * e.Cin * e.Cout * 4;
     auto kern = k_conv_ldsw<T>;
-    if (smem > 65536 && smem > attr_bytes) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (err != hipSuccess) return err;
-        attr_bytes = smem;
+    if (smem > 65536) {
+        // the limit only grows; the lock keeps two host threads from lowering it under each other
+        static std::mutex mu;
+        static size_t attr_bytes = 0;
+        std::lock_guard<std::mutex> lock(mu);
+        if (smem > attr_bytes) {
+            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (err != hipSuccess) return err;
+            attr_bytes = smem;
+        }
     }
     const long long nseg = (max_entries + kSegPixels - 1) / kSegPixels;
     const long long tps = (kSegPixels + ppb - 1) / ppb;
@@ -1716,13 +1724,13 @@ static hipError_t launch_ldsw(const EdgeBatch& eb, int nb, long long max_entries
 template <int KK, int CIN, int KS>
 static hipError_t launch_mfma_f32_inst(const EdgeBatch& eb, int nb, long long nseg, hipStream_t st) {
     const EdgeDev& e = eb.d[0];
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};
     auto kern = k_conv_mfma_f32<KK, CIN, KS>;
     const size_t smem = (size_t)KK * KK * CIN * 32 * 4;
-    if (smem > 49152 && !attr_set) {
+    if (smem > 49152 && !attr_set.load(std::memory_order_acquire)) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (err != hipSuccess) return err;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     const int nts = (e.Cout + 31) / 32;
     const long long tiles = nseg * (kSegPixels / (32 * (4 / KS)));

@@ -646,6 +646,16 @@ bool whole_view(const mdcnn_buffer* b) { return crop_pixels(b) == (size_t)b->d.H
 mdcnn_status frame_batch(mdcnn_net* const* nets, int n, const void* const* frames, const uint8_t* const* forced,
                          const int* dty, const int* dtx, void* const* outs_dev, void* stream, int* did_full_reset) {
     hipStream_t st = (hipStream_t)stream;
+    // a launch failure between the camera shift and the readout leaves the device state of a frame half
+    // done: the sites are then marked as never reset, so that the next camera shift re-initialises them
+    struct Unfinished {
+        mdcnn_net* const* nets; int n; bool armed = true;
+        ~Unfinished() {
+            if (!armed) return;
+            for (int b = 0; b < n; ++b)
+                for (mdcnn_buffer* s : nets[b]->sites) s->fresh = true;
+        }
+    } unfinished{nets, n};
     for (int b = 0; b < n; ++b) {
         mdcnn_status rc = mdcnn_shift_camera(nets[b]->sites.data(), (int)nets[b]->sites.size(), dty[b], dtx[b], stream,
                                              did_full_reset ? did_full_reset + b : nullptr);
@@ -730,6 +740,7 @@ mdcnn_status frame_batch(mdcnn_net* const* nets, int n, const void* const* frame
             o += crop_pixels(s) * s->d.C * esize(s->d.dtype);
         }
     }
+    unfinished.armed = false;
     return MDCNN_OK;
 }
 
@@ -879,9 +890,27 @@ mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, 
     // events: ring x n_events for the plan, then one per stream for fork and join
     const size_t ev_sync = (size_t)ring * pp.n_events;
     hipError_t err = aux_prepare(depth, ev_sync + kMaxStreams);
+    if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "stream set-up: %s", hipGetErrorString(err));
     hipStream_t s[kMaxStreams];
     s[0] = user;
     for (int k = 1; k < depth; ++k) s[k] = g_aux.s[k - 1];
+    // The camera path below moves the host state of the sites (ring origins, restrictions, crop) ahead by
+    // the whole run before anything is enqueued.  If the call fails, that state must not stay ahead of the
+    // device: while nothing is enqueued it is put back as it was; afterwards every site is marked as never
+    // reset, so that the next camera shift re-initialises everything.
+    struct HostState {
+        mdcnn_net* net;
+        std::vector<mdcnn_buffer> saved;
+        bool armed = true, enqueued = false;
+        explicit HostState(mdcnn_net* n) : net(n) { for (mdcnn_buffer* b : n->sites) saved.push_back(*b); }
+        ~HostState() {
+            if (!armed) return;
+            for (size_t i = 0; i < saved.size(); ++i) {
+                if (!enqueued) *net->sites[i] = saved[i];
+                else net->sites[i]->fresh = true;
+            }
+        }
+    } host_state(net);
     // the camera path of the whole run, on the host: every frame gets its own copy of the sites
     std::vector<FrameWork> work((size_t)n_frames);
     {
@@ -901,7 +930,8 @@ mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, 
             w.jobs = jobs;
         }
     }
-    if (err == hipSuccess && depth > 1) err = hipEventRecord(g_aux.events[ev_sync], user);
+    host_state.enqueued = true;
+    if (depth > 1) err = hipEventRecord(g_aux.events[ev_sync], user);
     for (int k = 1; k < depth && err == hipSuccess; ++k) err = hipStreamWaitEvent(s[k], g_aux.events[ev_sync], 0);
     if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "stream set-up: %s", hipGetErrorString(err));
     // whatever happens below, the caller's stream waits for the other streams before the call returns
@@ -1047,6 +1077,7 @@ mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, 
     if (rc) return rc;
     err = join.run();
     if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "stream synchronisation: %s", hipGetErrorString(err));
+    host_state.armed = false;
     return MDCNN_OK;
 }
 

@@ -235,3 +235,101 @@ def free_running(net, frames, shifts, forced=None, origins=None, log=None, crops
     finally:
         g.close()
     return dict(out_err=out_err, mask_mismatch=mism / max(total, 1), resets=resets, outputs=got_all, oracle_outputs=outs)
+
+
+class Follower:
+    """An oracle that follows a free-running GPU stream (protocol R with the guard band).  After every
+    frame the GPU's update masks of all sites are forced on the oracle, whose state therefore stays
+    within the fp tolerance of the GPU's, frame after frame.  check() asserts, per frame:
+      * reset decisions, and the input-site mask and list, bit for bit;
+      * every decision of the GPU against the decision this oracle takes by itself in that state
+        (OracleSite.own): where they differ, the magnitude the oracle compares with theta must lie
+        within 4 x tolerance of theta -- a wrong mask far from the threshold fails;
+      * the outputs at the tight tolerance (the masks agree by construction)."""
+
+    def __init__(self, net, origins=None):
+        self.net, self.o = net, OracleNet(net, origins)
+        self.tol = TOL[net.dtype]
+        self.band = 4 * self.tol
+        self.inner = [i for i, s in enumerate(net.sites) if s.kind != "output"]
+        self.out_err, self.flips, self.decisions, self.worst = 0.0, 0, 0, 0.0
+
+    def check(self, t, X, dy, dx, fm, got, reset, masks, l0, tag=""):
+        o = self.o
+        want, r_o = o.frame(X, dy, dx, forced_all={i: masks[i] for i in self.inner})
+        assert reset == r_o, f"{tag}frame {t}: reset decision differs"
+        for i in self.inner:
+            s = o.sites[i]
+            assert np.array_equal(s.M, masks[i]), f"{tag}frame {t} site {i}: a pixel that was no candidate was updated"
+            if i == 0 and fm is not None:
+                continue                          # the workload forces this mask: no threshold decision to compare
+            diff = s.own != masks[i]
+            self.decisions += masks[i].size
+            if i == 0:
+                assert not diff.any(), f"{tag}frame {t}: input-site mask differs"
+                assert np.array_equal(l0, np.flatnonzero(s.own.ravel())), f"{tag}frame {t}: input-site list differs"
+            if diff.any():
+                margin = np.abs(s.mag[diff] - np.float32(s.spec.theta))
+                self.flips += int(diff.sum())
+                self.worst = max(self.worst, float(margin.max()))
+                assert margin.max() < self.band, (
+                    f"{tag}frame {t} site {i} ({s.spec.name}): {int((margin >= self.band).sum())} decisions differ from the oracle's "
+                    f"outside the guard band (|magnitude - theta| up to {margin.max():.3e}, band {self.band:.1e})")
+        for a, b in zip(got, want):
+            e = maxerr(a, b)
+            self.out_err = max(self.out_err, e)
+            assert e < self.tol, f"{tag}frame {t}: output error {e:.3e} with the oracle following the GPU's masks"
+        return r_o
+
+    def result(self):
+        return dict(out_err=self.out_err, flips=self.flips, decisions=self.decisions, worst_margin=self.worst)
+
+
+def gpu_masks(g, inner):
+    return {i: (g.read(i, B.MDCNN_VIEW_FLAGS) & B.FLAG_M) != 0 for i in inner}
+
+
+def followed(net, frames, shifts, forced=None, origins=None, log=None):
+    """mdcnn_frame end to end with a Follower.  Returns dict(out_err, flips, decisions, worst_margin)."""
+    f = Follower(net, origins)
+    g = GpuNet(net, origins)
+    try:
+        for t, X in enumerate(frames):
+            dy, dx = (int(v) for v in shifts[t])
+            fm = None if forced is None else forced[t]
+            out, r = g.frame(dev(X), dy, dx, None if fm is None else dev(fm))
+            torch.cuda.synchronize()
+            got = [x.cpu().numpy() for x in g.split_outputs(out)]
+            f.check(t, X, dy, dx, fm, got, r, gpu_masks(g, f.inner), g.read(0, B.MDCNN_VIEW_LIST))
+            if log:
+                log(f"  followed frame {t}: reset={r} out_err={f.out_err:.2e} decisions off the oracle's: {f.flips}/{f.decisions}, worst margin {f.worst:.2e}")
+    finally:
+        g.close()
+    return f.result()
+
+
+def followed_batch(net, seqs, log=None):
+    """mdcnn_frame_batch: stream b runs seqs[b] = (frames, shifts, forced or None); every stream is checked
+    against a Follower of its own.  All sequences have the same length."""
+    from paper_2210_09887_amd.runtime import GpuBatch
+    n = len(seqs)
+    fs = [Follower(net) for _ in range(n)]
+    gb = GpuBatch(net, n)
+    try:
+        for t in range(len(seqs[0][0])):
+            Xs = [sq[0][t] for sq in seqs]
+            dys = [int(sq[1][t][0]) for sq in seqs]
+            dxs = [int(sq[1][t][1]) for sq in seqs]
+            fms = [None if sq[2] is None else sq[2][t] for sq in seqs]
+            keep = [None if m is None else dev(m) for m in fms]
+            outs, rs = gb.frame([dev(X) for X in Xs], dys, dxs, keep if any(m is not None for m in fms) else None)
+            torch.cuda.synchronize()
+            for b, g in enumerate(gb.streams):
+                got = [x.cpu().numpy() for x in g.split_outputs(outs[b])]
+                fs[b].check(t, Xs[b], dys[b], dxs[b], fms[b], got, bool(rs[b]), gpu_masks(g, fs[b].inner), g.read(0, B.MDCNN_VIEW_LIST),
+                            tag=f"stream {b} ")
+            if log:
+                log(f"  batch step {t}: resets={[bool(r) for r in rs]} out_err={[f'{f.out_err:.1e}' for f in fs]} flips={[f.flips for f in fs]}")
+    finally:
+        gb.close()
+    return [f.result() for f in fs]

@@ -1,6 +1,7 @@
 """Batch of independent streams (mdcnn_frame_batch): every stream must give, bit for
 bit, what mdcnn_frame gives on it alone -- outputs, reset decisions and counters --
-although all streams share their launches."""
+although all streams share their launches; and every stream is checked against an
+oracle of its own."""
 import numpy as np
 import pytest
 import torch
@@ -56,6 +57,37 @@ def test_batch_equals_single_streams(name, n_streams):
                 assert np.array_equal(g.read(i, B.MDCNN_VIEW_STATS), want_stats[b][i]), f"stream {b} site {i}: counters"
     finally:
         gb.close()
+
+
+def different_paths(net, seq, n_streams):
+    """n streams over the frames of one sequence, each with a camera path of its own: stream b takes the frames
+    from b on; streams 1.. get other steps, and one of them a reversal, i.e. a reset in the middle."""
+    T = len(seq.frames) - n_streams + 1
+    seqs = []
+    for b in range(n_streams):
+        fr, sh, fo = stream_inputs(seq, b)
+        sh = [tuple(int(v) for v in x) for x in sh[:T]]
+        if b == 1:
+            sh = [(0, 0), (1, 0), (1, 0), (-1, 0)] + [(0, 1)] * T          # the fourth frame steps back: reset
+        if b == 2:
+            sh = [(0, 0), (0, -1), (0, 0), (0, -1), (0, 1)] + [(0, 0)] * T  # the fifth frame steps back: reset
+        seqs.append((fr[:T], sh[:T], None if fo is None else fo[:T]))
+    return seqs
+
+
+@pytest.mark.parametrize("name", ["c3_resnet_96", "c5_bottleneck_40", "c2_cnn5_88x72"])
+def test_batch_against_per_stream_oracles(name):
+    """mdcnn_frame_batch against the oracle, not against the library: three streams with different camera paths and
+    resets; every stream's decisions within the guard band of an oracle that follows its masks, its reset
+    decisions and input-site lists bit for bit, its outputs at the tight tolerance."""
+    import gpu_harness as H
+    net, seq = load_case(name)
+    seqs = different_paths(net, seq, 3)
+    assert len(seqs[0][0]) >= 4
+    res = H.followed_batch(net, seqs, log=print)
+    for b, r in enumerate(res):
+        print(f"[batch vs oracle] {name} stream {b}: {r}", flush=True)
+        assert r["flips"] <= 0.02 * r["decisions"] and r["worst_margin"] < H.TOL[net.dtype] / 4     # seen: below 1e-3
 
 
 def test_batch_with_max_pooling():

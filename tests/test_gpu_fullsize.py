@@ -47,6 +47,30 @@ def test_config3_full_512_first_frames():
     log(f"config 3 mask-forced worst {worst:.2e}")
 
 
+def test_config3_full_512_teacher_forced():
+    """Every forward call of the headline network at full size from the oracle's state: update masks, lists L,
+    compute lists, counters and U flags of all 18 sites bit for bit -- the 256- and 512-channel layers included --
+    on a reset frame, a frame with a camera step that grows the view, the reset that the reversal causes, and
+    another growing step."""
+    import gpu_harness as H
+    net = build_net(3)
+    seq = build_sequence(3, n_frames=4)
+    assert [tuple(int(v) for v in s) for s in seq.shifts[1:]] == [(-1, 0), (1, 1), (-2, -2)]
+    worst = H.teacher_forced(net, seq.frames, seq.shifts, log=log)
+    log(f"config 3 teacher-forced, full size: worst fp error {worst:.2e}")
+
+
+def test_config3_full_512_followed():
+    """Free-running at full size with the guard band: every decision of the GPU against an oracle in the same
+    state, outputs at the tight tolerance."""
+    import gpu_harness as H
+    net = build_net(3)
+    seq = build_sequence(3, n_frames=5)
+    r = H.followed(net, seq.frames, seq.shifts, log=log)
+    log(f"config 3 followed: {r}")
+    assert r["flips"] < 0.02 * r["decisions"] and r["worst_margin"] < H.TOL[net.dtype] / 4      # seen: below 1e-3
+
+
 def test_config3_full_512_reset_frames_equal_library_dense_cnn():
     """Every reset frame is inferred densely, so its output must equal a plain
     dense CNN of that frame -- computed here with torch's CPU convolution in
@@ -108,7 +132,35 @@ def test_config4_full_hrnet_first_frames():
     log(f"config 4 mask-forced worst {worst:.2e}")
 
 
-@pytest.mark.parametrize("density", [0.01, 0.2, 1.0])
+def config4_frames_with_a_pan(n_tail=1):
+    """Frames 0, 1 and the first frame with a camera step (and n_tail more) of the sequence of config 4: the camera
+    rests in between, so this is a valid video with a larger gap between two of its frames."""
+    seq = build_sequence(4, n_frames=10 + n_tail)
+    k = next(t for t in range(1, len(seq.shifts)) if tuple(int(v) for v in seq.shifts[t]) != (0, 0))
+    idx = [0, 1] + list(range(k, k + 1 + n_tail))
+    return [seq.frames[t] for t in idx], [seq.shifts[t] for t in idx]
+
+
+def test_config4_full_hrnet_teacher_forced():
+    """Every forward call of the multi-resolution network at full size from the oracle's state (masks, lists,
+    compute lists, counters, flags bit for bit): a reset frame, a static frame and a frame with a camera step."""
+    import gpu_harness as H
+    net = build_net(4)
+    frames, shifts = config4_frames_with_a_pan(0)
+    worst = H.teacher_forced(net, frames, shifts, log=log)
+    log(f"config 4 teacher-forced, full size: worst fp error {worst:.2e}")
+
+
+def test_config4_full_hrnet_followed():
+    import gpu_harness as H
+    net = build_net(4)
+    frames, shifts = config4_frames_with_a_pan(1)
+    r = H.followed(net, frames, shifts, log=log)
+    log(f"config 4 followed: {r}")
+    assert r["flips"] < 0.02 * r["decisions"] and r["worst_margin"] < H.TOL[net.dtype] / 4      # seen: below 1e-3
+
+
+@pytest.mark.parametrize("density", [0.01, 0.05, 0.2, 0.5, 1.0])
 def test_config5_full_density(density):
     import gpu_harness as H
     net = build_net(5)

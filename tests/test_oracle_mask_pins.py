@@ -128,3 +128,26 @@ def test_mask_follows_the_crop():
     whole = o.input_mask(frames[1])
     assert np.array_equal(part, whole[2 * T:10 * T, 4 * T:10 * T])
     assert full.sum() > whole.sum()
+
+
+def test_a_cell_mean_equal_to_the_threshold_is_not_an_update():
+    """The downscaled delta is compared with the threshold by strict >, like every pixel delta (a delta that
+    equals the threshold is truncated, so that threshold 0 skips exactly the unchanged pixels): cells whose
+    mean is exactly theta, one ulp below and one ulp above it.  All values are exact in float32."""
+    theta = np.float32(0.25)
+    net, o = fresh(H=16, W=16, theta=float(theta))
+    up = np.nextafter(theta, np.float32(1))
+    dn = np.nextafter(theta, np.float32(0))
+    X = np.zeros((16, 16, 3), np.float32)                  # A is zero after the reset: the magnitude is max_c |X|
+    X[0:2, 0:2, 1] = theta                                 # cell (0, 0): four pixels at theta -> mean == theta
+    X[0:2, 2:4, 0] = [[0.5, 0.0], [0.25, 0.25]]            # cell (0, 1): sum 1.0 -> mean == theta exactly
+    X[2:4, 0:2, 2] = up                                    # cell (1, 0): just above
+    X[2:4, 2:4, 0] = dn                                    # cell (1, 1): just below
+    m = o.input_mask(X, pool=2)
+    cells = m.reshape(8, 2, 8, 2).max(axis=(1, 3))
+    assert cells[0, 0] == 0 and cells[0, 1] == 0 and cells[1, 1] == 0
+    assert cells[1, 0] == 1 and cells.sum() == 1
+    assert m[2:4, 0:2].all() and m.sum() == 4
+    # per pixel (pool = 1) the same rule: only the pixels above theta
+    m1 = o.input_mask(X)
+    assert m1.sum() == 4 + 1 and m1[0, 2] == 1 and m1[2:4, 0:2].all()

@@ -421,6 +421,37 @@ def test_reset_count_matches_independent_rule():
     assert sum(1 for d in seq.shifts[1:] if d.any()) == 29 and len(got) == 1
 
 
+def test_a_step_of_a_whole_view_resets_and_clears_the_restrictions():
+    """Buffer management: a step of a whole view extent (or more) leaves nothing to keep, so it is a full reset --
+    and like every reset it lifts the restrictions: the step AFTER it may go back without another reset.  The
+    sequences take such steps on either axis, in both directions, after growth in the other direction, and are
+    checked against the independent rule; the frames of the resets must be dense, the steps that follow them not."""
+    net = as_f32(small_nets()["cnn5"])                      # 24 x 24 pixels, total stride 4: a view of 6 x 6 tiles
+    Ht, Wt = net.H // net.total_stride, net.W // net.total_stride
+    paths = [
+        [(0, 0), (1, 0), (Ht, 0), (-1, 0), (0, 1)],         # grow down, whole view down (reset), back up: no reset
+        [(0, 0), (0, -1), (0, -Wt), (0, 1), (0, 1), (0, -1)],
+        [(0, 0), (0, 1), (-(Ht + 2), 0), (1, 0), (0, -1)],  # more than a view; the x restriction is lifted too
+        [(0, 0), (Ht - 1, 0), (-1, 0)],                     # one tile short of a view is growth; then a reversal
+        [(0, 0), (1, 1), (0, Wt), (-1, -1)],
+    ]
+    for path in paths:
+        o = OracleNet(net)
+        frames = rand_frames(net, len(path), 5)
+        want = refs.reset_frames(path, (Ht, Wt))
+        got = []
+        for t, (X, (dy, dx)) in enumerate(zip(frames, path)):
+            outs, r = o.frame(X, dy, dx)
+            if r:
+                got.append(t)
+                assert all(s.M.all() for s in o.sites if s.spec.kind != "output")       # inferred densely
+                assert np.abs(outs[0] - refs.dense_cnn(net, X)[0]).max() < 1e-4
+        assert got == want, (path, got, want)
+    # the rule itself on a hand-made case: the whole-view step is frame 2, and frame 3 does not reset
+    assert refs.reset_frames(paths[0], (Ht, Wt)) == [0, 2]
+    assert refs.reset_frames(paths[3], (Ht, Wt)) == [0, 2]
+
+
 # ---- I11: constants printed in the paper
 def test_paper_constants():
     g = golden()
