@@ -40,6 +40,7 @@ class SiteSpec:
     kind: str            # "input" | "preact" | "output"
     relu: bool
     theta: float
+    trunc_free: bool = False   # the site keeps accumulated values only and never truncates (see truncation_free)
 
 
 @dataclass
@@ -279,6 +280,21 @@ def _toposort(net: NetSpec):
     for e in net.edges:
         e.src, e.dst = new_of[e.src], new_of[e.dst]
     _sort_edges(net)
+
+
+def truncation_free(net: NetSpec, only=None) -> NetSpec:
+    """Marks the sites that may run without truncation: inner sites whose only producer is a 1x1
+    convolution (no upsampling) - the activation layers that do not follow a 3x3 convolution.  Such a
+    site keeps no truncated-values buffer; every update it receives is passed on.  `only`: restrict the
+    marking to these site indices.  Returns `net` (modified in place)."""
+    for i, s in enumerate(net.sites):
+        prods = [e for e in net.edges if e.dst == i]
+        ok = (s.kind == "preact" and len(prods) == 1 and prods[0].k == 1 and prods[0].up == 0 and prods[0].pad == 0
+              and not prods[0].pool)
+        s.trunc_free = bool(ok and (only is None or i in only))
+        if s.trunc_free:
+            s.theta = 0.0
+    return net
 
 
 def build_net(config: int, **overrides) -> NetSpec:

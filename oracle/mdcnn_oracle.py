@@ -35,7 +35,11 @@ What is followed, and where the paper defines it:
 * the update mask of the input may be post-processed before it is used: the
   delta is weighted by a region-of-interest map, isolated updates are
   suppressed on a downscaled delta, and the mask is dilated by a few pixels
-  -- Optimizations; Supplementary (ROI-focused sensing, first-layer dilation).
+  -- Optimizations; Supplementary (ROI-focused sensing, first-layer dilation);
+* truncation may be switched off at selected activation layers - those that do
+  not follow a 3x3 convolution - which then need only their accumulated-values
+  buffer, at the cost of passing on every update they receive
+  -- Supplementary, Optimizing memory consumption.
 
 Arithmetic: stored tensors (A, P, delta maps, weights, frames) are in the
 network's storage dtype; every elementwise operation is done in float32 in the
@@ -77,12 +81,13 @@ class OracleSite:
         self.gy = 0                         # global pixel coordinate of view pixel (0, 0)
         self.gx = 0
         self.pooled = False                 # destination of a max-pooling edge
+        self.tf = bool(getattr(spec, "trunc_free", False))   # truncation-free: accumulated values only, no P
 
     def allocate(self):
         by0, by1, bx0, bx1 = self.border
         self.Hp, self.Wp = self.H + by0 + by1, self.W + bx0 + bx1
         self.A = np.zeros((self.H, self.W, self.C), self.dtype)
-        self.P = np.zeros((self.Hp, self.Wp, self.C), self.dtype)
+        self.P = None if self.tf else np.zeros((self.Hp, self.Wp, self.C), self.dtype)
         self.N = np.zeros((self.H, self.W), bool)
         self.U = np.zeros((self.H, self.W), bool)
         self.M = np.zeros((self.H, self.W), bool)
@@ -133,7 +138,12 @@ class OracleSite:
 
     def get_P(self):
         """Pending values over the padded window (view plus dilated border)."""
+        assert not self.tf, "a truncation-free site keeps no truncated-values buffer"
         return self.P[self._p_index()]
+
+    def state_elements(self):
+        """Elements of the buffers the site keeps from frame to frame."""
+        return self.A.size + (0 if self.P is None else self.P.size) + (0 if self.Y is None else self.Y.size)
 
     def set_P(self, v):
         self.P[self._p_index()] = v
@@ -175,7 +185,12 @@ class OracleNet:
                 dst.border = [max(p, q) for p, q in zip(dst.border, b)]
                 if e.b is not None:
                     dst.beta = dst.beta + e.b.astype(np.float32)
-        for s in self.sites:
+        for i, s in enumerate(self.sites):
+            if s.tf:
+                # no truncation only where updates are not dilated: one producer, a 1x1 convolution
+                prods = [e for e in net.edges if e.dst == i]
+                assert s.spec.kind == "preact" and len(prods) == 1 and prods[0].k == 1 and prods[0].up == 0 and not prods[0].pad
+                assert not getattr(prods[0], "pool", False) and s.border == [0, 0, 0, 0] and not self.crops
             s.allocate()
         self.fresh = True
         self.R = dict(up=False, down=False, left=False, right=False)
@@ -197,7 +212,8 @@ class OracleNet:
                 s.gy += dty * s.tile
                 s.gx += dtx * s.tile
                 s.A[:] = 0
-                s.P[:] = s.beta.astype(s.dtype)
+                if not s.tf:
+                    s.P[:] = s.beta.astype(s.dtype)
                 s.N[:] = True
                 s.U[:] = False
                 s.unseen[:] = True
@@ -225,9 +241,10 @@ class OracleNet:
             Y = (s.gy - by0 + np.arange(s.Hp))[:, None]
             X = (s.gx - bx0 + np.arange(s.Wp))[None, :]
             held = (Y >= oy - by0) & (Y < oy - by0 + s.Hp) & (X >= ox - bx0) & (X < ox - bx0 + s.Wp)
-            Pw = s.get_P()
-            Pw[~held] = s.beta.astype(s.dtype)
-            s.set_P(Pw)
+            if not s.tf:
+                Pw = s.get_P()
+                Pw[~held] = s.beta.astype(s.dtype)
+                s.set_P(Pw)
             # pixels of the new view that the old view did not hold
             Y = (s.gy + np.arange(s.H))[:, None]
             X = (s.gx + np.arange(s.W))[None, :]
@@ -262,6 +279,14 @@ class OracleNet:
     def _truncate(self, i, frame, forced):
         s = self.sites[i]
         f32 = np.float32
+        if s.tf:
+            # Nothing is truncated here: the update mask and the deltas of this frame were made when the
+            # producer's output arrived (_edge); what is left is the compaction.
+            assert forced is None, "the mask of a truncation-free site cannot be forced"
+            s.L = np.flatnonzero(s.M.ravel()).astype(np.int32)
+            s.n_candidates = int(s.touched.sum())
+            s.N = np.zeros_like(s.N)
+            return
         theta = f32(s.spec.theta)
         A = s.get_A()
         a = A.astype(f32)
@@ -407,6 +432,37 @@ class OracleNet:
                     rows[ok] = src.delta[iy[ok], ix[ok]]
                     acc += rows @ w[jy * e.k + jx].T
             y = acc.astype(f32)
+        if dst.tf:
+            # Optimizing memory consumption: no truncated-values buffer.  The output of the (1x1) producer is
+            # accumulated at once and the change of the activation is passed on wherever it is not zero.
+            # A newly unveiled pixel starts from its bias and its previous activation counts as zero.  The
+            # roundings are those the path through a truncated-values buffer would take with threshold 0:
+            # the arriving value is rounded to the storage type (on top of the bias for a new pixel), then
+            # added to the accumulated value.
+            new = dst.N[oy, ox]
+            beta = dst.beta.astype(dst.dtype).astype(f32)
+            pend = (np.where(new[:, None], beta[None, :], f32(0)) + y).astype(dst.dtype).astype(f32)
+            A = dst.get_A()
+            a = np.where(new[:, None], f32(0), A[oy, ox].astype(f32))
+            acc = a + pend
+            if dst.spec.relu:
+                out = np.maximum(acc, f32(0)) - np.maximum(a, f32(0))
+            else:
+                out = acc - a
+            A[oy, ox] = acc.astype(dst.dtype)
+            dst.set_A(A)
+            mag = np.abs(out).max(axis=1) if len(lst) else np.zeros(0, f32)
+            dst.M = np.zeros((dst.H, dst.W), bool)
+            dst.M[oy, ox] = new | (mag > f32(0))
+            dst.mag = np.zeros((dst.H, dst.W), f32)
+            dst.mag[oy, ox] = mag
+            dst.own = dst.M.copy()
+            dst.touched = np.zeros((dst.H, dst.W), bool)
+            dst.touched[oy, ox] = True
+            dst.delta[:] = 0
+            upd = dst.M[oy, ox]
+            dst.delta[oy[upd], ox[upd]] = out.astype(dst.dtype)[upd]
+            return lst
         Pw = dst.get_P()
         Pw[wy, wx] = (Pw[wy, wx].astype(f32) + y).astype(dst.dtype)
         dst.set_P(Pw)
