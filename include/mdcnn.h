@@ -82,6 +82,17 @@ typedef struct {
     int crops;                /* 1: frames may cover a part of the view only            */
                               /* (mdcnn_set_crop); the site then keeps one more byte    */
                               /* per view pixel.  All sites of a network must agree.    */
+    int truncation_free;      /* 1: the site never truncates and keeps NO pending ring: */
+                              /* only A (half the state of the layer).  The output of   */
+                              /* its producer is accumulated at once, A <- A + y, and   */
+                              /* the change of the activation f(A + y) - f(A) is passed */
+                              /* on wherever it is not zero (a newly unveiled pixel     */
+                              /* starts from its bias and counts as updated).  For the  */
+                              /* activation layers that do not follow a 3x3 convolution:*/
+                              /* PREACT sites with ONE producer, a 1x1 convolution      */
+                              /* without upsampling (any stride), hence no border; no   */
+                              /* crops, no pooling.  theta is ignored (it is 0).        */
+                              /* [Supplementary: Optimizing memory consumption]         */
 } mdcnn_buffer_desc;
 
 typedef struct mdcnn_buffer mdcnn_buffer;
@@ -182,7 +193,15 @@ mdcnn_status mdcnn_set_crop(mdcnn_buffer* const* bufs, int n, int ty0, int tx0, 
  * candidate).  `outs[i]` is the destination of `edges[i]`; OUTPUT sites take no
  * forward call.  On a site with a crop (mdcnn_set_crop) `frame_dev` and
  * `forced_mask_dev` have the crop's extent and order, and step 1 leaves the
- * pixels outside the crop alone.   [Background: DeltaCNN; Padded Convolutions] */
+ * pixels outside the crop alone.
+ * Truncation-free sites (desc.truncation_free): as a DESTINATION, step 3 adds y to A
+ * instead of P and produces the site's update mask and delta map right there, in the
+ * arithmetic of steps 1 and 3 with theta 0 (y is rounded to the storage type as the
+ * pending ring would hold it, on top of the bias for a newly unveiled pixel, then
+ * added to A); the edge must be the site's only producer.  As the SOURCE `in`, step 1
+ * is skipped (its mask and deltas exist already; a forced mask is an error,
+ * MDCNN_ERR_STATE) and the call does steps 2 and 3.
+ *                                  [Background: DeltaCNN; Padded Convolutions] */
 mdcnn_status mdcnn_layer_forward(mdcnn_buffer* in, const void* frame_dev,
                                  const uint8_t* forced_mask_dev,
                                  const mdcnn_conv_desc* edges, mdcnn_buffer* const* outs,
@@ -368,6 +387,7 @@ mdcnn_status mdcnn_frames_masked(mdcnn_net* net, int n_frames, const void* const
 typedef enum {
     MDCNN_VIEW_A = 0,        /* H*W*C storage dtype: accumulated values                     */
     MDCNN_VIEW_P = 1,        /* Hp*Wp*C storage dtype: pending values over the padded window */
+                             /* (truncation-free sites have none: MDCNN_ERR_STATE)          */
     MDCNN_VIEW_DELTA = 2,    /* H*W*C storage dtype: delta map of the last forward (0 where not updated) */
     MDCNN_VIEW_FLAGS = 3,    /* H*W bytes: bit0 newly unveiled, bit1 touched, bit2 updated, */
                              /* bit3 visited by the last forward                            */

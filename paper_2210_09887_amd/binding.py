@@ -37,7 +37,8 @@ EXPORTS = ["mdcnn_conv_border", "mdcnn_buffer_bytes", "mdcnn_create_buffer", "md
 class mdcnn_buffer_desc(C.Structure):
     _fields_ = [("H", C.c_int), ("W", C.c_int), ("C", C.c_int), ("dtype", C.c_int), ("kind", C.c_int),
                 ("border", C.c_int * 4), ("tile", C.c_int), ("relu", C.c_int), ("theta", C.c_float),
-                ("bias_dev", C.c_void_p), ("origin_y", C.c_int), ("origin_x", C.c_int), ("pool_prev", C.c_int), ("crops", C.c_int)]
+                ("bias_dev", C.c_void_p), ("origin_y", C.c_int), ("origin_x", C.c_int), ("pool_prev", C.c_int), ("crops", C.c_int),
+                ("truncation_free", C.c_int)]
 
 
 class mdcnn_conv_desc(C.Structure):

@@ -1540,6 +1540,130 @@ __global__ __launch_bounds__(256) void k_pool(EdgeBatch eb) {
     }
 }
 
+// ---------------------------------------------------------------------------
+// 1x1 convolution into a truncation-free site (no pending ring): for every destination pixel q
+// whose source pixel was updated
+//   t = round(y[q] (+ bias, if q is newly unveiled));  a = newly unveiled ? 0 : A[q]
+//   A[q] <- a + t;  delta[q] <- f(a + t) - f(a);  updated if newly unveiled or any channel of the
+//   delta is not zero
+// which is what the pending ring and the delta kernel do with threshold 0.  One block per list
+// segment and ALL output channels, so the block owns its pixels: it writes their flag bytes
+// (also those of the pixels nobody touched: the mask of the frame is complete after this launch).
+// fp16 with Cin % 16 == 0 and Cout % 32 == 0 runs on the matrix cores (operands straight from
+// global memory: the layer is bound by the accumulated values it reads and writes); anything
+// else takes one thread per (entry, output channel).
+// ---------------------------------------------------------------------------
+template <typename T, bool MFMA>
+__global__ __launch_bounds__(256) void k_conv_tf(EdgeBatch eb) {
+    const EdgeDev& e = eb.d[blockIdx.z];                  // blockIdx.z: stream of the batch
+    __shared__ int s_src[kSegPixels], s_dst[kSegPixels];
+    __shared__ unsigned s_any[kSegPixels];
+    __shared__ uint8_t s_new[kSegPixels];
+    __shared__ int sh[8];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = e.dH * e.dW;                             // no border: the window is the view
+    const int nseg = (n + kSegPixels - 1) / kSegPixels;
+    T* __restrict__ A = (T*)e.dY;
+    T* __restrict__ D = (T*)const_cast<void*>(e.sA);
+    const float* __restrict__ bias = (const float*)e.wp;
+    const T* __restrict__ delta = (const T*)e.delta;
+    const T* __restrict__ w = (const T*)e.w;
+    carry_source_compaction(e, sh);
+    long long block_taps = 0;                               // statistics (thread 0 only)
+    // one (entry, channel) result: accumulate, emit the delta, remember whether it is not zero
+    auto finish = [&](int ent, int co, float y, bool& any) {
+        const int p = s_dst[ent];
+        const int vy = p / e.dW, vx = p - vy * e.dW;
+        const size_t aoff = ((size_t)wrapc(e.d_aoy + vy, e.dH) * e.dW + wrapc(e.d_aox + vx, e.dW)) * e.Cout + co;
+        const bool fresh = s_new[ent] != 0;
+        const float a = fresh ? 0.f : (float)A[aoff];
+        const float b = fresh && bias ? (float)(T)bias[co] : 0.f;
+        const float t = (float)(T)(b + y);                  // as the pending ring would hold it
+        const float acc = a + t;
+        const float out = e.s_relu ? fmaxf(acc, 0.f) - fmaxf(a, 0.f) : acc - a;
+        A[aoff] = (T)acc;
+        D[(size_t)p * e.Cout + co] = (T)out;
+        any |= out != 0.f;
+    };
+    for (int seg = blockIdx.x; seg < nseg; seg += gridDim.x) {
+        __syncthreads();                                    // previous segment is done with LDS
+        const int p = seg * kSegPixels + tid;
+        bool has = false;
+        int fl = 0, src = 0;
+        if (p < n) {
+            const int oy = p / e.dW, ox = p - oy * e.dW;
+            src = oy * e.stride * e.sW + ox * e.stride;       // k == 1, pad == 0: inside the source view
+            has = (e.sflags[src] & kFlagM) != 0;
+            fl = e.dflags[p];
+        }
+        s_any[tid] = 0u;
+        const unsigned long long bal = __ballot(has);
+        const int rank = __popcll(bal & ((1ull << lane) - 1ull));
+        if (lane == 0) sh[wave] = __popcll(bal);
+        __syncthreads();
+        int off = rank;
+        for (int i = 0; i < wave; ++i) off += sh[i];
+        const int tot = sh[0] + sh[1] + sh[2] + sh[3];
+        if (has) {
+            s_src[off] = src;
+            s_dst[off] = p;
+            s_new[off] = (uint8_t)(fl & kFlagN);
+            e.clist[seg * kSegPixels + off] = p;
+        }
+        if (tid == 0) {                                    // single writer per segment: no atomics
+            e.ccnt[seg] = tot;
+            e.cacc[seg] += (unsigned long long)tot;
+            block_taps += tot;
+        }
+        __syncthreads();
+        if constexpr (MFMA) {
+            // (32 entries x 32 couts) tiles dealt to the four waves; lane l feeds entry / cout l % 32 with
+            // the 8 consecutive cin starting at 8 * (l / 32); register r of a lane holds cout
+            // 8 * (r / 4) + 4 * (l / 32) + r % 4 of the tile for entry l % 32
+            const int nra = (tot + 31) >> 5, nca = e.Cout >> 5;
+            const int col = lane & 31, kh = lane >> 5;
+            for (int u = wave; u < nra * nca; u += 4) {
+                const int ra = u / nca, ca = u - ra * nca;
+                const int ent = ra * 32 + col;
+                const bool act = ent < tot;
+                const f16* brow = (const f16*)delta + (size_t)s_src[act ? ent : 0] * e.Cin + kh * 8;
+                const f16* arow = (const f16*)w + (size_t)(ca * 32 + col) * e.Cin + kh * 8;
+                f32x16 acc;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+                for (int c0 = 0; c0 < e.Cin; c0 += 16) {
+                    const f16x8 a = *reinterpret_cast<const f16x8*>(arow + c0);
+                    f16x8 b = *reinterpret_cast<const f16x8*>(brow + c0);
+                    if (!act)
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) b[i] = (f16)0.f;
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc, 0, 0, 0);
+                }
+                if (act) {
+                    bool any = false;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) finish(ent, ca * 32 + 8 * (r / 4) + 4 * kh + r % 4, acc[r], any);
+                    if (any) atomicOr(&s_any[ent], 1u);        // an OR: the order does not matter
+                }
+            }
+        } else {
+            for (int idx = tid; idx < tot * e.Cout; idx += 256) {
+                const int ent = idx / e.Cout, co = idx - ent * e.Cout;
+                const T* drow = delta + (size_t)s_src[ent] * e.Cin;
+                const T* wrow = w + (size_t)co * e.Cin;
+                float y = 0.f;
+                for (int ci = 0; ci < e.Cin; ++ci) y = fmaf((float)drow[ci], (float)wrow[ci], y);
+                bool any = false;
+                finish(ent, co, y, any);
+                if (any) atomicOr(&s_any[ent], 1u);
+            }
+        }
+        __syncthreads();
+        if (p < n) e.dflags[p] = (uint8_t)(has ? ((((fl & kFlagN) || s_any[off]) ? kFlagM : 0) | kFlagC) : 0);
+    }
+    if (tid == 0) add_macs(e, block_taps, MFMA ? 0 : 1);    // statistics: one atomic per block
+}
+
 // Compaction of the update mask alone (a forward call without outgoing edges).
 __global__ __launch_bounds__(256) void k_compact_source(EdgeBatch eb) {
     const EdgeDev& e = eb.d[blockIdx.z];                  // blockIdx.z: stream of the batch
@@ -1777,6 +1901,15 @@ hipError_t launch_conv(const EdgeBatch& eb, int nb, int dtype, int conv_path, hi
     if (e.k < 0) {                                         // no operator: source compaction only
         *cls = kClsLists;
         k_compact_source<<<dim3(cap_blocks(((long long)e.sH * e.sW + kSegPixels - 1) / kSegPixels, 4096), 1, nb), dim3(256), 0, st>>>(eb);
+        return hipGetLastError();
+    }
+    if (e.op == kOpTruncFree) {
+        const bool mfma = dtype == MDCNN_F16 && conv_path != 1 && e.Cin % 16 == 0 && e.Cout % 32 == 0;
+        *cls = mfma ? kClsConvMfma : kClsConvPlain;
+        const unsigned g = cap_blocks(((long long)e.dH * e.dW + kSegPixels - 1) / kSegPixels, 4096);
+        if (mfma) k_conv_tf<f16, true><<<dim3(g, 1, nb), dim3(256), 0, st>>>(eb);
+        else if (dtype == MDCNN_F16) k_conv_tf<f16, false><<<dim3(g, 1, nb), dim3(256), 0, st>>>(eb);
+        else k_conv_tf<float, false><<<dim3(g, 1, nb), dim3(256), 0, st>>>(eb);
         return hipGetLastError();
     }
     if (e.op) {

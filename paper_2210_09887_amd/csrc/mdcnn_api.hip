@@ -86,12 +86,18 @@ mdcnn_status check_desc(const mdcnn_buffer_desc* d) {
         return fail(MDCNN_ERR_SHAPE, "pool_prev is 0 or 1 and needs a PREACT site");
     if (d->crops != 0 && d->crops != 1) return fail(MDCNN_ERR_SHAPE, "crops is 0 or 1");
     if (d->crops && (d->H > 65535 || d->W > 65535)) return fail(MDCNN_ERR_SIZE, "a site with crops has H, W < 65536");
+    if (d->truncation_free != 0) {
+        if (d->truncation_free != 1 || d->kind != MDCNN_SITE_PREACT || d->crops || d->pool_prev ||
+            (d->border[0] | d->border[1] | d->border[2] | d->border[3]))
+            return fail(MDCNN_ERR_SHAPE, "truncation_free is 0 or 1 and needs a PREACT site without border, crops or pooling");
+    }
     return MDCNN_OK;
 }
 
 void make_layout(const mdcnn_buffer_desc& d, Layout& L) {
     const size_t e = esize(d.dtype);
-    const bool hasA = d.kind != MDCNN_SITE_OUTPUT, hasP = d.kind != MDCNN_SITE_INPUT;
+    const bool hasA = d.kind != MDCNN_SITE_OUTPUT, hasC = d.kind != MDCNN_SITE_INPUT;
+    const bool hasP = hasC && !d.truncation_free;         // a truncation-free site keeps no pending ring
     L.Hp = d.H + d.border[0] + d.border[1];
     L.Wp = d.W + d.border[2] + d.border[3];
     const size_t nseg_l = ((size_t)d.H * d.W + kSegPixels - 1) / kSegPixels;
@@ -106,10 +112,10 @@ void make_layout(const mdcnn_buffer_desc& d, Layout& L) {
     L.lcnt = take(hasA ? nseg_l * 2 * 4 : 0);
     L.lacc = take(hasA ? nseg_l * 2 * 8 : 0);
     L.nseg_l = hasA ? (int)nseg_l : 0;
-    L.nseg_c = hasP ? (int)nseg_c : 0;
-    L.clist = take(hasP ? nseg_c * kSegPixels * 4 : 0);
-    L.ccnt = take(hasP ? nseg_c * 4 : 0);
-    L.cacc = take(hasP ? nseg_c * 8 : 0);
+    L.nseg_c = hasC ? (int)nseg_c : 0;
+    L.clist = take(hasC ? nseg_c * kSegPixels * 4 : 0);
+    L.ccnt = take(hasC ? nseg_c * 4 : 0);
+    L.cacc = take(hasC ? nseg_c * 8 : 0);
     L.counters = take(kNumCounters * 4);
     L.Y = take(d.pool_prev ? (size_t)d.H * d.W * d.C * e : 0);
     L.S = take(d.crops && hasA ? (size_t)d.H * d.W : 0);
@@ -208,12 +214,15 @@ mdcnn_status validate_edge(const mdcnn_buffer* in, const mdcnn_buffer* out, cons
     if (out->d.dtype != in->d.dtype) return fail(MDCNN_ERR_DTYPE, "edge %d: dtype mismatch", idx);
     if (c.Cin != in->d.C || c.Cout != out->d.C)
         return fail(MDCNN_ERR_SHAPE, "edge %d: channels %d->%d do not match sites %d->%d", idx, c.Cin, c.Cout, in->d.C, out->d.C);
+    if (c.k == 0 && out->d.truncation_free) return fail(MDCNN_ERR_SHAPE, "edge %d: a residual skip cannot end at a truncation-free site", idx);
     if (c.k == 0) {
         if (c.op != 0 || c.stride != 1 || c.pad != 0 || c.up != 0 || c.Cin != c.Cout || in->d.H != out->d.H || in->d.W != out->d.W)
             return fail(MDCNN_ERR_SHAPE, "edge %d: identity edge needs equal shapes, stride 1, pad 0, up 0", idx);
         return MDCNN_OK;
     }
     if (c.op != 0 && c.op != 1) return fail(MDCNN_ERR_SHAPE, "edge %d: unknown op %d", idx, c.op);
+    if (out->d.truncation_free && (c.k != 1 || c.up != 0 || c.pad != 0 || c.op != 0))
+        return fail(MDCNN_ERR_SHAPE, "edge %d: the producer of a truncation-free site must be a 1x1 convolution without padding or upsampling", idx);
     if (c.k < 1 || c.k > 5 || c.stride < 1 || c.stride > 4 || c.pad < 0 || c.pad >= c.k || c.up < 0 || c.up > 5)
         return fail(MDCNN_ERR_SHAPE, "edge %d: unsupported geometry k=%d stride=%d pad=%d up=%d", idx, c.k, c.stride, c.pad, c.up);
     if (c.up && (c.k != 1 || c.stride != 1 || c.pad != 0))
@@ -260,11 +269,15 @@ EdgeDev make_edge(const mdcnn_buffer* in, const mdcnn_buffer* out, const mdcnn_c
     if (e.op == 1 && out->d.crops) e.op = 2;               // the reset zeroes the previous pooling output
     e.sA = in->dev.A; e.s_aoy = in->dev.a_oy; e.s_aox = in->dev.a_ox; e.s_relu = in->d.relu;
     e.dY = out->dev.Y; e.d_aoy = out->dev.a_oy; e.d_aox = out->dev.a_ox;
-    e.w = c.w_dev; e.wp = c.k && !c.op ? c.w_packed_dev : nullptr; e.k = c.k; e.stride = c.k ? c.stride : 1; e.pad = c.k ? c.pad : 0; e.up = c.k ? c.up : 0;
+    if (out->d.truncation_free) {                          // no P: the edge adds to A and makes the site's mask and deltas
+        e.op = kOpTruncFree;
+        e.dY = out->dev.A; e.sA = out->dev.delta; e.s_relu = out->d.relu;
+    }
+    e.w = c.w_dev; e.wp = out->d.truncation_free ? (const void*)out->dev.bias : c.k && !c.op ? c.w_packed_dev : nullptr; e.k = c.k; e.stride = c.k ? c.stride : 1; e.pad = c.k ? c.pad : 0; e.up = c.k ? c.up : 0;
     return e;
 }
 
-mdcnn_status validate_forward(const mdcnn_buffer* in, const void* frame, const mdcnn_conv_desc* edges,
+mdcnn_status validate_forward(const mdcnn_buffer* in, const void* frame, const uint8_t* forced, const mdcnn_conv_desc* edges,
                               mdcnn_buffer* const* outs, int n_edges) {
     if (!in) return fail(MDCNN_ERR_NULL, "input buffer is NULL");
     if (in->d.kind == MDCNN_SITE_OUTPUT) return fail(MDCNN_ERR_STATE, "OUTPUT sites take no forward call");
@@ -276,6 +289,7 @@ mdcnn_status validate_forward(const mdcnn_buffer* in, const void* frame, const m
         return fail(MDCNN_ERR_SHAPE, "frame given for a site that is not INPUT");
     }
     if (n_edges < 0 || (n_edges > 0 && (!edges || !outs))) return fail(MDCNN_ERR_NULL, "edges/outs missing");
+    if (in->d.truncation_free && forced) return fail(MDCNN_ERR_STATE, "the mask of a truncation-free site cannot be forced");
     for (int i = 0; i < n_edges; ++i) {
         mdcnn_status st = validate_edge(in, outs[i], edges[i], i);
         if (st) return st;
@@ -317,6 +331,8 @@ struct Sched {
     }
 };
 
+hipError_t launch_fill_jobs(const FillJob* jobs, const int* which, int count, hipStream_t st);
+
 mdcnn_status do_forward(int n, mdcnn_buffer* const* ins, const void* const* frames, const uint8_t* const* forced,
                         const mdcnn_conv_desc* const* edges, mdcnn_buffer* const* const* outs, int n_edges,
                         hipStream_t st, int fuse_skip = -1, Sched* sc = nullptr, const FillJob* jobs = nullptr,
@@ -337,8 +353,13 @@ mdcnn_status do_forward(int n, mdcnn_buffer* const* ins, const void* const* fram
             k.p_oy = d->dev.p_oy; k.p_ox = d->dev.p_ox;
         }
     }
-    if (sc) st = sc->begin();
     hipError_t err;
+    if (ins[0]->d.truncation_free) {
+        // step 1 happened in the producer's launch; initialisation jobs that would have ridden along get a launch of their own
+        err = n_riders > 0 ? launch_fill_jobs(jobs, riders, n_riders, st) : hipSuccess;
+        if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "shift launch: %s", hipGetErrorString(err));
+    } else {
+    if (sc) st = sc->begin();
     if (n == 1 && n_riders > 0) {
         // initialisation jobs of other sites, which nothing in this launch touches, ride along
         static thread_local Step1Fill sf;
@@ -351,6 +372,7 @@ mdcnn_status do_forward(int n, mdcnn_buffer* const* ins, const void* const* fram
     }
     if (sc) sc->end();
     if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "step-1 launch: %s", hipGetErrorString(err));
+    }
     auto launch_edge = [&](int idx) -> mdcnn_status {
         if (sc) st = sc->begin();
         struct AtExit { Sched* sc; ~AtExit() { if (sc) sc->end(); } } at_exit{sc};
@@ -405,7 +427,7 @@ bool same_shape(const mdcnn_net* a, const mdcnn_net* b) {
     if (a->sites.size() != b->sites.size() || a->esrc != b->esrc || a->edst != b->edst) return false;
     for (size_t i = 0; i < a->sites.size(); ++i) {
         const mdcnn_buffer_desc &x = a->sites[i]->d, &y = b->sites[i]->d;
-        if (x.H != y.H || x.W != y.W || x.C != y.C || x.dtype != y.dtype || x.kind != y.kind || x.relu != y.relu || x.crops != y.crops ||
+        if (x.H != y.H || x.W != y.W || x.C != y.C || x.dtype != y.dtype || x.kind != y.kind || x.relu != y.relu || x.crops != y.crops || x.truncation_free != y.truncation_free ||
             x.border[0] != y.border[0] || x.border[1] != y.border[1] || x.border[2] != y.border[2] || x.border[3] != y.border[3])
             return false;
     }
@@ -463,7 +485,8 @@ void make_plan(const mdcnn_net* net, int ns, Plan& plan) {
         if (home[i] < 0) home[i] = 0;
         const int fuse = fused_skip(net, e0, e1);
         const int skip_dst = fuse >= 0 ? net->edst[e0 + fuse] : -1;
-        const int s1 = add(home[i], {lastw[i], skip_dst >= 0 ? lastw[skip_dst] : -1});
+        // (a truncation-free site has no delta launch: its edges follow its producer)
+        const int s1 = net->sites[i]->d.truncation_free ? lastw[i] : add(home[i], {lastw[i], skip_dst >= 0 ? lastw[skip_dst] : -1});
         lastw[i] = s1;
         if (skip_dst >= 0) {
             lastw[skip_dst] = s1;
@@ -763,7 +786,7 @@ void make_pipe_plan(const mdcnn_net* net, int group_calls, int streams, int mode
         pp.call_e1.push_back(e1);
         // a delta launch counts one, a convolution launch four (measured on the benchmark networks: 5-8 us against 13-27 us)
         const int fuse = fused_skip(net, e0, e1);
-        cost.push_back(1.0 + 4.0 * ((e1 - e0) - (fuse >= 0 ? 1 : 0)));
+        cost.push_back((net->sites[i]->d.truncation_free ? 0.0 : 1.0) + 4.0 * ((e1 - e0) - (fuse >= 0 ? 1 : 0)));
         e0 = e1;
     }
     const int n_calls = (int)pp.call_site.size();
@@ -1166,7 +1189,8 @@ mdcnn_status mdcnn_create_buffer(const mdcnn_buffer_desc* desc, void* dev_mem, s
         return fail(MDCNN_ERR_SIZE, "dev_mem holds %zu bytes, %zu needed", bytes, need);
     }
     char* base = (char*)dev_mem;
-    const bool hasA = desc->kind != MDCNN_SITE_OUTPUT, hasP = desc->kind != MDCNN_SITE_INPUT;
+    const bool hasA = desc->kind != MDCNN_SITE_OUTPUT, hasC = desc->kind != MDCNN_SITE_INPUT;
+    const bool hasP = hasC && !desc->truncation_free;
     SiteDev& s = b->dev;
     s = SiteDev{};
     s.A = hasA ? base + b->L.A : nullptr;
@@ -1177,9 +1201,9 @@ mdcnn_status mdcnn_create_buffer(const mdcnn_buffer_desc* desc, void* dev_mem, s
     s.list = hasA ? (int*)(base + b->L.list) : nullptr;
     s.lcnt = hasA ? (int*)(base + b->L.lcnt) : nullptr;
     s.lacc = hasA ? (unsigned long long*)(base + b->L.lacc) : nullptr;
-    s.cacc = hasP ? (unsigned long long*)(base + b->L.cacc) : nullptr;
-    s.clist = hasP ? (int*)(base + b->L.clist) : nullptr;
-    s.ccnt = hasP ? (int*)(base + b->L.ccnt) : nullptr;
+    s.cacc = hasC ? (unsigned long long*)(base + b->L.cacc) : nullptr;
+    s.clist = hasC ? (int*)(base + b->L.clist) : nullptr;
+    s.ccnt = hasC ? (int*)(base + b->L.ccnt) : nullptr;
     s.counters = (int*)(base + b->L.counters);
     s.bias = desc->bias_dev;
     s.H = desc->H; s.W = desc->W; s.C = desc->C; s.Hp = b->L.Hp; s.Wp = b->L.Wp;
@@ -1232,7 +1256,7 @@ mdcnn_status mdcnn_set_crop(mdcnn_buffer* const* bufs, int n, int ty0, int tx0, 
 
 mdcnn_status mdcnn_layer_forward(mdcnn_buffer* in, const void* frame_dev, const uint8_t* forced_mask_dev,
                                  const mdcnn_conv_desc* edges, mdcnn_buffer* const* outs, int n_edges, void* stream) {
-    mdcnn_status st = validate_forward(in, frame_dev, edges, outs, n_edges);
+    mdcnn_status st = validate_forward(in, frame_dev, forced_mask_dev, edges, outs, n_edges);
     if (st) return st;
     return do_forward(1, &in, &frame_dev, &forced_mask_dev, &edges, &outs, n_edges, (hipStream_t)stream);
 }
@@ -1255,6 +1279,12 @@ mdcnn_status mdcnn_net_create(mdcnn_buffer* const* sites, int n_sites, const int
         if (sites[edge_src[i]]->d.kind == MDCNN_SITE_OUTPUT) return fail(MDCNN_ERR_SHAPE, "edge %d leaves an OUTPUT site", i);
         mdcnn_status st = validate_edge(sites[edge_src[i]], sites[edge_dst[i]], edges[i], i);
         if (st) return st;
+    }
+    for (int i = 0; i < n_sites; ++i) {
+        if (!sites[i]->d.truncation_free) continue;
+        int producers = 0;
+        for (int e = 0; e < n_edges; ++e) producers += edge_dst[e] == i;
+        if (producers != 1) return fail(MDCNN_ERR_SHAPE, "site %d is truncation-free and has %d producers (it needs exactly one)", i, producers);
     }
     mdcnn_net* net = new (std::nothrow) mdcnn_net();
     if (!net) return fail(MDCNN_ERR_SIZE, "out of host memory");
@@ -1471,17 +1501,17 @@ mdcnn_status mdcnn_input_mask(const mdcnn_buffer* in, const void* frame_dev, con
 static mdcnn_status view_bytes(const mdcnn_buffer* b, int what, size_t* need) {
     const mdcnn_buffer_desc& d = b->d;
     const size_t e = esize(d.dtype);
-    const bool hasA = d.kind != MDCNN_SITE_OUTPUT, hasP = d.kind != MDCNN_SITE_INPUT;
+    const bool hasA = d.kind != MDCNN_SITE_OUTPUT, hasC = d.kind != MDCNN_SITE_INPUT, hasP = hasC && !d.truncation_free;
     switch (what) {
         case MDCNN_VIEW_A:
         case MDCNN_VIEW_DELTA:
             if (!hasA) return fail(MDCNN_ERR_STATE, "OUTPUT sites hold no A / delta");
             *need = (size_t)d.H * d.W * d.C * e; return MDCNN_OK;
         case MDCNN_VIEW_P:
-            if (!hasP) return fail(MDCNN_ERR_STATE, "INPUT sites hold no P");
+            if (!hasP) return fail(MDCNN_ERR_STATE, "INPUT and truncation-free sites hold no P");
             *need = (size_t)b->L.Hp * b->L.Wp * d.C * e; return MDCNN_OK;
         case MDCNN_VIEW_OUT:
-            if (!hasP) return fail(MDCNN_ERR_STATE, "INPUT sites hold no P");
+            if (!hasP) return fail(MDCNN_ERR_STATE, "INPUT and truncation-free sites hold no P");
             *need = (size_t)d.H * d.W * d.C * e; return MDCNN_OK;
         case MDCNN_VIEW_FLAGS:
             if (!hasA) return fail(MDCNN_ERR_STATE, "OUTPUT sites hold no flags");
@@ -1490,7 +1520,7 @@ static mdcnn_status view_bytes(const mdcnn_buffer* b, int what, size_t* need) {
             if (!hasA) return fail(MDCNN_ERR_STATE, "OUTPUT sites hold no list");
             *need = ((size_t)d.H * d.W + 1) * 4; return MDCNN_OK;
         case MDCNN_VIEW_CLIST:
-            if (!hasP) return fail(MDCNN_ERR_STATE, "INPUT sites hold no compute list");
+            if (!hasC) return fail(MDCNN_ERR_STATE, "INPUT sites hold no compute list");
             *need = ((size_t)b->L.Hp * b->L.Wp + 1) * 4; return MDCNN_OK;
         case MDCNN_VIEW_STATS:
             *need = 18 * 4; return MDCNN_OK;

@@ -148,11 +148,15 @@ struct EdgeDev {
     const void* wp;           // the same weights packed [tap][cin/16][cout][16], or nullptr
     int k, stride, pad, up;
     // max pooling (op == 1; op == 2: the previous output of a reset pixel was zeroed with it): the source's
-    // accumulated ring and the destination's previous outputs
+    // accumulated ring and the destination's previous outputs.
+    // Truncation-free destination (op == 3, 1x1 convolution): there is no P; dY is the destination's
+    // accumulated ring A (addressed with d_aoy, d_aox), sA its delta map (view order, written here),
+    // wp its bias (floats, or nullptr) and s_relu its activation.
     const void* sA;
     void* dY;
     int s_aoy, s_aox, s_relu, d_aoy, d_aox, op;
 };
+constexpr int kOpTruncFree = 3;
 
 // Several independent streams (same network, own buffers and camera paths) share
 // one launch: blockIdx.z picks the stream.  The descriptors travel as kernel

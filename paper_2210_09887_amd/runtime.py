@@ -81,6 +81,7 @@ class GpuNet:
             d.origin_y, d.origin_x = (0, 0) if origins is None else origins[i]
             d.pool_prev = int(i in pooled)
             d.crops = int(bool(crops))
+            d.truncation_free = int(bool(getattr(s, "trunc_free", False)))
             nbytes = B.mdcnn_buffer_bytes(d)
             mem = torch.empty(nbytes, dtype=torch.uint8, device=self.dev)
             self.mem.append(mem)

@@ -48,6 +48,10 @@ def cut(net, a, crop):
 
 def load_site(g: GpuNet, o: OracleNet, i: int):
     s = o.sites[i]
+    if s.tf:                                  # accumulated values and the flags of the shift only: there is no P
+        g.write(i, B.MDCNN_VIEW_A, s.get_A())
+        g.write(i, B.MDCNN_VIEW_FLAGS, oracle_flags(s))
+        return
     if o.crops and s.spec.kind != "output":
         g.write(i, B.MDCNN_VIEW_PENDING, oracle_pending(s))
     if s.spec.kind != "output":
@@ -84,19 +88,20 @@ def teacher_forced(net, frames, shifts, forced=None, origins=None, log=None, cro
             if t == 0 or r_o:
                 # state after a (re)initialisation must already agree exactly
                 for i, s in enumerate(o.sites):
-                    if s.spec.kind != "input":
+                    if s.spec.kind != "input" and not s.tf:
                         assert np.array_equal(g.read(i, B.MDCNN_VIEW_P), s.get_P()), f"frame {t} site {i}: P after reset"
                     if s.spec.kind != "output":
                         assert np.array_equal(g.read(i, B.MDCNN_VIEW_A), s.get_A()), f"frame {t} site {i}: A after reset"
             for i, s in enumerate(o.sites):
                 if s.spec.kind == "output":
                     continue
-                if s.spec.kind != "output":
+                if not s.tf:
                     # flags set by the GPU's own shift / producers must match the oracle's N, U
                     fl = g.read(i, B.MDCNN_VIEW_FLAGS)
                     assert np.array_equal(fl & (B.FLAG_N | B.FLAG_U), oracle_flags(s)), f"frame {t} site {i}: N/U flags"
                 edges = net.out_edges(i)
-                load_site(g, o, i)
+                if not s.tf:                  # a truncation-free site keeps the mask and the deltas its producer's call made
+                    load_site(g, o, i)
                 for e in edges:
                     load_site(g, o, e.dst)
                 fm = forced[t] if (forced is not None and i == 0) else None
@@ -116,11 +121,18 @@ def teacher_forced(net, frames, shifts, forced=None, origins=None, log=None, cro
                 st = g.read(i, B.MDCNN_VIEW_STATS)
                 assert st[0] == len(s.L) and st[1] == s.n_candidates, where + ": counters"
                 errs = [maxerr(g.read(i, B.MDCNN_VIEW_A), s.get_A()), maxerr(g.read(i, B.MDCNN_VIEW_DELTA), s.delta)]
-                if s.spec.kind != "input":
+                if s.spec.kind != "input" and not s.tf:
                     errs.append(maxerr(g.read(i, B.MDCNN_VIEW_P), s.get_P()))
                 for e, lst in zip(edges, lists):
                     d = o.sites[e.dst]
                     w2 = where + f" -> site {e.dst}"
+                    if d.tf:
+                        # the call made the destination's mask and deltas: compared here, bit for bit / within tolerance
+                        fl = g.read(e.dst, B.MDCNN_VIEW_FLAGS)
+                        assert np.array_equal((fl & B.FLAG_M) != 0, d.M), w2 + ": update mask of the truncation-free site"
+                        assert np.array_equal((fl & 8) != 0, d.touched), w2 + ": touched pixels of the truncation-free site"
+                        errs += [maxerr(g.read(e.dst, B.MDCNN_VIEW_A), d.get_A()), maxerr(g.read(e.dst, B.MDCNN_VIEW_DELTA), d.delta)]
+                        continue
                     errs.append(maxerr(g.read(e.dst, B.MDCNN_VIEW_P), d.get_P()))
                     if getattr(e, "pool", False):   # a maximum of stored values: exact
                         assert np.array_equal(g.read(e.dst, B.MDCNN_VIEW_POOL_PREV), d.get_Y()), w2 + ": previous pooling output"
@@ -176,7 +188,7 @@ def mask_forced(net, frames, shifts, forced=None, log=None):
             for i, s in enumerate(net.sites):
                 if s.kind == "output":
                     continue
-                fm = dev(masks[t][i].astype(np.uint8))
+                fm = None if getattr(s, "trunc_free", False) else dev(masks[t][i].astype(np.uint8))   # (such a mask cannot be forced)
                 Xd = dev(X) if i == 0 else None
                 keep += [fm, Xd]
                 g.layer_forward(i, Xd, fm)
@@ -194,7 +206,7 @@ def mask_forced(net, frames, shifts, forced=None, log=None):
         for i, s in enumerate(o.sites):
             if s.spec.kind != "output":
                 worst = max(worst, maxerr(g.read(i, B.MDCNN_VIEW_A), s.get_A()))
-            if s.spec.kind != "input":
+            if s.spec.kind != "input" and not s.tf:
                 worst = max(worst, maxerr(g.read(i, B.MDCNN_VIEW_P), s.get_P()))
     finally:
         g.close()
@@ -256,11 +268,12 @@ class Follower:
 
     def check(self, t, X, dy, dx, fm, got, reset, masks, l0, tag=""):
         o = self.o
-        want, r_o = o.frame(X, dy, dx, forced_all={i: masks[i] for i in self.inner})
+        want, r_o = o.frame(X, dy, dx, forced_all={i: masks[i] for i in self.inner if not o.sites[i].tf})
         assert reset == r_o, f"{tag}frame {t}: reset decision differs"
         for i in self.inner:
             s = o.sites[i]
-            assert np.array_equal(s.M, masks[i]), f"{tag}frame {t} site {i}: a pixel that was no candidate was updated"
+            if not s.tf:      # (the mask of a truncation-free site cannot be forced: it is compared like any decision)
+                assert np.array_equal(s.M, masks[i]), f"{tag}frame {t} site {i}: a pixel that was no candidate was updated"
             if i == 0 and fm is not None:
                 continue                          # the workload forces this mask: no threshold decision to compare
             diff = s.own != masks[i]

@@ -38,6 +38,7 @@ def host_net(spec):
             d.border[j] = border[i][j]
         d.tile = spec.total_stride // s.stride
         d.pool_prev = int(i in pooled)
+        d.truncation_free = int(bool(getattr(s, "trunc_free", False)))
         bufs.append(B.mdcnn_create_buffer(d, FAKE, B.mdcnn_buffer_bytes(d)))
     net = B.mdcnn_net_create(bufs, [e.src for e in spec.edges], [e.dst for e in spec.edges], edges)
     return net, bufs
@@ -57,7 +58,8 @@ def launches_of(spec):
             if e.k == 0 and all(q.dst != e.dst for q in mine[:n]):
                 fused = n
                 break
-        out.append((set(), {i} | ({mine[fused].dst} if fused is not None else set())))
+        if not getattr(s, "trunc_free", False):              # (a truncation-free site has no delta launch)
+            out.append((set(), {i} | ({mine[fused].dst} if fused is not None else set())))
         rest = [e for n, e in enumerate(mine) if n != fused]
         for e in rest:
             out.append(({i}, {e.dst}))
