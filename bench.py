@@ -14,13 +14,22 @@ frame; that rate is reported next to it as "frame_at_a_time" and is the headline
 with --frames-in-flight 1 and for networks of fewer than 16 launches per frame;
 --crops uses mdcnn_frames_crop, --front-end mdcnn_frames_masked).
 
-Prints ONE JSON line.  Besides the throughput it carries
-  roofline     -- the dominant kernel class, timed with HIP events recorded by
-                  the library around every launch of a second, instrumented pass
-                  over the same frames (algorithmic flops / bytes from device-side
-                  counters of that pass);
-  cpu_baseline -- the NumPy oracle timed on the host cores on the first frames
-                  of the same sequence.
+Prints ONE JSON line.  `value` is the median over --reps repetitions of the timed
+region of --steps frames.  Besides the throughput the line carries
+  roofline       -- the dominant kernel class, timed with HIP events recorded by
+                    the library around every launch of a second, instrumented pass
+                    over the same frames (algorithmic flops / bytes from device-side
+                    counters of that pass);
+  per_layer      -- the same per layer: the convolution launches into every site and
+                    the delta launch of every site, with their own bound
+                    max(bytes / HBM peak, flops / matrix peak);
+  measured_peaks -- what a plain copy kernel and a loop of matrix-core instructions
+                    reach on this machine, and the fractions against those;
+  frame_at_a_time-- one mdcnn_frame call per frame (the latency of a frame), with the
+                    rate over the frames that are neither the first nor a reset;
+  dense_mode     -- the same library with threshold 0 and every pixel forced;
+  cpu_baseline   -- the NumPy oracle timed on the host cores on the first frames
+                    of the same sequence.
 """
 from __future__ import annotations
 
@@ -48,7 +57,11 @@ def parse():
     ap.add_argument("--config", type=int, default=3, help="benchmark workload 1..5 (3 = headline)")
     ap.add_argument("--density", type=float, default=0.2, help="config 5 only")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle baseline; 0 disables it")
+    ap.add_argument("--reps", type=int, default=5, help="repetitions of the timed region; the median is reported")
     ap.add_argument("--dense", action="store_true", help="library dense mode: threshold 0 and all pixels forced")
+    ap.add_argument("--no-dense-leg", action="store_true", help="skip the dense-mode leg of the default run")
+    ap.add_argument("--truncation-free", action="store_true",
+                    help="sites after a 1x1 convolution keep no pending ring and never truncate (config 5: one of its three inner sites)")
     ap.add_argument("--pool-stem", action="store_true",
                     help="config 3 with the usual ResNet stem: 3x3 stride-2 max pooling after the stem convolution (total stride 16)")
     ap.add_argument("--crops", action="store_true",
@@ -225,6 +238,195 @@ def run_batched(a, cfg, net, T, frames, shifts, forced, fused):
             "kernel_ms_per_batch_step": round(kernel_ms / n_prof, 4)}
 
 
+def measured_peaks(torch, B):
+    """What this machine reaches on a plain copy kernel (1 GiB) and on a loop of independent matrix-core
+    instructions: the achievable peaks to set beside the published ones."""
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    B.mdcnn_bench_copy(src.data_ptr(), dst.data_ptr(), n, st)
+    ev[0].record()
+    for _ in range(3):
+        B.mdcnn_bench_copy(src.data_ptr(), dst.data_ptr(), n, st)
+    ev[1].record()
+    blocks, iters = 2048, 4000
+    flops = B.mdcnn_bench_mfma(iters, blocks, sink.data_ptr(), st)
+    ev[2].record()
+    flops = B.mdcnn_bench_mfma(iters, blocks, sink.data_ptr(), st)
+    ev[3].record()
+    torch.cuda.synchronize()
+    copy_gbs = 3 * 2.0 * n / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9          # bytes read + bytes written
+    mfma_tflops = flops / (ev[2].elapsed_time(ev[3]) * 1e-3) / 1e12
+    del src, dst
+    return {"stream_copy_gbs": round(copy_gbs, 1), "stream_copy": "1 GiB device-to-device, own kernel, read + write counted",
+            "mfma_f16_tflops": round(mfma_tflops, 1), "mfma_loop": f"{blocks} blocks x 4 waves x {iters} x 4 v_mfma_f32_32x32x16_f16, operands in registers"}
+
+
+def per_layer_rows(launches, g, net, before, after, n_prof, mfma_peak, fused_skips):
+    """One row per layer from the tagged launches of the instrumented pass: all convolution / pooling launches into
+    a site together (their summed mean duration per frame against the site's algorithmic flops and bytes), and the
+    delta launch of every site.  bound_us = max(bytes / HBM peak, flops / matrix peak); frac = bound_us / us."""
+    d = {k: after["per_site"][k] - before["per_site"][k] for k in after["per_site"]}
+    cb = lambda i: g.shape[i][2] * g.esize
+    t_edge, t_step1, k_edge = {}, {}, {}
+    for cls, site, edge, us in launches:
+        if cls == "step1" and site >= 0:
+            t_step1[site] = t_step1.get(site, 0.0) + us
+        elif edge >= 0 and cls in ("conv_mfma", "conv_plain", "pool", "identity"):
+            t_edge[edge] = t_edge.get(edge, 0.0) + us
+            k_edge[edge] = cls
+    rows = []
+    skip_src = set()
+    if fused_skips:
+        seen = set()
+        for e in net.edges:
+            if e.k == 0 and e.src not in seen:
+                seen.add(e.src)
+                skip_src.add(e.src)
+    for i, sp in enumerate(net.sites):
+        if i in t_step1:
+            writes = 2 if sp.kind == "input" else 3
+            H, W, _ = g.shape[i]
+            by = n_prof * H * W * 2 + int(d["candidates"][i]) * 2 * cb(i) + int(d["updated"][i]) * (writes + (2 if i in skip_src else 0)) * cb(i)
+            us = t_step1[i] / n_prof
+            bound = by / n_prof / PEAK_HBM_GBS / 1e3
+            rows.append({"site": i, "name": sp.name, "kernel": "step1", "us": round(us, 2), "bytes": round(by / n_prof),
+                         "bound_us": round(bound, 2), "frac": round(bound / us, 4) if us else None})
+        mine = [k for k, e in enumerate(net.edges) if e.dst == i and k in t_edge]
+        if not mine:
+            continue
+        us = sum(t_edge[k] for k in mine) / n_prof
+        flops = 2.0 * (int(d["macs_mfma"][i]) + int(d["macs_plain"][i])) / n_prof
+        by = int(d["compute"][i]) * 2 * cb(i)
+        for k in mine:
+            e = net.edges[k]
+            by += int(d["updated"][e.src]) * cb(e.src) + (n_prof * e.w.size * g.esize if e.w is not None else 0)
+        by /= n_prof
+        bound = max(by / PEAK_HBM_GBS / 1e3, flops / mfma_peak / 1e6)
+        rows.append({"site": i, "name": sp.name, "kernel": "+".join(sorted({k_edge[k] for k in mine})),
+                     "edges": [f"{net.edges[k].src}->{i} {net.edges[k].k}x{net.edges[k].k}" + (f"/s{net.edges[k].stride}" if net.edges[k].stride > 1 else "") for k in mine],
+                     "us": round(us, 2), "flops": round(flops), "bytes": round(by), "bound_us": round(bound, 2),
+                     "bound": "mfma" if flops / mfma_peak / 1e6 > by / PEAK_HBM_GBS / 1e3 else "hbm", "frac": round(bound / us, 4) if us else None})
+    return rows
+
+
+class Workload:
+    """One network on the GPU plus the two ways a video is pushed through it."""
+
+    def __init__(self, a, net, seq, forced_all_ones=False):
+        import numpy as np
+        import torch
+        from paper_2210_09887_amd import binding as B
+        from paper_2210_09887_amd.runtime import GpuNet
+        self.a, self.net, self.seq, self.B, self.torch = a, net, seq, B, torch
+        self.T = T = len(seq.frames)
+        shifts = seq.shifts.astype(np.int64).copy()
+        shifts[0] = -shifts[1:].sum(axis=0)            # closing the cycle: jump back to the start
+        self.shifts = shifts
+        self.frames = torch.from_numpy(seq.frames).cuda()
+        self.forced = None
+        if forced_all_ones:
+            self.forced = torch.ones((T, net.H, net.W), dtype=torch.uint8, device="cuda")
+        elif seq.forced is not None:
+            self.forced = torch.from_numpy(seq.forced).cuda()
+        self.g = g = GpuNet(net, crops=a.crops)
+        self.crops = None
+        if a.crops:
+            # a box of about 2/3 x 2/3 of the view, moving by one tile every fourth frame (seeded walk)
+            rng = np.random.default_rng(2210)
+            Ts = net.total_stride
+            Ht, Wt = net.H // Ts, net.W // Ts
+            th, tw = max(1, round(2 * Ht / 3)), max(1, round(2 * Wt / 3))
+            y, x = (Ht - th) // 2, (Wt - tw) // 2
+            crops = []
+            for t in range(T):
+                if t % 4 == 0 and t:
+                    y = int(np.clip(y + rng.integers(-1, 2), 0, Ht - th))
+                    x = int(np.clip(x + rng.integers(-1, 2), 0, Wt - tw))
+                crops.append((y, x, th, tw))
+            crops[0] = (0, 0, Ht, Wt)                  # the cycle starts from a frame that covers the whole view
+            cut = lambda v, c: v[c[0] * Ts:(c[0] + c[2]) * Ts, c[1] * Ts:(c[1] + c[3]) * Ts].contiguous()
+            self.crops = crops
+            self.frames_c = [cut(self.frames[t], crops[t]) for t in range(T)]
+            self.forced_c = None if self.forced is None else [cut(self.forced[t], crops[t]) for t in range(T)]
+        self.FE = dict(suppress=True, dilate=2)
+        self.state = {"t": 0, "resets": 0}
+        self.in_flight = a.frames_in_flight or (4 if len(B.mdcnn_frame_plan(g.net, 1)[0]) >= 16 else 1)
+        self.outs_pool = [torch.empty_like(g.out) for _ in range(min(T, max(a.steps, a.warmup)))] if self.in_flight > 1 else []
+        self.masks_pool = [torch.empty((net.H, net.W), dtype=torch.uint8, device="cuda") for _ in self.outs_pool] if a.front_end else []
+
+    def step(self):
+        a, g, net, B, st = self.a, self.g, self.net, self.B, self.state
+        t = st["t"] % self.T
+        dy, dx = (0, 0) if st["t"] == 0 else (int(self.shifts[t][0]), int(self.shifts[t][1]))
+        frames, forced = self.frames, self.forced
+        if a.front_end:
+            # the mask needs the shifted buffers: shift, mask, then the forward calls of mdcnn_frame one by one
+            r = g.shift_camera(dy, dx)
+            fm = g.input_mask(frames[t], **self.FE)
+            for i, sp in enumerate(net.sites):
+                if sp.kind != "output":
+                    g.layer_forward(i, frames[t] if i == 0 else None, fm if i == 0 else None)
+            for i in g.terminals:
+                B.mdcnn_read_view(g.bufs[i], B.MDCNN_VIEW_OUT, g.out.data_ptr(), g.out.numel() * g.esize, g._stream())
+        elif self.crops is not None:
+            _, r = g.frame_crop(self.frames_c[t], dy, dx, self.crops[t], None if forced is None else self.forced_c[t])
+        else:
+            _, r = g.frame(frames[t], dy, dx, None if forced is None else forced[t])
+        st["t"] += 1
+        st["resets"] += int(r)
+        return bool(r)
+
+    def one_by_one(self, n):
+        for _ in range(n):
+            self.step()
+
+    def run_frames(self, n):
+        """n frames of the video through mdcnn_frames, in calls of as many frames as the sequence has."""
+        a, g, st, T, frames, forced, shifts = self.a, self.g, self.state, self.T, self.frames, self.forced, self.shifts
+        done = 0
+        while done < n:
+            t0_ = st["t"]
+            m = min(n - done, len(self.outs_pool))
+            idx = [(t0_ + k) % T for k in range(m)]
+            sh = [(0, 0) if t0_ + k == 0 else (int(shifts[i][0]), int(shifts[i][1])) for k, i in enumerate(idx)]
+            if a.front_end:
+                _, _, rs = g.frames_masked([frames[i] for i in idx], [v[0] for v in sh], [v[1] for v in sh], outs=self.outs_pool[:m],
+                                           masks=self.masks_pool[:m], depth=self.in_flight, **self.FE)
+            elif self.crops is not None:
+                _, rs = g.frames_crop([self.frames_c[i] for i in idx], [v[0] for v in sh], [v[1] for v in sh], [self.crops[i] for i in idx],
+                                      None if forced is None else [self.forced_c[i] for i in idx], outs=self.outs_pool[:m], depth=self.in_flight)
+            else:
+                _, rs = g.frames([frames[i] for i in idx], [v[0] for v in sh], [v[1] for v in sh],
+                                 None if forced is None else [forced[i] for i in idx], outs=self.outs_pool[:m], depth=self.in_flight)
+            st["t"] += m
+            st["resets"] += sum(int(r) for r in rs)
+            done += m
+
+    def timed(self, run, reps):
+        """`reps` repetitions of the timed region (a.steps frames each, device synchronised on both sides) after
+        a.warmup frames; returns the list of (seconds, resets)."""
+        torch = self.torch
+        run(self.a.warmup)
+        out = []
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            self.state["resets"] = 0
+            t0 = time.perf_counter()
+            run(self.a.steps)
+            torch.cuda.synchronize()
+            out.append((time.perf_counter() - t0, self.state["resets"]))
+        return out
+
+
+def median_of(runs):
+    """The repetition with the median time (the lower one of two): (seconds, resets)."""
+    return sorted(runs)[(len(runs) - 1) // 2]
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -233,147 +435,98 @@ def main():
     import numpy as np
     import torch
     from inputs import build_net, build_sequence
+    from inputs.nets import truncation_free
     from paper_2210_09887_amd import binding as B
-    from paper_2210_09887_amd.runtime import GpuNet
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
 
     cfg = a.config
-    net = build_net(cfg, **({"pool_stem": True} if a.pool_stem and cfg == 3 else {}))
+    net_kw = {"pool_stem": True} if a.pool_stem and cfg == 3 else {}
+    net = build_net(cfg, **net_kw)
+    if a.truncation_free:
+        truncation_free(net)
     seq = build_sequence(cfg, **({"density": a.density} if cfg == 5 else {"tile": 16} if a.pool_stem and cfg == 3 else {}))
     if a.dense:
         for s in net.sites:
             s.theta = 0.0
-    T = len(seq.frames)
-    shifts = seq.shifts.astype(np.int64).copy()
-    shifts[0] = -shifts[1:].sum(axis=0)            # closing the cycle: jump back to the start
-    frames = torch.from_numpy(seq.frames).cuda()
-    forced = None
-    if a.dense:
-        forced = torch.ones((T, net.H, net.W), dtype=torch.uint8, device="cuda")
-    elif seq.forced is not None:
-        forced = torch.from_numpy(seq.forced).cuda()
     for kv in a.opt:
         k, v = kv.split("=")
         B.mdcnn_set_option(int(k), int(v))
-    g = GpuNet(net, crops=a.crops)
-
-    crops = None
-    if a.crops:
-        # a box of about 2/3 x 2/3 of the view, moving by one tile every fourth frame (seeded walk)
-        rng = np.random.default_rng(2210)
-        Ts = net.total_stride
-        Ht, Wt = net.H // Ts, net.W // Ts
-        th, tw = max(1, round(2 * Ht / 3)), max(1, round(2 * Wt / 3))
-        y, x = (Ht - th) // 2, (Wt - tw) // 2
-        crops = []
-        for t in range(T):
-            if t % 4 == 0 and t:
-                y = int(np.clip(y + rng.integers(-1, 2), 0, Ht - th))
-                x = int(np.clip(x + rng.integers(-1, 2), 0, Wt - tw))
-            crops.append((y, x, th, tw))
-        crops[0] = (0, 0, Ht, Wt)                  # the cycle starts from a frame that covers the whole view
-        cut = lambda v, c: v[c[0] * Ts:(c[0] + c[2]) * Ts, c[1] * Ts:(c[1] + c[3]) * Ts].contiguous()
-        frames_c = [cut(frames[t], crops[t]) for t in range(T)]
-        forced_c = None if forced is None else [cut(forced[t], crops[t]) for t in range(T)]
+    if a.crops or a.front_end:
         a.streams = 0
-
-    FE = dict(suppress=True, dilate=2)
     if a.front_end:
-        assert crops is None and forced is None, "--front-end excludes --crops, --dense and config 5"
-        a.streams = 0
+        assert not a.crops and not a.dense and seq.forced is None, "--front-end excludes --crops, --dense and config 5"
 
-    state = {"t": 0, "resets": 0}
+    peaks = measured_peaks(torch, B)
+    wl = Workload(a, net, seq, forced_all_ones=a.dense)
+    g, T, in_flight, crops, frames = wl.g, wl.T, wl.in_flight, wl.crops, wl.frames
+    reps = max(1, a.reps)
 
-    def step():
-        t = state["t"] % T
-        dy, dx = (0, 0) if state["t"] == 0 else (int(shifts[t][0]), int(shifts[t][1]))
-        if a.front_end:
-            # the mask needs the shifted buffers: shift, mask, then the forward calls of mdcnn_frame one by one
-            r = g.shift_camera(dy, dx)
-            fm = g.input_mask(frames[t], **FE)
-            for i, sp in enumerate(net.sites):
-                if sp.kind != "output":
-                    g.layer_forward(i, frames[t] if i == 0 else None, fm if i == 0 else None)
-            for i in g.terminals:
-                B.mdcnn_read_view(g.bufs[i], B.MDCNN_VIEW_OUT, g.out.data_ptr(), g.out.numel() * g.esize, g._stream())
-        elif crops is not None:
-            _, r = g.frame_crop(frames_c[t], dy, dx, crops[t], None if forced is None else forced_c[t])
-        else:
-            _, r = g.frame(frames[t], dy, dx, None if forced is None else forced[t])
-        state["t"] += 1
-        state["resets"] += int(r)
-
-    in_flight = a.frames_in_flight or (4 if len(B.mdcnn_frame_plan(g.net, 1)[0]) >= 16 else 1)
-    outs_pool = [torch.empty_like(g.out) for _ in range(min(T, max(a.steps, a.warmup)))] if in_flight > 1 else []
-    masks_pool = [torch.empty((net.H, net.W), dtype=torch.uint8, device="cuda") for _ in outs_pool] if a.front_end else []
-
-    def run_frames(n):
-        """n frames of the video through mdcnn_frames, in calls of as many frames as the sequence has."""
-        done = 0
-        while done < n:
-            t0_ = state["t"]
-            m = min(n - done, len(outs_pool))
-            idx = [(t0_ + k) % T for k in range(m)]
-            sh = [(0, 0) if t0_ + k == 0 else (int(shifts[i][0]), int(shifts[i][1])) for k, i in enumerate(idx)]
-            if a.front_end:
-                _, _, rs = g.frames_masked([frames[i] for i in idx], [v[0] for v in sh], [v[1] for v in sh], outs=outs_pool[:m],
-                                           masks=masks_pool[:m], depth=in_flight, **FE)
-            elif crops is not None:
-                _, rs = g.frames_crop([frames_c[i] for i in idx], [v[0] for v in sh], [v[1] for v in sh], [crops[i] for i in idx],
-                                      None if forced is None else [forced_c[i] for i in idx], outs=outs_pool[:m], depth=in_flight)
-            else:
-                _, rs = g.frames([frames[i] for i in idx], [v[0] for v in sh], [v[1] for v in sh],
-                                 None if forced is None else [forced[i] for i in idx], outs=outs_pool[:m], depth=in_flight)
-            state["t"] += m
-            state["resets"] += sum(int(r) for r in rs)
-            done += m
-
-    def timed_region(run):
-        run(a.warmup)
-        torch.cuda.synchronize()
-        state["resets"] = 0
-        t0 = time.perf_counter()
-        run(a.steps)
-        torch.cuda.synchronize()
-        return time.perf_counter() - t0
-
-    one_by_one = lambda n: [step() for _ in range(n)]
-    dt_each = None
+    each_runs = None
     if in_flight > 1:
-        dt = timed_region(run_frames)
-        resets_timed = state["resets"]
-        dt_each = timed_region(one_by_one)
+        runs = wl.timed(wl.run_frames, reps)
+        each_runs = wl.timed(wl.one_by_one, reps)
     else:
-        dt = timed_region(one_by_one)
-        resets_timed = state["resets"]
+        runs = wl.timed(wl.one_by_one, reps)
+    dt, resets_timed = median_of(runs)
+    dt_each = median_of(each_runs)[0] if each_runs else None
 
-    # ---- instrumented pass: per-class kernel time (HIP events around every launch)
+    # ---- one frame per call with a pair of events around every call: what a reset frame costs, and the rate
+    #      over the frames that are neither the first of the cycle nor a reset
+    n_kind = min(2 * T, max(a.steps, 2))
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_kind)]
+    kinds = []
+    torch.cuda.synchronize()
+    for k in range(n_kind):
+        first_of_cycle = wl.state["t"] % T == 0
+        evs[k][0].record()
+        r = wl.step()
+        evs[k][1].record()
+        kinds.append("reset" if r or first_of_cycle else "sparse")
+    torch.cuda.synchronize()
+    ms_kind = {"reset": [], "sparse": []}
+    for k in range(n_kind):
+        ms_kind[kinds[k]].append(evs[k][0].elapsed_time(evs[k][1]))
+
+    # ---- instrumented pass: per-launch kernel time (HIP events around every launch)
     before = g.totals()
     B.mdcnn_set_option(B.MDCNN_OPT_PROFILE, 1)
     B.mdcnn_profile_read()
     n_prof = min(a.steps, 2 * T)
     t1 = time.perf_counter()
     for _ in range(n_prof):
-        step()
-    prof = B.mdcnn_profile_read()
+        wl.step()
+    launches = B.mdcnn_profile_read_launches()
     dt_prof = time.perf_counter() - t1
     B.mdcnn_set_option(B.MDCNN_OPT_PROFILE, 0)
     after = g.totals()
+    prof = {k: (0.0, 0) for k in B.KERNEL_CLASSES}
+    for cls, _, _, us in launches:
+        prof[cls] = (prof[cls][0] + us * 1e-3, prof[cls][1] + 1)
 
+    fused = "8=0" not in a.opt
     flops_mfma = 2.0 * (after["macs_mfma"] - before["macs_mfma"])
     flops_plain = 2.0 * (after["macs_plain"] - before["macs_plain"])
-    ab = algorithmic_bytes(g, net, before, after, n_prof, fused_skips="8=0" not in a.opt)
+    ab = algorithmic_bytes(g, net, before, after, n_prof, fused_skips=fused)
     mfma_peak = PEAK_MFMA_F32_TFLOPS if net.dtype == "f32" else PEAK_MFMA_F16_TFLOPS
     classes, kernel_ms, rl_all, roofline = rooflines(prof, flops_mfma, flops_plain, ab, cfg, mfma_peak=mfma_peak)
+    layers = per_layer_rows(launches, g, net, before, after, n_prof, mfma_peak, fused)
+    # fractions against what this machine reaches (the matrix-core loop is fp16: fp32 networks keep the published peak only)
+    for k, v in rl_all.items():
+        if v["bound"] == "hbm":
+            v["frac_of_measured_copy"] = round(v["achieved"] / peaks["stream_copy_gbs"], 4)
+        elif v["bound"] == "mfma" and net.dtype == "f16":
+            v["frac_of_measured_mfma"] = round(v["achieved"] / peaks["mfma_f16_tflops"], 4)
+    roofline = dict(rl_all.get(roofline["kernel"], roofline), kernel=roofline["kernel"])
 
     # ---- CPU baseline: the oracle as it stands, on the first frames of the same sequence
     cpu = None
     if a.cpu_seconds > 0:
         from oracle.mdcnn_oracle import OracleNet
         o = OracleNet(net, crops=a.crops)
+        Ts = net.total_stride
         ncut = lambda v, c: np.ascontiguousarray(v[c[0] * Ts:(c[0] + c[2]) * Ts, c[1] * Ts:(c[1] + c[3]) * Ts])
         tc = time.perf_counter()
         n_cpu = 0
@@ -386,7 +539,7 @@ def main():
                 fm = seq.forced[n_cpu]
             if a.front_end:
                 o.shift_camera(dy, dx)
-                fmo = o.input_mask(seq.frames[n_cpu], **FE)
+                fmo = o.input_mask(seq.frames[n_cpu], **wl.FE)
                 for i, sp in enumerate(net.sites):
                     if sp.kind != "output":
                         o.layer_forward(i, seq.frames[n_cpu] if i == 0 else None, fmo if i == 0 else None)
@@ -408,6 +561,9 @@ def main():
 
     upd = after["per_site"]["updated"] - before["per_site"]["updated"]
     dens = [float(upd[i]) / (n_prof * g.shape[i][0] * g.shape[i][1]) for i, s in enumerate(net.sites) if s.kind != "output"]
+    entry = (("mdcnn_frames_masked" if a.front_end else "mdcnn_frames_crop" if crops is not None else "mdcnn_frames") + f", calls of {len(wl.outs_pool)} frames" if in_flight > 1 else
+             "mdcnn_frame_crop" if crops is not None else "mdcnn_shift_camera + mdcnn_input_mask + mdcnn_layer_forward" if a.front_end else "mdcnn_frame")
+    entry_each = "mdcnn_shift_camera + mdcnn_input_mask + mdcnn_layer_forward" if a.front_end else "mdcnn_frame_crop" if crops is not None else "mdcnn_frame"
     out = {
         "metric": "frames/s (ResNet-18-style 512x512, 1 GPU)" if cfg == 3 else f"frames/s (config {cfg}, 1 GPU)",
         "value": round(a.steps / dt, 2), "unit": "frames/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
@@ -417,17 +573,21 @@ def main():
                                + (", max-pooling stem" if a.pool_stem and cfg == 3 else "")
                                + (f", frames cropped to a wandering box of {crops[1][2]}x{crops[1][3]} of {net.H // net.total_stride}x{net.W // net.total_stride} tiles" if crops is not None else "")
                                + (", library dense mode" if a.dense else "")
+                               + (", truncation-free sites: " + ",".join(s.name for s in net.sites if s.trunc_free) if a.truncation_free else "")
                                + (f", density {a.density}" if cfg == 5 else ""),
                    "input": [net.H, net.W, net.sites[0].C], "sites": len(net.sites), "edges": len(net.edges),
+                   "launches_per_frame": len(B.mdcnn_frame_plan(g.net, 1)[0]) + 2,
+                   "state_bytes": int(sum(m.numel() for m in g.mem)),
                    "resets_in_timed_steps": resets_timed, "mean_update_density": round(float(np.mean(dens)), 4),
-                   "input_update_density": round(dens[0], 4), "frames_in_flight": in_flight,
-                   "entry_point": ("mdcnn_frames_masked" if a.front_end else "mdcnn_frames_crop" if crops is not None else "mdcnn_frames") + f", calls of {len(outs_pool)} frames" if in_flight > 1 else
-                                  "mdcnn_frame_crop" if crops is not None else "mdcnn_shift_camera + mdcnn_input_mask + mdcnn_layer_forward" if a.front_end else "mdcnn_frame"},
+                   "input_update_density": round(dens[0], 4), "frames_in_flight": in_flight, "entry_point": entry},
+        "repetitions": {"n": reps, "value": "median", "values": [round(a.steps / r[0], 1) for r in runs]},
         "roofline": roofline,
         "roofline_all": rl_all,
+        "measured_peaks": peaks,
         "kernel_classes": classes,
         "kernel_ms_per_step": round(kernel_ms / n_prof, 4),
         "instrumented_ms_per_step": round(1e3 * dt_prof / n_prof, 4),
+        "per_layer": layers,
         "cpu_baseline": cpu,
     }
     # the whole path against the chip: algorithmic flops and bytes of a frame (instrumented pass) at the frame rate
@@ -438,28 +598,65 @@ def main():
                          "algorithmic_gbs": round(per_frame_bytes * out["value"] / 1e9, 1),
                          "hbm_frac": round(per_frame_bytes * out["value"] / 1e9 / PEAK_HBM_GBS, 4),
                          "gflop_per_frame": round(per_frame_flops / 1e9, 2), "mbytes_per_frame": round(per_frame_bytes / 1e6, 2)}
-    if dt_each is not None:
-        out["frame_at_a_time"] = {"value": round(a.steps / dt_each, 2), "unit": "frames/s", "ms_per_step": round(1e3 * dt_each / a.steps, 4),
-                                  "entry_point": "mdcnn_shift_camera + mdcnn_input_mask + mdcnn_layer_forward" if a.front_end else "mdcnn_frame_crop" if crops is not None else "mdcnn_frame"}
+    # one frame per call: the latency of a frame (frames in flight raise the rate, not this), and the rate without the
+    # first frame of the cycle and the reset frames, from the per-call events
+    mean = lambda v: sum(v) / len(v) if v else None
+    each_ms = 1e3 * (dt_each if dt_each is not None else dt) / a.steps
+    fa = {"value": round(1e3 / each_ms, 2), "unit": "frames/s", "ms_per_step": round(each_ms, 4), "entry_point": entry_each,
+          "latency_ms_per_frame": round(each_ms, 4),
+          "reset_frames": {"n": len(ms_kind["reset"]), "ms": round(mean(ms_kind["reset"]), 4) if ms_kind["reset"] else None},
+          "other_frames": {"n": len(ms_kind["sparse"]), "ms": round(mean(ms_kind["sparse"]), 4) if ms_kind["sparse"] else None},
+          "value_no_resets": round(1e3 / mean(ms_kind["sparse"]), 2) if ms_kind["sparse"] else None}
+    if each_runs:
+        fa["repetitions"] = [round(a.steps / r[0], 1) for r in each_runs]
+    out["frame_at_a_time"] = fa
+    out["latency_ms_per_frame"] = fa["latency_ms_per_frame"]
+    out["value_no_resets"] = fa["value_no_resets"] if in_flight == 1 else None
+    if in_flight > 1:
+        out["in_flight_note"] = ("value is the rate of a clip that is already in HBM with up to %d frames in flight; a frame then takes about "
+                                 "%.3f ms from its first to its last launch (frames_in_flight x ms_per_step), against latency_ms_per_frame alone; "
+                                 "frames overlap, so the rate without reset frames is given for one call per frame only "
+                                 "(frame_at_a_time.value_no_resets)" % (in_flight, in_flight * 1e3 * dt / a.steps))
     if a.front_end:
         # the mask kernel alone, HIP events on the stream it is launched on (torch's current stream)
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = 200
-        g.input_mask(frames[0], **FE)
+        reps_fe = 200
+        g.input_mask(frames[0], **wl.FE)
         ev0.record()
-        for k in range(reps):
-            g.input_mask(frames[k % T], **FE)
+        for k in range(reps_fe):
+            g.input_mask(frames[k % T], **wl.FE)
         ev1.record()
         torch.cuda.synchronize()
-        us = 1e3 * ev0.elapsed_time(ev1) / reps
+        us = 1e3 * ev0.elapsed_time(ev1) / reps_fe
         by = net.H * net.W * (2 * net.sites[0].C * g.esize + 1)       # frame + accumulated input read once, mask written
-        out["front_end"] = {"kernel": "k_input_mask", "params": FE, "avg_us": round(us, 2), "algorithmic_bytes_per_launch": by,
+        out["front_end"] = {"kernel": "k_input_mask", "params": wl.FE, "avg_us": round(us, 2), "algorithmic_bytes_per_launch": by,
                             "roofline": {"bound": "hbm", "achieved": round(by / us / 1e3, 2), "peak": 8000.0, "unit": "GB/s",
                                          "frac": round(by / us / 1e3 / 8000.0, 5), "traffic": None}}
         out["config"]["workload"] += ", input masks from mdcnn_input_mask (suppress, dilate 2), one call per layer"
     g.close()
+    del wl
+    # ---- the library's own dense mode on the same frames: threshold 0, every pixel forced
+    if not a.dense and not a.no_dense_leg and not a.crops and not a.front_end:
+        dnet = build_net(cfg, **net_kw)
+        for s in dnet.sites:
+            s.theta = 0.0
+        dw = Workload(a, dnet, seq, forced_all_ones=True)
+        r1 = dw.timed(dw.run_frames if dw.in_flight > 1 else dw.one_by_one, 1)
+        dm = {"value": round(a.steps / r1[0][0], 2), "unit": "frames/s", "frames_in_flight": dw.in_flight,
+              "what": "threshold 0 and every pixel forced at the input: every frame is inferred densely"}
+        if dw.in_flight > 1:
+            r2 = dw.timed(dw.one_by_one, 1)
+            dm["frame_at_a_time"] = round(a.steps / r2[0][0], 2)
+        out["dense_mode"] = dm
+        dw.g.close()
+        del dw
     if a.streams > 1 and not a.copy_calibration:
-        out["batched"] = run_batched(a, cfg, net, T, frames, shifts, forced, "8=0" not in a.opt)
+        frames_d = torch.from_numpy(seq.frames).cuda()
+        shifts = seq.shifts.astype(np.int64).copy()
+        shifts[0] = -shifts[1:].sum(axis=0)
+        forced = torch.ones((T, net.H, net.W), dtype=torch.uint8, device="cuda") if a.dense else \
+            torch.from_numpy(seq.forced).cuda() if seq.forced is not None else None
+        out["batched"] = run_batched(a, cfg, net, T, frames_d, shifts, forced, fused)
     if a.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)

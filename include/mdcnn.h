@@ -466,6 +466,23 @@ typedef enum {
  * and forgets them.  Not thread-safe. */
 mdcnn_status mdcnn_profile_read(int n_classes, double* ms, long long* launches);
 
+/* Profiling mode only.  Like mdcnn_profile_read, but one entry per launch recorded since the
+ * last read, in the order they were issued: its kernel class, the site whose forward call it
+ * belongs to and the edge it executes (indices of mdcnn_net_create; -1: none, e.g. the delta
+ * launch of a site has no edge, a launch outside mdcnn_frame has neither), and its device time
+ * in microseconds.  Host arrays of `cap` entries; *n gets the number of launches (if it exceeds
+ * cap nothing is forgotten and MDCNN_ERR_SIZE is returned).  BLOCKS until they have finished. */
+mdcnn_status mdcnn_profile_read_launches(int cap, int* cls, int* site, int* edge, float* us, int* n);
+
+/* Measurement helpers of the benchmark (not part of the path): what this machine reaches on a
+ * plain copy and on back-to-back matrix-core instructions, to set beside the published peaks.
+ * mdcnn_bench_copy: dst_dev <- src_dev, `bytes` (a multiple of 16, both 16-byte aligned), one
+ * kernel, asynchronous on `stream`.  mdcnn_bench_mfma: `blocks` blocks of four waves issue
+ * `iters` x 4 independent v_mfma_f32_32x32x16_f16 each; *flops (host, optional) gets the
+ * floating-point operations of the launch; sink_dev: at least one float of device memory. */
+mdcnn_status mdcnn_bench_copy(const void* src_dev, void* dst_dev, size_t bytes, void* stream);
+mdcnn_status mdcnn_bench_mfma(int iters, int blocks, float* sink_dev, void* stream, double* flops);
+
 const char* mdcnn_last_error(void);
 const char* mdcnn_version(void);
 

@@ -30,7 +30,7 @@ STATUS_NAMES = {0: "OK", 1: "ERR_NULL", 2: "ERR_SHAPE", 3: "ERR_DTYPE", 4: "ERR_
 
 EXPORTS = ["mdcnn_conv_border", "mdcnn_buffer_bytes", "mdcnn_create_buffer", "mdcnn_destroy_buffer",
            "mdcnn_shift_camera", "mdcnn_set_crop", "mdcnn_layer_forward", "mdcnn_net_create", "mdcnn_net_destroy",
-           "mdcnn_frame", "mdcnn_frame_crop", "mdcnn_frame_batch", "mdcnn_frame_plan", "mdcnn_frames", "mdcnn_frames_crop", "mdcnn_frames_masked", "mdcnn_frames_plan", "mdcnn_input_mask", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read",
+           "mdcnn_frame", "mdcnn_frame_crop", "mdcnn_frame_batch", "mdcnn_frame_plan", "mdcnn_frames", "mdcnn_frames_crop", "mdcnn_frames_masked", "mdcnn_frames_plan", "mdcnn_input_mask", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read", "mdcnn_profile_read_launches", "mdcnn_bench_copy", "mdcnn_bench_mfma",
            "mdcnn_pack_weights", "mdcnn_last_error", "mdcnn_version"]
 
 
@@ -93,6 +93,9 @@ def lib():
         L.mdcnn_set_option.argtypes = [C.c_int, C.c_int]
         L.mdcnn_pack_weights.argtypes = [C.POINTER(mdcnn_conv_desc), C.c_int, vp, sz, vp]
         L.mdcnn_profile_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_longlong)]
+        L.mdcnn_profile_read_launches.argtypes = [C.c_int, ip, ip, ip, C.POINTER(C.c_float), ip]
+        L.mdcnn_bench_copy.argtypes = [vp, vp, sz, vp]
+        L.mdcnn_bench_mfma.argtypes = [C.c_int, C.c_int, vp, vp, C.POINTER(C.c_double)]
         L.mdcnn_last_error.restype = C.c_char_p
         L.mdcnn_version.restype = C.c_char_p
         for name in EXPORTS:
@@ -125,6 +128,26 @@ def mdcnn_profile_read():
     ms, cnt = (C.c_double * n)(), (C.c_longlong * n)()
     _check(lib().mdcnn_profile_read(n, ms, cnt))
     return {k: (ms[i], cnt[i]) for i, k in enumerate(KERNEL_CLASSES)}
+
+
+def mdcnn_profile_read_launches():
+    """[(class name, site, edge, microseconds)] of the launches since the last read, in issue order (blocks)."""
+    n = C.c_int()
+    cap = 1 << 16
+    cls, site, edge, us = (C.c_int * cap)(), (C.c_int * cap)(), (C.c_int * cap)(), (C.c_float * cap)()
+    _check(lib().mdcnn_profile_read_launches(cap, cls, site, edge, us, C.byref(n)))
+    return [(KERNEL_CLASSES[cls[i]], site[i], edge[i], us[i]) for i in range(n.value)]
+
+
+def mdcnn_bench_copy(src_ptr: int, dst_ptr: int, nbytes: int, stream: int = 0):
+    _check(lib().mdcnn_bench_copy(src_ptr, dst_ptr, nbytes, stream))
+
+
+def mdcnn_bench_mfma(iters: int, blocks: int, sink_ptr: int, stream: int = 0) -> float:
+    """Launches the matrix-core loop; returns the floating-point operations of the launch."""
+    f = C.c_double()
+    _check(lib().mdcnn_bench_mfma(int(iters), int(blocks), sink_ptr, stream, C.byref(f)))
+    return f.value
 
 
 def mdcnn_conv_border(k, stride, pad, in_extent, out_extent):

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmdcnn.so")
-SOURCES = ["mdcnn_api.hip", "kernels_state.hip", "kernels_conv.hip"]
+SOURCES = ["mdcnn_api.hip", "kernels_state.hip", "kernels_conv.hip", "kernels_bench.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

@@ -1546,23 +1546,26 @@ __global__ __launch_bounds__(256) void k_pool(EdgeBatch eb) {
 //   t = round(y[q] (+ bias, if q is newly unveiled));  a = newly unveiled ? 0 : A[q]
 //   A[q] <- a + t;  delta[q] <- f(a + t) - f(a);  updated if newly unveiled or any channel of the
 //   delta is not zero
-// which is what the pending ring and the delta kernel do with threshold 0.  One block per list
-// segment and ALL output channels, so the block owns its pixels: it writes their flag bytes
-// (also those of the pixels nobody touched: the mask of the frame is complete after this launch).
-// fp16 with Cin % 16 == 0 and Cout % 32 == 0 runs on the matrix cores (operands straight from
-// global memory: the layer is bound by the accumulated values it reads and writes); anything
-// else takes one thread per (entry, output channel).
+// which is what the pending ring and the delta kernel do with threshold 0.  A tile is a quarter of a
+// list segment (64 destination pixels, the indices of one wave) and ALL output channels, so the block
+// owns its pixels: it writes their flag bytes, also those of the pixels nobody touched - the mask of
+// the frame is complete after this launch.  The first quarter also publishes the segment's compute list.
+// fp16 with Cin % 16 == 0 and Cout % 32 == 0 runs on the matrix cores (operands straight from global
+// memory: the layer is bound by the accumulated values it reads and writes); anything else takes one
+// thread per (entry, output channel).
 // ---------------------------------------------------------------------------
+constexpr int kTfTile = 64;
 template <typename T, bool MFMA>
 __global__ __launch_bounds__(256) void k_conv_tf(EdgeBatch eb) {
     const EdgeDev& e = eb.d[blockIdx.z];                  // blockIdx.z: stream of the batch
-    __shared__ int s_src[kSegPixels], s_dst[kSegPixels];
-    __shared__ unsigned s_any[kSegPixels];
-    __shared__ uint8_t s_new[kSegPixels];
+    __shared__ int s_src[kTfTile], s_dst[kTfTile];
+    __shared__ unsigned s_any[kTfTile];
+    __shared__ uint8_t s_new[kTfTile];
     __shared__ int sh[8];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = e.dH * e.dW;                             // no border: the window is the view
-    const int nseg = (n + kSegPixels - 1) / kSegPixels;
+    const int ntiles = ((n + kSegPixels - 1) / kSegPixels) * (kSegPixels / kTfTile);
     T* __restrict__ A = (T*)e.dY;
     T* __restrict__ D = (T*)const_cast<void*>(e.sA);
     const float* __restrict__ bias = (const float*)e.wp;
@@ -1570,51 +1573,41 @@ __global__ __launch_bounds__(256) void k_conv_tf(EdgeBatch eb) {
     const T* __restrict__ w = (const T*)e.w;
     carry_source_compaction(e, sh);
     long long block_taps = 0;                               // statistics (thread 0 only)
-    // one (entry, channel) result: accumulate, emit the delta, remember whether it is not zero
-    auto finish = [&](int ent, int co, float y, bool& any) {
-        const int p = s_dst[ent];
-        const int vy = p / e.dW, vx = p - vy * e.dW;
-        const size_t aoff = ((size_t)wrapc(e.d_aoy + vy, e.dH) * e.dW + wrapc(e.d_aox + vx, e.dW)) * e.Cout + co;
-        const bool fresh = s_new[ent] != 0;
-        const float a = fresh ? 0.f : (float)A[aoff];
-        const float b = fresh && bias ? (float)(T)bias[co] : 0.f;
-        const float t = (float)(T)(b + y);                  // as the pending ring would hold it
-        const float acc = a + t;
-        const float out = e.s_relu ? fmaxf(acc, 0.f) - fmaxf(a, 0.f) : acc - a;
-        A[aoff] = (T)acc;
-        D[(size_t)p * e.Cout + co] = (T)out;
-        any |= out != 0.f;
-    };
-    for (int seg = blockIdx.x; seg < nseg; seg += gridDim.x) {
-        __syncthreads();                                    // previous segment is done with LDS
+    for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int seg = tile / (kSegPixels / kTfTile), quarter = tile % (kSegPixels / kTfTile);
+        __syncthreads();                                    // previous tile is done with LDS
         const int p = seg * kSegPixels + tid;
+        const bool own = wave == quarter;                   // this wave's 64 indices are the tile
         bool has = false;
         int fl = 0, src = 0;
         if (p < n) {
             const int oy = p / e.dW, ox = p - oy * e.dW;
             src = oy * e.stride * e.sW + ox * e.stride;       // k == 1, pad == 0: inside the source view
             has = (e.sflags[src] & kFlagM) != 0;
-            fl = e.dflags[p];
+            if (own) fl = e.dflags[p];
         }
-        s_any[tid] = 0u;
+        if (tid < kTfTile) s_any[tid] = 0u;
         const unsigned long long bal = __ballot(has);
         const int rank = __popcll(bal & ((1ull << lane) - 1ull));
         if (lane == 0) sh[wave] = __popcll(bal);
         __syncthreads();
-        int off = rank;
-        for (int i = 0; i < wave; ++i) off += sh[i];
-        const int tot = sh[0] + sh[1] + sh[2] + sh[3];
-        if (has) {
-            s_src[off] = src;
-            s_dst[off] = p;
-            s_new[off] = (uint8_t)(fl & kFlagN);
-            e.clist[seg * kSegPixels + off] = p;
+        const int tot = sh[quarter];
+        if (own && has) {
+            s_src[rank] = src;
+            s_dst[rank] = p;
+            s_new[rank] = (uint8_t)(fl & kFlagN);
         }
-        if (tid == 0) {                                    // single writer per segment: no atomics
-            e.ccnt[seg] = tot;
-            e.cacc[seg] += (unsigned long long)tot;
-            block_taps += tot;
+        if (quarter == 0) {                                // the segment's compute list, by its first tile
+            int off = rank;
+            for (int i = 0; i < wave; ++i) off += sh[i];
+            if (has) e.clist[seg * kSegPixels + off] = p;
+            if (tid == 0) {                                // single writer per segment: no atomics
+                const int all = sh[0] + sh[1] + sh[2] + sh[3];
+                e.ccnt[seg] = all;
+                e.cacc[seg] += (unsigned long long)all;
+            }
         }
+        if (tid == 0) block_taps += tot;
         __syncthreads();
         if constexpr (MFMA) {
             // (32 entries x 32 couts) tiles dealt to the four waves; lane l feeds entry / cout l % 32 with
@@ -1631,18 +1624,49 @@ __global__ __launch_bounds__(256) void k_conv_tf(EdgeBatch eb) {
                 f32x16 acc;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-                for (int c0 = 0; c0 < e.Cin; c0 += 16) {
-                    const f16x8 a = *reinterpret_cast<const f16x8*>(arow + c0);
-                    f16x8 b = *reinterpret_cast<const f16x8*>(brow + c0);
-                    if (!act)
+                int c0 = 0;
+                for (; c0 + 64 <= e.Cin; c0 += 64) {           // four steps' operands are requested together
+                    f16x8 a4[4], b4[4];
 #pragma unroll
-                        for (int i = 0; i < 8; ++i) b[i] = (f16)0.f;
+                    for (int q = 0; q < 4; ++q) {
+                        a4[q] = *reinterpret_cast<const f16x8*>(arow + c0 + 16 * q);
+                        b4[q] = *reinterpret_cast<const f16x8*>(brow + c0 + 16 * q);
+                    }
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a4[q], b4[q], acc, 0, 0, 0);
+                }
+                for (; c0 < e.Cin; c0 += 16) {
+                    const f16x8 a = *reinterpret_cast<const f16x8*>(arow + c0);
+                    const f16x8 b = *reinterpret_cast<const f16x8*>(brow + c0);
                     acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc, 0, 0, 0);
                 }
-                if (act) {
+                if (act) {                                   // (a dead column multiplied entry 0's row: dropped here)
+                    const int p1 = s_dst[ent];
+                    const int vy = p1 / e.dW, vx = p1 - vy * e.dW;
+                    f16* Ap = (f16*)A + ((size_t)wrapc(e.d_aoy + vy, e.dH) * e.dW + wrapc(e.d_aox + vx, e.dW)) * e.Cout + ca * 32 + 4 * kh;
+                    f16* Dp = (f16*)D + (size_t)p1 * e.Cout + ca * 32 + 4 * kh;
+                    const bool fresh = s_new[ent] != 0;
+                    f16x4 av[4];
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) av[g] = *reinterpret_cast<const f16x4*>(Ap + 8 * g);
                     bool any = false;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) finish(ent, ca * 32 + 8 * (r / 4) + 4 * kh + r % 4, acc[r], any);
+                    for (int g = 0; g < 4; ++g) {
+                        f16x4 na, dv;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float a = fresh ? 0.f : (float)av[g][i];
+                            const float b = fresh && bias ? (float)(f16)bias[ca * 32 + 8 * g + 4 * kh + i] : 0.f;
+                            const float t = (float)(f16)(b + acc[4 * g + i]);      // as the pending ring would hold it
+                            const float sum = a + t;
+                            const float out = e.s_relu ? fmaxf(sum, 0.f) - fmaxf(a, 0.f) : sum - a;
+                            na[i] = (f16)sum;
+                            dv[i] = (f16)out;
+                            any |= out != 0.f;
+                        }
+                        *reinterpret_cast<f16x4*>(Ap + 8 * g) = na;
+                        *reinterpret_cast<f16x4*>(Dp + 8 * g) = dv;
+                    }
                     if (any) atomicOr(&s_any[ent], 1u);        // an OR: the order does not matter
                 }
             }
@@ -1653,13 +1677,22 @@ __global__ __launch_bounds__(256) void k_conv_tf(EdgeBatch eb) {
                 const T* wrow = w + (size_t)co * e.Cin;
                 float y = 0.f;
                 for (int ci = 0; ci < e.Cin; ++ci) y = fmaf((float)drow[ci], (float)wrow[ci], y);
-                bool any = false;
-                finish(ent, co, y, any);
-                if (any) atomicOr(&s_any[ent], 1u);
+                const int p1 = s_dst[ent];
+                const int vy = p1 / e.dW, vx = p1 - vy * e.dW;
+                const size_t aoff = ((size_t)wrapc(e.d_aoy + vy, e.dH) * e.dW + wrapc(e.d_aox + vx, e.dW)) * e.Cout + co;
+                const bool fresh = s_new[ent] != 0;
+                const float a = fresh ? 0.f : (float)A[aoff];
+                const float b = fresh && bias ? (float)(T)bias[co] : 0.f;
+                const float t = (float)(T)(b + y);          // as the pending ring would hold it
+                const float sum = a + t;
+                const float out = e.s_relu ? fmaxf(sum, 0.f) - fmaxf(a, 0.f) : sum - a;
+                A[aoff] = (T)sum;
+                D[(size_t)p1 * e.Cout + co] = (T)out;
+                if (out != 0.f) atomicOr(&s_any[ent], 1u);     // an OR: the order does not matter
             }
         }
         __syncthreads();
-        if (p < n) e.dflags[p] = (uint8_t)(has ? ((((fl & kFlagN) || s_any[off]) ? kFlagM : 0) | kFlagC) : 0);
+        if (own && p < n) e.dflags[p] = (uint8_t)(has ? ((((fl & kFlagN) || s_any[rank]) ? kFlagM : 0) | kFlagC) : 0);
     }
     if (tid == 0) add_macs(e, block_taps, MFMA ? 0 : 1);    // statistics: one atomic per block
 }
@@ -1906,7 +1939,7 @@ hipError_t launch_conv(const EdgeBatch& eb, int nb, int dtype, int conv_path, hi
     if (e.op == kOpTruncFree) {
         const bool mfma = dtype == MDCNN_F16 && conv_path != 1 && e.Cin % 16 == 0 && e.Cout % 32 == 0;
         *cls = mfma ? kClsConvMfma : kClsConvPlain;
-        const unsigned g = cap_blocks(((long long)e.dH * e.dW + kSegPixels - 1) / kSegPixels, 4096);
+        const unsigned g = cap_blocks((((long long)e.dH * e.dW + kSegPixels - 1) / kSegPixels) * (kSegPixels / kTfTile), 8192);
         if (mfma) k_conv_tf<f16, true><<<dim3(g, 1, nb), dim3(256), 0, st>>>(eb);
         else if (dtype == MDCNN_F16) k_conv_tf<f16, false><<<dim3(g, 1, nb), dim3(256), 0, st>>>(eb);
         else k_conv_tf<float, false><<<dim3(g, 1, nb), dim3(256), 0, st>>>(eb);

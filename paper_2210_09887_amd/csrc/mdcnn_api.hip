@@ -30,7 +30,8 @@ int g_pipe_threads = 1;   // mdcnn_frames: one issuing host thread per stream (m
 
 // Profiling mode: every kernel launch is bracketed by a pair of events on its
 // own stream; mdcnn_profile_read waits for them and sums the times per class.
-struct TimedLaunch { int cls; hipEvent_t start, stop; };
+struct TimedLaunch { int cls; hipEvent_t start, stop; int site, edge; };
+thread_local int g_tag_site = -1, g_tag_edge0 = -1;   // the forward call being issued (profiling mode: tags of its launches)
 std::vector<TimedLaunch> g_timed;
 std::vector<hipEvent_t> g_event_pool;
 
@@ -44,7 +45,7 @@ hipEvent_t take_event() {
 template <typename F>
 hipError_t timed(int cls, hipStream_t st, F&& launch) {
     if (!g_profile) return launch();
-    TimedLaunch t{cls, take_event(), take_event()};
+    TimedLaunch t{cls, take_event(), take_event(), g_tag_site, -1};
     if (!t.start || !t.stop) return hipErrorOutOfMemory;
     (void)hipEventRecord(t.start, st);
     hipError_t err = launch();
@@ -377,7 +378,7 @@ mdcnn_status do_forward(int n, mdcnn_buffer* const* ins, const void* const* fram
         if (sc) st = sc->begin();
         struct AtExit { Sched* sc; ~AtExit() { if (sc) sc->end(); } } at_exit{sc};
         int cls = kClsConvPlain;
-        TimedLaunch t{0, nullptr, nullptr};
+        TimedLaunch t{0, nullptr, nullptr, g_tag_site, idx >= 0 && g_tag_edge0 >= 0 ? g_tag_edge0 + idx : -1};
         if (g_profile) {              // the class is known only after dispatch: record around, file under it
             t.start = take_event();
             t.stop = take_event();
@@ -745,7 +746,9 @@ mdcnn_status frame_batch(mdcnn_net* const* nets, int n, const void* const* frame
         // order of the producers of its destination stays the same as long as no other
         // edge of this call goes to the same destination before it
         const int fuse = fused_skip(net, e0, e1);
+        g_tag_site = i; g_tag_edge0 = e0;
         mdcnn_status rc = do_forward(n, ins, i == 0 ? frames : nullptr, i == 0 ? forced : nullptr, edges, outs, ne, st, fuse, sc);
+        g_tag_site = g_tag_edge0 = -1;
         if (rc) return rc;
         e0 = e1;
     }
@@ -1044,8 +1047,10 @@ mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, 
                 mdcnn_buffer* const* outs = outs_flat.data();
                 const void* X = frames[f];
                 const uint8_t* fm = fe ? fe->masks[f] : forced ? forced[f] : nullptr;
+                g_tag_site = i; g_tag_edge0 = e0;
                 mdcnn_status rc = do_forward(1, &in, i == 0 ? &X : nullptr, i == 0 ? &fm : nullptr, &edges, &outs, ne, st,
                                              fused_skip(net, e0, e1), nullptr, jobs, riders, n_riders);
+                g_tag_site = g_tag_edge0 = -1;
                 if (rc) return rc;
                 if (issued(c) != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: event: %s", f, hipGetErrorString(err));
             }
@@ -1145,6 +1150,43 @@ mdcnn_status mdcnn_profile_read(int n_classes, double* ms, long long* launches) 
     }
     g_timed.clear();
     return rc;
+}
+
+mdcnn_status mdcnn_profile_read_launches(int cap, int* cls, int* site, int* edge, float* us, int* n) {
+    if (!cls || !site || !edge || !us || !n) return fail(MDCNN_ERR_NULL, "profile_read_launches: NULL argument");
+    *n = (int)g_timed.size();
+    if ((int)g_timed.size() > cap) return fail(MDCNN_ERR_SIZE, "profile_read_launches: %zu launches, room for %d", g_timed.size(), cap);
+    mdcnn_status rc = MDCNN_OK;
+    int k = 0;
+    for (TimedLaunch& t : g_timed) {
+        float dt = 0.f;
+        hipError_t err = hipEventSynchronize(t.stop);
+        if (err == hipSuccess) err = hipEventElapsedTime(&dt, t.start, t.stop);
+        if (err != hipSuccess) rc = fail(MDCNN_ERR_HIP, "profiling event: %s", hipGetErrorString(err));
+        cls[k] = t.cls; site[k] = t.site; edge[k] = t.edge; us[k] = 1e3f * dt;
+        ++k;
+        g_event_pool.push_back(t.start);
+        g_event_pool.push_back(t.stop);
+    }
+    g_timed.clear();
+    return rc;
+}
+
+mdcnn_status mdcnn_bench_copy(const void* src_dev, void* dst_dev, size_t bytes, void* stream) {
+    if (!src_dev || !dst_dev) return fail(MDCNN_ERR_NULL, "bench_copy: NULL argument");
+    if (((uintptr_t)src_dev | (uintptr_t)dst_dev | bytes) & 15) return fail(MDCNN_ERR_ALIGN, "bench_copy: pointers and size must be multiples of 16");
+    const hipError_t err = launch_bench_copy(src_dev, dst_dev, bytes, (hipStream_t)stream);
+    if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "bench_copy launch: %s", hipGetErrorString(err));
+    return MDCNN_OK;
+}
+
+mdcnn_status mdcnn_bench_mfma(int iters, int blocks, float* sink_dev, void* stream, double* flops) {
+    if (!sink_dev) return fail(MDCNN_ERR_NULL, "bench_mfma: sink is NULL");
+    if (iters < 1 || iters > (1 << 24) || blocks < 1 || blocks > 65536) return fail(MDCNN_ERR_SIZE, "bench_mfma: iters or blocks out of range");
+    const hipError_t err = launch_bench_mfma(sink_dev, iters, blocks, (hipStream_t)stream);
+    if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "bench_mfma launch: %s", hipGetErrorString(err));
+    if (flops) *flops = (double)blocks * 4.0 * (double)iters * 4.0 * 2.0 * 32.0 * 32.0 * 16.0;
+    return MDCNN_OK;
 }
 
 mdcnn_status mdcnn_pack_weights(const mdcnn_conv_desc* edge, int dtype, void* dst_dev, size_t dst_bytes, void* stream) {
