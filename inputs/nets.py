@@ -160,12 +160,13 @@ def _cnn5(rng, H=256, W=256) -> NetSpec:
     return net
 
 
-def _resnet18(rng, H=512, W=512, widths=(64, 128, 256, 512), pool_stem=False) -> NetSpec:
+def _resnet18(rng, H=512, W=512, widths=(64, 128, 256, 512), pool_stem=False, bn_scale=True) -> NetSpec:
     """3x3 stem with stride 2, then four stages of two basic blocks each, stage
     strides 1/2/2/1 (total stride 8), 1x1 projection wherever the shape changes.
     The second conv of every block carries a folded batch-norm scale of 0.5 so
-    that activations stay O(1) in fp16 storage.  pool_stem: the usual ResNet stem,
-    a 3x3 stride-2 max pooling after the stem convolution (total stride 16)."""
+    that activations stay O(1) in fp16 storage (bn_scale=False: plain He-normal weights
+    everywhere, the variant the tolerance study compares with).  pool_stem: the usual ResNet
+    stem, a 3x3 stride-2 max pooling after the stem convolution (total stride 16)."""
     net = NetSpec(CONFIG_NAMES[3] + ("_poolstem" if pool_stem else ""), "f16", H, W, 16 if pool_stem else 8)
     b = _Builder(net, rng, bias_amp=0.1)
     th_in, th = 0.02, 0.01
@@ -181,12 +182,12 @@ def _resnet18(rng, H=512, W=512, widths=(64, 128, 256, 512), pool_stem=False) ->
         for bi in range(2):
             last = si == 3 and bi == 1
             s = b.basic_block(s, C, st if bi == 0 else 1, th, f"s{si + 1}b{bi}",
-                              out_kind="output" if last else "preact")
+                              out_kind="output" if last else "preact", branch_gain=0.5 if bn_scale else 1.0)
     _sort_edges(net)
     return net
 
 
-def _hrnet(rng, H=384, W=288, widths=(32, 64, 128, 256), blocks=4) -> NetSpec:
+def _hrnet(rng, H=384, W=288, widths=(32, 64, 128, 256), blocks=4, bn_scale=True) -> NetSpec:
     """Two stride-2 3x3 stem convs, then three multi-resolution stages with
     2/3/4 parallel branches of `blocks` basic blocks each.  After every stage all
     branches are fused all-to-all: higher -> lower resolution through chains of
@@ -195,7 +196,9 @@ def _hrnet(rng, H=384, W=288, widths=(32, 64, 128, 256), blocks=4) -> NetSpec:
     lowest-resolution branch with a 3x3 stride-2 conv.  The network output is
     the fused highest-resolution branch of the last stage.  Total stride 32.
     Folded batch-norm scales (0.25 on the second conv of every block, 0.35 on
-    the fusion convs) keep the activations within a few units in fp16."""
+    the fusion convs) keep the activations within a few units in fp16; bn_scale=False
+    leaves all weights plain He-normal."""
+    g_block, g_fuse = (0.25, 0.35) if bn_scale else (1.0, 1.0)
     net = NetSpec(CONFIG_NAMES[4], "f16", H, W, 32)
     b = _Builder(net, rng, bias_amp=0.1)
     th = 0.015
@@ -211,7 +214,7 @@ def _hrnet(rng, H=384, W=288, widths=(32, 64, 128, 256), blocks=4) -> NetSpec:
         nb = len(br)
         for j in range(nb):
             for k in range(blocks):
-                br[j] = b.basic_block(br[j], widths[j], 1, th, f"st{stage}.b{j}.blk{k}", branch_gain=0.25)
+                br[j] = b.basic_block(br[j], widths[j], 1, th, f"st{stage}.b{j}.blk{k}", branch_gain=g_block)
         last_stage = stage == 4
         outs = [0] if last_stage else list(range(nb))
         fused = []
@@ -223,7 +226,7 @@ def _hrnet(rng, H=384, W=288, widths=(32, 64, 128, 256), blocks=4) -> NetSpec:
                 if j == i:
                     b.identity(br[j], fused[oi])
                 elif j > i:
-                    b.conv(br[j], fused[oi], 1, 1, pad=0, up=j - i, gain=0.35)
+                    b.conv(br[j], fused[oi], 1, 1, pad=0, up=j - i, gain=g_fuse)
                 else:
                     cur = br[j]
                     for step in range(i - j - 1):
@@ -231,7 +234,7 @@ def _hrnet(rng, H=384, W=288, widths=(32, 64, 128, 256), blocks=4) -> NetSpec:
                                      net.sites[cur].stride * 2, theta=th)
                         b.conv(cur, nxt, 3, 2)
                         cur = nxt
-                    b.conv(cur, fused[oi], 3, 2, gain=0.35)
+                    b.conv(cur, fused[oi], 3, 2, gain=g_fuse)
         if last_stage:
             br = fused
         else:

@@ -259,9 +259,10 @@ class Follower:
         within 4 x tolerance of theta -- a wrong mask far from the threshold fails;
       * the outputs at the tight tolerance (the masks agree by construction)."""
 
-    def __init__(self, net, origins=None):
+    def __init__(self, net, origins=None, tol=None):
+        """tol: the fp tolerance (default: the absolute one of the storage type)."""
         self.net, self.o = net, OracleNet(net, origins)
-        self.tol = TOL[net.dtype]
+        self.tol = TOL[net.dtype] if tol is None else tol
         self.band = 4 * self.tol
         self.inner = [i for i, s in enumerate(net.sites) if s.kind != "output"]
         self.out_err, self.flips, self.decisions, self.worst = 0.0, 0, 0, 0.0
@@ -302,9 +303,9 @@ def gpu_masks(g, inner):
     return {i: (g.read(i, B.MDCNN_VIEW_FLAGS) & B.FLAG_M) != 0 for i in inner}
 
 
-def followed(net, frames, shifts, forced=None, origins=None, log=None):
+def followed(net, frames, shifts, forced=None, origins=None, log=None, tol=None):
     """mdcnn_frame end to end with a Follower.  Returns dict(out_err, flips, decisions, worst_margin)."""
-    f = Follower(net, origins)
+    f = Follower(net, origins, tol)
     g = GpuNet(net, origins)
     try:
         for t, X in enumerate(frames):

@@ -160,6 +160,43 @@ def test_config4_full_hrnet_followed():
     assert r["flips"] < 0.02 * r["decisions"] and r["worst_margin"] < H.TOL[net.dtype] / 4      # seen: below 1e-3
 
 
+def ulp16(v):
+    """Spacing of fp16 values at magnitude v."""
+    return float(2.0 ** (np.floor(np.log2(max(float(v), 2.0 ** -14))) - 10))
+
+
+@pytest.mark.parametrize("cfg", [3, 4])
+def test_plain_he_normal_weights_relative_tolerance(cfg):
+    """The benchmark networks carry folded batch-norm scales on some convolutions so that fp16 activations stay within a
+    few units and the absolute tolerance of 2e-2 means something.  This is the same workload with plain He-normal
+    weights everywhere: the activations grow (printed per network), one fp16 spacing at their magnitude exceeds 2e-2,
+    and the GPU must agree with the oracle within five such spacings (what 2e-2 is for values between 4 and 8) - the
+    guard band of the mask decisions scales with it."""
+    import gpu_harness as H
+    from oracle.mdcnn_oracle import OracleNet
+    net = build_net(cfg, bn_scale=False)
+    scaled = build_net(cfg)
+    if cfg == 3:
+        seq = build_sequence(3, n_frames=3)
+        frames, shifts = seq.frames, seq.shifts
+    else:
+        frames, shifts = config4_frames_with_a_pan(0)
+    ranges = {}
+    for name, nn in (("scaled", scaled), ("he_normal", net)):
+        o = OracleNet(nn)
+        out, _ = o.frame(frames[0], 0, 0)
+        acts = [float(np.abs(s.get_A().astype(np.float32)).max()) for s in o.sites if s.spec.kind == "preact"]
+        ranges[name] = (max(acts), float(np.abs(out[0].astype(np.float32)).max()))
+        log(f"config {cfg} {name}: max |pre-activation| over the sites {max(acts):.1f}, max |output| {ranges[name][1]:.1f}, "
+            f"fp16 spacing there {ulp16(max(acts)):.4f}")
+    vmax = ranges["he_normal"][0]
+    tol = max(H.TOL["f16"], 5 * ulp16(vmax))       # 2e-2 is five fp16 spacings at the scaled networks' magnitude (4 <= |v| < 8)
+    r = H.followed(net, frames, shifts, log=log, tol=tol)
+    log(f"config {cfg} plain He-normal: tolerance {tol:.4f} (five fp16 spacings at {vmax:.1f}); output error {r['out_err']:.4f} = "
+        f"{r['out_err'] / ulp16(vmax):.2f} spacings; decisions off the oracle's {r['flips']} of {r['decisions']}, worst margin {r['worst_margin']:.4f}")
+    assert ranges["scaled"][0] < 16 and r["out_err"] < tol
+
+
 @pytest.mark.parametrize("density", [0.01, 0.05, 0.2, 0.5, 1.0])
 def test_config5_full_density(density):
     import gpu_harness as H
