@@ -60,6 +60,9 @@ def parse():
     ap.add_argument("--reps", type=int, default=5, help="repetitions of the timed region; the median is reported")
     ap.add_argument("--dense", action="store_true", help="library dense mode: threshold 0 and all pixels forced")
     ap.add_argument("--no-dense-leg", action="store_true", help="skip the dense-mode leg of the default run")
+    ap.add_argument("--f32-storage", action="store_true",
+                    help="the same network and frames with fp32 storage instead of fp16 (what the storage type costs or buys; "
+                         "its wide layers have no matrix-core kernel and run as plain FMA)")
     ap.add_argument("--truncation-free", action="store_true",
                     help="sites after a 1x1 convolution keep no pending ring and never truncate (config 5: one of its three inner sites)")
     ap.add_argument("--pool-stem", action="store_true",
@@ -448,6 +451,12 @@ def main():
     if a.truncation_free:
         truncation_free(net)
     seq = build_sequence(cfg, **({"density": a.density} if cfg == 5 else {"tile": 16} if a.pool_stem and cfg == 3 else {}))
+    if a.f32_storage and net.dtype == "f16":
+        net.dtype = "f32"
+        for e in net.edges:
+            if e.w is not None:
+                e.w = e.w.astype(np.float32)
+        seq.frames = seq.frames.astype(np.float32)
     if a.dense:
         for s in net.sites:
             s.theta = 0.0
@@ -573,6 +582,7 @@ def main():
                                + (", max-pooling stem" if a.pool_stem and cfg == 3 else "")
                                + (f", frames cropped to a wandering box of {crops[1][2]}x{crops[1][3]} of {net.H // net.total_stride}x{net.W // net.total_stride} tiles" if crops is not None else "")
                                + (", library dense mode" if a.dense else "")
+                               + (", fp32 storage" if a.f32_storage else "")
                                + (", truncation-free sites: " + ",".join(s.name for s in net.sites if s.trunc_free) if a.truncation_free else "")
                                + (f", density {a.density}" if cfg == 5 else ""),
                    "input": [net.H, net.W, net.sites[0].C], "sites": len(net.sites), "edges": len(net.edges),
@@ -640,6 +650,11 @@ def main():
         dnet = build_net(cfg, **net_kw)
         for s in dnet.sites:
             s.theta = 0.0
+        if a.f32_storage and dnet.dtype == "f16":
+            dnet.dtype = "f32"
+            for e in dnet.edges:
+                if e.w is not None:
+                    e.w = e.w.astype(np.float32)
         dw = Workload(a, dnet, seq, forced_all_ones=True)
         r1 = dw.timed(dw.run_frames if dw.in_flight > 1 else dw.one_by_one, 1)
         dm = {"value": round(a.steps / r1[0][0], 2), "unit": "frames/s", "frames_in_flight": dw.in_flight,

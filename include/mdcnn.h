@@ -254,7 +254,8 @@ mdcnn_status mdcnn_frame_plan(mdcnn_net* net, int streams, int* stream_of, int* 
  * is nets[b]: all nets must have the same topology and the same site and edge
  * shapes, each its own buffers (weights may be shared); they keep their own
  * camera paths, masks and reset decisions.  All arrays are host arrays of
- * n_streams entries (1 <= n_streams <= 16); frames_dev[b] / outs_dev[b] as in
+ * n_streams entries (1 <= n_streams <= 128; the streams share their launches in
+ * groups of 16, group after group); frames_dev[b] / outs_dev[b] as in
  * mdcnn_frame, out_bytes per stream; forced_masks_dev may be NULL or hold NULL
  * entries; did_full_reset: n_streams ints or NULL.  The results of every stream
  * are identical, bit for bit, to those of mdcnn_frame on it alone.

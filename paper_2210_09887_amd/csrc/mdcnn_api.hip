@@ -308,6 +308,7 @@ mdcnn_status validate_forward(const mdcnn_buffer* in, const void* frame, const u
 // Streams and events of one multi-stream frame.  Every wait is on an event that was recorded
 // earlier in the same call, so no stream can wait for something that never happens.
 constexpr int kMaxStreams = 4;
+constexpr int kMaxBatchStreams = 128;     // streams of one mdcnn_frame_batch call (kMaxBatch to a launch)
 struct Sched {
     const Plan* plan = nullptr;
     hipStream_t s[kMaxStreams] = {};
@@ -1403,8 +1404,8 @@ mdcnn_status mdcnn_frame_batch(mdcnn_net* const* nets, int n_streams, const void
                                const uint8_t* const* forced_masks_dev, const int* dty, const int* dtx,
                                void* const* outs_dev, size_t out_bytes, void* stream, int* did_full_reset) {
     if (!nets || !frames_dev || !dty || !dtx || !outs_dev) return fail(MDCNN_ERR_NULL, "frame_batch: NULL argument");
-    if (n_streams < 1 || n_streams > kMaxBatch) return fail(MDCNN_ERR_SIZE, "frame_batch: 1 <= n_streams <= %d", kMaxBatch);
-    const uint8_t* no_forced[kMaxBatch] = {};
+    if (n_streams < 1 || n_streams > kMaxBatchStreams) return fail(MDCNN_ERR_SIZE, "frame_batch: 1 <= n_streams <= %d", kMaxBatchStreams);
+    const uint8_t* no_forced[kMaxBatchStreams] = {};
     for (int b = 0; b < n_streams; ++b) {
         if (!nets[b] || !frames_dev[b] || !outs_dev[b]) return fail(MDCNN_ERR_NULL, "frame_batch: stream %d: net/frame/out is NULL", b);
         if (((uintptr_t)frames_dev[b] | (uintptr_t)outs_dev[b]) & 15) return fail(MDCNN_ERR_ALIGN, "frame_batch: stream %d: frame/out must be 16-byte aligned", b);
@@ -1415,7 +1416,16 @@ mdcnn_status mdcnn_frame_batch(mdcnn_net* const* nets, int n_streams, const void
             if (nets[c] == nets[b] || nets[c]->sites[0] == nets[b]->sites[0])
                 return fail(MDCNN_ERR_STATE, "frame_batch: streams %d and %d share a network or buffers", c, b);
     }
-    return frame_batch(nets, n_streams, frames_dev, forced_masks_dev ? forced_masks_dev : no_forced, dty, dtx, outs_dev, stream, did_full_reset);
+    // the descriptors of a launch travel as kernel arguments, kMaxBatch streams to a launch: larger batches go in
+    // groups of that many, one group after the other on the caller's stream (the streams are independent)
+    if (!forced_masks_dev) forced_masks_dev = no_forced;
+    for (int b0 = 0; b0 < n_streams; b0 += kMaxBatch) {
+        const int nb = n_streams - b0 < kMaxBatch ? n_streams - b0 : kMaxBatch;
+        const mdcnn_status rc = frame_batch(nets + b0, nb, frames_dev + b0, forced_masks_dev + b0, dty + b0, dtx + b0, outs_dev + b0, stream,
+                                            did_full_reset ? did_full_reset + b0 : nullptr);
+        if (rc) return rc;
+    }
+    return MDCNN_OK;
 }
 
 // Checks shared by mdcnn_frames and mdcnn_frames_crop; out_bytes[f] (crops) or out_bytes[0] (none) per frame.

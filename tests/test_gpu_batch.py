@@ -90,6 +90,35 @@ def test_batch_against_per_stream_oracles(name):
         assert r["flips"] <= 0.02 * r["decisions"] and r["worst_margin"] < H.TOL[net.dtype] / 4     # seen: below 1e-3
 
 
+def test_batch_of_more_streams_than_one_launch_carries():
+    """37 streams (the paper's batches go to 66): the library splits them into groups that share launches; every stream
+    still equals its single run bit for bit, with its own frames, camera path and resets."""
+    import gpu_harness as H
+    from paper_2210_09887_amd.runtime import GpuBatch, GpuNet
+    net, seq = load_case("c3_resnet_plain_80x112")
+    n, T = 37, 4
+    rng = np.random.default_rng(5)
+    start = [int(rng.integers(0, len(seq.frames) - T + 1)) for _ in range(n)]
+    path = [[(0, 0)] + [(int(rng.integers(-1, 2)), int(rng.integers(-1, 2))) for _ in range(T - 1)] for _ in range(n)]
+    want = {}
+    for b in range(0, n, 6):                                # every sixth stream is checked against its single run
+        g = GpuNet(net)
+        try:
+            want[b] = [(lambda o, r: (o.cpu().numpy().copy(), r))(*g.frame(H.dev(seq.frames[start[b] + t]), *path[b][t])) for t in range(T)]
+        finally:
+            g.close()
+    gb = GpuBatch(net, n)
+    try:
+        for t in range(T):
+            outs, rs = gb.frame([H.dev(seq.frames[start[b] + t]) for b in range(n)], [path[b][t][0] for b in range(n)],
+                                [path[b][t][1] for b in range(n)])
+            torch.cuda.synchronize()
+            for b in want:
+                assert rs[b] == want[b][t][1] and np.array_equal(outs[b].cpu().numpy(), want[b][t][0]), f"frame {t} stream {b}"
+    finally:
+        gb.close()
+
+
 def test_batch_with_max_pooling():
     """The pooling kernel in a batch: streams with different camera paths equal their single runs."""
     import gpu_harness as H
@@ -132,7 +161,7 @@ def test_batch_argument_checks():
         with pytest.raises(B.MdcnnError):              # different networks
             B.mdcnn_frame_batch([nets[0], other.net], [X.data_ptr()] * 2, None, [0, 0], [0, 0], outs, nbytes)
         with pytest.raises(B.MdcnnError):              # too many streams
-            B.mdcnn_frame_batch(nets * 9, [X.data_ptr()] * 18, None, [0] * 18, [0] * 18, outs * 9, nbytes)
+            B.mdcnn_frame_batch(nets * 65, [X.data_ptr()] * 130, None, [0] * 130, [0] * 130, outs * 65, nbytes)
     finally:
         other.close()
         gb.close()
