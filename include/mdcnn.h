@@ -207,6 +207,26 @@ mdcnn_status mdcnn_layer_forward(mdcnn_buffer* in, const void* frame_dev,
                                  const mdcnn_conv_desc* edges, mdcnn_buffer* const* outs,
                                  int n_edges, void* stream);
 
+/* mdcnn_layer_forward for callers that cannot allocate device memory - code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc - and that created their sites from memory they
+ * may not grow: the by-products of the call that only the library itself uses, i.e. the compacted list L
+ * of `in`, the compute lists of the destinations and their per-segment counts and running sums, are
+ * written to a buffer the library holds in a file-scope device array of 2 MiB (one per GPU the library
+ * runs on, kept until the process ends) instead of the sites' own list regions.  Everything else - A, P,
+ * delta maps, flags, the per-site counters of multiply-accumulates - is what mdcnn_layer_forward
+ * produces, bit for bit; MDCNN_VIEW_LIST / MDCNN_VIEW_CLIST and the update / candidate / compute-list
+ * entries of MDCNN_VIEW_STATS of the sites involved are NOT updated by this call.  The call allocates
+ * nothing (no hipMalloc, no hipFree, no allocating library routine) and clears the part of the array it
+ * uses with a fill kernel on `stream`.  All calls on one GPU share that array: calls that overlap in time
+ * on one GPU (different streams or host threads) race.
+ * Errors: those of mdcnn_layer_forward; MDCNN_ERR_SIZE if the lists of the call need more than the
+ * 2 MiB (4 bytes per pixel of `in` and per padded-window pixel of every destination, plus 24 bytes per
+ * 256 of them); MDCNN_ERR_HIP if the address of the array cannot be looked up. */
+mdcnn_status mdcnn_layer_forward_noalloc(mdcnn_buffer* in, const void* frame_dev,
+                                         const uint8_t* forced_mask_dev,
+                                         const mdcnn_conv_desc* edges, mdcnn_buffer* const* outs,
+                                         int n_edges, void* stream);
+
 /* Network = sites in topological order + edges (edge i: sites[edge_src[i]] ->
  * sites[edge_dst[i]], edge_src non-decreasing).  Topology only; holds no device
  * memory.  Site 0 must be the only INPUT site. */

@@ -29,7 +29,7 @@ STATUS_NAMES = {0: "OK", 1: "ERR_NULL", 2: "ERR_SHAPE", 3: "ERR_DTYPE", 4: "ERR_
                 5: "ERR_SIZE", 6: "ERR_STATE", 7: "ERR_HIP"}
 
 EXPORTS = ["mdcnn_conv_border", "mdcnn_buffer_bytes", "mdcnn_create_buffer", "mdcnn_destroy_buffer",
-           "mdcnn_shift_camera", "mdcnn_set_crop", "mdcnn_layer_forward", "mdcnn_net_create", "mdcnn_net_destroy",
+           "mdcnn_shift_camera", "mdcnn_set_crop", "mdcnn_layer_forward", "mdcnn_layer_forward_noalloc", "mdcnn_net_create", "mdcnn_net_destroy",
            "mdcnn_frame", "mdcnn_frame_crop", "mdcnn_frame_batch", "mdcnn_frame_plan", "mdcnn_frames", "mdcnn_frames_crop", "mdcnn_frames_masked", "mdcnn_frames_plan", "mdcnn_input_mask", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read", "mdcnn_profile_read_launches", "mdcnn_bench_copy", "mdcnn_bench_mfma",
            "mdcnn_pack_weights", "mdcnn_last_error", "mdcnn_version"]
 
@@ -76,6 +76,7 @@ def lib():
         L.mdcnn_set_crop.argtypes = [C.POINTER(vp), C.c_int] + [C.c_int] * 4
         L.mdcnn_frame_crop.argtypes = [vp, vp, vp] + [C.c_int] * 6 + [vp, sz, vp, ip]
         L.mdcnn_layer_forward.argtypes = [vp, vp, vp, C.POINTER(mdcnn_conv_desc), C.POINTER(vp), C.c_int, vp]
+        L.mdcnn_layer_forward_noalloc.argtypes = [vp, vp, vp, C.POINTER(mdcnn_conv_desc), C.POINTER(vp), C.c_int, vp]
         L.mdcnn_net_create.argtypes = [C.POINTER(vp), C.c_int, ip, ip, C.POINTER(mdcnn_conv_desc), C.c_int,
                                        C.POINTER(vp)]
         L.mdcnn_net_destroy.argtypes = [vp]
@@ -190,6 +191,12 @@ def mdcnn_layer_forward(buf: int, frame_ptr, forced_ptr, edges, outs, stream: in
     n = len(edges)
     arr = (mdcnn_conv_desc * max(n, 1))(*edges)
     _check(lib().mdcnn_layer_forward(buf, frame_ptr, forced_ptr, arr, _handles(outs) if n else None, n, stream))
+
+
+def mdcnn_layer_forward_noalloc(buf: int, frame_ptr, forced_ptr, edges, outs, stream: int = 0):
+    n = len(edges)
+    arr = (mdcnn_conv_desc * max(n, 1))(*edges)
+    _check(lib().mdcnn_layer_forward_noalloc(buf, frame_ptr, forced_ptr, arr, _handles(outs) if n else None, n, stream))
 
 
 def mdcnn_net_create(sites, edge_src, edge_dst, edges) -> int:

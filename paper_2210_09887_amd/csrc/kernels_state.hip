@@ -720,6 +720,19 @@ __global__ __launch_bounds__(256) void k_copy_bytes(const uint8_t* __restrict__ 
     for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += step) dst[i] = src[i];
 }
 
+__global__ __launch_bounds__(256) void k_zero_bytes(uint4* __restrict__ dst, size_t n16) {
+    const size_t step = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += step) dst[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+hipError_t launch_zero_bytes(void* dst, size_t bytes, hipStream_t st) {
+    if (bytes == 0) return hipSuccess;
+    const size_t n16 = bytes / 16;
+    const size_t blocks = (n16 + 255) / 256;
+    k_zero_bytes<<<dim3((unsigned)(blocks > 1024 ? 1024 : blocks)), dim3(256), 0, st>>>((uint4*)dst, n16);
+    return hipGetLastError();
+}
+
 static unsigned grid_for(long long total) {
     long long b = (total + 255) / 256;
     if (b < 1) b = 1;

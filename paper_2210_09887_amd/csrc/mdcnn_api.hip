@@ -7,6 +7,7 @@
 
 #include <algorithm>
 #include <atomic>
+#include <mutex>
 #include <new>
 #include <string>
 #include <thread>
@@ -124,6 +125,13 @@ void make_layout(const mdcnn_buffer_desc& d, Layout& L) {
 }
 
 }  // namespace
+
+// By-products of a forward call - the compacted list of the source site, the compute lists of the destinations and
+// their per-segment counts - for the entry point that keeps them out of the sites' memory (mdcnn_layer_forward_noalloc).
+// The name of the array is a host-side stand-in: the address the kernels get comes from hipGetSymbolAddress, once per device.
+// (No `used` attribute here: with it the compiler keeps the symbol local to the code object and the runtime cannot look it up.)
+constexpr size_t kScratchBytes = (size_t)2 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 struct mdcnn_buffer {
     mdcnn_buffer_desc d;
@@ -335,10 +343,16 @@ struct Sched {
 
 hipError_t launch_fill_jobs(const FillJob* jobs, const int* which, int count, hipStream_t st);
 
+// Where the by-products of a forward call go instead of the sites' own list regions (n == 1 only).
+struct ListScratch {
+    int* list; int* lcnt; unsigned long long* lacc;                          // of the source site
+    std::vector<int*> clist, ccnt; std::vector<unsigned long long*> cacc;    // per edge
+};
+
 mdcnn_status do_forward(int n, mdcnn_buffer* const* ins, const void* const* frames, const uint8_t* const* forced,
                         const mdcnn_conv_desc* const* edges, mdcnn_buffer* const* const* outs, int n_edges,
                         hipStream_t st, int fuse_skip = -1, Sched* sc = nullptr, const FillJob* jobs = nullptr,
-                        const int* riders = nullptr, int n_riders = 0) {
+                        const int* riders = nullptr, int n_riders = 0, const ListScratch* ls = nullptr) {
     static thread_local Step1Batch sb;                     // 3.4 KiB each: kept off the stack
     static thread_local EdgeBatch eb;
     for (int b = 0; b < n; ++b) {
@@ -397,6 +411,7 @@ mdcnn_status do_forward(int n, mdcnn_buffer* const* ins, const void* const* fram
     };
     auto with_source_list = [&](EdgeDev& e, const mdcnn_buffer* in) {
         e.pub_list = in->dev.list; e.pub_lcnt = in->dev.lcnt; e.pub_lacc = in->dev.lacc;
+        if (ls) { e.pub_list = ls->list; e.pub_lcnt = ls->lcnt; e.pub_lacc = ls->lacc; }
     };
     if (n_edges == 0 || (n_edges == 1 && fuse_skip == 0)) {
         for (int b = 0; b < n; ++b) {
@@ -414,6 +429,7 @@ mdcnn_status do_forward(int n, mdcnn_buffer* const* ins, const void* const* fram
         if (i == fuse_skip) continue;
         for (int b = 0; b < n; ++b) {
             eb.d[b] = make_edge(ins[b], outs[b][i], edges[b][i]);
+            if (ls) { eb.d[b].clist = ls->clist[(size_t)i]; eb.d[b].ccnt = ls->ccnt[(size_t)i]; eb.d[b].cacc = ls->cacc[(size_t)i]; }
             if (first) with_source_list(eb.d[b], ins[b]);
         }
         first = false;
@@ -1302,6 +1318,49 @@ mdcnn_status mdcnn_layer_forward(mdcnn_buffer* in, const void* frame_dev, const 
     mdcnn_status st = validate_forward(in, frame_dev, forced_mask_dev, edges, outs, n_edges);
     if (st) return st;
     return do_forward(1, &in, &frame_dev, &forced_mask_dev, &edges, &outs, n_edges, (hipStream_t)stream);
+}
+
+mdcnn_status mdcnn_layer_forward_noalloc(mdcnn_buffer* in, const void* frame_dev, const uint8_t* forced_mask_dev,
+                                         const mdcnn_conv_desc* edges, mdcnn_buffer* const* outs, int n_edges, void* stream) {
+    mdcnn_status rc = validate_forward(in, frame_dev, forced_mask_dev, edges, outs, n_edges);
+    if (rc) return rc;
+    // the address of the array on this device, looked up once per device with that device current
+    static std::mutex mu;
+    static void* base_of[64] = {};
+    int dev = 0;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess || dev < 0 || dev >= 64) return fail(MDCNN_ERR_HIP, "layer_forward_noalloc: cannot tell the current device");
+    void* base = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (!base_of[dev]) {
+            void* p = nullptr;
+            err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (err != hipSuccess || !p) return fail(MDCNN_ERR_HIP, "layer_forward_noalloc: hipGetSymbolAddress: %s", hipGetErrorString(err));
+            base_of[dev] = p;
+        }
+        base = base_of[dev];
+    }
+    // layout: the source's list, counts and running sums, then the same per edge; 256-byte aligned pieces
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return (char*)base + o; };
+    ListScratch ls;
+    const size_t nl = (size_t)in->L.nseg_l;
+    ls.list = (int*)take(nl * kSegPixels * 4);
+    ls.lcnt = (int*)take(nl * 2 * 4);
+    ls.lacc = (unsigned long long*)take(nl * 2 * 8);
+    for (int i = 0; i < n_edges; ++i) {
+        const size_t nc = (size_t)outs[i]->L.nseg_c;
+        ls.clist.push_back((int*)take(nc * kSegPixels * 4));
+        ls.ccnt.push_back((int*)take(nc * 4));
+        ls.cacc.push_back((unsigned long long*)take(nc * 8));
+    }
+    if (off > kScratchBytes)
+        return fail(MDCNN_ERR_SIZE, "layer_forward_noalloc: the lists of this call take %zu bytes, the library keeps %zu", off, kScratchBytes);
+    // counts and running sums start from zero (a fill kernel, not a memset: the caller may be capturing a graph)
+    err = launch_zero_bytes(base, off, (hipStream_t)stream);
+    if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "layer_forward_noalloc: fill launch: %s", hipGetErrorString(err));
+    return do_forward(1, &in, &frame_dev, &forced_mask_dev, &edges, &outs, n_edges, (hipStream_t)stream, -1, nullptr, nullptr, nullptr, 0, &ls);
 }
 
 mdcnn_status mdcnn_net_create(mdcnn_buffer* const* sites, int n_sites, const int* edge_src, const int* edge_dst,

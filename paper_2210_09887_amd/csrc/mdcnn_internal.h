@@ -209,6 +209,7 @@ struct MaskJob {
 constexpr int kMaskMaxDilate = 32;
 hipError_t launch_input_mask(const MaskJob& j, hipStream_t st);
 hipError_t launch_read_view(const SiteDev& s, int what, void* dst, hipStream_t st);
+hipError_t launch_zero_bytes(void* dst, size_t bytes, hipStream_t st);      // bytes a multiple of 16, dst 16-byte aligned
 hipError_t launch_bench_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
 hipError_t launch_bench_mfma(float* sink, int iters, int blocks, hipStream_t st);
 hipError_t launch_write_view(const SiteDev& s, int what, const void* src, hipStream_t st);

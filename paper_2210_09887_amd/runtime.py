@@ -188,9 +188,10 @@ class GpuNet:
                                   self.out.numel() * self.esize, depth, self._stream())
         return outs, masks, r
 
-    def layer_forward(self, i, frame=None, forced=None):
+    def layer_forward(self, i, frame=None, forced=None, noalloc=False):
         idx = [j for j, s in enumerate(self.esrc) if s == i]
-        B.mdcnn_layer_forward(self.bufs[i], None if frame is None else frame.data_ptr(),
+        call = B.mdcnn_layer_forward_noalloc if noalloc else B.mdcnn_layer_forward
+        call(self.bufs[i], None if frame is None else frame.data_ptr(),
                               None if forced is None else forced.data_ptr(),
                               [self.edges[j] for j in idx], [self.bufs[self.edst[j]] for j in idx], self._stream())
 
