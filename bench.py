@@ -228,17 +228,53 @@ def run_batched(a, cfg, net, T, frames, shifts, forced, fused):
     n_prof = min(steps, T)
     for _ in range(n_prof):
         step()
-    prof = B.mdcnn_profile_read()
+    launches = B.mdcnn_profile_read_launches()
+    prof = {k: (0.0, 0) for k in B.KERNEL_CLASSES}
+    for cls, _, _, us in launches:
+        prof[cls] = (prof[cls][0] + us * 1e-3, prof[cls][1] + 1)
     B.mdcnn_set_option(B.MDCNN_OPT_PROFILE, 0)
     after = sum_totals([g.totals() for g in gb.streams])
     ab = algorithmic_bytes(gb.streams[0], net, before, after, n_prof * n, fused_skips=fused)
     classes, kernel_ms, rl_all, _ = rooflines(prof, 2.0 * (after["macs_mfma"] - before["macs_mfma"]),
                                               2.0 * (after["macs_plain"] - before["macs_plain"]), ab, cfg, with_traffic=False,
                                               mfma_peak=PEAK_MFMA_F32_TFLOPS if net.dtype == "f32" else PEAK_MFMA_F16_TFLOPS)
+    peak = PEAK_MFMA_F32_TFLOPS if net.dtype == "f32" else PEAK_MFMA_F16_TFLOPS
+    pf_mfma = 2.0 * (after["macs_mfma"] - before["macs_mfma"]) / (n_prof * n)
+    pf_bytes = sum(ab.values()) / (n_prof * n)
+    whole = lambda rate: {"mfma_tflops": round(pf_mfma * rate / 1e12, 2), "mfma_frac": round(pf_mfma * rate / 1e12 / peak, 4),
+                          "algorithmic_gbs": round(pf_bytes * rate / 1e9, 1), "hbm_frac": round(pf_bytes * rate / 1e9 / PEAK_HBM_GBS, 4)}
+    layers = per_layer_rows(launches, gb.streams[0], net, before, after, n_prof * n, peak, fused) if n <= 16 else None
+    res = {"streams": n, "value": round(n * steps / dt, 2), "unit": "frames/s", "batch_steps": steps, "whole_path": whole(n * steps / dt),
+           "per_layer": layers, "per_layer_note": "us, flops and bytes per frame of one video (a launch carries one frame of every video)",
+           "ms_per_batch_step": round(1e3 * dt / steps, 4), "roofline_all": rl_all, "kernel_classes": classes,
+           "kernel_ms_per_batch_step": round(kernel_ms / n_prof, 4)}
+    # the same batch with frames of every video in flight (mdcnn_frames_batch): calls of T frames per video
+    if a.frames_in_flight != 1 and T >= 8:
+        outs = [[torch.empty_like(gb.streams[0].out) for _ in range(n)] for _ in range(T)]
+
+        def call(depth):
+            ts = [[(state["t"] + f + p) % T for p in phase] for f in range(T)]
+            gb.frames([[frames[t] for t in row] for row in ts], [[int(shifts[t][0]) for t in row] for row in ts],
+                      [[int(shifts[t][1]) for t in row] for row in ts],
+                      None if forced is None else [[forced[t] for t in row] for row in ts], outs=outs, depth=depth)
+            state["t"] += T
+
+        flight = {}
+        for depth in (2, 4):
+            call(depth)
+            torch.cuda.synchronize()
+            rates = []
+            for _ in range(3):
+                t0 = time.perf_counter()
+                call(depth)
+                torch.cuda.synchronize()
+                rates.append(n * T / (time.perf_counter() - t0))
+            flight[f"depth_{depth}"] = round(sorted(rates)[1], 2)
+        best = max(flight.values())
+        res["in_flight"] = {"entry_point": "mdcnn_frames_batch, calls of %d frames x %d videos" % (T, n), "unit": "frames/s", **flight,
+                            "value": best, "whole_path": whole(best)}
     gb.close()
-    return {"streams": n, "value": round(n * steps / dt, 2), "unit": "frames/s", "batch_steps": steps,
-            "ms_per_batch_step": round(1e3 * dt / steps, 4), "roofline_all": rl_all, "kernel_classes": classes,
-            "kernel_ms_per_batch_step": round(kernel_ms / n_prof, 4)}
+    return res
 
 
 def measured_peaks(torch, B):

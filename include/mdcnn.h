@@ -323,6 +323,28 @@ mdcnn_status mdcnn_frames(mdcnn_net* net, int n_frames, const void* const* frame
                           void* const* outs_dev, size_t out_bytes, int depth, void* stream,
                           int* did_full_reset);
 
+/* mdcnn_frames for a batch of videos: n_frames consecutive frames of each of n_streams
+ * independent videos (networks of equal topology and shapes with their own buffers,
+ * camera paths, masks and reset decisions, as for mdcnn_frame_batch), with frames in
+ * flight on `depth` streams as in mdcnn_frames.  One launch carries a forward call of
+ * all videos (16 to a launch; with more, the whole run of the first 16 videos is
+ * followed by that of the next 16 on the caller's stream), so a launch has n_streams
+ * times the blocks and the frames in flight fill what is left of the GPU  [Evaluation:
+ * batch sizes up to what the GPU holds; Method, Fig. 3].
+ * Frame f of video b is what mdcnn_frame(nets[b], ...) does with entry [f * n_streams + b]
+ * of frames_dev, forced_masks_dev (NULL or with NULL entries), dty, dtx, outs_dev
+ * (out_bytes each, no two may overlap) and did_full_reset (NULL or n_frames * n_streams
+ * ints): outputs and all state are identical, bit for bit, to those calls.
+ * 1 <= n_streams <= 128, 1 <= n_frames <= 4096, depth as for mdcnn_frames.
+ * Errors: as for mdcnn_frame_batch and mdcnn_frames, checked for all frames and videos
+ * before anything runs; cropped frames are not supported (MDCNN_ERR_STATE if a network
+ * has a crop smaller than its view). */
+mdcnn_status mdcnn_frames_batch(mdcnn_net* const* nets, int n_streams, int n_frames,
+                                const void* const* frames_dev,
+                                const uint8_t* const* forced_masks_dev, const int* dty,
+                                const int* dtx, void* const* outs_dev, size_t out_bytes,
+                                int depth, void* stream, int* did_full_reset);
+
 /* mdcnn_frames for cropped frames: frame f is what mdcnn_frame_crop does with the crop
  * (crops[4f .. 4f+3] = ty0, tx0, th, tw in tiles of the view); frames_dev[f], the forced
  * mask and outs_dev[f] have that crop's extent, out_bytes[f] the summed crop sizes of the

@@ -30,7 +30,7 @@ STATUS_NAMES = {0: "OK", 1: "ERR_NULL", 2: "ERR_SHAPE", 3: "ERR_DTYPE", 4: "ERR_
 
 EXPORTS = ["mdcnn_conv_border", "mdcnn_buffer_bytes", "mdcnn_create_buffer", "mdcnn_destroy_buffer",
            "mdcnn_shift_camera", "mdcnn_set_crop", "mdcnn_layer_forward", "mdcnn_layer_forward_noalloc", "mdcnn_net_create", "mdcnn_net_destroy",
-           "mdcnn_frame", "mdcnn_frame_crop", "mdcnn_frame_batch", "mdcnn_frame_plan", "mdcnn_frames", "mdcnn_frames_crop", "mdcnn_frames_masked", "mdcnn_frames_plan", "mdcnn_input_mask", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read", "mdcnn_profile_read_launches", "mdcnn_bench_copy", "mdcnn_bench_mfma",
+           "mdcnn_frame", "mdcnn_frame_crop", "mdcnn_frame_batch", "mdcnn_frame_plan", "mdcnn_frames", "mdcnn_frames_batch", "mdcnn_frames_crop", "mdcnn_frames_masked", "mdcnn_frames_plan", "mdcnn_input_mask", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read", "mdcnn_profile_read_launches", "mdcnn_bench_copy", "mdcnn_bench_mfma",
            "mdcnn_pack_weights", "mdcnn_last_error", "mdcnn_version"]
 
 
@@ -84,6 +84,7 @@ def lib():
         L.mdcnn_frame_batch.argtypes = [C.POINTER(vp), C.c_int, C.POINTER(vp), C.POINTER(vp), ip, ip, C.POINTER(vp), sz, vp, ip]
         L.mdcnn_frame_plan.argtypes = [vp, C.c_int, ip, ip, C.c_int, ip, ip]
         L.mdcnn_frames.argtypes = [vp, C.c_int, C.POINTER(vp), C.POINTER(vp), ip, ip, C.POINTER(vp), sz, C.c_int, vp, ip]
+        L.mdcnn_frames_batch.argtypes = [C.POINTER(vp), C.c_int, C.c_int, C.POINTER(vp), C.POINTER(vp), ip, ip, C.POINTER(vp), sz, C.c_int, vp, ip]
         L.mdcnn_frames_crop.argtypes = [vp, C.c_int, C.POINTER(vp), C.POINTER(vp), ip, ip, ip, C.POINTER(vp), C.POINTER(sz), C.c_int, vp, ip]
         L.mdcnn_frames_masked.argtypes = [vp, C.c_int, C.POINTER(vp), C.POINTER(vp), C.POINTER(mdcnn_mask_params), C.POINTER(vp), sz, ip, ip,
                                           C.POINTER(vp), sz, C.c_int, vp, ip]
@@ -262,6 +263,20 @@ def mdcnn_frames(net: int, frame_ptrs, forced_ptrs, dty, dtx, out_ptrs, out_byte
                               (C.c_int * n)(*[int(v) for v in dty]), (C.c_int * n)(*[int(v) for v in dtx]),
                               (C.c_void_p * n)(*out_ptrs), out_bytes, int(depth), stream, r))
     return [bool(v) for v in r]
+
+
+def mdcnn_frames_batch(nets, frame_ptrs, forced_ptrs, dty, dtx, out_ptrs, out_bytes: int, depth: int = 0, stream: int = 0):
+    """frame_ptrs[f][b] etc.: frame f of video b; len(nets) videos, up to `depth` frames of each in flight.  Returns
+    the reset decisions [f][b]."""
+    nb, nf = len(nets), len(frame_ptrs)
+    n = nb * nf
+    flat = lambda rows: [v for row in rows for v in row]
+    r = (C.c_int * n)()
+    forced = None if forced_ptrs is None else (C.c_void_p * n)(*flat(forced_ptrs))
+    _check(lib().mdcnn_frames_batch(_handles(nets), nb, nf, (C.c_void_p * n)(*flat(frame_ptrs)), forced,
+                                    (C.c_int * n)(*[int(v) for v in flat(dty)]), (C.c_int * n)(*[int(v) for v in flat(dtx)]),
+                                    (C.c_void_p * n)(*flat(out_ptrs)), out_bytes, int(depth), stream, r))
+    return [[bool(r[f * nb + b]) for b in range(nb)] for f in range(nf)]
 
 
 def mdcnn_frames_crop(net: int, frame_ptrs, forced_ptrs, dty, dtx, crops, out_ptrs, out_bytes, depth: int = 0, stream: int = 0):

@@ -923,9 +923,12 @@ struct IssueShared {
     explicit IssueShared(int n) : done((size_t)n) { for (auto& d : done) d.store(0, std::memory_order_relaxed); }
 };
 
-mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, const uint8_t* const* forced,
+// nb > 1: the same for nb videos of networks of equal shape at once (one launch carries a call of all of them; no crops,
+// no front end).  Everything per frame is then indexed [frame * nb + video].
+mdcnn_status frame_seq(mdcnn_net* const* nets, int nb, int n_frames, const void* const* frames, const uint8_t* const* forced,
                        const int* dty, const int* dtx, const int* crops, const FrontEnd* fe, void* const* outs_dev, int depth,
                        hipStream_t user, int* did_full_reset) {
+    mdcnn_net* const net = nets[0];
     const int group = pipe_group(net), key = (group * 8 + depth) * 2 + g_pipe_mode;
     if (net->pipe.key != key) make_pipe_plan(net, group, depth, g_pipe_mode, net->pipe);
     const PipePlan& pp = net->pipe;
@@ -942,35 +945,46 @@ mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, 
     // device: while nothing is enqueued it is put back as it was; afterwards every site is marked as never
     // reset, so that the next camera shift re-initialises everything.
     struct HostState {
-        mdcnn_net* net;
+        mdcnn_net* const* nets; int nb;
         std::vector<mdcnn_buffer> saved;
         bool armed = true, enqueued = false;
-        explicit HostState(mdcnn_net* n) : net(n) { for (mdcnn_buffer* b : n->sites) saved.push_back(*b); }
+        HostState(mdcnn_net* const* n, int count) : nets(n), nb(count) {
+            for (int v = 0; v < nb; ++v)
+                for (mdcnn_buffer* b : nets[v]->sites) saved.push_back(*b);
+        }
         ~HostState() {
             if (!armed) return;
-            for (size_t i = 0; i < saved.size(); ++i) {
-                if (!enqueued) *net->sites[i] = saved[i];
-                else net->sites[i]->fresh = true;
-            }
+            size_t k = 0;
+            for (int v = 0; v < nb; ++v)
+                for (mdcnn_buffer* b : nets[v]->sites) {
+                    if (!enqueued) *b = saved[k];
+                    else b->fresh = true;
+                    ++k;
+                }
         }
-    } host_state(net);
+    } host_state(nets, nb);
     // the camera path of the whole run, on the host: every frame gets its own copy of the sites
     std::vector<FrameWork> work((size_t)n_frames);
     {
         std::vector<FillJob> jobs;
         for (int f = 0; f < n_frames; ++f) {
-            bool full = false;
-            mdcnn_status rc = shift_jobs(net->sites.data(), n_sites, dty[f], dtx[f], jobs, &full);
-            if (rc) return rc;
-            if (did_full_reset) did_full_reset[f] = full ? 1 : 0;
-            if (crops) {
-                rc = mdcnn_set_crop(net->sites.data(), n_sites, crops[4 * f], crops[4 * f + 1], crops[4 * f + 2], crops[4 * f + 3]);
-                if (rc) return rc;
-            }
             FrameWork& w = work[(size_t)f];
-            w.sites.reserve((size_t)n_sites);
-            for (int i = 0; i < n_sites; ++i) w.sites.push_back(*net->sites[(size_t)i]);
-            w.jobs = jobs;
+            w.sites.reserve((size_t)nb * n_sites);
+            w.jobs.reserve((size_t)nb * n_sites);
+            for (int v = 0; v < nb; ++v) {
+                mdcnn_net* nv = nets[v];
+                const size_t fv = (size_t)f * nb + v;
+                bool full = false;
+                mdcnn_status rc = shift_jobs(nv->sites.data(), n_sites, dty[fv], dtx[fv], jobs, &full);
+                if (rc) return rc;
+                if (did_full_reset) did_full_reset[fv] = full ? 1 : 0;
+                if (crops) {                                   // (nb == 1)
+                    rc = mdcnn_set_crop(nv->sites.data(), n_sites, crops[4 * f], crops[4 * f + 1], crops[4 * f + 2], crops[4 * f + 3]);
+                    if (rc) return rc;
+                }
+                for (int i = 0; i < n_sites; ++i) w.sites.push_back(*nv->sites[(size_t)i]);
+                w.jobs.insert(w.jobs.end(), jobs.begin(), jobs.end());
+            }
         }
     }
     host_state.enqueued = true;
@@ -1012,7 +1026,16 @@ mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, 
         hipEvent_t* ev_prev = events + (size_t)((f + ring - 1) % ring) * pp.n_events;
         hipEvent_t* ev_mine = events + (size_t)(f % ring) * pp.n_events;
         std::vector<mdcnn_buffer*> outs_flat;
+        std::vector<int> fill_all;
         hipError_t err = hipSuccess;
+        // the initialisation jobs of the sites `fill` of every video
+        auto launch_fills = [&](const std::vector<int>& fill, hipStream_t st) {
+            if (nb == 1) return launch_fill_jobs(jobs, fill.data(), (int)fill.size(), st);
+            fill_all.clear();
+            for (int v = 0; v < nb; ++v)
+                for (int site : fill) fill_all.push_back(v * n_sites + site);
+            return launch_fill_jobs(jobs, fill_all.data(), (int)fill_all.size(), st);
+        };
         auto issued = [&](int call) {                          // everything up to `call` is issued
             if (depth > 1 && wanted[(size_t)call]) err = hipEventRecord(ev_mine[pp.event_of_call[(size_t)call]], s[pp.stream_of(f, call)]);
             shared.done[(size_t)f].store(call + 1, std::memory_order_release);
@@ -1033,7 +1056,7 @@ mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, 
             const PipeGroup& g = pp.groups[gi];
             if (gi == 0) {
                 err = wait_for(g, 0);
-                if (err == hipSuccess) err = launch_fill_jobs(jobs, g.fill.data(), (int)g.fill.size(), s[pp.stream_of(f, 0)]);
+                if (err == hipSuccess) err = launch_fills(g.fill, s[pp.stream_of(f, 0)]);
                 if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: shift launch: %s", f, hipGetErrorString(err));
                 if (fe) {                                      // the input site is initialised: its mask for this frame
                     mdcnn_status rc = mdcnn_input_mask(&w.sites[0], frames[f], fe->roi ? fe->roi[f] : nullptr, fe->prm, fe->masks[f],
@@ -1052,20 +1075,29 @@ mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, 
                 if (c == g.call1 - 1 && gi + 1 < pp.groups.size()) {          // the next group's sites are initialised here
                     const PipeGroup& nx = pp.groups[gi + 1];
                     err = wait_for(nx, c);
-                    if (err == hipSuccess && (int)nx.fill.size() > kMaxRiders) err = launch_fill_jobs(jobs, nx.fill.data(), (int)nx.fill.size(), st);
+                    // (a launch of several videos carries no riders)
+                    if (err == hipSuccess && ((int)nx.fill.size() > kMaxRiders || nb > 1)) err = launch_fills(nx.fill, st);
                     else { riders = nx.fill.data(); n_riders = (int)nx.fill.size(); }
                     if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: shift launch: %s", f, hipGetErrorString(err));
                 }
-                const int i = pp.call_site[c], e0 = pp.call_e0[c], e1 = pp.call_e1[c], ne = e1 - e0;
-                outs_flat.resize((size_t)(ne > 0 ? ne : 1));
-                for (int e = e0; e < e1; ++e) outs_flat[(size_t)(e - e0)] = &w.sites[(size_t)net->edst[e]];
-                mdcnn_buffer* in = &w.sites[(size_t)i];
-                const mdcnn_conv_desc* edges = net->edges.data() + e0;
-                mdcnn_buffer* const* outs = outs_flat.data();
-                const void* X = frames[f];
-                const uint8_t* fm = fe ? fe->masks[f] : forced ? forced[f] : nullptr;
+                const int i = pp.call_site[c], e0 = pp.call_e0[c], e1 = pp.call_e1[c], ne = e1 - e0, stride = ne > 0 ? ne : 1;
+                outs_flat.resize((size_t)nb * stride);
+                mdcnn_buffer* ins[kMaxBatch];
+                const mdcnn_conv_desc* edges[kMaxBatch];
+                mdcnn_buffer* const* outs[kMaxBatch];
+                const void* X[kMaxBatch];
+                const uint8_t* fm[kMaxBatch];
+                for (int v = 0; v < nb; ++v) {
+                    mdcnn_buffer* sites_v = w.sites.data() + (size_t)v * n_sites;
+                    for (int e = e0; e < e1; ++e) outs_flat[(size_t)v * stride + (e - e0)] = sites_v + net->edst[e];
+                    ins[v] = sites_v + i;
+                    edges[v] = nets[v]->edges.data() + e0;
+                    outs[v] = outs_flat.data() + (size_t)v * stride;
+                    X[v] = frames[(size_t)f * nb + v];
+                    fm[v] = fe ? fe->masks[f] : forced ? forced[(size_t)f * nb + v] : nullptr;
+                }
                 g_tag_site = i; g_tag_edge0 = e0;
-                mdcnn_status rc = do_forward(1, &in, i == 0 ? &X : nullptr, i == 0 ? &fm : nullptr, &edges, &outs, ne, st,
+                mdcnn_status rc = do_forward(nb, ins, i == 0 ? X : nullptr, i == 0 ? fm : nullptr, edges, outs, ne, st,
                                              fused_skip(net, e0, e1), nullptr, jobs, riders, n_riders);
                 g_tag_site = g_tag_edge0 = -1;
                 if (rc) return rc;
@@ -1073,12 +1105,15 @@ mdcnn_status frame_seq(mdcnn_net* net, int n_frames, const void* const* frames, 
             }
         }
         hipStream_t st = s[pp.stream_of(f, n_calls)];
-        char* o = (char*)outs_dev[f];
-        for (mdcnn_buffer& b : w.sites) {
-            if (b.d.kind != MDCNN_SITE_OUTPUT) continue;
-            err = timed(kClsReadout, st, [&] { return launch_read_view(b.dev, crops ? MDCNN_VIEW_CROP_OUT : MDCNN_VIEW_OUT, o, st); });
-            if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: readout launch: %s", f, hipGetErrorString(err));
-            o += crop_pixels(&b) * b.d.C * esize(b.d.dtype);
+        for (int v = 0; v < nb; ++v) {
+            char* o = (char*)outs_dev[(size_t)f * nb + v];
+            for (int i = 0; i < n_sites; ++i) {
+                mdcnn_buffer& b = w.sites[(size_t)v * n_sites + i];
+                if (b.d.kind != MDCNN_SITE_OUTPUT) continue;
+                err = timed(kClsReadout, st, [&] { return launch_read_view(b.dev, crops ? MDCNN_VIEW_CROP_OUT : MDCNN_VIEW_OUT, o, st); });
+                if (err != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: readout launch: %s", f, hipGetErrorString(err));
+                o += crop_pixels(&b) * b.d.C * esize(b.d.dtype);
+            }
         }
         if (issued(n_calls) != hipSuccess) return fail(MDCNN_ERR_HIP, "frame %d: event: %s", f, hipGetErrorString(err));
         return MDCNN_OK;
@@ -1539,7 +1574,7 @@ static mdcnn_status frames_checked(mdcnn_net* net, int n_frames, const void* con
         depth = (int)one.nodes.size() >= kMinLaunchesInFlight ? kDefaultDepth : 1;
     }
     if (n_frames == 1) depth = 1;
-    return frame_seq(net, n_frames, frames_dev, forced_masks_dev, dty, dtx, crops, fe, outs_dev, depth, (hipStream_t)stream, did_full_reset);
+    return frame_seq(&net, 1, n_frames, frames_dev, forced_masks_dev, dty, dtx, crops, fe, outs_dev, depth, (hipStream_t)stream, did_full_reset);
 }
 
 mdcnn_status mdcnn_frames(mdcnn_net* net, int n_frames, const void* const* frames_dev, const uint8_t* const* forced_masks_dev,
@@ -1561,6 +1596,70 @@ mdcnn_status mdcnn_frames_masked(mdcnn_net* net, int n_frames, const void* const
     if (!prm || !masks_dev) return fail(MDCNN_ERR_NULL, "frames_masked: mask parameters / mask buffers missing");
     const FrontEnd fe{prm, roi_dev, masks_dev, mask_bytes};
     return frames_checked(net, n_frames, frames_dev, nullptr, dty, dtx, nullptr, &fe, outs_dev, &out_bytes, depth, stream, did_full_reset);
+}
+
+mdcnn_status mdcnn_frames_batch(mdcnn_net* const* nets, int n_streams, int n_frames, const void* const* frames_dev,
+                                const uint8_t* const* forced_masks_dev, const int* dty, const int* dtx, void* const* outs_dev,
+                                size_t out_bytes, int depth, void* stream, int* did_full_reset) {
+    if (!nets || !frames_dev || !dty || !dtx || !outs_dev) return fail(MDCNN_ERR_NULL, "frames_batch: NULL argument");
+    if (n_streams < 1 || n_streams > kMaxBatchStreams) return fail(MDCNN_ERR_SIZE, "frames_batch: 1 <= n_streams <= %d", kMaxBatchStreams);
+    if (n_frames < 1 || n_frames > kMaxFrames) return fail(MDCNN_ERR_SIZE, "frames_batch: 1 <= n_frames <= %d", kMaxFrames);
+    if (depth < 0 || depth > kMaxStreams) return fail(MDCNN_ERR_SIZE, "frames_batch: 0 <= depth <= %d", kMaxStreams);
+    for (int b = 0; b < n_streams; ++b) {
+        if (!nets[b]) return fail(MDCNN_ERR_NULL, "frames_batch: stream %d: net is NULL", b);
+        if (out_bytes != nets[b]->out_bytes) return fail(MDCNN_ERR_SIZE, "frames_batch: out_bytes is %zu, the outputs take %zu", out_bytes, nets[b]->out_bytes);
+        if (!whole_view(nets[b]->sites[0])) return fail(MDCNN_ERR_STATE, "frames_batch: stream %d has a crop smaller than its view", b);
+        if (b && !same_shape(nets[0], nets[b])) return fail(MDCNN_ERR_SHAPE, "frames_batch: stream %d differs from stream 0 in topology or shapes", b);
+        for (int c = 0; c < b; ++c)
+            if (nets[c] == nets[b] || nets[c]->sites[0] == nets[b]->sites[0])
+                return fail(MDCNN_ERR_STATE, "frames_batch: streams %d and %d share a network or buffers", c, b);
+    }
+    const size_t total = (size_t)n_frames * n_streams;
+    for (size_t k = 0; k < total; ++k) {
+        if (!frames_dev[k] || !outs_dev[k]) return fail(MDCNN_ERR_NULL, "frames_batch: frame %zu, stream %zu: frame/out is NULL", k / n_streams, k % n_streams);
+        if (((uintptr_t)frames_dev[k] | (uintptr_t)outs_dev[k]) & 15) return fail(MDCNN_ERR_ALIGN, "frames_batch: frame %zu, stream %zu: frame/out must be 16-byte aligned", k / n_streams, k % n_streams);
+    }
+    {   // frames in flight write their outputs in no fixed order: no two may share memory
+        std::vector<const char*> o((size_t)total);
+        for (size_t k = 0; k < total; ++k) o[k] = (const char*)outs_dev[k];
+        std::sort(o.begin(), o.end());
+        for (size_t k = 1; k < total; ++k)
+            if (o[k] < o[k - 1] + out_bytes) return fail(MDCNN_ERR_STATE, "frames_batch: two output buffers overlap");
+    }
+    if (depth == 0) {
+        Plan one;
+        make_plan(nets[0], 1, one);
+        depth = (int)one.nodes.size() >= kMinLaunchesInFlight ? kDefaultDepth : 1;
+    }
+    if (n_frames == 1) depth = 1;
+    if (n_streams <= kMaxBatch)
+        return frame_seq(nets, n_streams, n_frames, frames_dev, forced_masks_dev, dty, dtx, nullptr, nullptr, outs_dev, depth, (hipStream_t)stream, did_full_reset);
+    // the descriptors of a launch travel as kernel arguments, kMaxBatch videos to a launch: more videos go in groups of
+    // that many, the whole run of one group after that of the other on the caller's stream
+    std::vector<const void*> fr;
+    std::vector<const uint8_t*> fm;
+    std::vector<void*> out;
+    std::vector<int> sy, sx, reset;
+    for (int b0 = 0; b0 < n_streams; b0 += kMaxBatch) {
+        const int nb = n_streams - b0 < kMaxBatch ? n_streams - b0 : kMaxBatch;
+        fr.clear(); fm.clear(); out.clear(); sy.clear(); sx.clear();
+        for (int f = 0; f < n_frames; ++f)
+            for (int v = 0; v < nb; ++v) {
+                const size_t k = (size_t)f * n_streams + b0 + v;
+                fr.push_back(frames_dev[k]);
+                fm.push_back(forced_masks_dev ? forced_masks_dev[k] : nullptr);
+                out.push_back(outs_dev[k]);
+                sy.push_back(dty[k]);
+                sx.push_back(dtx[k]);
+            }
+        reset.assign((size_t)n_frames * nb, 0);
+        const mdcnn_status rc = frame_seq(nets + b0, nb, n_frames, fr.data(), forced_masks_dev ? fm.data() : nullptr, sy.data(), sx.data(), nullptr, nullptr,
+                                          out.data(), depth, (hipStream_t)stream, reset.data());
+        if (rc) return rc;
+        for (int f = 0; did_full_reset && f < n_frames; ++f)
+            for (int v = 0; v < nb; ++v) did_full_reset[(size_t)f * n_streams + b0 + v] = reset[(size_t)f * nb + v];
+    }
+    return MDCNN_OK;
 }
 
 mdcnn_status mdcnn_frames_plan(mdcnn_net* net, int depth, int* first_call, int* wait_call, int* init_call, int cap_groups,

@@ -279,6 +279,16 @@ class GpuBatch:
                                 dty, dtx, [o.data_ptr() for o in outs], g0.out.numel() * g0.esize, g0._stream())
         return outs, r
 
+    def frames(self, frames, dty, dtx, forced=None, outs=None, depth=0):
+        """frames[f][b]: frame f of video b (device tensors), dty / dtx / forced alike.  Returns (outs[f][b], resets[f][b])."""
+        g0 = self.streams[0]
+        if outs is None:
+            outs = [[torch.empty_like(g0.out) for _ in row] for row in frames]
+        r = B.mdcnn_frames_batch([g.net for g in self.streams], [[x.data_ptr() for x in row] for row in frames],
+                                 None if forced is None else [[None if f is None else f.data_ptr() for f in row] for row in forced],
+                                 dty, dtx, [[o.data_ptr() for o in row] for row in outs], g0.out.numel() * g0.esize, depth, g0._stream())
+        return outs, r
+
     def close(self):
         for g in reversed(self.streams):
             g.close()

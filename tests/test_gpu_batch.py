@@ -165,3 +165,110 @@ def test_batch_argument_checks():
     finally:
         other.close()
         gb.close()
+
+
+@pytest.mark.parametrize("name,n_streams", [("c3_resnet_96", 3), ("c4_hrnet_128x96", 2), ("c5_bottleneck_40", 3), ("c2_cnn5_88x72", 2)])
+def test_frames_of_a_batch_in_flight(name, n_streams):
+    """mdcnn_frames_batch: several videos, each with frames in flight.  First the videos go frame by frame through
+    mdcnn_frame_batch with an oracle following every one of them (decisions within the guard band, outputs at the tight
+    tolerance); then the same videos go through mdcnn_frames_batch at several depths and cuts into calls, and every output
+    of every frame and all state at the end must be the same bits."""
+    import gpu_harness as H
+    from test_gpu_frames import state_of
+    from paper_2210_09887_amd import binding as B
+    from paper_2210_09887_amd.runtime import GpuBatch
+    net, seq = load_case(name)
+    seqs = different_paths(net, seq, n_streams)
+    T = len(seqs[0][0])
+    assert T >= 4
+    fs = [H.Follower(net) for _ in range(n_streams)]
+    want_o, want_r = [], []
+    gb = GpuBatch(net, n_streams)
+    try:
+        for t in range(T):
+            Xs = [sq[0][t] for sq in seqs]
+            dys, dxs = [sq[1][t][0] for sq in seqs], [sq[1][t][1] for sq in seqs]
+            fms = [None if sq[2] is None else sq[2][t] for sq in seqs]
+            outs, rs = gb.frame([H.dev(X) for X in Xs], dys, dxs, None if fms[0] is None else [H.dev(m) for m in fms])
+            torch.cuda.synchronize()
+            for b, g in enumerate(gb.streams):
+                got = [x.cpu().numpy() for x in g.split_outputs(outs[b])]
+                fs[b].check(t, Xs[b], dys[b], dxs[b], fms[b], got, bool(rs[b]), H.gpu_masks(g, fs[b].inner), g.read(0, B.MDCNN_VIEW_LIST),
+                            tag=f"stream {b} ")
+            want_o.append([o.clone() for o in outs])
+            want_r.append([bool(r) for r in rs])
+        want_s = [state_of(g, net) for g in gb.streams]
+    finally:
+        gb.close()
+    for b, f in enumerate(fs):
+        r = f.result()
+        print(f"[batch in flight, reference run vs oracle] {name} stream {b}: {r}", flush=True)
+        assert r["flips"] <= 0.02 * r["decisions"] and r["worst_margin"] < H.TOL[net.dtype] / 4
+    assert any(any(r) for r in want_r[1:]), "a reset after the first frame belongs to the case"
+    dev_frames = [[H.dev(sq[0][t]) for sq in seqs] for t in range(T)]
+    dev_forced = None if seqs[0][2] is None else [[H.dev(sq[2][t]) for sq in seqs] for t in range(T)]
+    dty = [[sq[1][t][0] for sq in seqs] for t in range(T)]
+    dtx = [[sq[1][t][1] for sq in seqs] for t in range(T)]
+    for depth, cut in [(4, T), (2, 3), (1, T), (0, 2)]:
+        print(f"{name}: {n_streams} videos, depth {depth}, calls of {cut} frames", flush=True)
+        gb = GpuBatch(net, n_streams)
+        try:
+            got_o, got_r = [], []
+            for t0 in range(0, T, cut):
+                sl = slice(t0, min(t0 + cut, T))
+                o, r = gb.frames(dev_frames[sl], dty[sl], dtx[sl], None if dev_forced is None else dev_forced[sl], depth=depth)
+                got_o += o
+                got_r += r
+            torch.cuda.synchronize()
+            assert got_r == want_r
+            for t in range(T):
+                for b in range(n_streams):
+                    assert torch.equal(got_o[t][b], want_o[t][b]), f"depth {depth}: frame {t}, video {b}: output differs"
+            for b, g in enumerate(gb.streams):
+                for k, (u, v) in enumerate(zip(want_s[b], state_of(g, net))):
+                    assert np.array_equal(u, v), f"depth {depth}: video {b}: state view {k} differs"
+        finally:
+            gb.close()
+
+
+def test_frames_batch_of_more_videos_than_one_launch_carries_and_argument_checks():
+    import gpu_harness as H
+    from paper_2210_09887_amd import binding as B
+    from paper_2210_09887_amd.runtime import GpuBatch, GpuNet
+    net, seq = load_case("c3_resnet_plain_80x112")
+    n, T = 19, 5
+    rng = np.random.default_rng(11)
+    start = [int(rng.integers(0, len(seq.frames) - T + 1)) for _ in range(n)]
+    path = [[(0, 0)] + [(int(rng.integers(-1, 2)), int(rng.integers(-1, 2))) for _ in range(T - 1)] for _ in range(n)]
+    want = {}
+    for b in (0, 7, 15, 16, 18):                             # videos of both groups against their single runs
+        g = GpuNet(net)
+        try:
+            want[b] = [(lambda o, r: (o.cpu().numpy().copy(), r))(*g.frame(H.dev(seq.frames[start[b] + t]), *path[b][t])) for t in range(T)]
+        finally:
+            g.close()
+    gb = GpuBatch(net, n)
+    try:
+        frames = [[H.dev(seq.frames[start[b] + t]) for b in range(n)] for t in range(T)]
+        dty = [[path[b][t][0] for b in range(n)] for t in range(T)]
+        dtx = [[path[b][t][1] for b in range(n)] for t in range(T)]
+        outs, rs = gb.frames(frames, dty, dtx, depth=3)
+        torch.cuda.synchronize()
+        for b in want:
+            for t in range(T):
+                assert rs[t][b] == want[b][t][1] and np.array_equal(outs[t][b].cpu().numpy(), want[b][t][0]), f"frame {t} video {b}"
+        g0 = gb.streams[0]
+        nets = [g.net for g in gb.streams]
+        nbytes = g0.out.numel() * g0.esize
+        X = frames[0][0].data_ptr()
+        o2 = [torch.empty_like(g0.out) for _ in range(4)]
+        with pytest.raises(B.MdcnnError):                    # the same video twice
+            B.mdcnn_frames_batch([nets[0], nets[0]], [[X, X]] * 2, None, [[0, 0]] * 2, [[0, 0]] * 2, [[o2[0].data_ptr(), o2[1].data_ptr()], [o2[2].data_ptr(), o2[3].data_ptr()]], nbytes)
+        with pytest.raises(B.MdcnnError):                    # two frames write the same output
+            B.mdcnn_frames_batch(nets[:2], [[X, X]] * 2, None, [[0, 0]] * 2, [[0, 0]] * 2, [[o2[0].data_ptr(), o2[1].data_ptr()], [o2[0].data_ptr(), o2[3].data_ptr()]], nbytes)
+        with pytest.raises(B.MdcnnError):                    # wrong output size
+            B.mdcnn_frames_batch(nets[:2], [[X, X]], None, [[0, 0]], [[0, 0]], [[o2[0].data_ptr(), o2[1].data_ptr()]], nbytes - 16)
+        with pytest.raises(B.MdcnnError):                    # depth out of range
+            B.mdcnn_frames_batch(nets[:2], [[X, X]], None, [[0, 0]], [[0, 0]], [[o2[0].data_ptr(), o2[1].data_ptr()]], nbytes, depth=5)
+    finally:
+        gb.close()
