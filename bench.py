@@ -201,6 +201,10 @@ def run_batched(a, cfg, net, T, frames, shifts, forced, fused):
     from paper_2210_09887_amd import binding as B
     from paper_2210_09887_amd.runtime import GpuBatch
     n = a.streams
+    # with many videos to a launch whole-segment convolution tiles are the faster choice (the default follows one video)
+    whole_tiles = not any(o.startswith("7=") for o in a.opt)
+    if whole_tiles:
+        B.mdcnn_set_option(B.MDCNN_OPT_CONV_HALO_SUB, 1)
     gb = GpuBatch(net, n)
     phase = [(b * T) // n for b in range(n)]
     state = {"t": 0}
@@ -274,6 +278,9 @@ def run_batched(a, cfg, net, T, frames, shifts, forced, fused):
         res["in_flight"] = {"entry_point": "mdcnn_frames_batch, calls of %d frames x %d videos" % (T, n), "unit": "frames/s", **flight,
                             "value": best, "whole_path": whole(best)}
     gb.close()
+    if whole_tiles:
+        B.mdcnn_set_option(B.MDCNN_OPT_CONV_HALO_SUB, 0)
+        res["options"] = "MDCNN_OPT_CONV_HALO_SUB = 1 (whole-segment convolution tiles)"
     return res
 
 

@@ -465,8 +465,12 @@ typedef enum {
     MDCNN_OPT_CONV_XCD = 4,  /* tuning: 1 (default) tie cout tiles to XCDs, 0 plain order  */
     MDCNN_OPT_CONV_KC = 5,   /* tuning: 0 auto, 64 cap the K step at 64 channels           */
     MDCNN_OPT_CONV_HALO = 6, /* tuning: 1 (default) packed-weights kernel where it applies,  */
-                             /* 0 never, 2 with 32-cout tiles                              */
-    MDCNN_OPT_CONV_HALO_SUB = 7, /* tuning: 0 auto, 1 / 2 / 4 tiles per list segment of that kernel */
+                             /* 0 never, 2 with 32-cout tiles, 3 with tiles that are index  */
+                             /* ranges of the padded window instead of rectangles           */
+    MDCNN_OPT_CONV_HALO_SUB = 7, /* 0 auto (by the tiles one video gives a launch), 1 / 2 / 4: tiles of a whole, */
+                             /* half or quarter list segment (256 pixels) in that kernel; 1 is the faster choice for */
+                             /* batches of many videos.  The split fixes the order of the sums: runs that are to  */
+                             /* agree bit for bit need the same value                                              */
     MDCNN_OPT_FUSE_SKIP = 8, /* 1 (default): mdcnn_frame lets the delta kernel of a site add its   */
                              /* residual skip (identity edge) instead of a launch of its own; */
                              /* such an edge then adds nothing to the compute-list statistics  */

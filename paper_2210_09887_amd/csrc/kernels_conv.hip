@@ -120,7 +120,12 @@ __device__ __forceinline__ void mark_touched(const EdgeDev& e, int wy, int wx) {
     for (int a = 0; a < f; ++a)
         for (int b = 0; b < f; ++b) {
             const int oy = wy + a - e.by0, ox = wx + b - e.bx0;
-            if (oy >= 0 && oy < e.dH && ox >= 0 && ox < e.dW) e.dflags[oy * e.dW + ox] |= (uint8_t)kFlagU;
+            if (oy >= 0 && oy < e.dH && ox >= 0 && ox < e.dW) {
+                // an atomic OR on the word that holds the flag byte, its result unused: nothing comes back to the wave, so the
+                // loads that follow do not queue behind a read-modify-write round trip (the flag region is 256-byte aligned)
+                const int idx = oy * e.dW + ox;
+                atomicOr(reinterpret_cast<unsigned*>(e.dflags + (idx & ~3)), (unsigned)kFlagU << (8 * (idx & 3)));
+            }
         }
 }
 
@@ -528,6 +533,69 @@ __device__ __forceinline__ int tile_prologue_sub(const EdgeDev& e, int seg, int 
     return cnt;
 }
 
+// Variant of tile_prologue for tiles that are th x tw rectangles of the padded window (th * tw <= 256, top-left
+// corner (wy0, wx0)): thread t looks at tile pixel (t / tw, t % tw); the live ones are ranked in that order.
+// Returns their number; rows s_wy / s_wx are filled for them, sh[4] = valid taps of the tile.
+// pub_seg >= 0: the block also ranks list segment pub_seg (256 consecutive window indices) - the flags of both
+// footprints are requested together; pub_off = this thread's position in that segment's compute list or -1,
+// sh[8 .. 11] the entries of the segment per wave.  Nothing is written to global memory here: the wave's later
+// loads would queue behind those stores (tile_effects_2d does it once the tile's own loads are done).
+__device__ __forceinline__ int tile_prologue_2d(const EdgeDev& e, int wy0, int wx0, int th, int tw, int pub_seg, int& pub_off,
+                                                int* s_wy, int* s_wx, int* sh) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) sh[4] = 0;
+    const int ly = tid / tw, lx = tid - ly * tw;
+    const int wy = wy0 + ly, wx = wx0 + lx;
+    const bool in_tile = ly < th && wy < e.Hp && wx < e.Wp;
+    const int p = pub_seg * kSegPixels + tid;
+    const bool in_seg = pub_seg >= 0 && p < e.Hp * e.Wp;
+    int qy = 0, qx = 0;
+    if (in_seg) { qy = p / e.Wp; qx = p - qy * e.Wp; }
+    // both footprints: out-of-range threads read the flags of pixel (0, 0) and are masked afterwards
+    const unsigned vm_t = tap_mask(e, in_tile ? wy - e.by0 : 0, in_tile ? wx - e.bx0 : 0);
+    unsigned vm_p = 0;
+    if (pub_seg >= 0) vm_p = tap_mask(e, in_seg ? qy - e.by0 : 0, in_seg ? qx - e.bx0 : 0);
+    const unsigned vm = in_tile ? vm_t : 0u;
+    const bool has = vm != 0, hasp = in_seg && vm_p != 0;
+    const unsigned long long bal = __ballot(has), balp = __ballot(hasp);
+    const unsigned long long below = (1ull << lane) - 1ull;
+    if (lane == 0) { sh[wave] = __popcll(bal); sh[8 + wave] = __popcll(balp); }
+    __syncthreads();
+    int off = __popcll(bal & below), offp = __popcll(balp & below);
+    for (int i = 0; i < wave; ++i) { off += sh[i]; offp += sh[8 + i]; }
+    const int cnt = sh[0] + sh[1] + sh[2] + sh[3];
+    if (has) {
+        s_wy[off] = wy;
+        s_wx[off] = wx;
+    }
+    pub_off = hasp ? offp : -1;
+    int taps = __popc(vm);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) taps += __shfl_xor(taps, o);
+    if (lane == 0 && taps) atomicAdd(&sh[4], taps);
+    __syncthreads();
+    return cnt;
+}
+
+// What a tile leaves behind besides its sums, after tile_prologue_2d: the touched marks of its `tot` entries and the
+// multiply-accumulate count (touch), the compute list of segment pub_seg and its counts.  No barrier.
+__device__ __forceinline__ void tile_effects_2d(const EdgeDev& e, int tot, bool touch, int pub_seg, int pub_off,
+                                                const int* s_wy, const int* s_wx, const int* sh) {
+    const int tid = threadIdx.x;
+    if (touch) {
+        for (int r = tid; r < tot; r += 256) mark_touched(e, s_wy[r], s_wx[r]);
+        if (tid == 0) add_macs(e, sh[4], 0);
+    }
+    if (pub_seg >= 0) {
+        if (pub_off >= 0) e.clist[pub_seg * kSegPixels + pub_off] = pub_seg * kSegPixels + tid;
+        if (tid == 0) {                                    // single writer per segment: no atomics
+            const int n = sh[8] + sh[9] + sh[10] + sh[11];
+            e.ccnt[pub_seg] = n;
+            e.cacc[pub_seg] += (unsigned long long)n;
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Halo-staged MFMA convolution: KS x KS, stride 1, fp16, weights in the packed
 // order [tap][cin/16][cout][16] (k_pack_weights).
@@ -579,9 +647,11 @@ struct HaloCfg {
     static constexpr int MINB = MINB_;               // tiles per compute unit the registers are budgeted for
 };
 
-template <int NSUB, int WMV, int WK, int TM, int TN, int KC, int NLD_, int KS, int RING_ = 3, int MINB_ = (NSUB >= 2 ? 2 : 1)>
+// T2D: the tiles are th x tw rectangles of the padded window (th * tw <= SUB) instead of index ranges: the staged rectangle
+// is the tile plus its KS - 1 halo whatever the width of the window, so wide rows fit and narrow ones stage less.
+template <int NSUB, int WMV, int WK, int TM, int TN, int KC, int NLD_, int KS, int RING_ = 3, int MINB_ = (NSUB >= 2 ? 2 : 1), bool T2D = false>
 __global__ __launch_bounds__(256, MINB_)
-void k_conv_halo(EdgeBatch eb, int NT, int work_items) {
+void k_conv_halo(EdgeBatch eb, int NT, int work_items, int th, int tw) {
     const EdgeDev& e = eb.d[blockIdx.z];                  // blockIdx.z: stream of the batch
     using Cfg = HaloCfg<NSUB, WMV, WK, TM, TN, KC, NLD_, KS, RING_, MINB_>;
     constexpr int SUB = Cfg::SUB, BN = Cfg::BN, KB = Cfg::KB, MB = Cfg::MB, NS = Cfg::NS, CPR = Cfg::CPR, NLD = Cfg::NLD,
@@ -591,13 +661,14 @@ void k_conv_halo(EdgeBatch eb, int NT, int work_items) {
     float* sC = reinterpret_cast<float*>(smem);          // [SUB][LDC] after it
     int* s_pix = reinterpret_cast<int*>(smem + Cfg::MAIN_BYTES);
     __shared__ int s_wy[SUB], s_wx[SUB];
-    __shared__ int sh[8];
+    __shared__ int sh[12];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform: scalar branches below
     const int wm = wave % WMV, wk = wave / WMV;
     const int r32 = lane & 31, kh = lane >> 5;
-    const int ntiles = edge_segments(e) * NSUB;
+    const int tiles_x = T2D ? (e.Wp + tw - 1) / tw : 1;
+    const int ntiles = T2D ? tiles_x * ((e.Hp + th - 1) / th) : edge_segments(e) * NSUB;
     const int nchunks = e.Cin / KC;
     const int nwin = e.Hp * e.Wp;
     // (the host checks that both tensors are smaller than 2 GiB)
@@ -606,31 +677,66 @@ void k_conv_halo(EdgeBatch eb, int NT, int work_items) {
     const unsigned tap_stride = (unsigned)(e.Cin / 16) * (unsigned)e.Cout * 32u;   // packed weights: bytes per tap
     const unsigned blk_stride = (unsigned)e.Cout * 32u;                            //                 per 16-channel block
 
-    carry_source_compaction(e, sh);
+    // the list L of the source site is a by-product nothing in this launch waits for; with rectangular tiles it is made
+    // after the tiles, where its stores delay no load of a tile
+    if constexpr (!T2D) carry_source_compaction(e, sh);
 
     for (int u = blockIdx.x; u < work_items; u += gridDim.x) {
         const int nt = u % NT, mt = u / NT;              // u % 8 picks the XCD: few cout tiles per XCD
         if (mt >= ntiles) continue;
-        const int seg = mt / NSUB, sub_lo = (mt % NSUB) * SUB;
         const int n0 = nt * BN;
         __syncthreads();                                  // previous tile is done with LDS
-        const int tot = tile_prologue_sub(e, seg, sub_lo, SUB, nt == 0 && sub_lo == 0, nt == 0, s_wy, s_wx, sh);
+        int tot, wyA, wyB, cxA, cxB;                      // entries; window rows and source columns the tile spans
+        constexpr int NRF = (Cfg::CAP + 255) / 256;       // rectangle positions per thread
+        int rpix[NRF];                                    // T2D: source pixel of this thread's positions, -1 outside the view
+        unsigned rflag[NRF];                              //      and its flags, requested together with those of the prologue
+        int pub_seg = -1, pub_off = -1;
+        if constexpr (T2D) {
+            const int ty = mt / tiles_x, tx = mt - ty * tiles_x;
+            wyA = ty * th;
+            wyB = (wyA + th < e.Hp ? wyA + th : e.Hp) - 1;
+            cxA = tx * tw - e.bx0;
+            cxB = (tx * tw + tw < e.Wp ? tx * tw + tw : e.Wp) - 1 - e.bx0;
+            const int ry0 = wyA - e.by0 - e.pad, rx0 = cxA - e.pad, rw = cxB - cxA + KS, rn = (wyB - wyA + KS) * rw;
+#pragma unroll
+            for (int j = 0; j < NRF; ++j) {
+                const int pos = tid + 256 * j;
+                const int ry = pos / rw, iy = ry0 + ry, ix = rx0 + pos - ry * rw;
+                const bool ok = pos < rn && iy >= 0 && iy < e.sH && ix >= 0 && ix < e.sW;
+                rpix[j] = ok ? iy * e.sW + ix : -1;
+                rflag[j] = e.sflags[ok ? rpix[j] : 0];
+            }
+            // every list segment is published by one of the first tiles (there are at least as many tiles as segments)
+            pub_seg = nt == 0 && mt < edge_segments(e) ? mt : -1;
+            tot = tile_prologue_2d(e, ty * th, tx * tw, th, tw, pub_seg, pub_off, s_wy, s_wx, sh);
+            if (tot <= 0) tile_effects_2d(e, 0, false, pub_seg, pub_off, s_wy, s_wx, sh);
+        } else {
+            const int seg = mt / NSUB, sub_lo = (mt % NSUB) * SUB;
+            tot = tile_prologue_sub(e, seg, sub_lo, SUB, nt == 0 && sub_lo == 0, nt == 0, s_wy, s_wx, sh);
+            // the source rectangle this index range reads (block-uniform)
+            const int a = seg * kSegPixels + sub_lo;
+            const int last = (a + SUB < nwin ? a + SUB : nwin) - 1;
+            wyA = a / e.Wp; wyB = last / e.Wp;
+            cxA = wyA == wyB ? a - wyA * e.Wp - e.bx0 : -e.bx0;
+            cxB = wyA == wyB ? last - wyA * e.Wp - e.bx0 : e.Wp - 1 - e.bx0;
+        }
         if (tot <= 0) continue;
-        if (tid == 0 && nt == 0) add_macs(e, sh[4], 0);
-
-        // the source rectangle this index range reads (block-uniform)
-        const int a = seg * kSegPixels + sub_lo;
-        const int last = (a + SUB < nwin ? a + SUB : nwin) - 1;
-        const int wyA = a / e.Wp, wyB = last / e.Wp;
-        const int cxA = wyA == wyB ? a - wyA * e.Wp - e.bx0 : -e.bx0;
-        const int cxB = wyA == wyB ? last - wyA * e.Wp - e.bx0 : e.Wp - 1 - e.bx0;
+        if (!T2D && tid == 0 && nt == 0) add_macs(e, sh[4], 0);
         const int iy0 = wyA - e.by0 - e.pad, ix0 = cxA - e.pad;
         const int RW = cxB - cxA + KS, npos = (wyB - wyA + KS) * RW;       // npos <= CAP: checked by the host
-        for (int pos = tid; pos < npos; pos += 256) {
-            const int ry = pos / RW, rx = pos - ry * RW;
-            const int iy = iy0 + ry, ix = ix0 + rx;
-            const bool ok = iy >= 0 && iy < e.sH && ix >= 0 && ix < e.sW && (e.sflags[iy * e.sW + ix] & kFlagM);
-            s_pix[pos] = ok ? iy * e.sW + ix : -1;
+        if constexpr (T2D) {
+#pragma unroll
+            for (int j = 0; j < NRF; ++j) {
+                const int pos = tid + 256 * j;
+                if (pos < npos) s_pix[pos] = rpix[j] >= 0 && (rflag[j] & kFlagM) ? rpix[j] : -1;
+            }
+        } else {
+            for (int pos = tid; pos < npos; pos += 256) {
+                const int ry = pos / RW, rx = pos - ry * RW;
+                const int iy = iy0 + ry, ix = ix0 + rx;
+                const bool ok = iy >= 0 && iy < e.sH && ix >= 0 && ix < e.sW && (e.sflags[iy * e.sW + ix] & kFlagM);
+                s_pix[pos] = ok ? iy * e.sW + ix : -1;
+            }
         }
         __syncthreads();
         const int nrt = (tot + 31) >> 5;                  // live 32-entry row tiles of the tile
@@ -811,6 +917,11 @@ void k_conv_halo(EdgeBatch eb, int NT, int work_items) {
                 *reinterpret_cast<f16x8*>(pp[t]) = o;
             }
         }
+        if constexpr (T2D) tile_effects_2d(e, tot, nt == 0, pub_seg, pub_off, s_wy, s_wx, sh);
+    }
+    if constexpr (T2D) {
+        __syncthreads();
+        carry_source_compaction(e, sh);
     }
 }
 
@@ -1779,14 +1890,14 @@ static hipError_t launch_tiled_kc(const EdgeBatch& eb, int nb, long long max_ent
     return launch_tiled_p<4, 1, 1, 1, KC>(eb, nb, max_entries, st);                                             // 128 x 32
 }
 
-int g_halo = 1;          // 0: never use the halo-staged kernel, 2: force 32-cout tiles
+int g_halo = 1;          // 0: never use the halo-staged kernel, 2: force 32-cout tiles, 3: tiles are index ranges only
 int g_halo_sub = 0;      // 0: auto, 1 / 2 / 4: tiles per list segment of the halo-staged kernel
 
-template <int NSUB, int WMV, int WK, int TM, int TN, int KC, int NLD, int RING = 3, int MINB = (NSUB >= 2 ? 2 : 1)>
-static hipError_t launch_halo_t(const EdgeBatch& eb, int nb, long long nseg, hipStream_t st) {
+template <int NSUB, int WMV, int WK, int TM, int TN, int KC, int NLD, int RING = 3, int MINB = (NSUB >= 2 ? 2 : 1), bool T2D = false>
+static hipError_t launch_halo_t(const EdgeBatch& eb, int nb, long long nseg, hipStream_t st, int th = 0, int tw = 0) {
     const EdgeDev& e = eb.d[0];
     using Cfg = HaloCfg<NSUB, WMV, WK, TM, TN, KC, NLD, 3, RING, MINB>;
-    auto kern = k_conv_halo<NSUB, WMV, WK, TM, TN, KC, NLD, 3, RING, MINB>;
+    auto kern = k_conv_halo<NSUB, WMV, WK, TM, TN, KC, NLD, 3, RING, MINB, T2D>;
     static std::atomic<bool> attr_set{false};
     if (!attr_set.load(std::memory_order_acquire)) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::SMEM);
@@ -1794,9 +1905,72 @@ static hipError_t launch_halo_t(const EdgeBatch& eb, int nb, long long nseg, hip
         attr_set.store(true, std::memory_order_release);
     }
     const int NT = e.Cout / Cfg::BN;
-    const long long items = nseg * NSUB * NT;
-    kern<<<dim3(cap_blocks(items, 16384), 1, nb), dim3(256), Cfg::SMEM, st>>>(eb, NT, (int)items);
+    const long long tiles = T2D ? (long long)((e.Hp + th - 1) / th) * ((e.Wp + tw - 1) / tw) : nseg * NSUB;
+    const long long items = tiles * NT;
+    kern<<<dim3(cap_blocks(items, 16384), 1, nb), dim3(256), Cfg::SMEM, st>>>(eb, NT, (int)items, th, tw);
     return hipGetLastError();
+}
+
+// Rectangle th x tw of at most `sub` pixels whose halo fits `cap` staged pixels, with the fewest tiles over an Hp x Wp window
+// (ties: the smaller halo).  False if none fits.
+static bool tile_2d(int Hp, int Wp, int k, int sub, int cap, int* th_out, int* tw_out, long long* tiles_out) {
+    long long best = -1, best_halo = 0;
+    for (int th = 1; th <= sub && th <= Hp; ++th) {
+        int tw = sub / th < Wp ? sub / th : Wp;
+        while (tw > 1 && (long long)(th + k - 1) * (tw + k - 1) > cap) --tw;
+        if ((long long)(th + k - 1) * (tw + k - 1) > cap) continue;
+        // the narrowest tile with the same number of columns of tiles
+        const int cols = (Wp + tw - 1) / tw;
+        tw = (Wp + cols - 1) / cols;
+        const long long tiles = (long long)((Hp + th - 1) / th) * cols, halo = (long long)(th + k - 1) * (tw + k - 1);
+        if (best < 0 || tiles < best || (tiles == best && halo < best_halo)) { best = tiles; best_halo = halo; *th_out = th; *tw_out = tw; }
+    }
+    if (best < 0) return false;
+    *tiles_out = best;
+    return true;
+}
+
+// Rectangular tiles.  The tile size follows the number of tiles of ONE stream, whatever the batch - the K split of a
+// tile fixes the order of the sums, and a stream in a batch must give the bits it gives alone: whole segments if that
+// gives every compute unit a tile, else the smallest split that gives half of them one.  A whole-segment tile keeps its
+// four waves on rows (no K split: 64 accumulator registers, two tiles per compute unit); it is what the 64-channel
+// layers with rows wider than a segment use.  With many streams to a launch whole segments are the faster choice
+// everywhere (ResNet-18-style network, 16 videos: 4.1 k frames/s against 3.9 k; one video: 3.5 k against 3.7 k): a caller
+// who serves batches sets MDCNN_OPT_CONV_HALO_SUB to 1.  128-channel chunks (half the chunk boundaries) were measured
+// too: no faster alone or in a batch, so chunks stay at 64 channels.
+template <int TN>
+static hipError_t launch_halo_2d(const EdgeBatch& eb, int nb, hipStream_t st, bool* done) {
+    const EdgeDev& e = eb.d[0];
+    const int NT = e.Cout / (32 * TN);
+    const bool c64 = e.Cin % 64 == 0, c32 = e.Cin % 32 == 0;
+    int th = 0, tw = 0;
+    long long tiles = 0;
+    *done = true;
+    const int first = g_halo_sub ? g_halo_sub : 1;
+    for (int nsub = first; nsub <= 4; nsub *= 2) {
+        const int sub = kSegPixels / nsub;
+        // whole segments if every compute unit gets a tile, else the smallest split that gives at least half of them one
+        // (a forced split is taken as it is)
+        if (!g_halo_sub && nsub < 4 && tile_2d(e.Hp, e.Wp, e.k, sub, 1 << 20, &th, &tw, &tiles) && tiles * NT < (nsub == 1 ? 256 : 128)) continue;
+        if (nsub == 1) {
+            if (c64 && tile_2d(e.Hp, e.Wp, e.k, sub, HaloCfg<1, 4, 1, 2, TN, 64, 11, 3>::CAP, &th, &tw, &tiles))
+                return launch_halo_t<1, 4, 1, 2, TN, 64, 11, 6, 2, true>(eb, nb, 0, st, th, tw);
+            if (c32 && tile_2d(e.Hp, e.Wp, e.k, sub, HaloCfg<1, 4, 1, 2, TN, 32, 6, 3>::CAP, &th, &tw, &tiles))
+                return launch_halo_t<1, 4, 1, 2, TN, 32, 6, 3, 2, true>(eb, nb, 0, st, th, tw);
+        } else if (nsub == 2) {
+            if (c64 && tile_2d(e.Hp, e.Wp, e.k, sub, HaloCfg<2, 2, 2, 2, TN, 64, 6, 3>::CAP, &th, &tw, &tiles))
+                return launch_halo_t<2, 2, 2, 2, TN, 64, 6, 6, 2, true>(eb, nb, 0, st, th, tw);
+            if (c32 && tile_2d(e.Hp, e.Wp, e.k, sub, HaloCfg<2, 2, 2, 2, TN, 32, 3, 3>::CAP, &th, &tw, &tiles))
+                return launch_halo_t<2, 2, 2, 2, TN, 32, 3, 3, 2, true>(eb, nb, 0, st, th, tw);
+        } else {
+            if (c64 && tile_2d(e.Hp, e.Wp, e.k, sub, HaloCfg<4, 1, 4, 2, TN, 64, 4, 3>::CAP, &th, &tw, &tiles))
+                return launch_halo_t<4, 1, 4, 2, TN, 64, 4, 9, 2, true>(eb, nb, 0, st, th, tw);
+            if (c32 && tile_2d(e.Hp, e.Wp, e.k, sub, HaloCfg<4, 2, 2, 1, TN, 32, 2, 3>::CAP, &th, &tw, &tiles))
+                return launch_halo_t<4, 2, 2, 1, TN, 32, 2, 9, 2, true>(eb, nb, 0, st, th, tw);
+        }
+    }
+    *done = false;
+    return hipSuccess;
 }
 
 // Staged pixels the rectangle of `sub` consecutive window indices can need.
@@ -1843,6 +2017,10 @@ static hipError_t launch_halo(const EdgeBatch& eb, int nb, long long nseg, hipSt
     if (!g_halo || !e.wp || e.k != 3 || e.stride != 1 || e.up != 0 || e.Cin % 16 || e.Cout % 32) return hipSuccess;
     if ((long long)e.sH * e.sW * e.Cin >= (1ll << 30) || (long long)e.k * e.k * e.Cin * e.Cout >= (1ll << 30))
         return hipSuccess;                                                     // 32-bit byte offsets into deltas and weights
+    if (g_halo != 3) {                                                         // rectangular tiles where they fit
+        const hipError_t err = e.Cout % 64 == 0 && g_halo != 2 ? launch_halo_2d<2>(eb, nb, st, done) : launch_halo_2d<1>(eb, nb, st, done);
+        if (err != hipSuccess || *done) return err;
+    }
     return e.Cout % 64 == 0 && g_halo != 2 ? launch_halo_n<2>(eb, nb, nseg, st, done) : launch_halo_n<1>(eb, nb, nseg, st, done);
 }
 
