@@ -677,9 +677,7 @@ void k_conv_halo(EdgeBatch eb, int NT, int work_items, int th, int tw) {
     const unsigned tap_stride = (unsigned)(e.Cin / 16) * (unsigned)e.Cout * 32u;   // packed weights: bytes per tap
     const unsigned blk_stride = (unsigned)e.Cout * 32u;                            //                 per 16-channel block
 
-    // the list L of the source site is a by-product nothing in this launch waits for; with rectangular tiles it is made
-    // after the tiles, where its stores delay no load of a tile
-    if constexpr (!T2D) carry_source_compaction(e, sh);
+    carry_source_compaction(e, sh);
 
     for (int u = blockIdx.x; u < work_items; u += gridDim.x) {
         const int nt = u % NT, mt = u / NT;              // u % 8 picks the XCD: few cout tiles per XCD
@@ -918,10 +916,6 @@ void k_conv_halo(EdgeBatch eb, int NT, int work_items, int th, int tw) {
             }
         }
         if constexpr (T2D) tile_effects_2d(e, tot, nt == 0, pub_seg, pub_off, s_wy, s_wx, sh);
-    }
-    if constexpr (T2D) {
-        __syncthreads();
-        carry_source_compaction(e, sh);
     }
 }
 
