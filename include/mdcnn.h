@@ -466,7 +466,9 @@ typedef enum {
     MDCNN_OPT_CONV_KC = 5,   /* tuning: 0 auto, 64 cap the K step at 64 channels           */
     MDCNN_OPT_CONV_HALO = 6, /* tuning: 1 (default) packed-weights kernel where it applies,  */
                              /* 0 never, 2 with 32-cout tiles, 3 with tiles that are index  */
-                             /* ranges of the padded window instead of rectangles           */
+                             /* ranges of the padded window instead of rectangles, 4 with   */
+                             /* rectangles also for windows of less than 4096 pixels (which */
+                             /* take index ranges by default)                               */
     MDCNN_OPT_CONV_HALO_SUB = 7, /* 0 auto (by the tiles one video gives a launch), 1 / 2 / 4: tiles of a whole, */
                              /* half or quarter list segment (256 pixels) in that kernel; 1 is the faster choice for */
                              /* batches of many videos.  The split fixes the order of the sums: runs that are to  */

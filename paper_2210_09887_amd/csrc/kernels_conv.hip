@@ -1897,7 +1897,8 @@ static hipError_t launch_tiled_kc(const EdgeBatch& eb, int nb, long long max_ent
     return launch_tiled_p<4, 1, 1, 1, KC>(eb, nb, max_entries, st);                                             // 128 x 32
 }
 
-int g_halo = 1;          // 0: never use the halo-staged kernel, 2: force 32-cout tiles, 3: tiles are index ranges only
+int g_halo = 1;          // 0: never use the halo-staged kernel, 2: force 32-cout tiles, 3: tiles are index ranges only,
+                         // 4: rectangular tiles whatever the size of the window
 int g_halo_sub = 0;      // 0: auto, 1 / 2 / 4: tiles per list segment of the halo-staged kernel
 
 template <int NSUB, int WMV, int WK, int TM, int TN, int KC, int NLD, int RING = 3, int MINB = (NSUB >= 2 ? 2 : 1), bool T2D = false>
@@ -2024,7 +2025,10 @@ static hipError_t launch_halo(const EdgeBatch& eb, int nb, long long nseg, hipSt
     if (!g_halo || !e.wp || e.k != 3 || e.stride != 1 || e.up != 0 || e.Cin % 16 || e.Cout % 32) return hipSuccess;
     if ((long long)e.sH * e.sW * e.Cin >= (1ll << 30) || (long long)e.k * e.k * e.Cin * e.Cout >= (1ll << 30))
         return hipSuccess;                                                     // 32-bit byte offsets into deltas and weights
-    if (g_halo != 3) {                                                         // rectangular tiles where they fit
+    // rectangular tiles where they fit; windows of a few list segments stay on index ranges (measured on the HRNet-like
+    // network, whose lower branches have 50 x 38 pixels and less: 15.5 against 16.3 us per launch - a tile's by-products are
+    // stored at its end there, which a launch of a few blocks has nothing to hide behind)
+    if (g_halo != 3 && ((long long)e.Hp * e.Wp >= 4096 || g_halo == 4)) {
         const hipError_t err = e.Cout % 64 == 0 && g_halo != 2 ? launch_halo_2d<2>(eb, nb, st, done) : launch_halo_2d<1>(eb, nb, st, done);
         if (err != hipSuccess || *done) return err;
     }

@@ -1170,7 +1170,7 @@ const char* mdcnn_version(void) { return "mdcnn 0.1 (gfx950)"; }
 
 mdcnn_status mdcnn_set_option(int option, int value) {
     if (option == MDCNN_OPT_CONV_PATH && value >= 0 && value <= 3) { g_conv_path = value; return MDCNN_OK; }
-    if (option == MDCNN_OPT_CONV_HALO && value >= 0 && value <= 3) { g_halo = value; return MDCNN_OK; }
+    if (option == MDCNN_OPT_CONV_HALO && value >= 0 && value <= 4) { g_halo = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_STREAMS && value >= 0 && value <= kMaxStreams) { g_streams = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_PIPE_GROUP && value >= 0 && value <= 64) { g_pipe_group = value; return MDCNN_OK; }
     if (option == MDCNN_OPT_PIPE_MODE && (value == 0 || value == 1)) { g_pipe_mode = value; return MDCNN_OK; }

@@ -76,7 +76,7 @@ def test_options_accept_their_documented_values_only():
     """mdcnn_set_option is host-only: every option takes its documented range and refuses the next value."""
     ranges = {
         B.MDCNN_OPT_CONV_PATH: (0, 3), B.MDCNN_OPT_PROFILE: (0, 1), B.MDCNN_OPT_CONV_XCD: (0, 1),
-        B.MDCNN_OPT_CONV_HALO: (0, 2), B.MDCNN_OPT_FUSE_SKIP: (0, 1), B.MDCNN_OPT_PIPE_MODE: (0, 1),
+        B.MDCNN_OPT_CONV_HALO: (0, 4), B.MDCNN_OPT_FUSE_SKIP: (0, 1), B.MDCNN_OPT_PIPE_MODE: (0, 1),
         B.MDCNN_OPT_PIPE_THREADS: (0, 1), B.MDCNN_OPT_CONV_F32_MFMA: (0, 1), B.MDCNN_OPT_PIPE_GROUP: (0, 64),
     }
     defaults = {B.MDCNN_OPT_CONV_XCD: 1, B.MDCNN_OPT_CONV_HALO: 1, B.MDCNN_OPT_FUSE_SKIP: 1, B.MDCNN_OPT_PIPE_MODE: 1,

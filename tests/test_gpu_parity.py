@@ -324,6 +324,60 @@ def test_conv_kernel_shapes(cin, cout, H, W, k, stride):
     log(f"[conv shapes] {cin}->{cout} {H}x{W} k{k} s{stride}: worst {worst:.3e}")
 
 
+@pytest.mark.parametrize("cin,cout,H,W,sub", [
+    (64, 64, 40, 56, 1),           # whole-segment rectangles, no K split, 64-channel chunk; ragged last tiles in both directions
+    (32, 32, 24, 88, 1),           # the same with a 32-channel chunk and 32-cout tiles
+    (128, 64, 40, 40, 2),          # half-segment rectangles, K split two ways, two chunks
+    (96, 64, 33, 47, 2),           # 32-channel chunks (three of them), odd window
+    (256, 128, 16, 24, 4),         # quarter-segment rectangles, K split four ways, four chunks, two cout tiles
+    (32, 32, 9, 70, 4),            # quarter segments with 32-channel chunks; a window lower than a tile is high
+    (64, 64, 72, 96, 0),           # the library's own choice on a window of more than 4096 pixels
+])
+def test_halo_kernel_on_rectangular_tiles(cin, cout, H, W, sub):
+    """The halo-staged kernel with rectangular tiles in each of its configurations, forced for windows the library would
+    give index-range tiles: a dense frame, a sparse frame and a frame after a camera shift, teacher-forced against the
+    oracle (masks, lists and compute lists bit for bit), and the same frames with index-range tiles: the same bits in
+    every output (both walk the chunks and taps of an entry in the same order)."""
+    import gpu_harness as H_
+    from inputs.nets import tiny_net
+    from paper_2210_09887_amd import binding as B
+    from paper_2210_09887_amd.runtime import GpuNet
+    net = tiny_net("f16", H, W, (cin, cout), k=3, stride=1, theta=0.05, seed=cin + cout + H, total_stride=1)
+    rng = np.random.default_rng(cin * 1000 + cout + W)
+    x = rng.normal(0, 1, (H, W, cin)).astype(np.float32)
+    frames = [x.astype(np.float16)]
+    for _ in range(2):
+        x = x.copy()
+        y0, x0 = int(rng.integers(0, max(1, H - 8))), int(rng.integers(0, max(1, W - 17)))
+        x[y0:y0 + 8, x0:x0 + 17] += rng.normal(0, 1, x[y0:y0 + 8, x0:x0 + 17].shape).astype(np.float32)
+        x[rng.random((H, W)) < 0.02] += 0.5
+        frames.append(x.astype(np.float16))
+    shifts = [(0, 0), (0, 0), (1, -1)]
+
+    def outputs():
+        g = GpuNet(net)
+        try:
+            return [g.frame(H_.dev(f), dy, dx)[0].cpu().numpy().copy() for f, (dy, dx) in zip(frames, shifts)]
+        finally:
+            g.close()
+
+    try:
+        B.mdcnn_set_option(B.MDCNN_OPT_CONV_HALO, 4)
+        B.mdcnn_set_option(B.MDCNN_OPT_CONV_HALO_SUB, sub)
+        worst = H_.teacher_forced(net, frames, shifts, log=log)
+        rect = outputs()
+        B.mdcnn_set_option(B.MDCNN_OPT_CONV_HALO, 3)
+        ranges = outputs()
+    finally:
+        B.mdcnn_set_option(B.MDCNN_OPT_CONV_HALO, 1)
+        B.mdcnn_set_option(B.MDCNN_OPT_CONV_HALO_SUB, 0)
+    log(f"[rectangular tiles] {cin}->{cout} {H}x{W} split {sub}: worst {worst:.3e}")
+    if sub in (2, 4):  # (whole-segment tiles: the rectangles do not split K, the index ranges do - other sums; left to
+                       # themselves the two may also choose different splits)
+        for t, (a, b) in enumerate(zip(rect, ranges)):
+            assert np.array_equal(a, b), f"frame {t}: rectangular and index-range tiles differ"
+
+
 def random_conv_cases(n=28, seed=2210):
     """Seeded single-convolution networks over the corners no named workload reaches: odd channel
     counts, 5x5 kernels, strides 3 and 4, 1x1 strided, both storage types."""
