@@ -201,8 +201,9 @@ def run_batched(a, cfg, net, T, frames, shifts, forced, fused):
     from paper_2210_09887_amd import binding as B
     from paper_2210_09887_amd.runtime import GpuBatch
     n = a.streams
-    # with many videos to a launch whole-segment convolution tiles are the faster choice (the default follows one video)
-    whole_tiles = not any(o.startswith("7=") for o in a.opt)
+    # with many videos of the ResNet-18-style network to a launch whole-segment convolution tiles are the faster choice (the
+    # default follows one video); the small maps of the other networks are better off with the default
+    whole_tiles = cfg == 3 and not any(o.startswith("7=") for o in a.opt)
     if whole_tiles:
         B.mdcnn_set_option(B.MDCNN_OPT_CONV_HALO_SUB, 1)
     gb = GpuBatch(net, n)
