@@ -286,6 +286,22 @@ mdcnn_status mdcnn_frame_batch(mdcnn_net* const* nets, int n_streams, const void
                                const uint8_t* const* forced_masks_dev, const int* dty, const int* dtx,
                                void* const* outs_dev, size_t out_bytes, void* stream, int* did_full_reset);
 
+/* mdcnn_frame_batch for cropped frames: stream b takes its frame with the crop
+ * crops[4b .. 4b+3] = (ty0, tx0, th, tw) in tiles of the view, as mdcnn_frame_crop
+ * does - every stream its own crop, camera path and output size (out_bytes[b] = the
+ * summed crop sizes of the OUTPUT sites of stream b; frames_dev[b], its forced mask and
+ * outs_dev[b] have that crop's extent).  All sites of all streams need crops == 1; the
+ * crops stay in force afterwards.  The results of every stream are identical, bit for
+ * bit, to those of mdcnn_frame_crop on it alone  [Supplementary: cropped frames;
+ * Evaluation: batch size].
+ * Errors: those of mdcnn_frame_batch and mdcnn_frame_crop, checked for all streams
+ * before anything changes. */
+mdcnn_status mdcnn_frame_batch_crop(mdcnn_net* const* nets, int n_streams,
+                                    const void* const* frames_dev,
+                                    const uint8_t* const* forced_masks_dev, const int* dty,
+                                    const int* dtx, const int* crops, void* const* outs_dev,
+                                    const size_t* out_bytes, void* stream, int* did_full_reset);
+
 /* A run of n_frames consecutive frames of ONE video in one call, frame f being what
  * mdcnn_frame(net, frames_dev[f], forced_masks_dev[f], dty[f], dtx[f], outs_dev[f])
  * does: the frames are taken in order and every result - outputs and all state of the

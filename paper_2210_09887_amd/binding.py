@@ -30,7 +30,7 @@ STATUS_NAMES = {0: "OK", 1: "ERR_NULL", 2: "ERR_SHAPE", 3: "ERR_DTYPE", 4: "ERR_
 
 EXPORTS = ["mdcnn_conv_border", "mdcnn_buffer_bytes", "mdcnn_create_buffer", "mdcnn_destroy_buffer",
            "mdcnn_shift_camera", "mdcnn_set_crop", "mdcnn_layer_forward", "mdcnn_layer_forward_noalloc", "mdcnn_net_create", "mdcnn_net_destroy",
-           "mdcnn_frame", "mdcnn_frame_crop", "mdcnn_frame_batch", "mdcnn_frame_plan", "mdcnn_frames", "mdcnn_frames_batch", "mdcnn_frames_crop", "mdcnn_frames_masked", "mdcnn_frames_plan", "mdcnn_input_mask", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read", "mdcnn_profile_read_launches", "mdcnn_bench_copy", "mdcnn_bench_mfma",
+           "mdcnn_frame", "mdcnn_frame_crop", "mdcnn_frame_batch", "mdcnn_frame_batch_crop", "mdcnn_frame_plan", "mdcnn_frames", "mdcnn_frames_batch", "mdcnn_frames_crop", "mdcnn_frames_masked", "mdcnn_frames_plan", "mdcnn_input_mask", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read", "mdcnn_profile_read_launches", "mdcnn_bench_copy", "mdcnn_bench_mfma",
            "mdcnn_pack_weights", "mdcnn_last_error", "mdcnn_version"]
 
 
@@ -84,6 +84,7 @@ def lib():
         L.mdcnn_frame_batch.argtypes = [C.POINTER(vp), C.c_int, C.POINTER(vp), C.POINTER(vp), ip, ip, C.POINTER(vp), sz, vp, ip]
         L.mdcnn_frame_plan.argtypes = [vp, C.c_int, ip, ip, C.c_int, ip, ip]
         L.mdcnn_frames.argtypes = [vp, C.c_int, C.POINTER(vp), C.POINTER(vp), ip, ip, C.POINTER(vp), sz, C.c_int, vp, ip]
+        L.mdcnn_frame_batch_crop.argtypes = [C.POINTER(vp), C.c_int, C.POINTER(vp), C.POINTER(vp), ip, ip, ip, C.POINTER(vp), C.POINTER(sz), vp, ip]
         L.mdcnn_frames_batch.argtypes = [C.POINTER(vp), C.c_int, C.c_int, C.POINTER(vp), C.POINTER(vp), ip, ip, C.POINTER(vp), sz, C.c_int, vp, ip]
         L.mdcnn_frames_crop.argtypes = [vp, C.c_int, C.POINTER(vp), C.POINTER(vp), ip, ip, ip, C.POINTER(vp), C.POINTER(sz), C.c_int, vp, ip]
         L.mdcnn_frames_masked.argtypes = [vp, C.c_int, C.POINTER(vp), C.POINTER(vp), C.POINTER(mdcnn_mask_params), C.POINTER(vp), sz, ip, ip,
@@ -241,6 +242,18 @@ def mdcnn_frame_batch(nets, frame_ptrs, forced_ptrs, dty, dtx, out_ptrs, out_byt
     _check(lib().mdcnn_frame_batch(_handles(nets), n, (C.c_void_p * n)(*frame_ptrs), forced,
                                    (C.c_int * n)(*[int(v) for v in dty]), (C.c_int * n)(*[int(v) for v in dtx]),
                                    (C.c_void_p * n)(*out_ptrs), out_bytes, stream, r))
+    return [bool(v) for v in r]
+
+
+def mdcnn_frame_batch_crop(nets, frame_ptrs, forced_ptrs, dty, dtx, crops, out_ptrs, out_bytes, stream: int = 0):
+    """One cropped frame for len(nets) streams, crops[b] = (ty0, tx0, th, tw); returns the list of reset decisions."""
+    n = len(nets)
+    r = (C.c_int * n)()
+    forced = None if forced_ptrs is None else (C.c_void_p * n)(*forced_ptrs)
+    flat = [int(v) for c in crops for v in c]
+    _check(lib().mdcnn_frame_batch_crop(_handles(nets), n, (C.c_void_p * n)(*frame_ptrs), forced,
+                                        (C.c_int * n)(*[int(v) for v in dty]), (C.c_int * n)(*[int(v) for v in dtx]), (C.c_int * (4 * n))(*flat),
+                                        (C.c_void_p * n)(*out_ptrs), (C.c_size_t * n)(*[int(v) for v in out_bytes]), stream, r))
     return [bool(v) for v in r]
 
 

@@ -1522,6 +1522,45 @@ mdcnn_status mdcnn_frame_batch(mdcnn_net* const* nets, int n_streams, const void
     return MDCNN_OK;
 }
 
+mdcnn_status mdcnn_frame_batch_crop(mdcnn_net* const* nets, int n_streams, const void* const* frames_dev,
+                                    const uint8_t* const* forced_masks_dev, const int* dty, const int* dtx, const int* crops,
+                                    void* const* outs_dev, const size_t* out_bytes, void* stream, int* did_full_reset) {
+    if (!nets || !frames_dev || !dty || !dtx || !crops || !outs_dev || !out_bytes) return fail(MDCNN_ERR_NULL, "frame_batch_crop: NULL argument");
+    if (n_streams < 1 || n_streams > kMaxBatchStreams) return fail(MDCNN_ERR_SIZE, "frame_batch_crop: 1 <= n_streams <= %d", kMaxBatchStreams);
+    const uint8_t* no_forced[kMaxBatchStreams] = {};
+    // all checks first: a refused call changes nothing
+    for (int b = 0; b < n_streams; ++b) {
+        if (!nets[b] || !frames_dev[b] || !outs_dev[b]) return fail(MDCNN_ERR_NULL, "frame_batch_crop: stream %d: net/frame/out is NULL", b);
+        if (((uintptr_t)frames_dev[b] | (uintptr_t)outs_dev[b]) & 15) return fail(MDCNN_ERR_ALIGN, "frame_batch_crop: stream %d: frame/out must be 16-byte aligned", b);
+        if (b && !same_shape(nets[0], nets[b])) return fail(MDCNN_ERR_SHAPE, "frame_batch_crop: stream %d differs from stream 0 in topology or shapes", b);
+        for (int c = 0; c < b; ++c)
+            if (nets[c] == nets[b] || nets[c]->sites[0] == nets[b]->sites[0])
+                return fail(MDCNN_ERR_STATE, "frame_batch_crop: streams %d and %d share a network or buffers", c, b);
+        const int ty0 = crops[4 * b], tx0 = crops[4 * b + 1], th = crops[4 * b + 2], tw = crops[4 * b + 3];
+        size_t need = 0;
+        for (const mdcnn_buffer* s : nets[b]->sites) {
+            const mdcnn_buffer_desc& d = s->d;
+            if (!d.crops) return fail(MDCNN_ERR_STATE, "frame_batch_crop: stream %d: the network was created without crops", b);
+            if (ty0 < 0 || tx0 < 0 || th < 1 || tw < 1 || ((long long)ty0 + th) * d.tile > d.H || ((long long)tx0 + tw) * d.tile > d.W)
+                return fail(MDCNN_ERR_SHAPE, "frame_batch_crop: stream %d: crop of %dx%d tiles at (%d, %d) leaves a view of %dx%d pixels (tile %d)", b, th, tw, ty0, tx0, d.H, d.W, d.tile);
+            if (d.kind == MDCNN_SITE_OUTPUT) need += (size_t)th * d.tile * tw * d.tile * d.C * esize(d.dtype);
+        }
+        if (out_bytes[b] != need) return fail(MDCNN_ERR_SIZE, "frame_batch_crop: stream %d: out_bytes is %zu, the cropped outputs take %zu", b, out_bytes[b], need);
+    }
+    for (int b = 0; b < n_streams; ++b) {
+        const mdcnn_status rc = mdcnn_set_crop(nets[b]->sites.data(), (int)nets[b]->sites.size(), crops[4 * b], crops[4 * b + 1], crops[4 * b + 2], crops[4 * b + 3]);
+        if (rc) return rc;
+    }
+    if (!forced_masks_dev) forced_masks_dev = no_forced;
+    for (int b0 = 0; b0 < n_streams; b0 += kMaxBatch) {
+        const int nb = n_streams - b0 < kMaxBatch ? n_streams - b0 : kMaxBatch;
+        const mdcnn_status rc = frame_batch(nets + b0, nb, frames_dev + b0, forced_masks_dev + b0, dty + b0, dtx + b0, outs_dev + b0, stream,
+                                            did_full_reset ? did_full_reset + b0 : nullptr);
+        if (rc) return rc;
+    }
+    return MDCNN_OK;
+}
+
 // Checks shared by mdcnn_frames and mdcnn_frames_crop; out_bytes[f] (crops) or out_bytes[0] (none) per frame.
 static mdcnn_status frames_checked(mdcnn_net* net, int n_frames, const void* const* frames_dev, const uint8_t* const* forced_masks_dev,
                                    const int* dty, const int* dtx, const int* crops, const FrontEnd* fe, void* const* outs_dev,

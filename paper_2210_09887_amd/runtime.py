@@ -262,11 +262,11 @@ class GpuBatch:
     """n independent streams of one network behind mdcnn_frame_batch: own buffers and
     camera paths, shared weights.  Marshalling only."""
 
-    def __init__(self, spec, n_streams, device="cuda:0"):
-        first = GpuNet(spec, device=device)
+    def __init__(self, spec, n_streams, device="cuda:0", crops=False):
+        first = GpuNet(spec, device=device, crops=crops)
         self.streams = [first]
         for _ in range(n_streams - 1):
-            g = GpuNet(spec, device=device, share_weights=first)
+            g = GpuNet(spec, device=device, share_weights=first, crops=crops)
             g.keep_alive(first)
             self.streams.append(g)
 
@@ -278,6 +278,27 @@ class GpuBatch:
                                 None if forced is None else [None if f is None else f.data_ptr() for f in forced],
                                 dty, dtx, [o.data_ptr() for o in outs], g0.out.numel() * g0.esize, g0._stream())
         return outs, r
+
+    def frame_crop(self, frames, dty, dtx, crops, forced=None):
+        """frames[b]: device tensor covering crops[b] = (ty0, tx0, th, tw) at the input site of stream b.  Returns (per
+        stream the list of output tensors in crop order, list of reset flags)."""
+        ns = [sum(int(c[2]) * g.tile[i] * int(c[3]) * g.tile[i] * g.shape[i][2] for i in g.terminals) for g, c in zip(self.streams, crops)]
+        outs = [g.out[:n] for g, n in zip(self.streams, ns)]
+        g0 = self.streams[0]
+        r = B.mdcnn_frame_batch_crop([g.net for g in self.streams], [x.data_ptr() for x in frames],
+                                     None if forced is None else [None if f is None else f.data_ptr() for f in forced],
+                                     dty, dtx, crops, [o.data_ptr() for o in outs], [n * g0.esize for n in ns], g0._stream())
+        res = []
+        for g, c, out in zip(self.streams, crops, outs):
+            g.crop = tuple(int(v) for v in c)
+            per, o = [], 0
+            for i in g.terminals:
+                shp = g.crop_shape(i)
+                m = int(np.prod(shp))
+                per.append(out[o:o + m].reshape(shp))
+                o += m
+            res.append(per)
+        return res, r
 
     def frames(self, frames, dty, dtx, forced=None, outs=None, depth=0):
         """frames[f][b]: frame f of video b (device tensors), dty / dtx / forced alike.  Returns (outs[f][b], resets[f][b])."""

@@ -150,6 +150,10 @@ def test_pack_weights_and_batch_argument_checks_need_no_gpu():
     for n in (0, 129):                        # more streams than a call takes: refused before any handle is read
         with pytest.raises(B.MdcnnError):
             B.mdcnn_frame_batch([4096] * n, [4096] * n, None, [0] * n, [0] * n, [4096] * n, 16)
+        with pytest.raises(B.MdcnnError):
+            B.mdcnn_frame_batch_crop([4096] * n, [4096] * n, None, [0] * n, [0] * n, [(0, 0, 1, 1)] * n, [4096] * n, [16] * n)
+        with pytest.raises(B.MdcnnError):
+            B.mdcnn_frames_batch([4096] * n, [[4096] * n], None, [[0] * n], [[0] * n], [[4096] * n], 16)
 
 
 def test_crop_argument_checks_need_no_gpu():

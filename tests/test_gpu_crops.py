@@ -202,3 +202,98 @@ def test_random_chains_with_crops(case):
     shifts = [(0, 0), (0, 1), (1, 0), (0, 0), (-1, 0), (0, 0)]        # frame 4 reverses: full reset
     worst = H.teacher_forced(net, frames, shifts, crops=rand_crops(net, 6, sum(C) + k, full_first=bool(k % 2 == 1 and stride < 3)))
     log(f"[random chains with crops] {case}: worst {worst:.3e}")
+
+
+@pytest.mark.parametrize("name", ["c2_cnn5_88x72", "c3_resnet_plain_80x112"])
+def test_batch_of_cropped_streams_against_per_stream_oracles(name):
+    """mdcnn_frame_batch_crop at threshold 0 in fp32 (no mask depends on a rounding): three streams with crops and camera
+    paths of their own share their launches; every stream follows an oracle of its own - outputs to the fp32 tolerance,
+    reset decisions, input-site lists and crop state exact."""
+    import gpu_harness as H
+    from oracle.mdcnn_oracle import OracleNet
+    from paper_2210_09887_amd import binding as B
+    from paper_2210_09887_amd.runtime import GpuBatch
+    cfg, kn, ks, _ = crop_cases()[name]
+    net, seq = build_net(cfg, **kn), build_sequence(cfg, **ks)
+    net.dtype = "f32"
+    for e in net.edges:
+        if e.w is not None:
+            e.w = e.w.astype(np.float32)
+    for s in net.sites:
+        s.theta = 0.0
+    n, T = 3, len(seq.frames) - 2
+    crops = [rand_crops(net, T, 5 + b, full_first=b != 1) for b in range(n)]      # stream 1 starts with a partial frame
+    paths = [[(int(v[0]), int(v[1])) for v in seq.shifts[b:b + T]] for b in range(n)]
+    paths[2] = [(0, 0), (0, 1), (0, 1), (0, -1)] + [(1, 0)] * T                    # the fourth frame of stream 2 steps back: reset
+    gb, os_ = GpuBatch(net, n, crops=True), [OracleNet(net, crops=True) for _ in range(n)]
+    try:
+        resets = 0
+        for t in range(T):
+            cs = [crops[b][t] for b in range(n)]
+            Xs = [H.cut(net, seq.frames[b + t].astype(np.float32), cs[b]) for b in range(n)]
+            dys, dxs = [paths[b][t][0] for b in range(n)], [paths[b][t][1] for b in range(n)]
+            got, rs = gb.frame_crop([H.dev(X) for X in Xs], dys, dxs, cs)
+            torch.cuda.synchronize()
+            for b in range(n):
+                want, r_o = os_[b].frame(Xs[b], dys[b], dxs[b], crop=cs[b])
+                assert bool(rs[b]) == bool(r_o), f"frame {t} stream {b}: reset decision"
+                resets += bool(r_o) and t > 0
+                for a, w in zip(got[b], want):
+                    assert a.shape == w.shape
+                    assert H.maxerr(a.cpu().numpy(), w) < 1e-4, f"frame {t} stream {b}"
+                g = gb.streams[b]
+                assert np.array_equal(g.read(0, B.MDCNN_VIEW_LIST), os_[b].sites[0].L), f"frame {t} stream {b}: input list"
+                for i, s in enumerate(os_[b].sites):
+                    if s.spec.kind != "output":
+                        assert np.array_equal(g.read(i, B.MDCNN_VIEW_PENDING) & B.STATE_UNSEEN, H.oracle_pending(s) & B.STATE_UNSEEN)
+        assert resets >= 1
+    finally:
+        gb.close()
+
+
+@pytest.mark.parametrize("name", ["c3_resnet_96", "c4_hrnet_128x96", "c3_resnet_poolstem_128"])
+def test_batch_of_cropped_streams_equals_single_streams(name):
+    """Every stream of mdcnn_frame_batch_crop gives the bits mdcnn_frame_crop gives on it alone (which the teacher-forced
+    tests above hold against the oracle): outputs, reset decisions and all state at the end; 18 streams, so that the
+    library has to split them into two groups of launches."""
+    import gpu_harness as H
+    from test_gpu_frames import state_of
+    from paper_2210_09887_amd.runtime import GpuBatch, GpuNet
+    cfg, kn, ks, _ = crop_cases()[name]
+    net, seq = build_net(cfg, **kn), build_sequence(cfg, **ks)
+    n, T = 18, 5
+    rng = np.random.default_rng(3)
+    start = [int(rng.integers(0, len(seq.frames) - T + 1)) for _ in range(n)]
+    crops = [rand_crops(net, T, 40 + b, full_first=b % 3 != 1, full_last=False) for b in range(n)]
+    paths = [[(0, 0)] + [(int(rng.integers(-1, 2)), int(rng.integers(-1, 2))) for _ in range(T - 1)] for _ in range(n)]
+    check = (0, 1, 7, 15, 16, 17)
+    want = {}
+    for b in check:
+        g = GpuNet(net, crops=True)
+        try:
+            per = []
+            for t in range(T):
+                X = H.cut(net, seq.frames[start[b] + t], crops[b][t])
+                o, r = g.frame_crop(H.dev(X), paths[b][t][0], paths[b][t][1], crops[b][t], None if seq.forced is None else H.dev(H.cut(net, seq.forced[start[b] + t], crops[b][t])))
+                torch.cuda.synchronize()
+                per.append(([x.cpu().numpy().copy() for x in o], r))
+            want[b] = (per, state_of(g, net))
+        finally:
+            g.close()
+    gb = GpuBatch(net, n, crops=True)
+    try:
+        for t in range(T):
+            cs = [crops[b][t] for b in range(n)]
+            Xs = [H.dev(H.cut(net, seq.frames[start[b] + t], cs[b])) for b in range(n)]
+            Fs = None if seq.forced is None else [H.dev(H.cut(net, seq.forced[start[b] + t], cs[b])) for b in range(n)]
+            got, rs = gb.frame_crop(Xs, [paths[b][t][0] for b in range(n)], [paths[b][t][1] for b in range(n)], cs, Fs)
+            torch.cuda.synchronize()
+            for b in check:
+                assert bool(rs[b]) == bool(want[b][0][t][1]), f"frame {t} stream {b}: reset decision"
+                for a, w in zip(got[b], want[b][0][t][0]):
+                    assert np.array_equal(a.cpu().numpy(), w), f"frame {t} stream {b}: output differs"
+        for b in check:
+            for k, (u, v) in enumerate(zip(want[b][1], state_of(gb.streams[b], net))):
+                assert np.array_equal(u, v), f"stream {b}: state view {k} differs"
+    finally:
+        gb.close()
