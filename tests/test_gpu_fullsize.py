@@ -60,6 +60,21 @@ def test_config3_full_512_teacher_forced():
     log(f"config 3 teacher-forced, full size: worst fp error {worst:.2e}")
 
 
+def test_config3_full_512_teacher_forced_whole_segment_tiles():
+    """The same with whole-segment convolution tiles everywhere (MDCNN_OPT_CONV_HALO_SUB = 1, what bench.py sets for its
+    batch legs): the 128- to 512-channel layers then run without a K split, two frames."""
+    import gpu_harness as H
+    from paper_2210_09887_amd import binding as B
+    net = build_net(3)
+    seq = build_sequence(3, n_frames=2)
+    try:
+        B.mdcnn_set_option(B.MDCNN_OPT_CONV_HALO_SUB, 1)
+        worst = H.teacher_forced(net, seq.frames, seq.shifts, log=log)
+    finally:
+        B.mdcnn_set_option(B.MDCNN_OPT_CONV_HALO_SUB, 0)
+    log(f"config 3 teacher-forced, full size, whole-segment tiles: worst fp error {worst:.2e}")
+
+
 def test_config3_full_512_followed():
     """Free-running at full size with the guard band: every decision of the GPU against an oracle in the same
     state, outputs at the tight tolerance."""
@@ -342,3 +357,48 @@ def test_full_size_frames_in_flight(cfg, n):
     for depth, cuts, mode in [(4, (), 0), (3, (n // 2,), 0), (4, (), 1)]:
         log(f"config {cfg}: {n} frames, {depth} streams, calls {cuts or 'one'}, mode {mode}")
         F.same(ref, F.in_flight(net, seq, depth, 1, cuts, mode), f"config {cfg}, depth {depth}, mode {mode}")
+
+
+def test_config3_full_512_batch_with_frames_in_flight():
+    """Two videos of the headline workload through mdcnn_frames_batch (frames of both in flight, whole-segment convolution
+    tiles as bench.py uses them for its batch legs) equal the same videos frame by frame through mdcnn_frame_batch, bit for
+    bit in every output, reset decision and state view; the frame-by-frame outputs of video 0 are held against the oracle
+    with the default tiles by the tests above."""
+    import gpu_harness as H
+    from test_gpu_frames import state_of
+    from paper_2210_09887_amd import binding as B
+    from paper_2210_09887_amd.runtime import GpuBatch
+    net = build_net(3)
+    seq = build_sequence(3, n_frames=8)
+    starts, T = (0, 2), 6
+    frames = [[H.dev(seq.frames[s0 + t]) for s0 in starts] for t in range(T)]
+    dty = [[0 if t == 0 else int(seq.shifts[s0 + t][0]) for s0 in starts] for t in range(T)]
+    dtx = [[0 if t == 0 else int(seq.shifts[s0 + t][1]) for s0 in starts] for t in range(T)]
+    try:
+        B.mdcnn_set_option(B.MDCNN_OPT_CONV_HALO_SUB, 1)
+        gb = GpuBatch(net, 2)
+        try:
+            want_o, want_r = [], []
+            for t in range(T):
+                o, r = gb.frame(frames[t], dty[t], dtx[t])
+                torch.cuda.synchronize()
+                want_o.append([x.clone() for x in o])
+                want_r.append([bool(v) for v in r])
+            want_s = [state_of(g, net) for g in gb.streams]
+        finally:
+            gb.close()
+        gb = GpuBatch(net, 2)
+        try:
+            got_o, got_r = gb.frames(frames, dty, dtx, depth=4)
+            torch.cuda.synchronize()
+            assert got_r == want_r
+            for t in range(T):
+                for b in range(2):
+                    assert torch.equal(got_o[t][b], want_o[t][b]), f"frame {t}, video {b}: output differs"
+            for b, g in enumerate(gb.streams):
+                for k, (u, v) in enumerate(zip(want_s[b], state_of(g, net))):
+                    assert np.array_equal(u, v), f"video {b}: state view {k} differs"
+        finally:
+            gb.close()
+    finally:
+        B.mdcnn_set_option(B.MDCNN_OPT_CONV_HALO_SUB, 0)
