@@ -536,26 +536,27 @@ __device__ __forceinline__ int tile_prologue_sub(const EdgeDev& e, int seg, int 
 // Variant of tile_prologue for tiles that are th x tw rectangles of the padded window (th * tw <= 256, top-left
 // corner (wy0, wx0)): thread t looks at tile pixel (t / tw, t % tw); the live ones are ranked in that order.
 // Returns their number; rows s_wy / s_wx are filled for them, sh[4] = valid taps of the tile.
-// pub_seg >= 0: the block also ranks list segment pub_seg (256 consecutive window indices) - the flags of both
-// footprints are requested together; pub_off = this thread's position in that segment's compute list or -1,
-// sh[8 .. 11] the entries of the segment per wave.  Nothing is written to global memory here: the wave's later
+// The tap mask of a tile pixel is read off the tile's staged rectangle: s_pix[ry * rw + rx] >= 0 where the source pixel
+// (ry, rx) of the rectangle (the tile plus its halo) is in view and updated (3x3, stride 1: the footprint of tile pixel
+// (ly, lx) is rectangle rows ly .. ly + 2, columns lx .. lx + 2) - no flag loads of its own.
+// pub_seg >= 0: the block also ranks list segment pub_seg (256 consecutive window indices), whose tap masks vm_p the
+// caller has requested with the rectangle's flags; pub_off = this thread's position in that segment's compute list or
+// -1, sh[8 .. 11] the entries of the segment per wave.  Nothing is written to global memory here: the wave's later
 // loads would queue behind those stores (tile_effects_2d does it once the tile's own loads are done).
-__device__ __forceinline__ int tile_prologue_2d(const EdgeDev& e, int wy0, int wx0, int th, int tw, int pub_seg, int& pub_off,
-                                                int* s_wy, int* s_wx, int* sh) {
+__device__ __forceinline__ int tile_prologue_2d(const EdgeDev& e, int wy0, int wx0, int th, int tw, const int* s_pix, int rw,
+                                                int pub_seg, unsigned vm_p, int& pub_off, int* s_wy, int* s_wx, int* sh) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (tid == 0) sh[4] = 0;
     const int ly = tid / tw, lx = tid - ly * tw;
     const int wy = wy0 + ly, wx = wx0 + lx;
     const bool in_tile = ly < th && wy < e.Hp && wx < e.Wp;
-    const int p = pub_seg * kSegPixels + tid;
-    const bool in_seg = pub_seg >= 0 && p < e.Hp * e.Wp;
-    int qy = 0, qx = 0;
-    if (in_seg) { qy = p / e.Wp; qx = p - qy * e.Wp; }
-    // both footprints: out-of-range threads read the flags of pixel (0, 0) and are masked afterwards
-    const unsigned vm_t = tap_mask(e, in_tile ? wy - e.by0 : 0, in_tile ? wx - e.bx0 : 0);
-    unsigned vm_p = 0;
-    if (pub_seg >= 0) vm_p = tap_mask(e, in_seg ? qy - e.by0 : 0, in_seg ? qx - e.bx0 : 0);
-    const unsigned vm = in_tile ? vm_t : 0u;
+    const bool in_seg = pub_seg >= 0 && pub_seg * kSegPixels + tid < e.Hp * e.Wp;
+    unsigned vm = 0;
+    if (in_tile) {
+        const int* r = s_pix + ly * rw + lx;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) vm |= (unsigned)(r[(t / 3) * rw + t % 3] >= 0) << t;
+    }
     const bool has = vm != 0, hasp = in_seg && vm_p != 0;
     const unsigned long long bal = __ballot(has), balp = __ballot(hasp);
     const unsigned long long below = (1ull << lane) - 1ull;
@@ -716,9 +717,23 @@ void k_conv_halo(EdgeBatch eb, int NT, int work_items, int th, int tw) {
                 rpix[j] = ok ? iy * e.sW + ix : -1;
                 rflag[j] = e.sflags[ok ? rpix[j] : 0];
             }
-            // every list segment is published by one of the first tiles (there are at least as many tiles as segments)
+            // every list segment is published by one of the first tiles (there are at least as many tiles as segments):
+            // the flags of its footprints travel with those of the rectangle
             pub_seg = nt == 0 && mt < edge_segments(e) ? mt : -1;
-            tot = tile_prologue_2d(e, ty * th, tx * tw, th, tw, pub_seg, pub_off, s_wy, s_wx, sh);
+            unsigned vm_p = 0;
+            if (pub_seg >= 0) {
+                const int p = pub_seg * kSegPixels + tid, qy = p / e.Wp, qx = p - qy * e.Wp;
+                const bool in_seg = p < nwin;              // (threads beyond the window read the flags of pixel (0, 0): unused)
+                vm_p = tap_mask(e, in_seg ? qy - e.by0 : 0, in_seg ? qx - e.bx0 : 0);
+            }
+            // the rectangle: source pixel of every position, -1 where it is out of view or not updated
+#pragma unroll
+            for (int j = 0; j < NRF; ++j) {
+                const int pos = tid + 256 * j;
+                if (pos < rn) s_pix[pos] = rpix[j] >= 0 && (rflag[j] & kFlagM) ? rpix[j] : -1;
+            }
+            __syncthreads();
+            tot = tile_prologue_2d(e, ty * th, tx * tw, th, tw, s_pix, rw, pub_seg, vm_p, pub_off, s_wy, s_wx, sh);
             if (tot <= 0) tile_effects_2d(e, 0, false, pub_seg, pub_off, s_wy, s_wx, sh);
         } else {
             const int seg = mt / NSUB, sub_lo = (mt % NSUB) * SUB;
@@ -734,21 +749,15 @@ void k_conv_halo(EdgeBatch eb, int NT, int work_items, int th, int tw) {
         if (!T2D && tid == 0 && nt == 0) add_macs(e, sh[4], 0);
         const int iy0 = wyA - e.by0 - e.pad, ix0 = cxA - e.pad;
         const int RW = cxB - cxA + KS, npos = (wyB - wyA + KS) * RW;       // npos <= CAP: checked by the host
-        if constexpr (T2D) {
-#pragma unroll
-            for (int j = 0; j < NRF; ++j) {
-                const int pos = tid + 256 * j;
-                if (pos < npos) s_pix[pos] = rpix[j] >= 0 && (rflag[j] & kFlagM) ? rpix[j] : -1;
-            }
-        } else {
+        if constexpr (!T2D) {                             // (rectangular tiles: s_pix was filled ahead of the prologue)
             for (int pos = tid; pos < npos; pos += 256) {
                 const int ry = pos / RW, rx = pos - ry * RW;
                 const int iy = iy0 + ry, ix = ix0 + rx;
                 const bool ok = iy >= 0 && iy < e.sH && ix >= 0 && ix < e.sW && (e.sflags[iy * e.sW + ix] & kFlagM);
                 s_pix[pos] = ok ? iy * e.sW + ix : -1;
             }
+            __syncthreads();
         }
-        __syncthreads();
         const int nrt = (tot + 31) >> 5;                  // live 32-entry row tiles of the tile
         const int mylive = nrt > wm ? (nrt - wm + WMV - 1) / WMV : 0;      // of this wave: row tiles wm, wm + WMV, ...
 
