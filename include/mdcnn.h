@@ -128,6 +128,15 @@ typedef struct {
 mdcnn_status mdcnn_pack_weights(const mdcnn_conv_desc* edge, int dtype, void* dst_dev, size_t dst_bytes,
                                 void* stream);
 
+/* Host-only helper.  The tile the halo-staged convolution kernel would cut an Hp x Wp padded window
+ * into: the rectangle th x tw of at most max_pixels (1 .. 256) pixels whose footprint
+ * (th + k - 1) x (tw + k - 1) has at most max_staged pixels and that covers the window with the
+ * fewest tiles (ties: the smaller footprint); *tiles = ceil(Hp / th) * ceil(Wp / tw).
+ * Errors: MDCNN_ERR_SHAPE if no rectangle fits, MDCNN_ERR_SIZE for arguments out of range.
+ * [Padded Convolutions: a tile's outputs read the tile and a border of (k - 1) / 2 pixels around it] */
+mdcnn_status mdcnn_conv_tiles(int Hp, int Wp, int k, int max_pixels, int max_staged, int* th, int* tw,
+                              long long* tiles);
+
 /* Host-only helper.  Width of the dilated border along one axis for a
  * convolution (k, stride, pad) from `in_extent` to `out_extent` pixels: how many
  * outputs before 0 / after out_extent-1 still read an in-view input.

@@ -28,7 +28,7 @@ STATE_UNSEEN, STATE_DIRTY = 1, 2
 STATUS_NAMES = {0: "OK", 1: "ERR_NULL", 2: "ERR_SHAPE", 3: "ERR_DTYPE", 4: "ERR_ALIGN",
                 5: "ERR_SIZE", 6: "ERR_STATE", 7: "ERR_HIP"}
 
-EXPORTS = ["mdcnn_conv_border", "mdcnn_buffer_bytes", "mdcnn_create_buffer", "mdcnn_destroy_buffer",
+EXPORTS = ["mdcnn_conv_border", "mdcnn_conv_tiles", "mdcnn_buffer_bytes", "mdcnn_create_buffer", "mdcnn_destroy_buffer",
            "mdcnn_shift_camera", "mdcnn_set_crop", "mdcnn_layer_forward", "mdcnn_layer_forward_noalloc", "mdcnn_net_create", "mdcnn_net_destroy",
            "mdcnn_frame", "mdcnn_frame_crop", "mdcnn_frame_batch", "mdcnn_frame_batch_crop", "mdcnn_frame_plan", "mdcnn_frames", "mdcnn_frames_batch", "mdcnn_frames_crop", "mdcnn_frames_masked", "mdcnn_frames_plan", "mdcnn_input_mask", "mdcnn_read_view", "mdcnn_write_view", "mdcnn_set_option", "mdcnn_profile_read", "mdcnn_profile_read_launches", "mdcnn_bench_copy", "mdcnn_bench_mfma",
            "mdcnn_pack_weights", "mdcnn_last_error", "mdcnn_version"]
@@ -69,6 +69,7 @@ def lib():
         L = C.CDLL(LIB_PATH)
         vp, ip, sz = C.c_void_p, C.POINTER(C.c_int), C.c_size_t
         L.mdcnn_conv_border.argtypes = [C.c_int] * 5 + [ip, ip]
+        L.mdcnn_conv_tiles.argtypes = [C.c_int] * 5 + [ip, ip, C.POINTER(C.c_longlong)]
         L.mdcnn_buffer_bytes.argtypes = [C.POINTER(mdcnn_buffer_desc), C.POINTER(sz)]
         L.mdcnn_create_buffer.argtypes = [C.POINTER(mdcnn_buffer_desc), vp, sz, C.POINTER(vp)]
         L.mdcnn_destroy_buffer.argtypes = [vp]
@@ -193,6 +194,13 @@ def mdcnn_layer_forward(buf: int, frame_ptr, forced_ptr, edges, outs, stream: in
     n = len(edges)
     arr = (mdcnn_conv_desc * max(n, 1))(*edges)
     _check(lib().mdcnn_layer_forward(buf, frame_ptr, forced_ptr, arr, _handles(outs) if n else None, n, stream))
+
+
+def mdcnn_conv_tiles(Hp: int, Wp: int, k: int, max_pixels: int, max_staged: int):
+    """(th, tw, tiles) of the rectangular tiles the halo-staged convolution would use."""
+    th, tw, n = C.c_int(), C.c_int(), C.c_longlong()
+    _check(lib().mdcnn_conv_tiles(int(Hp), int(Wp), int(k), int(max_pixels), int(max_staged), C.byref(th), C.byref(tw), C.byref(n)))
+    return th.value, tw.value, n.value
 
 
 def mdcnn_layer_forward_noalloc(buf: int, frame_ptr, forced_ptr, edges, outs, stream: int = 0):

@@ -1930,7 +1930,7 @@ static hipError_t launch_halo_t(const EdgeBatch& eb, int nb, long long nseg, hip
 
 // Rectangle th x tw of at most `sub` pixels whose halo fits `cap` staged pixels, with the fewest tiles over an Hp x Wp window
 // (ties: the smaller halo).  False if none fits.
-static bool tile_2d(int Hp, int Wp, int k, int sub, int cap, int* th_out, int* tw_out, long long* tiles_out) {
+bool tile_2d(int Hp, int Wp, int k, int sub, int cap, int* th_out, int* tw_out, long long* tiles_out) {
     long long best = -1, best_halo = 0;
     for (int th = 1; th <= sub && th <= Hp; ++th) {
         int tw = sub / th < Wp ? sub / th : Wp;

@@ -1253,6 +1253,14 @@ mdcnn_status mdcnn_pack_weights(const mdcnn_conv_desc* edge, int dtype, void* ds
     return MDCNN_OK;
 }
 
+mdcnn_status mdcnn_conv_tiles(int Hp, int Wp, int k, int max_pixels, int max_staged, int* th, int* tw, long long* tiles) {
+    if (!th || !tw || !tiles) return fail(MDCNN_ERR_NULL, "conv_tiles: NULL argument");
+    if (Hp < 1 || Wp < 1 || k < 1 || k > 5 || max_pixels < 1 || max_pixels > kSegPixels || max_staged < 1)
+        return fail(MDCNN_ERR_SIZE, "conv_tiles: argument out of range");
+    if (!tile_2d(Hp, Wp, k, max_pixels, max_staged, th, tw, tiles)) return fail(MDCNN_ERR_SHAPE, "conv_tiles: no tile of up to %d pixels has a halo of %d pixels or less", max_pixels, max_staged);
+    return MDCNN_OK;
+}
+
 mdcnn_status mdcnn_conv_border(int k, int stride, int pad, int in_extent, int out_extent, int* before, int* after) {
     if (!before || !after) return fail(MDCNN_ERR_NULL, "before/after is NULL");
     return border_1d(k, stride, pad, in_extent, out_extent, before, after);

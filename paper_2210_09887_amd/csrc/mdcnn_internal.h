@@ -195,6 +195,8 @@ hipError_t launch_step1_fill(Step1Fill& a, hipStream_t st);
 // returns the kernel class that was launched in *cls
 hipError_t launch_conv(const EdgeBatch& eb, int n, int dtype, int conv_path, hipStream_t st, int* cls);
 extern int g_tile, g_pipe, g_xcd, g_kc, g_halo, g_halo_sub, g_f32_mfma;   // convolution tuning knobs
+// host-only: the rectangle th x tw of at most `sub` pixels whose halo fits `cap` staged pixels, with the fewest tiles over an Hp x Wp window
+bool tile_2d(int Hp, int Wp, int k, int sub, int cap, int* th_out, int* tw_out, long long* tiles_out);
 hipError_t launch_pack_weights(const void* src, void* dst, int taps, int Cout, int Cin, hipStream_t st);
 // Post-processed update mask of an INPUT site over the rectangle (y0, x0, Hc, Wc) of its view.
 struct MaskJob {

@@ -192,3 +192,28 @@ def test_frames_in_flight_never_share_a_site(name, group, depth, mode):
         B.mdcnn_net_destroy(net)
         for b in bufs:
             B.mdcnn_destroy_buffer(b)
+
+
+def test_rectangular_tiles_cover_the_window_within_their_limits():
+    """mdcnn_conv_tiles (host only): the tile the halo-staged kernel would take.  It holds no more pixels than allowed,
+    its footprint no more than the staging buffer does, it is not larger than the window, no other rectangle within the
+    limits needs fewer tiles (brute force), and the shapes the benchmark networks meet come out as documented."""
+    import itertools
+    import numpy as np
+    rng = np.random.default_rng(3)
+    cases = [(258, 258, 256, 352), (130, 130, 128, 192), (66, 66, 128, 192), (66, 66, 64, 128), (98, 74, 256, 352), (14, 11, 64, 128),
+             (1, 300, 256, 352), (300, 1, 64, 128), (5, 5, 256, 512)]
+    cases += [(int(rng.integers(1, 200)), int(rng.integers(1, 200)), int(rng.choice([64, 128, 256])), int(rng.choice([128, 192, 352, 384, 512]))) for _ in range(40)]
+    for Hp, Wp, sub, cap in cases:
+        th, tw, tiles = B.mdcnn_conv_tiles(Hp, Wp, 3, sub, cap)
+        assert 1 <= th <= Hp and 1 <= tw <= Wp and th * tw <= sub and (th + 2) * (tw + 2) <= cap
+        assert tiles == -(-Hp // th) * -(-Wp // tw)
+        best = min(-(-Hp // a) * -(-Wp // b) for a, b in itertools.product(range(1, min(Hp, sub) + 1), range(1, min(Wp, sub) + 1))
+                   if a * b <= sub and (a + 2) * (b + 2) <= cap)
+        assert tiles == best, (Hp, Wp, sub, cap, th, tw, tiles, best)
+    assert B.mdcnn_conv_tiles(66, 66, 3, 128, 192) == (11, 11, 36)          # stages 3 and 4 of the ResNet-18-style network
+    assert B.mdcnn_conv_tiles(258, 258, 3, 256, 352)[2] == 280               # its stage 1
+    with pytest.raises(B.MdcnnError):
+        B.mdcnn_conv_tiles(66, 66, 3, 128, 8)                                # nothing fits a staging buffer of 8 pixels
+    with pytest.raises(B.MdcnnError):
+        B.mdcnn_conv_tiles(66, 66, 3, 300, 192)                              # more pixels than a list segment
